@@ -1,0 +1,225 @@
+"""One virtual-node training step, by definition (Section 3.2 steps 1-5, Section 5.2)."""
+import numpy as np
+
+from . import layers as L
+from .numerics import round_to_bf16
+from .optim import adam_update, sgdm_update
+from .partition import partition
+
+
+# ---- flat parameter layout (the oracle's own statement of it) -------------------------
+
+def layout(wl):
+    """[(name, shape)] in flat order: tensors in forward order; a Linear's weight
+    [K_in, N_out] row-major, then its bias, then the normalisation scale and shift."""
+    out = []
+    if wl.kind == "mlp":
+        n_lin = len(wl.dims) - 1
+        for l in range(n_lin):
+            k, n = wl.dims[l], wl.dims[l + 1]
+            hidden = l < n_lin - 1
+            out.append((f"l{l}.W", (k, n)))
+            if not (hidden and wl.batchnorm):
+                out.append((f"l{l}.b", (n,)))     # a bias feeding BatchNorm would have zero gradient
+            if hidden and wl.batchnorm:
+                out.append((f"l{l}.gamma", (n,)))
+                out.append((f"l{l}.beta", (n,)))
+        return out
+    d, f = wl.d_model, wl.d_ffn
+    out.append(("tok_emb", (wl.vocab, d)))
+    out.append(("pos_emb", (wl.seq_len, d)))
+    for l in range(wl.n_layers):
+        out += [(f"l{l}.ln1.gamma", (d,)), (f"l{l}.ln1.beta", (d,)),
+                (f"l{l}.Wqkv", (d, 3 * d)), (f"l{l}.bqkv", (3 * d,)),
+                (f"l{l}.Wo", (d, d)), (f"l{l}.bo", (d,)),
+                (f"l{l}.ln2.gamma", (d,)), (f"l{l}.ln2.beta", (d,)),
+                (f"l{l}.W1", (d, f)), (f"l{l}.b1", (f,)),
+                (f"l{l}.W2", (f, d)), (f"l{l}.b2", (d,))]
+    out += [("lnf.gamma", (d,)), ("lnf.beta", (d,)),
+            ("Wout", (d, wl.vocab)), ("bout", (wl.vocab,))]
+    return out
+
+
+def unflatten(wl, flat):
+    """dict name -> view of `flat` with the tensor's shape."""
+    views, pos = {}, 0
+    for name, shape in layout(wl):
+        n = int(np.prod(shape))
+        views[name] = flat[pos:pos + n].reshape(shape)
+        pos += n
+    if pos != flat.size:
+        raise ValueError(f"parameter vector has {flat.size} entries, layout needs {pos}")
+    return views
+
+
+def _flatten(wl, grads):
+    return np.concatenate([np.asarray(grads[name], dtype=np.float64).reshape(-1)
+                           for name, _ in layout(wl)])
+
+
+# ---- one node: loss L_i (mean over the node) and g_i = dL_i/dtheta ----------------------
+
+def _mlp_node(wl, p, x, y):
+    n_lin = len(wl.dims) - 1
+    h = np.asarray(x, dtype=np.float64)
+    saved = []
+    for l in range(n_lin - 1):
+        z = L.linear_fwd(h, p[f"l{l}.W"], None if wl.batchnorm else p[f"l{l}.b"])
+        if wl.batchnorm:
+            pre, bn_cache = L.batchnorm_fwd(z, p[f"l{l}.gamma"], p[f"l{l}.beta"], wl.bn_eps)
+        else:
+            pre, bn_cache = z, None
+        saved.append((h, pre, bn_cache))
+        h = L.relu_fwd(pre)
+    last = n_lin - 1
+    logits = L.linear_fwd(h, p[f"l{last}.W"], p[f"l{last}.b"])
+    loss, dlogits = L.softmax_xent_fwd_bwd(logits, np.asarray(y, dtype=np.int64))
+
+    g = {}
+    dh, g[f"l{last}.W"], g[f"l{last}.b"] = L.linear_bwd(h, p[f"l{last}.W"], dlogits, True)
+    for l in range(n_lin - 2, -1, -1):
+        h_in, pre, bn_cache = saved[l]
+        dpre = L.relu_bwd(dh, pre)
+        if wl.batchnorm:
+            dz, g[f"l{l}.gamma"], g[f"l{l}.beta"] = L.batchnorm_bwd(dpre, p[f"l{l}.gamma"], bn_cache)
+        else:
+            dz = dpre
+        dh, g[f"l{l}.W"], db = L.linear_bwd(h_in, p[f"l{l}.W"], dz, not wl.batchnorm)
+        if not wl.batchnorm:
+            g[f"l{l}.b"] = db
+    return loss, g
+
+
+def _split_heads(t, n_heads):
+    n, T, d = t.shape
+    return t.reshape(n, T, n_heads, d // n_heads).transpose(0, 2, 1, 3)
+
+
+def _merge_heads(t):
+    n, nh, T, dh = t.shape
+    return t.transpose(0, 2, 1, 3).reshape(n, T, nh * dh)
+
+
+def _encoder_node(wl, p, ids, y):
+    """ids [n, T] token ids (masked positions already hold id 0); y [n, 2, m]:
+    y[:,0] positions, y[:,1] target ids.  Pre-LayerNorm encoder, GELU FFN, final
+    LayerNorm, untied output projection on the masked rows, mean cross-entropy
+    over the node's n*m masked rows."""
+    ids = np.asarray(ids, dtype=np.int64)
+    y = np.asarray(y, dtype=np.int64)
+    n, T = ids.shape
+    d, nh = wl.d_model, wl.n_heads
+    h = p["tok_emb"][ids] + p["pos_emb"][None, :T, :]
+    saved = []
+    for l in range(wl.n_layers):
+        a, c1 = L.layernorm_fwd(h, p[f"l{l}.ln1.gamma"], p[f"l{l}.ln1.beta"], wl.ln_eps)
+        qkv = L.linear_fwd(a, p[f"l{l}.Wqkv"], p[f"l{l}.bqkv"])
+        q, k, v = (_split_heads(qkv[..., i * d:(i + 1) * d], nh) for i in range(3))
+        o, prob = L.attention_fwd(q, k, v)
+        om = _merge_heads(o)
+        h_mid = h + L.linear_fwd(om, p[f"l{l}.Wo"], p[f"l{l}.bo"])
+        f, c2 = L.layernorm_fwd(h_mid, p[f"l{l}.ln2.gamma"], p[f"l{l}.ln2.beta"], wl.ln_eps)
+        u = L.linear_fwd(f, p[f"l{l}.W1"], p[f"l{l}.b1"])
+        gl = L.gelu_fwd(u)
+        h_out = h_mid + L.linear_fwd(gl, p[f"l{l}.W2"], p[f"l{l}.b2"])
+        saved.append((a, c1, q, k, v, prob, om, f, c2, u, gl))
+        h = h_out
+    hf, cf = L.layernorm_fwd(h, p["lnf.gamma"], p["lnf.beta"], wl.ln_eps)
+    seq = np.repeat(np.arange(n), y.shape[2])
+    pos = y[:, 0, :].reshape(-1)
+    tgt = y[:, 1, :].reshape(-1)
+    rows = hf[seq, pos, :]                                  # [n*m, d]
+    logits = L.linear_fwd(rows, p["Wout"], p["bout"])
+    loss, dlogits = L.softmax_xent_fwd_bwd(logits, tgt)
+
+    g = {}
+    drows, g["Wout"], g["bout"] = L.linear_bwd(rows, p["Wout"], dlogits, True)
+    dhf = np.zeros_like(hf)
+    np.add.at(dhf, (seq, pos), drows)
+    dh, g["lnf.gamma"], g["lnf.beta"] = L.layernorm_bwd(dhf, p["lnf.gamma"], cf)
+    for l in range(wl.n_layers - 1, -1, -1):
+        a, c1, q, k, v, prob, om, f, c2, u, gl = saved[l]
+        dgl, g[f"l{l}.W2"], g[f"l{l}.b2"] = L.linear_bwd(gl.reshape(-1, wl.d_ffn), p[f"l{l}.W2"],
+                                                         dh.reshape(-1, d), True)
+        du = L.gelu_bwd(dgl, u.reshape(-1, wl.d_ffn))
+        df, g[f"l{l}.W1"], g[f"l{l}.b1"] = L.linear_bwd(f.reshape(-1, d), p[f"l{l}.W1"], du, True)
+        dmid, g[f"l{l}.ln2.gamma"], g[f"l{l}.ln2.beta"] = L.layernorm_bwd(
+            df.reshape(n, T, d), p[f"l{l}.ln2.gamma"], c2)
+        dmid = dmid + dh                                     # residual around the FFN
+        dom, g[f"l{l}.Wo"], g[f"l{l}.bo"] = L.linear_bwd(om.reshape(-1, d), p[f"l{l}.Wo"],
+                                                         dmid.reshape(-1, d), True)
+        dq, dk, dv = L.attention_bwd(_split_heads(dom.reshape(n, T, d), nh), q, k, v, prob)
+        dqkv = np.concatenate([_merge_heads(dq), _merge_heads(dk), _merge_heads(dv)], axis=-1)
+        da, g[f"l{l}.Wqkv"], g[f"l{l}.bqkv"] = L.linear_bwd(a.reshape(-1, d), p[f"l{l}.Wqkv"],
+                                                            dqkv.reshape(-1, 3 * d), True)
+        din, g[f"l{l}.ln1.gamma"], g[f"l{l}.ln1.beta"] = L.layernorm_bwd(
+            da.reshape(n, T, d), p[f"l{l}.ln1.gamma"], c1)
+        dh = din + dmid                                      # residual around attention
+    g["pos_emb"] = np.zeros_like(p["pos_emb"])
+    g["pos_emb"][:T] = dh.sum(axis=0)
+    g["tok_emb"] = np.zeros_like(p["tok_emb"])
+    np.add.at(g["tok_emb"], ids.reshape(-1), dh.reshape(-1, d))
+    return loss, g
+
+
+def node_loss_and_grads(wl, compute_params, x_node, y_node):
+    """(L_i, flat g_i) for one node given float64 compute parameters (flat)."""
+    p = unflatten(wl, compute_params)
+    if wl.kind == "mlp":
+        loss, g = _mlp_node(wl, p, x_node, y_node)
+    else:
+        loss, g = _encoder_node(wl, p, x_node, y_node)
+    return loss, _flatten(wl, g)
+
+
+def compute_copy(wl, theta):
+    """Parameters the forward/backward passes see: fp32 master values, rounded to
+    bf16 for bf16 workloads; returned as float64."""
+    if wl.dtype == "f64":                                    # tests only: no rounding at all
+        return np.asarray(theta, dtype=np.float64).copy()
+    theta32 = np.asarray(theta, dtype=np.float32)
+    if wl.dtype == "bf16":
+        return round_to_bf16(theta32)
+    return theta32.astype(np.float64)
+
+
+def new_state(wl, n):
+    if wl.optimizer == "sgdm":
+        return {"t": 0, "v": np.zeros(n)}
+    return {"t": 0, "m": np.zeros(n), "u": np.zeros(n)}
+
+
+def oracle_step(wl, theta, x, y, node_sizes=None, state=None, nodes=None):
+    """One step.  theta: flat fp32 master parameters.  Returns a dict with
+    off, w (bit-exact data), loss, node_losses, G (float64 [P]), theta (float64
+    [P] after the update), state (after the update).  `nodes` limits the nodes
+    that are evaluated (timing a sample of the work); G and the update are then
+    partial and must not be compared."""
+    sizes = list(wl.node_sizes if node_sizes is None else node_sizes)
+    off, w = partition(sizes, len(x))
+    cp = compute_copy(wl, theta)
+    n = cp.size
+    G = np.zeros(n)
+    loss = 0.0
+    node_losses = []
+    which = range(len(sizes)) if nodes is None else nodes
+    for i in which:                                          # node after node (Section 3.2)
+        lo, hi = int(off[i]), int(off[i + 1])
+        L_i, g_i = node_loss_and_grads(wl, cp, x[lo:hi], y[lo:hi])
+        weight = sizes[i] / float(len(x))                    # b_i / B (Section 5.2)
+        G += weight * g_i
+        loss += weight * L_i
+        node_losses.append(L_i)
+    state = new_state(wl, n) if state is None else state
+    t = state["t"] + 1
+    theta64 = (np.asarray(theta, dtype=np.float64) if wl.dtype == "f64"
+               else np.asarray(theta, dtype=np.float32).astype(np.float64))
+    if wl.optimizer == "sgdm":
+        theta_new, v = sgdm_update(theta64, G, state["v"], wl.lr, wl.momentum)
+        new = {"t": t, "v": v}
+    else:
+        theta_new, m, u = adam_update(theta64, G, state["m"], state["u"], t, wl.lr,
+                                      wl.beta1, wl.beta2, wl.adam_eps)
+        new = {"t": t, "m": m, "u": u}
+    return {"off": off, "w": w, "loss": loss, "node_losses": np.array(node_losses),
+            "G": G, "theta": theta_new, "state": new}
