@@ -1,0 +1,175 @@
+/*
+ * libvf -- virtual-node training step on one AMD MI355X (gfx950).
+ *
+ * One step of the method of "VirtualFlow: Decoupling Deep Learning Models from the
+ * Underlying Hardware" (arxiv 2009.09523), Section 3.2 (virtual node execution,
+ * steps 1-5 of its Figure 4) with the size weights of Section 5.2:
+ *
+ *   a batch of B samples is split into V virtual nodes of sizes b_i (sum b_i = B);
+ *   the nodes are run one after another on the accelerator, each with its own forward
+ *   and backward pass (BatchNorm statistics over that node's rows only, Section 4.1);
+ *   each node's gradient g_i is folded into one model-sized fp32 gradient buffer with
+ *   weight b_i / B; one optimizer update is applied after the last node.
+ *
+ * Conventions for every entry point
+ *   - returns VF_OK (0) or a negative VF_E* code; never throws or aborts;
+ *   - "device" pointers are HIP device memory on the device current at vf_init;
+ *     "host" pointers are ordinary host memory;
+ *   - the caller owns params, batch and output buffers; the library owns its context
+ *     (workspace, gradient buffer, staging, optimizer state, bf16 weight copies), all
+ *     allocated in vf_init and freed in vf_destroy; vf_step allocates nothing;
+ *   - all device work is enqueued on the stream given in the configuration.
+ *
+ * Flat parameter layout (fp32, also the layout of vf_grads and vf_opt_state):
+ *   tensors in forward order; a Linear is W[K_in, N_out] row-major, then its bias, then
+ *   the scale and shift of the normalisation that follows it.
+ *   MLP:     per hidden layer W, bias (only without BatchNorm), gamma, beta (only with
+ *            BatchNorm); last layer W, bias.
+ *   encoder: tok_emb[vocab,d], pos_emb[T,d]; per layer ln1.gamma, ln1.beta, Wqkv[d,3d],
+ *            bqkv, Wo[d,d], bo, ln2.gamma, ln2.beta, W1[d,ffn], b1, W2[ffn,d], b2; then
+ *            lnf.gamma, lnf.beta, Wout[d,vocab], bout.
+ */
+#ifndef VF_H
+#define VF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#pragma GCC visibility push(default)
+
+#define VF_OK        0
+#define VF_EINVAL   (-1)   /* bad argument (null pointer, sizes that are not a partition, ...) */
+#define VF_ENOMEM   (-2)   /* device or host allocation failed */
+#define VF_EDEVICE  (-3)   /* a HIP call failed; vf_last_error() has the text */
+#define VF_ESTATE   (-4)   /* call made in the wrong state (e.g. vf_grads before any vf_step) */
+
+#define VF_MLP      0
+#define VF_ENCODER  1
+
+#define VF_F32      0      /* fp32 operands and arithmetic throughout */
+#define VF_BF16     1      /* bf16 GEMM operands (round-to-nearest-even), fp32 accumulation,
+                              fp32 master parameters, gradients and optimizer */
+
+#define VF_SGDM     0      /* v <- mu v + G;  theta <- theta - lr v */
+#define VF_ADAM     1      /* bias-corrected Adam, t counted from 1 */
+
+#define VF_MAX_DIMS 16
+
+/* flags */
+#define VF_FLAG_FUSED_ACCUMULATE 1u  /* weight-gradient kernels add w_i*g_i straight into the
+                                        gradient buffer instead of writing a staging vector that
+                                        the accumulate kernel folds in; same arithmetic per
+                                        element (one fused multiply-add), same node order */
+#define VF_FLAG_NO_GRAPH         2u  /* launch kernels one by one instead of replaying a
+                                        captured HIP graph */
+
+typedef struct vf_ctx vf_ctx;
+
+/* Plain data, copied by vf_init. */
+typedef struct vf_config {
+  int32_t model_kind;            /* VF_MLP | VF_ENCODER */
+  int32_t n_dims;                /* MLP: number of entries of dims (layers + 1), 2..VF_MAX_DIMS */
+  int32_t dims[VF_MAX_DIMS];     /* MLP: [in, h1, ..., out] */
+  int32_t batchnorm;             /* MLP: 1 = every hidden Linear (no bias) is followed by
+                                    BatchNorm (statistics per virtual node) and ReLU;
+                                    0 = Linear with bias, then ReLU */
+  int32_t n_layers, d_model, n_heads, d_ffn, seq_len, vocab, n_masked;   /* encoder */
+  int32_t dtype;                 /* VF_F32 | VF_BF16 */
+  int32_t optimizer;             /* VF_SGDM | VF_ADAM */
+  float   lr, momentum, beta1, beta2, adam_eps, bn_eps, ln_eps;
+  int32_t max_batch;             /* largest B a step may use */
+  int32_t max_node_size;         /* largest b_i; sizes the per-node workspace */
+  int32_t max_nodes;             /* largest V */
+  uint32_t flags;                /* VF_FLAG_* */
+  void*   stream;                /* hipStream_t; NULL = the default stream */
+} vf_config;
+
+/* S0 of the step, host only (Section 3.2: the batch is split among the virtual nodes;
+ * Section 5.2: node i's mean gradient is weighted by b_i/B).  node_sizes: host, length V.
+ * off_out: host, V+1 entries, off[0]=0, off[i+1]=off[i]+b_i: node i owns the contiguous
+ * batch rows off[i]..off[i+1]-1.  w_out: host, V entries, the single IEEE fp32 division
+ * (float)b_i/(float)B.  Either output may be NULL.  VF_EINVAL if V<1, any b_i<1 or
+ * sum b_i != B; outputs are then untouched. */
+int vf_partition(const int32_t* node_sizes, int32_t V, int32_t B, int32_t* off_out, float* w_out);
+
+/* Creates a context on the current HIP device: validates the configuration, lays out the
+ * parameters and allocates every buffer a step needs (sized by max_node_size and max_batch,
+ * not by the number of nodes: Section 3.3, the gradient buffer is one model-sized vector
+ * shared by all nodes).  *out is NULL on failure. */
+int vf_init(const vf_config* cfg, vf_ctx** out);
+
+/* One training step (Section 3.2 steps 1-3 and 5; step 4, the cross-device exchange, is the
+ * identity on one device).
+ *   params      device, fp32 [vf_num_params], IN/OUT: master parameters, updated in place.
+ *   batch_x     device. MLP: [B, dims[0]] row-major, fp32 for VF_F32, bf16 for VF_BF16.
+ *               encoder: int32 token ids [B, seq_len], masked positions already replaced.
+ *   batch_y     device, int32. MLP: [B] class labels in [0, dims[last]).
+ *               encoder: [B, 2, n_masked]: [s,0,:] masked positions in [0, seq_len), distinct
+ *               per sequence; [s,1,:] target ids in [0, vocab).
+ *   B, V        batch size and number of virtual nodes.
+ *   node_sizes  host, length V.
+ * Validation (as vf_partition, plus V <= max_nodes, b_i <= max_node_size, B <= max_batch)
+ * happens before any device work: a rejected call leaves params and all state untouched.
+ * Label and id values are not validated (they live on the device); out-of-range values are
+ * clamped into range by the kernels.  Asynchronous: returns once the work is enqueued. */
+int vf_step(vf_ctx* ctx, void* params, const void* batch_x, const int32_t* batch_y,
+            int32_t B, int32_t V, const int32_t* node_sizes);
+
+/* Combined gradient G = sum_i (b_i/B) g_i of the last step (the value the update used),
+ * fp32 [vf_num_params] copied to `out`, which may be a device or a host pointer.
+ * Synchronises the stream.  VF_ESTATE before the first step. */
+int vf_grads(vf_ctx* ctx, float* out);
+
+/* Combined loss L = sum_i (b_i/B) L_i of the last step, L_i the mean loss over node i's
+ * samples (encoder: over its masked positions).  out: host, one float.  Synchronises. */
+int vf_loss(vf_ctx* ctx, float* out);
+
+/* Per-node mean losses L_i of the last step.  out: host, V floats (V of the last step). */
+int vf_node_losses(vf_ctx* ctx, float* out, int32_t V);
+
+/* Optimizer state after the last step, fp32 [vf_num_params], device or host `out`.
+ * which = 0: SGD-momentum velocity v, or Adam first moment m;  which = 1: Adam second
+ * moment u (VF_EINVAL for SGD-momentum).  Synchronises. */
+int vf_opt_state(vf_ctx* ctx, int32_t which, float* out);
+
+/* Number of optimizer updates applied so far (one per successful vf_step). */
+int64_t vf_step_count(const vf_ctx* ctx);
+
+int64_t vf_num_params(const vf_ctx* ctx);
+
+/* Bytes of device memory the context holds.  Depends on the model, max_node_size and
+ * max_batch only -- never on the number of virtual nodes (Section 3.3). */
+size_t vf_workspace_bytes(const vf_ctx* ctx);
+
+void vf_destroy(vf_ctx* ctx);
+
+const char* vf_strerror(int code);
+/* Text of the last device error seen by this thread ("" if none). */
+const char* vf_last_error(void);
+
+/* ---- the two bandwidth-bound kernels of the step, callable on their own -------------- */
+
+/* Step 3 of Section 3.2 with the weight of Section 5.2 over a flat fp32 vector:
+ *   first != 0:  buf[p] = w * g[p]          first == 0:  buf[p] = buf[p] + w * g[p]
+ * (one fused multiply-add per element).  buf, g: device, n floats, 16-byte aligned. */
+int vf_accumulate(float* buf, const float* g, float w, int64_t n, int32_t first, void* stream);
+
+/* Step 5 of Section 3.2 over flat fp32 vectors (device, n floats each):
+ *   v <- momentum*v + G ;  theta <- theta - lr*v. */
+int vf_sgdm_update(float* theta, float* v, const float* G, float lr, float momentum,
+                   int64_t n, void* stream);
+/*   m <- beta1*m + (1-beta1)*G ;  u <- beta2*u + (1-beta2)*G*G ;
+ *   theta <- theta - lr * (m/(1-beta1^t)) / (sqrt(u/(1-beta2^t)) + eps),  t >= 1. */
+int vf_adam_update(float* theta, float* m, float* u, const float* G, float lr, float beta1,
+                   float beta2, float eps, int64_t t, int64_t n, void* stream);
+
+#pragma GCC visibility pop
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VF_H */

@@ -1,0 +1,305 @@
+// C ABI of libvf: argument checks, partition (S0), context set-up, and the step executor
+// that strings the per-node launch sequences, the accumulate kernel and the optimizer
+// update together (Section 3.2, steps 1-5; weights of Section 5.2).
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "vf_ctx.h"
+
+namespace vf {
+
+static thread_local std::string g_last_error;
+
+void set_last_error(const char* what, hipError_t e, const char* file, int line) {
+  char buf[512];
+  snprintf(buf, sizeof buf, "%s failed: %s (%s:%d)", what, hipGetErrorString(e), file, line);
+  g_last_error = buf;
+}
+void set_last_error_text(const std::string& s) { g_last_error = s; }
+
+namespace {
+
+int check_partition(const int32_t* sizes, int32_t V, int32_t B) {
+  if (!sizes || V < 1 || B < 1) return VF_EINVAL;
+  int64_t sum = 0;
+  for (int32_t i = 0; i < V; ++i) {
+    if (sizes[i] < 1) return VF_EINVAL;
+    sum += sizes[i];
+  }
+  return sum == (int64_t)B ? VF_OK : VF_EINVAL;
+}
+
+int validate_config(const vf_config& c) {
+  if (c.dtype != VF_F32 && c.dtype != VF_BF16) return VF_EINVAL;
+  if (c.optimizer != VF_SGDM && c.optimizer != VF_ADAM) return VF_EINVAL;
+  if (c.max_batch < 1 || c.max_node_size < 1 || c.max_nodes < 1) return VF_EINVAL;
+  if (c.max_node_size > c.max_batch) return VF_EINVAL;
+  if (c.model_kind == VF_MLP) {
+    if (c.n_dims < 2 || c.n_dims > VF_MAX_DIMS) return VF_EINVAL;
+    for (int i = 0; i < c.n_dims; ++i)
+      if (c.dims[i] < 1) return VF_EINVAL;
+    // bf16 rows of the batch are read with 16-byte loads
+    if (c.dtype == VF_BF16 && (c.dims[0] % 8) != 0) return VF_EINVAL;
+    return VF_OK;
+  }
+  if (c.model_kind == VF_ENCODER) {
+    if (c.n_layers < 1 || c.d_model < 1 || c.n_heads < 1 || c.d_ffn < 1 || c.seq_len < 1 ||
+        c.vocab < 1 || c.n_masked < 1)
+      return VF_EINVAL;
+    if (c.d_model % c.n_heads) return VF_EINVAL;
+    if (c.n_masked > c.seq_len) return VF_EINVAL;
+    if (c.dtype == VF_BF16 && ((c.d_model % 8) || (c.d_ffn % 8) || ((c.d_model / c.n_heads) % 8)))
+      return VF_EINVAL;
+    return VF_OK;
+  }
+  return VF_EINVAL;
+}
+
+// Enqueue everything of one step except the optimizer update.
+int enqueue_nodes(Ctx& c, const StepArgs& a) {
+  VF_TRY(c.model->prepare(c, a.params));
+  for (int i = 0; i < a.V; ++i) {
+    VF_TRY(c.model->run_node(c, a, i));
+    if (!c.fused) VF_TRY(launch_accumulate(c.gbuf, c.gstage, a.w[i], c.P, i == 0, c.stream));
+  }
+  return VF_OK;
+}
+
+int enqueue_update(Ctx& c, float* params) {
+  const vf_config& f = c.cfg;
+  if (f.optimizer == VF_SGDM)
+    return launch_sgdm(params, c.opt0, c.gbuf, f.lr, f.momentum, c.P, c.stream);
+  const double t = (double)(c.steps + 1);
+  const float inv_c1 = (float)(1.0 / (1.0 - std::pow((double)f.beta1, t)));
+  const float inv_c2 = (float)(1.0 / (1.0 - std::pow((double)f.beta2, t)));
+  return launch_adam(params, c.opt0, c.opt1, c.gbuf, f.lr, f.beta1, f.beta2, f.adam_eps, inv_c1,
+                     inv_c2, c.P, c.stream);
+}
+
+bool graph_matches(const Ctx& c, const StepArgs& a) {
+  return c.graph_exec && c.graph_params == a.params && c.graph_x == a.x && c.graph_y == a.y &&
+         c.graph_sizes == a.sizes;
+}
+
+void drop_graph(Ctx& c) {
+  if (c.graph_exec) {
+    (void)hipGraphExecDestroy(c.graph_exec);
+    c.graph_exec = nullptr;
+  }
+}
+
+// Record the node sequence of this step into a graph and instantiate it.
+int capture_graph(Ctx& c, const StepArgs& a) {
+  drop_graph(c);
+  hipGraph_t graph = nullptr;
+  VF_HIP(hipStreamBeginCapture(c.stream, hipStreamCaptureModeThreadLocal));
+  int rc = enqueue_nodes(c, a);
+  hipError_t e = hipStreamEndCapture(c.stream, &graph);
+  if (rc != VF_OK) {
+    if (graph) (void)hipGraphDestroy(graph);
+    return rc;
+  }
+  if (e != hipSuccess) {
+    set_last_error("hipStreamEndCapture", e, __FILE__, __LINE__);
+    return VF_EDEVICE;
+  }
+  e = hipGraphInstantiate(&c.graph_exec, graph, nullptr, nullptr, 0);
+  (void)hipGraphDestroy(graph);
+  if (e != hipSuccess) {
+    c.graph_exec = nullptr;
+    set_last_error("hipGraphInstantiate", e, __FILE__, __LINE__);
+    return VF_EDEVICE;
+  }
+  c.graph_params = a.params; c.graph_x = a.x; c.graph_y = a.y; c.graph_sizes = a.sizes;
+  return VF_OK;
+}
+
+int copy_out(Ctx& c, const float* src, float* out, size_t count) {
+  VF_HIP(hipMemcpyAsync(out, src, count * sizeof(float), hipMemcpyDefault, c.stream));
+  VF_HIP(hipStreamSynchronize(c.stream));
+  return VF_OK;
+}
+
+}  // namespace
+}  // namespace vf
+
+using namespace vf;
+
+extern "C" {
+
+int vf_partition(const int32_t* node_sizes, int32_t V, int32_t B, int32_t* off_out, float* w_out) {
+  int rc = check_partition(node_sizes, V, B);
+  if (rc != VF_OK) return rc;
+  if (off_out) {
+    off_out[0] = 0;
+    for (int32_t i = 0; i < V; ++i) off_out[i + 1] = off_out[i] + node_sizes[i];
+  }
+  if (w_out)
+    for (int32_t i = 0; i < V; ++i) w_out[i] = (float)node_sizes[i] / (float)B;
+  return VF_OK;
+}
+
+int vf_init(const vf_config* cfg, vf_ctx** out) {
+  if (out) *out = nullptr;
+  if (!cfg || !out) return VF_EINVAL;
+  int rc = validate_config(*cfg);
+  if (rc != VF_OK) return rc;
+  vf_ctx* h = new (std::nothrow) vf_ctx();
+  if (!h) return VF_ENOMEM;
+  Ctx& c = h->c;
+  c.cfg = *cfg;
+  c.stream = static_cast<hipStream_t>(cfg->stream);
+  if (!c.stream) c.cfg.flags |= VF_FLAG_NO_GRAPH;   // the default stream cannot be captured
+  c.bf16 = cfg->dtype == VF_BF16;
+  c.fused = (cfg->flags & VF_FLAG_FUSED_ACCUMULATE) != 0;
+  hipError_t e = hipGetDevice(&c.device);
+  if (e != hipSuccess) {
+    set_last_error("hipGetDevice", e, __FILE__, __LINE__);
+    delete h;
+    return VF_EDEVICE;
+  }
+  c.model = cfg->model_kind == VF_MLP ? make_mlp(*cfg) : make_encoder(*cfg);
+  if (!c.model) { delete h; return VF_EINVAL; }
+  c.P = c.model->num_params();
+
+  Arena arena;
+  arena.request(&c.gbuf, (size_t)c.P);
+  if (!c.fused) arena.request(&c.gstage, (size_t)c.P);
+  arena.request(&c.opt0, (size_t)c.P);
+  if (cfg->optimizer == VF_ADAM) arena.request(&c.opt1, (size_t)c.P);
+  size_t loss_rows = (size_t)cfg->max_node_size;
+  if (cfg->model_kind == VF_ENCODER) loss_rows *= (size_t)cfg->n_masked;
+  arena.request(&c.rowloss, loss_rows);
+  arena.request(&c.node_loss, (size_t)cfg->max_nodes);
+  arena.request(&c.loss_total, 1);
+  c.model->request_buffers(arena);
+  c.arena_bytes = arena.total();
+  e = hipMalloc(reinterpret_cast<void**>(&c.arena), c.arena_bytes);
+  if (e != hipSuccess) {
+    set_last_error("hipMalloc", e, __FILE__, __LINE__);
+    c.arena = nullptr;
+    (void)hipGetLastError();
+    delete h;
+    return VF_ENOMEM;
+  }
+  arena.assign(c.arena);
+  // optimizer state and loss cells start at zero
+  e = hipMemsetAsync(c.arena, 0, c.arena_bytes, c.stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(c.stream);
+  if (e != hipSuccess) {
+    set_last_error("hipMemsetAsync", e, __FILE__, __LINE__);
+    (void)hipFree(c.arena);
+    delete h;
+    return VF_EDEVICE;
+  }
+  *out = h;
+  return VF_OK;
+}
+
+int vf_step(vf_ctx* h, void* params, const void* batch_x, const int32_t* batch_y, int32_t B,
+            int32_t V, const int32_t* node_sizes) {
+  if (!h || !params || !batch_x || !batch_y) return VF_EINVAL;
+  Ctx& c = h->c;
+  int rc = check_partition(node_sizes, V, B);
+  if (rc != VF_OK) return rc;
+  if (V > c.cfg.max_nodes || B > c.cfg.max_batch) return VF_EINVAL;
+  for (int32_t i = 0; i < V; ++i)
+    if (node_sizes[i] > c.cfg.max_node_size) return VF_EINVAL;
+  if (reinterpret_cast<uintptr_t>(params) & 15) return VF_EINVAL;
+
+  StepArgs a;
+  a.params = static_cast<float*>(params);
+  a.x = batch_x; a.y = batch_y; a.B = B; a.V = V;
+  a.sizes.assign(node_sizes, node_sizes + V);
+  a.off.resize(V + 1);
+  a.w.resize(V);
+  vf_partition(node_sizes, V, B, a.off.data(), a.w.data());
+
+  if (c.cfg.flags & VF_FLAG_NO_GRAPH) {
+    VF_TRY(enqueue_nodes(c, a));
+  } else {
+    if (!graph_matches(c, a)) VF_TRY(capture_graph(c, a));
+    VF_HIP(hipGraphLaunch(c.graph_exec, c.stream));
+  }
+  VF_TRY(enqueue_update(c, a.params));
+  c.steps += 1;
+  c.last_V = V;
+  return VF_OK;
+}
+
+int vf_grads(vf_ctx* h, float* out) {
+  if (!h || !out) return VF_EINVAL;
+  if (h->c.steps == 0) return VF_ESTATE;
+  return copy_out(h->c, h->c.gbuf, out, (size_t)h->c.P);
+}
+
+int vf_loss(vf_ctx* h, float* out) {
+  if (!h || !out) return VF_EINVAL;
+  if (h->c.steps == 0) return VF_ESTATE;
+  return copy_out(h->c, h->c.loss_total, out, 1);
+}
+
+int vf_node_losses(vf_ctx* h, float* out, int32_t V) {
+  if (!h || !out) return VF_EINVAL;
+  if (h->c.steps == 0) return VF_ESTATE;
+  if (V != h->c.last_V) return VF_EINVAL;
+  return copy_out(h->c, h->c.node_loss, out, (size_t)V);
+}
+
+int vf_opt_state(vf_ctx* h, int32_t which, float* out) {
+  if (!h || !out) return VF_EINVAL;
+  Ctx& c = h->c;
+  if (which == 0) return copy_out(c, c.opt0, out, (size_t)c.P);
+  if (which == 1 && c.cfg.optimizer == VF_ADAM) return copy_out(c, c.opt1, out, (size_t)c.P);
+  return VF_EINVAL;
+}
+
+int64_t vf_step_count(const vf_ctx* h) { return h ? h->c.steps : 0; }
+int64_t vf_num_params(const vf_ctx* h) { return h ? h->c.P : 0; }
+size_t vf_workspace_bytes(const vf_ctx* h) { return h ? h->c.arena_bytes : 0; }
+
+void vf_destroy(vf_ctx* h) {
+  if (!h) return;
+  Ctx& c = h->c;
+  if (c.arena) {
+    (void)hipStreamSynchronize(c.stream);
+    drop_graph(c);
+    (void)hipFree(c.arena);
+  }
+  delete h;
+}
+
+const char* vf_strerror(int code) {
+  switch (code) {
+    case VF_OK: return "ok";
+    case VF_EINVAL: return "invalid argument";
+    case VF_ENOMEM: return "out of memory";
+    case VF_EDEVICE: return "device error";
+    case VF_ESTATE: return "call made in the wrong state";
+    default: return "unknown error";
+  }
+}
+
+const char* vf_last_error(void) { return g_last_error.c_str(); }
+
+int vf_accumulate(float* buf, const float* g, float w, int64_t n, int32_t first, void* stream) {
+  return launch_accumulate(buf, g, w, n, first, static_cast<hipStream_t>(stream));
+}
+
+int vf_sgdm_update(float* theta, float* v, const float* G, float lr, float momentum, int64_t n,
+                   void* stream) {
+  return launch_sgdm(theta, v, G, lr, momentum, n, static_cast<hipStream_t>(stream));
+}
+
+int vf_adam_update(float* theta, float* m, float* u, const float* G, float lr, float beta1,
+                   float beta2, float eps, int64_t t, int64_t n, void* stream) {
+  if (t < 1) return VF_EINVAL;
+  const float inv_c1 = (float)(1.0 / (1.0 - std::pow((double)beta1, (double)t)));
+  const float inv_c2 = (float)(1.0 / (1.0 - std::pow((double)beta2, (double)t)));
+  return launch_adam(theta, m, u, G, lr, beta1, beta2, eps, inv_c1, inv_c2, n,
+                     static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

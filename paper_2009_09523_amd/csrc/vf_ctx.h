@@ -1,0 +1,99 @@
+// The library context: configuration, parameter layout, device buffers, per-model runners.
+#pragma once
+
+#include <memory>
+#include <string>
+#include <vector>
+
+#include "vf_internal.h"
+
+namespace vf {
+
+// Collects buffer requests, then carves them out of one device allocation.
+class Arena {
+ public:
+  template <typename T>
+  void request(T** target, size_t count) {
+    size_t bytes = (count * sizeof(T) + 255) & ~size_t(255);
+    reqs_.push_back({reinterpret_cast<void**>(target), total_});
+    total_ += bytes;
+  }
+  size_t total() const { return total_; }
+  void assign(char* base) {
+    for (auto& r : reqs_) *r.target = base + r.offset;
+  }
+
+ private:
+  struct Req { void** target; size_t offset; };
+  std::vector<Req> reqs_;
+  size_t total_ = 0;
+};
+
+struct StepArgs {
+  float* params;
+  const void* x;
+  const int32_t* y;
+  int32_t B, V;
+  std::vector<int32_t> sizes, off;
+  std::vector<float> w;
+};
+
+struct Ctx;
+
+// A model = parameter layout + buffers + the launch sequence of one virtual node.
+class Model {
+ public:
+  virtual ~Model() {}
+  virtual int64_t num_params() const = 0;
+  virtual void request_buffers(Arena& a) = 0;
+  // Refresh whatever the passes read instead of the fp32 master (bf16 weight copies).
+  virtual int prepare(Ctx& c, const float* params) = 0;
+  // Forward + backward of node `i` (rows off..off+b): loss bookkeeping and gradients
+  // through `gout(flat offset)`.
+  virtual int run_node(Ctx& c, const StepArgs& a, int i) = 0;
+};
+
+struct Ctx {
+  vf_config cfg;
+  hipStream_t stream = nullptr;
+  int device = 0;
+  bool bf16 = false;
+  bool fused = false;
+  int64_t P = 0;
+  std::unique_ptr<Model> model;
+
+  char* arena = nullptr;
+  size_t arena_bytes = 0;
+  float* gbuf = nullptr;      // combined gradient G (the shared gradient buffer)
+  float* gstage = nullptr;    // one node's gradient g_i (unused when fused)
+  float* opt0 = nullptr;      // v (SGD-momentum) or m (Adam)
+  float* opt1 = nullptr;      // u (Adam)
+  float* rowloss = nullptr;   // per-row losses of the node in flight
+  float* node_loss = nullptr; // [max_nodes]
+  float* loss_total = nullptr;
+
+  int64_t steps = 0;
+  int32_t last_V = 0;
+
+  // graph replay of the node sequence
+  hipGraphExec_t graph_exec = nullptr;
+  std::vector<int32_t> graph_sizes;
+  const void* graph_params = nullptr;
+  const void* graph_x = nullptr;
+  const void* graph_y = nullptr;
+
+  // Destination of node i's gradient entry at flat offset `off`.
+  GradOut gout(int64_t off, float w, int node) const {
+    if (fused) return GradOut{gbuf + off, w, node > 0 ? 1 : 0};
+    return GradOut{gstage + off, 1.0f, 0};
+  }
+};
+
+std::unique_ptr<Model> make_mlp(const vf_config& cfg);
+std::unique_ptr<Model> make_encoder(const vf_config& cfg);
+
+}  // namespace vf
+
+struct vf_ctx {
+  vf::Ctx c;
+};

@@ -1,0 +1,124 @@
+// Internal declarations shared by the host code and the kernel launchers of libvf.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "vf.h"
+
+namespace vf {
+
+// ---------------------------------------------------------------------------------------
+// errors
+// ---------------------------------------------------------------------------------------
+void set_last_error(const char* what, hipError_t e, const char* file, int line);
+void set_last_error_text(const std::string& s);
+
+#define VF_HIP(expr)                                              \
+  do {                                                            \
+    hipError_t e__ = (expr);                                      \
+    if (e__ != hipSuccess) {                                      \
+      ::vf::set_last_error(#expr, e__, __FILE__, __LINE__);       \
+      return VF_EDEVICE;                                          \
+    }                                                             \
+  } while (0)
+
+#define VF_TRY(expr)            \
+  do {                          \
+    int rc__ = (expr);          \
+    if (rc__ != VF_OK) return rc__; \
+  } while (0)
+
+#define VF_LAUNCH_CHECK() VF_HIP(hipGetLastError())
+
+// ---------------------------------------------------------------------------------------
+// element types
+// ---------------------------------------------------------------------------------------
+typedef uint16_t bf16_t;   // raw bfloat16 bits
+
+// Where a gradient-producing kernel puts a value v for flat index p:
+//   accumulate == 0 :  dst[p] = alpha * v            (written as fma(alpha, v, 0))
+//   accumulate != 0 :  dst[p] = fma(alpha, v, dst[p])
+// With the staging vector: alpha = 1, accumulate = 0.  Fused into the gradient buffer:
+// alpha = b_i/B, accumulate = (node index > 0).
+struct GradOut {
+  float* dst;
+  float alpha;
+  int accumulate;
+};
+
+// Epilogue of a GEMM:  C[m,n] = fma(alpha, acc[m,n], fma(beta, R[m,n], bias[n]))
+// (with bias = 0 and beta = 1 this is the single fused multiply-add R + alpha*acc).
+struct Epilogue {
+  float alpha = 1.f;
+  const float* bias = nullptr;   // fp32 [N] or null
+  int bias_round_bf16 = 0;       // round bias values to bf16 before adding
+  const float* R = nullptr;      // fp32 addend (may alias C) or null
+  int64_t ldr = 0;
+  float beta = 0.f;
+  void* C = nullptr;
+  int64_t ldc = 0;
+  int c_is_bf16 = 0;             // store C as bf16 (RNE) instead of fp32
+};
+
+// ---------------------------------------------------------------------------------------
+// kernel launchers (each returns VF_OK or VF_EDEVICE/VF_EINVAL); all asynchronous
+// ---------------------------------------------------------------------------------------
+
+// k_accum_opt.hip
+int launch_accumulate(float* buf, const float* g, float w, int64_t n, int first, hipStream_t s);
+int launch_sgdm(float* theta, float* v, const float* G, float lr, float mu, int64_t n, hipStream_t s);
+int launch_adam(float* theta, float* m, float* u, const float* G, float lr, float b1, float b2,
+                float eps, float inv_c1, float inv_c2, int64_t n, hipStream_t s);
+int launch_fill_f32(float* p, float value, int64_t n, hipStream_t s);
+
+// k_gemm_f32.hip:  acc[m,n] = sum_k A[m*sam + k*sak] * B[n*sbn + k*sbk]   (fp32)
+int launch_gemm_f32(const float* A, int64_t sam, int64_t sak, const float* B, int64_t sbn,
+                    int64_t sbk, int M, int N, int K, const Epilogue& ep, hipStream_t s);
+
+// k_gemm_bf16.hip: acc[m,n] = sum_k A[m*lda + k] * B[n*ldb + k]  (bf16 operands, fp32 MFMA
+// accumulation).  lda, ldb multiples of 8, A and B 16-byte aligned.
+int launch_gemm_bf16(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, int M, int N,
+                     int K, const Epilogue& ep, hipStream_t s);
+
+// k_elem.hip
+// out[c*ldo + r] = in[r*ldi + c]  for r < R, c < C
+int launch_transpose_bf16(const bf16_t* in, int64_t ldi, bf16_t* out, int64_t ldo, int R, int C,
+                          hipStream_t s);
+// fp32 [R,C] (ld = C) -> bf16 natural copy [R, ldn] and transposed copy [C, ldt]
+int launch_cast_weight(const float* w, int R, int C, bf16_t* nat, int64_t ldn, bf16_t* tr,
+                       int64_t ldt, hipStream_t s);
+// fp32 [R,C] -> bf16 [R,C] with the given leading dimensions
+int launch_cast_bf16(const float* in, int64_t ldi, bf16_t* out, int64_t ldo, int R, int C,
+                     hipStream_t s);
+
+// k_norm.hip -- T is float or bf16_t (is_bf16 selects)
+// BatchNorm over the R rows given + ReLU:  a = relu(gamma*xhat + beta); saves mean, rstd.
+// With gamma == nullptr: a = relu(z) (plain bias-free ReLU; the bias is in the GEMM epilogue).
+int launch_bn_relu_fwd(const float* z, int64_t ldz, int R, int C, const float* gamma,
+                       const float* beta, int round_params, float eps, void* a, int64_t lda,
+                       int a_is_bf16, float* mean, float* rstd, hipStream_t s);
+// Backward of the above.  da: fp32 gradient w.r.t. a.  Writes dz (T) and, with BatchNorm,
+// dgamma/dbeta through GradOut; without BatchNorm (gamma == nullptr) writes the bias
+// gradient (column sums of dz) through gout_b.
+int launch_bn_relu_bwd(const float* da, int64_t ldda, const float* z, int64_t ldz, int R, int C,
+                       const float* gamma, const float* beta, int round_params,
+                       const float* mean, const float* rstd, void* dz, int64_t lddz,
+                       int dz_is_bf16, GradOut gout_g, GradOut gout_b, hipStream_t s);
+// out[c] = sum_r x[r*ld + c] through GradOut (x is T)
+int launch_colsum(const void* x, int64_t ld, int x_is_bf16, int R, int C, GradOut out,
+                  hipStream_t s);
+
+// k_loss.hip
+// Softmax cross-entropy over R rows of fp32 logits [R, ldz] with C classes:
+//   rowloss[r] = logsumexp(z_r) - z_r[label_r];  dz[r,c] = (softmax(z_r)[c] - [c==label_r]) / R
+int launch_softmax_xent(const float* z, int64_t ldz, const int32_t* labels, int R, int C,
+                        float* rowloss, void* dz, int64_t lddz, int dz_is_bf16, hipStream_t s);
+// node_loss[i] = (1/R) sum_r rowloss[r];  total = (i == 0 ? 0 : total) + w * node_loss[i]
+int launch_loss_reduce(const float* rowloss, int R, float w, int node, float* node_loss,
+                       float* total, hipStream_t s);
+
+}  // namespace vf

@@ -1,0 +1,169 @@
+// MLP with optional per-node BatchNorm: buffers and the launch sequence of one virtual node
+// (forward, loss, backward), Section 3.2 steps 1-3.
+#include "vf_ctx.h"
+
+namespace vf {
+namespace {
+
+inline int64_t round8(int64_t v) { return (v + 7) & ~int64_t(7); }
+
+struct Layer {
+  int K = 0, N = 0;
+  bool hidden = false, has_bias = false, has_bn = false;
+  int64_t w_off = -1, b_off = -1, g_off = -1, be_off = -1;   // flat parameter offsets
+  int64_t ldn = 0, ldt = 0;        // leading dims of the bf16 weight copies
+  bf16_t* wnat = nullptr;          // bf16 W  [K, ldn]   (contraction = N: input gradients)
+  bf16_t* wtr = nullptr;           // bf16 W^T [N, ldt]  (contraction = K: forward)
+  int64_t ld = 0;                  // leading dim of this layer's [b, N] buffers (N rounded to 8)
+  float* z = nullptr;              // fp32 [max_b, ld]: Linear output (logits for the last layer)
+  float* mean = nullptr;           // [N]
+  float* rstd = nullptr;           // [N]
+  void* a = nullptr;               // T [max_b, ld]: activation after BatchNorm/ReLU
+  float* da = nullptr;             // fp32 [max_b, ld]: gradient w.r.t. a
+  void* dz = nullptr;              // T [max_b, ld]: gradient w.r.t. z
+  bf16_t* aT = nullptr;            // bf16 [N, ldb]: a transposed   (weight-gradient operand)
+  bf16_t* dzT = nullptr;           // bf16 [N, ldb]: dz transposed  (weight-gradient operand)
+};
+
+class Mlp final : public Model {
+ public:
+  explicit Mlp(const vf_config& cfg) : cfg_(cfg) {
+    bf16_ = cfg.dtype == VF_BF16;
+    const int nl = cfg.n_dims - 1;
+    int64_t off = 0;
+    layers_.resize(nl);
+    for (int l = 0; l < nl; ++l) {
+      Layer& L = layers_[l];
+      L.K = cfg.dims[l];
+      L.N = cfg.dims[l + 1];
+      L.hidden = l < nl - 1;
+      L.has_bn = L.hidden && cfg.batchnorm;
+      L.has_bias = !L.has_bn;
+      L.w_off = off; off += (int64_t)L.K * L.N;
+      if (L.has_bias) { L.b_off = off; off += L.N; }
+      if (L.has_bn) { L.g_off = off; off += L.N; L.be_off = off; off += L.N; }
+      L.ld = round8(L.N);
+      L.ldn = round8(L.N);
+      L.ldt = round8(L.K);
+    }
+    P_ = off;
+    ldb_ = round8(cfg.max_node_size);
+  }
+
+  int64_t num_params() const override { return P_; }
+
+  void request_buffers(Arena& a) override {
+    const size_t mb = (size_t)cfg_.max_node_size;
+    const size_t esz = bf16_ ? 2 : 4;
+    for (Layer& L : layers_) {
+      a.request(&L.z, mb * L.ld);
+      a.request(reinterpret_cast<char**>(&L.dz), mb * L.ld * esz);
+      if (L.hidden) {
+        a.request(&L.mean, (size_t)L.N);
+        a.request(&L.rstd, (size_t)L.N);
+        a.request(reinterpret_cast<char**>(&L.a), mb * L.ld * esz);
+        a.request(&L.da, mb * L.ld);
+      }
+      if (bf16_) {
+        a.request(&L.wnat, (size_t)L.K * L.ldn);
+        a.request(&L.wtr, (size_t)L.N * L.ldt);
+        a.request(&L.dzT, (size_t)L.N * ldb_);
+        if (L.hidden) a.request(&L.aT, (size_t)L.N * ldb_);
+      }
+    }
+    if (bf16_) a.request(&xT_, (size_t)cfg_.dims[0] * ldb_);
+  }
+
+  int prepare(Ctx& c, const float* params) override {
+    if (!bf16_) return VF_OK;
+    for (Layer& L : layers_)
+      VF_TRY(launch_cast_weight(params + L.w_off, L.K, L.N, L.wnat, L.ldn, L.wtr, L.ldt, c.stream));
+    return VF_OK;
+  }
+
+  int run_node(Ctx& c, const StepArgs& s, int i) override {
+    hipStream_t st = c.stream;
+    const int b = s.sizes[i];
+    const int64_t row0 = s.off[i];
+    const float w = s.w[i];
+    const float* P = s.params;
+    const int nl = (int)layers_.size();
+    const int D = cfg_.dims[0];
+    const void* x = bf16_ ? (const void*)(static_cast<const bf16_t*>(s.x) + row0 * D)
+                          : (const void*)(static_cast<const float*>(s.x) + row0 * D);
+    const int32_t* y = s.y + row0;
+
+    // ---- forward -----------------------------------------------------------------------
+    for (int l = 0; l < nl; ++l) {
+      Layer& L = layers_[l];
+      const void* in = l == 0 ? x : layers_[l - 1].a;
+      const int64_t ldin = l == 0 ? D : layers_[l - 1].ld;
+      Epilogue ep;
+      ep.C = L.z; ep.ldc = L.ld;
+      if (L.has_bias) { ep.bias = P + L.b_off; ep.bias_round_bf16 = bf16_; }
+      if (bf16_)
+        VF_TRY(launch_gemm_bf16(static_cast<const bf16_t*>(in), ldin, L.wtr, L.ldt, b, L.N, L.K, ep, st));
+      else
+        VF_TRY(launch_gemm_f32(static_cast<const float*>(in), ldin, 1, P + L.w_off, 1, L.N, b, L.N, L.K, ep, st));
+      if (L.hidden)
+        VF_TRY(launch_bn_relu_fwd(L.z, L.ld, b, L.N, L.has_bn ? P + L.g_off : nullptr,
+                                  L.has_bn ? P + L.be_off : nullptr, bf16_, cfg_.bn_eps, L.a, L.ld,
+                                  bf16_, L.mean, L.rstd, st));
+    }
+    Layer& last = layers_[nl - 1];
+    VF_TRY(launch_softmax_xent(last.z, last.ld, y, b, last.N, c.rowloss, last.dz, last.ld, bf16_, st));
+    VF_TRY(launch_loss_reduce(c.rowloss, b, w, i, c.node_loss, c.loss_total, st));
+
+    // ---- backward ----------------------------------------------------------------------
+    for (int l = nl - 1; l >= 0; --l) {
+      Layer& L = layers_[l];
+      const void* in = l == 0 ? x : layers_[l - 1].a;
+      const int64_t ldin = l == 0 ? D : layers_[l - 1].ld;
+      if (!L.hidden)   // last layer: bias gradient = column sums of dlogits
+        VF_TRY(launch_colsum(L.dz, L.ld, bf16_, b, L.N, c.gout(L.b_off, w, i), st));
+      // weight gradient dW[K,N] = in^T dz
+      GradOut go = c.gout(L.w_off, w, i);
+      Epilogue ep;
+      ep.C = go.dst; ep.ldc = L.N; ep.alpha = go.alpha;
+      if (go.accumulate) { ep.R = go.dst; ep.ldr = L.N; ep.beta = 1.f; }
+      if (bf16_) {
+        bf16_t* inT = l == 0 ? xT_ : layers_[l - 1].aT;
+        VF_TRY(launch_transpose_bf16(static_cast<const bf16_t*>(in), ldin, inT, ldb_, b, L.K, st));
+        VF_TRY(launch_transpose_bf16(static_cast<const bf16_t*>(L.dz), L.ld, L.dzT, ldb_, b, L.N, st));
+        VF_TRY(launch_gemm_bf16(inT, ldb_, L.dzT, ldb_, L.K, L.N, b, ep, st));
+      } else {
+        VF_TRY(launch_gemm_f32(static_cast<const float*>(in), 1, ldin, static_cast<const float*>(L.dz), 1,
+                               L.ld, L.K, L.N, b, ep, st));
+      }
+      if (l == 0) break;
+      // input gradient da[l-1][b,K] = dz W^T, then through ReLU / BatchNorm of layer l-1
+      Layer& Pv = layers_[l - 1];
+      Epilogue ed;
+      ed.C = Pv.da; ed.ldc = Pv.ld;
+      if (bf16_)
+        VF_TRY(launch_gemm_bf16(static_cast<const bf16_t*>(L.dz), L.ld, L.wnat, L.ldn, b, L.K, L.N, ed, st));
+      else
+        VF_TRY(launch_gemm_f32(static_cast<const float*>(L.dz), L.ld, 1, P + L.w_off, L.N, 1, b, L.K, L.N, ed, st));
+      GradOut gg = Pv.has_bn ? c.gout(Pv.g_off, w, i) : GradOut{nullptr, 0.f, 0};
+      GradOut gb = c.gout(Pv.has_bn ? Pv.be_off : Pv.b_off, w, i);
+      VF_TRY(launch_bn_relu_bwd(Pv.da, Pv.ld, Pv.z, Pv.ld, b, Pv.N, Pv.has_bn ? P + Pv.g_off : nullptr,
+                                Pv.has_bn ? P + Pv.be_off : nullptr, bf16_, Pv.mean, Pv.rstd, Pv.dz,
+                                Pv.ld, bf16_, gg, gb, st));
+    }
+    return VF_OK;
+  }
+
+ private:
+  vf_config cfg_;
+  bool bf16_ = false;
+  int64_t P_ = 0;
+  int64_t ldb_ = 0;
+  std::vector<Layer> layers_;
+  bf16_t* xT_ = nullptr;
+};
+
+}  // namespace
+
+std::unique_ptr<Model> make_mlp(const vf_config& cfg) { return std::unique_ptr<Model>(new Mlp(cfg)); }
+
+}  // namespace vf

@@ -1,0 +1,94 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, partitions bit-exactly like the oracle, and rejects bad arguments."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle as O
+import paper_2009_09523_amd as vf
+from paper_2009_09523_amd import binding
+import vf_inputs as I
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_in_header():
+    text = open(os.path.join(ROOT, "include", "vf.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(vf_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    declared = _declared_in_header()
+    assert declared == vf.exported_symbols()
+    L = C.CDLL(vf.lib_path())
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+@pytest.mark.parametrize("sizes", [[16] * 4, [48, 48, 32, 32, 16, 16, 48, 16], [1], [7, 1, 300], [128] * 64,
+                                   [3, 5, 7, 11, 13]])
+def test_partition_bit_exact_with_oracle(sizes):
+    B = sum(sizes)
+    off, w = vf.vf_partition(sizes, B)
+    o_off, o_w = O.partition(sizes, B)
+    assert off.dtype == o_off.dtype == np.int32
+    assert off.tobytes() == o_off.tobytes()
+    assert w.tobytes() == o_w.tobytes()
+
+
+@pytest.mark.parametrize("sizes,B", [([], 0), ([0, 4], 4), ([3, 3], 7), ([-1, 5], 4), ([4], 0)])
+def test_partition_rejects(sizes, B):
+    with pytest.raises(vf.VfError) as e:
+        vf.vf_partition(sizes, B)
+    assert e.value.code == binding.VF_EINVAL
+
+
+def test_partition_null_and_untouched_outputs():
+    L = vf.lib()
+    assert L.vf_partition(None, 2, 4, None, None) == binding.VF_EINVAL
+    sizes = (C.c_int32 * 2)(3, 2)
+    off = (C.c_int32 * 3)(-7, -7, -7)
+    assert L.vf_partition(sizes, 2, 6, off, None) == binding.VF_EINVAL
+    assert list(off) == [-7, -7, -7]
+    assert L.vf_partition(sizes, 2, 5, off, None) == binding.VF_OK
+    assert list(off) == [0, 3, 5]
+
+
+def _cfg(**kw):
+    cfg = binding.config_from_workload(I.workload("C1"))
+    for k, v in kw.items():
+        setattr(cfg, k, v)
+    return cfg
+
+
+@pytest.mark.parametrize("kw", [dict(dtype=7), dict(optimizer=3), dict(max_nodes=0), dict(max_node_size=0),
+                                dict(n_dims=1), dict(n_dims=17), dict(model_kind=5),
+                                dict(max_node_size=100, max_batch=64)])
+def test_init_rejects_bad_config_before_touching_the_device(kw):
+    h = C.c_void_p(123)
+    cfg = _cfg(**kw)
+    assert vf.lib().vf_init(C.byref(cfg), C.byref(h)) == binding.VF_EINVAL
+    assert not h.value
+
+
+def test_init_null_arguments():
+    L = vf.lib()
+    h = C.c_void_p()
+    assert L.vf_init(None, C.byref(h)) == binding.VF_EINVAL
+    assert L.vf_step(None, None, None, None, 1, 1, None) == binding.VF_EINVAL
+    assert L.vf_grads(None, None) == binding.VF_EINVAL
+    assert L.vf_num_params(None) == 0
+    L.vf_destroy(None)
+    assert L.vf_strerror(binding.VF_EINVAL).decode() == "invalid argument"
+
+
+def test_bf16_mlp_needs_16_byte_rows():
+    wl = I.Workload(name="odd", kind="mlp", dims=(100, 16, 4), batchnorm=False, node_sizes=(4,),
+                    dtype="bf16")
+    cfg = binding.config_from_workload(wl)
+    h = C.c_void_p()
+    assert vf.lib().vf_init(C.byref(cfg), C.byref(h)) == binding.VF_EINVAL

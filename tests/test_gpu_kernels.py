@@ -1,0 +1,79 @@
+"""GPU parity of the two bandwidth-bound kernels on their own (accumulate, optimizer)."""
+import numpy as np
+import pytest
+
+import oracle as O
+import vf_inputs as I
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("n", [1, 3, 4, 1023, 1024, 4096 + 5, 203530, 5_000_003])
+def test_accumulate_matches_weighted_sum(n):
+    import torch
+    import paper_2009_09523_amd as vf
+    print(f"accumulate n={n}", flush=True)
+    sizes = [48, 48, 32, 32, 16, 16, 48, 16]
+    off, w = O.partition(sizes, 256)
+    g = I.make_flat_gradients(n, len(sizes))
+    buf = torch.full((n,), 7.0, device="cuda")            # stale contents must be overwritten
+    want32 = np.zeros(n, dtype=np.float32)
+    want64 = np.zeros(n)
+    for i in range(len(sizes)):
+        gi = torch.from_numpy(g[i]).cuda()
+        vf.vf_accumulate(buf, gi, float(w[i]), first=(i == 0))
+        want64 += (sizes[i] / 256.0) * g[i].astype(np.float64)
+    torch.cuda.synchronize()
+    got = buf.cpu().numpy()
+    assert np.max(np.abs(got - want64)) <= 1e-6 * np.max(np.abs(want64)) + 1e-7
+    # the kernel's own order of operations: one fused multiply-add per node, in node order
+    acc = np.zeros(n, dtype=np.float64)
+    for i in range(len(sizes)):
+        acc = (np.float64(w[i]) * g[i].astype(np.float64) + acc).astype(np.float32).astype(np.float64)
+    np.testing.assert_array_equal(got, acc.astype(np.float32))
+
+
+def test_accumulate_empty_and_misaligned():
+    import torch
+    import paper_2009_09523_amd as vf
+    buf = torch.zeros(16, device="cuda")
+    g = torch.ones(16, device="cuda")
+    vf.vf_accumulate(buf[:0], g[:0], 1.0, first=True)       # n = 0 is a no-op
+    with pytest.raises(vf.VfError):
+        vf.vf_accumulate(buf[1:9], g[1:9], 1.0, first=True)  # not 16-byte aligned
+
+
+@pytest.mark.parametrize("n", [5, 4096, 1_000_003])
+def test_sgdm_kernel(n):
+    import torch
+    import paper_2009_09523_amd as vf
+    rng = np.random.Generator(np.random.PCG64(n))
+    th0 = rng.standard_normal(n).astype(np.float32)
+    th, v = th0.astype(np.float64), np.zeros(n)
+    tht, vt = torch.from_numpy(th0).cuda(), torch.zeros(n, device="cuda")
+    for step in range(3):
+        G = rng.standard_normal(n).astype(np.float32)
+        vf.vf_sgdm_update(tht, vt, torch.from_numpy(G).cuda(), 0.1, 0.9)
+        th, v = O.sgdm_update(th, G, v, 0.1, 0.9)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(tht.cpu().numpy(), th, rtol=1e-5, atol=1e-6)
+    np.testing.assert_allclose(vt.cpu().numpy(), v, rtol=1e-5, atol=1e-6)
+
+
+@pytest.mark.parametrize("n", [5, 4096, 1_000_003])
+def test_adam_kernel(n):
+    import torch
+    import paper_2009_09523_amd as vf
+    rng = np.random.Generator(np.random.PCG64(n + 1))
+    th0 = rng.standard_normal(n).astype(np.float32)
+    th, m, u = th0.astype(np.float64), np.zeros(n), np.zeros(n)
+    tht = torch.from_numpy(th0).cuda()
+    mt, ut = torch.zeros(n, device="cuda"), torch.zeros(n, device="cuda")
+    for t in range(1, 4):
+        G = rng.standard_normal(n).astype(np.float32)
+        vf.vf_adam_update(tht, mt, ut, torch.from_numpy(G).cuda(), 1e-3, 0.9, 0.999, 1e-8, t)
+        th, m, u = O.adam_update(th, G, m, u, t, 1e-3, 0.9, 0.999, 1e-8)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(tht.cpu().numpy(), th, rtol=1e-5, atol=1e-6)
+    np.testing.assert_allclose(mt.cpu().numpy(), m, rtol=1e-5, atol=1e-7)
+    np.testing.assert_allclose(ut.cpu().numpy(), u, rtol=1e-5, atol=1e-9)

@@ -1,0 +1,128 @@
+"""Shared helpers of the GPU parity tests: run a workload through the C ABI on the device and
+compare with the CPU oracle tensor by tensor."""
+from __future__ import annotations
+
+import numpy as np
+
+import oracle as O
+import vf_inputs as I
+
+# Tolerances of the build's target: fp32 path rel 1e-4, bf16 path (fp32 accumulation) rel 2e-2.
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def to_device_batch(wl, x, y, device="cuda"):
+    import torch
+    if wl.kind == "mlp":
+        xt = torch.from_numpy(x).to(device)
+        if wl.dtype == "bf16":
+            xt = xt.to(torch.bfloat16)          # exact: the generator made x bf16-representable
+    else:
+        xt = torch.from_numpy(x).to(device)
+    yt = torch.from_numpy(y).to(device)
+    return xt.contiguous(), yt.contiguous()
+
+
+def run_gpu(wl, theta, x, y, node_sizes=None, flags=0, steps=1, max_node_size=None, max_nodes=None,
+            max_batch=None):
+    """Runs `steps` vf_step calls on the same batch; returns the results of the last one."""
+    import torch
+    import paper_2009_09523_amd as vf
+    from paper_2009_09523_amd.binding import config_from_workload
+    sizes = list(wl.node_sizes if node_sizes is None else node_sizes)
+    stream = torch.cuda.Stream()
+    cfg = config_from_workload(wl, flags=flags, stream=stream,
+                               max_node_size=max_node_size or max(sizes),
+                               max_nodes=max_nodes or len(sizes), max_batch=max_batch or sum(sizes))
+    eng = vf.VirtualNodeStep(cfg)
+    assert eng.num_params == theta.size
+    params = torch.from_numpy(theta.astype(np.float32)).cuda()
+    xt, yt = to_device_batch(wl, x, y)
+    torch.cuda.synchronize()
+    for _ in range(steps):
+        eng.step(params, xt, yt, sizes)
+    G = torch.empty_like(params)
+    eng.grads(G)
+    out = {"G": G.cpu().numpy(), "loss": eng.loss(), "node_losses": eng.node_losses(len(sizes)),
+           "t": eng.step_count, "workspace_bytes": eng.workspace_bytes}
+    s0 = torch.empty_like(params)
+    eng.opt_state(0, s0)
+    out["s0"] = s0.cpu().numpy()
+    if wl.optimizer == "adam":
+        s1 = torch.empty_like(params)
+        eng.opt_state(1, s1)
+        out["s1"] = s1.cpu().numpy()
+    stream.synchronize()
+    out["theta"] = params.cpu().numpy()
+    eng.close()
+    return out
+
+
+def oracle_steps(wl, theta, x, y, node_sizes=None, steps=1):
+    th = theta.astype(np.float32)
+    state = None
+    r = None
+    for _ in range(steps):
+        r = O.oracle_step(wl, th, x, y, node_sizes=node_sizes, state=state)
+        state = r["state"]
+        th = r["theta"].astype(np.float32)      # the master copy is fp32
+    return r
+
+
+def tensor_errors(wl, got, want):
+    """[(name, rel_l2, max_abs_err / max_abs_ref)] per parameter tensor."""
+    rows, pos = [], 0
+    for name, shape in O.layout(wl):
+        n = int(np.prod(shape))
+        a = np.asarray(got[pos:pos + n], dtype=np.float64)
+        b = np.asarray(want[pos:pos + n], dtype=np.float64)
+        nb, mb = np.linalg.norm(b), np.max(np.abs(b))
+        d = a - b
+        rel = np.linalg.norm(d) / nb if nb > 0 else np.linalg.norm(d)
+        mx = np.max(np.abs(d)) / mb if mb > 0 else np.max(np.abs(d))
+        rows.append((name, float(rel), float(mx)))
+        pos += n
+    return rows
+
+
+def assert_close_per_tensor(wl, got, want, tol, what):
+    bad = [(n, r, m) for n, r, m in tensor_errors(wl, got, want) if not (r <= tol and m <= tol)]
+    assert not bad, f"{what}: tensors beyond tol {tol}: {bad[:8]}"
+
+
+def check_against_oracle(wl, gpu, ref, tol=None, check_theta=True):
+    """Per tensor: ||a-b||2/||b||2 <= tol and max|a-b| <= tol*max|b|; loss relative."""
+    tol = TOL[wl.dtype] if tol is None else tol
+    assert abs(gpu["loss"] - ref["loss"]) <= tol * abs(ref["loss"]), (gpu["loss"], ref["loss"])
+    np.testing.assert_allclose(gpu["node_losses"], ref["node_losses"], rtol=tol)
+    assert_close_per_tensor(wl, gpu["G"], ref["G"], tol, "G")
+    assert gpu["t"] == ref["state"]["t"]
+    if not check_theta:
+        return
+    if wl.optimizer == "sgdm":
+        assert_close_per_tensor(wl, gpu["theta"], ref["theta"], tol, "theta")
+        assert_close_per_tensor(wl, gpu["s0"], ref["state"]["v"], tol, "velocity")
+    else:
+        assert_close_per_tensor(wl, gpu["s0"], ref["state"]["m"], tol, "adam m")
+        assert_close_per_tensor(wl, gpu["s1"], ref["state"]["u"], 2.5 * tol, "adam u")   # quadratic in G
+
+
+def check_update_from_own_gradient(wl, gpu, theta0, tol=1e-5):
+    """The optimizer kernel in isolation: the oracle's update applied to the device's own
+    combined gradient must reproduce the device's new parameters and state (first step).
+    For Adam this is the meaningful check of theta: its step depends on G only through
+    G/|G|, so an element whose gradient is within rounding noise of zero may legitimately
+    move by +lr on one side and -lr on the other."""
+    G = gpu["G"].astype(np.float64)
+    th0 = theta0.astype(np.float32).astype(np.float64)
+    n = G.size
+    if wl.optimizer == "sgdm":
+        th, v = O.sgdm_update(th0, G, np.zeros(n), wl.lr, wl.momentum)
+        assert_close_per_tensor(wl, gpu["theta"], th, tol, "theta from own G")
+        assert_close_per_tensor(wl, gpu["s0"], v, tol, "v from own G")
+    else:
+        th, m, u = O.adam_update(th0, G, np.zeros(n), np.zeros(n), 1, wl.lr, wl.beta1, wl.beta2,
+                                 wl.adam_eps)
+        assert_close_per_tensor(wl, gpu["theta"], th, tol, "theta from own G")
+        assert_close_per_tensor(wl, gpu["s0"], m, tol, "m from own G")
+        assert_close_per_tensor(wl, gpu["s1"], u, tol, "u from own G")
