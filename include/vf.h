@@ -167,6 +167,19 @@ int vf_sgdm_update(float* theta, float* v, const float* G, float lr, float momen
 int vf_adam_update(float* theta, float* m, float* u, const float* G, float lr, float beta1,
                    float beta2, float eps, int64_t t, int64_t n, void* stream);
 
+/* The contraction every Linear layer of a virtual node's forward and backward pass uses
+ * (Section 3.2 steps 1-2), callable on its own:
+ *     C[m,n] = alpha * sum_k A[m*lda + k] * B[n*ldb + k]  (+ C[m,n] if accumulate != 0)
+ * i.e. C = alpha * A * B^T (+ C) with both operands contiguous along the contraction.
+ * dtype VF_BF16: A, B bf16 (device, 16-byte aligned, lda and ldb multiples of 8), products
+ * accumulated in fp32 on the matrix cores; VF_F32: A, B fp32.  C: device fp32 [M, ldc].
+ * Forward y = x W uses B = W^T; input gradient dx = dy W^T uses B = W; weight gradient
+ * dW = x^T dy uses A = x^T, B = dy^T with alpha = b_i/B and accumulate = 1 to fold a node's
+ * gradient straight into the gradient buffer. */
+int vf_gemm(int32_t dtype, const void* A, int64_t lda, const void* B, int64_t ldb, float* C,
+            int64_t ldc, int32_t M, int32_t N, int32_t K, float alpha, int32_t accumulate,
+            void* stream);
+
 #pragma GCC visibility pop
 
 #ifdef __cplusplus

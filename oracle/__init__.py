@@ -13,9 +13,12 @@ with the weights of Section 5.2), written in NumPy float64:
   3. G = sum_i (b_i/B) g_i and L = sum_i (b_i/B) L_i   (Section 5.2);
   4. one optimizer update with G                        (Section 3.2, step 5).
 
-For bf16 workloads the only low-precision step imitated is rounding the fp32
-master parameters to bf16 (round-to-nearest-even) before the forward pass;
-everything else is float64.
+bf16 workloads are defined as "bf16 weights and activations, fp32 accumulation,
+fp32 master weights": the oracle rounds the fp32 master parameters to bf16
+(round-to-nearest-even) before the passes and, in the MLP, rounds every operand
+of a Linear contraction (activations, output gradients) to bf16; everything
+else is float64.  The encoder has no discontinuous activation and rounds the
+parameters only.
 
 Pins (tests/test_oracle_*.py): the 6+2 worked example of Section 5.2 with its
 unweighted negative control; partition-invariance of G without BatchNorm;

@@ -59,7 +59,20 @@ def _flatten(wl, grads):
 
 # ---- one node: loss L_i (mean over the node) and g_i = dL_i/dtheta ----------------------
 
+def _operand(wl):
+    """How a tensor enters a Linear contraction.  bf16 workloads are defined with bf16
+    weights AND activations (fp32 accumulation): every operand of a contraction -- the
+    activation fed to a Linear, and the output gradient fed to its two backward
+    contractions -- is rounded to bf16; everything between contractions stays float64.
+    This also puts the one discontinuous decision of the MLP, the ReLU mask of the next
+    layer, at the same precision on both sides of a parity check."""
+    if wl.dtype == "bf16":
+        return lambda a: round_to_bf16(np.asarray(a, dtype=np.float32))
+    return lambda a: a
+
+
 def _mlp_node(wl, p, x, y):
+    q = _operand(wl)
     n_lin = len(wl.dims) - 1
     h = np.asarray(x, dtype=np.float64)
     saved = []
@@ -70,13 +83,14 @@ def _mlp_node(wl, p, x, y):
         else:
             pre, bn_cache = z, None
         saved.append((h, pre, bn_cache))
-        h = L.relu_fwd(pre)
+        h = q(L.relu_fwd(pre))
     last = n_lin - 1
     logits = L.linear_fwd(h, p[f"l{last}.W"], p[f"l{last}.b"])
     loss, dlogits = L.softmax_xent_fwd_bwd(logits, np.asarray(y, dtype=np.int64))
 
     g = {}
-    dh, g[f"l{last}.W"], g[f"l{last}.b"] = L.linear_bwd(h, p[f"l{last}.W"], dlogits, True)
+    dh, g[f"l{last}.W"], _ = L.linear_bwd(h, p[f"l{last}.W"], q(dlogits), False)
+    g[f"l{last}.b"] = dlogits.sum(axis=0)
     for l in range(n_lin - 2, -1, -1):
         h_in, pre, bn_cache = saved[l]
         dpre = L.relu_bwd(dh, pre)
@@ -84,9 +98,8 @@ def _mlp_node(wl, p, x, y):
             dz, g[f"l{l}.gamma"], g[f"l{l}.beta"] = L.batchnorm_bwd(dpre, p[f"l{l}.gamma"], bn_cache)
         else:
             dz = dpre
-        dh, g[f"l{l}.W"], db = L.linear_bwd(h_in, p[f"l{l}.W"], dz, not wl.batchnorm)
-        if not wl.batchnorm:
-            g[f"l{l}.b"] = db
+            g[f"l{l}.b"] = dz.sum(axis=0)
+        dh, g[f"l{l}.W"], _ = L.linear_bwd(h_in, p[f"l{l}.W"], q(dz), False)
     return loss, g
 
 

@@ -63,6 +63,8 @@ _SIGNATURES = {
                                  C.c_void_p]),
     "vf_adam_update": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_float,
                                  C.c_float, C.c_float, C.c_int64, C.c_int64, C.c_void_p]),
+    "vf_gemm": (C.c_int, [C.c_int32, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
+                          C.c_int32, C.c_int32, C.c_int32, C.c_float, C.c_int32, C.c_void_p]),
 }
 
 
@@ -132,6 +134,17 @@ def vf_adam_update(theta, m, u, G, lr, beta1, beta2, eps, t: int, stream=None):
     _check(lib().vf_adam_update(_ptr(theta), _ptr(m), _ptr(u), _ptr(G), float(lr), float(beta1),
                                 float(beta2), float(eps), int(t), theta.numel(),
                                 _stream_handle(stream)), "vf_adam_update")
+
+
+def vf_gemm(A, B, Cout, M: int, N: int, K: int, alpha: float = 1.0, accumulate: bool = False,
+            stream=None):
+    """Cout[M,N] (fp32) = alpha * A[M,K] B[N,K]^T (+ Cout).  A, B: 2-D torch tensors (bf16 or
+    fp32), unit stride along the contraction."""
+    import torch
+    dtype = VF_BF16 if A.dtype == torch.bfloat16 else VF_F32
+    assert A.dtype == B.dtype and A.stride(1) == 1 and B.stride(1) == 1 and Cout.stride(1) == 1
+    _check(lib().vf_gemm(dtype, _ptr(A), A.stride(0), _ptr(B), B.stride(0), _ptr(Cout), Cout.stride(0),
+                         M, N, K, float(alpha), int(bool(accumulate)), _stream_handle(stream)), "vf_gemm")
 
 
 def config_from_workload(wl, max_batch: Optional[int] = None, max_node_size: Optional[int] = None,

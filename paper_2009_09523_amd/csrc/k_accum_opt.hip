@@ -158,8 +158,8 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 }  // namespace
 
 int launch_accumulate(float* buf, const float* g, float w, int64_t n, int first, hipStream_t s) {
-  if (n < 0 || !buf || !g) return VF_EINVAL;
   if (n == 0) return VF_OK;
+  if (n < 0 || !buf || !g) return VF_EINVAL;
   if (!aligned16(buf) || !aligned16(g)) return VF_EINVAL;
   int grid = grid_for(n >> 2);
   if (first) accumulate_kernel<true><<<grid, kThreads, 0, s>>>(buf, g, w, n);
@@ -169,8 +169,8 @@ int launch_accumulate(float* buf, const float* g, float w, int64_t n, int first,
 }
 
 int launch_sgdm(float* theta, float* v, const float* G, float lr, float mu, int64_t n, hipStream_t s) {
-  if (n < 0 || !theta || !v || !G) return VF_EINVAL;
   if (n == 0) return VF_OK;
+  if (n < 0 || !theta || !v || !G) return VF_EINVAL;
   if (!aligned16(theta) || !aligned16(v) || !aligned16(G)) return VF_EINVAL;
   sgdm_kernel<<<grid_for(n >> 2), kThreads, 0, s>>>(theta, v, G, lr, mu, n);
   VF_LAUNCH_CHECK();
@@ -179,8 +179,8 @@ int launch_sgdm(float* theta, float* v, const float* G, float lr, float mu, int6
 
 int launch_adam(float* theta, float* m, float* u, const float* G, float lr, float b1, float b2,
                 float eps, float inv_c1, float inv_c2, int64_t n, hipStream_t s) {
-  if (n < 0 || !theta || !m || !u || !G) return VF_EINVAL;
   if (n == 0) return VF_OK;
+  if (n < 0 || !theta || !m || !u || !G) return VF_EINVAL;
   if (!aligned16(theta) || !aligned16(m) || !aligned16(u) || !aligned16(G)) return VF_EINVAL;
   adam_kernel<<<grid_for(n >> 2), kThreads, 0, s>>>(theta, m, u, G, lr, b1, b2, eps, inv_c1, inv_c2, n);
   VF_LAUNCH_CHECK();

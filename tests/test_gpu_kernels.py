@@ -74,6 +74,40 @@ def test_adam_kernel(n):
         vf.vf_adam_update(tht, mt, ut, torch.from_numpy(G).cuda(), 1e-3, 0.9, 0.999, 1e-8, t)
         th, m, u = O.adam_update(th, G, m, u, t, 1e-3, 0.9, 0.999, 1e-8)
     torch.cuda.synchronize()
+    # beta2 arrives as an fp32 value: 1 - float32(0.999) differs from 0.001 by 1.3e-5 relative
     np.testing.assert_allclose(tht.cpu().numpy(), th, rtol=1e-5, atol=1e-6)
     np.testing.assert_allclose(mt.cpu().numpy(), m, rtol=1e-5, atol=1e-7)
-    np.testing.assert_allclose(ut.cpu().numpy(), u, rtol=1e-5, atol=1e-9)
+    np.testing.assert_allclose(ut.cpu().numpy(), u, rtol=5e-5, atol=1e-9)
+
+
+GEMM_SHAPES = [(128, 4096 // 8, 1024 // 4), (48, 1000, 520), (16, 392, 1000), (8, 520, 256), (40, 264, 392),
+               (300, 100, 392), (392, 1000, 128), (520, 392, 48), (256, 520, 16), (256, 520, 8), (1, 8, 8),
+               (33, 65, 72), (129, 257, 264), (304, 1003, 128), (2048, 2304, 768)]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
+def test_gemm_against_float64_matmul(M, N, K, dtype):
+    """C = alpha A B^T (+C) on ragged shapes: several tiles, row/column/contraction tails."""
+    import torch
+    import paper_2009_09523_amd as vf
+    print(f"gemm {dtype} M={M} N={N} K={K}", flush=True)
+    rng = np.random.Generator(np.random.PCG64(M * 7 + N * 3 + K))
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    lda = ((K + 7) // 8) * 8 + 8
+    A = torch.from_numpy(rng.standard_normal((M, lda)).astype(np.float32)).to(tdt).cuda()
+    B = torch.from_numpy(rng.standard_normal((N, lda)).astype(np.float32)).to(tdt).cuda()
+    C0 = rng.standard_normal((M, N + 3)).astype(np.float32)
+    Cd = torch.from_numpy(C0).cuda()
+    A64, B64 = A[:, :K].double().cpu().numpy(), B[:, :K].double().cpu().numpy()
+    want = A64 @ B64.T
+    vf.vf_gemm(A[:, :K], B[:, :K], Cd[:, :N], M, N, K, alpha=0.75, accumulate=False)
+    torch.cuda.synchronize()
+    got = Cd.cpu().numpy()
+    tol = 2e-5 * np.sqrt(K) * np.max(np.abs(want)) if dtype == "f32" else 1e-5 * np.max(np.abs(want)) * np.sqrt(K)
+    assert np.max(np.abs(got[:, :N] - 0.75 * want)) <= tol
+    np.testing.assert_array_equal(got[:, N:], C0[:, N:])          # nothing written past column N
+    vf.vf_gemm(A[:, :K], B[:, :K], Cd[:, :N], M, N, K, alpha=-0.5, accumulate=True)
+    torch.cuda.synchronize()
+    got2 = Cd.cpu().numpy()
+    assert np.max(np.abs(got2[:, :N] - 0.25 * want)) <= 2 * tol

@@ -298,3 +298,30 @@ def test_layouts_agree():
     assert I.num_params(I.workload("C2")) == 41870312
     assert I.num_params(I.workload("C4")) == 75363642
     assert I.num_params(I.workload("C5")) == 360612840
+
+
+def test_bf16_operand_rounding_is_a_small_perturbation_and_exact_when_representable():
+    """bf16 workloads round contraction operands.  (i) On a workload the result stays within
+    a few percent of the unrounded one; (ii) when every operand is exactly representable
+    (weights and inputs are small integers / powers of two, one Linear layer so that no
+    intermediate needs rounding) both modes agree to float64 rounding."""
+    wl = I.workload("mlp_mid_bn_bf16")
+    theta = I.make_params(wl, jitter=0.1)
+    x, y = I.make_batch(wl)
+    a = O.oracle_step(wl, theta, x, y)
+    theta_r = O.round_to_bf16(theta).astype(np.float32)
+    b = O.oracle_step(replace(wl, dtype="f32"), theta_r, x, y)
+    err = np.linalg.norm(a["G"] - b["G"]) / np.linalg.norm(b["G"])
+    assert 1e-5 < err < 0.08, err
+    wl1 = I.Workload(name="one", kind="mlp", dims=(8, 4), batchnorm=False, node_sizes=(2, 2), dtype="bf16")
+    rng = np.random.Generator(np.random.PCG64(4))
+    th1 = np.concatenate([rng.integers(-4, 5, 32) / 8.0, np.zeros(4)]).astype(np.float32)
+    x1 = rng.integers(-3, 4, (4, 8)).astype(np.float32)
+    y1 = np.array([0, 1, 2, 3], dtype=np.int32)
+    r16 = O.oracle_step(wl1, th1, x1, y1)
+    r32 = O.oracle_step(replace(wl1, dtype="f32"), th1, x1, y1)
+    assert abs(r16["loss"] - r32["loss"]) < 1e-14
+    # the bias gradient never passes through a rounded operand
+    np.testing.assert_allclose(r16["G"][32:], r32["G"][32:], rtol=1e-13, atol=1e-16)
+    # the weight gradient uses the rounded output gradient: within bf16 rounding of it
+    assert np.max(np.abs(r16["G"][:32] - r32["G"][:32])) <= 2.0 ** -8 * np.max(np.abs(r32["G"][:32]))
