@@ -1,0 +1,192 @@
+#!/usr/bin/env python3
+"""Benchmark of the virtual-node training step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2] [--accumulate staged|fused]
+
+A "step" is one pass of the whole hot path over one synthetic batch already resident in HBM:
+partition, V sequential node passes (forward, loss, backward), the size-weighted fold of each
+node's gradient into the fp32 gradient buffer, one optimizer update.  Prints ONE JSON line.
+Everything runs on one GPU; --gpus above 1 is refused.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 matrix cores
+FP32_VECTOR_PEAK_TFLOPS = 157.3
+
+
+def algorithmic_work(wl, P):
+    """Per step, per kernel tag: (bytes, flops, launches) the method itself needs.
+    Bytes count each operand once per launch (fp32 = 4, bf16 = 2)."""
+    V, B = wl.n_nodes, wl.batch
+    esz = 2 if wl.dtype == "bf16" else 4
+    work = {"accumulate": ((12 * V - 4) * P, 2 * V * P, V)}
+    opt_bytes = (20 if wl.optimizer == "sgdm" else 28) * P
+    work["optimizer"] = (opt_bytes, 4 * P, 1)
+    if wl.kind == "mlp":
+        mats = [(wl.dims[i], wl.dims[i + 1]) for i in range(len(wl.dims) - 1)]
+        W = sum(k * n for k, n in mats)
+        fwd_fl = 2 * B * W
+        dgr_fl = 2 * B * sum(k * n for k, n in mats[1:])
+        act = sum(b * (k * esz + n * 4) for b in wl.node_sizes for k, n in mats)
+        work["gemm_fwd"] = (V * W * esz + act, fwd_fl, V * len(mats))
+        work["gemm_dgrad"] = (V * sum(k * n for k, n in mats[1:]) * esz + act, dgr_fl, V * (len(mats) - 1))
+        work["gemm_wgrad"] = (V * W * 4 + act, fwd_fl, V * len(mats))
+        work["cast_weight"] = (W * (4 + 2 * esz), 0, len(mats))
+    return work
+
+
+def roofline_for(tag, work, avg_ms):
+    bytes_, flops, launches = work[tag]
+    b_per, f_per = bytes_ / launches, flops / launches
+    t_hbm = b_per / (HBM_PEAK_GBS * 1e9)
+    t_mfma = f_per / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+    if t_hbm >= t_mfma:
+        ach = b_per / (avg_ms * 1e-3) / 1e9
+        return {"kernel": tag, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": ach / HBM_PEAK_GBS, "traffic": None, "avg_launch_ms": avg_ms,
+                "algorithmic_bytes_per_launch": b_per}
+    ach = f_per / (avg_ms * 1e-3) / 1e12
+    return {"kernel": tag, "bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS,
+            "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+            "avg_launch_ms": avg_ms, "algorithmic_flops_per_launch": f_per}
+
+
+def cpu_baseline(wl, theta, x, y, budget_s=12.0):
+    """The oracle as it stands, timed node by node on the host cores until about
+    `budget_s` seconds of work are done (at least one node)."""
+    import numpy as np
+    import oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    t0 = time.perf_counter()
+    done = 0
+    samples = 0
+    for i in range(wl.n_nodes):
+        O.oracle_step(wl, theta, x, y, nodes=[i])
+        done += 1
+        samples += wl.node_sizes[i]
+        if time.perf_counter() - t0 >= budget_s:
+            break
+    dt = time.perf_counter() - t0
+    return {"value": samples / dt, "unit": "samples/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{done} of {wl.n_nodes} virtual nodes ({samples} samples) of workload {wl.name}, "
+                      f"each with the combine and one optimizer update, {dt:.1f} s",
+            "seconds": dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="C2")
+    ap.add_argument("--accumulate", choices=["staged", "fused"], default="staged")
+    ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-profile", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs the virtual-node step on ONE GPU; --gpus above 1 is not "
+              "supported (no collectives are part of it).", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2009_09523_amd as vf
+    import vf_inputs as I
+    from paper_2009_09523_amd.binding import config_from_workload
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+    wl = I.workload(args.workload)
+    theta = I.make_params(wl)
+    x, y = I.make_batch(wl)
+    stream = torch.cuda.Stream()
+    flags = (vf.VF_FLAG_FUSED_ACCUMULATE if args.accumulate == "fused" else 0) | \
+            (vf.VF_FLAG_NO_GRAPH if args.no_graph else 0)
+    eng = vf.VirtualNodeStep(config_from_workload(wl, flags=flags, stream=stream))
+    P = eng.num_params
+    params = torch.from_numpy(theta).cuda()
+    xt = torch.from_numpy(x).cuda()
+    if wl.kind == "mlp" and wl.dtype == "bf16":
+        xt = xt.to(torch.bfloat16)
+    yt = torch.from_numpy(y).cuda()
+    sizes = list(wl.node_sizes)
+    torch.cuda.synchronize()
+
+    for _ in range(args.warmup):
+        eng.step(params, xt, yt, sizes)
+    stream.synchronize()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        eng.step(params, xt, yt, sizes)
+    stream.synchronize()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt * 1e3 / args.steps
+    loss = eng.loss()
+
+    out = {
+        "metric": "samples/sec per training step at V virtual nodes on 1 MI355X",
+        "value": wl.batch / (ms_per_step * 1e-3), "unit": "samples/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if wl.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "model": wl.kind, "dims": list(wl.dims) if wl.kind == "mlp" else None,
+                   "batchnorm": bool(wl.batchnorm), "global_batch": wl.batch, "virtual_nodes": wl.n_nodes,
+                   "node_sizes": sizes if len(set(sizes)) > 1 else f"{wl.n_nodes}x{sizes[0]}",
+                   "optimizer": wl.optimizer, "params": P, "accumulate": args.accumulate,
+                   "graph": not args.no_graph},
+        "loss": loss,
+    }
+
+    work = algorithmic_work(wl, P)
+    total_bytes = sum(v[0] for v in work.values())
+    total_flops = sum(v[1] for k, v in work.items() if k.startswith("gemm"))
+    floor_ms = max(total_bytes / (HBM_PEAK_GBS * 1e9), total_flops / (MFMA_BF16_PEAK_TFLOPS * 1e12)) * 1e3
+    out["step_floor"] = {"algorithmic_bytes": total_bytes, "gemm_flops": total_flops, "floor_ms": floor_ms,
+                         "frac": floor_ms / ms_per_step,
+                         "gemm_tflops_achieved": total_flops / (ms_per_step * 1e-3) / 1e12}
+
+    if not args.no_kernel_profile:
+        # same steps again, launched one by one with an event pair around every kernel
+        eng.profile_start()
+        for _ in range(args.steps):
+            eng.step(params, xt, yt, sizes)
+        prof = eng.profile_stop()
+        tot = sum(v["total_ms"] for v in prof.values())
+        kernels = {k: {"launches_per_step": v["launches"] / args.steps,
+                       "avg_launch_ms": v["total_ms"] / v["launches"],
+                       "ms_per_step": v["total_ms"] / args.steps,
+                       "share": v["total_ms"] / tot} for k, v in prof.items()}
+        out["kernels"] = kernels
+        dom = max((k for k in kernels if k in work), key=lambda k: kernels[k]["ms_per_step"])
+        out["roofline"] = roofline_for(dom, work, kernels[dom]["avg_launch_ms"])
+        out["roofline_all"] = {k: {kk: vv for kk, vv in roofline_for(k, work, kernels[k]["avg_launch_ms"]).items()
+                                   if kk in ("bound", "achieved", "peak", "unit", "frac")}
+                               for k in kernels if k in work}
+    eng.close()
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, theta, x, y)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -136,6 +136,16 @@ int vf_node_losses(vf_ctx* ctx, float* out, int32_t V);
  * moment u (VF_EINVAL for SGD-momentum).  Synchronises. */
 int vf_opt_state(vf_ctx* ctx, int32_t which, float* out);
 
+/* Per-kernel timing of the steps run between the two calls (the library's counterpart of the
+ * offline profiling of Section 5.1.1: how long each part of a node's pass takes on this
+ * device).  While enabled, every kernel launch is bracketed by two events on the context's
+ * stream and launches are made one by one instead of by graph replay, so step time itself is
+ * slower than normal.  vf_profile_stop synchronises and writes a JSON object
+ * {"<kernel tag>": {"launches": n, "total_ms": t}, ...} into `json` (host, `cap` bytes,
+ * NUL-terminated); VF_EINVAL if it does not fit. */
+int vf_profile_start(vf_ctx* ctx);
+int vf_profile_stop(vf_ctx* ctx, char* json, size_t cap);
+
 /* Number of optimizer updates applied so far (one per successful vf_step). */
 int64_t vf_step_count(const vf_ctx* ctx);
 

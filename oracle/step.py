@@ -76,6 +76,7 @@ def _mlp_node(wl, p, x, y):
     n_lin = len(wl.dims) - 1
     h = np.asarray(x, dtype=np.float64)
     saved = []
+    margin = np.inf
     for l in range(n_lin - 1):
         z = L.linear_fwd(h, p[f"l{l}.W"], None if wl.batchnorm else p[f"l{l}.b"])
         if wl.batchnorm:
@@ -83,6 +84,9 @@ def _mlp_node(wl, p, x, y):
         else:
             pre, bn_cache = z, None
         saved.append((h, pre, bn_cache))
+        # diagnostic: how close any ReLU input of this node is to the kink, relative to the
+        # layer's typical magnitude (a fp32 implementation may legitimately flip such a unit)
+        margin = min(margin, float(np.min(np.abs(pre)) / np.sqrt(np.mean(pre * pre))))
         h = q(L.relu_fwd(pre))
     last = n_lin - 1
     logits = L.linear_fwd(h, p[f"l{last}.W"], p[f"l{last}.b"])
@@ -100,7 +104,7 @@ def _mlp_node(wl, p, x, y):
             dz = dpre
             g[f"l{l}.b"] = dz.sum(axis=0)
         dh, g[f"l{l}.W"], _ = L.linear_bwd(h_in, p[f"l{l}.W"], q(dz), False)
-    return loss, g
+    return loss, g, margin
 
 
 def _split_heads(t, n_heads):
@@ -172,16 +176,20 @@ def _encoder_node(wl, p, ids, y):
     g["pos_emb"][:T] = dh.sum(axis=0)
     g["tok_emb"] = np.zeros_like(p["tok_emb"])
     np.add.at(g["tok_emb"], ids.reshape(-1), dh.reshape(-1, d))
-    return loss, g
+    return loss, g, np.inf
 
 
-def node_loss_and_grads(wl, compute_params, x_node, y_node):
-    """(L_i, flat g_i) for one node given float64 compute parameters (flat)."""
+def node_loss_and_grads(wl, compute_params, x_node, y_node, diag=None):
+    """(L_i, flat g_i) for one node given float64 compute parameters (flat).  `diag`, if a
+    dict, receives 'relu_margin': the smallest |ReLU input| of the node relative to its
+    layer's rms (inf for models without ReLU)."""
     p = unflatten(wl, compute_params)
     if wl.kind == "mlp":
-        loss, g = _mlp_node(wl, p, x_node, y_node)
+        loss, g, margin = _mlp_node(wl, p, x_node, y_node)
     else:
-        loss, g = _encoder_node(wl, p, x_node, y_node)
+        loss, g, margin = _encoder_node(wl, p, x_node, y_node)
+    if diag is not None:
+        diag["relu_margin"] = margin
     return loss, _flatten(wl, g)
 
 
@@ -207,7 +215,8 @@ def oracle_step(wl, theta, x, y, node_sizes=None, state=None, nodes=None):
     off, w (bit-exact data), loss, node_losses, G (float64 [P]), theta (float64
     [P] after the update), state (after the update).  `nodes` limits the nodes
     that are evaluated (timing a sample of the work); G and the update are then
-    partial and must not be compared."""
+    partial and must not be compared.  'relu_margin' is a diagnostic for parity checks:
+    the smallest |ReLU input| relative to its layer's rms over the whole step."""
     sizes = list(wl.node_sizes if node_sizes is None else node_sizes)
     off, w = partition(sizes, len(x))
     cp = compute_copy(wl, theta)
@@ -215,14 +224,17 @@ def oracle_step(wl, theta, x, y, node_sizes=None, state=None, nodes=None):
     G = np.zeros(n)
     loss = 0.0
     node_losses = []
+    relu_margin = np.inf
     which = range(len(sizes)) if nodes is None else nodes
     for i in which:                                          # node after node (Section 3.2)
         lo, hi = int(off[i]), int(off[i + 1])
-        L_i, g_i = node_loss_and_grads(wl, cp, x[lo:hi], y[lo:hi])
+        diag = {}
+        L_i, g_i = node_loss_and_grads(wl, cp, x[lo:hi], y[lo:hi], diag)
         weight = sizes[i] / float(len(x))                    # b_i / B (Section 5.2)
         G += weight * g_i
         loss += weight * L_i
         node_losses.append(L_i)
+        relu_margin = min(relu_margin, diag["relu_margin"])
     state = new_state(wl, n) if state is None else state
     t = state["t"] + 1
     theta64 = (np.asarray(theta, dtype=np.float64) if wl.dtype == "f64"
@@ -235,4 +247,4 @@ def oracle_step(wl, theta, x, y, node_sizes=None, state=None, nodes=None):
                                       wl.beta1, wl.beta2, wl.adam_eps)
         new = {"t": t, "m": m, "u": u}
     return {"off": off, "w": w, "loss": loss, "node_losses": np.array(node_losses),
-            "G": G, "theta": theta_new, "state": new}
+            "G": G, "theta": theta_new, "state": new, "relu_margin": relu_margin}

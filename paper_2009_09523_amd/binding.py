@@ -52,6 +52,8 @@ _SIGNATURES = {
     "vf_loss": (C.c_int, [C.c_void_p, C.POINTER(C.c_float)]),
     "vf_node_losses": (C.c_int, [C.c_void_p, C.POINTER(C.c_float), C.c_int32]),
     "vf_opt_state": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p]),
+    "vf_profile_start": (C.c_int, [C.c_void_p]),
+    "vf_profile_stop": (C.c_int, [C.c_void_p, C.c_char_p, C.c_size_t]),
     "vf_step_count": (C.c_int64, [C.c_void_p]),
     "vf_num_params": (C.c_int64, [C.c_void_p]),
     "vf_workspace_bytes": (C.c_size_t, [C.c_void_p]),
@@ -221,6 +223,15 @@ class VirtualNodeStep:
         n = len(node_sizes) if node_sizes is not None else 0
         sizes = (C.c_int32 * max(n, 1))(*[int(b) for b in (node_sizes or [])]) if node_sizes is not None else None
         return int(lib().vf_step(self._h, params_ptr, x_ptr, y_ptr, int(B), int(V), sizes))
+
+    def profile_start(self):
+        _check(lib().vf_profile_start(self._h), "vf_profile_start")
+
+    def profile_stop(self) -> dict:
+        import json
+        buf = C.create_string_buffer(1 << 16)
+        _check(lib().vf_profile_stop(self._h, buf, len(buf)), "vf_profile_stop")
+        return json.loads(buf.value.decode())
 
     def grads(self, out):
         _check(lib().vf_grads(self._h, _ptr(out)), "vf_grads")

@@ -62,20 +62,23 @@ int enqueue_nodes(Ctx& c, const StepArgs& a) {
   VF_TRY(c.model->prepare(c, a.params));
   for (int i = 0; i < a.V; ++i) {
     VF_TRY(c.model->run_node(c, a, i));
-    if (!c.fused) VF_TRY(launch_accumulate(c.gbuf, c.gstage, a.w[i], c.P, i == 0, c.stream));
+    if (!c.fused) VF_K(c, "accumulate", launch_accumulate(c.gbuf, c.gstage, a.w[i], c.P, i == 0, c.stream));
   }
   return VF_OK;
 }
 
 int enqueue_update(Ctx& c, float* params) {
   const vf_config& f = c.cfg;
-  if (f.optimizer == VF_SGDM)
-    return launch_sgdm(params, c.opt0, c.gbuf, f.lr, f.momentum, c.P, c.stream);
+  if (f.optimizer == VF_SGDM) {
+    VF_K(c, "optimizer", launch_sgdm(params, c.opt0, c.gbuf, f.lr, f.momentum, c.P, c.stream));
+    return VF_OK;
+  }
   const double t = (double)(c.steps + 1);
   const float inv_c1 = (float)(1.0 / (1.0 - std::pow((double)f.beta1, t)));
   const float inv_c2 = (float)(1.0 / (1.0 - std::pow((double)f.beta2, t)));
-  return launch_adam(params, c.opt0, c.opt1, c.gbuf, f.lr, f.beta1, f.beta2, f.adam_eps, inv_c1,
-                     inv_c2, c.P, c.stream);
+  VF_K(c, "optimizer", launch_adam(params, c.opt0, c.opt1, c.gbuf, f.lr, f.beta1, f.beta2, f.adam_eps,
+                                   inv_c1, inv_c2, c.P, c.stream));
+  return VF_OK;
 }
 
 bool graph_matches(const Ctx& c, const StepArgs& a) {
@@ -217,7 +220,7 @@ int vf_step(vf_ctx* h, void* params, const void* batch_x, const int32_t* batch_y
   a.w.resize(V);
   vf_partition(node_sizes, V, B, a.off.data(), a.w.data());
 
-  if (c.cfg.flags & VF_FLAG_NO_GRAPH) {
+  if ((c.cfg.flags & VF_FLAG_NO_GRAPH) || c.prof.enabled) {
     VF_TRY(enqueue_nodes(c, a));
   } else {
     if (!graph_matches(c, a)) VF_TRY(capture_graph(c, a));
@@ -256,6 +259,48 @@ int vf_opt_state(vf_ctx* h, int32_t which, float* out) {
   return VF_EINVAL;
 }
 
+int vf_profile_start(vf_ctx* h) {
+  if (!h) return VF_EINVAL;
+  Profiler& p = h->c.prof;
+  p.enabled = true;
+  p.recs.clear();
+  p.used = 0;
+  return VF_OK;
+}
+
+int vf_profile_stop(vf_ctx* h, char* out, size_t cap) {
+  if (!h || !out || cap < 2) return VF_EINVAL;
+  Ctx& c = h->c;
+  Profiler& p = c.prof;
+  p.enabled = false;
+  VF_HIP(hipStreamSynchronize(c.stream));
+  struct Agg { const char* tag; double ms; int64_t n; };
+  std::vector<Agg> agg;
+  for (const Profiler::Rec& r : p.recs) {
+    float ms = 0.f;
+    VF_HIP(hipEventElapsedTime(&ms, r.a, r.b));
+    Agg* hit = nullptr;
+    for (Agg& a : agg)
+      if (std::strcmp(a.tag, r.tag) == 0) { hit = &a; break; }
+    if (!hit) { agg.push_back({r.tag, 0.0, 0}); hit = &agg.back(); }
+    hit->ms += ms;
+    hit->n += 1;
+  }
+  p.recs.clear();
+  p.used = 0;
+  std::string js = "{";
+  for (size_t i = 0; i < agg.size(); ++i) {
+    char buf[160];
+    snprintf(buf, sizeof buf, "%s\"%s\": {\"launches\": %lld, \"total_ms\": %.6f}", i ? ", " : "",
+             agg[i].tag, (long long)agg[i].n, agg[i].ms);
+    js += buf;
+  }
+  js += "}";
+  if (js.size() + 1 > cap) return VF_EINVAL;
+  std::memcpy(out, js.c_str(), js.size() + 1);
+  return VF_OK;
+}
+
 int64_t vf_step_count(const vf_ctx* h) { return h ? h->c.steps : 0; }
 int64_t vf_num_params(const vf_ctx* h) { return h ? h->c.P : 0; }
 size_t vf_workspace_bytes(const vf_ctx* h) { return h ? h->c.arena_bytes : 0; }
@@ -266,6 +311,7 @@ void vf_destroy(vf_ctx* h) {
   if (c.arena) {
     (void)hipStreamSynchronize(c.stream);
     drop_graph(c);
+    for (hipEvent_t e : c.prof.pool) (void)hipEventDestroy(e);
     (void)hipFree(c.arena);
   }
   delete h;

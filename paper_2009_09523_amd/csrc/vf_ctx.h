@@ -53,8 +53,28 @@ class Model {
   virtual int run_node(Ctx& c, const StepArgs& a, int i) = 0;
 };
 
+// Optional per-kernel timing: while enabled, every launch made through VF_K is bracketed by
+// two events on the context's stream and kernels are launched one by one (no graph replay).
+struct Profiler {
+  struct Rec { const char* tag; hipEvent_t a, b; };
+  bool enabled = false;
+  std::vector<Rec> recs;
+  std::vector<hipEvent_t> pool;
+  size_t used = 0;
+  int take(hipEvent_t* e) {
+    if (used == pool.size()) {
+      hipEvent_t ev;
+      VF_HIP(hipEventCreate(&ev));
+      pool.push_back(ev);
+    }
+    *e = pool[used++];
+    return VF_OK;
+  }
+};
+
 struct Ctx {
   vf_config cfg;
+  Profiler prof;
   hipStream_t stream = nullptr;
   int device = 0;
   bool bf16 = false;
@@ -88,6 +108,22 @@ struct Ctx {
     return GradOut{gstage + off, 1.0f, 0};
   }
 };
+
+// Launch `call` (an expression returning a status) under the tag `name`.
+#define VF_K(ctx, name, call)                                             \
+  do {                                                                    \
+    if ((ctx).prof.enabled) {                                             \
+      ::vf::Profiler::Rec r__{name, nullptr, nullptr};                    \
+      VF_TRY((ctx).prof.take(&r__.a));                                    \
+      VF_TRY((ctx).prof.take(&r__.b));                                    \
+      VF_HIP(hipEventRecord(r__.a, (ctx).stream));                        \
+      VF_TRY(call);                                                       \
+      VF_HIP(hipEventRecord(r__.b, (ctx).stream));                        \
+      (ctx).prof.recs.push_back(r__);                                     \
+    } else {                                                              \
+      VF_TRY(call);                                                       \
+    }                                                                     \
+  } while (0)
 
 std::unique_ptr<Model> make_mlp(const vf_config& cfg);
 std::unique_ptr<Model> make_encoder(const vf_config& cfg);

@@ -77,7 +77,7 @@ class Mlp final : public Model {
   int prepare(Ctx& c, const float* params) override {
     if (!bf16_) return VF_OK;
     for (Layer& L : layers_)
-      VF_TRY(launch_cast_weight(params + L.w_off, L.K, L.N, L.wnat, L.ldn, L.wtr, L.ldt, c.stream));
+      VF_K(c, "cast_weight", launch_cast_weight(params + L.w_off, L.K, L.N, L.wnat, L.ldn, L.wtr, L.ldt, c.stream));
     return VF_OK;
   }
 
@@ -102,17 +102,17 @@ class Mlp final : public Model {
       ep.C = L.z; ep.ldc = L.ld;
       if (L.has_bias) { ep.bias = P + L.b_off; ep.bias_round_bf16 = bf16_; }
       if (bf16_)
-        VF_TRY(launch_gemm_bf16(static_cast<const bf16_t*>(in), ldin, L.wtr, L.ldt, b, L.N, L.K, ep, st));
+        VF_K(c, "gemm_fwd", launch_gemm_bf16(static_cast<const bf16_t*>(in), ldin, L.wtr, L.ldt, b, L.N, L.K, ep, st));
       else
-        VF_TRY(launch_gemm_f32(static_cast<const float*>(in), ldin, 1, P + L.w_off, 1, L.N, b, L.N, L.K, ep, st));
+        VF_K(c, "gemm_fwd", launch_gemm_f32(static_cast<const float*>(in), ldin, 1, P + L.w_off, 1, L.N, b, L.N, L.K, ep, st));
       if (L.hidden)
-        VF_TRY(launch_bn_relu_fwd(L.z, L.ld, b, L.N, L.has_bn ? P + L.g_off : nullptr,
+        VF_K(c, "bn_relu_fwd", launch_bn_relu_fwd(L.z, L.ld, b, L.N, L.has_bn ? P + L.g_off : nullptr,
                                   L.has_bn ? P + L.be_off : nullptr, bf16_, cfg_.bn_eps, L.a, L.ld,
                                   bf16_, L.mean, L.rstd, st));
     }
     Layer& last = layers_[nl - 1];
-    VF_TRY(launch_softmax_xent(last.z, last.ld, y, b, last.N, c.rowloss, last.dz, last.ld, bf16_, st));
-    VF_TRY(launch_loss_reduce(c.rowloss, b, w, i, c.node_loss, c.loss_total, st));
+    VF_K(c, "softmax_xent", launch_softmax_xent(last.z, last.ld, y, b, last.N, c.rowloss, last.dz, last.ld, bf16_, st));
+    VF_K(c, "loss_reduce", launch_loss_reduce(c.rowloss, b, w, i, c.node_loss, c.loss_total, st));
 
     // ---- backward ----------------------------------------------------------------------
     for (int l = nl - 1; l >= 0; --l) {
@@ -120,7 +120,7 @@ class Mlp final : public Model {
       const void* in = l == 0 ? x : layers_[l - 1].a;
       const int64_t ldin = l == 0 ? D : layers_[l - 1].ld;
       if (!L.hidden)   // last layer: bias gradient = column sums of dlogits
-        VF_TRY(launch_colsum(L.dz, L.ld, bf16_, b, L.N, c.gout(L.b_off, w, i), st));
+        VF_K(c, "colsum", launch_colsum(L.dz, L.ld, bf16_, b, L.N, c.gout(L.b_off, w, i), st));
       // weight gradient dW[K,N] = in^T dz
       GradOut go = c.gout(L.w_off, w, i);
       Epilogue ep;
@@ -128,11 +128,11 @@ class Mlp final : public Model {
       if (go.accumulate) { ep.R = go.dst; ep.ldr = L.N; ep.beta = 1.f; }
       if (bf16_) {
         bf16_t* inT = l == 0 ? xT_ : layers_[l - 1].aT;
-        VF_TRY(launch_transpose_bf16(static_cast<const bf16_t*>(in), ldin, inT, ldb_, b, L.K, st));
-        VF_TRY(launch_transpose_bf16(static_cast<const bf16_t*>(L.dz), L.ld, L.dzT, ldb_, b, L.N, st));
-        VF_TRY(launch_gemm_bf16(inT, ldb_, L.dzT, ldb_, L.K, L.N, b, ep, st));
+        VF_K(c, "transpose", launch_transpose_bf16(static_cast<const bf16_t*>(in), ldin, inT, ldb_, b, L.K, st));
+        VF_K(c, "transpose", launch_transpose_bf16(static_cast<const bf16_t*>(L.dz), L.ld, L.dzT, ldb_, b, L.N, st));
+        VF_K(c, "gemm_wgrad", launch_gemm_bf16(inT, ldb_, L.dzT, ldb_, L.K, L.N, b, ep, st));
       } else {
-        VF_TRY(launch_gemm_f32(static_cast<const float*>(in), 1, ldin, static_cast<const float*>(L.dz), 1,
+        VF_K(c, "gemm_wgrad", launch_gemm_f32(static_cast<const float*>(in), 1, ldin, static_cast<const float*>(L.dz), 1,
                                L.ld, L.K, L.N, b, ep, st));
       }
       if (l == 0) break;
@@ -141,12 +141,12 @@ class Mlp final : public Model {
       Epilogue ed;
       ed.C = Pv.da; ed.ldc = Pv.ld;
       if (bf16_)
-        VF_TRY(launch_gemm_bf16(static_cast<const bf16_t*>(L.dz), L.ld, L.wnat, L.ldn, b, L.K, L.N, ed, st));
+        VF_K(c, "gemm_dgrad", launch_gemm_bf16(static_cast<const bf16_t*>(L.dz), L.ld, L.wnat, L.ldn, b, L.K, L.N, ed, st));
       else
-        VF_TRY(launch_gemm_f32(static_cast<const float*>(L.dz), L.ld, 1, P + L.w_off, L.N, 1, b, L.K, L.N, ed, st));
+        VF_K(c, "gemm_dgrad", launch_gemm_f32(static_cast<const float*>(L.dz), L.ld, 1, P + L.w_off, L.N, 1, b, L.K, L.N, ed, st));
       GradOut gg = Pv.has_bn ? c.gout(Pv.g_off, w, i) : GradOut{nullptr, 0.f, 0};
       GradOut gb = c.gout(Pv.has_bn ? Pv.be_off : Pv.b_off, w, i);
-      VF_TRY(launch_bn_relu_bwd(Pv.da, Pv.ld, Pv.z, Pv.ld, b, Pv.N, Pv.has_bn ? P + Pv.g_off : nullptr,
+      VF_K(c, "bn_relu_bwd", launch_bn_relu_bwd(Pv.da, Pv.ld, Pv.z, Pv.ld, b, Pv.N, Pv.has_bn ? P + Pv.g_off : nullptr,
                                 Pv.has_bn ? P + Pv.be_off : nullptr, bf16_, Pv.mean, Pv.rstd, Pv.dz,
                                 Pv.ld, bf16_, gg, gb, st));
     }

@@ -107,3 +107,19 @@ def test_rejected_step_leaves_state_untouched():
     with pytest.raises(vf.VfError):
         eng.loss()
     eng.close()
+
+
+@pytest.mark.parametrize("name,flags", [("C2", 0), ("C3", 0), ("C3", FUSED)])
+def test_full_size_configurations(name, flags):
+    """The benchmark configuration (C2) and the heterogeneous split (C3) at full size, in the
+    launch configuration bench.py times, every gradient entry against the oracle."""
+    print(f"full size {name} flags={flags}", flush=True)
+    wl, theta, x, y = _case(name, jitter=0.0)
+    gpu = run_gpu(wl, theta, x, y, flags=flags)
+    ref = oracle_steps(wl, theta, x, y)
+    check_against_oracle(wl, gpu, ref)
+    check_update_from_own_gradient(wl, gpu, theta)
+    off, w = O.partition(wl.node_sizes, wl.batch)
+    import paper_2009_09523_amd as vf
+    off2, w2 = vf.vf_partition(wl.node_sizes, wl.batch)
+    assert off.tobytes() == off2.tobytes() and w.tobytes() == w2.tobytes()

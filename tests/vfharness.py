@@ -85,26 +85,38 @@ def tensor_errors(wl, got, want):
     return rows
 
 
-def assert_close_per_tensor(wl, got, want, tol, what):
-    bad = [(n, r, m) for n, r, m in tensor_errors(wl, got, want) if not (r <= tol and m <= tol)]
-    assert not bad, f"{what}: tensors beyond tol {tol}: {bad[:8]}"
+# A ReLU unit whose input is within fp32 accumulation error of zero may be switched on by one
+# implementation and off by the other; both outcomes are valid.  One such unit changes a
+# single sample's contribution to a few gradient columns: invisible in the L2 norm, visible
+# in the max-abs norm of a small workload.  When the oracle reports such a unit (input
+# smaller than RELU_AMBIGUOUS times the layer's rms) the max-abs bound is relaxed to
+# MAXABS_RELAX * tol; the L2 bound never is.
+RELU_AMBIGUOUS = 1e-5
+MAXABS_RELAX = 5.0
+
+
+def assert_close_per_tensor(wl, got, want, tol, what, maxabs_tol=None):
+    mt = tol if maxabs_tol is None else maxabs_tol
+    bad = [(n, r, m) for n, r, m in tensor_errors(wl, got, want) if not (r <= tol and m <= mt)]
+    assert not bad, f"{what}: tensors beyond tol {tol} (max-abs {mt}): {bad[:8]}"
 
 
 def check_against_oracle(wl, gpu, ref, tol=None, check_theta=True):
     """Per tensor: ||a-b||2/||b||2 <= tol and max|a-b| <= tol*max|b|; loss relative."""
     tol = TOL[wl.dtype] if tol is None else tol
+    mt = tol * (MAXABS_RELAX if ref.get("relu_margin", np.inf) < RELU_AMBIGUOUS else 1.0)
     assert abs(gpu["loss"] - ref["loss"]) <= tol * abs(ref["loss"]), (gpu["loss"], ref["loss"])
     np.testing.assert_allclose(gpu["node_losses"], ref["node_losses"], rtol=tol)
-    assert_close_per_tensor(wl, gpu["G"], ref["G"], tol, "G")
+    assert_close_per_tensor(wl, gpu["G"], ref["G"], tol, "G", mt)
     assert gpu["t"] == ref["state"]["t"]
     if not check_theta:
         return
     if wl.optimizer == "sgdm":
-        assert_close_per_tensor(wl, gpu["theta"], ref["theta"], tol, "theta")
-        assert_close_per_tensor(wl, gpu["s0"], ref["state"]["v"], tol, "velocity")
+        assert_close_per_tensor(wl, gpu["theta"], ref["theta"], tol, "theta", mt)
+        assert_close_per_tensor(wl, gpu["s0"], ref["state"]["v"], tol, "velocity", mt)
     else:
-        assert_close_per_tensor(wl, gpu["s0"], ref["state"]["m"], tol, "adam m")
-        assert_close_per_tensor(wl, gpu["s1"], ref["state"]["u"], 2.5 * tol, "adam u")   # quadratic in G
+        assert_close_per_tensor(wl, gpu["s0"], ref["state"]["m"], tol, "adam m", mt)
+        assert_close_per_tensor(wl, gpu["s1"], ref["state"]["u"], 2.5 * tol, "adam u", 2.5 * mt)   # quadratic in G
 
 
 def check_update_from_own_gradient(wl, gpu, theta0, tol=1e-5):
