@@ -69,8 +69,10 @@ def oracle_steps(wl, theta, x, y, node_sizes=None, steps=1):
     return r
 
 
-def tensor_errors(wl, got, want):
-    """[(name, rel_l2, max_abs_err / max_abs_ref)] per parameter tensor."""
+def tensor_errors(wl, got, want, outlier_tol=None):
+    """[(name, rel_l2, max_abs_err / max_abs_ref)] per parameter tensor; with outlier_tol
+    the third entry is instead the fraction of elements whose error exceeds
+    outlier_tol * max_abs_ref."""
     rows, pos = [], 0
     for name, shape in O.layout(wl):
         n = int(np.prod(shape))
@@ -80,31 +82,41 @@ def tensor_errors(wl, got, want):
         d = a - b
         rel = np.linalg.norm(d) / nb if nb > 0 else np.linalg.norm(d)
         mx = np.max(np.abs(d)) / mb if mb > 0 else np.max(np.abs(d))
+        if outlier_tol is not None:
+            mx = float(np.mean(np.abs(d) > outlier_tol * mb))
         rows.append((name, float(rel), float(mx)))
         pos += n
     return rows
 
 
 # A ReLU unit whose input is within fp32 accumulation error of zero may be switched on by one
-# implementation and off by the other; both outcomes are valid.  One such unit changes a
-# single sample's contribution to a few gradient columns: invisible in the L2 norm, visible
-# in the max-abs norm of a small workload.  When the oracle reports such a unit (input
-# smaller than RELU_AMBIGUOUS times the layer's rms) the max-abs bound is relaxed to
-# MAXABS_RELAX * tol; the L2 bound never is.
+# implementation and off by the other; both outcomes are valid.  One such unit changes one
+# sample's contribution to one column of the gradients upstream: barely visible in the L2
+# norm, but it can dominate the max-abs norm (a float32-accumulating CPU emulation of the
+# forward pass shows the same against the float64 oracle: about 1 percent in L2, isolated
+# entries off by 10-25 percent of the tensor's maximum at the size of the benchmark
+# configuration).  So: the relative L2 bound always holds per tensor.  The max-abs bound
+# holds when the oracle reports no ambiguous unit (every ReLU input at least RELU_AMBIGUOUS
+# times its layer's rms away from zero); otherwise it is replaced by an outlier budget: at
+# most OUTLIER_FRACTION of a tensor's entries may miss the max-abs bound.
 RELU_AMBIGUOUS = 1e-5
-MAXABS_RELAX = 5.0
+OUTLIER_FRACTION = 0.01
 
 
-def assert_close_per_tensor(wl, got, want, tol, what, maxabs_tol=None):
-    mt = tol if maxabs_tol is None else maxabs_tol
-    bad = [(n, r, m) for n, r, m in tensor_errors(wl, got, want) if not (r <= tol and m <= mt)]
-    assert not bad, f"{what}: tensors beyond tol {tol} (max-abs {mt}): {bad[:8]}"
+def assert_close_per_tensor(wl, got, want, tol, what, ambiguous=False):
+    if ambiguous:
+        bad = [(n, r, f) for n, r, f in tensor_errors(wl, got, want, outlier_tol=tol)
+               if not (r <= tol and f <= OUTLIER_FRACTION)]
+        assert not bad, f"{what}: tensors beyond rel-L2 {tol} or outlier budget: {bad[:8]}"
+        return
+    bad = [(n, r, m) for n, r, m in tensor_errors(wl, got, want) if not (r <= tol and m <= tol)]
+    assert not bad, f"{what}: tensors beyond tol {tol}: {bad[:8]}"
 
 
 def check_against_oracle(wl, gpu, ref, tol=None, check_theta=True):
     """Per tensor: ||a-b||2/||b||2 <= tol and max|a-b| <= tol*max|b|; loss relative."""
     tol = TOL[wl.dtype] if tol is None else tol
-    mt = tol * (MAXABS_RELAX if ref.get("relu_margin", np.inf) < RELU_AMBIGUOUS else 1.0)
+    mt = ref.get("relu_margin", np.inf) < RELU_AMBIGUOUS
     assert abs(gpu["loss"] - ref["loss"]) <= tol * abs(ref["loss"]), (gpu["loss"], ref["loss"])
     np.testing.assert_allclose(gpu["node_losses"], ref["node_losses"], rtol=tol)
     assert_close_per_tensor(wl, gpu["G"], ref["G"], tol, "G", mt)
@@ -116,7 +128,7 @@ def check_against_oracle(wl, gpu, ref, tol=None, check_theta=True):
         assert_close_per_tensor(wl, gpu["s0"], ref["state"]["v"], tol, "velocity", mt)
     else:
         assert_close_per_tensor(wl, gpu["s0"], ref["state"]["m"], tol, "adam m", mt)
-        assert_close_per_tensor(wl, gpu["s1"], ref["state"]["u"], 2.5 * tol, "adam u", 2.5 * mt)   # quadratic in G
+        assert_close_per_tensor(wl, gpu["s1"], ref["state"]["u"], 2.5 * tol, "adam u", mt)   # quadratic in G
 
 
 def check_update_from_own_gradient(wl, gpu, theta0, tol=1e-5):
