@@ -185,10 +185,14 @@ int vf_adam_update(float* theta, float* m, float* u, const float* G, float lr, f
  * accumulated in fp32 on the matrix cores; VF_F32: A, B fp32.  C: device fp32 [M, ldc].
  * Forward y = x W uses B = W^T; input gradient dx = dy W^T uses B = W; weight gradient
  * dW = x^T dy uses A = x^T, B = dy^T with alpha = b_i/B and accumulate = 1 to fold a node's
- * gradient straight into the gradient buffer. */
+ * gradient straight into the gradient buffer.
+ * nsplit >= 1 cuts the contraction into nsplit slices (bf16 only, accumulate must be 0):
+ * C is then [nsplit][M][ldc] and slab s holds slice s's partial product; the caller adds
+ * the slabs (the library's consumers do so in slab order).  This is how the skinny products
+ * of a small virtual node are spread over all compute units. */
 int vf_gemm(int32_t dtype, const void* A, int64_t lda, const void* B, int64_t ldb, float* C,
             int64_t ldc, int32_t M, int32_t N, int32_t K, float alpha, int32_t accumulate,
-            void* stream);
+            int32_t nsplit, void* stream);
 
 #pragma GCC visibility pop
 

@@ -66,7 +66,7 @@ _SIGNATURES = {
     "vf_adam_update": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_float,
                                  C.c_float, C.c_float, C.c_int64, C.c_int64, C.c_void_p]),
     "vf_gemm": (C.c_int, [C.c_int32, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
-                          C.c_int32, C.c_int32, C.c_int32, C.c_float, C.c_int32, C.c_void_p]),
+                          C.c_int32, C.c_int32, C.c_int32, C.c_float, C.c_int32, C.c_int32, C.c_void_p]),
 }
 
 
@@ -139,14 +139,19 @@ def vf_adam_update(theta, m, u, G, lr, beta1, beta2, eps, t: int, stream=None):
 
 
 def vf_gemm(A, B, Cout, M: int, N: int, K: int, alpha: float = 1.0, accumulate: bool = False,
-            stream=None):
+            nsplit: int = 1, stream=None):
     """Cout[M,N] (fp32) = alpha * A[M,K] B[N,K]^T (+ Cout).  A, B: 2-D torch tensors (bf16 or
-    fp32), unit stride along the contraction."""
+    fp32), unit stride along the contraction.  With nsplit > 1 Cout is [nsplit, M, ldc]
+    (contiguous slabs) and receives the partial products of the contraction slices."""
     import torch
     dtype = VF_BF16 if A.dtype == torch.bfloat16 else VF_F32
-    assert A.dtype == B.dtype and A.stride(1) == 1 and B.stride(1) == 1 and Cout.stride(1) == 1
-    _check(lib().vf_gemm(dtype, _ptr(A), A.stride(0), _ptr(B), B.stride(0), _ptr(Cout), Cout.stride(0),
-                         M, N, K, float(alpha), int(bool(accumulate)), _stream_handle(stream)), "vf_gemm")
+    assert A.dtype == B.dtype and A.stride(-1) == 1 and B.stride(-1) == 1 and Cout.stride(-1) == 1
+    ldc = Cout.stride(-2)
+    if nsplit > 1:
+        assert Cout.dim() == 3 and Cout.stride(0) == M * ldc
+    _check(lib().vf_gemm(dtype, _ptr(A), A.stride(0), _ptr(B), B.stride(0), _ptr(Cout), ldc,
+                         M, N, K, float(alpha), int(bool(accumulate)), int(nsplit),
+                         _stream_handle(stream)), "vf_gemm")
 
 
 def config_from_workload(wl, max_batch: Optional[int] = None, max_node_size: Optional[int] = None,

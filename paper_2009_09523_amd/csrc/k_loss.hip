@@ -19,17 +19,25 @@ __device__ __forceinline__ float block_reduce(float v, bool is_max, float* red) 
 
 // One workgroup per row.
 template <typename T>
-__global__ __launch_bounds__(256) void softmax_xent_kernel(const float* __restrict__ z, int64_t ldz,
+__global__ __launch_bounds__(256) void softmax_xent_kernel(const float* __restrict__ zp, int nsplit,
+                                                           int64_t slab, int64_t ldzp,
+                                                           float* __restrict__ z, int64_t ldz,
                                                            const int32_t* __restrict__ labels, int R,
                                                            int C, float* __restrict__ rowloss,
                                                            T* __restrict__ dz, int64_t lddz) {
   __shared__ float red[4];
   const int r = blockIdx.x;
-  const float* zr = z + (int64_t)r * ldz;
+  float* zr = z + (int64_t)r * ldz;
   int label = labels[r];
   label = label < 0 ? 0 : (label >= C ? C - 1 : label);
   float mx = -INFINITY;
-  for (int c = threadIdx.x; c < C; c += 256) mx = fmaxf(mx, zr[c]);
+  for (int c = threadIdx.x; c < C; c += 256) {      // add the partial slabs in order
+    const int64_t idx = (int64_t)r * ldzp + c;
+    float v = zp[idx];
+    for (int s = 1; s < nsplit; ++s) v += zp[(int64_t)s * slab + idx];
+    zr[c] = v;
+    mx = fmaxf(mx, v);
+  }
   mx = block_reduce(mx, true, red);
   float sum = 0.f;
   for (int c = threadIdx.x; c < C; c += 256) sum += expf(zr[c] - mx);
@@ -41,6 +49,7 @@ __global__ __launch_bounds__(256) void softmax_xent_kernel(const float* __restri
     float p = expf(zr[c] - mx) * inv;
     store_f(&dr[c], (p - (c == label ? 1.f : 0.f)) * invR);
   }
+  __syncthreads();   // zr[label] was written by another thread of this workgroup
   if (threadIdx.x == 0) rowloss[r] = logf(sum) + mx - zr[label];
 }
 
@@ -62,14 +71,15 @@ __global__ __launch_bounds__(256) void loss_reduce_kernel(const float* __restric
 
 }  // namespace
 
-int launch_softmax_xent(const float* z, int64_t ldz, const int32_t* labels, int R, int C,
-                        float* rowloss, void* dz, int64_t lddz, int dz_is_bf16, hipStream_t s) {
-  if (R <= 0 || C <= 0) return VF_EINVAL;
+int launch_softmax_xent(const float* zp, int nsplit, int64_t slab, int64_t ldzp, float* z, int64_t ldz,
+                        const int32_t* labels, int R, int C, float* rowloss, void* dz, int64_t lddz,
+                        int dz_is_bf16, hipStream_t s) {
+  if (R <= 0 || C <= 0 || nsplit < 1) return VF_EINVAL;
   if (dz_is_bf16)
-    softmax_xent_kernel<bf16_t><<<R, 256, 0, s>>>(z, ldz, labels, R, C, rowloss,
+    softmax_xent_kernel<bf16_t><<<R, 256, 0, s>>>(zp, nsplit, slab, ldzp, z, ldz, labels, R, C, rowloss,
                                                   static_cast<bf16_t*>(dz), lddz);
   else
-    softmax_xent_kernel<float><<<R, 256, 0, s>>>(z, ldz, labels, R, C, rowloss,
+    softmax_xent_kernel<float><<<R, 256, 0, s>>>(zp, nsplit, slab, ldzp, z, ldz, labels, R, C, rowloss,
                                                  static_cast<float*>(dz), lddz);
   VF_LAUNCH_CHECK();
   return VF_OK;

@@ -2,6 +2,11 @@
 // The statistics are taken over exactly the R rows passed in -- the rows of the virtual node
 // being processed (Section 4.1: such state is computed by each pass on its own; Section 3.2:
 // each node is a separate forward and backward pass).  All reductions in fp32.
+//
+// Inputs that come from a GEMM arrive as `nsplit` partial slabs (see k_gemm_bf16.hip) and
+// are summed here in slab order.  Outputs that feed a weight-gradient GEMM are also written
+// transposed ([C, ldt], rows of the node contiguous), staged through LDS so that both
+// copies are written with full-width stores.
 #include "vf_device.h"
 
 namespace vf {
@@ -9,6 +14,7 @@ namespace {
 
 constexpr int CB = 32;    // columns per workgroup (128-byte fp32 row segments)
 constexpr int RL = 8;     // row lanes per column; 256 threads = CB x RL
+constexpr int RCH = 128;  // rows per transposed-store chunk
 
 // Sum over the RL row lanes of one column (threads with equal tx); result to all lanes.
 __device__ __forceinline__ float col_reduce(float v, float (*red)[CB + 1], int tx, int ty) {
@@ -21,47 +27,99 @@ __device__ __forceinline__ float col_reduce(float v, float (*red)[CB + 1], int t
   return s;
 }
 
-template <typename T>
-__global__ __launch_bounds__(256) void bn_relu_fwd_kernel(const float* __restrict__ z, int64_t ldz,
-                                                          int R, int C, const float* __restrict__ gamma,
+// Sum of the NS slabs at one element, in slab order; all loads are issued before the adds.
+template <int NS>
+__device__ __forceinline__ float sum_slabs(const float* __restrict__ p, int64_t stride, int64_t idx) {
+  float v[NS];
+#pragma unroll
+  for (int s = 0; s < NS; ++s) v[s] = p[(int64_t)s * stride + idx];
+  float t = v[0];
+#pragma unroll
+  for (int s = 1; s < NS; ++s) t += v[s];
+  return t;
+}
+
+// Writes the bf16 tile held in LDS ([CB][RCH+8], column-major of the node's rows r0..r0+RCH)
+// to outT[c*ldt + r].  16-byte stores; rows beyond R are padding inside the buffer's row.
+__device__ __forceinline__ void store_transposed(const bf16_t (*tile)[RCH + 8], bf16_t* __restrict__ outT,
+                                                 int64_t ldt, int c0, int C, int r0, int R) {
+  const int col = threadIdx.x >> 3, seg = threadIdx.x & 7;     // 32 columns x 8 segments of 16 rows
+  const int c = c0 + col;
+  if (c >= C) return;
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int rl = seg * 16 + h * 8;
+    if (r0 + rl < R)   // the vector holds at least one live row; ldt is a multiple of 8
+      *reinterpret_cast<uint4*>(&outT[(int64_t)c * ldt + r0 + rl]) =
+          *reinterpret_cast<const uint4*>(&tile[col][rl]);
+  }
+}
+
+template <typename T, int NS>
+__global__ __launch_bounds__(256) void bn_relu_fwd_kernel(const float* __restrict__ zp,
+                                                          int64_t slab, int64_t ldzp, int R, int C,
+                                                          const float* __restrict__ gamma,
                                                           const float* __restrict__ beta,
                                                           int round_params, float eps,
+                                                          float* __restrict__ z, int64_t ldz,
                                                           T* __restrict__ a, int64_t lda,
+                                                          bf16_t* __restrict__ aT, int64_t ldt,
                                                           float* __restrict__ mean_out,
                                                           float* __restrict__ rstd_out) {
   __shared__ float red[RL][CB + 1];
+  __shared__ __attribute__((aligned(16))) bf16_t tile[CB][RCH + 8];
   const int tx = threadIdx.x % CB, ty = threadIdx.x / CB;
-  const int c = blockIdx.x * CB + tx;
+  const int c0 = blockIdx.x * CB;
+  const int c = c0 + tx;
   const bool live = c < C;
-  if (gamma == nullptr) {                 // plain ReLU
-    if (live)
-      for (int r = ty; r < R; r += RL) store_f(&a[(int64_t)r * lda + c], fmaxf(z[(int64_t)r * ldz + c], 0.f));
-    return;
-  }
+  float mean = 0.f, rstd = 1.f, g = 1.f, b = 0.f;
+  // pass 1: reduce the slabs into z, column sums
   float s = 0.f;
   if (live)
-    for (int r = ty; r < R; r += RL) s += z[(int64_t)r * ldz + c];
-  const float mean = col_reduce(s, red, tx, ty) / (float)R;
-  float q = 0.f;
-  if (live)
     for (int r = ty; r < R; r += RL) {
-      float d = z[(int64_t)r * ldz + c] - mean;
-      q = fmaf(d, d, q);
+      float v = sum_slabs<NS>(zp, slab, (int64_t)r * ldzp + c);
+      z[(int64_t)r * ldz + c] = v;
+      s += v;
     }
-  const float var = col_reduce(q, red, tx, ty) / (float)R;
-  const float rstd = 1.0f / sqrtf(var + eps);
-  if (!live) return;
-  float g = gamma[c], b = beta[c];
-  if (round_params) { g = round_bf16(g); b = round_bf16(b); }
-  for (int r = ty; r < R; r += RL) {
-    float xhat = (z[(int64_t)r * ldz + c] - mean) * rstd;
-    store_f(&a[(int64_t)r * lda + c], fmaxf(fmaf(g, xhat, b), 0.f));
+  if (gamma != nullptr) {
+    mean = col_reduce(s, red, tx, ty) / (float)R;
+    float q = 0.f;
+    if (live)
+      for (int r = ty; r < R; r += RL) {
+        float d = z[(int64_t)r * ldz + c] - mean;
+        q = fmaf(d, d, q);
+      }
+    const float var = col_reduce(q, red, tx, ty) / (float)R;
+    rstd = 1.0f / sqrtf(var + eps);
+    if (live) {
+      g = gamma[c]; b = beta[c];
+      if (round_params) { g = round_bf16(g); b = round_bf16(b); }
+      if (ty == 0) { mean_out[c] = mean; rstd_out[c] = rstd; }
+    }
   }
-  if (ty == 0) { mean_out[c] = mean; rstd_out[c] = rstd; }
+  // pass 2: activation, in chunks of RCH rows so the transposed copy can go through LDS
+  for (int r0 = 0; r0 < R; r0 += RCH) {
+    for (int rl = ty; rl < RCH; rl += RL) {
+      const int r = r0 + rl;
+      float v = 0.f;
+      if (live && r < R) {
+        float zz = z[(int64_t)r * ldz + c];
+        v = gamma != nullptr ? fmaxf(fmaf(g, (zz - mean) * rstd, b), 0.f) : fmaxf(zz, 0.f);
+        store_f(&a[(int64_t)r * lda + c], v);
+      }
+      if (aT) tile[tx][rl] = f32_to_bf16(v);
+    }
+    if (aT) {
+      __syncthreads();
+      store_transposed(tile, aT, ldt, c0, C, r0, R);
+      __syncthreads();
+    }
+  }
 }
 
-template <typename T>
-__global__ __launch_bounds__(256) void bn_relu_bwd_kernel(const float* __restrict__ da, int64_t ldda,
+template <typename T, int NS>
+__global__ __launch_bounds__(256) void bn_relu_bwd_kernel(float* __restrict__ dap,
+                                                          int64_t slab, int64_t ldda,
                                                           const float* __restrict__ z, int64_t ldz,
                                                           int R, int C, const float* __restrict__ gamma,
                                                           const float* __restrict__ beta,
@@ -69,48 +127,68 @@ __global__ __launch_bounds__(256) void bn_relu_bwd_kernel(const float* __restric
                                                           const float* __restrict__ mean_in,
                                                           const float* __restrict__ rstd_in,
                                                           T* __restrict__ dz, int64_t lddz,
+                                                          bf16_t* __restrict__ dzT, int64_t ldt,
                                                           GradOut gout_g, GradOut gout_b) {
   __shared__ float red[RL][CB + 1];
+  __shared__ __attribute__((aligned(16))) bf16_t tile[CB][RCH + 8];
   const int tx = threadIdx.x % CB, ty = threadIdx.x / CB;
-  const int c = blockIdx.x * CB + tx;
+  const int c0 = blockIdx.x * CB;
+  const int c = c0 + tx;
   const bool live = c < C;
-  if (gamma == nullptr) {                 // ReLU backward + bias gradient
-    float sb = 0.f;
-    if (live)
-      for (int r = ty; r < R; r += RL) {
-        float d = z[(int64_t)r * ldz + c] > 0.f ? da[(int64_t)r * ldda + c] : 0.f;
-        store_f(&dz[(int64_t)r * lddz + c], d);
-        sb += d;
-      }
-    sb = col_reduce(sb, red, tx, ty);
-    if (live && ty == 0 && gout_b.dst) grad_store(gout_b, c, sb);
-    return;
-  }
-  float g = 0.f, b = 0.f, mean = 0.f, rstd = 0.f;
-  if (live) {
+  const bool bn = gamma != nullptr;
+  float g = 1.f, b = 0.f, mean = 0.f, rstd = 1.f;
+  if (live && bn) {
     g = gamma[c]; b = beta[c];
     if (round_params) { g = round_bf16(g); b = round_bf16(b); }
     mean = mean_in[c]; rstd = rstd_in[c];
   }
-  float sg = 0.f, sb = 0.f;               // sum dout*xhat, sum dout
+  // pass 1: sum dout*xhat, sum dout  (dout = da where the ReLU was open)
+  float sg = 0.f, sb = 0.f;
   if (live)
     for (int r = ty; r < R; r += RL) {
-      float xhat = (z[(int64_t)r * ldz + c] - mean) * rstd;
-      float dout = fmaf(g, xhat, b) > 0.f ? da[(int64_t)r * ldda + c] : 0.f;
+      float zz = z[(int64_t)r * ldz + c];
+      float xhat = (zz - mean) * rstd;
+      float pre = bn ? fmaf(g, xhat, b) : zz;
+      float d = sum_slabs<NS>(dap, slab, (int64_t)r * ldda + c);
+      float dout = pre > 0.f ? d : 0.f;
+      if (NS > 1) dap[(int64_t)r * ldda + c] = dout;   // keep the reduced, masked value in slab 0
       sg = fmaf(dout, xhat, sg);
       sb += dout;
     }
   sg = col_reduce(sg, red, tx, ty);
   sb = col_reduce(sb, red, tx, ty);
-  if (!live) return;
+  if (live && ty == 0) {
+    if (bn) grad_store(gout_g, c, sg);
+    if (gout_b.dst) grad_store(gout_b, c, sb);
+  }
   const float invR = 1.0f / (float)R;
   const float k = g * rstd;
-  for (int r = ty; r < R; r += RL) {
-    float xhat = (z[(int64_t)r * ldz + c] - mean) * rstd;
-    float dout = fmaf(g, xhat, b) > 0.f ? da[(int64_t)r * ldda + c] : 0.f;
-    store_f(&dz[(int64_t)r * lddz + c], k * (dout - sb * invR - xhat * sg * invR));
+  // pass 2: dz (and its transposed copy)
+  for (int r0 = 0; r0 < R; r0 += RCH) {
+    for (int rl = ty; rl < RCH; rl += RL) {
+      const int r = r0 + rl;
+      float v = 0.f;
+      if (live && r < R) {
+        float zz = z[(int64_t)r * ldz + c];
+        float xhat = (zz - mean) * rstd;
+        float dout;
+        if (NS > 1) {
+          dout = dap[(int64_t)r * ldda + c];           // written by this thread in pass 1
+        } else {
+          float pre = bn ? fmaf(g, xhat, b) : zz;
+          dout = pre > 0.f ? dap[(int64_t)r * ldda + c] : 0.f;
+        }
+        v = bn ? k * (dout - sb * invR - xhat * sg * invR) : dout;
+        store_f(&dz[(int64_t)r * lddz + c], v);
+      }
+      if (dzT) tile[tx][rl] = f32_to_bf16(v);
+    }
+    if (dzT) {
+      __syncthreads();
+      store_transposed(tile, dzT, ldt, c0, C, r0, R);
+      __syncthreads();
+    }
   }
-  if (ty == 0) { grad_store(gout_g, c, sg); grad_store(gout_b, c, sb); }
 }
 
 template <typename T>
@@ -128,35 +206,53 @@ __global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ x, in
 
 }  // namespace
 
-int launch_bn_relu_fwd(const float* z, int64_t ldz, int R, int C, const float* gamma,
-                       const float* beta, int round_params, float eps, void* a, int64_t lda,
-                       int a_is_bf16, float* mean, float* rstd, hipStream_t s) {
-  if (R <= 0 || C <= 0) return VF_EINVAL;
+int launch_bn_relu_fwd(const float* zp, int nsplit, int64_t slab, int64_t ldzp, int R, int C,
+                       const float* gamma, const float* beta, int round_params, float eps, float* z,
+                       int64_t ldz, void* a, int64_t lda, int a_is_bf16, bf16_t* aT, int64_t ldt,
+                       float* mean, float* rstd, hipStream_t s) {
+  if (R <= 0 || C <= 0 || nsplit < 1) return VF_EINVAL;
+  if (aT && ((ldt & 7) || !a_is_bf16)) return VF_EINVAL;
   int grid = (C + CB - 1) / CB;
-  if (a_is_bf16)
-    bn_relu_fwd_kernel<bf16_t><<<grid, 256, 0, s>>>(z, ldz, R, C, gamma, beta, round_params, eps,
-                                                    static_cast<bf16_t*>(a), lda, mean, rstd);
-  else
-    bn_relu_fwd_kernel<float><<<grid, 256, 0, s>>>(z, ldz, R, C, gamma, beta, round_params, eps,
-                                                   static_cast<float*>(a), lda, mean, rstd);
+#define VF_FWD(NS)                                                                                   \
+  case NS:                                                                                           \
+    if (a_is_bf16)                                                                                   \
+      bn_relu_fwd_kernel<bf16_t, NS><<<grid, 256, 0, s>>>(zp, slab, ldzp, R, C, gamma, beta,        \
+          round_params, eps, z, ldz, static_cast<bf16_t*>(a), lda, aT, ldt, mean, rstd);             \
+    else                                                                                             \
+      bn_relu_fwd_kernel<float, NS><<<grid, 256, 0, s>>>(zp, slab, ldzp, R, C, gamma, beta,         \
+          round_params, eps, z, ldz, static_cast<float*>(a), lda, aT, ldt, mean, rstd);              \
+    break;
+  switch (nsplit) {
+    VF_FWD(1) VF_FWD(2) VF_FWD(4) VF_FWD(8) VF_FWD(16) VF_FWD(32)
+    default: return VF_EINVAL;
+  }
+#undef VF_FWD
   VF_LAUNCH_CHECK();
   return VF_OK;
 }
 
-int launch_bn_relu_bwd(const float* da, int64_t ldda, const float* z, int64_t ldz, int R, int C,
-                       const float* gamma, const float* beta, int round_params,
-                       const float* mean, const float* rstd, void* dz, int64_t lddz,
-                       int dz_is_bf16, GradOut gout_g, GradOut gout_b, hipStream_t s) {
-  if (R <= 0 || C <= 0) return VF_EINVAL;
+int launch_bn_relu_bwd(float* dap, int nsplit, int64_t slab, int64_t ldda, const float* z,
+                       int64_t ldz, int R, int C, const float* gamma, const float* beta,
+                       int round_params, const float* mean, const float* rstd, void* dz, int64_t lddz,
+                       int dz_is_bf16, bf16_t* dzT, int64_t ldt, GradOut gout_g, GradOut gout_b,
+                       hipStream_t s) {
+  if (R <= 0 || C <= 0 || nsplit < 1) return VF_EINVAL;
+  if (dzT && ((ldt & 7) || !dz_is_bf16)) return VF_EINVAL;
   int grid = (C + CB - 1) / CB;
-  if (dz_is_bf16)
-    bn_relu_bwd_kernel<bf16_t><<<grid, 256, 0, s>>>(da, ldda, z, ldz, R, C, gamma, beta, round_params,
-                                                    mean, rstd, static_cast<bf16_t*>(dz), lddz,
-                                                    gout_g, gout_b);
-  else
-    bn_relu_bwd_kernel<float><<<grid, 256, 0, s>>>(da, ldda, z, ldz, R, C, gamma, beta, round_params,
-                                                   mean, rstd, static_cast<float*>(dz), lddz,
-                                                   gout_g, gout_b);
+#define VF_BWD(NS)                                                                                   \
+  case NS:                                                                                           \
+    if (dz_is_bf16)                                                                                  \
+      bn_relu_bwd_kernel<bf16_t, NS><<<grid, 256, 0, s>>>(dap, slab, ldda, z, ldz, R, C, gamma,     \
+          beta, round_params, mean, rstd, static_cast<bf16_t*>(dz), lddz, dzT, ldt, gout_g, gout_b); \
+    else                                                                                             \
+      bn_relu_bwd_kernel<float, NS><<<grid, 256, 0, s>>>(dap, slab, ldda, z, ldz, R, C, gamma,      \
+          beta, round_params, mean, rstd, static_cast<float*>(dz), lddz, dzT, ldt, gout_g, gout_b);  \
+    break;
+  switch (nsplit) {
+    VF_BWD(1) VF_BWD(2) VF_BWD(4) VF_BWD(8) VF_BWD(16) VF_BWD(32)
+    default: return VF_EINVAL;
+  }
+#undef VF_BWD
   VF_LAUNCH_CHECK();
   return VF_OK;
 }

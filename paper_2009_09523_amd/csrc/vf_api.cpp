@@ -350,15 +350,16 @@ int vf_adam_update(float* theta, float* m, float* u, const float* G, float lr, f
 
 int vf_gemm(int32_t dtype, const void* A, int64_t lda, const void* B, int64_t ldb, float* C,
             int64_t ldc, int32_t M, int32_t N, int32_t K, float alpha, int32_t accumulate,
-            void* stream) {
+            int32_t nsplit, void* stream) {
   if (!A || !B || !C || M < 1 || N < 1 || K < 1 || lda < K || ldb < K || ldc < N) return VF_EINVAL;
+  if (nsplit < 1 || (nsplit > 1 && (accumulate || dtype != VF_BF16))) return VF_EINVAL;
   Epilogue ep;
   ep.C = C; ep.ldc = ldc; ep.alpha = alpha;
   if (accumulate) { ep.R = C; ep.ldr = ldc; ep.beta = 1.f; }
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (dtype == VF_BF16)
     return launch_gemm_bf16(static_cast<const bf16_t*>(A), lda, static_cast<const bf16_t*>(B), ldb,
-                            M, N, K, ep, s);
+                            M, N, K, nsplit, (int64_t)M * ldc, ep, s);
   if (dtype == VF_F32)
     return launch_gemm_f32(static_cast<const float*>(A), lda, 1, static_cast<const float*>(B), ldb, 1,
                            M, N, K, ep, s);

@@ -80,9 +80,13 @@ int launch_gemm_f32(const float* A, int64_t sam, int64_t sak, const float* B, in
                     int64_t sbk, int M, int N, int K, const Epilogue& ep, hipStream_t s);
 
 // k_gemm_bf16.hip: acc[m,n] = sum_k A[m*lda + k] * B[n*ldb + k]  (bf16 operands, fp32 MFMA
-// accumulation).  lda, ldb multiples of 8, A and B 16-byte aligned.
+// accumulation).  lda, ldb multiples of 8, A and B 16-byte aligned.  The contraction is cut
+// into nsplit slices; slice s goes to ep.C + s*slab_stride elements (the consumer adds the
+// slabs in order).  With nsplit > 1 the epilogue may not add R; the bias goes to slab 0.
 int launch_gemm_bf16(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, int M, int N,
-                     int K, const Epilogue& ep, hipStream_t s);
+                     int K, int nsplit, int64_t slab_stride, const Epilogue& ep, hipStream_t s);
+// Number of slices that fills the chip for this shape (1 when the tile grid already does).
+int gemm_bf16_pick_split(int M, int N, int K);
 
 // k_elem.hip
 // out[c*ldo + r] = in[r*ldi + c]  for r < R, c < C
@@ -96,27 +100,34 @@ int launch_cast_bf16(const float* in, int64_t ldi, bf16_t* out, int64_t ldo, int
                      hipStream_t s);
 
 // k_norm.hip -- T is float or bf16_t (is_bf16 selects)
-// BatchNorm over the R rows given + ReLU:  a = relu(gamma*xhat + beta); saves mean, rstd.
-// With gamma == nullptr: a = relu(z) (plain bias-free ReLU; the bias is in the GEMM epilogue).
-int launch_bn_relu_fwd(const float* z, int64_t ldz, int R, int C, const float* gamma,
-                       const float* beta, int round_params, float eps, void* a, int64_t lda,
-                       int a_is_bf16, float* mean, float* rstd, hipStream_t s);
-// Backward of the above.  da: fp32 gradient w.r.t. a.  Writes dz (T) and, with BatchNorm,
-// dgamma/dbeta through GradOut; without BatchNorm (gamma == nullptr) writes the bias
-// gradient (column sums of dz) through gout_b.
-int launch_bn_relu_bwd(const float* da, int64_t ldda, const float* z, int64_t ldz, int R, int C,
-                       const float* gamma, const float* beta, int round_params,
-                       const float* mean, const float* rstd, void* dz, int64_t lddz,
-                       int dz_is_bf16, GradOut gout_g, GradOut gout_b, hipStream_t s);
+// BatchNorm over the R rows given + ReLU.  zp: nsplit partial slabs (slab elements apart,
+// leading dimension ldzp) of the Linear output; their sum is written to z (saved for the
+// backward pass).  a = relu(gamma*xhat + beta) as T; aT (optional, bf16 only) the same
+// transposed, [C, ldt].  Saves mean, rstd.  With gamma == nullptr: a = relu(z).
+int launch_bn_relu_fwd(const float* zp, int nsplit, int64_t slab, int64_t ldzp, int R, int C,
+                       const float* gamma, const float* beta, int round_params, float eps, float* z,
+                       int64_t ldz, void* a, int64_t lda, int a_is_bf16, bf16_t* aT, int64_t ldt,
+                       float* mean, float* rstd, hipStream_t s);
+// Backward of the above.  dap: nsplit partial slabs of the fp32 gradient w.r.t. a (slab 0 is
+// overwritten when nsplit > 1).  Writes dz (T), dzT (optional, bf16, [C, ldt]) and, with
+// BatchNorm, dgamma/dbeta through GradOut; without BatchNorm (gamma == nullptr) the bias
+// gradient (column sums of dz) through gout_b.  nsplit must be a power of two <= 32.
+int launch_bn_relu_bwd(float* dap, int nsplit, int64_t slab, int64_t ldda, const float* z,
+                       int64_t ldz, int R, int C, const float* gamma, const float* beta,
+                       int round_params, const float* mean, const float* rstd, void* dz, int64_t lddz,
+                       int dz_is_bf16, bf16_t* dzT, int64_t ldt, GradOut gout_g, GradOut gout_b,
+                       hipStream_t s);
 // out[c] = sum_r x[r*ld + c] through GradOut (x is T)
 int launch_colsum(const void* x, int64_t ld, int x_is_bf16, int R, int C, GradOut out,
                   hipStream_t s);
 
 // k_loss.hip
-// Softmax cross-entropy over R rows of fp32 logits [R, ldz] with C classes:
+// Softmax cross-entropy over R rows of fp32 logits with C classes.  zp: nsplit partial slabs
+// of the logits (summed into z, which may be slab 0 itself):
 //   rowloss[r] = logsumexp(z_r) - z_r[label_r];  dz[r,c] = (softmax(z_r)[c] - [c==label_r]) / R
-int launch_softmax_xent(const float* z, int64_t ldz, const int32_t* labels, int R, int C,
-                        float* rowloss, void* dz, int64_t lddz, int dz_is_bf16, hipStream_t s);
+int launch_softmax_xent(const float* zp, int nsplit, int64_t slab, int64_t ldzp, float* z, int64_t ldz,
+                        const int32_t* labels, int R, int C, float* rowloss, void* dz, int64_t lddz,
+                        int dz_is_bf16, hipStream_t s);
 // node_loss[i] = (1/R) sum_r rowloss[r];  total = (i == 0 ? 0 : total) + w * node_loss[i]
 int launch_loss_reduce(const float* rowloss, int R, float w, int node, float* node_loss,
                        float* total, hipStream_t s);

@@ -1,5 +1,7 @@
 // MLP with optional per-node BatchNorm: buffers and the launch sequence of one virtual node
 // (forward, loss, backward), Section 3.2 steps 1-3.
+#include <algorithm>
+
 #include "vf_ctx.h"
 
 namespace vf {
@@ -19,7 +21,6 @@ struct Layer {
   float* mean = nullptr;           // [N]
   float* rstd = nullptr;           // [N]
   void* a = nullptr;               // T [max_b, ld]: activation after BatchNorm/ReLU
-  float* da = nullptr;             // fp32 [max_b, ld]: gradient w.r.t. a
   void* dz = nullptr;              // T [max_b, ld]: gradient w.r.t. z
   bf16_t* aT = nullptr;            // bf16 [N, ldb]: a transposed   (weight-gradient operand)
   bf16_t* dzT = nullptr;           // bf16 [N, ldb]: dz transposed  (weight-gradient operand)
@@ -48,6 +49,34 @@ class Mlp final : public Model {
     }
     P_ = off;
     ldb_ = round8(cfg.max_node_size);
+    // Scratch for GEMM outputs that arrive as partial slabs: the largest split * rows * ld
+    // over the forward (N_l columns) and input-gradient (K_l columns) products.
+    slab_elems_ = 0;
+    for (const Layer& L : layers_) {
+      slab_elems_ = std::max(slab_elems_, slab_need(cfg.max_node_size, L.N, L.K, L.ld));
+      slab_elems_ = std::max(slab_elems_, slab_need(cfg.max_node_size, L.K, L.N, round8(L.K)));
+    }
+  }
+
+  // split * rows * ld maximised over node sizes up to max_b (the split only changes when the
+  // number of row tiles does)
+  int64_t slab_need(int max_b, int N, int K, int64_t ld) const {
+    int64_t need = 0;
+    auto probe = [&](int m) {
+      if (m > max_b) m = max_b;
+      int split = bf16_ ? gemm_bf16_pick_split(m, N, K) : 1;
+      need = std::max(need, (int64_t)split * m * ld);
+    };
+    probe(32); probe(64);
+    for (int m = 128; m < max_b + 128; m += 128) probe(m);
+    return need;
+  }
+
+  int split_for(int b, int N, int K, int64_t ld) const {
+    if (!bf16_) return 1;
+    int split = gemm_bf16_pick_split(b, N, K);
+    while (split > 1 && (int64_t)split * b * ld > slab_elems_) split /= 2;
+    return split;
   }
 
   int64_t num_params() const override { return P_; }
@@ -62,7 +91,6 @@ class Mlp final : public Model {
         a.request(&L.mean, (size_t)L.N);
         a.request(&L.rstd, (size_t)L.N);
         a.request(reinterpret_cast<char**>(&L.a), mb * L.ld * esz);
-        a.request(&L.da, mb * L.ld);
       }
       if (bf16_) {
         a.request(&L.wnat, (size_t)L.K * L.ldn);
@@ -72,6 +100,7 @@ class Mlp final : public Model {
       }
     }
     if (bf16_) a.request(&xT_, (size_t)cfg_.dims[0] * ldb_);
+    a.request(&slab_, (size_t)slab_elems_);
   }
 
   int prepare(Ctx& c, const float* params) override {
@@ -98,20 +127,25 @@ class Mlp final : public Model {
       Layer& L = layers_[l];
       const void* in = l == 0 ? x : layers_[l - 1].a;
       const int64_t ldin = l == 0 ? D : layers_[l - 1].ld;
+      const int split = split_for(b, L.N, L.K, L.ld);
+      const int64_t slab = (int64_t)b * L.ld;
       Epilogue ep;
-      ep.C = L.z; ep.ldc = L.ld;
+      ep.C = slab_; ep.ldc = L.ld;
       if (L.has_bias) { ep.bias = P + L.b_off; ep.bias_round_bf16 = bf16_; }
       if (bf16_)
-        VF_K(c, "gemm_fwd", launch_gemm_bf16(static_cast<const bf16_t*>(in), ldin, L.wtr, L.ldt, b, L.N, L.K, ep, st));
+        VF_K(c, "gemm_fwd", launch_gemm_bf16(static_cast<const bf16_t*>(in), ldin, L.wtr, L.ldt, b, L.N, L.K,
+                                             split, slab, ep, st));
       else
         VF_K(c, "gemm_fwd", launch_gemm_f32(static_cast<const float*>(in), ldin, 1, P + L.w_off, 1, L.N, b, L.N, L.K, ep, st));
       if (L.hidden)
-        VF_K(c, "bn_relu_fwd", launch_bn_relu_fwd(L.z, L.ld, b, L.N, L.has_bn ? P + L.g_off : nullptr,
-                                  L.has_bn ? P + L.be_off : nullptr, bf16_, cfg_.bn_eps, L.a, L.ld,
-                                  bf16_, L.mean, L.rstd, st));
+        VF_K(c, "bn_relu_fwd", launch_bn_relu_fwd(slab_, split, slab, L.ld, b, L.N,
+                                  L.has_bn ? P + L.g_off : nullptr, L.has_bn ? P + L.be_off : nullptr,
+                                  bf16_, cfg_.bn_eps, L.z, L.ld, L.a, L.ld, bf16_, L.aT, ldb_,
+                                  L.mean, L.rstd, st));
+      else
+        VF_K(c, "softmax_xent", launch_softmax_xent(slab_, split, slab, L.ld, L.z, L.ld, y, b, L.N,
+                                                    c.rowloss, L.dz, L.ld, bf16_, st));
     }
-    Layer& last = layers_[nl - 1];
-    VF_K(c, "softmax_xent", launch_softmax_xent(last.z, last.ld, y, b, last.N, c.rowloss, last.dz, last.ld, bf16_, st));
     VF_K(c, "loss_reduce", launch_loss_reduce(c.rowloss, b, w, i, c.node_loss, c.loss_total, st));
 
     // ---- backward ----------------------------------------------------------------------
@@ -127,10 +161,14 @@ class Mlp final : public Model {
       ep.C = go.dst; ep.ldc = L.N; ep.alpha = go.alpha;
       if (go.accumulate) { ep.R = go.dst; ep.ldr = L.N; ep.beta = 1.f; }
       if (bf16_) {
+        // transposed operands: hidden activations and their gradients were written by the
+        // BatchNorm/ReLU kernels; only the batch slice and the logits gradient remain
         bf16_t* inT = l == 0 ? xT_ : layers_[l - 1].aT;
-        VF_K(c, "transpose", launch_transpose_bf16(static_cast<const bf16_t*>(in), ldin, inT, ldb_, b, L.K, st));
-        VF_K(c, "transpose", launch_transpose_bf16(static_cast<const bf16_t*>(L.dz), L.ld, L.dzT, ldb_, b, L.N, st));
-        VF_K(c, "gemm_wgrad", launch_gemm_bf16(inT, ldb_, L.dzT, ldb_, L.K, L.N, b, ep, st));
+        if (l == 0)
+          VF_K(c, "transpose", launch_transpose_bf16(static_cast<const bf16_t*>(in), ldin, inT, ldb_, b, L.K, st));
+        if (!L.hidden)
+          VF_K(c, "transpose", launch_transpose_bf16(static_cast<const bf16_t*>(L.dz), L.ld, L.dzT, ldb_, b, L.N, st));
+        VF_K(c, "gemm_wgrad", launch_gemm_bf16(inT, ldb_, L.dzT, ldb_, L.K, L.N, b, 1, 0, ep, st));
       } else {
         VF_K(c, "gemm_wgrad", launch_gemm_f32(static_cast<const float*>(in), 1, ldin, static_cast<const float*>(L.dz), 1,
                                L.ld, L.K, L.N, b, ep, st));
@@ -138,17 +176,21 @@ class Mlp final : public Model {
       if (l == 0) break;
       // input gradient da[l-1][b,K] = dz W^T, then through ReLU / BatchNorm of layer l-1
       Layer& Pv = layers_[l - 1];
+      const int split = split_for(b, L.K, L.N, Pv.ld);
+      const int64_t slab = (int64_t)b * Pv.ld;
       Epilogue ed;
-      ed.C = Pv.da; ed.ldc = Pv.ld;
+      ed.C = slab_; ed.ldc = Pv.ld;
       if (bf16_)
-        VF_K(c, "gemm_dgrad", launch_gemm_bf16(static_cast<const bf16_t*>(L.dz), L.ld, L.wnat, L.ldn, b, L.K, L.N, ed, st));
+        VF_K(c, "gemm_dgrad", launch_gemm_bf16(static_cast<const bf16_t*>(L.dz), L.ld, L.wnat, L.ldn, b, L.K, L.N,
+                                               split, slab, ed, st));
       else
         VF_K(c, "gemm_dgrad", launch_gemm_f32(static_cast<const float*>(L.dz), L.ld, 1, P + L.w_off, L.N, 1, b, L.K, L.N, ed, st));
       GradOut gg = Pv.has_bn ? c.gout(Pv.g_off, w, i) : GradOut{nullptr, 0.f, 0};
       GradOut gb = c.gout(Pv.has_bn ? Pv.be_off : Pv.b_off, w, i);
-      VF_K(c, "bn_relu_bwd", launch_bn_relu_bwd(Pv.da, Pv.ld, Pv.z, Pv.ld, b, Pv.N, Pv.has_bn ? P + Pv.g_off : nullptr,
-                                Pv.has_bn ? P + Pv.be_off : nullptr, bf16_, Pv.mean, Pv.rstd, Pv.dz,
-                                Pv.ld, bf16_, gg, gb, st));
+      VF_K(c, "bn_relu_bwd", launch_bn_relu_bwd(slab_, split, slab, Pv.ld, Pv.z, Pv.ld, b, Pv.N,
+                                Pv.has_bn ? P + Pv.g_off : nullptr, Pv.has_bn ? P + Pv.be_off : nullptr,
+                                bf16_, Pv.mean, Pv.rstd, Pv.dz, Pv.ld, bf16_, bf16_ ? Pv.dzT : nullptr, ldb_,
+                                gg, gb, st));
     }
     return VF_OK;
   }
@@ -160,6 +202,8 @@ class Mlp final : public Model {
   int64_t ldb_ = 0;
   std::vector<Layer> layers_;
   bf16_t* xT_ = nullptr;
+  float* slab_ = nullptr;
+  int64_t slab_elems_ = 0;
 };
 
 }  // namespace

@@ -111,3 +111,22 @@ def test_gemm_against_float64_matmul(M, N, K, dtype):
     torch.cuda.synchronize()
     got2 = Cd.cpu().numpy()
     assert np.max(np.abs(got2[:, :N] - 0.25 * want)) <= 2 * tol
+
+
+@pytest.mark.parametrize("M,N,K,nsplit", [(128, 512, 4096, 16), (48, 1000, 520, 3), (16, 392, 1000, 4),
+                                         (128, 264, 72, 2), (300, 100, 1000, 8)])
+def test_gemm_split_contraction_slabs_sum_to_product(M, N, K, nsplit):
+    import torch
+    import paper_2009_09523_amd as vf
+    print(f"gemm split M={M} N={N} K={K} nsplit={nsplit}", flush=True)
+    rng = np.random.Generator(np.random.PCG64(M + N + K))
+    A = torch.from_numpy(rng.standard_normal((M, K)).astype(np.float32)).to(torch.bfloat16).cuda()
+    B = torch.from_numpy(rng.standard_normal((N, K)).astype(np.float32)).to(torch.bfloat16).cuda()
+    ldc = N + 5
+    Cd = torch.full((nsplit, M, ldc), 3.0, device="cuda")
+    vf.vf_gemm(A, B, Cd, M, N, K, nsplit=nsplit)
+    torch.cuda.synchronize()
+    got = Cd.cpu().numpy().astype(np.float64)
+    want = A.double().cpu().numpy() @ B.double().cpu().numpy().T
+    assert np.all(got[:, :, N:] == 3.0)
+    assert np.max(np.abs(got[:, :, :N].sum(axis=0) - want)) <= 1e-5 * np.sqrt(K) * np.max(np.abs(want))
