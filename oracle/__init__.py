@@ -15,10 +15,10 @@ with the weights of Section 5.2), written in NumPy float64:
 
 bf16 workloads are defined as "bf16 weights and activations, fp32 accumulation,
 fp32 master weights": the oracle rounds the fp32 master parameters to bf16
-(round-to-nearest-even) before the passes and, in the MLP, rounds every operand
-of a Linear contraction (activations, output gradients) to bf16; everything
-else is float64.  The encoder has no discontinuous activation and rounds the
-parameters only.
+(round-to-nearest-even) before the passes and rounds every operand of a
+contraction (activations fed to a Linear or an attention product, gradients
+fed to a backward contraction, and the saved FFN pre-activation) to bf16;
+everything else is float64.
 
 Pins (tests/test_oracle_*.py): the 6+2 worked example of Section 5.2 with its
 unweighted negative control; partition-invariance of G without BatchNorm;

@@ -111,22 +111,28 @@ def softmax_xent_fwd_bwd(logits, labels):
 
 # ---- multi-head self-attention (no mask, no dropout) --------------------------------------
 
-def attention_fwd(q, k, v):
-    """q, k, v: [n_seq, n_heads, T, d_head].  softmax(q k^T / sqrt(d_head)) v."""
+def _identity(a):
+    return a
+
+
+def attention_fwd(q, k, v, operand=_identity):
+    """q, k, v: [n_seq, n_heads, T, d_head].  softmax(q k^T / sqrt(d_head)) v.
+    `operand` is applied to the probabilities before they enter the product with v
+    (identity, or bf16 rounding for bf16 workloads); the returned p is that operand."""
     dh = q.shape[-1]
     s = (q @ np.swapaxes(k, -1, -2)) / np.sqrt(dh)
     s = s - s.max(axis=-1, keepdims=True)
     p = np.exp(s)
-    p = p / p.sum(axis=-1, keepdims=True)
+    p = operand(p / p.sum(axis=-1, keepdims=True))
     return p @ v, p
 
 
-def attention_bwd(do, q, k, v, p):
+def attention_bwd(do, q, k, v, p, operand=_identity):
+    """`operand` is applied to the score gradient before its products with k and q."""
     dh = q.shape[-1]
     dv = np.swapaxes(p, -1, -2) @ do
     dp = do @ np.swapaxes(v, -1, -2)
-    ds = p * (dp - (dp * p).sum(axis=-1, keepdims=True))
-    ds = ds / np.sqrt(dh)
-    dq = ds @ k
-    dk = np.swapaxes(ds, -1, -2) @ q
+    ds = operand(p * (dp - (dp * p).sum(axis=-1, keepdims=True)))
+    dq = (ds @ k) / np.sqrt(dh)
+    dk = (np.swapaxes(ds, -1, -2) @ q) / np.sqrt(dh)
     return dq, dk, dv

@@ -60,10 +60,10 @@ def _flatten(wl, grads):
 # ---- one node: loss L_i (mean over the node) and g_i = dL_i/dtheta ----------------------
 
 def _operand(wl):
-    """How a tensor enters a Linear contraction.  bf16 workloads are defined with bf16
-    weights AND activations (fp32 accumulation): every operand of a contraction -- the
-    activation fed to a Linear, and the output gradient fed to its two backward
-    contractions -- is rounded to bf16; everything between contractions stays float64.
+    """How a tensor enters a contraction.  bf16 workloads are defined with bf16 weights
+    AND activations (fp32 accumulation): every operand of a contraction -- the activation
+    fed to a Linear or to an attention product, and the gradient fed to a backward
+    contraction -- is rounded to bf16; everything between contractions stays float64.
     This also puts the one discontinuous decision of the MLP, the ReLU mask of the next
     layer, at the same precision on both sides of a parity check."""
     if wl.dtype == "bf16":
@@ -121,23 +121,33 @@ def _encoder_node(wl, p, ids, y):
     """ids [n, T] token ids (masked positions already hold id 0); y [n, 2, m]:
     y[:,0] positions, y[:,1] target ids.  Pre-LayerNorm encoder, GELU FFN, final
     LayerNorm, untied output projection on the masked rows, mean cross-entropy
-    over the node's n*m masked rows."""
+    over the node's n*m masked rows.
+
+    bf16 workloads: every tensor that is stored as an operand of a later
+    contraction or saved as an activation (LayerNorm outputs, q/k/v, attention
+    probabilities and outputs, FFN pre-activation and GELU output, and in the
+    backward pass every gradient handed to a contraction) is rounded to bf16 by
+    `q`; the residual stream, statistics, logits and the gradients between a
+    contraction and the next element-wise step stay float64."""
+    q_ = _operand(wl)
     ids = np.asarray(ids, dtype=np.int64)
     y = np.asarray(y, dtype=np.int64)
     n, T = ids.shape
-    d, nh = wl.d_model, wl.n_heads
+    d, nh, ffn = wl.d_model, wl.n_heads, wl.d_ffn
     h = p["tok_emb"][ids] + p["pos_emb"][None, :T, :]
     saved = []
     for l in range(wl.n_layers):
         a, c1 = L.layernorm_fwd(h, p[f"l{l}.ln1.gamma"], p[f"l{l}.ln1.beta"], wl.ln_eps)
-        qkv = L.linear_fwd(a, p[f"l{l}.Wqkv"], p[f"l{l}.bqkv"])
+        a = q_(a)
+        qkv = q_(L.linear_fwd(a, p[f"l{l}.Wqkv"], p[f"l{l}.bqkv"]))
         q, k, v = (_split_heads(qkv[..., i * d:(i + 1) * d], nh) for i in range(3))
-        o, prob = L.attention_fwd(q, k, v)
-        om = _merge_heads(o)
+        o, prob = L.attention_fwd(q, k, v, q_)
+        om = q_(_merge_heads(o))
         h_mid = h + L.linear_fwd(om, p[f"l{l}.Wo"], p[f"l{l}.bo"])
         f, c2 = L.layernorm_fwd(h_mid, p[f"l{l}.ln2.gamma"], p[f"l{l}.ln2.beta"], wl.ln_eps)
-        u = L.linear_fwd(f, p[f"l{l}.W1"], p[f"l{l}.b1"])
-        gl = L.gelu_fwd(u)
+        f = q_(f)
+        u = q_(L.linear_fwd(f, p[f"l{l}.W1"], p[f"l{l}.b1"]))
+        gl = q_(L.gelu_fwd(u))
         h_out = h_mid + L.linear_fwd(gl, p[f"l{l}.W2"], p[f"l{l}.b2"])
         saved.append((a, c1, q, k, v, prob, om, f, c2, u, gl))
         h = h_out
@@ -145,28 +155,28 @@ def _encoder_node(wl, p, ids, y):
     seq = np.repeat(np.arange(n), y.shape[2])
     pos = y[:, 0, :].reshape(-1)
     tgt = y[:, 1, :].reshape(-1)
-    rows = hf[seq, pos, :]                                  # [n*m, d]
+    rows = q_(hf[seq, pos, :])                              # [n*m, d]
     logits = L.linear_fwd(rows, p["Wout"], p["bout"])
     loss, dlogits = L.softmax_xent_fwd_bwd(logits, tgt)
 
     g = {}
-    drows, g["Wout"], g["bout"] = L.linear_bwd(rows, p["Wout"], dlogits, True)
+    drows, g["Wout"], g["bout"] = L.linear_bwd(rows, p["Wout"], q_(dlogits), True)
     dhf = np.zeros_like(hf)
     np.add.at(dhf, (seq, pos), drows)
     dh, g["lnf.gamma"], g["lnf.beta"] = L.layernorm_bwd(dhf, p["lnf.gamma"], cf)
     for l in range(wl.n_layers - 1, -1, -1):
         a, c1, q, k, v, prob, om, f, c2, u, gl = saved[l]
-        dgl, g[f"l{l}.W2"], g[f"l{l}.b2"] = L.linear_bwd(gl.reshape(-1, wl.d_ffn), p[f"l{l}.W2"],
-                                                         dh.reshape(-1, d), True)
-        du = L.gelu_bwd(dgl, u.reshape(-1, wl.d_ffn))
+        dgl, g[f"l{l}.W2"], _ = L.linear_bwd(gl.reshape(-1, ffn), p[f"l{l}.W2"], q_(dh.reshape(-1, d)), False)
+        g[f"l{l}.b2"] = dh.reshape(-1, d).sum(axis=0)
+        du = q_(L.gelu_bwd(dgl, u.reshape(-1, ffn)))
         df, g[f"l{l}.W1"], g[f"l{l}.b1"] = L.linear_bwd(f.reshape(-1, d), p[f"l{l}.W1"], du, True)
         dmid, g[f"l{l}.ln2.gamma"], g[f"l{l}.ln2.beta"] = L.layernorm_bwd(
             df.reshape(n, T, d), p[f"l{l}.ln2.gamma"], c2)
         dmid = dmid + dh                                     # residual around the FFN
-        dom, g[f"l{l}.Wo"], g[f"l{l}.bo"] = L.linear_bwd(om.reshape(-1, d), p[f"l{l}.Wo"],
-                                                         dmid.reshape(-1, d), True)
-        dq, dk, dv = L.attention_bwd(_split_heads(dom.reshape(n, T, d), nh), q, k, v, prob)
-        dqkv = np.concatenate([_merge_heads(dq), _merge_heads(dk), _merge_heads(dv)], axis=-1)
+        dom, g[f"l{l}.Wo"], _ = L.linear_bwd(om.reshape(-1, d), p[f"l{l}.Wo"], q_(dmid.reshape(-1, d)), False)
+        g[f"l{l}.bo"] = dmid.reshape(-1, d).sum(axis=0)
+        dq, dk, dv = L.attention_bwd(_split_heads(q_(dom.reshape(n, T, d)), nh), q, k, v, prob, q_)
+        dqkv = q_(np.concatenate([_merge_heads(dq), _merge_heads(dk), _merge_heads(dv)], axis=-1))
         da, g[f"l{l}.Wqkv"], g[f"l{l}.bqkv"] = L.linear_bwd(a.reshape(-1, d), p[f"l{l}.Wqkv"],
                                                             dqkv.reshape(-1, 3 * d), True)
         din, g[f"l{l}.ln1.gamma"], g[f"l{l}.ln1.beta"] = L.layernorm_bwd(

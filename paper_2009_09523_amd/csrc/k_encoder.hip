@@ -1,0 +1,362 @@
+// Row-wise and element-wise kernels of the pre-LayerNorm encoder: embedding gather and its
+// deterministic scatter-add backward, LayerNorm forward/backward, exact GELU, row softmax.
+// All statistics and reductions in fp32; one wavefront per row where a row is reduced.
+#include "vf_device.h"
+
+namespace vf {
+namespace {
+
+constexpr int NT = 256;
+constexpr int WAVES = NT / 64;
+
+__device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
+
+__global__ __launch_bounds__(NT) void embed_fwd_kernel(const int32_t* __restrict__ ids,
+                                                       const float* __restrict__ tok,
+                                                       const float* __restrict__ pos, int R, int T, int d,
+                                                       int vocab, int round_params, float* __restrict__ h) {
+  const int r = blockIdx.x;
+  const int id = clampi(ids[r], 0, vocab - 1);
+  const int t = r % T;
+  for (int c = threadIdx.x; c < d; c += NT) {
+    float a = tok[(int64_t)id * d + c], b = pos[(int64_t)t * d + c];
+    if (round_params) { a = round_bf16(a); b = round_bf16(b); }
+    h[(int64_t)r * d + c] = a + b;
+  }
+}
+
+__global__ __launch_bounds__(NT) void embed_pos_bwd_kernel(const float* __restrict__ dh, int nseq, int T,
+                                                           int d, GradOut out) {
+  const int t = blockIdx.x;
+  for (int c = threadIdx.x; c < d; c += NT) {
+    float s = 0.f;
+    for (int q = 0; q < nseq; ++q) s += dh[((int64_t)q * T + t) * d + c];
+    grad_store(out, (int64_t)t * d + c, s);
+  }
+}
+
+// One workgroup per token r.  The first token that carries a given id (the "leader") adds up
+// the rows of all tokens with that id in increasing token order and writes the table row;
+// the other workgroups exit.  No atomics: the sum order is fixed.
+__global__ __launch_bounds__(NT) void embed_tok_bwd_kernel(const int32_t* __restrict__ ids,
+                                                           const float* __restrict__ dh, int R, int d,
+                                                           int vocab, GradOut out) {
+  __shared__ int earlier;
+  const int r = blockIdx.x;
+  const int id = clampi(ids[r], 0, vocab - 1);
+  if (threadIdx.x == 0) earlier = 0;
+  __syncthreads();
+  int found = 0;
+  for (int q = threadIdx.x; q < r; q += NT) found |= (clampi(ids[q], 0, vocab - 1) == id);
+  if (found) earlier = 1;     // benign race: every writer stores 1
+  __syncthreads();
+  if (earlier) return;
+  for (int c = threadIdx.x; c < d; c += NT) {
+    float s = dh[(int64_t)r * d + c];
+    for (int q = r + 1; q < R; ++q)
+      if (clampi(ids[q], 0, vocab - 1) == id) s += dh[(int64_t)q * d + c];
+    grad_store(out, (int64_t)id * d + c, s);
+  }
+}
+
+__global__ __launch_bounds__(NT) void extract_masked_kernel(const int32_t* __restrict__ y, int nseq, int m,
+                                                            int T, int vocab, int32_t* __restrict__ rowidx,
+                                                            int32_t* __restrict__ labels) {
+  const int i = blockIdx.x * NT + threadIdx.x;
+  if (i >= nseq * m) return;
+  const int sq = i / m, j = i % m;
+  const int p = clampi(y[(int64_t)sq * 2 * m + j], 0, T - 1);
+  rowidx[i] = sq * T + p;
+  labels[i] = clampi(y[(int64_t)sq * 2 * m + m + j], 0, vocab - 1);
+}
+
+// ---- LayerNorm: one wavefront per row ------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(NT) void layernorm_fwd_kernel(const float* __restrict__ x, int64_t ldx,
+                                                           const int32_t* __restrict__ row_map, int R,
+                                                           int d, const float* __restrict__ gamma,
+                                                           const float* __restrict__ beta,
+                                                           int round_params, float eps, T* __restrict__ y,
+                                                           int64_t ldy, float* __restrict__ mean_out,
+                                                           float* __restrict__ rstd_out) {
+  const int lane = threadIdx.x & 63;
+  const int r = blockIdx.x * WAVES + (threadIdx.x >> 6);
+  if (r >= R) return;
+  const float* xr = x + (int64_t)(row_map ? row_map[r] : r) * ldx;
+  float s = 0.f;
+  for (int c = lane; c < d; c += 64) s += xr[c];
+  const float mean = wave_sum(s) / (float)d;
+  float q = 0.f;
+  for (int c = lane; c < d; c += 64) {
+    float v = xr[c] - mean;
+    q = fmaf(v, v, q);
+  }
+  const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)d + eps);
+  for (int c = lane; c < d; c += 64) {
+    float g = gamma[c], b = beta[c];
+    if (round_params) { g = round_bf16(g); b = round_bf16(b); }
+    store_f(&y[(int64_t)r * ldy + c], fmaf(g, (xr[c] - mean) * rstd, b));
+  }
+  if (lane == 0) { mean_out[r] = mean; rstd_out[r] = rstd; }
+}
+
+__global__ __launch_bounds__(NT) void layernorm_bwd_kernel(const float* __restrict__ dyp, int nsplit,
+                                                           int64_t slab, int64_t lddy,
+                                                           const float* __restrict__ x, int64_t ldx,
+                                                           const int32_t* __restrict__ row_map, int R,
+                                                           int d, const float* __restrict__ gamma,
+                                                           int round_params,
+                                                           const float* __restrict__ mean_in,
+                                                           const float* __restrict__ rstd_in,
+                                                           const float* __restrict__ dres,
+                                                           float* __restrict__ dx, int64_t lddx) {
+  const int lane = threadIdx.x & 63;
+  const int r = blockIdx.x * WAVES + (threadIdx.x >> 6);
+  if (r >= R) return;
+  const int64_t orow = row_map ? row_map[r] : r;
+  const float* xr = x + orow * ldx;
+  const float mean = mean_in[r], rstd = rstd_in[r];
+  float s1 = 0.f, s2 = 0.f;
+  for (int c = lane; c < d; c += 64) {
+    float dy = dyp[(int64_t)r * lddy + c];
+    for (int s = 1; s < nsplit; ++s) dy += dyp[(int64_t)s * slab + (int64_t)r * lddy + c];
+    float g = gamma[c];
+    if (round_params) g = round_bf16(g);
+    float dxh = dy * g;
+    float xh = (xr[c] - mean) * rstd;
+    s1 += dxh;
+    s2 = fmaf(dxh, xh, s2);
+  }
+  s1 = wave_sum(s1) / (float)d;
+  s2 = wave_sum(s2) / (float)d;
+  for (int c = lane; c < d; c += 64) {
+    float dy = dyp[(int64_t)r * lddy + c];
+    for (int s = 1; s < nsplit; ++s) dy += dyp[(int64_t)s * slab + (int64_t)r * lddy + c];
+    float g = gamma[c];
+    if (round_params) g = round_bf16(g);
+    float xh = (xr[c] - mean) * rstd;
+    float v = (dy * g - s1 - xh * s2) * rstd;
+    if (dres) v += dres[orow * lddx + c];
+    dx[orow * lddx + c] = v;
+  }
+}
+
+constexpr int CB = 32, RL = 8;
+__global__ __launch_bounds__(NT) void layernorm_param_bwd_kernel(const float* __restrict__ dyp, int nsplit,
+                                                                 int64_t slab, int64_t lddy,
+                                                                 const float* __restrict__ x, int64_t ldx,
+                                                                 const int32_t* __restrict__ row_map,
+                                                                 int R, int d,
+                                                                 const float* __restrict__ mean_in,
+                                                                 const float* __restrict__ rstd_in,
+                                                                 GradOut gout_g, GradOut gout_b) {
+  __shared__ float red[2][RL][CB + 1];
+  const int tx = threadIdx.x % CB, ty = threadIdx.x / CB;
+  const int c = blockIdx.x * CB + tx;
+  float sg = 0.f, sb = 0.f;
+  if (c < d)
+    for (int r = ty; r < R; r += RL) {
+      float dy = dyp[(int64_t)r * lddy + c];
+      for (int s = 1; s < nsplit; ++s) dy += dyp[(int64_t)s * slab + (int64_t)r * lddy + c];
+      const int64_t xrow = row_map ? row_map[r] : r;
+      float xh = (x[xrow * ldx + c] - mean_in[r]) * rstd_in[r];
+      sg = fmaf(dy, xh, sg);
+      sb += dy;
+    }
+  red[0][ty][tx] = sg;
+  red[1][ty][tx] = sb;
+  __syncthreads();
+  if (ty == 0 && c < d) {
+    float a = 0.f, b = 0.f;
+#pragma unroll
+    for (int i = 0; i < RL; ++i) { a += red[0][i][tx]; b += red[1][i][tx]; }
+    grad_store(gout_g, c, a);
+    grad_store(gout_b, c, b);
+  }
+}
+
+// ---- GELU (exact) ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(NT) void gelu_fwd_kernel(const T* __restrict__ u, T* __restrict__ g, int64_t n) {
+  int64_t i = (int64_t)blockIdx.x * NT + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * NT;
+  for (; i < n; i += stride) {
+    float v = load_f(&u[i]);
+    store_f(&g[i], 0.5f * v * (1.0f + erff(v * 0.70710678118654752f)));
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(NT) void gelu_bwd_kernel(const float* __restrict__ dg, const T* __restrict__ u,
+                                                      T* __restrict__ du, int64_t n) {
+  int64_t i = (int64_t)blockIdx.x * NT + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * NT;
+  for (; i < n; i += stride) {
+    float v = load_f(&u[i]);
+    float cdf = 0.5f * (1.0f + erff(v * 0.70710678118654752f));
+    float pdf = 0.3989422804014327f * expf(-0.5f * v * v);
+    store_f(&du[i], dg[i] * (cdf + v * pdf));
+  }
+}
+
+// ---- row softmax: one wavefront per row --------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(NT) void softmax_rows_kernel(const float* __restrict__ S, T* __restrict__ P,
+                                                          int64_t rows, int n) {
+  const int lane = threadIdx.x & 63;
+  const int64_t r = (int64_t)blockIdx.x * WAVES + (threadIdx.x >> 6);
+  if (r >= rows) return;
+  const float* sr = S + r * n;
+  float mx = -INFINITY;
+  for (int c = lane; c < n; c += 64) mx = fmaxf(mx, sr[c]);
+  mx = wave_max(mx);
+  float sum = 0.f;
+  for (int c = lane; c < n; c += 64) sum += expf(sr[c] - mx);
+  const float inv = 1.0f / wave_sum(sum);
+  for (int c = lane; c < n; c += 64) store_f(&P[r * n + c], expf(sr[c] - mx) * inv);
+}
+
+template <typename T>
+__global__ __launch_bounds__(NT) void softmax_rows_bwd_kernel(float* __restrict__ dP, const T* __restrict__ P,
+                                                              int64_t rows, int n) {
+  const int lane = threadIdx.x & 63;
+  const int64_t r = (int64_t)blockIdx.x * WAVES + (threadIdx.x >> 6);
+  if (r >= rows) return;
+  float dot = 0.f;
+  for (int c = lane; c < n; c += 64) dot = fmaf(dP[r * n + c], load_f(&P[r * n + c]), dot);
+  dot = wave_sum(dot);
+  for (int c = lane; c < n; c += 64) {
+    float p = load_f(&P[r * n + c]);
+    dP[r * n + c] = p * (dP[r * n + c] - dot);
+  }
+}
+
+__global__ __launch_bounds__(NT) void reduce_slabs_kernel(const float* __restrict__ in, int nsplit,
+                                                          int64_t slab, int64_t n, float* __restrict__ out) {
+  int64_t i = (int64_t)blockIdx.x * NT + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * NT;
+  for (; i < n; i += stride) {
+    float v = in[i];
+    for (int s = 1; s < nsplit; ++s) v += in[(int64_t)s * slab + i];
+    out[i] = v;
+  }
+}
+
+inline int blocks_for(int64_t n) {
+  int64_t b = (n + NT - 1) / NT;
+  return (int)(b > 8192 ? 8192 : (b < 1 ? 1 : b));
+}
+
+}  // namespace
+
+int launch_embed_fwd(const int32_t* ids, const float* tok, const float* pos, int R, int T, int d,
+                     int vocab, int round_params, float* h, hipStream_t s) {
+  if (R <= 0) return VF_EINVAL;
+  embed_fwd_kernel<<<R, NT, 0, s>>>(ids, tok, pos, R, T, d, vocab, round_params, h);
+  VF_LAUNCH_CHECK();
+  return VF_OK;
+}
+
+int launch_embed_pos_bwd(const float* dh, int nseq, int T, int d, GradOut out, hipStream_t s) {
+  embed_pos_bwd_kernel<<<T, NT, 0, s>>>(dh, nseq, T, d, out);
+  VF_LAUNCH_CHECK();
+  return VF_OK;
+}
+
+int launch_embed_tok_bwd(const int32_t* ids, const float* dh, int R, int d, int vocab, GradOut out,
+                         hipStream_t s) {
+  embed_tok_bwd_kernel<<<R, NT, 0, s>>>(ids, dh, R, d, vocab, out);
+  VF_LAUNCH_CHECK();
+  return VF_OK;
+}
+
+int launch_extract_masked(const int32_t* y, int nseq, int m, int T, int vocab, int32_t* rowidx,
+                          int32_t* labels, hipStream_t s) {
+  extract_masked_kernel<<<(nseq * m + NT - 1) / NT, NT, 0, s>>>(y, nseq, m, T, vocab, rowidx, labels);
+  VF_LAUNCH_CHECK();
+  return VF_OK;
+}
+
+int launch_layernorm_fwd(const float* x, int64_t ldx, const int32_t* row_map, int R, int d,
+                         const float* gamma, const float* beta, int round_params, float eps, void* y,
+                         int64_t ldy, int y_is_bf16, float* mean, float* rstd, hipStream_t s) {
+  if (R <= 0 || d <= 0) return VF_EINVAL;
+  int grid = (R + WAVES - 1) / WAVES;
+  if (y_is_bf16)
+    layernorm_fwd_kernel<bf16_t><<<grid, NT, 0, s>>>(x, ldx, row_map, R, d, gamma, beta, round_params, eps,
+                                                     static_cast<bf16_t*>(y), ldy, mean, rstd);
+  else
+    layernorm_fwd_kernel<float><<<grid, NT, 0, s>>>(x, ldx, row_map, R, d, gamma, beta, round_params, eps,
+                                                    static_cast<float*>(y), ldy, mean, rstd);
+  VF_LAUNCH_CHECK();
+  return VF_OK;
+}
+
+int launch_layernorm_bwd(const float* dyp, int nsplit, int64_t slab, int64_t lddy, const float* x,
+                         int64_t ldx, const int32_t* row_map, int R, int d, const float* gamma,
+                         int round_params, const float* mean, const float* rstd, const float* dres,
+                         float* dx, int64_t lddx, hipStream_t s) {
+  if (R <= 0 || d <= 0 || nsplit < 1) return VF_EINVAL;
+  layernorm_bwd_kernel<<<(R + WAVES - 1) / WAVES, NT, 0, s>>>(dyp, nsplit, slab, lddy, x, ldx, row_map, R, d,
+                                                              gamma, round_params, mean, rstd, dres, dx,
+                                                              lddx);
+  VF_LAUNCH_CHECK();
+  return VF_OK;
+}
+
+int launch_layernorm_param_bwd(const float* dyp, int nsplit, int64_t slab, int64_t lddy, const float* x,
+                               int64_t ldx, const int32_t* row_map, int R, int d, const float* mean,
+                               const float* rstd, GradOut gout_g, GradOut gout_b, hipStream_t s) {
+  if (R <= 0 || d <= 0 || nsplit < 1) return VF_EINVAL;
+  layernorm_param_bwd_kernel<<<(d + CB - 1) / CB, NT, 0, s>>>(dyp, nsplit, slab, lddy, x, ldx, row_map, R, d,
+                                                              mean, rstd, gout_g, gout_b);
+  VF_LAUNCH_CHECK();
+  return VF_OK;
+}
+
+int launch_gelu_fwd(const void* u, void* g, int is_bf16, int64_t n, hipStream_t s) {
+  if (n <= 0) return VF_OK;
+  if (is_bf16) gelu_fwd_kernel<bf16_t><<<blocks_for(n), NT, 0, s>>>(static_cast<const bf16_t*>(u),
+                                                                    static_cast<bf16_t*>(g), n);
+  else         gelu_fwd_kernel<float><<<blocks_for(n), NT, 0, s>>>(static_cast<const float*>(u),
+                                                                   static_cast<float*>(g), n);
+  VF_LAUNCH_CHECK();
+  return VF_OK;
+}
+
+int launch_gelu_bwd(const float* dg, const void* u, void* du, int is_bf16, int64_t n, hipStream_t s) {
+  if (n <= 0) return VF_OK;
+  if (is_bf16) gelu_bwd_kernel<bf16_t><<<blocks_for(n), NT, 0, s>>>(dg, static_cast<const bf16_t*>(u),
+                                                                    static_cast<bf16_t*>(du), n);
+  else         gelu_bwd_kernel<float><<<blocks_for(n), NT, 0, s>>>(dg, static_cast<const float*>(u),
+                                                                   static_cast<float*>(du), n);
+  VF_LAUNCH_CHECK();
+  return VF_OK;
+}
+
+int launch_softmax_rows(const float* S, void* P, int p_is_bf16, int64_t rows, int n, hipStream_t s) {
+  if (rows <= 0 || n <= 0) return VF_EINVAL;
+  int grid = (int)((rows + WAVES - 1) / WAVES);
+  if (p_is_bf16) softmax_rows_kernel<bf16_t><<<grid, NT, 0, s>>>(S, static_cast<bf16_t*>(P), rows, n);
+  else           softmax_rows_kernel<float><<<grid, NT, 0, s>>>(S, static_cast<float*>(P), rows, n);
+  VF_LAUNCH_CHECK();
+  return VF_OK;
+}
+
+int launch_softmax_rows_bwd(float* dP, const void* P, int p_is_bf16, int64_t rows, int n, hipStream_t s) {
+  if (rows <= 0 || n <= 0) return VF_EINVAL;
+  int grid = (int)((rows + WAVES - 1) / WAVES);
+  if (p_is_bf16) softmax_rows_bwd_kernel<bf16_t><<<grid, NT, 0, s>>>(dP, static_cast<const bf16_t*>(P), rows, n);
+  else           softmax_rows_bwd_kernel<float><<<grid, NT, 0, s>>>(dP, static_cast<const float*>(P), rows, n);
+  VF_LAUNCH_CHECK();
+  return VF_OK;
+}
+
+int launch_reduce_slabs(const float* in, int nsplit, int64_t slab, int64_t n, float* out, hipStream_t s) {
+  if (n <= 0) return VF_OK;
+  reduce_slabs_kernel<<<blocks_for(n), NT, 0, s>>>(in, nsplit, slab, n, out);
+  VF_LAUNCH_CHECK();
+  return VF_OK;
+}
+
+}  // namespace vf

@@ -19,9 +19,9 @@ __device__ __forceinline__ float block_reduce(float v, bool is_max, float* red) 
 
 // One workgroup per row.
 template <typename T>
-__global__ __launch_bounds__(256) void softmax_xent_kernel(const float* __restrict__ zp, int nsplit,
+__global__ __launch_bounds__(256) void softmax_xent_kernel(const float* zp, int nsplit,
                                                            int64_t slab, int64_t ldzp,
-                                                           float* __restrict__ z, int64_t ldz,
+                                                           float* z, int64_t ldz,
                                                            const int32_t* __restrict__ labels, int R,
                                                            int C, float* __restrict__ rowloss,
                                                            T* __restrict__ dz, int64_t lddz) {

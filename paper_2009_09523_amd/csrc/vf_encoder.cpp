@@ -1,5 +1,342 @@
-// Placeholder until the encoder launch sequence lands.
+// Pre-LayerNorm transformer encoder with a masked-position cross-entropy head: buffers and the
+// launch sequence of one virtual node (forward, loss, backward), Section 3.2 steps 1-3.
+//
+//   h = tok_emb[ids] + pos_emb;  per layer: h += Wo . attention(LN1(h));  h += W2 . gelu(W1 . LN2(h));
+//   logits = Wout . LNf(h[masked positions]);  L_i = mean cross-entropy over the node's masked rows.
+#include <algorithm>
+#include <cmath>
+
 #include "vf_ctx.h"
+
 namespace vf {
-std::unique_ptr<Model> make_encoder(const vf_config&) { return nullptr; }
+namespace {
+
+inline int64_t round8(int64_t v) { return (v + 7) & ~int64_t(7); }
+
+struct Lin {
+  int K = 0, N = 0;
+  int64_t w_off = -1, b_off = -1;
+  int64_t ldn = 0, ldt = 0;
+  bf16_t* wnat = nullptr;   // bf16 W   [K, ldn]
+  bf16_t* wtr = nullptr;    // bf16 W^T [N, ldt]
+};
+
+struct Block {
+  int64_t ln1_g, ln1_b, ln2_g, ln2_b;
+  Lin qkv, o, w1, w2;
+  float* hin = nullptr;                 // fp32 [R, d] input of the block (residual stream)
+  float *mean1 = nullptr, *rstd1 = nullptr, *mean2 = nullptr, *rstd2 = nullptr;
+  void* a = nullptr;                    // T [R, d]   LN1 output
+  void* qkv_act = nullptr;              // T [R, 3d]
+  void* prob = nullptr;                 // T [b*heads, T, T] attention probabilities
+  void* om = nullptr;                   // T [R, d]   attention output, heads merged
+  float* hmid = nullptr;                // fp32 [R, d] after the attention residual
+  void* f = nullptr;                    // T [R, d]   LN2 output
+  void* u = nullptr;                    // T [R, ffn] FFN pre-activation
+  void* g = nullptr;                    // T [R, ffn] gelu(u)
+};
+
+class Encoder final : public Model {
+ public:
+  explicit Encoder(const vf_config& cfg) : cfg_(cfg) {
+    bf16_ = cfg.dtype == VF_BF16;
+    d_ = cfg.d_model; f_ = cfg.d_ffn; T_ = cfg.seq_len; V_ = cfg.vocab; m_ = cfg.n_masked;
+    nh_ = cfg.n_heads; dh_ = d_ / nh_;
+    int64_t off = 0;
+    tok_off_ = off; off += (int64_t)V_ * d_;
+    pos_off_ = off; off += (int64_t)T_ * d_;
+    blocks_.resize(cfg.n_layers);
+    auto lin = [&](Lin& L, int K, int N) {
+      L.K = K; L.N = N;
+      L.w_off = off; off += (int64_t)K * N;
+      L.b_off = off; off += N;
+      L.ldn = round8(N); L.ldt = round8(K);
+      lins_.push_back(&L);
+    };
+    for (Block& B : blocks_) {
+      B.ln1_g = off; off += d_; B.ln1_b = off; off += d_;
+      lin(B.qkv, d_, 3 * d_);
+      lin(B.o, d_, d_);
+      B.ln2_g = off; off += d_; B.ln2_b = off; off += d_;
+      lin(B.w1, d_, f_);
+      lin(B.w2, f_, d_);
+    }
+    lnf_g_ = off; off += d_; lnf_b_ = off; off += d_;
+    lin(out_, d_, V_);
+    P_ = off;
+    maxR_ = (int64_t)cfg.max_node_size * T_;
+    maxRm_ = (int64_t)cfg.max_node_size * m_;
+    ldR_ = round8(maxR_);
+    ldV_ = round8(V_);
+    out_split_max_ = 32;
+  }
+
+  int64_t num_params() const override { return P_; }
+
+  void request_buffers(Arena& a) override {
+    const size_t esz = bf16_ ? 2 : 4;
+    const size_t R = (size_t)maxR_, Rm = (size_t)maxRm_;
+    const size_t heads = (size_t)cfg_.max_node_size * nh_;
+    auto act = [&](void** p, size_t n) { a.request(reinterpret_cast<char**>(p), n * esz); };
+    for (Block& B : blocks_) {
+      a.request(&B.hin, R * d_);
+      a.request(&B.mean1, R); a.request(&B.rstd1, R); a.request(&B.mean2, R); a.request(&B.rstd2, R);
+      act(&B.a, R * d_); act(&B.qkv_act, R * 3 * d_); act(&B.prob, heads * T_ * T_); act(&B.om, R * d_);
+      a.request(&B.hmid, R * d_);
+      act(&B.f, R * d_); act(&B.u, R * f_); act(&B.g, R * f_);
+    }
+    a.request(&hlast_, R * d_);
+    a.request(&rowidx_, Rm); a.request(&labels_, Rm);
+    a.request(&meanf_, Rm); a.request(&rstdf_, Rm);
+    act(&rows_, Rm * d_);
+    a.request(&logits_, Rm * ldV_);
+    act(&dlogits_, Rm * ldV_);
+    a.request(&scores_, heads * T_ * T_);
+    a.request(&dh_buf_, R * d_);
+    a.request(&dmid_, R * d_);
+    a.request(&tmp32_, R * (size_t)std::max(f_, 3 * d_));
+    act(&du_, R * f_);
+    act(&dqkv_, R * 3 * d_);
+    a.request(&drows_, (size_t)out_split_max_ * Rm * d_);
+    if (bf16_) {
+      act(&cast_, R * d_);
+      const size_t maxdim = (size_t)std::max(std::max(d_, f_), 3 * d_);
+      a.request(&tA_, maxdim * ldR_);
+      a.request(&tB_, std::max(maxdim * (size_t)ldR_, (size_t)V_ * round8(maxRm_)));
+      for (Lin* L : lins_) {
+        a.request(&L->wnat, (size_t)L->K * L->ldn);
+        a.request(&L->wtr, (size_t)L->N * L->ldt);
+      }
+    }
+  }
+
+  int prepare(Ctx& c, const float* params) override {
+    if (!bf16_) return VF_OK;
+    for (Lin* L : lins_)
+      VF_K(c, "cast_weight", launch_cast_weight(params + L->w_off, L->K, L->N, L->wnat, L->ldn, L->wtr,
+                                                L->ldt, c.stream));
+    return VF_OK;
+  }
+
+  int run_node(Ctx& c, const StepArgs& s, int i) override {
+    hipStream_t st = c.stream;
+    const int b = s.sizes[i];
+    const int64_t row0 = s.off[i];
+    const float w = s.w[i];
+    const float* P = s.params;
+    const int R = b * T_, Rm = b * m_;
+    const int nl = (int)blocks_.size();
+    const int heads = b * nh_;
+    const int32_t* ids = static_cast<const int32_t*>(s.x) + row0 * T_;
+    const int32_t* y = s.y + row0 * 2 * m_;
+    const float scale = 1.0f / std::sqrt((float)dh_);
+
+    // ---- forward -----------------------------------------------------------------------
+    VF_K(c, "extract_masked", launch_extract_masked(y, b, m_, T_, V_, rowidx_, labels_, st));
+    VF_K(c, "embed_fwd", launch_embed_fwd(ids, P + tok_off_, P + pos_off_, R, T_, d_, V_, bf16_,
+                                          blocks_[0].hin, st));
+    for (int l = 0; l < nl; ++l) {
+      Block& B = blocks_[l];
+      float* hnext = l + 1 < nl ? blocks_[l + 1].hin : hlast_;
+      VF_K(c, "layernorm_fwd", launch_layernorm_fwd(B.hin, d_, nullptr, R, d_, P + B.ln1_g, P + B.ln1_b, bf16_,
+                                                    cfg_.ln_eps, B.a, d_, bf16_, B.mean1, B.rstd1, st));
+      VF_TRY(lin_fwd(c, "gemm_fwd", B.qkv, P, B.a, d_, R, B.qkv_act, 3 * d_, true, nullptr));
+      VF_K(c, "attn_scores", launch_bgemm(qkv_mat(B.qkv_act, 0), qkv_mat(B.qkv_act, 1), score_mat(scores_, 0, false),
+                                          T_, T_, dh_, heads, nh_, scale, st));
+      VF_K(c, "attn_softmax", launch_softmax_rows(scores_, B.prob, bf16_, (int64_t)heads * T_, T_, st));
+      VF_K(c, "attn_pv", launch_bgemm(score_mat(B.prob, 0, bf16_), vt_mat(B.qkv_act), merged_mat(B.om, bf16_),
+                                      T_, dh_, T_, heads, nh_, 1.0f, st));
+      VF_TRY(lin_fwd(c, "gemm_fwd", B.o, P, B.om, d_, R, B.hmid, d_, false, B.hin));
+      VF_K(c, "layernorm_fwd", launch_layernorm_fwd(B.hmid, d_, nullptr, R, d_, P + B.ln2_g, P + B.ln2_b, bf16_,
+                                                    cfg_.ln_eps, B.f, d_, bf16_, B.mean2, B.rstd2, st));
+      VF_TRY(lin_fwd(c, "gemm_fwd", B.w1, P, B.f, d_, R, B.u, f_, true, nullptr));
+      VF_K(c, "gelu_fwd", launch_gelu_fwd(B.u, B.g, bf16_, (int64_t)R * f_, st));
+      VF_TRY(lin_fwd(c, "gemm_fwd", B.w2, P, B.g, f_, R, hnext, d_, false, B.hmid));
+    }
+    VF_K(c, "layernorm_fwd", launch_layernorm_fwd(hlast_, d_, rowidx_, Rm, d_, P + lnf_g_, P + lnf_b_, bf16_,
+                                                  cfg_.ln_eps, rows_, d_, bf16_, meanf_, rstdf_, st));
+    VF_TRY(lin_fwd(c, "gemm_head", out_, P, rows_, d_, Rm, logits_, ldV_, false, nullptr));
+    VF_K(c, "softmax_xent", launch_softmax_xent(logits_, 1, 0, ldV_, logits_, ldV_, labels_, Rm, V_, c.rowloss,
+                                                dlogits_, ldV_, bf16_, st));
+    VF_K(c, "loss_reduce", launch_loss_reduce(c.rowloss, Rm, w, i, c.node_loss, c.loss_total, st));
+
+    // ---- backward: output head -----------------------------------------------------------
+    VF_K(c, "colsum", launch_colsum(dlogits_, ldV_, bf16_, Rm, V_, c.gout(out_.b_off, w, i), st));
+    VF_TRY(lin_bwd_w(c, "gemm_head_wgrad", out_, rows_, d_, dlogits_, ldV_, Rm, c.gout(out_.w_off, w, i)));
+    int osplit = 1;
+    VF_TRY(lin_bwd_x(c, "gemm_head_dgrad", out_, P, dlogits_, ldV_, Rm, drows_, d_, &osplit));
+    const int64_t oslab = (int64_t)Rm * d_;
+    VF_K(c, "fill", launch_fill_f32(dh_buf_, 0.f, (int64_t)R * d_, st));
+    VF_K(c, "layernorm_param_bwd",
+         launch_layernorm_param_bwd(drows_, osplit, oslab, d_, hlast_, d_, rowidx_, Rm, d_, meanf_, rstdf_,
+                                    c.gout(lnf_g_, w, i), c.gout(lnf_b_, w, i), st));
+    VF_K(c, "layernorm_bwd", launch_layernorm_bwd(drows_, osplit, oslab, d_, hlast_, d_, rowidx_, Rm, d_,
+                                                  P + lnf_g_, bf16_, meanf_, rstdf_, nullptr, dh_buf_, d_, st));
+
+    // ---- backward: blocks -------------------------------------------------------------------
+    for (int l = nl - 1; l >= 0; --l) {
+      Block& B = blocks_[l];
+      // FFN
+      const void* dh_op = dh_buf_;
+      if (bf16_) {
+        VF_K(c, "cast", launch_cast_bf16(dh_buf_, d_, static_cast<bf16_t*>(cast_), d_, R, d_, st));
+        dh_op = cast_;
+      }
+      VF_K(c, "colsum", launch_colsum(dh_buf_, d_, 0, R, d_, c.gout(B.w2.b_off, w, i), st));
+      VF_TRY(lin_bwd_w(c, "gemm_wgrad", B.w2, B.g, f_, dh_op, d_, R, c.gout(B.w2.w_off, w, i)));
+      VF_TRY(lin_bwd_x(c, "gemm_dgrad", B.w2, P, dh_op, d_, R, tmp32_, f_, nullptr));
+      VF_K(c, "gelu_bwd", launch_gelu_bwd(tmp32_, B.u, du_, bf16_, (int64_t)R * f_, st));
+      VF_K(c, "colsum", launch_colsum(du_, f_, bf16_, R, f_, c.gout(B.w1.b_off, w, i), st));
+      VF_TRY(lin_bwd_w(c, "gemm_wgrad", B.w1, B.f, d_, du_, f_, R, c.gout(B.w1.w_off, w, i)));
+      VF_TRY(lin_bwd_x(c, "gemm_dgrad", B.w1, P, du_, f_, R, tmp32_, d_, nullptr));
+      VF_K(c, "layernorm_param_bwd",
+           launch_layernorm_param_bwd(tmp32_, 1, 0, d_, B.hmid, d_, nullptr, R, d_, B.mean2, B.rstd2,
+                                      c.gout(B.ln2_g, w, i), c.gout(B.ln2_b, w, i), st));
+      VF_K(c, "layernorm_bwd", launch_layernorm_bwd(tmp32_, 1, 0, d_, B.hmid, d_, nullptr, R, d_, P + B.ln2_g,
+                                                    bf16_, B.mean2, B.rstd2, dh_buf_, dmid_, d_, st));
+      // attention
+      const void* dmid_op = dmid_;
+      if (bf16_) {
+        VF_K(c, "cast", launch_cast_bf16(dmid_, d_, static_cast<bf16_t*>(cast_), d_, R, d_, st));
+        dmid_op = cast_;
+      }
+      VF_K(c, "colsum", launch_colsum(dmid_, d_, 0, R, d_, c.gout(B.o.b_off, w, i), st));
+      VF_TRY(lin_bwd_w(c, "gemm_wgrad", B.o, B.om, d_, dmid_op, d_, R, c.gout(B.o.w_off, w, i)));
+      VF_TRY(lin_bwd_x(c, "gemm_dgrad", B.o, P, dmid_op, d_, R, tmp32_, d_, nullptr));   // d(om), fp32
+      // dP = dO V^T ; dV = P^T dO ; dS = P (dP - rowsum(dP P)) ; dQ = dS K / sqrt(dh) ; dK = dS^T Q / sqrt(dh)
+      VF_K(c, "attn_bwd_dp", launch_bgemm(merged_mat(tmp32_, false, true), qkv_mat(B.qkv_act, 2), score_mat(scores_, 0, false),
+                                          T_, T_, dh_, heads, nh_, 1.0f, st));
+      VF_K(c, "attn_bwd_dv", launch_bgemm(score_mat(B.prob, 1, bf16_), merged_t_mat(tmp32_), qkv_mat(dqkv_, 2),
+                                          T_, dh_, T_, heads, nh_, 1.0f, st));
+      VF_K(c, "attn_softmax_bwd", launch_softmax_rows_bwd(scores_, B.prob, bf16_, (int64_t)heads * T_, T_, st));
+      VF_K(c, "attn_bwd_dq", launch_bgemm(score_mat(scores_, 0, false, true), kt_mat(B.qkv_act, 1), qkv_mat(dqkv_, 0),
+                                          T_, dh_, T_, heads, nh_, scale, st));
+      VF_K(c, "attn_bwd_dk", launch_bgemm(score_mat(scores_, 1, false, true), kt_mat(B.qkv_act, 0), qkv_mat(dqkv_, 1),
+                                          T_, dh_, T_, heads, nh_, scale, st));
+      VF_K(c, "colsum", launch_colsum(dqkv_, 3 * d_, bf16_, R, 3 * d_, c.gout(B.qkv.b_off, w, i), st));
+      VF_TRY(lin_bwd_w(c, "gemm_wgrad", B.qkv, B.a, d_, dqkv_, 3 * d_, R, c.gout(B.qkv.w_off, w, i)));
+      VF_TRY(lin_bwd_x(c, "gemm_dgrad", B.qkv, P, dqkv_, 3 * d_, R, tmp32_, d_, nullptr));
+      VF_K(c, "layernorm_param_bwd",
+           launch_layernorm_param_bwd(tmp32_, 1, 0, d_, B.hin, d_, nullptr, R, d_, B.mean1, B.rstd1,
+                                      c.gout(B.ln1_g, w, i), c.gout(B.ln1_b, w, i), st));
+      VF_K(c, "layernorm_bwd", launch_layernorm_bwd(tmp32_, 1, 0, d_, B.hin, d_, nullptr, R, d_, P + B.ln1_g,
+                                                    bf16_, B.mean1, B.rstd1, dmid_, dh_buf_, d_, st));
+    }
+    // ---- backward: embeddings ----------------------------------------------------------------
+    VF_K(c, "embed_bwd", launch_embed_pos_bwd(dh_buf_, b, T_, d_, c.gout(pos_off_, w, i), st));
+    GradOut gt = c.gout(tok_off_, w, i);
+    if (!c.fused || i == 0) VF_K(c, "fill", launch_fill_f32(gt.dst, 0.f, (int64_t)V_ * d_, st));
+    VF_K(c, "embed_bwd", launch_embed_tok_bwd(ids, dh_buf_, R, d_, V_, gt, st));
+    return VF_OK;
+  }
+
+ private:
+  // ---- operand views for the batched attention products (batch = sequence * heads + head) ------
+  const void* at(const void* p, int64_t elems, bool is16) const {
+    return static_cast<const char*>(p) + elems * (is16 ? 2 : 4);
+  }
+  // [t, e] window of Q (which=0), K (1) or V (2) inside qkv [R, 3d]
+  BMat qkv_mat(const void* qkv, int which) const {
+    return BMat{at(qkv, (int64_t)which * d_, bf16_), bf16_, (int64_t)T_ * 3 * d_, dh_, 3 * (int64_t)d_, 1};
+  }
+  // the same window read as [e, t] (rows = feature, contraction = token)
+  BMat kt_mat(const void* qkv, int which) const {
+    return BMat{at(qkv, (int64_t)which * d_, bf16_), bf16_, (int64_t)T_ * 3 * d_, dh_, 1, 3 * (int64_t)d_};
+  }
+  BMat vt_mat(const void* qkv) const { return kt_mat(qkv, 2); }
+  // [q, j] scores / probabilities; transposed = 1 reads them as [j, q]
+  BMat score_mat(const void* p, int transposed, bool is16, bool round_operand = false) const {
+    const int64_t TT = (int64_t)T_ * T_;
+    return BMat{p, is16, nh_ * TT, TT, transposed ? 1 : (int64_t)T_, transposed ? (int64_t)T_ : 1,
+                round_operand && bf16_};
+  }
+  // [t, e] window of one head inside a [R, d] tensor
+  BMat merged_mat(const void* p, bool is16, bool round_operand = false) const {
+    return BMat{p, is16, (int64_t)T_ * d_, dh_, d_, 1, round_operand && bf16_};
+  }
+  // fp32 [R, d] tensor read as [e, t]; values enter the product as bf16 in bf16 workloads
+  BMat merged_t_mat(const void* p) const { return BMat{p, 0, (int64_t)T_ * d_, dh_, 1, d_, bf16_}; }
+
+  // out[R, N] = in[R, K] W + bias (+ residual); out is T (out_act) or fp32
+  int lin_fwd(Ctx& c, const char* tag, const Lin& L, const float* P, const void* in, int64_t ldin, int R,
+              void* out, int64_t ldo, bool out_act, const float* residual) {
+    Epilogue ep;
+    ep.C = out; ep.ldc = ldo;
+    ep.c_is_bf16 = out_act && bf16_;
+    ep.bias = P + L.b_off; ep.bias_round_bf16 = bf16_;
+    if (residual) { ep.R = residual; ep.ldr = ldo; ep.beta = 1.f; }
+    if (bf16_)
+      VF_K(c, tag, launch_gemm_bf16(static_cast<const bf16_t*>(in), ldin, L.wtr, L.ldt, R, L.N, L.K, 1, 0, ep,
+                                    c.stream));
+    else
+      VF_K(c, tag, launch_gemm_f32(static_cast<const float*>(in), ldin, 1, P + L.w_off, 1, L.N, R, L.N, L.K, ep,
+                                   c.stream));
+    return VF_OK;
+  }
+
+  // dW[K, N] = in^T dy through GradOut
+  int lin_bwd_w(Ctx& c, const char* tag, const Lin& L, const void* in, int64_t ldin, const void* dy,
+                int64_t lddy, int R, GradOut go) {
+    Epilogue ep;
+    ep.C = go.dst; ep.ldc = L.N; ep.alpha = go.alpha;
+    if (go.accumulate) { ep.R = go.dst; ep.ldr = L.N; ep.beta = 1.f; }
+    if (bf16_) {
+      const int64_t ldr = round8(R);
+      VF_K(c, "transpose", launch_transpose_bf16(static_cast<const bf16_t*>(in), ldin, tA_, ldr, R, L.K, c.stream));
+      VF_K(c, "transpose", launch_transpose_bf16(static_cast<const bf16_t*>(dy), lddy, tB_, ldr, R, L.N, c.stream));
+      VF_K(c, tag, launch_gemm_bf16(tA_, ldr, tB_, ldr, L.K, L.N, R, 1, 0, ep, c.stream));
+    } else {
+      VF_K(c, tag, launch_gemm_f32(static_cast<const float*>(in), 1, ldin, static_cast<const float*>(dy), 1, lddy,
+                                   L.K, L.N, R, ep, c.stream));
+    }
+    return VF_OK;
+  }
+
+  // dx[R, K] (fp32) = dy W^T.  With `split` the product may arrive as partial slabs.
+  int lin_bwd_x(Ctx& c, const char* tag, const Lin& L, const float* P, const void* dy, int64_t lddy, int R,
+                float* dx, int64_t lddx, int* split) {
+    Epilogue ep;
+    ep.C = dx; ep.ldc = lddx;
+    int ns = 1;
+    if (bf16_) {
+      if (split) {
+        ns = std::min(gemm_bf16_pick_split(R, L.K, L.N), out_split_max_);
+        *split = ns;
+      }
+      VF_K(c, tag, launch_gemm_bf16(static_cast<const bf16_t*>(dy), lddy, L.wnat, L.ldn, R, L.K, L.N, ns,
+                                    (int64_t)R * lddx, ep, c.stream));
+    } else {
+      if (split) *split = 1;
+      VF_K(c, tag, launch_gemm_f32(static_cast<const float*>(dy), lddy, 1, P + L.w_off, L.N, 1, R, L.K, L.N, ep,
+                                   c.stream));
+    }
+    return VF_OK;
+  }
+
+  vf_config cfg_;
+  bool bf16_ = false;
+  int d_ = 0, f_ = 0, T_ = 0, V_ = 0, m_ = 0, nh_ = 0, dh_ = 0;
+  int64_t P_ = 0, tok_off_ = 0, pos_off_ = 0, lnf_g_ = 0, lnf_b_ = 0;
+  int64_t maxR_ = 0, maxRm_ = 0, ldR_ = 0, ldV_ = 0;
+  int out_split_max_ = 32;
+  std::vector<Block> blocks_;
+  std::vector<Lin*> lins_;
+  Lin out_;
+  float* hlast_ = nullptr;
+  int32_t *rowidx_ = nullptr, *labels_ = nullptr;
+  float *meanf_ = nullptr, *rstdf_ = nullptr;
+  void* rows_ = nullptr;
+  float* logits_ = nullptr;
+  void* dlogits_ = nullptr;
+  float* scores_ = nullptr;
+  float *dh_buf_ = nullptr, *dmid_ = nullptr, *tmp32_ = nullptr;
+  void *du_ = nullptr, *dqkv_ = nullptr, *cast_ = nullptr;
+  float* drows_ = nullptr;
+  bf16_t *tA_ = nullptr, *tB_ = nullptr;
+};
+
+}  // namespace
+
+std::unique_ptr<Model> make_encoder(const vf_config& cfg) { return std::unique_ptr<Model>(new Encoder(cfg)); }
+
 }  // namespace vf

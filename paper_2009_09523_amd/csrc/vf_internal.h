@@ -132,4 +132,52 @@ int launch_softmax_xent(const float* zp, int nsplit, int64_t slab, int64_t ldzp,
 int launch_loss_reduce(const float* rowloss, int R, float w, int node, float* node_loss,
                        float* total, hipStream_t s);
 
+// k_bgemm.hip -- batched strided GEMM for the attention contractions.
+// Element [b][i,k] of an operand lives at p + (b / inner)*outer + (b % inner)*inner + i*rs + k*cs.
+struct BMat {
+  const void* p;
+  int is_bf16;
+  int64_t outer, inner, rs, cs;
+  int round_bf16 = 0;   // fp32 storage, but values enter the product rounded to bf16
+};
+// C[b][m,n] = alpha * sum_k A[b][m,k] * B[b][n,k], b < batch (<= 65535)
+int launch_bgemm(const BMat& A, const BMat& B, const BMat& C, int M, int N, int K, int batch, int inner,
+                 float alpha, hipStream_t s);
+
+// k_encoder.hip -- element-wise and row-wise kernels of the encoder
+// h[r,:] = tok[ids[r]] + pos[r % T]   (table values rounded to bf16 when round_params)
+int launch_embed_fwd(const int32_t* ids, const float* tok, const float* pos, int R, int T, int d,
+                     int vocab, int round_params, float* h, hipStream_t s);
+// pos table gradient: gpos[t,:] = sum over sequences of dh[seq*T + t, :]
+int launch_embed_pos_bwd(const float* dh, int nseq, int T, int d, GradOut out, hipStream_t s);
+// token table gradient: row ids[r] += dh[r,:], duplicates added in increasing r (deterministic)
+int launch_embed_tok_bwd(const int32_t* ids, const float* dh, int R, int d, int vocab, GradOut out,
+                         hipStream_t s);
+// rowidx[s*m + j] = s*T + pos(s,j);  labels[s*m + j] = target(s,j)   from y [nseq, 2, m]
+int launch_extract_masked(const int32_t* y, int nseq, int m, int T, int vocab, int32_t* rowidx,
+                          int32_t* labels, hipStream_t s);
+// LayerNorm over the last axis.  x row for output row r is x[row_map ? row_map[r] : r].
+int launch_layernorm_fwd(const float* x, int64_t ldx, const int32_t* row_map, int R, int d,
+                         const float* gamma, const float* beta, int round_params, float eps, void* y,
+                         int64_t ldy, int y_is_bf16, float* mean, float* rstd, hipStream_t s);
+// dx[orow] = LNbwd(sum of dy slabs)[r] (+ dres[orow]),  orow = row_map ? row_map[r] : r
+int launch_layernorm_bwd(const float* dyp, int nsplit, int64_t slab, int64_t lddy, const float* x,
+                         int64_t ldx, const int32_t* row_map, int R, int d, const float* gamma,
+                         int round_params, const float* mean, const float* rstd, const float* dres,
+                         float* dx, int64_t lddx, hipStream_t s);
+// dgamma[c] = sum_r dy[r,c]*xhat[r,c];  dbeta[c] = sum_r dy[r,c]
+int launch_layernorm_param_bwd(const float* dyp, int nsplit, int64_t slab, int64_t lddy, const float* x,
+                               int64_t ldx, const int32_t* row_map, int R, int d, const float* mean,
+                               const float* rstd, GradOut gout_g, GradOut gout_b, hipStream_t s);
+// exact GELU: g = 0.5 u (1 + erf(u / sqrt 2))
+int launch_gelu_fwd(const void* u, void* g, int is_bf16, int64_t n, hipStream_t s);
+// du = dg * (Phi(u) + u phi(u));  dg fp32, u and du T
+int launch_gelu_bwd(const float* dg, const void* u, void* du, int is_bf16, int64_t n, hipStream_t s);
+// row softmax in place over fp32 S [rows, n] -> P written as T to p (and nothing else)
+int launch_softmax_rows(const float* S, void* P, int p_is_bf16, int64_t rows, int n, hipStream_t s);
+// dS = P * (dP - sum_j dP*P) in place over dP (fp32); P is T
+int launch_softmax_rows_bwd(float* dP, const void* P, int p_is_bf16, int64_t rows, int n, hipStream_t s);
+// out[r,c] = sum of slabs
+int launch_reduce_slabs(const float* in, int nsplit, int64_t slab, int64_t n, float* out, hipStream_t s);
+
 }  // namespace vf
