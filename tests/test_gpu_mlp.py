@@ -123,3 +123,39 @@ def test_full_size_configurations(name, flags):
     import paper_2009_09523_amd as vf
     off2, w2 = vf.vf_partition(wl.node_sizes, wl.batch)
     assert off.tobytes() == off2.tobytes() and w.tobytes() == w2.tobytes()
+
+
+def test_c5_full_size_launch_configuration():
+    """Large-batch emulation: MLP 2048-8192x6-1000 + BatchNorm, 64 nodes of 128 (B = 8192).
+    The oracle can afford single nodes of this model, so: (a) the step is run in the launch
+    configuration bench.py times (V = 64) on a batch whose 64 nodes all hold the rows of
+    node 0 -- the combined gradient must then equal the oracle's g_0, and the update the
+    oracle's update with it; (b) two different nodes (V = 2) against (g_0 + g_1)/2."""
+    print("full size C5", flush=True)
+    wl = I.workload("C5")
+    theta = I.make_params(wl)
+    x, y = I.make_batch(wl)
+    from oracle.step import compute_copy
+    cp = compute_copy(wl, theta)
+    L0, g0 = O.node_loss_and_grads(wl, cp, x[:128], y[:128])
+    print("oracle node 0 done", flush=True)
+    L1, g1 = O.node_loss_and_grads(wl, cp, x[128:256], y[128:256])
+    print("oracle node 1 done", flush=True)
+    del cp
+    from vfharness import assert_close_per_tensor
+    tol = TOL["bf16"]
+    # (a)
+    xa, ya = np.tile(x[:128], (64, 1)), np.tile(y[:128], 64)
+    gpu = run_gpu(wl, theta, xa, ya)
+    assert abs(gpu["loss"] - L0) <= tol * abs(L0)
+    np.testing.assert_allclose(gpu["node_losses"], np.full(64, L0), rtol=tol)
+    assert_close_per_tensor(wl, gpu["G"], g0, tol, "G (64 equal nodes)", ambiguous=True)
+    check_update_from_own_gradient(wl, gpu, theta)
+    th_new, v_new = O.sgdm_update(theta.astype(np.float64), g0, np.zeros(g0.size), wl.lr, wl.momentum)
+    assert_close_per_tensor(wl, gpu["theta"], th_new, tol, "theta", ambiguous=True)
+    del gpu, xa, ya
+    # (b)
+    w2 = wl.with_nodes([128, 128])
+    gpu = run_gpu(w2, theta, x[:256], y[:256])
+    assert abs(gpu["loss"] - 0.5 * (L0 + L1)) <= tol * abs(L0)
+    assert_close_per_tensor(wl, gpu["G"], 0.5 * (g0 + g1), tol, "G (two nodes)", ambiguous=True)
