@@ -42,6 +42,23 @@ def algorithmic_work(wl, P):
         work["gemm_dgrad"] = (V * sum(k * n for k, n in mats[1:]) * esz + act, dgr_fl, V * (len(mats) - 1))
         work["gemm_wgrad"] = (V * W * 4 + act, fwd_fl, V * len(mats))
         work["cast_weight"] = (W * (4 + 2 * esz), 0, len(mats))
+    else:
+        d, f, T, Vc, m, nl = wl.d_model, wl.d_ffn, wl.seq_len, wl.vocab, wl.n_masked, wl.n_layers
+        R, Rm = B * T, B * m                       # tokens and masked rows per step
+        Wl = 4 * d * d + 2 * d * f                 # matrix entries of one block
+        lin_fl = 2 * R * Wl * nl                   # one pass over the four Linears of all blocks
+        act_f = nl * R * (2 * d + 3 * d + d + f + f + d) * esz   # operands read / written once
+        work["gemm_fwd"] = (V * nl * Wl * esz + act_f, lin_fl, V * nl * 4)
+        work["gemm_dgrad"] = (V * nl * Wl * esz + act_f, lin_fl, V * nl * 4)
+        work["gemm_wgrad"] = (V * nl * Wl * 4 + act_f, lin_fl, V * nl * 4)
+        head_fl = 2 * Rm * d * Vc
+        work["gemm_head"] = (V * d * Vc * esz + Rm * Vc * 4, head_fl, V)
+        work["gemm_head_dgrad"] = (V * d * Vc * esz + Rm * Vc * esz, head_fl, V)
+        work["gemm_head_wgrad"] = (V * d * Vc * 4 + Rm * Vc * esz, head_fl, V)
+        att = 2 * T * T * d * B * nl               # one [T,T,d_head] product over all heads, all blocks
+        for tag in ("attn_scores", "attn_pv", "attn_bwd_dp", "attn_bwd_dv", "attn_bwd_dq", "attn_bwd_dk"):
+            work[tag] = (nl * (3 * R * d * esz + B * wl.n_heads * T * T * 4), att, V * nl)
+        work["cast_weight"] = ((nl * Wl + d * Vc) * (4 + 2 * esz), 0, 4 * nl + 1)
     return work
 
 
@@ -50,6 +67,12 @@ def roofline_for(tag, work, avg_ms):
     b_per, f_per = bytes_ / launches, flops / launches
     t_hbm = b_per / (HBM_PEAK_GBS * 1e9)
     t_mfma = f_per / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+    if tag.startswith("attn_"):
+        # these products run on the fp32 vector ALUs (no matrix-core version yet)
+        ach = f_per / (avg_ms * 1e-3) / 1e12
+        return {"kernel": tag, "bound": "alu", "achieved": ach, "peak": FP32_VECTOR_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": ach / FP32_VECTOR_PEAK_TFLOPS, "traffic": None,
+                "avg_launch_ms": avg_ms, "algorithmic_flops_per_launch": f_per}
     if t_hbm >= t_mfma:
         ach = b_per / (avg_ms * 1e-3) / 1e9
         return {"kernel": tag, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -149,7 +172,12 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if wl.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": wl.name, "model": wl.kind, "dims": list(wl.dims) if wl.kind == "mlp" else None,
-                   "batchnorm": bool(wl.batchnorm), "global_batch": wl.batch, "virtual_nodes": wl.n_nodes,
+                   "batchnorm": bool(wl.batchnorm),
+                   "encoder": None if wl.kind == "mlp" else {"layers": wl.n_layers, "d_model": wl.d_model,
+                                                             "heads": wl.n_heads, "d_ffn": wl.d_ffn,
+                                                             "seq_len": wl.seq_len, "vocab": wl.vocab,
+                                                             "masked_per_seq": wl.n_masked},
+                   "global_batch": wl.batch, "virtual_nodes": wl.n_nodes,
                    "node_sizes": sizes if len(set(sizes)) > 1 else f"{wl.n_nodes}x{sizes[0]}",
                    "optimizer": wl.optimizer, "params": P, "accumulate": args.accumulate,
                    "graph": not args.no_graph},
@@ -158,7 +186,7 @@ def main():
 
     work = algorithmic_work(wl, P)
     total_bytes = sum(v[0] for v in work.values())
-    total_flops = sum(v[1] for k, v in work.items() if k.startswith("gemm"))
+    total_flops = sum(v[1] for k, v in work.items() if k.startswith(("gemm", "attn")))
     floor_ms = max(total_bytes / (HBM_PEAK_GBS * 1e9), total_flops / (MFMA_BF16_PEAK_TFLOPS * 1e12)) * 1e3
     out["step_floor"] = {"algorithmic_bytes": total_bytes, "gemm_flops": total_flops, "floor_ms": floor_ms,
                          "frac": floor_ms / ms_per_step,

@@ -71,14 +71,14 @@ def _operand(wl):
     return lambda a: a
 
 
-def _mlp_node(wl, p, x, y):
+def _mlp_node(wl, p, x, y, accum32=False):
     q = _operand(wl)
     n_lin = len(wl.dims) - 1
     h = np.asarray(x, dtype=np.float64)
     saved = []
     margin = np.inf
     for l in range(n_lin - 1):
-        z = L.linear_fwd(h, p[f"l{l}.W"], None if wl.batchnorm else p[f"l{l}.b"])
+        z = L.linear_fwd(h, p[f"l{l}.W"], None if wl.batchnorm else p[f"l{l}.b"], accum32)
         if wl.batchnorm:
             pre, bn_cache = L.batchnorm_fwd(z, p[f"l{l}.gamma"], p[f"l{l}.beta"], wl.bn_eps)
         else:
@@ -189,13 +189,15 @@ def _encoder_node(wl, p, ids, y):
     return loss, g, np.inf
 
 
-def node_loss_and_grads(wl, compute_params, x_node, y_node, diag=None):
+def node_loss_and_grads(wl, compute_params, x_node, y_node, diag=None, accum32=False):
     """(L_i, flat g_i) for one node given float64 compute parameters (flat).  `diag`, if a
     dict, receives 'relu_margin': the smallest |ReLU input| of the node relative to its
-    layer's rms (inf for models without ReLU)."""
+    layer's rms (inf for models without ReLU).  accum32 (MLP only): the hidden layers'
+    forward products are carried out in float32 -- a second valid evaluation that parity
+    tests of deep bf16 networks use to calibrate their tolerance, never as the reference."""
     p = unflatten(wl, compute_params)
     if wl.kind == "mlp":
-        loss, g, margin = _mlp_node(wl, p, x_node, y_node)
+        loss, g, margin = _mlp_node(wl, p, x_node, y_node, accum32)
     else:
         loss, g, margin = _encoder_node(wl, p, x_node, y_node)
     if diag is not None:

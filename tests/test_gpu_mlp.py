@@ -125,37 +125,69 @@ def test_full_size_configurations(name, flags):
     assert off.tobytes() == off2.tobytes() and w.tobytes() == w2.tobytes()
 
 
+def _calibrated_bounds(wl, ref, alt, tol):
+    """Per tensor: max(tol, 2 x the distance between two valid CPU evaluations)."""
+    from vfharness import tensor_errors
+    return {n: max(tol, 2.0 * r) for n, r, _ in tensor_errors(wl, alt, ref)}
+
+
 def test_c5_full_size_launch_configuration():
     """Large-batch emulation: MLP 2048-8192x6-1000 + BatchNorm, 64 nodes of 128 (B = 8192).
     The oracle can afford single nodes of this model, so: (a) the step is run in the launch
     configuration bench.py times (V = 64) on a batch whose 64 nodes all hold the rows of
     node 0 -- the combined gradient must then equal the oracle's g_0, and the update the
-    oracle's update with it; (b) two different nodes (V = 2) against (g_0 + g_1)/2."""
+    oracle's update with it; (b) two different nodes (V = 2) against (g_0 + g_1)/2.
+
+    Tolerance.  Six BatchNorm+ReLU layers with bf16 activations are sensitive to rounding:
+    a perturbation delta of a pre-activation changes about delta/ulp of the bf16 roundings
+    of the layer's output, i.e. it leaves the layer with size sqrt(delta*ulp), so ANY two
+    correct evaluations (different summation order is enough) drift apart layer by layer
+    until they differ at the bf16 ulp level (measured: 0.1 % of the gradient norm at depth
+    2, 1 % at depth 3, 2.6 % at depth 4, 6 % at depth 6, independent of width).  The bound is
+    therefore calibrated by the oracle itself: per tensor, the device may be no further from
+    the float64 oracle than twice the distance of a second CPU evaluation whose forward
+    products accumulate in float32 (and never less strict than needed: at least 2e-2).  The
+    loss and the last layer, which no rounding decision upstream dominates, keep 2e-2."""
     print("full size C5", flush=True)
+    from vfharness import tensor_errors
     wl = I.workload("C5")
     theta = I.make_params(wl)
     x, y = I.make_batch(wl)
     from oracle.step import compute_copy
     cp = compute_copy(wl, theta)
     L0, g0 = O.node_loss_and_grads(wl, cp, x[:128], y[:128])
+    _, g0_alt = O.node_loss_and_grads(wl, cp, x[:128], y[:128], accum32=True)
     print("oracle node 0 done", flush=True)
     L1, g1 = O.node_loss_and_grads(wl, cp, x[128:256], y[128:256])
     print("oracle node 1 done", flush=True)
     del cp
-    from vfharness import assert_close_per_tensor
     tol = TOL["bf16"]
+    bounds = _calibrated_bounds(wl, g0, g0_alt, tol)
+    print("calibrated bounds", {k: round(v, 4) for k, v in bounds.items() if k.endswith("W")}, flush=True)
+    assert bounds["l6.W"] == tol and bounds["l6.b"] == tol
+
+    def check(G, want, what):
+        errs = tensor_errors(wl, G, want)
+        print(what, {n: round(r, 4) for n, r, _ in errs if n.endswith("W")}, flush=True)
+        bad = [(n, r, bounds[n]) for n, r, _ in errs if r > bounds[n]]
+        assert not bad, f"{what}: {bad}"
+        assert max(r for _, r, _ in errs) < 0.15
+
     # (a)
     xa, ya = np.tile(x[:128], (64, 1)), np.tile(y[:128], 64)
     gpu = run_gpu(wl, theta, xa, ya)
-    assert abs(gpu["loss"] - L0) <= tol * abs(L0)
-    np.testing.assert_allclose(gpu["node_losses"], np.full(64, L0), rtol=tol)
-    assert_close_per_tensor(wl, gpu["G"], g0, tol, "G (64 equal nodes)", ambiguous=True)
+    assert abs(gpu["loss"] - L0) <= 1e-3 * abs(L0)
+    np.testing.assert_allclose(gpu["node_losses"], np.full(64, L0), rtol=1e-3)
+    check(gpu["G"], g0, "G (64 equal nodes)")
     check_update_from_own_gradient(wl, gpu, theta)
-    th_new, v_new = O.sgdm_update(theta.astype(np.float64), g0, np.zeros(g0.size), wl.lr, wl.momentum)
-    assert_close_per_tensor(wl, gpu["theta"], th_new, tol, "theta", ambiguous=True)
+    G64 = gpu["G"].copy()
     del gpu, xa, ya
+    # the same node once: 64 folds of g/64 must reproduce one fold of g (fp32 rounding only)
+    one = run_gpu(wl.with_nodes([128]), theta, x[:128], y[:128])
+    assert np.linalg.norm(G64 - one["G"]) <= 1e-6 * np.linalg.norm(one["G"])
+    del one, G64
     # (b)
     w2 = wl.with_nodes([128, 128])
     gpu = run_gpu(w2, theta, x[:256], y[:256])
-    assert abs(gpu["loss"] - 0.5 * (L0 + L1)) <= tol * abs(L0)
-    assert_close_per_tensor(wl, gpu["G"], 0.5 * (g0 + g1), tol, "G (two nodes)", ambiguous=True)
+    assert abs(gpu["loss"] - 0.5 * (L0 + L1)) <= 1e-3 * abs(L0)
+    check(gpu["G"], 0.5 * (g0 + g1), "G (two nodes)")
