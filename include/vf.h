@@ -66,6 +66,10 @@ extern "C" {
                                         element (one fused multiply-add), same node order */
 #define VF_FLAG_NO_GRAPH         2u  /* launch kernels one by one instead of replaying a
                                         captured HIP graph */
+#define VF_FLAG_NO_OVERLAP       4u  /* keep every kernel of a step on the one stream given in
+                                        the configuration (by default weight gradients and the
+                                        fold into the gradient buffer run on a second,
+                                        library-owned stream beside the input-gradient chain) */
 
 typedef struct vf_ctx vf_ctx;
 

@@ -149,6 +149,113 @@ __global__ __launch_bounds__(NT) void gemm_bf16_kernel(const bf16_t* __restrict_
   }
 }
 
+// Short contraction (K <= 2*BK = 128: the weight gradient of a node of up to 128 rows).  The
+// cost of such a product is one trip to memory for the operands and the write (or
+// read-modify-write) of the output, so everything is issued at once: both stages of operand
+// loads and, when the epilogue adds into C (fused fold into the gradient buffer), the old C
+// values as well; then one LDS barrier, the MFMAs, and the stores.
+template <int BM, int BN, int WGM, int WGN>
+__global__ __launch_bounds__(NT) void gemm_bf16_shortk_kernel(const bf16_t* __restrict__ A, int64_t lda,
+                                                              const bf16_t* __restrict__ B, int64_t ldb,
+                                                              int M, int N, int K, Epilogue ep) {
+  static_assert(WGM * WGN == 4, "four waves");
+  constexpr int WTM = BM / WGM, WTN = BN / WGN;
+  constexpr int TM = WTM / 32, TN = WTN / 32;
+  constexpr int KT = 2 * BK;                  // 128
+  constexpr int LD2 = KT + 8;                 // padded LDS row
+  constexpr int A_VECS = BM * (KT / 8) / NT;  // 16-byte vectors per thread
+  constexpr int B_VECS = BN * (KT / 8) / NT;
+
+  __shared__ __attribute__((aligned(16))) bf16_t As[BM * LD2];
+  __shared__ __attribute__((aligned(16))) bf16_t Bs[BN * LD2];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WGN, wn = wave % WGN;
+  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  const int vcol = (tid & 15) * 8;   // 16 vectors per 128-wide row
+  const int vrow = tid >> 4;         // 0..15
+
+  u32x4 ra[A_VECS], rb[B_VECS];
+#pragma unroll
+  for (int i = 0; i < A_VECS; ++i) ra[i] = load_vec(A, lda, m0 + vrow + 16 * i, M, vcol, K);
+#pragma unroll
+  for (int i = 0; i < B_VECS; ++i) rb[i] = load_vec(B, ldb, n0 + vrow + 16 * i, N, vcol, K);
+
+  // old C values for a read-modify-write epilogue, requested before anything waits
+  float oldc[TM][TN][16];
+  if (ep.R) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int n = n0 + wn * WTN + j * 32 + (lane & 31);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int m = m0 + wm * WTM + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+          oldc[i][j][r] = (m < M && n < N) ? ep.R[(int64_t)m * ep.ldr + n] : 0.f;
+        }
+      }
+  }
+
+#pragma unroll
+  for (int i = 0; i < A_VECS; ++i) *reinterpret_cast<u32x4*>(&As[(vrow + 16 * i) * LD2 + vcol]) = ra[i];
+#pragma unroll
+  for (int i = 0; i < B_VECS; ++i) *reinterpret_cast<u32x4*>(&Bs[(vrow + 16 * i) * LD2 + vcol]) = rb[i];
+  __syncthreads();
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  const int ksteps = (K + 15) / 16;            // 16-wide MFMA steps that hold any data
+#pragma unroll
+  for (int ks = 0; ks < KT / 16; ++ks) {
+    if (ks < ksteps) {
+      bf16x8 a[TM], b[TN];
+      const int koff = ks * 16 + (lane >> 5) * 8;
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+        a[i] = *reinterpret_cast<const bf16x8*>(&As[(wm * WTM + i * 32 + (lane & 31)) * LD2 + koff]);
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        b[j] = *reinterpret_cast<const bf16x8*>(&Bs[(wn * WTN + j * 32 + (lane & 31)) * LD2 + koff]);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+  }
+
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int n = n0 + wn * WTN + j * 32 + (lane & 31);
+      if (n >= N) continue;
+      float bias = 0.f;
+      if (ep.bias) {
+        bias = ep.bias[n];
+        if (ep.bias_round_bf16) bias = round_bf16(bias);
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = m0 + wm * WTM + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        if (m >= M) continue;
+        float addend = bias;
+        if (ep.R) addend = fmaf(ep.beta, oldc[i][j][r], bias);
+        float v = fmaf(ep.alpha, acc[i][j][r], addend);
+        if (ep.c_is_bf16) static_cast<bf16_t*>(ep.C)[(int64_t)m * ep.ldc + n] = f32_to_bf16(v);
+        else              static_cast<float*>(ep.C)[(int64_t)m * ep.ldc + n] = v;
+      }
+    }
+  }
+}
+
 struct Shape {
   const bf16_t* A; int64_t lda; const bf16_t* B; int64_t ldb; int M, N, K, nsplit; int64_t slab;
 };
@@ -215,6 +322,14 @@ int launch_gemm_bf16(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb,
     case 5: return launch_cfg<32, 128, 1, 4>(g, ep, s);
     case 6: return launch_cfg<128, 32, 4, 1>(g, ep, s);
     default: break;
+  }
+  // short contraction with a read-modify-write epilogue: single-trip kernel (measured faster
+  // there; the plain-store case does better with the smaller LDS footprint of the general one)
+  if (K <= 2 * BK && nsplit == 1 && ep.R && M > 32 && N > 32) {
+    dim3 grid((N + 63) / 64, (M + 63) / 64);
+    gemm_bf16_shortk_kernel<64, 64, 2, 2><<<grid, NT, 0, s>>>(A, lda, B, ldb, M, N, K, ep);
+    VF_LAUNCH_CHECK();
+    return VF_OK;
   }
   if (use_big_tile(M, N, K)) return launch_cfg<128, 128, 2, 2>(g, ep, s);
   if (M <= 32) return launch_cfg<32, 128, 1, 4>(g, ep, s);

@@ -17,40 +17,84 @@ __device__ __forceinline__ float block_reduce(float v, bool is_max, float* red) 
   return r;
 }
 
-// One workgroup per row.
-template <typename T>
+// One workgroup per row.  SMALL: the row (C <= 256*CPT classes) lives in registers and global
+// memory is read once; otherwise the reduced logits are re-read from z.
+constexpr int CPT = 4;
+
+template <typename T, bool SMALL>
 __global__ __launch_bounds__(256) void softmax_xent_kernel(const float* zp, int nsplit,
                                                            int64_t slab, int64_t ldzp,
                                                            float* z, int64_t ldz,
                                                            const int32_t* __restrict__ labels, int R,
                                                            int C, float* __restrict__ rowloss,
-                                                           T* __restrict__ dz, int64_t lddz) {
+                                                           T* __restrict__ dz, int64_t lddz,
+                                                           bf16_t* __restrict__ dzT, int64_t ldt) {
   __shared__ float red[4];
+  __shared__ float zlabel;
   const int r = blockIdx.x;
   float* zr = z + (int64_t)r * ldz;
   int label = labels[r];
   label = label < 0 ? 0 : (label >= C ? C - 1 : label);
+  float v[CPT];
   float mx = -INFINITY;
-  for (int c = threadIdx.x; c < C; c += 256) {      // add the partial slabs in order
-    const int64_t idx = (int64_t)r * ldzp + c;
-    float v = zp[idx];
-    for (int s = 1; s < nsplit; ++s) v += zp[(int64_t)s * slab + idx];
-    zr[c] = v;
-    mx = fmaxf(mx, v);
+  if (SMALL) {
+#pragma unroll
+    for (int k = 0; k < CPT; ++k) {
+      const int c = threadIdx.x + 256 * k;
+      v[k] = -INFINITY;
+      if (c < C) {
+        const int64_t idx = (int64_t)r * ldzp + c;
+        float t = zp[idx];
+        for (int s = 1; s < nsplit; ++s) t += zp[(int64_t)s * slab + idx];   // slabs in order
+        v[k] = t;
+        zr[c] = t;
+        if (c == label) zlabel = t;
+      }
+      mx = fmaxf(mx, v[k]);
+    }
+  } else {
+    for (int c = threadIdx.x; c < C; c += 256) {
+      const int64_t idx = (int64_t)r * ldzp + c;
+      float t = zp[idx];
+      for (int s = 1; s < nsplit; ++s) t += zp[(int64_t)s * slab + idx];
+      zr[c] = t;
+      if (c == label) zlabel = t;
+      mx = fmaxf(mx, t);
+    }
   }
   mx = block_reduce(mx, true, red);
   float sum = 0.f;
-  for (int c = threadIdx.x; c < C; c += 256) sum += expf(zr[c] - mx);
+  if (SMALL) {
+#pragma unroll
+    for (int k = 0; k < CPT; ++k) {
+      v[k] = expf(v[k] - mx);          // exp(-inf) = 0 for the padding
+      sum += v[k];
+    }
+  } else {
+    for (int c = threadIdx.x; c < C; c += 256) sum += expf(zr[c] - mx);
+  }
   sum = block_reduce(sum, false, red);
   const float inv = 1.0f / sum;
   const float invR = 1.0f / (float)R;
   T* dr = dz + (int64_t)r * lddz;
-  for (int c = threadIdx.x; c < C; c += 256) {
-    float p = expf(zr[c] - mx) * inv;
-    store_f(&dr[c], (p - (c == label ? 1.f : 0.f)) * invR);
+  if (SMALL) {
+#pragma unroll
+    for (int k = 0; k < CPT; ++k) {
+      const int c = threadIdx.x + 256 * k;
+      if (c < C) {
+        float d = (v[k] * inv - (c == label ? 1.f : 0.f)) * invR;
+        store_f(&dr[c], d);
+        if (dzT) dzT[(int64_t)c * ldt + r] = f32_to_bf16(d);
+      }
+    }
+  } else {
+    for (int c = threadIdx.x; c < C; c += 256) {
+      float d = (expf(zr[c] - mx) * inv - (c == label ? 1.f : 0.f)) * invR;
+      store_f(&dr[c], d);
+      if (dzT) dzT[(int64_t)c * ldt + r] = f32_to_bf16(d);
+    }
   }
-  __syncthreads();   // zr[label] was written by another thread of this workgroup
-  if (threadIdx.x == 0) rowloss[r] = logf(sum) + mx - zr[label];
+  if (threadIdx.x == 0) rowloss[r] = logf(sum) + mx - zlabel;   // zlabel: visible after the reductions' barriers
 }
 
 __global__ __launch_bounds__(256) void loss_reduce_kernel(const float* __restrict__ rowloss, int R,
@@ -73,14 +117,16 @@ __global__ __launch_bounds__(256) void loss_reduce_kernel(const float* __restric
 
 int launch_softmax_xent(const float* zp, int nsplit, int64_t slab, int64_t ldzp, float* z, int64_t ldz,
                         const int32_t* labels, int R, int C, float* rowloss, void* dz, int64_t lddz,
-                        int dz_is_bf16, hipStream_t s) {
+                        int dz_is_bf16, bf16_t* dzT, int64_t ldt, hipStream_t s) {
   if (R <= 0 || C <= 0 || nsplit < 1) return VF_EINVAL;
-  if (dz_is_bf16)
-    softmax_xent_kernel<bf16_t><<<R, 256, 0, s>>>(zp, nsplit, slab, ldzp, z, ldz, labels, R, C, rowloss,
-                                                  static_cast<bf16_t*>(dz), lddz);
-  else
-    softmax_xent_kernel<float><<<R, 256, 0, s>>>(zp, nsplit, slab, ldzp, z, ldz, labels, R, C, rowloss,
-                                                 static_cast<float*>(dz), lddz);
+  if (dzT && !dz_is_bf16) return VF_EINVAL;
+  const bool small = C <= 256 * CPT;
+#define VF_SX(TT, SM)                                                                              \
+  softmax_xent_kernel<TT, SM><<<R, 256, 0, s>>>(zp, nsplit, slab, ldzp, z, ldz, labels, R, C, rowloss, \
+                                                static_cast<TT*>(dz), lddz, dzT, ldt)
+  if (dz_is_bf16) { if (small) VF_SX(bf16_t, true); else VF_SX(bf16_t, false); }
+  else            { if (small) VF_SX(float, true);  else VF_SX(float, false); }
+#undef VF_SX
   VF_LAUNCH_CHECK();
   return VF_OK;
 }

@@ -3,18 +3,24 @@
 // being processed (Section 4.1: such state is computed by each pass on its own; Section 3.2:
 // each node is a separate forward and backward pass).  All reductions in fp32.
 //
-// Inputs that come from a GEMM arrive as `nsplit` partial slabs (see k_gemm_bf16.hip) and
-// are summed here in slab order.  Outputs that feed a weight-gradient GEMM are also written
-// transposed ([C, ldt], rows of the node contiguous), staged through LDS so that both
-// copies are written with full-width stores.
+// Inputs that come from a GEMM arrive as NS partial slabs (see k_gemm_bf16.hip) and are summed
+// here in slab order.  Outputs that feed a weight-gradient GEMM are also written transposed
+// ([C, ldt], rows of the node contiguous), staged through LDS so that both copies are written
+// with wide stores.
+//
+// Shape: a workgroup owns CB = 16 columns and all rows; 256 threads = 16 columns x 16 row
+// lanes, so a 4096-wide layer gives 256 workgroups (one per compute unit).  For nodes of up
+// to RPT*16 = 128 rows every thread keeps its rows in registers and global memory is read
+// exactly once; larger nodes re-read the reduced values.
 #include "vf_device.h"
 
 namespace vf {
 namespace {
 
-constexpr int CB = 32;    // columns per workgroup (128-byte fp32 row segments)
-constexpr int RL = 8;     // row lanes per column; 256 threads = CB x RL
-constexpr int RCH = 128;  // rows per transposed-store chunk
+constexpr int CB = 16;    // columns per workgroup
+constexpr int RL = 16;    // row lanes per column; 256 threads = CB x RL
+constexpr int RPT = 8;    // rows per thread held in registers (nodes up to RL*RPT rows)
+constexpr int RCH = RL * RPT;  // 128: rows per transposed-store chunk
 
 // Sum over the RL row lanes of one column (threads with equal tx); result to all lanes.
 __device__ __forceinline__ float col_reduce(float v, float (*red)[CB + 1], int tx, int ty) {
@@ -39,25 +45,22 @@ __device__ __forceinline__ float sum_slabs(const float* __restrict__ p, int64_t 
   return t;
 }
 
-// Writes the bf16 tile held in LDS ([CB][RCH+8], column-major of the node's rows r0..r0+RCH)
-// to outT[c*ldt + r].  16-byte stores; rows beyond R are padding inside the buffer's row.
+// Writes the bf16 tile held in LDS ([CB][RCH+8]: column c, rows r0..r0+RCH) to
+// outT[c*ldt + r] with 16-byte stores; rows beyond R are padding inside the buffer's row.
 __device__ __forceinline__ void store_transposed(const bf16_t (*tile)[RCH + 8], bf16_t* __restrict__ outT,
                                                  int64_t ldt, int c0, int C, int r0, int R) {
-  const int col = threadIdx.x >> 3, seg = threadIdx.x & 7;     // 32 columns x 8 segments of 16 rows
+  const int col = threadIdx.x >> 4, seg = threadIdx.x & 15;    // 16 columns x 16 segments of 8 rows
   const int c = c0 + col;
-  if (c >= C) return;
-#pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    const int rl = seg * 16 + h * 8;
-    if (r0 + rl < R)   // the vector holds at least one live row; ldt is a multiple of 8
-      *reinterpret_cast<uint4*>(&outT[(int64_t)c * ldt + r0 + rl]) =
-          *reinterpret_cast<const uint4*>(&tile[col][rl]);
-  }
+  const int rl = seg * 8;
+  if (c < C && r0 + rl < R)   // the vector holds at least one live row; ldt is a multiple of 8
+    *reinterpret_cast<uint4*>(&outT[(int64_t)c * ldt + r0 + rl]) =
+        *reinterpret_cast<const uint4*>(&tile[col][rl]);
 }
 
-template <typename T, int NS>
-__global__ __launch_bounds__(256) void bn_relu_fwd_kernel(const float* __restrict__ zp,
-                                                          int64_t slab, int64_t ldzp, int R, int C,
+// SMALL: R <= RCH, rows live in registers.
+template <typename T, int NS, bool SMALL>
+__global__ __launch_bounds__(256) void bn_relu_fwd_kernel(const float* __restrict__ zp, int64_t slab,
+                                                          int64_t ldzp, int R, int C,
                                                           const float* __restrict__ gamma,
                                                           const float* __restrict__ beta,
                                                           int round_params, float eps,
@@ -72,23 +75,46 @@ __global__ __launch_bounds__(256) void bn_relu_fwd_kernel(const float* __restric
   const int c0 = blockIdx.x * CB;
   const int c = c0 + tx;
   const bool live = c < C;
+  const bool bn = gamma != nullptr;
   float mean = 0.f, rstd = 1.f, g = 1.f, b = 0.f;
+  float zr[RPT];
   // pass 1: reduce the slabs into z, column sums
   float s = 0.f;
-  if (live)
+  if (SMALL) {
+#pragma unroll
+    for (int k = 0; k < RPT; ++k) {
+      const int r = ty + RL * k;
+      zr[k] = (live && r < R) ? sum_slabs<NS>(zp, slab, (int64_t)r * ldzp + c) : 0.f;
+      s += zr[k];
+    }
+#pragma unroll
+    for (int k = 0; k < RPT; ++k) {
+      const int r = ty + RL * k;
+      if (live && r < R) z[(int64_t)r * ldz + c] = zr[k];
+    }
+  } else if (live) {
     for (int r = ty; r < R; r += RL) {
       float v = sum_slabs<NS>(zp, slab, (int64_t)r * ldzp + c);
       z[(int64_t)r * ldz + c] = v;
       s += v;
     }
-  if (gamma != nullptr) {
+  }
+  if (bn) {
     mean = col_reduce(s, red, tx, ty) / (float)R;
     float q = 0.f;
-    if (live)
+    if (SMALL) {
+#pragma unroll
+      for (int k = 0; k < RPT; ++k) {
+        const int r = ty + RL * k;
+        float d = (live && r < R) ? zr[k] - mean : 0.f;
+        q = fmaf(d, d, q);
+      }
+    } else if (live) {
       for (int r = ty; r < R; r += RL) {
         float d = z[(int64_t)r * ldz + c] - mean;
         q = fmaf(d, d, q);
       }
+    }
     const float var = col_reduce(q, red, tx, ty) / (float)R;
     rstd = 1.0f / sqrtf(var + eps);
     if (live) {
@@ -99,12 +125,14 @@ __global__ __launch_bounds__(256) void bn_relu_fwd_kernel(const float* __restric
   }
   // pass 2: activation, in chunks of RCH rows so the transposed copy can go through LDS
   for (int r0 = 0; r0 < R; r0 += RCH) {
-    for (int rl = ty; rl < RCH; rl += RL) {
+#pragma unroll
+    for (int k = 0; k < RPT; ++k) {
+      const int rl = ty + RL * k;
       const int r = r0 + rl;
       float v = 0.f;
       if (live && r < R) {
-        float zz = z[(int64_t)r * ldz + c];
-        v = gamma != nullptr ? fmaxf(fmaf(g, (zz - mean) * rstd, b), 0.f) : fmaxf(zz, 0.f);
+        float zz = SMALL ? zr[k] : z[(int64_t)r * ldz + c];
+        v = bn ? fmaxf(fmaf(g, (zz - mean) * rstd, b), 0.f) : fmaxf(zz, 0.f);
         store_f(&a[(int64_t)r * lda + c], v);
       }
       if (aT) tile[tx][rl] = f32_to_bf16(v);
@@ -117,11 +145,11 @@ __global__ __launch_bounds__(256) void bn_relu_fwd_kernel(const float* __restric
   }
 }
 
-template <typename T, int NS>
-__global__ __launch_bounds__(256) void bn_relu_bwd_kernel(float* __restrict__ dap,
-                                                          int64_t slab, int64_t ldda,
-                                                          const float* __restrict__ z, int64_t ldz,
-                                                          int R, int C, const float* __restrict__ gamma,
+template <typename T, int NS, bool SMALL>
+__global__ __launch_bounds__(256) void bn_relu_bwd_kernel(float* __restrict__ dap, int64_t slab,
+                                                          int64_t ldda, const float* __restrict__ z,
+                                                          int64_t ldz, int R, int C,
+                                                          const float* __restrict__ gamma,
                                                           const float* __restrict__ beta,
                                                           int round_params,
                                                           const float* __restrict__ mean_in,
@@ -143,18 +171,36 @@ __global__ __launch_bounds__(256) void bn_relu_bwd_kernel(float* __restrict__ da
     mean = mean_in[c]; rstd = rstd_in[c];
   }
   // pass 1: sum dout*xhat, sum dout  (dout = da where the ReLU was open)
+  float xr[RPT], dr[RPT];
   float sg = 0.f, sb = 0.f;
-  if (live)
+  if (SMALL) {
+#pragma unroll
+    for (int k = 0; k < RPT; ++k) {
+      const int r = ty + RL * k;
+      xr[k] = 0.f; dr[k] = 0.f;
+      if (live && r < R) {
+        float zz = z[(int64_t)r * ldz + c];
+        float xhat = (zz - mean) * rstd;
+        float pre = bn ? fmaf(g, xhat, b) : zz;
+        float d = sum_slabs<NS>(dap, slab, (int64_t)r * ldda + c);
+        xr[k] = xhat;
+        dr[k] = pre > 0.f ? d : 0.f;
+      }
+      sg = fmaf(dr[k], xr[k], sg);
+      sb += dr[k];
+    }
+  } else if (live) {
     for (int r = ty; r < R; r += RL) {
       float zz = z[(int64_t)r * ldz + c];
       float xhat = (zz - mean) * rstd;
       float pre = bn ? fmaf(g, xhat, b) : zz;
       float d = sum_slabs<NS>(dap, slab, (int64_t)r * ldda + c);
       float dout = pre > 0.f ? d : 0.f;
-      if (NS > 1) dap[(int64_t)r * ldda + c] = dout;   // keep the reduced, masked value in slab 0
+      dap[(int64_t)r * ldda + c] = dout;   // keep the reduced, masked value in slab 0
       sg = fmaf(dout, xhat, sg);
       sb += dout;
     }
+  }
   sg = col_reduce(sg, red, tx, ty);
   sb = col_reduce(sb, red, tx, ty);
   if (live && ty == 0) {
@@ -162,23 +208,23 @@ __global__ __launch_bounds__(256) void bn_relu_bwd_kernel(float* __restrict__ da
     if (gout_b.dst) grad_store(gout_b, c, sb);
   }
   const float invR = 1.0f / (float)R;
-  const float k = g * rstd;
+  const float kk = g * rstd;
   // pass 2: dz (and its transposed copy)
   for (int r0 = 0; r0 < R; r0 += RCH) {
-    for (int rl = ty; rl < RCH; rl += RL) {
+#pragma unroll
+    for (int k = 0; k < RPT; ++k) {
+      const int rl = ty + RL * k;
       const int r = r0 + rl;
       float v = 0.f;
       if (live && r < R) {
-        float zz = z[(int64_t)r * ldz + c];
-        float xhat = (zz - mean) * rstd;
-        float dout;
-        if (NS > 1) {
-          dout = dap[(int64_t)r * ldda + c];           // written by this thread in pass 1
+        float xhat, dout;
+        if (SMALL) {
+          xhat = xr[k]; dout = dr[k];
         } else {
-          float pre = bn ? fmaf(g, xhat, b) : zz;
-          dout = pre > 0.f ? dap[(int64_t)r * ldda + c] : 0.f;
+          xhat = (z[(int64_t)r * ldz + c] - mean) * rstd;
+          dout = dap[(int64_t)r * ldda + c];           // written by this thread in pass 1
         }
-        v = bn ? k * (dout - sb * invR - xhat * sg * invR) : dout;
+        v = bn ? kk * (dout - sb * invR - xhat * sg * invR) : dout;
         store_f(&dz[(int64_t)r * lddz + c], v);
       }
       if (dzT) tile[tx][rl] = f32_to_bf16(v);
@@ -191,17 +237,36 @@ __global__ __launch_bounds__(256) void bn_relu_bwd_kernel(float* __restrict__ da
   }
 }
 
+constexpr int SCB = 32, SRL = 8;
 template <typename T>
 __global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ x, int64_t ld, int R, int C,
                                                      GradOut out) {
-  __shared__ float red[RL][CB + 1];
-  const int tx = threadIdx.x % CB, ty = threadIdx.x / CB;
-  const int c = blockIdx.x * CB + tx;
+  __shared__ float red[SRL][SCB + 1];
+  const int tx = threadIdx.x % SCB, ty = threadIdx.x / SCB;
+  const int c = blockIdx.x * SCB + tx;
   float s = 0.f;
   if (c < C)
-    for (int r = ty; r < R; r += RL) s += load_f(&x[(int64_t)r * ld + c]);
-  s = col_reduce(s, red, tx, ty);
-  if (c < C && ty == 0) grad_store(out, c, s);
+    for (int r = ty; r < R; r += SRL) s += load_f(&x[(int64_t)r * ld + c]);
+  red[ty][tx] = s;
+  __syncthreads();
+  if (ty == 0 && c < C) {
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < SRL; ++i) t += red[i][tx];
+    grad_store(out, c, t);
+  }
+}
+
+// out[r] = sum_c x[r*ld + c]: one wavefront per row (bias gradient from a transposed gradient)
+__global__ __launch_bounds__(256) void rowsum_kernel(const bf16_t* __restrict__ x, int64_t ld, int R, int C,
+                                                     GradOut out) {
+  const int lane = threadIdx.x & 63;
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= R) return;
+  float s = 0.f;
+  for (int c = lane; c < C; c += 64) s += bf16_to_f32(x[(int64_t)r * ld + c]);
+  s = wave_sum(s);
+  if (lane == 0) grad_store(out, r, s);
 }
 
 }  // namespace
@@ -212,21 +277,22 @@ int launch_bn_relu_fwd(const float* zp, int nsplit, int64_t slab, int64_t ldzp, 
                        float* mean, float* rstd, hipStream_t s) {
   if (R <= 0 || C <= 0 || nsplit < 1) return VF_EINVAL;
   if (aT && ((ldt & 7) || !a_is_bf16)) return VF_EINVAL;
-  int grid = (C + CB - 1) / CB;
-#define VF_FWD(NS)                                                                                   \
-  case NS:                                                                                           \
-    if (a_is_bf16)                                                                                   \
-      bn_relu_fwd_kernel<bf16_t, NS><<<grid, 256, 0, s>>>(zp, slab, ldzp, R, C, gamma, beta,        \
-          round_params, eps, z, ldz, static_cast<bf16_t*>(a), lda, aT, ldt, mean, rstd);             \
-    else                                                                                             \
-      bn_relu_fwd_kernel<float, NS><<<grid, 256, 0, s>>>(zp, slab, ldzp, R, C, gamma, beta,         \
-          round_params, eps, z, ldz, static_cast<float*>(a), lda, aT, ldt, mean, rstd);              \
+  const int grid = (C + CB - 1) / CB;
+  const bool small = R <= RCH;
+#define VF_FWD2(TT, NS, SM)                                                                        \
+  bn_relu_fwd_kernel<TT, NS, SM><<<grid, 256, 0, s>>>(zp, slab, ldzp, R, C, gamma, beta, round_params, \
+      eps, z, ldz, static_cast<TT*>(a), lda, aT, ldt, mean, rstd)
+#define VF_FWD(NS)                                                                                 \
+  case NS:                                                                                         \
+    if (a_is_bf16) { if (small) VF_FWD2(bf16_t, NS, true); else VF_FWD2(bf16_t, NS, false); }      \
+    else           { if (small) VF_FWD2(float, NS, true);  else VF_FWD2(float, NS, false); }       \
     break;
   switch (nsplit) {
     VF_FWD(1) VF_FWD(2) VF_FWD(4) VF_FWD(8) VF_FWD(16) VF_FWD(32)
     default: return VF_EINVAL;
   }
 #undef VF_FWD
+#undef VF_FWD2
   VF_LAUNCH_CHECK();
   return VF_OK;
 }
@@ -238,21 +304,22 @@ int launch_bn_relu_bwd(float* dap, int nsplit, int64_t slab, int64_t ldda, const
                        hipStream_t s) {
   if (R <= 0 || C <= 0 || nsplit < 1) return VF_EINVAL;
   if (dzT && ((ldt & 7) || !dz_is_bf16)) return VF_EINVAL;
-  int grid = (C + CB - 1) / CB;
-#define VF_BWD(NS)                                                                                   \
-  case NS:                                                                                           \
-    if (dz_is_bf16)                                                                                  \
-      bn_relu_bwd_kernel<bf16_t, NS><<<grid, 256, 0, s>>>(dap, slab, ldda, z, ldz, R, C, gamma,     \
-          beta, round_params, mean, rstd, static_cast<bf16_t*>(dz), lddz, dzT, ldt, gout_g, gout_b); \
-    else                                                                                             \
-      bn_relu_bwd_kernel<float, NS><<<grid, 256, 0, s>>>(dap, slab, ldda, z, ldz, R, C, gamma,      \
-          beta, round_params, mean, rstd, static_cast<float*>(dz), lddz, dzT, ldt, gout_g, gout_b);  \
+  const int grid = (C + CB - 1) / CB;
+  const bool small = R <= RCH;
+#define VF_BWD2(TT, NS, SM)                                                                        \
+  bn_relu_bwd_kernel<TT, NS, SM><<<grid, 256, 0, s>>>(dap, slab, ldda, z, ldz, R, C, gamma, beta,  \
+      round_params, mean, rstd, static_cast<TT*>(dz), lddz, dzT, ldt, gout_g, gout_b)
+#define VF_BWD(NS)                                                                                 \
+  case NS:                                                                                         \
+    if (dz_is_bf16) { if (small) VF_BWD2(bf16_t, NS, true); else VF_BWD2(bf16_t, NS, false); }     \
+    else            { if (small) VF_BWD2(float, NS, true);  else VF_BWD2(float, NS, false); }      \
     break;
   switch (nsplit) {
     VF_BWD(1) VF_BWD(2) VF_BWD(4) VF_BWD(8) VF_BWD(16) VF_BWD(32)
     default: return VF_EINVAL;
   }
 #undef VF_BWD
+#undef VF_BWD2
   VF_LAUNCH_CHECK();
   return VF_OK;
 }
@@ -260,9 +327,16 @@ int launch_bn_relu_bwd(float* dap, int nsplit, int64_t slab, int64_t ldda, const
 int launch_colsum(const void* x, int64_t ld, int x_is_bf16, int R, int C, GradOut out,
                   hipStream_t s) {
   if (R <= 0 || C <= 0) return VF_EINVAL;
-  int grid = (C + CB - 1) / CB;
+  int grid = (C + SCB - 1) / SCB;
   if (x_is_bf16) colsum_kernel<bf16_t><<<grid, 256, 0, s>>>(static_cast<const bf16_t*>(x), ld, R, C, out);
   else           colsum_kernel<float><<<grid, 256, 0, s>>>(static_cast<const float*>(x), ld, R, C, out);
+  VF_LAUNCH_CHECK();
+  return VF_OK;
+}
+
+int launch_rowsum_bf16(const bf16_t* x, int64_t ld, int R, int C, GradOut out, hipStream_t s) {
+  if (R <= 0 || C <= 0) return VF_EINVAL;
+  rowsum_kernel<<<(R + 3) / 4, 256, 0, s>>>(x, ld, R, C, out);
   VF_LAUNCH_CHECK();
   return VF_OK;
 }

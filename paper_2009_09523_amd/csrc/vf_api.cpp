@@ -60,10 +60,9 @@ int validate_config(const vf_config& c) {
 // Enqueue everything of one step except the optimizer update.
 int enqueue_nodes(Ctx& c, const StepArgs& a) {
   VF_TRY(c.model->prepare(c, a.params));
-  for (int i = 0; i < a.V; ++i) {
-    VF_TRY(c.model->run_node(c, a, i));
-    if (!c.fused) VF_K(c, "accumulate", launch_accumulate(c.gbuf, c.gstage, a.w[i], c.P, i == 0, c.stream));
-  }
+  for (int i = 0; i < a.V; ++i) VF_TRY(c.model->run_node(c, a, i));
+  // join: the side stream is in order, so its latest event covers all nodes
+  if (c.overlapping()) VF_HIP(hipStreamWaitEvent(c.stream, c.side_done[(a.V - 1) & 1], 0));
   return VF_OK;
 }
 
@@ -84,6 +83,14 @@ int enqueue_update(Ctx& c, float* params) {
 bool graph_matches(const Ctx& c, const StepArgs& a) {
   return c.graph_exec && c.graph_params == a.params && c.graph_x == a.x && c.graph_y == a.y &&
          c.graph_sizes == a.sizes;
+}
+
+void release_streams(Ctx& c) {
+  for (hipEvent_t ev : c.order_events) (void)hipEventDestroy(ev);
+  c.order_events.clear();
+  for (int k = 0; k < 2; ++k)
+    if (c.side_done[k]) { (void)hipEventDestroy(c.side_done[k]); c.side_done[k] = nullptr; }
+  if (c.side) { (void)hipStreamDestroy(c.side); c.side = nullptr; }
 }
 
 void drop_graph(Ctx& c) {
@@ -126,6 +133,13 @@ int copy_out(Ctx& c, const float* src, float* out, size_t count) {
 }
 
 }  // namespace
+
+int Ctx::fold(int node, float w, hipStream_t st) {
+  if (fused) return VF_OK;
+  VF_KS(*this, st, "accumulate", launch_accumulate(gbuf, stage_for(node), w, P, node == 0, st));
+  return VF_OK;
+}
+
 }  // namespace vf
 
 using namespace vf;
@@ -166,10 +180,29 @@ int vf_init(const vf_config* cfg, vf_ctx** out) {
   c.model = cfg->model_kind == VF_MLP ? make_mlp(*cfg) : make_encoder(*cfg);
   if (!c.model) { delete h; return VF_EINVAL; }
   c.P = c.model->num_params();
+  // Overlap needs a capturable main stream and a model that double-buffers what the side
+  // stream reads (the bf16 MLP does).
+  c.overlap = c.stream != nullptr && !(cfg->flags & VF_FLAG_NO_OVERLAP) && c.model->supports_overlap();
+  if (c.overlap) {
+    e = hipStreamCreateWithFlags(&c.side, hipStreamNonBlocking);
+    for (int k = 0; k < 2 && e == hipSuccess; ++k) e = hipEventCreateWithFlags(&c.side_done[k], hipEventDisableTiming);
+    for (int k = 0; k < 32 && e == hipSuccess; ++k) {
+      hipEvent_t ev = nullptr;
+      e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
+      if (e == hipSuccess) c.order_events.push_back(ev);
+    }
+    if (e != hipSuccess) {
+      set_last_error("side stream set-up", e, __FILE__, __LINE__);
+      release_streams(c);
+      delete h;
+      return VF_EDEVICE;
+    }
+  }
 
   Arena arena;
   arena.request(&c.gbuf, (size_t)c.P);
   if (!c.fused) arena.request(&c.gstage, (size_t)c.P);
+  if (!c.fused && c.overlap) arena.request(&c.gstage2, (size_t)c.P);
   arena.request(&c.opt0, (size_t)c.P);
   if (cfg->optimizer == VF_ADAM) arena.request(&c.opt1, (size_t)c.P);
   size_t loss_rows = (size_t)cfg->max_node_size;
@@ -184,6 +217,7 @@ int vf_init(const vf_config* cfg, vf_ctx** out) {
     set_last_error("hipMalloc", e, __FILE__, __LINE__);
     c.arena = nullptr;
     (void)hipGetLastError();
+    release_streams(c);
     delete h;
     return VF_ENOMEM;
   }
@@ -310,7 +344,9 @@ void vf_destroy(vf_ctx* h) {
   Ctx& c = h->c;
   if (c.arena) {
     (void)hipStreamSynchronize(c.stream);
+    if (c.side) (void)hipStreamSynchronize(c.side);
     drop_graph(c);
+    release_streams(c);
     for (hipEvent_t e : c.prof.pool) (void)hipEventDestroy(e);
     (void)hipFree(c.arena);
   }

@@ -50,7 +50,10 @@ class Model {
   virtual int prepare(Ctx& c, const float* params) = 0;
   // Forward + backward of node `i` (rows off..off+b): loss bookkeeping and gradients
   // through `gout(flat offset)`.
+  // (in staged mode it ends with c.fold(i, ...)).
   virtual int run_node(Ctx& c, const StepArgs& a, int i) = 0;
+  // True if run_node can put weight gradients and the fold on the context's side stream.
+  virtual bool supports_overlap() const { return false; }
 };
 
 // Optional per-kernel timing: while enabled, every launch made through VF_K is bracketed by
@@ -95,6 +98,28 @@ struct Ctx {
   int64_t steps = 0;
   int32_t last_V = 0;
 
+  // Second stream (library-owned, default priority) for work off a node's critical path:
+  // weight gradients and the fold into the gradient buffer run there while the main stream
+  // goes on with the input-gradient chain and the next node's forward pass.
+  hipStream_t side = nullptr;
+  bool overlap = false;
+  float* gstage2 = nullptr;               // second staging vector (nodes alternate) when overlapping
+  hipEvent_t side_done[2] = {nullptr, nullptr};
+  std::vector<hipEvent_t> order_events;   // rotating pool for cross-stream ordering
+  size_t order_next = 0;
+
+  bool overlapping() const { return overlap && !prof.enabled; }
+  hipStream_t side_stream() const { return overlapping() ? side : stream; }
+  // Everything enqueued so far on `from` happens before anything enqueued later on `to`.
+  int order(hipStream_t from, hipStream_t to) {
+    if (from == to) return VF_OK;
+    hipEvent_t e = order_events[order_next++ % order_events.size()];
+    VF_HIP(hipEventRecord(e, from));
+    VF_HIP(hipStreamWaitEvent(to, e, 0));
+    return VF_OK;
+  }
+  float* stage_for(int node) const { return (overlapping() && (node & 1)) ? gstage2 : gstage; }
+
   // graph replay of the node sequence
   hipGraphExec_t graph_exec = nullptr;
   std::vector<int32_t> graph_sizes;
@@ -105,20 +130,25 @@ struct Ctx {
   // Destination of node i's gradient entry at flat offset `off`.
   GradOut gout(int64_t off, float w, int node) const {
     if (fused) return GradOut{gbuf + off, w, node > 0 ? 1 : 0};
-    return GradOut{gstage + off, 1.0f, 0};
+    return GradOut{stage_for(node) + off, 1.0f, 0};
   }
+  // Staged mode: fold node i's staging vector into the gradient buffer on stream `st`
+  // (Section 3.2 step 3 with the weight of Section 5.2).  No-op in fused mode.
+  int fold(int node, float w, hipStream_t st);
 };
 
-// Launch `call` (an expression returning a status) under the tag `name`.
-#define VF_K(ctx, name, call)                                             \
+// Launch `call` (an expression returning a status) under the tag `name`; the launch goes to
+// stream `strm` (VF_K: the context's main stream).
+#define VF_K(ctx, name, call) VF_KS(ctx, (ctx).stream, name, call)
+#define VF_KS(ctx, strm, name, call)                                             \
   do {                                                                    \
     if ((ctx).prof.enabled) {                                             \
       ::vf::Profiler::Rec r__{name, nullptr, nullptr};                    \
       VF_TRY((ctx).prof.take(&r__.a));                                    \
       VF_TRY((ctx).prof.take(&r__.b));                                    \
-      VF_HIP(hipEventRecord(r__.a, (ctx).stream));                        \
+      VF_HIP(hipEventRecord(r__.a, (strm)));                              \
       VF_TRY(call);                                                       \
-      VF_HIP(hipEventRecord(r__.b, (ctx).stream));                        \
+      VF_HIP(hipEventRecord(r__.b, (strm)));                              \
       (ctx).prof.recs.push_back(r__);                                     \
     } else {                                                              \
       VF_TRY(call);                                                       \

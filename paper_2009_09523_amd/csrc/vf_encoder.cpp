@@ -157,7 +157,7 @@ class Encoder final : public Model {
                                                   cfg_.ln_eps, rows_, d_, bf16_, meanf_, rstdf_, st));
     VF_TRY(lin_fwd(c, "gemm_head", out_, P, rows_, d_, Rm, logits_, ldV_, false, nullptr));
     VF_K(c, "softmax_xent", launch_softmax_xent(logits_, 1, 0, ldV_, logits_, ldV_, labels_, Rm, V_, c.rowloss,
-                                                dlogits_, ldV_, bf16_, st));
+                                                dlogits_, ldV_, bf16_, nullptr, 0, st));
     VF_K(c, "loss_reduce", launch_loss_reduce(c.rowloss, Rm, w, i, c.node_loss, c.loss_total, st));
 
     // ---- backward: output head -----------------------------------------------------------
@@ -227,7 +227,7 @@ class Encoder final : public Model {
     GradOut gt = c.gout(tok_off_, w, i);
     if (!c.fused || i == 0) VF_K(c, "fill", launch_fill_f32(gt.dst, 0.f, (int64_t)V_ * d_, st));
     VF_K(c, "embed_bwd", launch_embed_tok_bwd(ids, dh_buf_, R, d_, V_, gt, st));
-    return VF_OK;
+    return c.fold(i, w, st);
   }
 
  private:

@@ -117,6 +117,8 @@ int launch_bn_relu_bwd(float* dap, int nsplit, int64_t slab, int64_t ldda, const
                        int round_params, const float* mean, const float* rstd, void* dz, int64_t lddz,
                        int dz_is_bf16, bf16_t* dzT, int64_t ldt, GradOut gout_g, GradOut gout_b,
                        hipStream_t s);
+// out[r] = sum_c x[r*ld + c] through GradOut (bias gradient from a transposed bf16 gradient)
+int launch_rowsum_bf16(const bf16_t* x, int64_t ld, int R, int C, GradOut out, hipStream_t s);
 // out[c] = sum_r x[r*ld + c] through GradOut (x is T)
 int launch_colsum(const void* x, int64_t ld, int x_is_bf16, int R, int C, GradOut out,
                   hipStream_t s);
@@ -125,9 +127,10 @@ int launch_colsum(const void* x, int64_t ld, int x_is_bf16, int R, int C, GradOu
 // Softmax cross-entropy over R rows of fp32 logits with C classes.  zp: nsplit partial slabs
 // of the logits (summed into z, which may be slab 0 itself):
 //   rowloss[r] = logsumexp(z_r) - z_r[label_r];  dz[r,c] = (softmax(z_r)[c] - [c==label_r]) / R
+// dzT (optional, bf16 only): the same gradient transposed, [C, ldt].
 int launch_softmax_xent(const float* zp, int nsplit, int64_t slab, int64_t ldzp, float* z, int64_t ldz,
                         const int32_t* labels, int R, int C, float* rowloss, void* dz, int64_t lddz,
-                        int dz_is_bf16, hipStream_t s);
+                        int dz_is_bf16, bf16_t* dzT, int64_t ldt, hipStream_t s);
 // node_loss[i] = (1/R) sum_r rowloss[r];  total = (i == 0 ? 0 : total) + w * node_loss[i]
 int launch_loss_reduce(const float* rowloss, int R, float w, int node, float* node_loss,
                        float* total, hipStream_t s);

@@ -22,8 +22,11 @@ struct Layer {
   float* rstd = nullptr;           // [N]
   void* a = nullptr;               // T [max_b, ld]: activation after BatchNorm/ReLU
   void* dz = nullptr;              // T [max_b, ld]: gradient w.r.t. z
-  bf16_t* aT = nullptr;            // bf16 [N, ldb]: a transposed   (weight-gradient operand)
-  bf16_t* dzT = nullptr;           // bf16 [N, ldb]: dz transposed  (weight-gradient operand)
+  // Weight-gradient operands, transposed ([N, ldb], rows of the node contiguous).  Two copies:
+  // nodes alternate between them so that the side stream can still read node i's operands
+  // while the main stream produces those of node i+1.
+  bf16_t* aT[2] = {nullptr, nullptr};    // a transposed
+  bf16_t* dzT[2] = {nullptr, nullptr};   // dz transposed
 };
 
 class Mlp final : public Model {
@@ -80,6 +83,7 @@ class Mlp final : public Model {
   }
 
   int64_t num_params() const override { return P_; }
+  bool supports_overlap() const override { return bf16_; }
 
   void request_buffers(Arena& a) override {
     const size_t mb = (size_t)cfg_.max_node_size;
@@ -95,11 +99,14 @@ class Mlp final : public Model {
       if (bf16_) {
         a.request(&L.wnat, (size_t)L.K * L.ldn);
         a.request(&L.wtr, (size_t)L.N * L.ldt);
-        a.request(&L.dzT, (size_t)L.N * ldb_);
-        if (L.hidden) a.request(&L.aT, (size_t)L.N * ldb_);
+        for (int k = 0; k < 2; ++k) {
+          a.request(&L.dzT[k], (size_t)L.N * ldb_);
+          if (L.hidden) a.request(&L.aT[k], (size_t)L.N * ldb_);
+        }
       }
     }
-    if (bf16_) a.request(&xT_, (size_t)cfg_.dims[0] * ldb_);
+    if (bf16_)
+      for (int k = 0; k < 2; ++k) a.request(&xT_[k], (size_t)cfg_.dims[0] * ldb_);
     a.request(&slab_, (size_t)slab_elems_);
   }
 
@@ -112,6 +119,10 @@ class Mlp final : public Model {
 
   int run_node(Ctx& c, const StepArgs& s, int i) override {
     hipStream_t st = c.stream;
+    // weight gradients and the fold go to the side stream (bf16 path, when overlapping)
+    hipStream_t sd = bf16_ ? c.side_stream() : c.stream;
+    const bool forked = sd != st;
+    const int p = i & 1;                 // which copy of the transposed operands this node uses
     const int b = s.sizes[i];
     const int64_t row0 = s.off[i];
     const float w = s.w[i];
@@ -122,7 +133,10 @@ class Mlp final : public Model {
                           : (const void*)(static_cast<const float*>(s.x) + row0 * D);
     const int32_t* y = s.y + row0;
 
-    // ---- forward -----------------------------------------------------------------------
+    // copy p of the operands (and of the staging vector) was last read by node i-2's side work
+    if (forked && i >= 2) VF_HIP(hipStreamWaitEvent(st, c.side_done[p], 0));
+
+    // ---- forward (main stream) ---------------------------------------------------------------
     for (int l = 0; l < nl; ++l) {
       Layer& L = layers_[l];
       const void* in = l == 0 ? x : layers_[l - 1].a;
@@ -140,38 +154,38 @@ class Mlp final : public Model {
       if (L.hidden)
         VF_K(c, "bn_relu_fwd", launch_bn_relu_fwd(slab_, split, slab, L.ld, b, L.N,
                                   L.has_bn ? P + L.g_off : nullptr, L.has_bn ? P + L.be_off : nullptr,
-                                  bf16_, cfg_.bn_eps, L.z, L.ld, L.a, L.ld, bf16_, L.aT, ldb_,
+                                  bf16_, cfg_.bn_eps, L.z, L.ld, L.a, L.ld, bf16_, L.aT[p], ldb_,
                                   L.mean, L.rstd, st));
       else
         VF_K(c, "softmax_xent", launch_softmax_xent(slab_, split, slab, L.ld, L.z, L.ld, y, b, L.N,
-                                                    c.rowloss, L.dz, L.ld, bf16_, st));
+                                                    c.rowloss, L.dz, L.ld, bf16_, L.dzT[p], ldb_, st));
     }
     VF_K(c, "loss_reduce", launch_loss_reduce(c.rowloss, b, w, i, c.node_loss, c.loss_total, st));
 
-    // ---- backward ----------------------------------------------------------------------
+    // ---- backward: input-gradient chain on the main stream, weight gradients beside it --------
     for (int l = nl - 1; l >= 0; --l) {
       Layer& L = layers_[l];
       const void* in = l == 0 ? x : layers_[l - 1].a;
       const int64_t ldin = l == 0 ? D : layers_[l - 1].ld;
-      if (!L.hidden)   // last layer: bias gradient = column sums of dlogits
-        VF_K(c, "colsum", launch_colsum(L.dz, L.ld, bf16_, b, L.N, c.gout(L.b_off, w, i), st));
+      // dz of layer l (and its transposed copy) is complete on the main stream here
+      VF_TRY(c.order(st, sd));
+      if (l == nl - 1 && bf16_)   // first side-stream work of the node: the batch slice, transposed
+        VF_KS(c, sd, "transpose", launch_transpose_bf16(static_cast<const bf16_t*>(x), D, xT_[p], ldb_, b, D, sd));
+      if (!L.hidden) {   // last layer: bias gradient = sums over the node of dlogits
+        if (bf16_) VF_KS(c, sd, "bias_grad", launch_rowsum_bf16(L.dzT[p], ldb_, L.N, b, c.gout(L.b_off, w, i), sd));
+        else       VF_KS(c, sd, "bias_grad", launch_colsum(L.dz, L.ld, 0, b, L.N, c.gout(L.b_off, w, i), sd));
+      }
       // weight gradient dW[K,N] = in^T dz
       GradOut go = c.gout(L.w_off, w, i);
       Epilogue ep;
       ep.C = go.dst; ep.ldc = L.N; ep.alpha = go.alpha;
       if (go.accumulate) { ep.R = go.dst; ep.ldr = L.N; ep.beta = 1.f; }
       if (bf16_) {
-        // transposed operands: hidden activations and their gradients were written by the
-        // BatchNorm/ReLU kernels; only the batch slice and the logits gradient remain
-        bf16_t* inT = l == 0 ? xT_ : layers_[l - 1].aT;
-        if (l == 0)
-          VF_K(c, "transpose", launch_transpose_bf16(static_cast<const bf16_t*>(in), ldin, inT, ldb_, b, L.K, st));
-        if (!L.hidden)
-          VF_K(c, "transpose", launch_transpose_bf16(static_cast<const bf16_t*>(L.dz), L.ld, L.dzT, ldb_, b, L.N, st));
-        VF_K(c, "gemm_wgrad", launch_gemm_bf16(inT, ldb_, L.dzT, ldb_, L.K, L.N, b, 1, 0, ep, st));
+        const bf16_t* inT = l == 0 ? xT_[p] : layers_[l - 1].aT[p];
+        VF_KS(c, sd, "gemm_wgrad", launch_gemm_bf16(inT, ldb_, L.dzT[p], ldb_, L.K, L.N, b, 1, 0, ep, sd));
       } else {
-        VF_K(c, "gemm_wgrad", launch_gemm_f32(static_cast<const float*>(in), 1, ldin, static_cast<const float*>(L.dz), 1,
-                               L.ld, L.K, L.N, b, ep, st));
+        VF_KS(c, sd, "gemm_wgrad", launch_gemm_f32(static_cast<const float*>(in), 1, ldin,
+                                                   static_cast<const float*>(L.dz), 1, L.ld, L.K, L.N, b, ep, sd));
       }
       if (l == 0) break;
       // input gradient da[l-1][b,K] = dz W^T, then through ReLU / BatchNorm of layer l-1
@@ -189,9 +203,12 @@ class Mlp final : public Model {
       GradOut gb = c.gout(Pv.has_bn ? Pv.be_off : Pv.b_off, w, i);
       VF_K(c, "bn_relu_bwd", launch_bn_relu_bwd(slab_, split, slab, Pv.ld, Pv.z, Pv.ld, b, Pv.N,
                                 Pv.has_bn ? P + Pv.g_off : nullptr, Pv.has_bn ? P + Pv.be_off : nullptr,
-                                bf16_, Pv.mean, Pv.rstd, Pv.dz, Pv.ld, bf16_, bf16_ ? Pv.dzT : nullptr, ldb_,
+                                bf16_, Pv.mean, Pv.rstd, Pv.dz, Pv.ld, bf16_, bf16_ ? Pv.dzT[p] : nullptr, ldb_,
                                 gg, gb, st));
     }
+    // every entry of node i's gradient is now enqueued (main: small vectors; side: matrices)
+    VF_TRY(c.fold(i, w, sd));
+    if (forked) VF_HIP(hipEventRecord(c.side_done[p], sd));
     return VF_OK;
   }
 
@@ -201,7 +218,7 @@ class Mlp final : public Model {
   int64_t P_ = 0;
   int64_t ldb_ = 0;
   std::vector<Layer> layers_;
-  bf16_t* xT_ = nullptr;
+  bf16_t* xT_[2] = {nullptr, nullptr};
   float* slab_ = nullptr;
   int64_t slab_elems_ = 0;
 };

@@ -191,3 +191,17 @@ def test_c5_full_size_launch_configuration():
     gpu = run_gpu(w2, theta, x[:256], y[:256])
     assert abs(gpu["loss"] - 0.5 * (L0 + L1)) <= 1e-3 * abs(L0)
     check(gpu["G"], 0.5 * (g0 + g1), "G (two nodes)")
+
+
+NO_OVERLAP = 4
+
+
+def test_overlap_and_single_stream_agree_bitwise():
+    """Weight gradients on the side stream change scheduling only, never a bit of the result."""
+    wl, theta, x, y = _case("mlp_mid_bn_bf16")
+    base = run_gpu(wl, theta, x, y, flags=NO_OVERLAP | NO_GRAPH, steps=2)
+    for flags in (0, NO_GRAPH, FUSED, FUSED | NO_GRAPH, NO_OVERLAP, FUSED | NO_OVERLAP):
+        other = run_gpu(wl, theta, x, y, flags=flags, steps=2)
+        assert base["G"].tobytes() == other["G"].tobytes(), flags
+        assert base["theta"].tobytes() == other["theta"].tobytes(), flags
+        assert base["loss"] == other["loss"], flags
