@@ -24,12 +24,15 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 matrix cores
 FP32_VECTOR_PEAK_TFLOPS = 157.3
 
 
-def algorithmic_work(wl, P):
+def algorithmic_work(wl, P, fused=False):
     """Per step, per kernel tag: (bytes, flops, launches) the method itself needs.
-    Bytes count each operand once per launch (fp32 = 4, bf16 = 2)."""
+    Bytes count each operand once per launch (fp32 = 4, bf16 = 2).  With the fused fold the
+    weight-gradient kernels read and write the gradient buffer (node 0 only writes it) and
+    there is no accumulate kernel."""
     V, B = wl.n_nodes, wl.batch
     esz = 2 if wl.dtype == "bf16" else 4
-    work = {"accumulate": ((12 * V - 4) * P, 2 * V * P, V)}
+    work = {} if fused else {"accumulate": ((12 * V - 4) * P, 2 * V * P, V)}
+    wg = (8 * V - 4) if fused else 4 * V          # fp32 bytes per matrix entry per step
     opt_bytes = (20 if wl.optimizer == "sgdm" else 28) * P
     work["optimizer"] = (opt_bytes, 4 * P, 1)
     if wl.kind == "mlp":
@@ -40,7 +43,7 @@ def algorithmic_work(wl, P):
         act = sum(b * (k * esz + n * 4) for b in wl.node_sizes for k, n in mats)
         work["gemm_fwd"] = (V * W * esz + act, fwd_fl, V * len(mats))
         work["gemm_dgrad"] = (V * sum(k * n for k, n in mats[1:]) * esz + act, dgr_fl, V * (len(mats) - 1))
-        work["gemm_wgrad"] = (V * W * 4 + act, fwd_fl, V * len(mats))
+        work["gemm_wgrad"] = (wg * W + act, fwd_fl, V * len(mats))
         work["cast_weight"] = (W * (4 + 2 * esz), 0, len(mats))
     else:
         d, f, T, Vc, m, nl = wl.d_model, wl.d_ffn, wl.seq_len, wl.vocab, wl.n_masked, wl.n_layers
@@ -50,11 +53,11 @@ def algorithmic_work(wl, P):
         act_f = nl * R * (2 * d + 3 * d + d + f + f + d) * esz   # operands read / written once
         work["gemm_fwd"] = (V * nl * Wl * esz + act_f, lin_fl, V * nl * 4)
         work["gemm_dgrad"] = (V * nl * Wl * esz + act_f, lin_fl, V * nl * 4)
-        work["gemm_wgrad"] = (V * nl * Wl * 4 + act_f, lin_fl, V * nl * 4)
+        work["gemm_wgrad"] = (wg * nl * Wl + act_f, lin_fl, V * nl * 4)
         head_fl = 2 * Rm * d * Vc
         work["gemm_head"] = (V * d * Vc * esz + Rm * Vc * 4, head_fl, V)
         work["gemm_head_dgrad"] = (V * d * Vc * esz + Rm * Vc * esz, head_fl, V)
-        work["gemm_head_wgrad"] = (V * d * Vc * 4 + Rm * Vc * esz, head_fl, V)
+        work["gemm_head_wgrad"] = (wg * d * Vc + Rm * Vc * esz, head_fl, V)
         att = 2 * T * T * d * B * nl               # one [T,T,d_head] product over all heads, all blocks
         for tag in ("attn_scores", "attn_pv", "attn_bwd_dp", "attn_bwd_dv", "attn_bwd_dq", "attn_bwd_dk"):
             work[tag] = (nl * (3 * R * d * esz + B * wl.n_heads * T * T * 4), att, V * nl)
@@ -116,7 +119,10 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="C2")
-    ap.add_argument("--accumulate", choices=["staged", "fused"], default="staged")
+    ap.add_argument("--accumulate", choices=["staged", "fused"], default="fused",
+                    help="fused (default): weight-gradient epilogues fold w_i*g_i into the gradient buffer; "
+                         "staged: per-node staging vector + the accumulate kernel")
+    ap.add_argument("--no-alt", action="store_true", help="skip the timing of the other accumulate mode")
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-profile", action="store_true")
@@ -184,7 +190,7 @@ def main():
         "loss": loss,
     }
 
-    work = algorithmic_work(wl, P)
+    work = algorithmic_work(wl, P, fused=args.accumulate == "fused")
     total_bytes = sum(v[0] for v in work.values())
     total_flops = sum(v[1] for k, v in work.items() if k.startswith(("gemm", "attn")))
     floor_ms = max(total_bytes / (HBM_PEAK_GBS * 1e9), total_flops / (MFMA_BF16_PEAK_TFLOPS * 1e12)) * 1e3
@@ -210,6 +216,38 @@ def main():
                                    if kk in ("bound", "achieved", "peak", "unit", "frac")}
                                for k in kernels if k in work}
     eng.close()
+
+    if not args.no_alt:
+        # the other accumulate mode, same workload, for comparison (never `value`)
+        alt_mode = "staged" if args.accumulate == "fused" else "fused"
+        aflags = (vf.VF_FLAG_FUSED_ACCUMULATE if alt_mode == "fused" else 0) | \
+                 (vf.VF_FLAG_NO_GRAPH if args.no_graph else 0)
+        eng2 = vf.VirtualNodeStep(config_from_workload(wl, flags=aflags, stream=stream))
+        p2 = torch.from_numpy(theta).cuda()
+        for _ in range(args.warmup):
+            eng2.step(p2, xt, yt, sizes)
+        stream.synchronize()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(args.steps):
+            eng2.step(p2, xt, yt, sizes)
+        stream.synchronize()
+        torch.cuda.synchronize()
+        ams = (time.perf_counter() - t1) * 1e3 / args.steps
+        alt = {"accumulate": alt_mode, "ms_per_step": ams, "value": wl.batch / (ams * 1e-3)}
+        if alt_mode == "staged" and not args.no_kernel_profile:
+            eng2.profile_start()
+            for _ in range(args.steps):
+                eng2.step(p2, xt, yt, sizes)
+            pr = eng2.profile_stop()
+            w2 = algorithmic_work(wl, P, fused=False)
+            if "accumulate" in pr:
+                avg = pr["accumulate"]["total_ms"] / pr["accumulate"]["launches"]
+                alt["accumulate_kernel"] = {k: v for k, v in roofline_for("accumulate", w2, avg).items()
+                                            if k in ("bound", "achieved", "peak", "unit", "frac", "avg_launch_ms")}
+        out["alt"] = alt
+        eng2.close()
+        del p2
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, theta, x, y)
