@@ -124,6 +124,7 @@ def main():
                          "staged: per-node staging vector + the accumulate kernel")
     ap.add_argument("--no-alt", action="store_true", help="skip the timing of the other accumulate mode")
     ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--no-overlap", action="store_true", help="keep all kernels of a step on one stream")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-profile", action="store_true")
     args = ap.parse_args()
@@ -147,7 +148,8 @@ def main():
     x, y = I.make_batch(wl)
     stream = torch.cuda.Stream()
     flags = (vf.VF_FLAG_FUSED_ACCUMULATE if args.accumulate == "fused" else 0) | \
-            (vf.VF_FLAG_NO_GRAPH if args.no_graph else 0)
+            (vf.VF_FLAG_NO_GRAPH if args.no_graph else 0) | \
+            (vf.VF_FLAG_NO_OVERLAP if args.no_overlap else 0)
     eng = vf.VirtualNodeStep(config_from_workload(wl, flags=flags, stream=stream))
     P = eng.num_params
     params = torch.from_numpy(theta).cuda()
@@ -186,7 +188,7 @@ def main():
                    "global_batch": wl.batch, "virtual_nodes": wl.n_nodes,
                    "node_sizes": sizes if len(set(sizes)) > 1 else f"{wl.n_nodes}x{sizes[0]}",
                    "optimizer": wl.optimizer, "params": P, "accumulate": args.accumulate,
-                   "graph": not args.no_graph},
+                   "graph": not args.no_graph, "overlap": not args.no_overlap},
         "loss": loss,
     }
 

@@ -1,6 +1,8 @@
 // Row-wise and element-wise kernels of the pre-LayerNorm encoder: embedding gather and its
 // deterministic scatter-add backward, LayerNorm forward/backward, exact GELU, row softmax.
 // All statistics and reductions in fp32; one wavefront per row where a row is reduced.
+#include <algorithm>
+
 #include "vf_device.h"
 
 namespace vf {
@@ -37,25 +39,75 @@ __global__ __launch_bounds__(NT) void embed_pos_bwd_kernel(const float* __restri
 
 // One workgroup per token r.  The first token that carries a given id (the "leader") adds up
 // the rows of all tokens with that id in increasing token order and writes the table row;
-// the other workgroups exit.  No atomics: the sum order is fixed.
+// the other workgroups exit.  No atomics: the sum order is fixed.  The workgroup first marks
+// the matching tokens in an LDS bitmap (one coalesced scan of the ids), then every thread
+// walks the set bits for its columns.
+constexpr int MAX_TOK_WORDS = 2048;     // bitmap capacity: 65536 tokens per node
 __global__ __launch_bounds__(NT) void embed_tok_bwd_kernel(const int32_t* __restrict__ ids,
                                                            const float* __restrict__ dh, int R, int d,
                                                            int vocab, GradOut out) {
+  __shared__ uint32_t match[MAX_TOK_WORDS];
+  __shared__ int list[256];      // matching tokens of the current batch, in increasing order
+  __shared__ int nlist, next_word;
   __shared__ int earlier;
   const int r = blockIdx.x;
   const int id = clampi(ids[r], 0, vocab - 1);
+  const int nwords = (R + 31) / 32;
   if (threadIdx.x == 0) earlier = 0;
+  for (int wd = threadIdx.x; wd < nwords; wd += NT) match[wd] = 0u;
   __syncthreads();
-  int found = 0;
-  for (int q = threadIdx.x; q < r; q += NT) found |= (clampi(ids[q], 0, vocab - 1) == id);
-  if (found) earlier = 1;     // benign race: every writer stores 1
+  for (int q0 = 0; q0 < R; q0 += NT) {
+    const int q = q0 + threadIdx.x;
+    const bool hit = q < R && clampi(ids[q], 0, vocab - 1) == id;
+    if (hit) {
+      if (q < r) earlier = 1;                       // benign race: every writer stores 1
+      else atomicOr(&match[q >> 5], 1u << (q & 31));  // LDS bit set; order does not matter
+    }
+  }
   __syncthreads();
   if (earlier) return;
-  for (int c = threadIdx.x; c < d; c += NT) {
-    float s = dh[(int64_t)r * d + c];
-    for (int q = r + 1; q < R; ++q)
-      if (clampi(ids[q], 0, vocab - 1) == id) s += dh[(int64_t)q * d + c];
-    grad_store(out, (int64_t)id * d + c, s);
+  // Walk the bitmap in batches of up to 256 matches: thread 0 lists them in increasing order,
+  // then every thread adds its columns of those rows, 8 independent loads at a time.
+  constexpr int CPT = 4;                            // columns per thread: d <= 1024
+  float acc[CPT] = {0.f, 0.f, 0.f, 0.f};
+  if (threadIdx.x == 0) next_word = r >> 5;
+  __syncthreads();
+  while (true) {
+    if (threadIdx.x == 0) {
+      int n = 0, wd = next_word;
+      for (; wd < nwords && n <= 256 - 32; ++wd) {
+        uint32_t bits = match[wd];
+        while (bits) {
+          list[n++] = (wd << 5) + __ffs(bits) - 1;
+          bits &= bits - 1;
+        }
+      }
+      nlist = n;
+      next_word = wd;
+    }
+    __syncthreads();
+    const int n = nlist;
+    const bool last = next_word >= nwords;
+    for (int k0 = 0; k0 < n; k0 += 8) {
+#pragma unroll
+      for (int j = 0; j < CPT; ++j) {
+        const int c = threadIdx.x + NT * j;
+        if (c < d) {
+          float v[8];
+#pragma unroll
+          for (int u = 0; u < 8; ++u) v[u] = (k0 + u < n) ? dh[(int64_t)list[k0 + u] * d + c] : 0.f;
+#pragma unroll
+          for (int u = 0; u < 8; ++u) acc[j] += v[u];   // increasing token order; padding adds +0
+        }
+      }
+    }
+    __syncthreads();
+    if (last) break;
+  }
+#pragma unroll
+  for (int j = 0; j < CPT; ++j) {
+    const int c = threadIdx.x + NT * j;
+    if (c < d) grad_store(out, (int64_t)id * d + c, acc[j]);
   }
 }
 
@@ -100,6 +152,11 @@ __global__ __launch_bounds__(NT) void layernorm_fwd_kernel(const float* __restri
   if (lane == 0) { mean_out[r] = mean; rstd_out[r] = rstd; }
 }
 
+// Backward of LayerNorm for `rows_per_wg` consecutive rows per workgroup (one wavefront per
+// row at a time).  Besides dx it produces this row chunk's contribution to dgamma and dbeta
+// (partial[0][chunk][c], partial[1][chunk][c]) so that no second pass over dy and x is needed;
+// layernorm_param_finish adds the chunks in order.
+constexpr int LN_JMAX = 16;     // columns per lane held in registers: d <= 64*LN_JMAX
 __global__ __launch_bounds__(NT) void layernorm_bwd_kernel(const float* __restrict__ dyp, int nsplit,
                                                            int64_t slab, int64_t lddy,
                                                            const float* __restrict__ x, int64_t ldx,
@@ -109,70 +166,124 @@ __global__ __launch_bounds__(NT) void layernorm_bwd_kernel(const float* __restri
                                                            const float* __restrict__ mean_in,
                                                            const float* __restrict__ rstd_in,
                                                            const float* __restrict__ dres,
-                                                           float* __restrict__ dx, int64_t lddx) {
-  const int lane = threadIdx.x & 63;
-  const int r = blockIdx.x * WAVES + (threadIdx.x >> 6);
-  if (r >= R) return;
-  const int64_t orow = row_map ? row_map[r] : r;
-  const float* xr = x + orow * ldx;
-  const float mean = mean_in[r], rstd = rstd_in[r];
-  float s1 = 0.f, s2 = 0.f;
-  for (int c = lane; c < d; c += 64) {
-    float dy = dyp[(int64_t)r * lddy + c];
-    for (int s = 1; s < nsplit; ++s) dy += dyp[(int64_t)s * slab + (int64_t)r * lddy + c];
-    float g = gamma[c];
-    if (round_params) g = round_bf16(g);
-    float dxh = dy * g;
-    float xh = (xr[c] - mean) * rstd;
-    s1 += dxh;
-    s2 = fmaf(dxh, xh, s2);
+                                                           float* __restrict__ dx, int64_t lddx,
+                                                           int rows_per_wg, float* __restrict__ partial,
+                                                           int64_t pstride) {
+  extern __shared__ float wsum[];            // [2][WAVES][d]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int chunk = blockIdx.x;
+  const int rbeg = chunk * rows_per_wg;
+  const int rend = min(R, rbeg + rows_per_wg);
+  float pg[LN_JMAX], pb[LN_JMAX];
+#pragma unroll
+  for (int j = 0; j < LN_JMAX; ++j) { pg[j] = 0.f; pb[j] = 0.f; }
+  for (int r = rbeg + wave; r < rend; r += WAVES) {
+    const int64_t orow = row_map ? row_map[r] : r;
+    const float* xr = x + orow * ldx;
+    const float mean = mean_in[r], rstd = rstd_in[r];
+    float dyv[LN_JMAX], xhv[LN_JMAX];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int j = 0; j < LN_JMAX; ++j) {
+      const int c = lane + 64 * j;
+      dyv[j] = 0.f; xhv[j] = 0.f;
+      if (c < d) {
+        float dy = dyp[(int64_t)r * lddy + c];
+        for (int s = 1; s < nsplit; ++s) dy += dyp[(int64_t)s * slab + (int64_t)r * lddy + c];
+        float g = gamma[c];
+        if (round_params) g = round_bf16(g);
+        const float xh = (xr[c] - mean) * rstd;
+        dyv[j] = dy; xhv[j] = xh;
+        const float dxh = dy * g;
+        s1 += dxh;
+        s2 = fmaf(dxh, xh, s2);
+        pg[j] = fmaf(dy, xh, pg[j]);
+        pb[j] += dy;
+      }
+    }
+    s1 = wave_sum(s1) / (float)d;
+    s2 = wave_sum(s2) / (float)d;
+#pragma unroll
+    for (int j = 0; j < LN_JMAX; ++j) {
+      const int c = lane + 64 * j;
+      if (c < d) {
+        float g = gamma[c];
+        if (round_params) g = round_bf16(g);
+        float v = (dyv[j] * g - s1 - xhv[j] * s2) * rstd;
+        if (dres) v += dres[orow * lddx + c];
+        dx[orow * lddx + c] = v;
+      }
+    }
   }
-  s1 = wave_sum(s1) / (float)d;
-  s2 = wave_sum(s2) / (float)d;
-  for (int c = lane; c < d; c += 64) {
-    float dy = dyp[(int64_t)r * lddy + c];
-    for (int s = 1; s < nsplit; ++s) dy += dyp[(int64_t)s * slab + (int64_t)r * lddy + c];
-    float g = gamma[c];
-    if (round_params) g = round_bf16(g);
-    float xh = (xr[c] - mean) * rstd;
-    float v = (dy * g - s1 - xh * s2) * rstd;
-    if (dres) v += dres[orow * lddx + c];
-    dx[orow * lddx + c] = v;
+  if (!partial) return;
+#pragma unroll
+  for (int j = 0; j < LN_JMAX; ++j) {
+    const int c = lane + 64 * j;
+    if (c < d) { wsum[(0 * WAVES + wave) * d + c] = pg[j]; wsum[(1 * WAVES + wave) * d + c] = pb[j]; }
+  }
+  __syncthreads();
+  for (int c = threadIdx.x; c < d; c += NT) {
+    float a = 0.f, b = 0.f;
+#pragma unroll
+    for (int wv = 0; wv < WAVES; ++wv) { a += wsum[(0 * WAVES + wv) * d + c]; b += wsum[(1 * WAVES + wv) * d + c]; }
+    partial[(int64_t)chunk * d + c] = a;
+    partial[pstride + (int64_t)chunk * d + c] = b;
   }
 }
 
-constexpr int CB = 32, RL = 8;
-__global__ __launch_bounds__(NT) void layernorm_param_bwd_kernel(const float* __restrict__ dyp, int nsplit,
-                                                                 int64_t slab, int64_t lddy,
-                                                                 const float* __restrict__ x, int64_t ldx,
-                                                                 const int32_t* __restrict__ row_map,
-                                                                 int R, int d,
-                                                                 const float* __restrict__ mean_in,
-                                                                 const float* __restrict__ rstd_in,
-                                                                 GradOut gout_g, GradOut gout_b) {
-  __shared__ float red[2][RL][CB + 1];
-  const int tx = threadIdx.x % CB, ty = threadIdx.x / CB;
-  const int c = blockIdx.x * CB + tx;
-  float sg = 0.f, sb = 0.f;
+// out_g[c] = sum over chunks of partial[0][chunk][c]; out_b likewise from partial[1].
+// 64 columns per workgroup, 4 chunk lanes (lane q adds chunks q, q+4, ...), combined in lane order.
+__global__ __launch_bounds__(NT) void layernorm_param_finish_kernel(const float* __restrict__ partial,
+                                                                    int64_t pstride, int nchunk, int d,
+                                                                    GradOut gout_g, GradOut gout_b) {
+  __shared__ float red[2][4][64];
+  const int tx = threadIdx.x & 63, q = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + tx;
+  float a = 0.f, b = 0.f;
   if (c < d)
-    for (int r = ty; r < R; r += RL) {
-      float dy = dyp[(int64_t)r * lddy + c];
-      for (int s = 1; s < nsplit; ++s) dy += dyp[(int64_t)s * slab + (int64_t)r * lddy + c];
-      const int64_t xrow = row_map ? row_map[r] : r;
-      float xh = (x[xrow * ldx + c] - mean_in[r]) * rstd_in[r];
-      sg = fmaf(dy, xh, sg);
-      sb += dy;
-    }
-  red[0][ty][tx] = sg;
-  red[1][ty][tx] = sb;
+    for (int k = q; k < nchunk; k += 4) { a += partial[(int64_t)k * d + c]; b += partial[pstride + (int64_t)k * d + c]; }
+  red[0][q][tx] = a;
+  red[1][q][tx] = b;
   __syncthreads();
-  if (ty == 0 && c < d) {
-    float a = 0.f, b = 0.f;
-#pragma unroll
-    for (int i = 0; i < RL; ++i) { a += red[0][i][tx]; b += red[1][i][tx]; }
-    grad_store(gout_g, c, a);
-    grad_store(gout_b, c, b);
+  if (q == 0 && c < d) {
+    grad_store(gout_g, c, (red[0][0][tx] + red[0][1][tx]) + (red[0][2][tx] + red[0][3][tx]));
+    grad_store(gout_b, c, (red[1][0][tx] + red[1][1][tx]) + (red[1][2][tx] + red[1][3][tx]));
   }
+}
+
+// Column sums over many rows in two steps: partial sums per row chunk, then the chunks in order.
+template <typename T>
+__global__ __launch_bounds__(NT) void colsum_partial_kernel(const T* __restrict__ xin, int64_t ld, int R, int C,
+                                                            int rows_per_chunk, float* __restrict__ partial) {
+  __shared__ float red[8][33];
+  const int tx = threadIdx.x % 32, ty = threadIdx.x / 32;
+  const int c = blockIdx.x * 32 + tx;
+  const int rbeg = blockIdx.y * rows_per_chunk, rend = min(R, rbeg + rows_per_chunk);
+  float s = 0.f;
+  if (c < C)
+    for (int r = rbeg + ty; r < rend; r += 8) s += load_f(&xin[(int64_t)r * ld + c]);
+  red[ty][tx] = s;
+  __syncthreads();
+  if (ty == 0 && c < C) {
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) t += red[i][tx];
+    partial[(int64_t)blockIdx.y * C + c] = t;
+  }
+}
+
+// 64 columns per workgroup, 4 chunk lanes (lane q adds chunks q, q+4, ...), combined in lane order.
+__global__ __launch_bounds__(NT) void colsum_finish_kernel(const float* __restrict__ partial, int nchunk, int C,
+                                                           GradOut out) {
+  __shared__ float red[4][64];
+  const int tx = threadIdx.x & 63, q = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + tx;
+  float a = 0.f;
+  if (c < C)
+    for (int k = q; k < nchunk; k += 4) a += partial[(int64_t)k * C + c];
+  red[q][tx] = a;
+  __syncthreads();
+  if (q == 0 && c < C) grad_store(out, c, (red[0][tx] + red[1][tx]) + (red[2][tx] + red[3][tx]));
 }
 
 // ---- GELU (exact) ---------------------------------------------------------------------------
@@ -295,21 +406,34 @@ int launch_layernorm_fwd(const float* x, int64_t ldx, const int32_t* row_map, in
 int launch_layernorm_bwd(const float* dyp, int nsplit, int64_t slab, int64_t lddy, const float* x,
                          int64_t ldx, const int32_t* row_map, int R, int d, const float* gamma,
                          int round_params, const float* mean, const float* rstd, const float* dres,
-                         float* dx, int64_t lddx, hipStream_t s) {
-  if (R <= 0 || d <= 0 || nsplit < 1) return VF_EINVAL;
-  layernorm_bwd_kernel<<<(R + WAVES - 1) / WAVES, NT, 0, s>>>(dyp, nsplit, slab, lddy, x, ldx, row_map, R, d,
-                                                              gamma, round_params, mean, rstd, dres, dx,
-                                                              lddx);
+                         float* dx, int64_t lddx, float* scratch, GradOut gout_g, GradOut gout_b,
+                         hipStream_t s) {
+  if (R <= 0 || d <= 0 || nsplit < 1 || d > 64 * LN_JMAX || !scratch) return VF_EINVAL;
+  const int rows_per_wg = std::max(WAVES, (R + kLnChunks - 1) / kLnChunks);
+  const int nchunk = (R + rows_per_wg - 1) / rows_per_wg;
+  const int64_t pstride = (int64_t)kLnChunks * d;
+  const size_t lds = (size_t)2 * WAVES * d * sizeof(float);
+  layernorm_bwd_kernel<<<nchunk, NT, lds, s>>>(dyp, nsplit, slab, lddy, x, ldx, row_map, R, d, gamma,
+                                               round_params, mean, rstd, dres, dx, lddx, rows_per_wg,
+                                               scratch, pstride);
+  VF_LAUNCH_CHECK();
+  layernorm_param_finish_kernel<<<(d + 63) / 64, NT, 0, s>>>(scratch, pstride, nchunk, d, gout_g, gout_b);
   VF_LAUNCH_CHECK();
   return VF_OK;
 }
 
-int launch_layernorm_param_bwd(const float* dyp, int nsplit, int64_t slab, int64_t lddy, const float* x,
-                               int64_t ldx, const int32_t* row_map, int R, int d, const float* mean,
-                               const float* rstd, GradOut gout_g, GradOut gout_b, hipStream_t s) {
-  if (R <= 0 || d <= 0 || nsplit < 1) return VF_EINVAL;
-  layernorm_param_bwd_kernel<<<(d + CB - 1) / CB, NT, 0, s>>>(dyp, nsplit, slab, lddy, x, ldx, row_map, R, d,
-                                                              mean, rstd, gout_g, gout_b);
+int launch_colsum_rows(const void* x, int64_t ld, int x_is_bf16, int R, int C, float* scratch, GradOut out,
+                       hipStream_t s) {
+  if (R <= 0 || C <= 0 || !scratch) return VF_EINVAL;
+  const int rows_per_chunk = std::max(32, (R + kReduceChunks - 1) / kReduceChunks);
+  const int nchunk = (R + rows_per_chunk - 1) / rows_per_chunk;
+  dim3 grid((C + 31) / 32, nchunk);
+  if (x_is_bf16)
+    colsum_partial_kernel<bf16_t><<<grid, NT, 0, s>>>(static_cast<const bf16_t*>(x), ld, R, C, rows_per_chunk, scratch);
+  else
+    colsum_partial_kernel<float><<<grid, NT, 0, s>>>(static_cast<const float*>(x), ld, R, C, rows_per_chunk, scratch);
+  VF_LAUNCH_CHECK();
+  colsum_finish_kernel<<<(C + 63) / 64, NT, 0, s>>>(scratch, nchunk, C, out);
   VF_LAUNCH_CHECK();
   return VF_OK;
 }

@@ -149,29 +149,206 @@ __global__ __launch_bounds__(NT) void gemm_bf16_kernel(const bf16_t* __restrict_
   }
 }
 
-// Short contraction (K <= 2*BK = 128: the weight gradient of a node of up to 128 rows).  The
-// cost of such a product is one trip to memory for the operands and the write (or
-// read-modify-write) of the output, so everything is issued at once: both stages of operand
-// loads and, when the epilogue adds into C (fused fold into the gradient buffer), the old C
-// values as well; then one LDS barrier, the MFMAs, and the stores.
-template <int BM, int BN, int WGM, int WGN>
-__global__ __launch_bounds__(NT) void gemm_bf16_shortk_kernel(const bf16_t* __restrict__ A, int64_t lda,
-                                                              const bf16_t* __restrict__ B, int64_t ldb,
-                                                              int M, int N, int K, Epilogue ep) {
+// ---- software-pipelined variant ---------------------------------------------------------------
+// Same tiling as gemm_bf16_kernel, but NS stages of global loads are kept in flight in
+// registers.  A virtual node's products are short and memory-latency bound, so the depth of
+// this ring is what fills the memory system.  The loads are issued with inline assembly and
+// waited for with explicit s_waitcnt vmcnt(n): loads complete in order, so "all but the newest
+// n" is exactly "the stage about to be written to LDS has landed".  (The compiler's own wait
+// insertion falls back to vmcnt(0) across the loop's control flow, which serialises the ring.)
+// Every load uses an in-bounds address (row and contraction offset clamped); what lies outside
+// the matrix is zeroed when the stage is written to LDS.  LDS is double buffered: one barrier
+// per stage.
+__device__ __forceinline__ u32x4 load_vec_async(const bf16_t* p) {
+  u32x4 v;
+  asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(v) : "v"(p) : "memory");
+  return v;
+}
+template <int N>
+__device__ __forceinline__ void wait_loads_but() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+__device__ __forceinline__ u32x4 mask_vec(u32x4 v, bool row_ok, int k, int kend) {
+  const int valid = row_ok ? kend - k : 0;
+  if (valid >= 8) return v;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int e = 2 * j;
+    const uint32_t keep = (e + 1 < valid) ? 0xffffffffu : (e < valid ? 0x0000ffffu : 0u);
+    v[j] &= keep;
+  }
+  return v;
+}
+
+template <int BM, int BN, int WGM, int WGN, int NS>
+__global__ __launch_bounds__(NT) void gemm_bf16_pipe_kernel(const bf16_t* __restrict__ A, int64_t lda,
+                                                            const bf16_t* __restrict__ B, int64_t ldb,
+                                                            int M, int N, int K, int kchunk,
+                                                            int64_t slab_stride, Epilogue ep) {
   static_assert(WGM * WGN == 4, "four waves");
   constexpr int WTM = BM / WGM, WTN = BN / WGN;
   constexpr int TM = WTM / 32, TN = WTN / 32;
-  constexpr int KT = 2 * BK;                  // 128
-  constexpr int LD2 = KT + 8;                 // padded LDS row
-  constexpr int A_VECS = BM * (KT / 8) / NT;  // 16-byte vectors per thread
-  constexpr int B_VECS = BN * (KT / 8) / NT;
+  constexpr int A_VECS = BM * (BK / 8) / NT;
+  constexpr int B_VECS = BN * (BK / 8) / NT;
+  constexpr int VPS = A_VECS + B_VECS;           // loads per thread per stage
+  static_assert(NS >= 2 && NS <= 4 && (NS - 1) * VPS < 60, "ring depth");
 
-  __shared__ __attribute__((aligned(16))) bf16_t As[BM * LD2];
-  __shared__ __attribute__((aligned(16))) bf16_t Bs[BN * LD2];
+  __shared__ __attribute__((aligned(16))) bf16_t As[2][BM * LDS_LD];
+  __shared__ __attribute__((aligned(16))) bf16_t Bs[2][BN * LDS_LD];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
+  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  const int kbeg = blockIdx.z * kchunk;
+  const int kend = min(K, kbeg + kchunk);
+  const int nstage = kend > kbeg ? (kend - kbeg + BK - 1) / BK : 0;
+  const int vcol = (tid & 7) * 8;
+  const int vrow = tid >> 3;
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  // row base pointers, clamped into the matrix
+  const bf16_t* arow[A_VECS];
+  const bf16_t* brow[B_VECS];
+  bool aok[A_VECS], bok[B_VECS];
+#pragma unroll
+  for (int i = 0; i < A_VECS; ++i) {
+    const int r = m0 + vrow + 32 * i;
+    aok[i] = r < M;
+    arow[i] = A + (int64_t)min(r, M - 1) * lda;
+  }
+#pragma unroll
+  for (int i = 0; i < B_VECS; ++i) {
+    const int r = n0 + vrow + 32 * i;
+    bok[i] = r < N;
+    brow[i] = B + (int64_t)min(r, N - 1) * ldb;
+  }
+  const int klast = ((K - 1) / 8) * 8;           // last 16-byte vector that starts inside a row
+
+  u32x4 ra[NS][A_VECS], rb[NS][B_VECS];
+  auto issue = [&](int slot, int stage) {
+    const int k = min(kbeg + stage * BK + vcol, klast);
+#pragma unroll
+    for (int i = 0; i < A_VECS; ++i) ra[slot][i] = load_vec_async(arow[i] + k);
+#pragma unroll
+    for (int i = 0; i < B_VECS; ++i) rb[slot][i] = load_vec_async(brow[i] + k);
+  };
+  auto to_lds = [&](int slot, int stage, int buf) {
+    const int k = kbeg + stage * BK + vcol;
+#pragma unroll
+    for (int i = 0; i < A_VECS; ++i)
+      *reinterpret_cast<u32x4*>(&As[buf][(vrow + 32 * i) * LDS_LD + vcol]) = mask_vec(ra[slot][i], aok[i], k, kend);
+#pragma unroll
+    for (int i = 0; i < B_VECS; ++i)
+      *reinterpret_cast<u32x4*>(&Bs[buf][(vrow + 32 * i) * LDS_LD + vcol]) = mask_vec(rb[slot][i], bok[i], k, kend);
+  };
+  auto compute = [&](int buf) {
+#pragma unroll
+    for (int kk = 0; kk < BK; kk += 16) {
+      bf16x8 a[TM], b[TN];
+      const int koff = kk + (lane >> 5) * 8;
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+        a[i] = *reinterpret_cast<const bf16x8*>(&As[buf][(wm * WTM + i * 32 + (lane & 31)) * LDS_LD + koff]);
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        b[j] = *reinterpret_cast<const bf16x8*>(&Bs[buf][(wn * WTN + j * 32 + (lane & 31)) * LDS_LD + koff]);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+  };
+
+  if (nstage > 0) {
+    // prologue: the first NS stages (stage indices past the end repeat the last address: their
+    // data is never used, they only keep the count of outstanding loads uniform)
+#pragma unroll
+    for (int s = 0; s < NS; ++s) issue(s, min(s, nstage - 1));
+    for (int base = 0; base < nstage; base += NS) {
+#pragma unroll
+      for (int s = 0; s < NS; ++s) {
+        const int it = base + s;
+        if (it < nstage) {
+          // outstanding: stages it .. it+NS-1 (NS of them); stage `it` is the oldest
+          wait_loads_but<(NS - 1) * VPS>();
+          to_lds(s, it, it & 1);
+          // refill the slot; past the end this re-reads the last stage's lines (cache hits)
+          issue(s, min(it + NS, nstage - 1));
+          __syncthreads();
+          compute(it & 1);
+        }
+      }
+    }
+    wait_loads_but<0>();   // drain the padding loads before the registers are reused
+  }
+
+  const bool first_slice = blockIdx.z == 0;
+  char* cbase = static_cast<char*>(ep.C) +
+                (int64_t)blockIdx.z * slab_stride * (ep.c_is_bf16 ? 2 : 4);
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int n = n0 + wn * WTN + j * 32 + (lane & 31);
+      if (n >= N) continue;
+      float bias = 0.f;
+      if (ep.bias && first_slice) {
+        bias = ep.bias[n];
+        if (ep.bias_round_bf16) bias = round_bf16(bias);
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = m0 + wm * WTM + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        if (m >= M) continue;
+        float addend = bias;
+        if (ep.R) addend = fmaf(ep.beta, ep.R[(int64_t)m * ep.ldr + n], bias);
+        float v = fmaf(ep.alpha, acc[i][j][r], addend);
+        if (ep.c_is_bf16) reinterpret_cast<bf16_t*>(cbase)[(int64_t)m * ep.ldc + n] = f32_to_bf16(v);
+        else              reinterpret_cast<float*>(cbase)[(int64_t)m * ep.ldc + n] = v;
+      }
+    }
+  }
+}
+
+// Short contraction (K <= 2*BK = 128: the weight gradient of a node of up to 128 rows).  The
+// cost of such a product is one trip to memory for the operands and the write (or
+// read-modify-write) of the fp32 output, so everything is issued at once: both stages of
+// operand loads and, when the epilogue adds into C (fused fold into the gradient buffer), the
+// old C values as well; then one LDS barrier and the MFMAs.  The accumulators are then passed
+// through LDS so that every lane reads/writes 16 contiguous bytes of C: a wavefront touches
+// four full 256-byte row segments per instruction instead of two 128-byte ones.
+// Requires fp32 C, 16-byte aligned, ldc (and ldr) multiples of 4, N a multiple of 4.
+template <int BM, int BN>
+__global__ __launch_bounds__(NT) void gemm_bf16_shortk_kernel(const bf16_t* __restrict__ A, int64_t lda,
+                                                              const bf16_t* __restrict__ B, int64_t ldb,
+                                                              int M, int N, int K, Epilogue ep) {
+  static_assert(BM == 64 && BN == 64, "2x2 waves of 32x32");
+  constexpr int KT = 2 * BK;                  // 128
+  constexpr int LD2 = KT + 8;                 // padded LDS row of the operands
+  constexpr int LDC = BN + 4;                 // padded fp32 row of the staged output tile
+  constexpr int A_VECS = BM * (KT / 8) / NT;  // 16-byte vectors per thread
+  constexpr int B_VECS = BN * (KT / 8) / NT;
+  constexpr int C_VECS = BM * (BN / 4) / NT;  // float4 per thread of the output tile
+
+  __shared__ __attribute__((aligned(16))) char smem[(BM + BN) * LD2 * 2];
+  bf16_t* As = reinterpret_cast<bf16_t*>(smem);
+  bf16_t* Bs = As + BM * LD2;
+  float* Ct = reinterpret_cast<float*>(smem);   // reused after the MFMAs
+  static_assert(BM * LDC * 4 <= (BM + BN) * LD2 * 2, "output tile fits in the operand buffers");
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
   const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
   const int vcol = (tid & 15) * 8;   // 16 vectors per 128-wide row
   const int vrow = tid >> 4;         // 0..15
@@ -182,20 +359,18 @@ __global__ __launch_bounds__(NT) void gemm_bf16_shortk_kernel(const bf16_t* __re
 #pragma unroll
   for (int i = 0; i < B_VECS; ++i) rb[i] = load_vec(B, ldb, n0 + vrow + 16 * i, N, vcol, K);
 
-  // old C values for a read-modify-write epilogue, requested before anything waits
-  float oldc[TM][TN][16];
+  // this thread's float4 pieces of the output tile: row crow + 16*i, columns ccol..ccol+3
+  const int ccol = (tid & 15) * 4;
+  const int crow = tid >> 4;
+  const bool col_ok = n0 + ccol < N;           // N % 4 == 0: a float4 is all in or all out
+  float4 oldc[C_VECS];
   if (ep.R) {
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        const int n = n0 + wn * WTN + j * 32 + (lane & 31);
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int m = m0 + wm * WTM + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-          oldc[i][j][r] = (m < M && n < N) ? ep.R[(int64_t)m * ep.ldr + n] : 0.f;
-        }
-      }
+    for (int i = 0; i < C_VECS; ++i) {
+      const int m = m0 + crow + 16 * i;
+      oldc[i] = (col_ok && m < M) ? *reinterpret_cast<const float4*>(&ep.R[(int64_t)m * ep.ldr + n0 + ccol])
+                                  : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
   }
 
 #pragma unroll
@@ -204,55 +379,51 @@ __global__ __launch_bounds__(NT) void gemm_bf16_shortk_kernel(const bf16_t* __re
   for (int i = 0; i < B_VECS; ++i) *reinterpret_cast<u32x4*>(&Bs[(vrow + 16 * i) * LD2 + vcol]) = rb[i];
   __syncthreads();
 
-  f32x16 acc[TM][TN];
+  f32x16 acc;
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
   const int ksteps = (K + 15) / 16;            // 16-wide MFMA steps that hold any data
 #pragma unroll
   for (int ks = 0; ks < KT / 16; ++ks) {
     if (ks < ksteps) {
-      bf16x8 a[TM], b[TN];
       const int koff = ks * 16 + (lane >> 5) * 8;
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-        a[i] = *reinterpret_cast<const bf16x8*>(&As[(wm * WTM + i * 32 + (lane & 31)) * LD2 + koff]);
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-        b[j] = *reinterpret_cast<const bf16x8*>(&Bs[(wn * WTN + j * 32 + (lane & 31)) * LD2 + koff]);
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+      bf16x8 a = *reinterpret_cast<const bf16x8*>(&As[(wm * 32 + (lane & 31)) * LD2 + koff]);
+      bf16x8 b = *reinterpret_cast<const bf16x8*>(&Bs[(wn * 32 + (lane & 31)) * LD2 + koff]);
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0);
     }
   }
+  __syncthreads();                             // operands no longer needed: reuse LDS for the tile
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int row = wm * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+    Ct[row * LDC + wn * 32 + (lane & 31)] = acc[r];
+  }
+  __syncthreads();
 
-#pragma unroll
-  for (int i = 0; i < TM; ++i) {
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int n = n0 + wn * WTN + j * 32 + (lane & 31);
-      if (n >= N) continue;
-      float bias = 0.f;
-      if (ep.bias) {
-        bias = ep.bias[n];
-        if (ep.bias_round_bf16) bias = round_bf16(bias);
-      }
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wm * WTM + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        if (m >= M) continue;
-        float addend = bias;
-        if (ep.R) addend = fmaf(ep.beta, oldc[i][j][r], bias);
-        float v = fmaf(ep.alpha, acc[i][j][r], addend);
-        if (ep.c_is_bf16) static_cast<bf16_t*>(ep.C)[(int64_t)m * ep.ldc + n] = f32_to_bf16(v);
-        else              static_cast<float*>(ep.C)[(int64_t)m * ep.ldc + n] = v;
-      }
+  float4 bias4 = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (ep.bias && col_ok) {
+    bias4 = *reinterpret_cast<const float4*>(&ep.bias[n0 + ccol]);
+    if (ep.bias_round_bf16) {
+      bias4.x = round_bf16(bias4.x); bias4.y = round_bf16(bias4.y);
+      bias4.z = round_bf16(bias4.z); bias4.w = round_bf16(bias4.w);
     }
+  }
+  float* C = static_cast<float*>(ep.C);
+#pragma unroll
+  for (int i = 0; i < C_VECS; ++i) {
+    const int row = crow + 16 * i;
+    const int m = m0 + row;
+    if (!col_ok || m >= M) continue;
+    const float4 a4 = *reinterpret_cast<const float4*>(&Ct[row * LDC + ccol]);
+    float4 add = bias4;
+    if (ep.R) {
+      add.x = fmaf(ep.beta, oldc[i].x, bias4.x); add.y = fmaf(ep.beta, oldc[i].y, bias4.y);
+      add.z = fmaf(ep.beta, oldc[i].z, bias4.z); add.w = fmaf(ep.beta, oldc[i].w, bias4.w);
+    }
+    float4 v;
+    v.x = fmaf(ep.alpha, a4.x, add.x); v.y = fmaf(ep.alpha, a4.y, add.y);
+    v.z = fmaf(ep.alpha, a4.z, add.z); v.w = fmaf(ep.alpha, a4.w, add.w);
+    *reinterpret_cast<float4*>(&C[(int64_t)m * ep.ldc + n0 + ccol]) = v;
   }
 }
 
@@ -260,12 +431,25 @@ struct Shape {
   const bf16_t* A; int64_t lda; const bf16_t* B; int64_t ldb; int M, N, K, nsplit; int64_t slab;
 };
 
+bool shortk_enabled();
+int pipe_depth();   // 0 = plain kernel, 2..4 = ring depth of the pipelined kernel
+
 template <int BM, int BN, int WGM, int WGN>
 int launch_cfg(const Shape& g, const Epilogue& ep, hipStream_t s) {
   int kchunk = ((g.K + g.nsplit - 1) / g.nsplit + BK - 1) / BK * BK;
   dim3 grid((g.N + BN - 1) / BN, (g.M + BM - 1) / BM, g.nsplit);
-  gemm_bf16_kernel<BM, BN, WGM, WGN><<<grid, NT, 0, s>>>(g.A, g.lda, g.B, g.ldb, g.M, g.N, g.K, kchunk,
-                                                         g.slab, ep);
+  constexpr int VPS = (BM + BN) * (BK / 8) / NT;
+  const int depth = pipe_depth();
+#define VF_PIPE(NS)                                                                               \
+  gemm_bf16_pipe_kernel<BM, BN, WGM, WGN, NS><<<grid, NT, 0, s>>>(g.A, g.lda, g.B, g.ldb, g.M, g.N, \
+                                                                  g.K, kchunk, g.slab, ep)
+  if (depth >= 4 && 3 * VPS < 60 && VPS <= 8) VF_PIPE(4);
+  else if (depth >= 3 && VPS <= 8) VF_PIPE(3);
+  else if (depth >= 2) VF_PIPE(2);
+  else
+    gemm_bf16_kernel<BM, BN, WGM, WGN><<<grid, NT, 0, s>>>(g.A, g.lda, g.B, g.ldb, g.M, g.N, g.K, kchunk,
+                                                           g.slab, ep);
+#undef VF_PIPE
   VF_LAUNCH_CHECK();
   return VF_OK;
 }
@@ -288,6 +472,25 @@ int forced_tile() {
   return cached;
 }
 
+bool shortk_enabled() {   // tuning aid: VF_GEMM_SHORTK=0 sends weight gradients to the general kernel
+  static int cached = -1;
+  if (cached < 0) {
+    const char* e = std::getenv("VF_GEMM_SHORTK");
+    cached = (e && e[0] == '0') ? 0 : 1;
+  }
+  return cached != 0;
+}
+
+int pipe_depth() {
+  static int cached = -1;
+  if (cached < 0) {
+    const char* e = std::getenv("VF_GEMM_PIPE");   // tuning aid; 3 measured best on the node shapes
+    cached = e ? std::atoi(e) : 3;
+    if (cached < 0 || cached > 4) cached = 0;
+  }
+  return cached;
+}
+
 }  // namespace
 
 // Compute-bound shapes take the big tile; everything else (few rows, or a short contraction
@@ -295,14 +498,15 @@ int forced_tile() {
 static bool use_big_tile(int M, int N, int K) { return M >= 1024 && N >= 1024 && K >= 512; }
 
 int gemm_bf16_pick_split(int M, int N, int K) {
-  // Measured on the node-sized products (128 x 4096 x 4096 and relatives): about four
-  // 64x64 workgroups per compute unit, slices no shorter than 3 LDS stages.
+  // Measured on the node-sized products (128 x 4096 x 4096 and relatives) with the
+  // pipelined kernel: about two 64x64 workgroups per compute unit, slices no shorter than
+  // 3 LDS stages.
   if (use_big_tile(M, N, K)) return 1;
   int bm = M <= 32 ? 32 : 64;
   int bn = M <= 32 ? 128 : 64;
   int64_t tiles = (int64_t)((M + bm - 1) / bm) * ((N + bn - 1) / bn);
   int split = 1;
-  while (tiles * split < 1024 && K / (split * 2) >= 3 * BK && split < 32) split *= 2;
+  while (tiles * split < 512 && K / (split * 2) >= 3 * BK && split < 32) split *= 2;
   return split;
 }
 
@@ -323,11 +527,14 @@ int launch_gemm_bf16(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb,
     case 6: return launch_cfg<128, 32, 4, 1>(g, ep, s);
     default: break;
   }
-  // short contraction with a read-modify-write epilogue: single-trip kernel (measured faster
-  // there; the plain-store case does better with the smaller LDS footprint of the general one)
-  if (K <= 2 * BK && nsplit == 1 && ep.R && M > 32 && N > 32) {
+  // short contraction into an fp32 matrix (weight gradients): single-trip kernel
+  const bool vec_ok = !ep.c_is_bf16 && (N & 3) == 0 && (ep.ldc & 3) == 0 &&
+                      (reinterpret_cast<uintptr_t>(ep.C) & 15) == 0 &&
+                      (!ep.R || ((ep.ldr & 3) == 0 && (reinterpret_cast<uintptr_t>(ep.R) & 15) == 0)) &&
+                      (!ep.bias || (reinterpret_cast<uintptr_t>(ep.bias) & 15) == 0);
+  if (K <= 2 * BK && nsplit == 1 && vec_ok && M > 32 && N > 32 && shortk_enabled()) {
     dim3 grid((N + 63) / 64, (M + 63) / 64);
-    gemm_bf16_shortk_kernel<64, 64, 2, 2><<<grid, NT, 0, s>>>(A, lda, B, ldb, M, N, K, ep);
+    gemm_bf16_shortk_kernel<64, 64><<<grid, NT, 0, s>>>(A, lda, B, ldb, M, N, K, ep);
     VF_LAUNCH_CHECK();
     return VF_OK;
   }

@@ -21,14 +21,40 @@ __device__ __forceinline__ float block_reduce(float v, bool is_max, float* red) 
 // memory is read once; otherwise the reduced logits are re-read from z.
 constexpr int CPT = 4;
 
-template <typename T, bool SMALL>
+// Node-loss bookkeeping done by the last workgroup of a softmax launch to finish.
+struct LossTail {
+  float* node_loss;        // [max_nodes] or null (then a separate loss_reduce launch follows)
+  float* total;
+  unsigned int* ticket;    // zero between launches; the last workgroup resets it
+  float w;
+  int node;
+};
+
+template <int NS>
+__device__ __forceinline__ float slab_sum(const float* zp, int nsplit, int64_t slab, int64_t idx) {
+  if (NS > 0) {
+    float v[NS > 0 ? NS : 1];
+#pragma unroll
+    for (int s = 0; s < NS; ++s) v[s] = zp[(int64_t)s * slab + idx];
+    float t = v[0];
+#pragma unroll
+    for (int s = 1; s < NS; ++s) t += v[s];
+    return t;
+  }
+  float t = zp[idx];
+  for (int s = 1; s < nsplit; ++s) t += zp[(int64_t)s * slab + idx];
+  return t;
+}
+
+template <typename T, bool SMALL, int NS>
 __global__ __launch_bounds__(256) void softmax_xent_kernel(const float* zp, int nsplit,
                                                            int64_t slab, int64_t ldzp,
                                                            float* z, int64_t ldz,
                                                            const int32_t* __restrict__ labels, int R,
                                                            int C, float* __restrict__ rowloss,
                                                            T* __restrict__ dz, int64_t lddz,
-                                                           bf16_t* __restrict__ dzT, int64_t ldt) {
+                                                           bf16_t* __restrict__ dzT, int64_t ldt,
+                                                           LossTail tail) {
   __shared__ float red[4];
   __shared__ float zlabel;
   const int r = blockIdx.x;
@@ -43,9 +69,7 @@ __global__ __launch_bounds__(256) void softmax_xent_kernel(const float* zp, int 
       const int c = threadIdx.x + 256 * k;
       v[k] = -INFINITY;
       if (c < C) {
-        const int64_t idx = (int64_t)r * ldzp + c;
-        float t = zp[idx];
-        for (int s = 1; s < nsplit; ++s) t += zp[(int64_t)s * slab + idx];   // slabs in order
+        const float t = slab_sum<NS>(zp, nsplit, slab, (int64_t)r * ldzp + c);   // slabs in order
         v[k] = t;
         zr[c] = t;
         if (c == label) zlabel = t;
@@ -54,9 +78,7 @@ __global__ __launch_bounds__(256) void softmax_xent_kernel(const float* zp, int 
     }
   } else {
     for (int c = threadIdx.x; c < C; c += 256) {
-      const int64_t idx = (int64_t)r * ldzp + c;
-      float t = zp[idx];
-      for (int s = 1; s < nsplit; ++s) t += zp[(int64_t)s * slab + idx];
+      const float t = slab_sum<NS>(zp, nsplit, slab, (int64_t)r * ldzp + c);
       zr[c] = t;
       if (c == label) zlabel = t;
       mx = fmaxf(mx, t);
@@ -95,6 +117,27 @@ __global__ __launch_bounds__(256) void softmax_xent_kernel(const float* zp, int 
     }
   }
   if (threadIdx.x == 0) rowloss[r] = logf(sum) + mx - zlabel;   // zlabel: visible after the reductions' barriers
+  if (tail.node_loss == nullptr) return;
+  // The last workgroup to get here adds up the row losses in row order (so the result does
+  // not depend on which workgroup that is) and resets the ticket for the next launch.
+  __shared__ unsigned int last;
+  if (threadIdx.x == 0) {
+    __threadfence();                                     // rowloss[r] before the ticket
+    last = atomicAdd(tail.ticket, 1u) == (unsigned int)(R - 1);
+  }
+  __syncthreads();
+  if (!last) return;
+  __threadfence();
+  float s = 0.f;
+  for (int q = threadIdx.x; q < R; q += 256) s += __builtin_nontemporal_load(&rowloss[q]);
+  s = block_reduce(s, false, red);
+  if (threadIdx.x == 0) {
+    const float L = s / (float)R;
+    tail.node_loss[tail.node] = L;
+    const float old = tail.node == 0 ? 0.f : *tail.total;
+    *tail.total = fmaf(tail.w, L, old);
+    *tail.ticket = 0u;
+  }
 }
 
 __global__ __launch_bounds__(256) void loss_reduce_kernel(const float* __restrict__ rowloss, int R,
@@ -117,16 +160,29 @@ __global__ __launch_bounds__(256) void loss_reduce_kernel(const float* __restric
 
 int launch_softmax_xent(const float* zp, int nsplit, int64_t slab, int64_t ldzp, float* z, int64_t ldz,
                         const int32_t* labels, int R, int C, float* rowloss, void* dz, int64_t lddz,
-                        int dz_is_bf16, bf16_t* dzT, int64_t ldt, hipStream_t s) {
+                        int dz_is_bf16, bf16_t* dzT, int64_t ldt, float w, int node, float* node_loss,
+                        float* total, unsigned int* ticket, hipStream_t s) {
   if (R <= 0 || C <= 0 || nsplit < 1) return VF_EINVAL;
   if (dzT && !dz_is_bf16) return VF_EINVAL;
+  if (node_loss && (!total || !ticket)) return VF_EINVAL;
   const bool small = C <= 256 * CPT;
-#define VF_SX(TT, SM)                                                                              \
-  softmax_xent_kernel<TT, SM><<<R, 256, 0, s>>>(zp, nsplit, slab, ldzp, z, ldz, labels, R, C, rowloss, \
-                                                static_cast<TT*>(dz), lddz, dzT, ldt)
-  if (dz_is_bf16) { if (small) VF_SX(bf16_t, true); else VF_SX(bf16_t, false); }
-  else            { if (small) VF_SX(float, true);  else VF_SX(float, false); }
-#undef VF_SX
+  LossTail tail{node_loss, total, ticket, w, node};
+#define VF_SX3(TT, SM, NS)                                                                         \
+  softmax_xent_kernel<TT, SM, NS><<<R, 256, 0, s>>>(zp, nsplit, slab, ldzp, z, ldz, labels, R, C,  \
+                                                    rowloss, static_cast<TT*>(dz), lddz, dzT, ldt, tail)
+#define VF_SX2(TT, SM)                                                                             \
+  switch (nsplit) {                                                                                \
+    case 1: VF_SX3(TT, SM, 1); break;                                                              \
+    case 2: VF_SX3(TT, SM, 2); break;                                                              \
+    case 4: VF_SX3(TT, SM, 4); break;                                                              \
+    case 8: VF_SX3(TT, SM, 8); break;                                                              \
+    case 16: VF_SX3(TT, SM, 16); break;                                                            \
+    default: VF_SX3(TT, SM, 0); break;                                                             \
+  }
+  if (dz_is_bf16) { if (small) { VF_SX2(bf16_t, true) } else { VF_SX2(bf16_t, false) } }
+  else            { if (small) { VF_SX2(float, true) }  else { VF_SX2(float, false) } }
+#undef VF_SX2
+#undef VF_SX3
   VF_LAUNCH_CHECK();
   return VF_OK;
 }

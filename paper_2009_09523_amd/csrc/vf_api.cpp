@@ -49,6 +49,8 @@ int validate_config(const vf_config& c) {
         c.vocab < 1 || c.n_masked < 1)
       return VF_EINVAL;
     if (c.d_model % c.n_heads) return VF_EINVAL;
+    if (c.d_model > 1024) return VF_EINVAL;                       // LayerNorm kernels keep a row in registers
+    if ((int64_t)c.max_node_size * c.seq_len > 65536) return VF_EINVAL;   // token bitmap of the embedding backward
     if (c.n_masked > c.seq_len) return VF_EINVAL;
     if (c.dtype == VF_BF16 && ((c.d_model % 8) || (c.d_ffn % 8) || ((c.d_model / c.n_heads) % 8)))
       return VF_EINVAL;
@@ -57,12 +59,101 @@ int validate_config(const vf_config& c) {
   return VF_EINVAL;
 }
 
-// Enqueue everything of one step except the optimizer update.
-int enqueue_nodes(Ctx& c, const StepArgs& a) {
-  VF_TRY(c.model->prepare(c, a.params));
-  for (int i = 0; i < a.V; ++i) VF_TRY(c.model->run_node(c, a, i));
+bool graph_matches(const Ctx& c, const StepArgs& a) {
+  return !c.graphs.empty() && c.graph_params == a.params && c.graph_x == a.x && c.graph_y == a.y &&
+         c.graph_sizes == a.sizes;
+}
+
+void release_streams(Ctx& c) {
+  for (int k = 0; k < 2; ++k)
+    if (c.side_done[k]) { (void)hipEventDestroy(c.side_done[k]); c.side_done[k] = nullptr; }
+  if (c.main_done) { (void)hipEventDestroy(c.main_done); c.main_done = nullptr; }
+  if (c.side) { (void)hipStreamDestroy(c.side); c.side = nullptr; }
+}
+
+void drop_graph(Ctx& c) {
+  for (hipGraphExec_t g : c.graphs)
+    if (g) (void)hipGraphExecDestroy(g);
+  c.graphs.clear();
+}
+
+// The three kinds of launch sequence of a step; `part` 0 = weight preparation, 1 = main(i),
+// 2 = side(i).  Each runs on one stream.
+int enqueue_part(Ctx& c, const StepArgs& a, int part, int node, hipStream_t st) {
+  if (part == 0) return c.model->prepare(c, a.params, st);
+  if (part == 1) return c.model->run_node_main(c, a, node, st);
+  return c.model->run_node_side(c, a, node, st);
+}
+
+// Record one part into a graph (captured on the main stream; replayed on whichever stream).
+int capture_part(Ctx& c, const StepArgs& a, int part, int node, hipGraphExec_t* out) {
+  hipGraph_t graph = nullptr;
+  VF_HIP(hipStreamBeginCapture(c.stream, hipStreamCaptureModeThreadLocal));
+  int rc = enqueue_part(c, a, part, node, c.stream);
+  hipError_t e = hipStreamEndCapture(c.stream, &graph);
+  if (rc != VF_OK) {
+    if (graph) (void)hipGraphDestroy(graph);
+    return rc;
+  }
+  if (e != hipSuccess) {
+    set_last_error("hipStreamEndCapture", e, __FILE__, __LINE__);
+    return VF_EDEVICE;
+  }
+  e = hipGraphInstantiate(out, graph, nullptr, nullptr, 0);
+  (void)hipGraphDestroy(graph);
+  if (e != hipSuccess) {
+    *out = nullptr;
+    set_last_error("hipGraphInstantiate", e, __FILE__, __LINE__);
+    return VF_EDEVICE;
+  }
+  return VF_OK;
+}
+
+int capture_graphs(Ctx& c, const StepArgs& a) {
+  drop_graph(c);
+  c.graphs.assign((size_t)1 + 2 * a.V, nullptr);
+  int rc = capture_part(c, a, 0, 0, &c.graphs[0]);
+  for (int i = 0; i < a.V && rc == VF_OK; ++i) {
+    rc = capture_part(c, a, 1, i, &c.graphs[1 + 2 * i]);
+    if (rc == VF_OK) rc = capture_part(c, a, 2, i, &c.graphs[2 + 2 * i]);
+  }
+  if (rc != VF_OK) {
+    drop_graph(c);
+    return rc;
+  }
+  c.graph_params = a.params; c.graph_x = a.x; c.graph_y = a.y; c.graph_sizes = a.sizes;
+  return VF_OK;
+}
+
+// Run one part: replay its graph, or launch its kernels one by one.
+int run_part(Ctx& c, const StepArgs& a, bool use_graph, int part, int node, hipStream_t st) {
+  if (!use_graph) return enqueue_part(c, a, part, node, st);
+  hipGraphExec_t g = c.graphs[part == 0 ? 0 : (size_t)part + 2 * node];
+  VF_HIP(hipGraphLaunch(g, st));
+  return VF_OK;
+}
+
+// Everything of one step except the optimizer update (Section 3.2 steps 1-3): the nodes one
+// after another on the main stream, each node's weight gradients (and fold) beside the next
+// node's passes on the side stream.
+int enqueue_nodes(Ctx& c, const StepArgs& a, bool use_graph) {
+  const bool ov = c.overlapping();
+  hipStream_t side = ov ? c.side : c.stream;
+  VF_TRY(run_part(c, a, use_graph, 0, 0, c.stream));
+  for (int i = 0; i < a.V; ++i) {
+    const int p = i & 1;
+    // copy p of the side part's operands was last read by side(i-2)
+    if (ov && i >= 2) VF_HIP(hipStreamWaitEvent(c.stream, c.side_done[p], 0));
+    VF_TRY(run_part(c, a, use_graph, 1, i, c.stream));
+    if (ov) {
+      VF_HIP(hipEventRecord(c.main_done, c.stream));
+      VF_HIP(hipStreamWaitEvent(side, c.main_done, 0));
+    }
+    VF_TRY(run_part(c, a, use_graph, 2, i, side));
+    if (ov) VF_HIP(hipEventRecord(c.side_done[p], side));
+  }
   // join: the side stream is in order, so its latest event covers all nodes
-  if (c.overlapping()) VF_HIP(hipStreamWaitEvent(c.stream, c.side_done[(a.V - 1) & 1], 0));
+  if (ov) VF_HIP(hipStreamWaitEvent(c.stream, c.side_done[(a.V - 1) & 1], 0));
   return VF_OK;
 }
 
@@ -77,52 +168,6 @@ int enqueue_update(Ctx& c, float* params) {
   const float inv_c2 = (float)(1.0 / (1.0 - std::pow((double)f.beta2, t)));
   VF_K(c, "optimizer", launch_adam(params, c.opt0, c.opt1, c.gbuf, f.lr, f.beta1, f.beta2, f.adam_eps,
                                    inv_c1, inv_c2, c.P, c.stream));
-  return VF_OK;
-}
-
-bool graph_matches(const Ctx& c, const StepArgs& a) {
-  return c.graph_exec && c.graph_params == a.params && c.graph_x == a.x && c.graph_y == a.y &&
-         c.graph_sizes == a.sizes;
-}
-
-void release_streams(Ctx& c) {
-  for (hipEvent_t ev : c.order_events) (void)hipEventDestroy(ev);
-  c.order_events.clear();
-  for (int k = 0; k < 2; ++k)
-    if (c.side_done[k]) { (void)hipEventDestroy(c.side_done[k]); c.side_done[k] = nullptr; }
-  if (c.side) { (void)hipStreamDestroy(c.side); c.side = nullptr; }
-}
-
-void drop_graph(Ctx& c) {
-  if (c.graph_exec) {
-    (void)hipGraphExecDestroy(c.graph_exec);
-    c.graph_exec = nullptr;
-  }
-}
-
-// Record the node sequence of this step into a graph and instantiate it.
-int capture_graph(Ctx& c, const StepArgs& a) {
-  drop_graph(c);
-  hipGraph_t graph = nullptr;
-  VF_HIP(hipStreamBeginCapture(c.stream, hipStreamCaptureModeThreadLocal));
-  int rc = enqueue_nodes(c, a);
-  hipError_t e = hipStreamEndCapture(c.stream, &graph);
-  if (rc != VF_OK) {
-    if (graph) (void)hipGraphDestroy(graph);
-    return rc;
-  }
-  if (e != hipSuccess) {
-    set_last_error("hipStreamEndCapture", e, __FILE__, __LINE__);
-    return VF_EDEVICE;
-  }
-  e = hipGraphInstantiate(&c.graph_exec, graph, nullptr, nullptr, 0);
-  (void)hipGraphDestroy(graph);
-  if (e != hipSuccess) {
-    c.graph_exec = nullptr;
-    set_last_error("hipGraphInstantiate", e, __FILE__, __LINE__);
-    return VF_EDEVICE;
-  }
-  c.graph_params = a.params; c.graph_x = a.x; c.graph_y = a.y; c.graph_sizes = a.sizes;
   return VF_OK;
 }
 
@@ -186,11 +231,7 @@ int vf_init(const vf_config* cfg, vf_ctx** out) {
   if (c.overlap) {
     e = hipStreamCreateWithFlags(&c.side, hipStreamNonBlocking);
     for (int k = 0; k < 2 && e == hipSuccess; ++k) e = hipEventCreateWithFlags(&c.side_done[k], hipEventDisableTiming);
-    for (int k = 0; k < 32 && e == hipSuccess; ++k) {
-      hipEvent_t ev = nullptr;
-      e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
-      if (e == hipSuccess) c.order_events.push_back(ev);
-    }
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&c.main_done, hipEventDisableTiming);
     if (e != hipSuccess) {
       set_last_error("side stream set-up", e, __FILE__, __LINE__);
       release_streams(c);
@@ -210,6 +251,7 @@ int vf_init(const vf_config* cfg, vf_ctx** out) {
   arena.request(&c.rowloss, loss_rows);
   arena.request(&c.node_loss, (size_t)cfg->max_nodes);
   arena.request(&c.loss_total, 1);
+  arena.request(&c.loss_ticket, 1);
   c.model->request_buffers(arena);
   c.arena_bytes = arena.total();
   e = hipMalloc(reinterpret_cast<void**>(&c.arena), c.arena_bytes);
@@ -254,12 +296,9 @@ int vf_step(vf_ctx* h, void* params, const void* batch_x, const int32_t* batch_y
   a.w.resize(V);
   vf_partition(node_sizes, V, B, a.off.data(), a.w.data());
 
-  if ((c.cfg.flags & VF_FLAG_NO_GRAPH) || c.prof.enabled) {
-    VF_TRY(enqueue_nodes(c, a));
-  } else {
-    if (!graph_matches(c, a)) VF_TRY(capture_graph(c, a));
-    VF_HIP(hipGraphLaunch(c.graph_exec, c.stream));
-  }
+  const bool use_graph = !((c.cfg.flags & VF_FLAG_NO_GRAPH) || c.prof.enabled);
+  if (use_graph && !graph_matches(c, a)) VF_TRY(capture_graphs(c, a));
+  VF_TRY(enqueue_nodes(c, a, use_graph));
   VF_TRY(enqueue_update(c, a.params));
   c.steps += 1;
   c.last_V = V;

@@ -47,12 +47,17 @@ class Model {
   virtual int64_t num_params() const = 0;
   virtual void request_buffers(Arena& a) = 0;
   // Refresh whatever the passes read instead of the fp32 master (bf16 weight copies).
-  virtual int prepare(Ctx& c, const float* params) = 0;
-  // Forward + backward of node `i` (rows off..off+b): loss bookkeeping and gradients
-  // through `gout(flat offset)`.
-  // (in staged mode it ends with c.fold(i, ...)).
-  virtual int run_node(Ctx& c, const StepArgs& a, int i) = 0;
-  // True if run_node can put weight gradients and the fold on the context's side stream.
+  virtual int prepare(Ctx& c, const float* params, hipStream_t st) = 0;
+  // Node `i` (rows off..off+b) in two parts, each a plain sequence of launches on ONE stream:
+  //   main part: forward pass, loss bookkeeping, and the input-gradient chain of the backward
+  //              pass (everything the next node's passes have to wait for);
+  //   side part: what only the gradient buffer waits for -- weight gradients and, in staged
+  //              mode, the fold c.fold(i, ...).  It reads operands the main part left behind.
+  // The executor runs main(i) then side(i); with overlap the side part goes to the second
+  // stream and runs beside main(i+1), so a model that supports overlap keeps two copies of
+  // the operands the side part reads (nodes alternate; side(i) is complete before main(i+2)).
+  virtual int run_node_main(Ctx& c, const StepArgs& a, int i, hipStream_t st) = 0;
+  virtual int run_node_side(Ctx& c, const StepArgs& a, int i, hipStream_t st) = 0;
   virtual bool supports_overlap() const { return false; }
 };
 
@@ -94,6 +99,7 @@ struct Ctx {
   float* rowloss = nullptr;   // per-row losses of the node in flight
   float* node_loss = nullptr; // [max_nodes]
   float* loss_total = nullptr;
+  unsigned int* loss_ticket = nullptr;   // arrival counter of the fused loss bookkeeping
 
   int64_t steps = 0;
   int32_t last_V = 0;
@@ -105,23 +111,15 @@ struct Ctx {
   bool overlap = false;
   float* gstage2 = nullptr;               // second staging vector (nodes alternate) when overlapping
   hipEvent_t side_done[2] = {nullptr, nullptr};
-  std::vector<hipEvent_t> order_events;   // rotating pool for cross-stream ordering
-  size_t order_next = 0;
+  hipEvent_t main_done = nullptr;
 
   bool overlapping() const { return overlap && !prof.enabled; }
-  hipStream_t side_stream() const { return overlapping() ? side : stream; }
-  // Everything enqueued so far on `from` happens before anything enqueued later on `to`.
-  int order(hipStream_t from, hipStream_t to) {
-    if (from == to) return VF_OK;
-    hipEvent_t e = order_events[order_next++ % order_events.size()];
-    VF_HIP(hipEventRecord(e, from));
-    VF_HIP(hipStreamWaitEvent(to, e, 0));
-    return VF_OK;
-  }
-  float* stage_for(int node) const { return (overlapping() && (node & 1)) ? gstage2 : gstage; }
+  float* stage_for(int node) const { return (overlap && (node & 1)) ? gstage2 : gstage; }
 
-  // graph replay of the node sequence
-  hipGraphExec_t graph_exec = nullptr;
+  // Graph replay: one captured launch sequence per part (weight preparation, main(i), side(i)),
+  // each a single-stream chain, so replay keeps the two streams apart exactly as eager
+  // launches do.
+  std::vector<hipGraphExec_t> graphs;     // [0] prepare, [1+2i] main(i), [2+2i] side(i)
   std::vector<int32_t> graph_sizes;
   const void* graph_params = nullptr;
   const void* graph_x = nullptr;

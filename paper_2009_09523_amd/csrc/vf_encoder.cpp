@@ -98,6 +98,7 @@ class Encoder final : public Model {
     act(&du_, R * f_);
     act(&dqkv_, R * 3 * d_);
     a.request(&drows_, (size_t)out_split_max_ * Rm * d_);
+    a.request(&red_, std::max((size_t)kReduceChunks * std::max(std::max(V_, 3 * d_), f_), (size_t)2 * kLnChunks * d_));
     if (bf16_) {
       act(&cast_, R * d_);
       const size_t maxdim = (size_t)std::max(std::max(d_, f_), 3 * d_);
@@ -110,16 +111,21 @@ class Encoder final : public Model {
     }
   }
 
-  int prepare(Ctx& c, const float* params) override {
+  int prepare(Ctx& c, const float* params, hipStream_t st) override {
     if (!bf16_) return VF_OK;
     for (Lin* L : lins_)
-      VF_K(c, "cast_weight", launch_cast_weight(params + L->w_off, L->K, L->N, L->wnat, L->ldn, L->wtr,
-                                                L->ldt, c.stream));
+      VF_KS(c, st, "cast_weight", launch_cast_weight(params + L->w_off, L->K, L->N, L->wnat, L->ldn, L->wtr,
+                                                     L->ldt, st));
     return VF_OK;
   }
 
-  int run_node(Ctx& c, const StepArgs& s, int i) override {
-    hipStream_t st = c.stream;
+  // The encoder keeps its whole node on one stream: the side part is only the fold.
+  int run_node_side(Ctx& c, const StepArgs& s, int i, hipStream_t st) override {
+    return c.fold(i, s.w[i], st);
+  }
+
+  int run_node_main(Ctx& c, const StepArgs& s, int i, hipStream_t st) override {
+    stream_ = st;
     const int b = s.sizes[i];
     const int64_t row0 = s.off[i];
     const float w = s.w[i];
@@ -157,21 +163,19 @@ class Encoder final : public Model {
                                                   cfg_.ln_eps, rows_, d_, bf16_, meanf_, rstdf_, st));
     VF_TRY(lin_fwd(c, "gemm_head", out_, P, rows_, d_, Rm, logits_, ldV_, false, nullptr));
     VF_K(c, "softmax_xent", launch_softmax_xent(logits_, 1, 0, ldV_, logits_, ldV_, labels_, Rm, V_, c.rowloss,
-                                                dlogits_, ldV_, bf16_, nullptr, 0, st));
-    VF_K(c, "loss_reduce", launch_loss_reduce(c.rowloss, Rm, w, i, c.node_loss, c.loss_total, st));
+                                                dlogits_, ldV_, bf16_, nullptr, 0, w, i, c.node_loss, c.loss_total,
+                                                c.loss_ticket, st));
 
     // ---- backward: output head -----------------------------------------------------------
-    VF_K(c, "colsum", launch_colsum(dlogits_, ldV_, bf16_, Rm, V_, c.gout(out_.b_off, w, i), st));
+    VF_K(c, "colsum", launch_colsum_rows(dlogits_, ldV_, bf16_, Rm, V_, red_, c.gout(out_.b_off, w, i), st));
     VF_TRY(lin_bwd_w(c, "gemm_head_wgrad", out_, rows_, d_, dlogits_, ldV_, Rm, c.gout(out_.w_off, w, i)));
     int osplit = 1;
     VF_TRY(lin_bwd_x(c, "gemm_head_dgrad", out_, P, dlogits_, ldV_, Rm, drows_, d_, &osplit));
     const int64_t oslab = (int64_t)Rm * d_;
     VF_K(c, "fill", launch_fill_f32(dh_buf_, 0.f, (int64_t)R * d_, st));
-    VF_K(c, "layernorm_param_bwd",
-         launch_layernorm_param_bwd(drows_, osplit, oslab, d_, hlast_, d_, rowidx_, Rm, d_, meanf_, rstdf_,
-                                    c.gout(lnf_g_, w, i), c.gout(lnf_b_, w, i), st));
     VF_K(c, "layernorm_bwd", launch_layernorm_bwd(drows_, osplit, oslab, d_, hlast_, d_, rowidx_, Rm, d_,
-                                                  P + lnf_g_, bf16_, meanf_, rstdf_, nullptr, dh_buf_, d_, st));
+                                                  P + lnf_g_, bf16_, meanf_, rstdf_, nullptr, dh_buf_, d_, red_,
+                                                  c.gout(lnf_g_, w, i), c.gout(lnf_b_, w, i), st));
 
     // ---- backward: blocks -------------------------------------------------------------------
     for (int l = nl - 1; l >= 0; --l) {
@@ -182,25 +186,23 @@ class Encoder final : public Model {
         VF_K(c, "cast", launch_cast_bf16(dh_buf_, d_, static_cast<bf16_t*>(cast_), d_, R, d_, st));
         dh_op = cast_;
       }
-      VF_K(c, "colsum", launch_colsum(dh_buf_, d_, 0, R, d_, c.gout(B.w2.b_off, w, i), st));
+      VF_K(c, "colsum", launch_colsum_rows(dh_buf_, d_, 0, R, d_, red_, c.gout(B.w2.b_off, w, i), st));
       VF_TRY(lin_bwd_w(c, "gemm_wgrad", B.w2, B.g, f_, dh_op, d_, R, c.gout(B.w2.w_off, w, i)));
       VF_TRY(lin_bwd_x(c, "gemm_dgrad", B.w2, P, dh_op, d_, R, tmp32_, f_, nullptr));
       VF_K(c, "gelu_bwd", launch_gelu_bwd(tmp32_, B.u, du_, bf16_, (int64_t)R * f_, st));
-      VF_K(c, "colsum", launch_colsum(du_, f_, bf16_, R, f_, c.gout(B.w1.b_off, w, i), st));
+      VF_K(c, "colsum", launch_colsum_rows(du_, f_, bf16_, R, f_, red_, c.gout(B.w1.b_off, w, i), st));
       VF_TRY(lin_bwd_w(c, "gemm_wgrad", B.w1, B.f, d_, du_, f_, R, c.gout(B.w1.w_off, w, i)));
       VF_TRY(lin_bwd_x(c, "gemm_dgrad", B.w1, P, du_, f_, R, tmp32_, d_, nullptr));
-      VF_K(c, "layernorm_param_bwd",
-           launch_layernorm_param_bwd(tmp32_, 1, 0, d_, B.hmid, d_, nullptr, R, d_, B.mean2, B.rstd2,
-                                      c.gout(B.ln2_g, w, i), c.gout(B.ln2_b, w, i), st));
       VF_K(c, "layernorm_bwd", launch_layernorm_bwd(tmp32_, 1, 0, d_, B.hmid, d_, nullptr, R, d_, P + B.ln2_g,
-                                                    bf16_, B.mean2, B.rstd2, dh_buf_, dmid_, d_, st));
+                                                    bf16_, B.mean2, B.rstd2, dh_buf_, dmid_, d_, red_,
+                                                    c.gout(B.ln2_g, w, i), c.gout(B.ln2_b, w, i), st));
       // attention
       const void* dmid_op = dmid_;
       if (bf16_) {
         VF_K(c, "cast", launch_cast_bf16(dmid_, d_, static_cast<bf16_t*>(cast_), d_, R, d_, st));
         dmid_op = cast_;
       }
-      VF_K(c, "colsum", launch_colsum(dmid_, d_, 0, R, d_, c.gout(B.o.b_off, w, i), st));
+      VF_K(c, "colsum", launch_colsum_rows(dmid_, d_, 0, R, d_, red_, c.gout(B.o.b_off, w, i), st));
       VF_TRY(lin_bwd_w(c, "gemm_wgrad", B.o, B.om, d_, dmid_op, d_, R, c.gout(B.o.w_off, w, i)));
       VF_TRY(lin_bwd_x(c, "gemm_dgrad", B.o, P, dmid_op, d_, R, tmp32_, d_, nullptr));   // d(om), fp32
       // dP = dO V^T ; dV = P^T dO ; dS = P (dP - rowsum(dP P)) ; dQ = dS K / sqrt(dh) ; dK = dS^T Q / sqrt(dh)
@@ -213,21 +215,19 @@ class Encoder final : public Model {
                                           T_, dh_, T_, heads, nh_, scale, st));
       VF_K(c, "attn_bwd_dk", launch_bgemm(score_mat(scores_, 1, false, true), kt_mat(B.qkv_act, 0), qkv_mat(dqkv_, 1),
                                           T_, dh_, T_, heads, nh_, scale, st));
-      VF_K(c, "colsum", launch_colsum(dqkv_, 3 * d_, bf16_, R, 3 * d_, c.gout(B.qkv.b_off, w, i), st));
+      VF_K(c, "colsum", launch_colsum_rows(dqkv_, 3 * d_, bf16_, R, 3 * d_, red_, c.gout(B.qkv.b_off, w, i), st));
       VF_TRY(lin_bwd_w(c, "gemm_wgrad", B.qkv, B.a, d_, dqkv_, 3 * d_, R, c.gout(B.qkv.w_off, w, i)));
       VF_TRY(lin_bwd_x(c, "gemm_dgrad", B.qkv, P, dqkv_, 3 * d_, R, tmp32_, d_, nullptr));
-      VF_K(c, "layernorm_param_bwd",
-           launch_layernorm_param_bwd(tmp32_, 1, 0, d_, B.hin, d_, nullptr, R, d_, B.mean1, B.rstd1,
-                                      c.gout(B.ln1_g, w, i), c.gout(B.ln1_b, w, i), st));
       VF_K(c, "layernorm_bwd", launch_layernorm_bwd(tmp32_, 1, 0, d_, B.hin, d_, nullptr, R, d_, P + B.ln1_g,
-                                                    bf16_, B.mean1, B.rstd1, dmid_, dh_buf_, d_, st));
+                                                    bf16_, B.mean1, B.rstd1, dmid_, dh_buf_, d_, red_,
+                                                    c.gout(B.ln1_g, w, i), c.gout(B.ln1_b, w, i), st));
     }
     // ---- backward: embeddings ----------------------------------------------------------------
     VF_K(c, "embed_bwd", launch_embed_pos_bwd(dh_buf_, b, T_, d_, c.gout(pos_off_, w, i), st));
     GradOut gt = c.gout(tok_off_, w, i);
     if (!c.fused || i == 0) VF_K(c, "fill", launch_fill_f32(gt.dst, 0.f, (int64_t)V_ * d_, st));
     VF_K(c, "embed_bwd", launch_embed_tok_bwd(ids, dh_buf_, R, d_, V_, gt, st));
-    return c.fold(i, w, st);
+    return VF_OK;
   }
 
  private:
@@ -267,10 +267,10 @@ class Encoder final : public Model {
     if (residual) { ep.R = residual; ep.ldr = ldo; ep.beta = 1.f; }
     if (bf16_)
       VF_K(c, tag, launch_gemm_bf16(static_cast<const bf16_t*>(in), ldin, L.wtr, L.ldt, R, L.N, L.K, 1, 0, ep,
-                                    c.stream));
+                                    stream_));
     else
       VF_K(c, tag, launch_gemm_f32(static_cast<const float*>(in), ldin, 1, P + L.w_off, 1, L.N, R, L.N, L.K, ep,
-                                   c.stream));
+                                   stream_));
     return VF_OK;
   }
 
@@ -282,12 +282,12 @@ class Encoder final : public Model {
     if (go.accumulate) { ep.R = go.dst; ep.ldr = L.N; ep.beta = 1.f; }
     if (bf16_) {
       const int64_t ldr = round8(R);
-      VF_K(c, "transpose", launch_transpose_bf16(static_cast<const bf16_t*>(in), ldin, tA_, ldr, R, L.K, c.stream));
-      VF_K(c, "transpose", launch_transpose_bf16(static_cast<const bf16_t*>(dy), lddy, tB_, ldr, R, L.N, c.stream));
-      VF_K(c, tag, launch_gemm_bf16(tA_, ldr, tB_, ldr, L.K, L.N, R, 1, 0, ep, c.stream));
+      VF_K(c, "transpose", launch_transpose_bf16(static_cast<const bf16_t*>(in), ldin, tA_, ldr, R, L.K, stream_));
+      VF_K(c, "transpose", launch_transpose_bf16(static_cast<const bf16_t*>(dy), lddy, tB_, ldr, R, L.N, stream_));
+      VF_K(c, tag, launch_gemm_bf16(tA_, ldr, tB_, ldr, L.K, L.N, R, 1, 0, ep, stream_));
     } else {
       VF_K(c, tag, launch_gemm_f32(static_cast<const float*>(in), 1, ldin, static_cast<const float*>(dy), 1, lddy,
-                                   L.K, L.N, R, ep, c.stream));
+                                   L.K, L.N, R, ep, stream_));
     }
     return VF_OK;
   }
@@ -304,16 +304,17 @@ class Encoder final : public Model {
         *split = ns;
       }
       VF_K(c, tag, launch_gemm_bf16(static_cast<const bf16_t*>(dy), lddy, L.wnat, L.ldn, R, L.K, L.N, ns,
-                                    (int64_t)R * lddx, ep, c.stream));
+                                    (int64_t)R * lddx, ep, stream_));
     } else {
       if (split) *split = 1;
       VF_K(c, tag, launch_gemm_f32(static_cast<const float*>(dy), lddy, 1, P + L.w_off, L.N, 1, R, L.K, L.N, ep,
-                                   c.stream));
+                                   stream_));
     }
     return VF_OK;
   }
 
   vf_config cfg_;
+  hipStream_t stream_ = nullptr;        // stream of the part being enqueued
   bool bf16_ = false;
   int d_ = 0, f_ = 0, T_ = 0, V_ = 0, m_ = 0, nh_ = 0, dh_ = 0;
   int64_t P_ = 0, tok_off_ = 0, pos_off_ = 0, lnf_g_ = 0, lnf_b_ = 0;
@@ -332,6 +333,7 @@ class Encoder final : public Model {
   float *dh_buf_ = nullptr, *dmid_ = nullptr, *tmp32_ = nullptr;
   void *du_ = nullptr, *dqkv_ = nullptr, *cast_ = nullptr;
   float* drows_ = nullptr;
+  float* red_ = nullptr;                // scratch of the row-chunked reductions
   bf16_t *tA_ = nullptr, *tB_ = nullptr;
 };
 

@@ -128,9 +128,13 @@ int launch_colsum(const void* x, int64_t ld, int x_is_bf16, int R, int C, GradOu
 // of the logits (summed into z, which may be slab 0 itself):
 //   rowloss[r] = logsumexp(z_r) - z_r[label_r];  dz[r,c] = (softmax(z_r)[c] - [c==label_r]) / R
 // dzT (optional, bf16 only): the same gradient transposed, [C, ldt].
+// With node_loss != null the launch also does the node's loss bookkeeping (what
+// launch_loss_reduce does) in its last workgroup to finish; `ticket` is a zero-initialised
+// counter the kernel leaves at zero.
 int launch_softmax_xent(const float* zp, int nsplit, int64_t slab, int64_t ldzp, float* z, int64_t ldz,
                         const int32_t* labels, int R, int C, float* rowloss, void* dz, int64_t lddz,
-                        int dz_is_bf16, bf16_t* dzT, int64_t ldt, hipStream_t s);
+                        int dz_is_bf16, bf16_t* dzT, int64_t ldt, float w, int node, float* node_loss,
+                        float* total, unsigned int* ticket, hipStream_t s);
 // node_loss[i] = (1/R) sum_r rowloss[r];  total = (i == 0 ? 0 : total) + w * node_loss[i]
 int launch_loss_reduce(const float* rowloss, int R, float w, int node, float* node_loss,
                        float* total, hipStream_t s);
@@ -163,15 +167,22 @@ int launch_extract_masked(const int32_t* y, int nseq, int m, int T, int vocab, i
 int launch_layernorm_fwd(const float* x, int64_t ldx, const int32_t* row_map, int R, int d,
                          const float* gamma, const float* beta, int round_params, float eps, void* y,
                          int64_t ldy, int y_is_bf16, float* mean, float* rstd, hipStream_t s);
-// dx[orow] = LNbwd(sum of dy slabs)[r] (+ dres[orow]),  orow = row_map ? row_map[r] : r
+// Row-chunked reductions: column sums use a scratch of kReduceChunks * columns floats, the
+// LayerNorm backward one of 2 * kLnChunks * d floats.
+constexpr int kReduceChunks = 64;
+constexpr int kLnChunks = 256;
+// dx[orow] = LNbwd(sum of dy slabs)[r] (+ dres[orow]),  orow = row_map ? row_map[r] : r; also
+// dgamma[c] = sum_r dy[r,c]*xhat[r,c] and dbeta[c] = sum_r dy[r,c] through GradOut (row chunks
+// added in order).  d <= 1024.  scratch: 2 * kLnChunks * d floats.
 int launch_layernorm_bwd(const float* dyp, int nsplit, int64_t slab, int64_t lddy, const float* x,
                          int64_t ldx, const int32_t* row_map, int R, int d, const float* gamma,
                          int round_params, const float* mean, const float* rstd, const float* dres,
-                         float* dx, int64_t lddx, hipStream_t s);
-// dgamma[c] = sum_r dy[r,c]*xhat[r,c];  dbeta[c] = sum_r dy[r,c]
-int launch_layernorm_param_bwd(const float* dyp, int nsplit, int64_t slab, int64_t lddy, const float* x,
-                               int64_t ldx, const int32_t* row_map, int R, int d, const float* mean,
-                               const float* rstd, GradOut gout_g, GradOut gout_b, hipStream_t s);
+                         float* dx, int64_t lddx, float* scratch, GradOut gout_g, GradOut gout_b,
+                         hipStream_t s);
+// out[c] = sum_r x[r*ld + c] for many rows: partial sums per row chunk, then the chunks in order.
+// scratch: kReduceChunks * C floats.
+int launch_colsum_rows(const void* x, int64_t ld, int x_is_bf16, int R, int C, float* scratch, GradOut out,
+                       hipStream_t s);
 // exact GELU: g = 0.5 u (1 + erf(u / sqrt 2))
 int launch_gelu_fwd(const void* u, void* g, int is_bf16, int64_t n, hipStream_t s);
 // du = dg * (Phi(u) + u phi(u));  dg fp32, u and du T

@@ -110,19 +110,17 @@ class Mlp final : public Model {
     a.request(&slab_, (size_t)slab_elems_);
   }
 
-  int prepare(Ctx& c, const float* params) override {
+  int prepare(Ctx& c, const float* params, hipStream_t st) override {
     if (!bf16_) return VF_OK;
     for (Layer& L : layers_)
-      VF_K(c, "cast_weight", launch_cast_weight(params + L.w_off, L.K, L.N, L.wnat, L.ldn, L.wtr, L.ldt, c.stream));
+      VF_KS(c, st, "cast_weight", launch_cast_weight(params + L.w_off, L.K, L.N, L.wnat, L.ldn, L.wtr, L.ldt, st));
     return VF_OK;
   }
 
-  int run_node(Ctx& c, const StepArgs& s, int i) override {
-    hipStream_t st = c.stream;
-    // weight gradients and the fold go to the side stream (bf16 path, when overlapping)
-    hipStream_t sd = bf16_ ? c.side_stream() : c.stream;
-    const bool forked = sd != st;
-    const int p = i & 1;                 // which copy of the transposed operands this node uses
+  // Forward pass, loss, and the input-gradient chain (with the small-vector gradients the
+  // BatchNorm/ReLU backward kernels produce on the way).
+  int run_node_main(Ctx& c, const StepArgs& s, int i, hipStream_t st) override {
+    const int p = c.overlap ? (i & 1) : 0;   // which copy of the side part's operands
     const int b = s.sizes[i];
     const int64_t row0 = s.off[i];
     const float w = s.w[i];
@@ -133,10 +131,6 @@ class Mlp final : public Model {
                           : (const void*)(static_cast<const float*>(s.x) + row0 * D);
     const int32_t* y = s.y + row0;
 
-    // copy p of the operands (and of the staging vector) was last read by node i-2's side work
-    if (forked && i >= 2) VF_HIP(hipStreamWaitEvent(st, c.side_done[p], 0));
-
-    // ---- forward (main stream) ---------------------------------------------------------------
     for (int l = 0; l < nl; ++l) {
       Layer& L = layers_[l];
       const void* in = l == 0 ? x : layers_[l - 1].a;
@@ -147,47 +141,23 @@ class Mlp final : public Model {
       ep.C = slab_; ep.ldc = L.ld;
       if (L.has_bias) { ep.bias = P + L.b_off; ep.bias_round_bf16 = bf16_; }
       if (bf16_)
-        VF_K(c, "gemm_fwd", launch_gemm_bf16(static_cast<const bf16_t*>(in), ldin, L.wtr, L.ldt, b, L.N, L.K,
-                                             split, slab, ep, st));
+        VF_KS(c, st, "gemm_fwd", launch_gemm_bf16(static_cast<const bf16_t*>(in), ldin, L.wtr, L.ldt, b, L.N, L.K,
+                                                  split, slab, ep, st));
       else
-        VF_K(c, "gemm_fwd", launch_gemm_f32(static_cast<const float*>(in), ldin, 1, P + L.w_off, 1, L.N, b, L.N, L.K, ep, st));
+        VF_KS(c, st, "gemm_fwd", launch_gemm_f32(static_cast<const float*>(in), ldin, 1, P + L.w_off, 1, L.N, b, L.N, L.K, ep, st));
       if (L.hidden)
-        VF_K(c, "bn_relu_fwd", launch_bn_relu_fwd(slab_, split, slab, L.ld, b, L.N,
-                                  L.has_bn ? P + L.g_off : nullptr, L.has_bn ? P + L.be_off : nullptr,
-                                  bf16_, cfg_.bn_eps, L.z, L.ld, L.a, L.ld, bf16_, L.aT[p], ldb_,
-                                  L.mean, L.rstd, st));
+        VF_KS(c, st, "bn_relu_fwd", launch_bn_relu_fwd(slab_, split, slab, L.ld, b, L.N,
+                                       L.has_bn ? P + L.g_off : nullptr, L.has_bn ? P + L.be_off : nullptr,
+                                       bf16_, cfg_.bn_eps, L.z, L.ld, L.a, L.ld, bf16_, L.aT[p], ldb_,
+                                       L.mean, L.rstd, st));
       else
-        VF_K(c, "softmax_xent", launch_softmax_xent(slab_, split, slab, L.ld, L.z, L.ld, y, b, L.N,
-                                                    c.rowloss, L.dz, L.ld, bf16_, L.dzT[p], ldb_, st));
+        VF_KS(c, st, "softmax_xent", launch_softmax_xent(slab_, split, slab, L.ld, L.z, L.ld, y, b, L.N,
+                                                         c.rowloss, L.dz, L.ld, bf16_, L.dzT[p], ldb_, w, i,
+                                                         c.node_loss, c.loss_total, c.loss_ticket, st));
     }
-    VF_K(c, "loss_reduce", launch_loss_reduce(c.rowloss, b, w, i, c.node_loss, c.loss_total, st));
 
-    // ---- backward: input-gradient chain on the main stream, weight gradients beside it --------
-    for (int l = nl - 1; l >= 0; --l) {
+    for (int l = nl - 1; l >= 1; --l) {
       Layer& L = layers_[l];
-      const void* in = l == 0 ? x : layers_[l - 1].a;
-      const int64_t ldin = l == 0 ? D : layers_[l - 1].ld;
-      // dz of layer l (and its transposed copy) is complete on the main stream here
-      VF_TRY(c.order(st, sd));
-      if (l == nl - 1 && bf16_)   // first side-stream work of the node: the batch slice, transposed
-        VF_KS(c, sd, "transpose", launch_transpose_bf16(static_cast<const bf16_t*>(x), D, xT_[p], ldb_, b, D, sd));
-      if (!L.hidden) {   // last layer: bias gradient = sums over the node of dlogits
-        if (bf16_) VF_KS(c, sd, "bias_grad", launch_rowsum_bf16(L.dzT[p], ldb_, L.N, b, c.gout(L.b_off, w, i), sd));
-        else       VF_KS(c, sd, "bias_grad", launch_colsum(L.dz, L.ld, 0, b, L.N, c.gout(L.b_off, w, i), sd));
-      }
-      // weight gradient dW[K,N] = in^T dz
-      GradOut go = c.gout(L.w_off, w, i);
-      Epilogue ep;
-      ep.C = go.dst; ep.ldc = L.N; ep.alpha = go.alpha;
-      if (go.accumulate) { ep.R = go.dst; ep.ldr = L.N; ep.beta = 1.f; }
-      if (bf16_) {
-        const bf16_t* inT = l == 0 ? xT_[p] : layers_[l - 1].aT[p];
-        VF_KS(c, sd, "gemm_wgrad", launch_gemm_bf16(inT, ldb_, L.dzT[p], ldb_, L.K, L.N, b, 1, 0, ep, sd));
-      } else {
-        VF_KS(c, sd, "gemm_wgrad", launch_gemm_f32(static_cast<const float*>(in), 1, ldin,
-                                                   static_cast<const float*>(L.dz), 1, L.ld, L.K, L.N, b, ep, sd));
-      }
-      if (l == 0) break;
       // input gradient da[l-1][b,K] = dz W^T, then through ReLU / BatchNorm of layer l-1
       Layer& Pv = layers_[l - 1];
       const int split = split_for(b, L.K, L.N, Pv.ld);
@@ -195,21 +165,54 @@ class Mlp final : public Model {
       Epilogue ed;
       ed.C = slab_; ed.ldc = Pv.ld;
       if (bf16_)
-        VF_K(c, "gemm_dgrad", launch_gemm_bf16(static_cast<const bf16_t*>(L.dz), L.ld, L.wnat, L.ldn, b, L.K, L.N,
-                                               split, slab, ed, st));
+        VF_KS(c, st, "gemm_dgrad", launch_gemm_bf16(static_cast<const bf16_t*>(L.dz), L.ld, L.wnat, L.ldn, b, L.K, L.N,
+                                                    split, slab, ed, st));
       else
-        VF_K(c, "gemm_dgrad", launch_gemm_f32(static_cast<const float*>(L.dz), L.ld, 1, P + L.w_off, L.N, 1, b, L.K, L.N, ed, st));
+        VF_KS(c, st, "gemm_dgrad", launch_gemm_f32(static_cast<const float*>(L.dz), L.ld, 1, P + L.w_off, L.N, 1, b, L.K, L.N, ed, st));
       GradOut gg = Pv.has_bn ? c.gout(Pv.g_off, w, i) : GradOut{nullptr, 0.f, 0};
       GradOut gb = c.gout(Pv.has_bn ? Pv.be_off : Pv.b_off, w, i);
-      VF_K(c, "bn_relu_bwd", launch_bn_relu_bwd(slab_, split, slab, Pv.ld, Pv.z, Pv.ld, b, Pv.N,
-                                Pv.has_bn ? P + Pv.g_off : nullptr, Pv.has_bn ? P + Pv.be_off : nullptr,
-                                bf16_, Pv.mean, Pv.rstd, Pv.dz, Pv.ld, bf16_, bf16_ ? Pv.dzT[p] : nullptr, ldb_,
-                                gg, gb, st));
+      VF_KS(c, st, "bn_relu_bwd", launch_bn_relu_bwd(slab_, split, slab, Pv.ld, Pv.z, Pv.ld, b, Pv.N,
+                                     Pv.has_bn ? P + Pv.g_off : nullptr, Pv.has_bn ? P + Pv.be_off : nullptr,
+                                     bf16_, Pv.mean, Pv.rstd, Pv.dz, Pv.ld, bf16_, bf16_ ? Pv.dzT[p] : nullptr, ldb_,
+                                     gg, gb, st));
     }
-    // every entry of node i's gradient is now enqueued (main: small vectors; side: matrices)
-    VF_TRY(c.fold(i, w, sd));
-    if (forked) VF_HIP(hipEventRecord(c.side_done[p], sd));
     return VF_OK;
+  }
+
+  // Weight gradients, the last layer's bias gradient, and (staged mode) the fold.  Reads the
+  // transposed operands of copy p (bf16) that the main part wrote.
+  int run_node_side(Ctx& c, const StepArgs& s, int i, hipStream_t st) override {
+    const int p = c.overlap ? (i & 1) : 0;
+    const int b = s.sizes[i];
+    const int64_t row0 = s.off[i];
+    const float w = s.w[i];
+    const int nl = (int)layers_.size();
+    const int D = cfg_.dims[0];
+    const void* x = bf16_ ? (const void*)(static_cast<const bf16_t*>(s.x) + row0 * D)
+                          : (const void*)(static_cast<const float*>(s.x) + row0 * D);
+    if (bf16_)
+      VF_KS(c, st, "transpose", launch_transpose_bf16(static_cast<const bf16_t*>(x), D, xT_[p], ldb_, b, D, st));
+    for (int l = nl - 1; l >= 0; --l) {
+      Layer& L = layers_[l];
+      const void* in = l == 0 ? x : layers_[l - 1].a;
+      const int64_t ldin = l == 0 ? D : layers_[l - 1].ld;
+      if (!L.hidden) {   // last layer: bias gradient = sums over the node of dlogits
+        if (bf16_) VF_KS(c, st, "bias_grad", launch_rowsum_bf16(L.dzT[p], ldb_, L.N, b, c.gout(L.b_off, w, i), st));
+        else       VF_KS(c, st, "bias_grad", launch_colsum(L.dz, L.ld, 0, b, L.N, c.gout(L.b_off, w, i), st));
+      }
+      GradOut go = c.gout(L.w_off, w, i);
+      Epilogue ep;
+      ep.C = go.dst; ep.ldc = L.N; ep.alpha = go.alpha;
+      if (go.accumulate) { ep.R = go.dst; ep.ldr = L.N; ep.beta = 1.f; }
+      if (bf16_) {
+        const bf16_t* inT = l == 0 ? xT_[p] : layers_[l - 1].aT[p];
+        VF_KS(c, st, "gemm_wgrad", launch_gemm_bf16(inT, ldb_, L.dzT[p], ldb_, L.K, L.N, b, 1, 0, ep, st));
+      } else {
+        VF_KS(c, st, "gemm_wgrad", launch_gemm_f32(static_cast<const float*>(in), 1, ldin,
+                                                   static_cast<const float*>(L.dz), 1, L.ld, L.K, L.N, b, ep, st));
+      }
+    }
+    return c.fold(i, w, st);
   }
 
  private:
