@@ -87,6 +87,22 @@ def roofline_for(tag, work, avg_ms):
             "avg_launch_ms": avg_ms, "algorithmic_flops_per_launch": f_per}
 
 
+def measured_traffic(workload, accumulate, tag):
+    """HBM bytes per launch of kernel `tag` from the committed hardware-counter summary
+    (profiles/<workload>_hbm_traffic.txt: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+    script, scaled by the plain-copy dispatch), or None when no summary covers this case."""
+    path = os.path.join(ROOT, "profiles", f"{workload.lower()}_hbm_traffic.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                parts = line.split()
+                if len(parts) >= 4 and parts[0] == "traffic" and parts[1] == accumulate and parts[2] == tag:
+                    return float(parts[3])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(wl, theta, x, y, budget_s=12.0):
     """The oracle as it stands, timed node by node on the host cores until about
     `budget_s` seconds of work are done (at least one node)."""
@@ -124,7 +140,8 @@ def main():
                          "staged: per-node staging vector + the accumulate kernel")
     ap.add_argument("--no-alt", action="store_true", help="skip the timing of the other accumulate mode")
     ap.add_argument("--no-graph", action="store_true")
-    ap.add_argument("--no-overlap", action="store_true", help="keep all kernels of a step on one stream")
+    ap.add_argument("--overlap", action="store_true",
+                    help="weight gradients on a second stream beside the next node's passes")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-profile", action="store_true")
     args = ap.parse_args()
@@ -149,7 +166,7 @@ def main():
     stream = torch.cuda.Stream()
     flags = (vf.VF_FLAG_FUSED_ACCUMULATE if args.accumulate == "fused" else 0) | \
             (vf.VF_FLAG_NO_GRAPH if args.no_graph else 0) | \
-            (vf.VF_FLAG_NO_OVERLAP if args.no_overlap else 0)
+            (vf.VF_FLAG_OVERLAP if args.overlap else 0)
     eng = vf.VirtualNodeStep(config_from_workload(wl, flags=flags, stream=stream))
     P = eng.num_params
     params = torch.from_numpy(theta).cuda()
@@ -159,6 +176,15 @@ def main():
     yt = torch.from_numpy(y).cuda()
     sizes = list(wl.node_sizes)
     torch.cuda.synchronize()
+
+    # One plain copy of known size (P floats read, P floats written; first-node form of the
+    # accumulate kernel with weight 1): the reference dispatch that hardware-counter runs use
+    # to scale FETCH_SIZE / WRITE_SIZE.  Not part of the timed region.
+    cal_src = torch.ones(P, device="cuda")
+    cal_dst = torch.empty(P, device="cuda")
+    vf.vf_accumulate(cal_dst, cal_src, 1.0, first=True, stream=stream)
+    stream.synchronize()
+    del cal_src, cal_dst
 
     for _ in range(args.warmup):
         eng.step(params, xt, yt, sizes)
@@ -188,7 +214,7 @@ def main():
                    "global_batch": wl.batch, "virtual_nodes": wl.n_nodes,
                    "node_sizes": sizes if len(set(sizes)) > 1 else f"{wl.n_nodes}x{sizes[0]}",
                    "optimizer": wl.optimizer, "params": P, "accumulate": args.accumulate,
-                   "graph": not args.no_graph, "overlap": not args.no_overlap},
+                   "graph": not args.no_graph, "overlap": bool(args.overlap)},
         "loss": loss,
     }
 
@@ -214,6 +240,7 @@ def main():
         out["kernels"] = kernels
         dom = max((k for k in kernels if k in work), key=lambda k: kernels[k]["ms_per_step"])
         out["roofline"] = roofline_for(dom, work, kernels[dom]["avg_launch_ms"])
+        out["roofline"]["traffic"] = measured_traffic(wl.name, args.accumulate, dom)
         out["roofline_all"] = {k: {kk: vv for kk, vv in roofline_for(k, work, kernels[k]["avg_launch_ms"]).items()
                                    if kk in ("bound", "achieved", "peak", "unit", "frac")}
                                for k in kernels if k in work}

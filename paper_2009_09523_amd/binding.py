@@ -14,7 +14,7 @@ VF_SGDM, VF_ADAM = 0, 1
 VF_MAX_DIMS = 16
 VF_FLAG_FUSED_ACCUMULATE = 1
 VF_FLAG_NO_GRAPH = 2
-VF_FLAG_NO_OVERLAP = 4
+VF_FLAG_OVERLAP = 4
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 

@@ -109,7 +109,38 @@ int capture_part(Ctx& c, const StepArgs& a, int part, int node, hipGraphExec_t* 
   return VF_OK;
 }
 
+int enqueue_nodes(Ctx& c, const StepArgs& a, bool use_graph);
+
+// Without overlap the whole step (minus the update) is one single-stream chain: one graph.
+int capture_whole_step(Ctx& c, const StepArgs& a) {
+  drop_graph(c);
+  c.graphs.assign(1, nullptr);
+  hipGraph_t graph = nullptr;
+  VF_HIP(hipStreamBeginCapture(c.stream, hipStreamCaptureModeThreadLocal));
+  int rc = enqueue_nodes(c, a, false);
+  hipError_t e = hipStreamEndCapture(c.stream, &graph);
+  if (rc == VF_OK && e != hipSuccess) {
+    set_last_error("hipStreamEndCapture", e, __FILE__, __LINE__);
+    rc = VF_EDEVICE;
+  }
+  if (rc == VF_OK) {
+    e = hipGraphInstantiate(&c.graphs[0], graph, nullptr, nullptr, 0);
+    if (e != hipSuccess) {
+      set_last_error("hipGraphInstantiate", e, __FILE__, __LINE__);
+      rc = VF_EDEVICE;
+    }
+  }
+  if (graph) (void)hipGraphDestroy(graph);
+  if (rc != VF_OK) {
+    c.graphs.clear();
+    return rc;
+  }
+  c.graph_params = a.params; c.graph_x = a.x; c.graph_y = a.y; c.graph_sizes = a.sizes;
+  return VF_OK;
+}
+
 int capture_graphs(Ctx& c, const StepArgs& a) {
+  if (!c.overlapping()) return capture_whole_step(c, a);
   drop_graph(c);
   c.graphs.assign((size_t)1 + 2 * a.V, nullptr);
   int rc = capture_part(c, a, 0, 0, &c.graphs[0]);
@@ -138,6 +169,10 @@ int run_part(Ctx& c, const StepArgs& a, bool use_graph, int part, int node, hipS
 // node's passes on the side stream.
 int enqueue_nodes(Ctx& c, const StepArgs& a, bool use_graph) {
   const bool ov = c.overlapping();
+  if (use_graph && !ov) {          // the whole step is one captured chain
+    VF_HIP(hipGraphLaunch(c.graphs[0], c.stream));
+    return VF_OK;
+  }
   hipStream_t side = ov ? c.side : c.stream;
   VF_TRY(run_part(c, a, use_graph, 0, 0, c.stream));
   for (int i = 0; i < a.V; ++i) {
@@ -227,7 +262,7 @@ int vf_init(const vf_config* cfg, vf_ctx** out) {
   c.P = c.model->num_params();
   // Overlap needs a capturable main stream and a model that double-buffers what the side
   // stream reads (the bf16 MLP does).
-  c.overlap = c.stream != nullptr && !(cfg->flags & VF_FLAG_NO_OVERLAP) && c.model->supports_overlap();
+  c.overlap = c.stream != nullptr && (cfg->flags & VF_FLAG_OVERLAP) && c.model->supports_overlap();
   if (c.overlap) {
     e = hipStreamCreateWithFlags(&c.side, hipStreamNonBlocking);
     for (int k = 0; k < 2 && e == hipSuccess; ++k) e = hipEventCreateWithFlags(&c.side_done[k], hipEventDisableTiming);

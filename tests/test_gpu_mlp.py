@@ -193,14 +193,15 @@ def test_c5_full_size_launch_configuration():
     check(gpu["G"], 0.5 * (g0 + g1), "G (two nodes)")
 
 
-NO_OVERLAP = 4
+OVERLAP = 4
 
 
 def test_overlap_and_single_stream_agree_bitwise():
     """Weight gradients on the side stream change scheduling only, never a bit of the result."""
     wl, theta, x, y = _case("mlp_mid_bn_bf16")
-    base = run_gpu(wl, theta, x, y, flags=NO_OVERLAP | NO_GRAPH, steps=2)
-    for flags in (0, NO_GRAPH, FUSED, FUSED | NO_GRAPH, NO_OVERLAP, FUSED | NO_OVERLAP):
+    base = run_gpu(wl, theta, x, y, flags=NO_GRAPH, steps=2)
+    for flags in (0, FUSED, FUSED | NO_GRAPH, OVERLAP, OVERLAP | NO_GRAPH, FUSED | OVERLAP,
+                  FUSED | OVERLAP | NO_GRAPH):
         other = run_gpu(wl, theta, x, y, flags=flags, steps=2)
         assert base["G"].tobytes() == other["G"].tobytes(), flags
         assert base["theta"].tobytes() == other["theta"].tobytes(), flags
