@@ -61,6 +61,9 @@ def algorithmic_work(wl, P, fused=False):
         att = 2 * T * T * d * B * nl               # one [T,T,d_head] product over all heads, all blocks
         for tag in ("attn_scores", "attn_pv", "attn_bwd_dp", "attn_bwd_dv", "attn_bwd_dq", "attn_bwd_dk"):
             work[tag] = (nl * (3 * R * d * esz + B * wl.n_heads * T * T * 4), att, V * nl)
+        # fused matrix-core kernels: 2 products forward, 4 backward, per head
+        work["attn_fwd"] = (nl * (4 * R * d * esz + B * wl.n_heads * T * T * esz), 2 * att, V * nl)
+        work["attn_bwd"] = (nl * (6 * R * d * esz + R * d * 4 + B * wl.n_heads * T * T * esz), 4 * att, V * nl)
         work["cast_weight"] = ((nl * Wl + d * Vc) * (4 + 2 * esz), 0, 4 * nl + 1)
     return work
 
@@ -70,7 +73,7 @@ def roofline_for(tag, work, avg_ms):
     b_per, f_per = bytes_ / launches, flops / launches
     t_hbm = b_per / (HBM_PEAK_GBS * 1e9)
     t_mfma = f_per / (MFMA_BF16_PEAK_TFLOPS * 1e12)
-    if tag.startswith("attn_"):
+    if tag.startswith("attn_") and tag not in ("attn_fwd", "attn_bwd"):
         # these products run on the fp32 vector ALUs (no matrix-core version yet)
         ach = f_per / (avg_ms * 1e-3) / 1e12
         return {"kernel": tag, "bound": "alu", "achieved": ach, "peak": FP32_VECTOR_PEAK_TFLOPS,

@@ -69,6 +69,7 @@ class Encoder final : public Model {
     ldR_ = round8(maxR_);
     ldV_ = round8(V_);
     out_split_max_ = 32;
+    mfma_attn_ = bf16_ && attn_mfma_supported(T_, dh_);
   }
 
   int64_t num_params() const override { return P_; }
@@ -147,11 +148,16 @@ class Encoder final : public Model {
       VF_K(c, "layernorm_fwd", launch_layernorm_fwd(B.hin, d_, nullptr, R, d_, P + B.ln1_g, P + B.ln1_b, bf16_,
                                                     cfg_.ln_eps, B.a, d_, bf16_, B.mean1, B.rstd1, st));
       VF_TRY(lin_fwd(c, "gemm_fwd", B.qkv, P, B.a, d_, R, B.qkv_act, 3 * d_, true, nullptr));
-      VF_K(c, "attn_scores", launch_bgemm(qkv_mat(B.qkv_act, 0), qkv_mat(B.qkv_act, 1), score_mat(scores_, 0, false),
-                                          T_, T_, dh_, heads, nh_, scale, st));
-      VF_K(c, "attn_softmax", launch_softmax_rows(scores_, B.prob, bf16_, (int64_t)heads * T_, T_, st));
-      VF_K(c, "attn_pv", launch_bgemm(score_mat(B.prob, 0, bf16_), vt_mat(B.qkv_act), merged_mat(B.om, bf16_),
-                                      T_, dh_, T_, heads, nh_, 1.0f, st));
+      if (mfma_attn_) {
+        VF_K(c, "attn_fwd", launch_attn_fwd(static_cast<const bf16_t*>(B.qkv_act), b, T_, d_, nh_,
+                                            static_cast<bf16_t*>(B.prob), static_cast<bf16_t*>(B.om), scale, st));
+      } else {
+        VF_K(c, "attn_scores", launch_bgemm(qkv_mat(B.qkv_act, 0), qkv_mat(B.qkv_act, 1), score_mat(scores_, 0, false),
+                                            T_, T_, dh_, heads, nh_, scale, st));
+        VF_K(c, "attn_softmax", launch_softmax_rows(scores_, B.prob, bf16_, (int64_t)heads * T_, T_, st));
+        VF_K(c, "attn_pv", launch_bgemm(score_mat(B.prob, 0, bf16_), vt_mat(B.qkv_act), merged_mat(B.om, bf16_),
+                                        T_, dh_, T_, heads, nh_, 1.0f, st));
+      }
       VF_TRY(lin_fwd(c, "gemm_fwd", B.o, P, B.om, d_, R, B.hmid, d_, false, B.hin));
       VF_K(c, "layernorm_fwd", launch_layernorm_fwd(B.hmid, d_, nullptr, R, d_, P + B.ln2_g, P + B.ln2_b, bf16_,
                                                     cfg_.ln_eps, B.f, d_, bf16_, B.mean2, B.rstd2, st));
@@ -206,6 +212,11 @@ class Encoder final : public Model {
       VF_TRY(lin_bwd_w(c, "gemm_wgrad", B.o, B.om, d_, dmid_op, d_, R, c.gout(B.o.w_off, w, i)));
       VF_TRY(lin_bwd_x(c, "gemm_dgrad", B.o, P, dmid_op, d_, R, tmp32_, d_, nullptr));   // d(om), fp32
       // dP = dO V^T ; dV = P^T dO ; dS = P (dP - rowsum(dP P)) ; dQ = dS K / sqrt(dh) ; dK = dS^T Q / sqrt(dh)
+      if (mfma_attn_) {
+        VF_K(c, "attn_bwd", launch_attn_bwd(tmp32_, static_cast<const bf16_t*>(B.qkv_act),
+                                            static_cast<const bf16_t*>(B.prob), b, T_, d_, nh_,
+                                            static_cast<bf16_t*>(dqkv_), scale, st));
+      } else {
       VF_K(c, "attn_bwd_dp", launch_bgemm(merged_mat(tmp32_, false, true), qkv_mat(B.qkv_act, 2), score_mat(scores_, 0, false),
                                           T_, T_, dh_, heads, nh_, 1.0f, st));
       VF_K(c, "attn_bwd_dv", launch_bgemm(score_mat(B.prob, 1, bf16_), merged_t_mat(tmp32_), qkv_mat(dqkv_, 2),
@@ -215,6 +226,7 @@ class Encoder final : public Model {
                                           T_, dh_, T_, heads, nh_, scale, st));
       VF_K(c, "attn_bwd_dk", launch_bgemm(score_mat(scores_, 1, false, true), kt_mat(B.qkv_act, 0), qkv_mat(dqkv_, 1),
                                           T_, dh_, T_, heads, nh_, scale, st));
+      }
       VF_K(c, "colsum", launch_colsum_rows(dqkv_, 3 * d_, bf16_, R, 3 * d_, red_, c.gout(B.qkv.b_off, w, i), st));
       VF_TRY(lin_bwd_w(c, "gemm_wgrad", B.qkv, B.a, d_, dqkv_, 3 * d_, R, c.gout(B.qkv.w_off, w, i)));
       VF_TRY(lin_bwd_x(c, "gemm_dgrad", B.qkv, P, dqkv_, 3 * d_, R, tmp32_, d_, nullptr));
@@ -320,6 +332,7 @@ class Encoder final : public Model {
   int64_t P_ = 0, tok_off_ = 0, pos_off_ = 0, lnf_g_ = 0, lnf_b_ = 0;
   int64_t maxR_ = 0, maxRm_ = 0, ldR_ = 0, ldV_ = 0;
   int out_split_max_ = 32;
+  bool mfma_attn_ = false;              // fused matrix-core attention kernels apply
   std::vector<Block> blocks_;
   std::vector<Lin*> lins_;
   Lin out_;

@@ -151,6 +151,16 @@ struct BMat {
 int launch_bgemm(const BMat& A, const BMat& B, const BMat& C, int M, int N, int K, int batch, int inner,
                  float alpha, hipStream_t s);
 
+// k_attn.hip -- fused self-attention on the matrix cores (bf16, head size 64, sequence length
+// 32, 64 or 128).  qkv: [n_seq*T, 3d] (q | k | v, heads side by side); prob: [n_seq*heads, T, T]
+// softmax probabilities (written by the forward pass, read by the backward pass); om: [n_seq*T, d].
+bool attn_mfma_supported(int seq_len, int d_head);
+int launch_attn_fwd(const bf16_t* qkv, int n_seq, int seq_len, int d, int n_heads, bf16_t* prob, bf16_t* om,
+                    float scale, hipStream_t s);
+// dO: fp32 [n_seq*T, d] gradient w.r.t. om (rounded to bf16 as it is staged); dqkv: [n_seq*T, 3d]
+int launch_attn_bwd(const float* dO, const bf16_t* qkv, const bf16_t* prob, int n_seq, int seq_len, int d,
+                    int n_heads, bf16_t* dqkv, float scale, hipStream_t s);
+
 // k_encoder.hip -- element-wise and row-wise kernels of the encoder
 // h[r,:] = tok[ids[r]] + pos[r % T]   (table values rounded to bf16 when round_params)
 int launch_embed_fwd(const int32_t* ids, const float* tok, const float* pos, int R, int T, int d,

@@ -107,6 +107,8 @@ WORKLOADS: Dict[str, Workload] = {
                          optimizer="adam", lr=1e-3),
     "enc_small_bf16": _enc("enc_small_bf16", 2, 128, 2, 264, 32, 1003, [4, 2, 3], "bf16",
                            optimizer="adam", lr=1e-4),
+    "enc_mid_bf16": _enc("enc_mid_bf16", 2, 192, 3, 264, 64, 1003, [2, 1, 2], "bf16",
+                         optimizer="adam", lr=1e-4),
     "enc_small_f32": _enc("enc_small_f32", 2, 128, 2, 264, 32, 1003, [4, 2, 3], "f32",
                           optimizer="adam", lr=1e-4),
 }
