@@ -132,6 +132,75 @@ def cpu_baseline(wl, theta, x, y, budget_s=12.0):
             "seconds": dt}
 
 
+def time_steps(vf, torch, wl, theta, x, y, flags, steps, warmup, max_node_size=None):
+    """(ms per step, workspace bytes) of `wl` on the device."""
+    from paper_2009_09523_amd.binding import config_from_workload
+    stream = torch.cuda.Stream()
+    eng = vf.VirtualNodeStep(config_from_workload(wl, flags=flags, stream=stream, max_node_size=max_node_size))
+    params = torch.from_numpy(theta).cuda()
+    xt = torch.from_numpy(x).cuda()
+    if wl.kind == "mlp" and wl.dtype == "bf16":
+        xt = xt.to(torch.bfloat16)
+    yt = torch.from_numpy(y).cuda()
+    sizes = list(wl.node_sizes)
+    for _ in range(warmup):
+        eng.step(params, xt, yt, sizes)
+    stream.synchronize()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        eng.step(params, xt, yt, sizes)
+    stream.synchronize()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    ws = eng.workspace_bytes
+    eng.close()
+    return ms, ws
+
+
+def vsweep(args):
+    """Synthetic analogue of the paper's microbenchmark of virtual node processing on one
+    accelerator (Section 6.6, Figures 13 and 14): (a) node size fixed, batch growing with the
+    number of virtual nodes -- throughput and memory relative to one node; (b) batch fixed (it
+    already fits), split into more and more nodes -- throughput relative to no virtual nodes."""
+    from dataclasses import replace
+    import numpy as np
+    import torch
+    import paper_2009_09523_amd as vf
+    import vf_inputs as I
+    base = I.workload(args.workload)
+    flags = vf.VF_FLAG_FUSED_ACCUMULATE if args.accumulate == "fused" else 0
+    b = max(base.node_sizes)
+    grow, fits = [], []
+    for V in (1, 2, 4, 8, 16, 32):
+        wl = replace(base, node_sizes=(b,) * V)
+        theta = I.make_params(wl)
+        x, y = I.make_batch(wl)
+        ms, ws = time_steps(vf, torch, wl, theta, x, y, flags, args.steps, args.warmup)
+        grow.append({"V": V, "batch": b * V, "ms_per_step": ms, "samples_per_s": b * V / (ms * 1e-3),
+                     "workspace_bytes": ws})
+    B = base.batch
+    theta = I.make_params(base)
+    x, y = I.make_batch(base)
+    V = 1
+    while B // V >= 16 and B % V == 0:
+        wl = replace(base, node_sizes=(B // V,) * V)
+        ms, ws = time_steps(vf, torch, wl, theta, x, y, flags, args.steps, args.warmup)
+        fits.append({"V": V, "node_size": B // V, "ms_per_step": ms, "samples_per_s": B / (ms * 1e-3),
+                     "workspace_bytes": ws})
+        V *= 2
+    for rows in (grow, fits):
+        for r in rows:
+            r["throughput_vs_V1"] = r["samples_per_s"] / rows[0]["samples_per_s"]
+            r["workspace_vs_V1"] = r["workspace_bytes"] / rows[0]["workspace_bytes"]
+    print(json.dumps({"mode": "vsweep", "workload": base.name, "accumulate": args.accumulate,
+                      "growing_batch_fixed_node_size": grow, "fixed_batch": fits,
+                      "paper_context": "Section 6.6 on one RTX 2080 Ti, normalised to TensorFlow: throughput "
+                                       "-4.2 % to +31.4 % as virtual nodes are added at growing batch; at "
+                                       "least 88.4 % when the batch already fits; memory overhead constant "
+                                       "beyond two nodes"}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -147,6 +216,9 @@ def main():
                     help="weight gradients on a second stream beside the next node's passes")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-profile", action="store_true")
+    ap.add_argument("--vsweep", action="store_true",
+                    help="instead of the benchmark line: throughput and memory against the number of "
+                         "virtual nodes (the paper's Section 6.6 microbenchmark, synthetic)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs the virtual-node step on ONE GPU; --gpus above 1 is not "
@@ -163,6 +235,9 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
     torch.cuda.set_device(0)
+    if args.vsweep:
+        vsweep(args)
+        return
     wl = I.workload(args.workload)
     theta = I.make_params(wl)
     x, y = I.make_batch(wl)

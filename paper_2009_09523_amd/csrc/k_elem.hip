@@ -34,6 +34,43 @@ __global__ __launch_bounds__(256) void transpose_kernel(const TIN* __restrict__ 
   }
 }
 
+// fp32 [R, C] -> bf16 natural copy [R, ldn] and transposed copy [C, ldt], 64x64 tiles.
+// Every thread reads 16 bytes and writes 8 bytes at a time in both orientations.
+// Requires C % 4 == 0, ldi % 4 == 0, ldn % 4 == 0, ldt % 4 == 0 and 16-byte aligned bases.
+__global__ __launch_bounds__(256) void cast_weight_kernel(const float* __restrict__ in, int64_t ldi,
+                                                          bf16_t* __restrict__ nat, int64_t ldn,
+                                                          bf16_t* __restrict__ tr, int64_t ldt, int R, int C) {
+  __shared__ bf16_t tile[64][64 + 2];
+  const int q = threadIdx.x & 15, g = threadIdx.x >> 4;      // 16 quads per row, 16 row groups
+  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int rl = g + 16 * i, r = r0 + rl, c = c0 + 4 * q;
+    bf16_t h[4] = {0, 0, 0, 0};
+    if (r < R && c < C) {
+      const float4 v = *reinterpret_cast<const float4*>(&in[(int64_t)r * ldi + c]);
+      h[0] = f32_to_bf16(v.x); h[1] = f32_to_bf16(v.y); h[2] = f32_to_bf16(v.z); h[3] = f32_to_bf16(v.w);
+      uint2 pk;
+      pk.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
+      pk.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
+      *reinterpret_cast<uint2*>(&nat[(int64_t)r * ldn + c]) = pk;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) tile[rl][4 * q + u] = h[u];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int cl = g + 16 * i, c = c0 + cl, r = r0 + 4 * q;
+    if (c < C && r < R) {      // R % 4 == 0 is not required: rows past R inside the quad are padding of ldt
+      uint2 pk;
+      pk.x = (uint32_t)tile[4 * q][cl] | ((uint32_t)tile[4 * q + 1][cl] << 16);
+      pk.y = (uint32_t)tile[4 * q + 2][cl] | ((uint32_t)tile[4 * q + 3][cl] << 16);
+      *reinterpret_cast<uint2*>(&tr[(int64_t)c * ldt + r]) = pk;
+    }
+  }
+}
+
 __global__ __launch_bounds__(256) void cast_kernel(const float* __restrict__ in, int64_t ldi,
                                                    bf16_t* __restrict__ out, int64_t ldo, int R, int C) {
   int c = blockIdx.x * 256 + threadIdx.x;
@@ -55,8 +92,16 @@ int launch_transpose_bf16(const bf16_t* in, int64_t ldi, bf16_t* out, int64_t ld
 int launch_cast_weight(const float* w, int R, int C, bf16_t* nat, int64_t ldn, bf16_t* tr,
                        int64_t ldt, hipStream_t s) {
   if (R <= 0 || C <= 0) return VF_OK;
-  dim3 grid((C + TS - 1) / TS, (R + TS - 1) / TS);
-  transpose_kernel<float><<<grid, 256, 0, s>>>(w, C, tr, ldt, nat, ldn, R, C);
+  const bool vec = (C & 3) == 0 && (ldn & 3) == 0 && (ldt & 3) == 0 &&
+                   (reinterpret_cast<uintptr_t>(w) & 15) == 0 && (reinterpret_cast<uintptr_t>(nat) & 7) == 0 &&
+                   (reinterpret_cast<uintptr_t>(tr) & 7) == 0;
+  if (vec) {
+    dim3 grid((C + 63) / 64, (R + 63) / 64);
+    cast_weight_kernel<<<grid, 256, 0, s>>>(w, C, nat, ldn, tr, ldt, R, C);
+  } else {
+    dim3 grid((C + TS - 1) / TS, (R + TS - 1) / TS);
+    transpose_kernel<float><<<grid, 256, 0, s>>>(w, C, tr, ldt, nat, ldn, R, C);
+  }
   VF_LAUNCH_CHECK();
   return VF_OK;
 }

@@ -181,8 +181,13 @@ __global__ __launch_bounds__(NT) void layernorm_bwd_kernel(const float* __restri
     const int64_t orow = row_map ? row_map[r] : r;
     const float* xr = x + orow * ldx;
     const float mean = mean_in[r], rstd = rstd_in[r];
-    float dyv[LN_JMAX], xhv[LN_JMAX];
+    float dyv[LN_JMAX], xhv[LN_JMAX], resv[LN_JMAX];
     float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int j = 0; j < LN_JMAX; ++j) {          // the residual addend travels with the first loads
+      const int c = lane + 64 * j;
+      resv[j] = (dres && c < d) ? dres[orow * lddx + c] : 0.f;
+    }
 #pragma unroll
     for (int j = 0; j < LN_JMAX; ++j) {
       const int c = lane + 64 * j;
@@ -210,8 +215,7 @@ __global__ __launch_bounds__(NT) void layernorm_bwd_kernel(const float* __restri
         float g = gamma[c];
         if (round_params) g = round_bf16(g);
         float v = (dyv[j] * g - s1 - xhv[j] * s2) * rstd;
-        if (dres) v += dres[orow * lddx + c];
-        dx[orow * lddx + c] = v;
+        dx[orow * lddx + c] = v + resv[j];
       }
     }
   }
@@ -232,22 +236,25 @@ __global__ __launch_bounds__(NT) void layernorm_bwd_kernel(const float* __restri
 }
 
 // out_g[c] = sum over chunks of partial[0][chunk][c]; out_b likewise from partial[1].
-// 64 columns per workgroup, 4 chunk lanes (lane q adds chunks q, q+4, ...), combined in lane order.
+// 16 columns per workgroup, 16 chunk lanes (lane q adds chunks q, q+16, ...), combined in lane order.
 __global__ __launch_bounds__(NT) void layernorm_param_finish_kernel(const float* __restrict__ partial,
                                                                     int64_t pstride, int nchunk, int d,
                                                                     GradOut gout_g, GradOut gout_b) {
-  __shared__ float red[2][4][64];
-  const int tx = threadIdx.x & 63, q = threadIdx.x >> 6;
-  const int c = blockIdx.x * 64 + tx;
+  __shared__ float red[2][16][17];
+  const int tx = threadIdx.x & 15, q = threadIdx.x >> 4;
+  const int c = blockIdx.x * 16 + tx;
   float a = 0.f, b = 0.f;
   if (c < d)
-    for (int k = q; k < nchunk; k += 4) { a += partial[(int64_t)k * d + c]; b += partial[pstride + (int64_t)k * d + c]; }
+    for (int k = q; k < nchunk; k += 16) { a += partial[(int64_t)k * d + c]; b += partial[pstride + (int64_t)k * d + c]; }
   red[0][q][tx] = a;
   red[1][q][tx] = b;
   __syncthreads();
   if (q == 0 && c < d) {
-    grad_store(gout_g, c, (red[0][0][tx] + red[0][1][tx]) + (red[0][2][tx] + red[0][3][tx]));
-    grad_store(gout_b, c, (red[1][0][tx] + red[1][1][tx]) + (red[1][2][tx] + red[1][3][tx]));
+    float sa = 0.f, sb = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { sa += red[0][i][tx]; sb += red[1][i][tx]; }
+    grad_store(gout_g, c, sa);
+    grad_store(gout_b, c, sb);
   }
 }
 
@@ -417,7 +424,7 @@ int launch_layernorm_bwd(const float* dyp, int nsplit, int64_t slab, int64_t ldd
                                                round_params, mean, rstd, dres, dx, lddx, rows_per_wg,
                                                scratch, pstride);
   VF_LAUNCH_CHECK();
-  layernorm_param_finish_kernel<<<(d + 63) / 64, NT, 0, s>>>(scratch, pstride, nchunk, d, gout_g, gout_b);
+  layernorm_param_finish_kernel<<<(d + 15) / 16, NT, 0, s>>>(scratch, pstride, nchunk, d, gout_g, gout_b);
   VF_LAUNCH_CHECK();
   return VF_OK;
 }

@@ -180,7 +180,7 @@ int launch_layernorm_fwd(const float* x, int64_t ldx, const int32_t* row_map, in
 // Row-chunked reductions: column sums use a scratch of kReduceChunks * columns floats, the
 // LayerNorm backward one of 2 * kLnChunks * d floats.
 constexpr int kReduceChunks = 64;
-constexpr int kLnChunks = 256;
+constexpr int kLnChunks = 1024;
 // dx[orow] = LNbwd(sum of dy slabs)[r] (+ dres[orow]),  orow = row_map ? row_map[r] : r; also
 // dgamma[c] = sum_r dy[r,c]*xhat[r,c] and dbeta[c] = sum_r dy[r,c] through GradOut (row chunks
 // added in order).  d <= 1024.  scratch: 2 * kLnChunks * d floats.
