@@ -472,7 +472,7 @@ int vf_gemm(int32_t dtype, const void* A, int64_t lda, const void* B, int64_t ld
                             M, N, K, nsplit, (int64_t)M * ldc, ep, s);
   if (dtype == VF_F32)
     return launch_gemm_f32(static_cast<const float*>(A), lda, 1, static_cast<const float*>(B), ldb, 1,
-                           M, N, K, ep, s);
+                           M, N, K, 1, 0, ep, s);
   return VF_EINVAL;
 }
 

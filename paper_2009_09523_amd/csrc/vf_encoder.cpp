@@ -281,7 +281,7 @@ class Encoder final : public Model {
       VF_K(c, tag, launch_gemm_bf16(static_cast<const bf16_t*>(in), ldin, L.wtr, L.ldt, R, L.N, L.K, 1, 0, ep,
                                     stream_));
     else
-      VF_K(c, tag, launch_gemm_f32(static_cast<const float*>(in), ldin, 1, P + L.w_off, 1, L.N, R, L.N, L.K, ep,
+      VF_K(c, tag, launch_gemm_f32(static_cast<const float*>(in), ldin, 1, P + L.w_off, 1, L.N, R, L.N, L.K, 1, 0, ep,
                                    stream_));
     return VF_OK;
   }
@@ -299,7 +299,7 @@ class Encoder final : public Model {
       VF_K(c, tag, launch_gemm_bf16(tA_, ldr, tB_, ldr, L.K, L.N, R, 1, 0, ep, stream_));
     } else {
       VF_K(c, tag, launch_gemm_f32(static_cast<const float*>(in), 1, ldin, static_cast<const float*>(dy), 1, lddy,
-                                   L.K, L.N, R, ep, stream_));
+                                   L.K, L.N, R, 1, 0, ep, stream_));
     }
     return VF_OK;
   }
@@ -319,7 +319,7 @@ class Encoder final : public Model {
                                     (int64_t)R * lddx, ep, stream_));
     } else {
       if (split) *split = 1;
-      VF_K(c, tag, launch_gemm_f32(static_cast<const float*>(dy), lddy, 1, P + L.w_off, L.N, 1, R, L.K, L.N, ep,
+      VF_K(c, tag, launch_gemm_f32(static_cast<const float*>(dy), lddy, 1, P + L.w_off, L.N, 1, R, L.K, L.N, 1, 0, ep,
                                    stream_));
     }
     return VF_OK;

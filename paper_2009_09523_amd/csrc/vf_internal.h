@@ -76,8 +76,12 @@ int launch_adam(float* theta, float* m, float* u, const float* G, float lr, floa
 int launch_fill_f32(float* p, float value, int64_t n, hipStream_t s);
 
 // k_gemm_f32.hip:  acc[m,n] = sum_k A[m*sam + k*sak] * B[n*sbn + k*sbk]   (fp32)
+// The contraction may be cut into nsplit slices as for the bf16 kernel (slab s at
+// ep.C + s*slab_stride elements; no R with nsplit > 1).
 int launch_gemm_f32(const float* A, int64_t sam, int64_t sak, const float* B, int64_t sbn,
-                    int64_t sbk, int M, int N, int K, const Epilogue& ep, hipStream_t s);
+                    int64_t sbk, int M, int N, int K, int nsplit, int64_t slab_stride,
+                    const Epilogue& ep, hipStream_t s);
+int gemm_f32_pick_split(int M, int N, int K);
 
 // k_gemm_bf16.hip: acc[m,n] = sum_k A[m*lda + k] * B[n*ldb + k]  (bf16 operands, fp32 MFMA
 // accumulation).  lda, ldb multiples of 8, A and B 16-byte aligned.  The contraction is cut

@@ -67,7 +67,7 @@ class Mlp final : public Model {
     int64_t need = 0;
     auto probe = [&](int m) {
       if (m > max_b) m = max_b;
-      int split = bf16_ ? gemm_bf16_pick_split(m, N, K) : 1;
+      int split = bf16_ ? gemm_bf16_pick_split(m, N, K) : gemm_f32_pick_split(m, N, K);
       need = std::max(need, (int64_t)split * m * ld);
     };
     probe(32); probe(64);
@@ -76,8 +76,7 @@ class Mlp final : public Model {
   }
 
   int split_for(int b, int N, int K, int64_t ld) const {
-    if (!bf16_) return 1;
-    int split = gemm_bf16_pick_split(b, N, K);
+    int split = bf16_ ? gemm_bf16_pick_split(b, N, K) : gemm_f32_pick_split(b, N, K);
     while (split > 1 && (int64_t)split * b * ld > slab_elems_) split /= 2;
     return split;
   }
@@ -144,7 +143,7 @@ class Mlp final : public Model {
         VF_KS(c, st, "gemm_fwd", launch_gemm_bf16(static_cast<const bf16_t*>(in), ldin, L.wtr, L.ldt, b, L.N, L.K,
                                                   split, slab, ep, st));
       else
-        VF_KS(c, st, "gemm_fwd", launch_gemm_f32(static_cast<const float*>(in), ldin, 1, P + L.w_off, 1, L.N, b, L.N, L.K, ep, st));
+        VF_KS(c, st, "gemm_fwd", launch_gemm_f32(static_cast<const float*>(in), ldin, 1, P + L.w_off, 1, L.N, b, L.N, L.K, split, slab, ep, st));
       if (L.hidden)
         VF_KS(c, st, "bn_relu_fwd", launch_bn_relu_fwd(slab_, split, slab, L.ld, b, L.N,
                                        L.has_bn ? P + L.g_off : nullptr, L.has_bn ? P + L.be_off : nullptr,
@@ -168,7 +167,7 @@ class Mlp final : public Model {
         VF_KS(c, st, "gemm_dgrad", launch_gemm_bf16(static_cast<const bf16_t*>(L.dz), L.ld, L.wnat, L.ldn, b, L.K, L.N,
                                                     split, slab, ed, st));
       else
-        VF_KS(c, st, "gemm_dgrad", launch_gemm_f32(static_cast<const float*>(L.dz), L.ld, 1, P + L.w_off, L.N, 1, b, L.K, L.N, ed, st));
+        VF_KS(c, st, "gemm_dgrad", launch_gemm_f32(static_cast<const float*>(L.dz), L.ld, 1, P + L.w_off, L.N, 1, b, L.K, L.N, split, slab, ed, st));
       GradOut gg = Pv.has_bn ? c.gout(Pv.g_off, w, i) : GradOut{nullptr, 0.f, 0};
       GradOut gb = c.gout(Pv.has_bn ? Pv.be_off : Pv.b_off, w, i);
       VF_KS(c, st, "bn_relu_bwd", launch_bn_relu_bwd(slab_, split, slab, Pv.ld, Pv.z, Pv.ld, b, Pv.N,
@@ -209,7 +208,7 @@ class Mlp final : public Model {
         VF_KS(c, st, "gemm_wgrad", launch_gemm_bf16(inT, ldb_, L.dzT[p], ldb_, L.K, L.N, b, 1, 0, ep, st));
       } else {
         VF_KS(c, st, "gemm_wgrad", launch_gemm_f32(static_cast<const float*>(in), 1, ldin,
-                                                   static_cast<const float*>(L.dz), 1, L.ld, L.K, L.N, b, ep, st));
+                                                   static_cast<const float*>(L.dz), 1, L.ld, L.K, L.N, b, 1, 0, ep, st));
       }
     }
     return c.fold(i, w, st);
