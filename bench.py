@@ -201,6 +201,43 @@ def vsweep(args):
                                        "beyond two nodes"}))
 
 
+def het_profile(args):
+    """Offline profile of Section 5.1.1 on this accelerator (time of one virtual-node pass against
+    node batch size, power-of-2 and power-of-2-like sizes), then the split solver of Section 5.1.2
+    on a synthetic mix: 2 accelerators with the measured curve and 8 of a type 4x as slow (the
+    paper's V100 : P100 ratio), global batch 8192."""
+    from dataclasses import replace
+    import torch
+    import paper_2009_09523_amd as vf
+    import vf_inputs as I
+    base = I.workload(args.workload)
+    flags = vf.VF_FLAG_FUSED_ACCUMULATE if args.accumulate == "fused" else 0
+    V = 4                                   # several nodes per step so that the update is amortised
+    sizes = [16, 24, 32, 48, 64, 96, 128, 192, 256]
+    curve = []
+    for b in sizes:
+        wl = replace(base, node_sizes=(b,) * V)
+        theta = I.make_params(wl)
+        x, y = I.make_batch(wl)
+        ms, _ = time_steps(vf, torch, wl, theta, x, y, flags, args.steps, args.warmup)
+        curve.append({"node_batch": b, "ms_per_node": ms / V, "samples_per_s": b * V / (ms * 1e-3)})
+    fast = [c["ms_per_node"] for c in curve]
+    slow = [4.0 * t for t in fast]
+    mix = [(2, sizes, fast), (8, sizes, slow)]
+    b_het, v_het, t_het = vf.vf_solve_split(mix, 8192, 0.0)
+    b_hom, v_hom, t_hom = vf.vf_solve_split(mix[:1], 8192, 0.0)
+    print(json.dumps({"mode": "het-profile", "workload": base.name, "profile": curve,
+                      "synthetic_mix": {"types": [{"n": 2, "speed": "measured"}, {"n": 8, "speed": "measured / 4"}],
+                                        "global_batch": 8192,
+                                        "split": {"batch_per_device": b_het, "nodes_per_device": v_het,
+                                                  "ms_per_step": t_het},
+                                        "fast_type_only": {"batch_per_device": b_hom, "nodes_per_device": v_hom,
+                                                           "ms_per_step": t_hom},
+                                        "throughput_gain": t_hom / t_het - 1.0},
+                      "paper_context": "Table 4 / Section 6.5: 2 V100 + 8 P100 at 2048 / 512 per GPU, "
+                                       "+42 % throughput over V100 only"}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -219,6 +256,9 @@ def main():
     ap.add_argument("--vsweep", action="store_true",
                     help="instead of the benchmark line: throughput and memory against the number of "
                          "virtual nodes (the paper's Section 6.6 microbenchmark, synthetic)")
+    ap.add_argument("--het-profile", action="store_true",
+                    help="instead of the benchmark line: the offline profile (time per virtual node "
+                         "against node batch size) and the heterogeneous split it gives on a synthetic mix")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs the virtual-node step on ONE GPU; --gpus above 1 is not "
@@ -237,6 +277,9 @@ def main():
     torch.cuda.set_device(0)
     if args.vsweep:
         vsweep(args)
+        return
+    if args.het_profile:
+        het_profile(args)
         return
     wl = I.workload(args.workload)
     theta = I.make_params(wl)

@@ -200,6 +200,32 @@ int vf_gemm(int32_t dtype, const void* A, int64_t lda, const void* B, int64_t ld
             int64_t ldc, int32_t M, int32_t N, int32_t K, float alpha, int32_t accumulate,
             int32_t nsplit, void* stream);
 
+/* ---- heterogeneous split solver (host only) ---------------------------------------------- */
+
+/* Offline profile of one accelerator type (Section 5.1.1): the time of one virtual-node pass
+ * for the node batch sizes that fit in its memory.  batch ascending, step_time > 0 (any unit). */
+typedef struct vf_device_profile {
+  int32_t n_devices;            /* n_i: accelerators of this type in the job */
+  int32_t n_points;
+  const int32_t* batch;         /* host, n_points node batch sizes */
+  const double* step_time;      /* host, t_i(batch[k]) */
+} vf_device_profile;
+
+/* Section 5.1.2: minimise max_i ( t_i(b_i / v_i) * v_i ) + comm subject to sum_i n_i b_i = B over
+ * the per-device batch b_i and the virtual nodes per device v_i of every type.  Reading of the
+ * paper's formula (it prints t_i(b_i) * v_i): t_i is evaluated at the node batch b_i / v_i, which
+ * is what its "virtual nodes on a GPU run sequentially" explanation and its Table 4 (per-GPU
+ * batch and nodes per GPU) imply.  b_i ranges over 0 (type unused: the homogeneous fallback)
+ * and the power-of-2 and power-of-2-like sizes 1,2,3,4,6,8,12,16,24,... the profiler considers;
+ * b_i / v_i must be a profiled size.  comm (>= 0, same unit) is added when more than one
+ * device takes part.  Among equal optima the first in lexicographic order of (b_0, b_1, ...)
+ * ascending is returned, and for a given b_i the smallest v_i.
+ * types: host, n_types (1..8) entries.  b_out, v_out: host, n_types entries (v = 0 for an unused
+ * type).  step_time_out: host, optional.  VF_EINVAL for malformed input, VF_ESTATE when no
+ * combination of profiled sizes adds up to B. */
+int vf_solve_split(const vf_device_profile* types, int32_t n_types, int32_t B, double comm,
+                   int32_t* b_out, int32_t* v_out, double* step_time_out);
+
 #pragma GCC visibility pop
 
 #ifdef __cplusplus

@@ -29,6 +29,11 @@ class VfError(RuntimeError):
         super().__init__(f"{where}: error {code}" + (f" ({detail})" if detail else ""))
 
 
+class VfDeviceProfile(C.Structure):
+    _fields_ = [("n_devices", C.c_int32), ("n_points", C.c_int32),
+                ("batch", C.POINTER(C.c_int32)), ("step_time", C.POINTER(C.c_double))]
+
+
 class VfConfig(C.Structure):
     _fields_ = [
         ("model_kind", C.c_int32), ("n_dims", C.c_int32), ("dims", C.c_int32 * VF_MAX_DIMS),
@@ -68,6 +73,8 @@ _SIGNATURES = {
                                  C.c_float, C.c_float, C.c_int64, C.c_int64, C.c_void_p]),
     "vf_gemm": (C.c_int, [C.c_int32, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
                           C.c_int32, C.c_int32, C.c_int32, C.c_float, C.c_int32, C.c_int32, C.c_void_p]),
+    "vf_solve_split": (C.c_int, [C.POINTER(VfDeviceProfile), C.c_int32, C.c_int32, C.c_double,
+                                 C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_double)]),
 }
 
 
@@ -153,6 +160,24 @@ def vf_gemm(A, B, Cout, M: int, N: int, K: int, alpha: float = 1.0, accumulate: 
     _check(lib().vf_gemm(dtype, _ptr(A), A.stride(0), _ptr(B), B.stride(0), _ptr(Cout), ldc,
                          M, N, K, float(alpha), int(bool(accumulate)), int(nsplit),
                          _stream_handle(stream)), "vf_gemm")
+
+
+def vf_solve_split(types, B: int, comm: float = 0.0):
+    """types: sequence of (n_devices, batches, step_times).  Returns (b list, v list, step time)."""
+    n = len(types)
+    arr = (VfDeviceProfile * max(n, 1))()
+    keep = []
+    for i, (nd, batches, times) in enumerate(types):
+        bs = (C.c_int32 * max(len(batches), 1))(*[int(b) for b in batches])
+        ts = (C.c_double * max(len(times), 1))(*[float(t) for t in times])
+        keep += [bs, ts]
+        arr[i].n_devices, arr[i].n_points = int(nd), len(batches)
+        arr[i].batch, arr[i].step_time = bs, ts
+    b = (C.c_int32 * max(n, 1))()
+    v = (C.c_int32 * max(n, 1))()
+    t = C.c_double()
+    _check(lib().vf_solve_split(arr, n, int(B), float(comm), b, v, C.byref(t)), "vf_solve_split")
+    return list(b[:n]), list(v[:n]), float(t.value)
 
 
 def config_from_workload(wl, max_batch: Optional[int] = None, max_node_size: Optional[int] = None,
