@@ -87,6 +87,9 @@ typedef struct vf_config {
   int32_t dtype;                 /* VF_F32 | VF_BF16 */
   int32_t optimizer;             /* VF_SGDM | VF_ADAM */
   float   lr, momentum, beta1, beta2, adam_eps, bn_eps, ln_eps;
+  float   bn_momentum;           /* MLP with BatchNorm: share of a pass's statistics blended into
+                                    the moving mean / variance after every virtual node, in
+                                    [0, 1]; 0 freezes them */
   int32_t max_batch;             /* largest B a step may use */
   int32_t max_node_size;         /* largest b_i; sizes the per-node workspace */
   int32_t max_nodes;             /* largest V */
@@ -199,6 +202,35 @@ int vf_adam_update(float* theta, float* m, float* u, const float* G, float lr, f
 int vf_gemm(int32_t dtype, const void* A, int64_t lda, const void* B, int64_t ldb, float* C,
             int64_t ldc, int32_t M, int32_t N, int32_t K, float alpha, int32_t accumulate,
             int32_t nsplit, void* stream);
+
+/* ---- training state of this device (Section 4.1) ---------------------------------------
+ * What a device that joins a job has to receive before it can continue the job's steps: the
+ * master parameters, the optimizer state, and the state the passes themselves carry (the
+ * BatchNorm moving mean and variance, which every device updates on its own, once per virtual
+ * node in node order, from that node's statistics:  moving += bn_momentum * (node - moving),
+ * biased variance; start: mean 0, variance 1.  The paper does not say how several nodes on one
+ * device share the moving statistics; this is the reading of a framework that runs the nodes
+ * as consecutive passes).  Payload, little endian, VF_STATE_HEADER_BYTES + 4*(P + n_opt*P + 2*S)
+ * bytes:
+ *   int64 header[8] = { VF_STATE_MAGIC, P, n_opt (1 SGD-momentum, 2 Adam), S (summed width of
+ *                       the BatchNorm layers), completed steps, optimizer, 0, 0 }
+ *   fp32 theta[P]; fp32 opt[n_opt][P] (v | m, u); fp32 moving_mean[S]; fp32 moving_var[S]
+ * (BatchNorm layers in forward order). */
+#define VF_STATE_MAGIC        0x3145544154534656LL   /* "VFSTATE1" */
+#define VF_STATE_HEADER_BYTES 64
+
+/* Size of the payload for this context. */
+int64_t vf_state_bytes(const vf_ctx* ctx);
+
+/* Writes the payload to dst (device or host pointer, `bytes` >= vf_state_bytes).  params: device,
+ * the master parameters the caller owns.  Synchronises the context's stream. */
+int vf_state_export(vf_ctx* ctx, const float* params, void* dst, int64_t bytes);
+
+/* Reads a payload (device or host pointer) written by vf_state_export of a context with the same
+ * model and optimizer: overwrites params (device), the optimizer state, the moving statistics
+ * and the step count (Adam's bias correction depends on it).  VF_EINVAL and nothing changed if
+ * the header does not match this context.  Synchronises the context's stream. */
+int vf_state_import(vf_ctx* ctx, float* params, const void* src, int64_t bytes);
 
 /* ---- heterogeneous split solver (host only) ---------------------------------------------- */
 

@@ -38,11 +38,11 @@ def batchnorm_fwd(z, gamma, beta, eps):
     var = ((z - mu) ** 2).sum(axis=0) / n
     rstd = 1.0 / np.sqrt(var + eps)
     xhat = (z - mu) * rstd
-    return gamma * xhat + beta, (xhat, rstd)
+    return gamma * xhat + beta, (xhat, rstd, mu, var)
 
 
 def batchnorm_bwd(dout, gamma, cache):
-    xhat, rstd = cache
+    xhat, rstd = cache[:2]
     n = dout.shape[0]
     dgamma = (dout * xhat).sum(axis=0)
     dbeta = dout.sum(axis=0)

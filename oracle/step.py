@@ -104,7 +104,8 @@ def _mlp_node(wl, p, x, y, accum32=False):
             dz = dpre
             g[f"l{l}.b"] = dz.sum(axis=0)
         dh, g[f"l{l}.W"], _ = L.linear_bwd(h_in, p[f"l{l}.W"], q(dz), False)
-    return loss, g, margin
+    stats = [(c[2], c[3]) for _, _, c in saved] if wl.batchnorm else []
+    return loss, g, margin, stats
 
 
 def _split_heads(t, n_heads):
@@ -197,11 +198,13 @@ def node_loss_and_grads(wl, compute_params, x_node, y_node, diag=None, accum32=F
     tests of deep bf16 networks use to calibrate their tolerance, never as the reference."""
     p = unflatten(wl, compute_params)
     if wl.kind == "mlp":
-        loss, g, margin = _mlp_node(wl, p, x_node, y_node, accum32)
+        loss, g, margin, stats = _mlp_node(wl, p, x_node, y_node, accum32)
     else:
         loss, g, margin = _encoder_node(wl, p, x_node, y_node)
+        stats = []
     if diag is not None:
         diag["relu_margin"] = margin
+        diag["bn_stats"] = stats          # per BatchNorm layer: (mean, biased variance) of this node
     return loss, _flatten(wl, g)
 
 
@@ -217,9 +220,21 @@ def compute_copy(wl, theta):
 
 
 def new_state(wl, n):
-    if wl.optimizer == "sgdm":
-        return {"t": 0, "v": np.zeros(n)}
-    return {"t": 0, "m": np.zeros(n), "u": np.zeros(n)}
+    st = {"t": 0, "v": np.zeros(n)} if wl.optimizer == "sgdm" else {"t": 0, "m": np.zeros(n), "u": np.zeros(n)}
+    if wl.kind == "mlp" and wl.batchnorm:      # moving statistics start at mean 0, variance 1
+        widths = wl.dims[1:-1]
+        st["bn_mean"] = [np.zeros(n_) for n_ in widths]
+        st["bn_var"] = [np.ones(n_) for n_ in widths]
+    return st
+
+
+def blend_moving_stats(moving_mean, moving_var, node_stats, share):
+    """Section 4.1: moving mean / variance belong to the device and are updated by every pass
+    it runs, i.e. once per virtual node, in node order, from that node's own statistics
+    (biased variance): moving <- (1 - share) * moving + share * node."""
+    mean = [(1.0 - share) * m + share * s[0] for m, s in zip(moving_mean, node_stats)]
+    var = [(1.0 - share) * v + share * s[1] for v, s in zip(moving_var, node_stats)]
+    return mean, var
 
 
 def oracle_step(wl, theta, x, y, node_sizes=None, state=None, nodes=None):
@@ -238,6 +253,8 @@ def oracle_step(wl, theta, x, y, node_sizes=None, state=None, nodes=None):
     node_losses = []
     relu_margin = np.inf
     which = range(len(sizes)) if nodes is None else nodes
+    state = new_state(wl, n) if state is None else state
+    bn_mean, bn_var = state.get("bn_mean"), state.get("bn_var")
     for i in which:                                          # node after node (Section 3.2)
         lo, hi = int(off[i]), int(off[i + 1])
         diag = {}
@@ -247,7 +264,8 @@ def oracle_step(wl, theta, x, y, node_sizes=None, state=None, nodes=None):
         loss += weight * L_i
         node_losses.append(L_i)
         relu_margin = min(relu_margin, diag["relu_margin"])
-    state = new_state(wl, n) if state is None else state
+        if bn_mean is not None:
+            bn_mean, bn_var = blend_moving_stats(bn_mean, bn_var, diag["bn_stats"], wl.bn_momentum)
     t = state["t"] + 1
     theta64 = (np.asarray(theta, dtype=np.float64) if wl.dtype == "f64"
                else np.asarray(theta, dtype=np.float32).astype(np.float64))
@@ -258,5 +276,7 @@ def oracle_step(wl, theta, x, y, node_sizes=None, state=None, nodes=None):
         theta_new, m, u = adam_update(theta64, G, state["m"], state["u"], t, wl.lr,
                                       wl.beta1, wl.beta2, wl.adam_eps)
         new = {"t": t, "m": m, "u": u}
+    if bn_mean is not None:
+        new["bn_mean"], new["bn_var"] = bn_mean, bn_var
     return {"off": off, "w": w, "loss": loss, "node_losses": np.array(node_losses),
             "G": G, "theta": theta_new, "state": new, "relu_margin": relu_margin}

@@ -29,6 +29,10 @@ class VfError(RuntimeError):
         super().__init__(f"{where}: error {code}" + (f" ({detail})" if detail else ""))
 
 
+VF_STATE_MAGIC = 0x3145544154534656
+VF_STATE_HEADER_BYTES = 64
+
+
 class VfDeviceProfile(C.Structure):
     _fields_ = [("n_devices", C.c_int32), ("n_points", C.c_int32),
                 ("batch", C.POINTER(C.c_int32)), ("step_time", C.POINTER(C.c_double))]
@@ -43,6 +47,7 @@ class VfConfig(C.Structure):
         ("dtype", C.c_int32), ("optimizer", C.c_int32),
         ("lr", C.c_float), ("momentum", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float),
         ("adam_eps", C.c_float), ("bn_eps", C.c_float), ("ln_eps", C.c_float),
+        ("bn_momentum", C.c_float),
         ("max_batch", C.c_int32), ("max_node_size", C.c_int32), ("max_nodes", C.c_int32),
         ("flags", C.c_uint32), ("stream", C.c_void_p),
     ]
@@ -73,6 +78,9 @@ _SIGNATURES = {
                                  C.c_float, C.c_float, C.c_int64, C.c_int64, C.c_void_p]),
     "vf_gemm": (C.c_int, [C.c_int32, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
                           C.c_int32, C.c_int32, C.c_int32, C.c_float, C.c_int32, C.c_int32, C.c_void_p]),
+    "vf_state_bytes": (C.c_int64, [C.c_void_p]),
+    "vf_state_export": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64]),
+    "vf_state_import": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64]),
     "vf_solve_split": (C.c_int, [C.POINTER(VfDeviceProfile), C.c_int32, C.c_int32, C.c_double,
                                  C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_double)]),
 }
@@ -162,6 +170,20 @@ def vf_gemm(A, B, Cout, M: int, N: int, K: int, alpha: float = 1.0, accumulate: 
                          _stream_handle(stream)), "vf_gemm")
 
 
+def parse_state(payload: np.ndarray) -> dict:
+    """Splits a host payload of vf_state_export into its parts (views, no arithmetic)."""
+    header = payload[:VF_STATE_HEADER_BYTES].view(np.int64)
+    if int(header[0]) != VF_STATE_MAGIC:
+        raise VfError("not a state payload")
+    P, n_opt, S, steps = (int(v) for v in header[1:5])
+    body = payload[VF_STATE_HEADER_BYTES:VF_STATE_HEADER_BYTES + 4 * (P + n_opt * P + 2 * S)].view(np.float32)
+    out = {"P": P, "steps": steps, "optimizer": int(header[5]), "theta": body[:P],
+           "opt": [body[P * (1 + k):P * (2 + k)] for k in range(n_opt)]}
+    tail = body[P * (1 + n_opt):]
+    out["bn_mean"], out["bn_var"] = tail[:S], tail[S:2 * S]
+    return out
+
+
 def vf_solve_split(types, B: int, comm: float = 0.0):
     """types: sequence of (n_devices, batches, step_times).  Returns (b list, v list, step time)."""
     n = len(types)
@@ -198,6 +220,7 @@ def config_from_workload(wl, max_batch: Optional[int] = None, max_node_size: Opt
     cfg.optimizer = {"sgdm": VF_SGDM, "adam": VF_ADAM}[wl.optimizer]
     cfg.lr, cfg.momentum, cfg.beta1, cfg.beta2 = wl.lr, wl.momentum, wl.beta1, wl.beta2
     cfg.adam_eps, cfg.bn_eps, cfg.ln_eps = wl.adam_eps, wl.bn_eps, wl.ln_eps
+    cfg.bn_momentum = wl.bn_momentum
     cfg.max_batch = int(max_batch if max_batch is not None else wl.batch)
     cfg.max_node_size = int(max_node_size if max_node_size is not None else max(wl.node_sizes))
     cfg.max_nodes = int(max_nodes if max_nodes is not None else len(wl.node_sizes))
@@ -277,6 +300,26 @@ class VirtualNodeStep:
         buf = (C.c_float * V)()
         _check(lib().vf_node_losses(self._h, buf, V), "vf_node_losses")
         return np.array(buf[:V], dtype=np.float32)
+
+    @property
+    def state_bytes(self) -> int:
+        return int(lib().vf_state_bytes(self._h))
+
+    def state_export(self, params, out=None):
+        """vf_state_export into `out` (a uint8 torch tensor on the device or the host, or None for
+        a new host numpy buffer).  Returns `out`."""
+        n = self.state_bytes
+        if out is None:
+            out = np.empty(n, dtype=np.uint8)
+        ptr = out.ctypes.data if isinstance(out, np.ndarray) else _ptr(out)
+        size = out.nbytes if isinstance(out, np.ndarray) else out.numel() * out.element_size()
+        _check(lib().vf_state_export(self._h, _ptr(params), ptr, size), "vf_state_export")
+        return out
+
+    def state_import(self, params, payload):
+        ptr = payload.ctypes.data if isinstance(payload, np.ndarray) else _ptr(payload)
+        size = payload.nbytes if isinstance(payload, np.ndarray) else payload.numel() * payload.element_size()
+        _check(lib().vf_state_import(self._h, _ptr(params), ptr, size), "vf_state_import")
 
     def opt_state(self, which: int, out):
         _check(lib().vf_opt_state(self._h, which, _ptr(out)), "vf_opt_state")

@@ -68,7 +68,9 @@ __global__ __launch_bounds__(256) void bn_relu_fwd_kernel(const float* __restric
                                                           T* __restrict__ a, int64_t lda,
                                                           bf16_t* __restrict__ aT, int64_t ldt,
                                                           float* __restrict__ mean_out,
-                                                          float* __restrict__ rstd_out) {
+                                                          float* __restrict__ rstd_out,
+                                                          float* __restrict__ run_mean,
+                                                          float* __restrict__ run_var, float run_mix) {
   __shared__ float red[RL][CB + 1];
   __shared__ __attribute__((aligned(16))) bf16_t tile[CB][RCH + 8];
   const int tx = threadIdx.x % CB, ty = threadIdx.x / CB;
@@ -120,7 +122,13 @@ __global__ __launch_bounds__(256) void bn_relu_fwd_kernel(const float* __restric
     if (live) {
       g = gamma[c]; b = beta[c];
       if (round_params) { g = round_bf16(g); b = round_bf16(b); }
-      if (ty == 0) { mean_out[c] = mean; rstd_out[c] = rstd; }
+      if (ty == 0) {
+        mean_out[c] = mean; rstd_out[c] = rstd;
+        if (run_mean) {   // moving statistics of this device: one blend per pass (Section 4.1)
+          run_mean[c] = fmaf(run_mix, mean - run_mean[c], run_mean[c]);
+          run_var[c] = fmaf(run_mix, var - run_var[c], run_var[c]);
+        }
+      }
     }
   }
   // pass 2: activation, in chunks of RCH rows so the transposed copy can go through LDS
@@ -274,14 +282,16 @@ __global__ __launch_bounds__(256) void rowsum_kernel(const bf16_t* __restrict__ 
 int launch_bn_relu_fwd(const float* zp, int nsplit, int64_t slab, int64_t ldzp, int R, int C,
                        const float* gamma, const float* beta, int round_params, float eps, float* z,
                        int64_t ldz, void* a, int64_t lda, int a_is_bf16, bf16_t* aT, int64_t ldt,
-                       float* mean, float* rstd, hipStream_t s) {
+                       float* mean, float* rstd, float* run_mean, float* run_var, float run_mix,
+                       hipStream_t s) {
   if (R <= 0 || C <= 0 || nsplit < 1) return VF_EINVAL;
+  if ((run_mean == nullptr) != (run_var == nullptr)) return VF_EINVAL;
   if (aT && ((ldt & 7) || !a_is_bf16)) return VF_EINVAL;
   const int grid = (C + CB - 1) / CB;
   const bool small = R <= RCH;
 #define VF_FWD2(TT, NS, SM)                                                                        \
   bn_relu_fwd_kernel<TT, NS, SM><<<grid, 256, 0, s>>>(zp, slab, ldzp, R, C, gamma, beta, round_params, \
-      eps, z, ldz, static_cast<TT*>(a), lda, aT, ldt, mean, rstd)
+      eps, z, ldz, static_cast<TT*>(a), lda, aT, ldt, mean, rstd, run_mean, run_var, run_mix)
 #define VF_FWD(NS)                                                                                 \
   case NS:                                                                                         \
     if (a_is_bf16) { if (small) VF_FWD2(bf16_t, NS, true); else VF_FWD2(bf16_t, NS, false); }      \

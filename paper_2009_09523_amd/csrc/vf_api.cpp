@@ -36,6 +36,7 @@ int validate_config(const vf_config& c) {
   if (c.optimizer != VF_SGDM && c.optimizer != VF_ADAM) return VF_EINVAL;
   if (c.max_batch < 1 || c.max_node_size < 1 || c.max_nodes < 1) return VF_EINVAL;
   if (c.max_node_size > c.max_batch) return VF_EINVAL;
+  if (!(c.bn_momentum >= 0.f && c.bn_momentum <= 1.f)) return VF_EINVAL;
   if (c.model_kind == VF_MLP) {
     if (c.n_dims < 2 || c.n_dims > VF_MAX_DIMS) return VF_EINVAL;
     for (int i = 0; i < c.n_dims; ++i)
@@ -301,6 +302,7 @@ int vf_init(const vf_config* cfg, vf_ctx** out) {
   arena.assign(c.arena);
   // optimizer state and loss cells start at zero
   e = hipMemsetAsync(c.arena, 0, c.arena_bytes, c.stream);
+  if (e == hipSuccess && c.model->init_state(c.stream) != VF_OK) e = hipErrorUnknown;
   if (e == hipSuccess) e = hipStreamSynchronize(c.stream);
   if (e != hipSuccess) {
     set_last_error("hipMemsetAsync", e, __FILE__, __LINE__);
@@ -406,6 +408,53 @@ int vf_profile_stop(vf_ctx* h, char* out, size_t cap) {
   js += "}";
   if (js.size() + 1 > cap) return VF_EINVAL;
   std::memcpy(out, js.c_str(), js.size() + 1);
+  return VF_OK;
+}
+
+int64_t vf_state_bytes(const vf_ctx* h) {
+  if (!h) return 0;
+  const Ctx& c = h->c;
+  const int64_t n_opt = c.cfg.optimizer == VF_ADAM ? 2 : 1;
+  return VF_STATE_HEADER_BYTES + 4 * (c.P + n_opt * c.P + c.model->state_floats());
+}
+
+int vf_state_export(vf_ctx* h, const float* params, void* dst, int64_t bytes) {
+  if (!h || !params || !dst || bytes < vf_state_bytes(h)) return VF_EINVAL;
+  Ctx& c = h->c;
+  const int64_t n_opt = c.cfg.optimizer == VF_ADAM ? 2 : 1;
+  const int64_t S2 = c.model->state_floats();
+  const int64_t header[8] = {VF_STATE_MAGIC, c.P, n_opt, S2 / 2, c.steps, c.cfg.optimizer, 0, 0};
+  char* out = static_cast<char*>(dst);
+  const size_t pb = (size_t)c.P * sizeof(float);
+  VF_HIP(hipMemcpyAsync(out, header, sizeof header, hipMemcpyDefault, c.stream));
+  out += VF_STATE_HEADER_BYTES;
+  VF_HIP(hipMemcpyAsync(out, params, pb, hipMemcpyDefault, c.stream)); out += pb;
+  VF_HIP(hipMemcpyAsync(out, c.opt0, pb, hipMemcpyDefault, c.stream)); out += pb;
+  if (n_opt == 2) { VF_HIP(hipMemcpyAsync(out, c.opt1, pb, hipMemcpyDefault, c.stream)); out += pb; }
+  if (S2) VF_HIP(hipMemcpyAsync(out, c.model->state_ptr(), (size_t)S2 * sizeof(float), hipMemcpyDefault, c.stream));
+  VF_HIP(hipStreamSynchronize(c.stream));   // `header` lives on this frame
+  return VF_OK;
+}
+
+int vf_state_import(vf_ctx* h, float* params, const void* src, int64_t bytes) {
+  if (!h || !params || !src || bytes < vf_state_bytes(h)) return VF_EINVAL;
+  Ctx& c = h->c;
+  const int64_t n_opt = c.cfg.optimizer == VF_ADAM ? 2 : 1;
+  const int64_t S2 = c.model->state_floats();
+  int64_t header[8];
+  VF_HIP(hipStreamSynchronize(c.stream));
+  VF_HIP(hipMemcpy(header, src, sizeof header, hipMemcpyDefault));
+  if (header[0] != VF_STATE_MAGIC || header[1] != c.P || header[2] != n_opt || header[3] != S2 / 2 ||
+      header[4] < 0 || header[5] != c.cfg.optimizer)
+    return VF_EINVAL;
+  const char* in = static_cast<const char*>(src) + VF_STATE_HEADER_BYTES;
+  const size_t pb = (size_t)c.P * sizeof(float);
+  VF_HIP(hipMemcpyAsync(params, in, pb, hipMemcpyDefault, c.stream)); in += pb;
+  VF_HIP(hipMemcpyAsync(c.opt0, in, pb, hipMemcpyDefault, c.stream)); in += pb;
+  if (n_opt == 2) { VF_HIP(hipMemcpyAsync(c.opt1, in, pb, hipMemcpyDefault, c.stream)); in += pb; }
+  if (S2) VF_HIP(hipMemcpyAsync(c.model->state_ptr(), in, (size_t)S2 * sizeof(float), hipMemcpyDefault, c.stream));
+  VF_HIP(hipStreamSynchronize(c.stream));
+  c.steps = header[4];
   return VF_OK;
 }
 

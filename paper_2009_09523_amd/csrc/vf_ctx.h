@@ -59,6 +59,12 @@ class Model {
   virtual int run_node_main(Ctx& c, const StepArgs& a, int i, hipStream_t st) = 0;
   virtual int run_node_side(Ctx& c, const StepArgs& a, int i, hipStream_t st) = 0;
   virtual bool supports_overlap() const { return false; }
+  // State that the passes themselves carry from step to step on this device (BatchNorm moving
+  // mean and variance, Section 4.1): `state_floats` fp32 values at `state_ptr`, laid out as all
+  // layers' means then all layers' variances; init_state sets the starting values.
+  virtual int64_t state_floats() const { return 0; }
+  virtual float* state_ptr() const { return nullptr; }
+  virtual int init_state(hipStream_t) { return VF_OK; }
 };
 
 // Optional per-kernel timing: while enabled, every launch made through VF_K is bracketed by

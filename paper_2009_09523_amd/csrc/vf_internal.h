@@ -108,10 +108,13 @@ int launch_cast_bf16(const float* in, int64_t ldi, bf16_t* out, int64_t ldo, int
 // leading dimension ldzp) of the Linear output; their sum is written to z (saved for the
 // backward pass).  a = relu(gamma*xhat + beta) as T; aT (optional, bf16 only) the same
 // transposed, [C, ldt].  Saves mean, rstd.  With gamma == nullptr: a = relu(z).
+// run_mean / run_var (both or neither): moving statistics, blended in place with the pass's
+// own: run += run_mix * (stat - run), biased variance.
 int launch_bn_relu_fwd(const float* zp, int nsplit, int64_t slab, int64_t ldzp, int R, int C,
                        const float* gamma, const float* beta, int round_params, float eps, float* z,
                        int64_t ldz, void* a, int64_t lda, int a_is_bf16, bf16_t* aT, int64_t ldt,
-                       float* mean, float* rstd, hipStream_t s);
+                       float* mean, float* rstd, float* run_mean, float* run_var, float run_mix,
+                       hipStream_t s);
 // Backward of the above.  dap: nsplit partial slabs of the fp32 gradient w.r.t. a (slab 0 is
 // overwritten when nsplit > 1).  Writes dz (T), dzT (optional, bf16, [C, ldt]) and, with
 // BatchNorm, dgamma/dbeta through GradOut; without BatchNorm (gamma == nullptr) the bias

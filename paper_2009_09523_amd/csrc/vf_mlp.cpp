@@ -20,6 +20,7 @@ struct Layer {
   float* z = nullptr;              // fp32 [max_b, ld]: Linear output (logits for the last layer)
   float* mean = nullptr;           // [N]
   float* rstd = nullptr;           // [N]
+  int64_t s_off = 0;               // offset of this layer's moving statistics within a state half
   void* a = nullptr;               // T [max_b, ld]: activation after BatchNorm/ReLU
   void* dz = nullptr;              // T [max_b, ld]: gradient w.r.t. z
   // Weight-gradient operands, transposed ([N, ldb], rows of the node contiguous).  Two copies:
@@ -51,6 +52,8 @@ class Mlp final : public Model {
       L.ldt = round8(L.K);
     }
     P_ = off;
+    for (Layer& L : layers_)
+      if (L.has_bn) { L.s_off = bn_width_; bn_width_ += L.N; }
     ldb_ = round8(cfg.max_node_size);
     // Scratch for GEMM outputs that arrive as partial slabs: the largest split * rows * ld
     // over the forward (N_l columns) and input-gradient (K_l columns) products.
@@ -107,6 +110,15 @@ class Mlp final : public Model {
     if (bf16_)
       for (int k = 0; k < 2; ++k) a.request(&xT_[k], (size_t)cfg_.dims[0] * ldb_);
     a.request(&slab_, (size_t)slab_elems_);
+    if (bn_width_) a.request(&state_, (size_t)(2 * bn_width_));
+  }
+
+  int64_t state_floats() const override { return 2 * bn_width_; }
+  float* state_ptr() const override { return state_; }
+  int init_state(hipStream_t st) override {   // moving mean 0, moving variance 1
+    if (!bn_width_) return VF_OK;
+    VF_TRY(launch_fill_f32(state_, 0.f, bn_width_, st));
+    return launch_fill_f32(state_ + bn_width_, 1.f, bn_width_, st);
   }
 
   int prepare(Ctx& c, const float* params, hipStream_t st) override {
@@ -148,7 +160,8 @@ class Mlp final : public Model {
         VF_KS(c, st, "bn_relu_fwd", launch_bn_relu_fwd(slab_, split, slab, L.ld, b, L.N,
                                        L.has_bn ? P + L.g_off : nullptr, L.has_bn ? P + L.be_off : nullptr,
                                        bf16_, cfg_.bn_eps, L.z, L.ld, L.a, L.ld, bf16_, L.aT[p], ldb_,
-                                       L.mean, L.rstd, st));
+                                       L.mean, L.rstd, L.has_bn ? state_ + L.s_off : nullptr,
+                                       L.has_bn ? state_ + bn_width_ + L.s_off : nullptr, cfg_.bn_momentum, st));
       else
         VF_KS(c, st, "softmax_xent", launch_softmax_xent(slab_, split, slab, L.ld, L.z, L.ld, y, b, L.N,
                                                          c.rowloss, L.dz, L.ld, bf16_, L.dzT[p], ldb_, w, i,
@@ -223,6 +236,8 @@ class Mlp final : public Model {
   bf16_t* xT_[2] = {nullptr, nullptr};
   float* slab_ = nullptr;
   int64_t slab_elems_ = 0;
+  int64_t bn_width_ = 0;           // summed width of the BatchNorm layers
+  float* state_ = nullptr;         // [2 * bn_width_]: moving means, then moving variances
 };
 
 }  // namespace

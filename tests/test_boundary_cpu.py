@@ -92,3 +92,14 @@ def test_bf16_mlp_needs_16_byte_rows():
     cfg = binding.config_from_workload(wl)
     h = C.c_void_p()
     assert vf.lib().vf_init(C.byref(cfg), C.byref(h)) == binding.VF_EINVAL
+
+
+def test_state_size_of_a_null_context_is_zero_and_config_rejects_a_bad_share():
+    import ctypes as C
+    assert vf.lib().vf_state_bytes(None) == 0
+    from paper_2009_09523_amd.binding import config_from_workload
+    import vf_inputs as I
+    from dataclasses import replace
+    cfg = config_from_workload(replace(I.workload("mlp_small_bn_f32"), bn_momentum=1.5))
+    h = C.c_void_p()
+    assert vf.lib().vf_init(C.byref(cfg), C.byref(h)) != 0 and not h

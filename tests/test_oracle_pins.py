@@ -325,3 +325,61 @@ def test_bf16_operand_rounding_is_a_small_perturbation_and_exact_when_representa
     np.testing.assert_allclose(r16["G"][32:], r32["G"][32:], rtol=1e-13, atol=1e-16)
     # the weight gradient uses the rounded output gradient: within bf16 rounding of it
     assert np.max(np.abs(r16["G"][:32] - r32["G"][:32])) <= 2.0 ** -8 * np.max(np.abs(r32["G"][:32]))
+
+
+# ---- moving BatchNorm statistics (Section 4.1: per-device state, updated by every pass) -------
+
+def _bn_workload(node_sizes, lr=0.0):
+    from dataclasses import replace
+    return replace(I.workload("mlp_small_bn_f32"), node_sizes=tuple(node_sizes), lr=lr, momentum=0.0,
+                   dtype="f64")
+
+
+def test_moving_stats_of_identical_nodes_follow_the_geometric_closed_form():
+    """k passes over the same samples from (mean 0, variance 1) with share s leave
+    mean = (1-(1-s)^k) mu and var = (1-s)^k + (1-(1-s)^k) sigma^2, with mu and sigma^2 the
+    library mean / biased variance of the first Linear's output over ONE node."""
+    wl = _bn_workload([6, 6, 6])
+    theta = I.make_params(wl, jitter=0.1).astype(np.float64)
+    x, y = I.make_batch(wl)
+    x = np.tile(x[:6], (3, 1)).astype(np.float64)
+    y = np.tile(y[:6], 3)
+    r = O.oracle_step(wl, theta, x, y)
+    W0 = O.unflatten(wl, theta)["l0.W"]
+    z = x[:6] @ W0
+    keep = (1 - wl.bn_momentum) ** 3
+    np.testing.assert_allclose(r["state"]["bn_mean"][0], (1 - keep) * z.mean(axis=0), rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(r["state"]["bn_var"][0], keep + (1 - keep) * z.var(axis=0), rtol=1e-12)
+    # a second step with a zero learning rate continues the same series (k = 6)
+    r2 = O.oracle_step(wl, r["theta"], x, y, state=r["state"])
+    keep = (1 - wl.bn_momentum) ** 6
+    np.testing.assert_allclose(r2["state"]["bn_mean"][0], (1 - keep) * z.mean(axis=0), rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(r2["state"]["bn_var"][0], keep + (1 - keep) * z.var(axis=0), rtol=1e-12)
+
+
+def test_moving_stats_use_each_nodes_own_samples_in_node_order():
+    wl = _bn_workload([5, 9])
+    theta = I.make_params(wl, jitter=0.1).astype(np.float64)
+    x, y = I.make_batch(wl)
+    x = x.astype(np.float64)
+    r = O.oracle_step(wl, theta, x, y)
+    W0 = O.unflatten(wl, theta)["l0.W"]
+    z1, z2 = x[:5] @ W0, x[5:] @ W0
+    s = wl.bn_momentum
+    want_mean = (1 - s) * (s * z1.mean(axis=0)) + s * z2.mean(axis=0)
+    want_var = (1 - s) * ((1 - s) * 1.0 + s * z1.var(axis=0)) + s * z2.var(axis=0)
+    np.testing.assert_allclose(r["state"]["bn_mean"][0], want_mean, rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(r["state"]["bn_var"][0], want_var, rtol=1e-12)
+    # not the statistics of the whole batch, and not order-free
+    zb = x @ W0
+    assert not np.allclose(r["state"]["bn_mean"][0], s * zb.mean(axis=0))
+    swapped = O.oracle_step(wl.with_nodes([9, 5]), theta, np.concatenate([x[5:], x[:5]]),
+                            np.concatenate([y[5:], y[:5]]))
+    assert not np.allclose(swapped["state"]["bn_mean"][0], r["state"]["bn_mean"][0])
+
+
+def test_models_without_batchnorm_carry_no_moving_stats():
+    wl = I.workload("mlp_small_f32")
+    x, y = I.make_batch(wl)
+    r = O.oracle_step(wl, I.make_params(wl), x, y)
+    assert "bn_mean" not in r["state"]

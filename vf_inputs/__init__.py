@@ -58,6 +58,7 @@ class Workload:
     beta2: float = 0.999
     adam_eps: float = 1e-8
     bn_eps: float = 1e-5
+    bn_momentum: float = 0.1        # share of a node's statistics blended into the moving ones
     ln_eps: float = 1e-5
 
     @property
