@@ -290,6 +290,14 @@ __global__ __launch_bounds__(NT) void gemm_bf16_pipe_kernel(const bf16_t* __rest
       }
     }
     wait_loads_but<0>();   // drain the padding loads before the registers are reused
+    // the destination registers of loads that were still in flight stay allocated up to here
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+#pragma unroll
+      for (int i = 0; i < A_VECS; ++i) asm volatile("" ::"v"(ra[s][i]));
+#pragma unroll
+      for (int i = 0; i < B_VECS; ++i) asm volatile("" ::"v"(rb[s][i]));
+    }
   }
 
   const bool first_slice = blockIdx.z == 0;
