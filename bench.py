@@ -249,6 +249,8 @@ def main():
                          "staged: per-node staging vector + the accumulate kernel")
     ap.add_argument("--no-alt", action="store_true", help="skip the timing of the other accumulate mode")
     ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--fold-window", type=int, default=1,
+                    help="fused fold: weight gradients of this many consecutive nodes per pass over the buffer")
     ap.add_argument("--overlap", action="store_true",
                     help="weight gradients on a second stream beside the next node's passes")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -288,7 +290,7 @@ def main():
     flags = (vf.VF_FLAG_FUSED_ACCUMULATE if args.accumulate == "fused" else 0) | \
             (vf.VF_FLAG_NO_GRAPH if args.no_graph else 0) | \
             (vf.VF_FLAG_OVERLAP if args.overlap else 0)
-    eng = vf.VirtualNodeStep(config_from_workload(wl, flags=flags, stream=stream))
+    eng = vf.VirtualNodeStep(config_from_workload(wl, flags=flags, stream=stream, fold_window=args.fold_window))
     P = eng.num_params
     params = torch.from_numpy(theta).cuda()
     xt = torch.from_numpy(x).cuda()

@@ -93,6 +93,13 @@ typedef struct vf_config {
   int32_t max_batch;             /* largest B a step may use */
   int32_t max_node_size;         /* largest b_i; sizes the per-node workspace */
   int32_t max_nodes;             /* largest V */
+  int32_t fold_window;           /* MLP, bf16, fused fold: the weight gradients of this many
+                                    consecutive nodes (1..8; 0 = 1) are folded into the gradient
+                                    buffer in one pass over it.  Same chain of fused multiply-adds
+                                    as node by node (bitwise the same result), 1/window of the
+                                    buffer traffic; the transposed bf16 operands of the window's
+                                    nodes are kept until then, so the workspace grows with the
+                                    window (not with V). */
   uint32_t flags;                /* VF_FLAG_* */
   void*   stream;                /* hipStream_t; NULL = the default stream */
 } vf_config;

@@ -328,6 +328,115 @@ __global__ __launch_bounds__(NT) void gemm_bf16_pipe_kernel(const bf16_t* __rest
   }
 }
 
+// ---- LDS-direct variant -----------------------------------------------------------------------
+// Same 64 x 64 tiling, but the operand tiles go from global memory straight into LDS
+// (global_load_lds_dwordx4: lane l of a wavefront deposits its 16 bytes at LDS base + 16 l), so a
+// stage in flight costs no registers and no LDS-store instructions: a ring of NS stages of
+// 16 KB keeps NS-1 stages (48 KB per workgroup at NS = 4) on their way, which is what a
+// latency-bound node-sized product needs.  A wavefront instruction fills 8 rows of 128 bytes;
+// rows cannot be padded, so the eight 16-byte chunks of a row are stored permuted
+// (chunk c of row r at position c ^ f(r), f(r) = (r & 7) ^ ((r >> 3) & 1)): the 16-byte reads of
+// the MFMA operands (32 rows, one chunk index) then spread over all banks.  The permutation is
+// applied on the global side: a lane fetches the chunk that belongs at its position.
+// Requires a contraction that is a whole number of 64-element stages per slice (operand rows
+// are clamped into the matrix, their products never stored; nothing is masked).
+__device__ __forceinline__ int dl_swizzle(int r) { return (r & 7) ^ ((r >> 3) & 1); }
+
+template <int NS>
+__global__ __launch_bounds__(NT) void gemm_bf16_dl_kernel(const bf16_t* __restrict__ A, int64_t lda,
+                                                          const bf16_t* __restrict__ B, int64_t ldb,
+                                                          int M, int N, int K, int kchunk,
+                                                          int64_t slab_stride, Epilogue ep) {
+  constexpr int TILE = 64 * BK;                 // elements of one operand tile (8 KB)
+  constexpr int STAGE = 2 * TILE;
+  constexpr int LPS = 4;                        // loads per lane and stage (2 for A, 2 for B)
+  static_assert(NS >= 3 && NS <= 6, "ring depth");
+  __shared__ __attribute__((aligned(1024))) bf16_t lds[NS * STAGE];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+  const int kbeg = blockIdx.z * kchunk;
+  const int kend = min(K, kbeg + kchunk);
+  const int nstage = kend > kbeg ? (kend - kbeg) / BK : 0;
+
+  // this lane's source of each of its loads: row (8 rows per wavefront instruction), permuted chunk
+  const bf16_t* ga[2];
+  const bf16_t* gb[2];
+#pragma unroll
+  for (int q = 0; q < 2; ++q) {
+    const int row = (wave * 2 + q) * 8 + (lane >> 3);
+    const int chunk = (lane & 7) ^ dl_swizzle(row);
+    ga[q] = A + (int64_t)min(m0 + row, M - 1) * lda + kbeg + chunk * 8;
+    gb[q] = B + (int64_t)min(n0 + row, N - 1) * ldb + kbeg + chunk * 8;
+  }
+  auto issue = [&](int stage, int slot) {
+    const int k = stage * BK;
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(ga[q] + k),
+                                       (void __attribute__((address_space(3)))*)&lds[slot * STAGE + (wave * 2 + q) * 512],
+                                       16, 0, 0);
+      __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(gb[q] + k),
+                                       (void __attribute__((address_space(3)))*)&lds[slot * STAGE + TILE + (wave * 2 + q) * 512],
+                                       16, 0, 0);
+    }
+  };
+
+  f32x16 acc;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+  const int arow = wm * 32 + (lane & 31), brow = wn * 32 + (lane & 31);
+  const int asw = dl_swizzle(arow), bsw = dl_swizzle(brow);
+
+  if (nstage > 0) {
+    // NS-1 stages in flight (indices past the end repeat the last stage into a free slot: never
+    // read, they only keep the count of outstanding loads uniform)
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s) issue(min(s, nstage - 1), s);
+    for (int it = 0; it < nstage; ++it) {
+      // loads complete in order: stage `it` has landed when at most NS-2 stages are outstanding
+      wait_loads_but<(NS - 2) * LPS>();
+      // every wave's part of stage `it` is in LDS, and every wave is done reading stage it-1,
+      // whose slot the next loads overwrite.  (A bare barrier: the loop issues no LDS stores, and
+      // __syncthreads would wait for ALL outstanding loads.)
+      __builtin_amdgcn_s_barrier();
+      asm volatile("" ::: "memory");
+      issue(min(it + NS - 1, nstage - 1), (it + NS - 1) % NS);
+      const bf16_t* as = &lds[(it % NS) * STAGE];
+      const bf16_t* bs = as + TILE;
+#pragma unroll
+      for (int kk = 0; kk < BK / 16; ++kk) {
+        const int cidx = 2 * kk + (lane >> 5);
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(&as[arow * BK + ((cidx ^ asw) * 8)]);
+        const bf16x8 b = *reinterpret_cast<const bf16x8*>(&bs[brow * BK + ((cidx ^ bsw) * 8)]);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0);
+      }
+    }
+    wait_loads_but<0>();
+  }
+
+  const int n = n0 + wn * 32 + (lane & 31);
+  if (n >= N) return;
+  char* cbase = static_cast<char*>(ep.C) + (int64_t)blockIdx.z * slab_stride * (ep.c_is_bf16 ? 2 : 4);
+  float bias = 0.f;
+  if (ep.bias && blockIdx.z == 0) {
+    bias = ep.bias[n];
+    if (ep.bias_round_bf16) bias = round_bf16(bias);
+  }
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int m = m0 + wm * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+    if (m >= M) continue;
+    float addend = bias;
+    if (ep.R) addend = fmaf(ep.beta, ep.R[(int64_t)m * ep.ldr + n], bias);
+    const float v = fmaf(ep.alpha, acc[r], addend);
+    if (ep.c_is_bf16) reinterpret_cast<bf16_t*>(cbase)[(int64_t)m * ep.ldc + n] = f32_to_bf16(v);
+    else              reinterpret_cast<float*>(cbase)[(int64_t)m * ep.ldc + n] = v;
+  }
+}
+
 // Short contraction (K <= 2*BK = 128: the weight gradient of a node of up to 128 rows).  The
 // cost of such a product is one trip to memory for the operands and the write (or
 // read-modify-write) of the fp32 output, so everything is issued at once: both stages of
@@ -435,11 +544,128 @@ __global__ __launch_bounds__(NT) void gemm_bf16_shortk_kernel(const bf16_t* __re
   }
 }
 
+// Weight gradients of up to kFoldMax consecutive virtual nodes folded into the gradient buffer
+// in ONE pass over it (Section 3.2 step 3 with the weights of Section 5.2):
+//     C[m, n] <- fma(w_{c-1}, P_{c-1}[m, n], ... fma(w_1, P_1[m, n], fma(w_0, P_0[m, n], C[m, n])))
+// with P_j = A_j B_j^T the product over node j's rows (at most 128, contiguous in the transposed
+// operand copies) -- exactly the chain of fused multiply-adds that one launch per node produces,
+// so the result is bitwise the same, but C is read and written once per window instead of once
+// per node.  With `overwrite` the chain starts from zero (first window of a step).
+// 128 x 128 tile, four waves of 64 x 64; node j+1's operands are in flight while node j's
+// products are computed; each product passes through LDS so that a lane owns 16 contiguous
+// bytes of C.  Requires fp32 C, 16-byte aligned, ldc % 4 == 0, N % 4 == 0.
+__global__ __launch_bounds__(NT) void gemm_bf16_fold_kernel(FoldArgs fa, int64_t ld, int M, int N,
+                                                            float* __restrict__ C, int64_t ldc) {
+  constexpr int BM = 128, BN = 128;
+  constexpr int KT = 2 * BK;                  // 128: the longest node
+  constexpr int LD2 = KT + 8;
+  constexpr int LDC = BN + 4;
+  constexpr int A_VECS = BM * (KT / 8) / NT;  // 8
+  constexpr int B_VECS = BN * (KT / 8) / NT;  // 8
+  constexpr int C_VECS = BM * (BN / 4) / NT;  // 16
+
+  __shared__ __attribute__((aligned(16))) char smem[(BM + BN) * LD2 * 2];
+  bf16_t* As = reinterpret_cast<bf16_t*>(smem);
+  bf16_t* Bs = As + BM * LD2;
+  float* Ct = reinterpret_cast<float*>(smem);   // reused between the MFMAs of consecutive nodes
+  static_assert(BM * LDC * 4 <= (BM + BN) * LD2 * 2, "output tile fits in the operand buffers");
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  const int vcol = (tid & 15) * 8;
+  const int vrow = tid >> 4;         // 0..15
+  const int ccol = (tid & 31) * 4;
+  const int crow = tid >> 5;         // 0..7
+  const bool col_ok = n0 + ccol < N;
+
+  u32x4 ra[A_VECS], rb[B_VECS];
+  auto load_node = [&](int j) {
+    const bf16_t* A = fa.A[j];
+    const bf16_t* B = fa.B[j];
+    const int K = fa.K[j];
+#pragma unroll
+    for (int i = 0; i < A_VECS; ++i) ra[i] = load_vec(A, ld, m0 + vrow + 16 * i, M, vcol, K);
+#pragma unroll
+    for (int i = 0; i < B_VECS; ++i) rb[i] = load_vec(B, ld, n0 + vrow + 16 * i, N, vcol, K);
+  };
+  load_node(0);
+
+  float4 c[C_VECS];
+#pragma unroll
+  for (int i = 0; i < C_VECS; ++i) {
+    const int m = m0 + crow + 8 * i;
+    c[i] = (!fa.overwrite && col_ok && m < M) ? *reinterpret_cast<const float4*>(&C[(int64_t)m * ldc + n0 + ccol])
+                                              : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+
+  for (int j = 0; j < fa.count; ++j) {
+    if (j) __syncthreads();                    // every lane has read node j-1's tile
+#pragma unroll
+    for (int i = 0; i < A_VECS; ++i) *reinterpret_cast<u32x4*>(&As[(vrow + 16 * i) * LD2 + vcol]) = ra[i];
+#pragma unroll
+    for (int i = 0; i < B_VECS; ++i) *reinterpret_cast<u32x4*>(&Bs[(vrow + 16 * i) * LD2 + vcol]) = rb[i];
+    __syncthreads();
+    if (j + 1 < fa.count) load_node(j + 1);    // in flight during this node's MFMAs
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int ti = 0; ti < 2; ++ti)
+#pragma unroll
+      for (int tj = 0; tj < 2; ++tj)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[ti][tj][r] = 0.f;
+    const int ksteps = (fa.K[j] + 15) / 16;
+#pragma unroll
+    for (int ks = 0; ks < KT / 16; ++ks) {
+      if (ks < ksteps) {
+        const int koff = ks * 16 + (lane >> 5) * 8;
+        bf16x8 a[2], b[2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          a[t] = *reinterpret_cast<const bf16x8*>(&As[(wm * 64 + t * 32 + (lane & 31)) * LD2 + koff]);
+          b[t] = *reinterpret_cast<const bf16x8*>(&Bs[(wn * 64 + t * 32 + (lane & 31)) * LD2 + koff]);
+        }
+#pragma unroll
+        for (int ti = 0; ti < 2; ++ti)
+#pragma unroll
+          for (int tj = 0; tj < 2; ++tj)
+            acc[ti][tj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ti], b[tj], acc[ti][tj], 0, 0, 0);
+      }
+    }
+    __syncthreads();                           // operands consumed: the tile may overwrite them
+#pragma unroll
+    for (int ti = 0; ti < 2; ++ti)
+#pragma unroll
+      for (int tj = 0; tj < 2; ++tj)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row = wm * 64 + ti * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+          Ct[row * LDC + wn * 64 + tj * 32 + (lane & 31)] = acc[ti][tj][r];
+        }
+    __syncthreads();
+    const float w = fa.w[j];
+#pragma unroll
+    for (int i = 0; i < C_VECS; ++i) {
+      const float4 p = *reinterpret_cast<const float4*>(&Ct[(crow + 8 * i) * LDC + ccol]);
+      c[i].x = fmaf(w, p.x, c[i].x); c[i].y = fmaf(w, p.y, c[i].y);
+      c[i].z = fmaf(w, p.z, c[i].z); c[i].w = fmaf(w, p.w, c[i].w);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < C_VECS; ++i) {
+    const int m = m0 + crow + 8 * i;
+    if (col_ok && m < M) *reinterpret_cast<float4*>(&C[(int64_t)m * ldc + n0 + ccol]) = c[i];
+  }
+}
+
 struct Shape {
   const bf16_t* A; int64_t lda; const bf16_t* B; int64_t ldb; int M, N, K, nsplit; int64_t slab;
 };
 
 bool shortk_enabled();
+int dl_depth();
 int pipe_depth();   // 0 = plain kernel, 2..4 = ring depth of the pipelined kernel
 
 template <int BM, int BN, int WGM, int WGN>
@@ -489,6 +715,16 @@ bool shortk_enabled() {   // tuning aid: VF_GEMM_SHORTK=0 sends weight gradients
   return cached != 0;
 }
 
+int dl_depth() {   // tuning aid: VF_GEMM_DL=0 disables the LDS-direct kernel, 3..5 sets its ring depth
+  static int cached = -1;
+  if (cached < 0) {
+    const char* e = std::getenv("VF_GEMM_DL");
+    cached = e ? std::atoi(e) : 4;
+    if (cached != 0 && (cached < 3 || cached > 5)) cached = 4;
+  }
+  return cached;
+}
+
 int pipe_depth() {
   static int cached = -1;
   if (cached < 0) {
@@ -513,8 +749,9 @@ int gemm_bf16_pick_split(int M, int N, int K) {
   int bm = M <= 32 ? 32 : 64;
   int bn = M <= 32 ? 128 : 64;
   int64_t tiles = (int64_t)((M + bm - 1) / bm) * ((N + bn - 1) / bn);
+  static const int target = std::getenv("VF_GEMM_SPLIT_TARGET") ? std::atoi(std::getenv("VF_GEMM_SPLIT_TARGET")) : 256;
   int split = 1;
-  while (tiles * split < 512 && K / (split * 2) >= 3 * BK && split < 32) split *= 2;
+  while (tiles * split < target && K / (split * 2) >= 3 * BK && split < 32) split *= 2;
   return split;
 }
 
@@ -549,7 +786,33 @@ int launch_gemm_bf16(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb,
   if (use_big_tile(M, N, K)) return launch_cfg<128, 128, 2, 2>(g, ep, s);
   if (M <= 32) return launch_cfg<32, 128, 1, 4>(g, ep, s);
   if (N <= 32) return launch_cfg<128, 32, 4, 1>(g, ep, s);
+  // whole 64-element stages in every slice: operand tiles straight into LDS
+  const int kchunk = ((K + nsplit - 1) / nsplit + BK - 1) / BK * BK;
+  const int depth = dl_depth();
+  if (depth && (K % BK) == 0 && (K % kchunk) == 0) {
+    dim3 grid((N + 63) / 64, (M + 63) / 64, nsplit);
+    switch (depth) {
+      case 3: gemm_bf16_dl_kernel<3><<<grid, NT, 0, s>>>(A, lda, B, ldb, M, N, K, kchunk, slab_stride, ep); break;
+      case 5: gemm_bf16_dl_kernel<5><<<grid, NT, 0, s>>>(A, lda, B, ldb, M, N, K, kchunk, slab_stride, ep); break;
+      default: gemm_bf16_dl_kernel<4><<<grid, NT, 0, s>>>(A, lda, B, ldb, M, N, K, kchunk, slab_stride, ep); break;
+    }
+    VF_LAUNCH_CHECK();
+    return VF_OK;
+  }
   return launch_cfg<64, 64, 2, 2>(g, ep, s);
+}
+
+int launch_gemm_bf16_fold(const FoldArgs& fa, int64_t ld, int M, int N, float* C, int64_t ldc, hipStream_t s) {
+  if (fa.count < 1 || fa.count > kFoldMax || M <= 0 || N <= 0 || !C) return VF_EINVAL;
+  if ((N & 3) || (ldc & 3) || (ld & 7) || (reinterpret_cast<uintptr_t>(C) & 15)) return VF_EINVAL;
+  for (int j = 0; j < fa.count; ++j) {
+    if (!fa.A[j] || !fa.B[j] || fa.K[j] < 1 || fa.K[j] > 2 * BK || fa.K[j] > ld) return VF_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(fa.A[j]) & 15) || (reinterpret_cast<uintptr_t>(fa.B[j]) & 15)) return VF_EINVAL;
+  }
+  dim3 grid((N + 127) / 128, (M + 127) / 128);
+  gemm_bf16_fold_kernel<<<grid, NT, 0, s>>>(fa, ld, M, N, C, ldc);
+  VF_LAUNCH_CHECK();
+  return VF_OK;
 }
 
 }  // namespace vf

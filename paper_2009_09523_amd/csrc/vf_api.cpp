@@ -1,6 +1,7 @@
 // C ABI of libvf: argument checks, partition (S0), context set-up, and the step executor
 // that strings the per-node launch sequences, the accumulate kernel and the optimizer
 // update together (Section 3.2, steps 1-5; weights of Section 5.2).
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -37,6 +38,7 @@ int validate_config(const vf_config& c) {
   if (c.max_batch < 1 || c.max_node_size < 1 || c.max_nodes < 1) return VF_EINVAL;
   if (c.max_node_size > c.max_batch) return VF_EINVAL;
   if (!(c.bn_momentum >= 0.f && c.bn_momentum <= 1.f)) return VF_EINVAL;
+  if (c.fold_window < 0 || c.fold_window > kFoldMax) return VF_EINVAL;
   if (c.model_kind == VF_MLP) {
     if (c.n_dims < 2 || c.n_dims > VF_MAX_DIMS) return VF_EINVAL;
     for (int i = 0; i < c.n_dims; ++i)
@@ -83,7 +85,7 @@ void drop_graph(Ctx& c) {
 int enqueue_part(Ctx& c, const StepArgs& a, int part, int node, hipStream_t st) {
   if (part == 0) return c.model->prepare(c, a.params, st);
   if (part == 1) return c.model->run_node_main(c, a, node, st);
-  return c.model->run_node_side(c, a, node, st);
+  return c.model->run_nodes_side(c, a, node, 1, st);
 }
 
 // Record one part into a graph (captured on the main stream; replayed on whichever stream).
@@ -176,6 +178,14 @@ int enqueue_nodes(Ctx& c, const StepArgs& a, bool use_graph) {
   }
   hipStream_t side = ov ? c.side : c.stream;
   VF_TRY(run_part(c, a, use_graph, 0, 0, c.stream));
+  if (!ov) {   // one stream: windows of nodes, each followed by one side part for the whole window
+    for (int i0 = 0; i0 < a.V; i0 += c.window) {
+      const int count = std::min(c.window, a.V - i0);
+      for (int i = i0; i < i0 + count; ++i) VF_TRY(c.model->run_node_main(c, a, i, c.stream));
+      VF_TRY(c.model->run_nodes_side(c, a, i0, count, c.stream));
+    }
+    return VF_OK;
+  }
   for (int i = 0; i < a.V; ++i) {
     const int p = i & 1;
     // copy p of the side part's operands was last read by side(i-2)
@@ -264,6 +274,8 @@ int vf_init(const vf_config* cfg, vf_ctx** out) {
   // Overlap needs a capturable main stream and a model that double-buffers what the side
   // stream reads (the bf16 MLP does).
   c.overlap = c.stream != nullptr && (cfg->flags & VF_FLAG_OVERLAP) && c.model->supports_overlap();
+  // A window needs the fused fold: a staged node's gradient lives in one staging vector.
+  c.window = (c.overlap || !c.fused || cfg->fold_window < 1) ? 1 : std::min(cfg->fold_window, c.model->max_window());
   if (c.overlap) {
     e = hipStreamCreateWithFlags(&c.side, hipStreamNonBlocking);
     for (int k = 0; k < 2 && e == hipSuccess; ++k) e = hipEventCreateWithFlags(&c.side_done[k], hipEventDisableTiming);

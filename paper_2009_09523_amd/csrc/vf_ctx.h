@@ -52,13 +52,18 @@ class Model {
   //   main part: forward pass, loss bookkeeping, and the input-gradient chain of the backward
   //              pass (everything the next node's passes have to wait for);
   //   side part: what only the gradient buffer waits for -- weight gradients and, in staged
-  //              mode, the fold c.fold(i, ...).  It reads operands the main part left behind.
-  // The executor runs main(i) then side(i); with overlap the side part goes to the second
-  // stream and runs beside main(i+1), so a model that supports overlap keeps two copies of
-  // the operands the side part reads (nodes alternate; side(i) is complete before main(i+2)).
+  //              mode, the fold c.fold(i, ...).  It reads operands the main part left behind,
+  //              and covers `count` consecutive nodes i0 .. i0+count-1 (the fold window): a model
+  //              may fold their weight gradients into the buffer in one pass over it.
+  // The executor runs main(i0) .. main(i0+count-1), then side(i0, count); the main part of node i
+  // leaves its operands in copy c.slot(i).  With overlap (window 1) the side part goes to the
+  // second stream and runs beside main(i+1): nodes alternate between two copies and side(i) is
+  // complete before main(i+2).
   virtual int run_node_main(Ctx& c, const StepArgs& a, int i, hipStream_t st) = 0;
-  virtual int run_node_side(Ctx& c, const StepArgs& a, int i, hipStream_t st) = 0;
+  virtual int run_nodes_side(Ctx& c, const StepArgs& a, int i0, int count, hipStream_t st) = 0;
   virtual bool supports_overlap() const { return false; }
+  // Largest fold window the side part can take (it must keep that many nodes' operands).
+  virtual int max_window() const { return 1; }
   // State that the passes themselves carry from step to step on this device (BatchNorm moving
   // mean and variance, Section 4.1): `state_floats` fp32 values at `state_ptr`, laid out as all
   // layers' means then all layers' variances; init_state sets the starting values.
@@ -118,6 +123,10 @@ struct Ctx {
   float* gstage2 = nullptr;               // second staging vector (nodes alternate) when overlapping
   hipEvent_t side_done[2] = {nullptr, nullptr};
   hipEvent_t main_done = nullptr;
+
+  int window = 1;                         // nodes whose weight gradients are folded in one pass
+  int copies() const { return overlap ? 2 : window; }        // copies of the side part's operands
+  int slot(int node) const { return overlap ? (node & 1) : node % window; }
 
   bool overlapping() const { return overlap && !prof.enabled; }
   float* stage_for(int node) const { return (overlap && (node & 1)) ? gstage2 : gstage; }

@@ -121,8 +121,9 @@ class Encoder final : public Model {
   }
 
   // The encoder keeps its whole node on one stream: the side part is only the fold.
-  int run_node_side(Ctx& c, const StepArgs& s, int i, hipStream_t st) override {
-    return c.fold(i, s.w[i], st);
+  int run_nodes_side(Ctx& c, const StepArgs& s, int i0, int count, hipStream_t st) override {
+    for (int i = i0; i < i0 + count; ++i) VF_TRY(c.fold(i, s.w[i], st));
+    return VF_OK;
   }
 
   int run_node_main(Ctx& c, const StepArgs& s, int i, hipStream_t st) override {

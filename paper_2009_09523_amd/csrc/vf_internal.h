@@ -92,6 +92,20 @@ int launch_gemm_bf16(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb,
 // Number of slices that fills the chip for this shape (1 when the tile grid already does).
 int gemm_bf16_pick_split(int M, int N, int K);
 
+// Weight gradients of `count` consecutive nodes folded into C in one pass over it:
+//   C <- fma(w[count-1], A[count-1] B[count-1]^T, ... fma(w[0], A[0] B[0]^T, overwrite ? 0 : C))
+// A[j]: bf16 [M, ld] (rows = input features, K[j] <= 128 node rows contiguous), B[j]: bf16 [N, ld].
+constexpr int kFoldMax = 8;
+struct FoldArgs {
+  const bf16_t* A[kFoldMax];
+  const bf16_t* B[kFoldMax];
+  int K[kFoldMax];
+  float w[kFoldMax];
+  int count;
+  int overwrite;
+};
+int launch_gemm_bf16_fold(const FoldArgs& fa, int64_t ld, int M, int N, float* C, int64_t ldc, hipStream_t s);
+
 // k_elem.hip
 // out[c*ldo + r] = in[r*ldi + c]  for r < R, c < C
 int launch_transpose_bf16(const bf16_t* in, int64_t ldi, bf16_t* out, int64_t ldo, int R, int C,

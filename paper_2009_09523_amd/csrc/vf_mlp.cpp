@@ -23,17 +23,20 @@ struct Layer {
   int64_t s_off = 0;               // offset of this layer's moving statistics within a state half
   void* a = nullptr;               // T [max_b, ld]: activation after BatchNorm/ReLU
   void* dz = nullptr;              // T [max_b, ld]: gradient w.r.t. z
-  // Weight-gradient operands, transposed ([N, ldb], rows of the node contiguous).  Two copies:
-  // nodes alternate between them so that the side stream can still read node i's operands
-  // while the main stream produces those of node i+1.
-  bf16_t* aT[2] = {nullptr, nullptr};    // a transposed
-  bf16_t* dzT[2] = {nullptr, nullptr};   // dz transposed
+  // Weight-gradient operands, transposed ([N, ldb], rows of the node contiguous).  Several
+  // copies (Ctx::copies): node i writes copy Ctx::slot(i), so that the operands of a whole fold
+  // window are still there when its weight gradients are taken in one pass, or (two streams) the
+  // side stream can read node i's operands while the main stream produces those of node i+1.
+  bf16_t* aT[kFoldMax] = {};     // a transposed
+  bf16_t* dzT[kFoldMax] = {};    // dz transposed
 };
 
 class Mlp final : public Model {
  public:
   explicit Mlp(const vf_config& cfg) : cfg_(cfg) {
     bf16_ = cfg.dtype == VF_BF16;
+    // as many copies of the weight-gradient operands as Ctx::copies() will ask for
+    copies_ = std::max(2, cfg.fold_window);
     const int nl = cfg.n_dims - 1;
     int64_t off = 0;
     layers_.resize(nl);
@@ -86,6 +89,7 @@ class Mlp final : public Model {
 
   int64_t num_params() const override { return P_; }
   bool supports_overlap() const override { return bf16_; }
+  int max_window() const override { return bf16_ ? copies_ : 1; }
 
   void request_buffers(Arena& a) override {
     const size_t mb = (size_t)cfg_.max_node_size;
@@ -101,14 +105,14 @@ class Mlp final : public Model {
       if (bf16_) {
         a.request(&L.wnat, (size_t)L.K * L.ldn);
         a.request(&L.wtr, (size_t)L.N * L.ldt);
-        for (int k = 0; k < 2; ++k) {
+        for (int k = 0; k < copies_; ++k) {
           a.request(&L.dzT[k], (size_t)L.N * ldb_);
           if (L.hidden) a.request(&L.aT[k], (size_t)L.N * ldb_);
         }
       }
     }
     if (bf16_)
-      for (int k = 0; k < 2; ++k) a.request(&xT_[k], (size_t)cfg_.dims[0] * ldb_);
+      for (int k = 0; k < copies_; ++k) a.request(&xT_[k], (size_t)cfg_.dims[0] * ldb_);
     a.request(&slab_, (size_t)slab_elems_);
     if (bn_width_) a.request(&state_, (size_t)(2 * bn_width_));
   }
@@ -131,7 +135,7 @@ class Mlp final : public Model {
   // Forward pass, loss, and the input-gradient chain (with the small-vector gradients the
   // BatchNorm/ReLU backward kernels produce on the way).
   int run_node_main(Ctx& c, const StepArgs& s, int i, hipStream_t st) override {
-    const int p = c.overlap ? (i & 1) : 0;   // which copy of the side part's operands
+    const int p = c.slot(i);                 // which copy of the side part's operands
     const int b = s.sizes[i];
     const int64_t row0 = s.off[i];
     const float w = s.w[i];
@@ -191,40 +195,66 @@ class Mlp final : public Model {
     return VF_OK;
   }
 
-  // Weight gradients, the last layer's bias gradient, and (staged mode) the fold.  Reads the
-  // transposed operands of copy p (bf16) that the main part wrote.
-  int run_node_side(Ctx& c, const StepArgs& s, int i, hipStream_t st) override {
-    const int p = c.overlap ? (i & 1) : 0;
-    const int b = s.sizes[i];
-    const int64_t row0 = s.off[i];
-    const float w = s.w[i];
+  // Weight gradients, the last layer's bias gradient, and (staged mode) the fold, of nodes
+  // i0 .. i0+count-1.  Reads the transposed operands (bf16) that their main parts wrote.
+  int run_nodes_side(Ctx& c, const StepArgs& s, int i0, int count, hipStream_t st) override {
     const int nl = (int)layers_.size();
     const int D = cfg_.dims[0];
-    const void* x = bf16_ ? (const void*)(static_cast<const bf16_t*>(s.x) + row0 * D)
-                          : (const void*)(static_cast<const float*>(s.x) + row0 * D);
-    if (bf16_)
-      VF_KS(c, st, "transpose", launch_transpose_bf16(static_cast<const bf16_t*>(x), D, xT_[p], ldb_, b, D, st));
-    for (int l = nl - 1; l >= 0; --l) {
-      Layer& L = layers_[l];
-      const void* in = l == 0 ? x : layers_[l - 1].a;
-      const int64_t ldin = l == 0 ? D : layers_[l - 1].ld;
-      if (!L.hidden) {   // last layer: bias gradient = sums over the node of dlogits
-        if (bf16_) VF_KS(c, st, "bias_grad", launch_rowsum_bf16(L.dzT[p], ldb_, L.N, b, c.gout(L.b_off, w, i), st));
-        else       VF_KS(c, st, "bias_grad", launch_colsum(L.dz, L.ld, 0, b, L.N, c.gout(L.b_off, w, i), st));
+    // One pass over the gradient buffer for the whole window: fused fold, bf16, every node short
+    // enough for the single-trip kernel, shapes the 16-byte epilogue accepts.
+    bool fold = bf16_ && c.fused && count > 1;
+    for (int i = i0; i < i0 + count && fold; ++i) fold = s.sizes[i] <= 128;
+    for (const Layer& L : layers_) fold = fold && (L.N & 3) == 0 && ((L.w_off & 3) == 0);
+
+    for (int i = i0; i < i0 + count; ++i) {
+      const int p = c.slot(i);
+      const int b = s.sizes[i];
+      const int64_t row0 = s.off[i];
+      const float w = s.w[i];
+      const void* x = bf16_ ? (const void*)(static_cast<const bf16_t*>(s.x) + row0 * D)
+                            : (const void*)(static_cast<const float*>(s.x) + row0 * D);
+      if (bf16_)
+        VF_KS(c, st, "transpose", launch_transpose_bf16(static_cast<const bf16_t*>(x), D, xT_[p], ldb_, b, D, st));
+      for (int l = nl - 1; l >= 0; --l) {
+        Layer& L = layers_[l];
+        const void* in = l == 0 ? x : layers_[l - 1].a;
+        const int64_t ldin = l == 0 ? D : layers_[l - 1].ld;
+        if (!L.hidden) {   // last layer: bias gradient = sums over the node of dlogits
+          if (bf16_) VF_KS(c, st, "bias_grad", launch_rowsum_bf16(L.dzT[p], ldb_, L.N, b, c.gout(L.b_off, w, i), st));
+          else       VF_KS(c, st, "bias_grad", launch_colsum(L.dz, L.ld, 0, b, L.N, c.gout(L.b_off, w, i), st));
+        }
+        if (fold) continue;
+        GradOut go = c.gout(L.w_off, w, i);
+        Epilogue ep;
+        ep.C = go.dst; ep.ldc = L.N; ep.alpha = go.alpha;
+        if (go.accumulate) { ep.R = go.dst; ep.ldr = L.N; ep.beta = 1.f; }
+        if (bf16_) {
+          const bf16_t* inT = l == 0 ? xT_[p] : layers_[l - 1].aT[p];
+          VF_KS(c, st, "gemm_wgrad", launch_gemm_bf16(inT, ldb_, L.dzT[p], ldb_, L.K, L.N, b, 1, 0, ep, st));
+        } else {
+          VF_KS(c, st, "gemm_wgrad", launch_gemm_f32(static_cast<const float*>(in), 1, ldin,
+                                                     static_cast<const float*>(L.dz), 1, L.ld, L.K, L.N, b, 1, 0, ep, st));
+        }
       }
-      GradOut go = c.gout(L.w_off, w, i);
-      Epilogue ep;
-      ep.C = go.dst; ep.ldc = L.N; ep.alpha = go.alpha;
-      if (go.accumulate) { ep.R = go.dst; ep.ldr = L.N; ep.beta = 1.f; }
-      if (bf16_) {
-        const bf16_t* inT = l == 0 ? xT_[p] : layers_[l - 1].aT[p];
-        VF_KS(c, st, "gemm_wgrad", launch_gemm_bf16(inT, ldb_, L.dzT[p], ldb_, L.K, L.N, b, 1, 0, ep, st));
-      } else {
-        VF_KS(c, st, "gemm_wgrad", launch_gemm_f32(static_cast<const float*>(in), 1, ldin,
-                                                   static_cast<const float*>(L.dz), 1, L.ld, L.K, L.N, b, 1, 0, ep, st));
+      if (!fold) VF_TRY(c.fold(i, w, st));
+    }
+    if (fold) {
+      for (int l = nl - 1; l >= 0; --l) {
+        Layer& L = layers_[l];
+        FoldArgs fa{};
+        fa.count = count;
+        fa.overwrite = i0 == 0;
+        for (int j = 0; j < count; ++j) {
+          const int p = c.slot(i0 + j);
+          fa.A[j] = l == 0 ? xT_[p] : layers_[l - 1].aT[p];
+          fa.B[j] = L.dzT[p];
+          fa.K[j] = s.sizes[i0 + j];
+          fa.w[j] = s.w[i0 + j];
+        }
+        VF_KS(c, st, "gemm_wgrad", launch_gemm_bf16_fold(fa, ldb_, L.K, L.N, c.gbuf + L.w_off, L.N, st));
       }
     }
-    return c.fold(i, w, st);
+    return VF_OK;
   }
 
  private:
@@ -233,7 +263,8 @@ class Mlp final : public Model {
   int64_t P_ = 0;
   int64_t ldb_ = 0;
   std::vector<Layer> layers_;
-  bf16_t* xT_[2] = {nullptr, nullptr};
+  int copies_ = 2;
+  bf16_t* xT_[kFoldMax] = {};
   float* slab_ = nullptr;
   int64_t slab_elems_ = 0;
   int64_t bn_width_ = 0;           // summed width of the BatchNorm layers

@@ -114,7 +114,10 @@ def test_gemm_against_float64_matmul(M, N, K, dtype):
 
 
 @pytest.mark.parametrize("M,N,K,nsplit", [(128, 512, 4096, 16), (48, 1000, 520, 3), (16, 392, 1000, 4),
-                                         (128, 264, 72, 2), (300, 100, 1000, 8)])
+                                         (128, 264, 72, 2), (300, 100, 1000, 8),
+                                         # whole 64-element stages per slice: the LDS-direct kernel
+                                         (128, 4096, 4096, 4), (100, 1000, 1024, 8), (70, 130, 192, 3),
+                                         (65, 64, 64, 1), (48, 392, 64, 2), (128, 1000, 4096, 16)])
 def test_gemm_split_contraction_slabs_sum_to_product(M, N, K, nsplit):
     import torch
     import paper_2009_09523_amd as vf

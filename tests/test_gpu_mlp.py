@@ -206,3 +206,50 @@ def test_overlap_and_single_stream_agree_bitwise():
         assert base["G"].tobytes() == other["G"].tobytes(), flags
         assert base["theta"].tobytes() == other["theta"].tobytes(), flags
         assert base["loss"] == other["loss"], flags
+
+
+# ---- fold window: the weight gradients of several nodes folded in one pass over the buffer -------
+
+@pytest.mark.parametrize("window", [2, 3, 4, 8])
+@pytest.mark.parametrize("name,flags", [("mlp_mid_bn_bf16", FUSED), ("mlp_mid_bf16", FUSED),
+                                        ("mlp_mid_bn_bf16", FUSED | NO_GRAPH)])
+def test_fold_window_gives_the_node_by_node_result_bitwise(name, flags, window):
+    """Same chain of fused multiply-adds, so the same bits: five unequal nodes (the last window is
+    ragged), two steps so that the buffer is overwritten, not accumulated, by the second."""
+    wl, theta, x, y = _case(name)
+    one = run_gpu(wl, theta, x, y, flags=flags, steps=2)
+    win = run_gpu(wl, theta, x, y, flags=flags, steps=2, fold_window=window)
+    assert one["G"].tobytes() == win["G"].tobytes()
+    assert one["theta"].tobytes() == win["theta"].tobytes()
+    assert one["loss"] == win["loss"]
+
+
+def test_fold_window_with_long_nodes_and_other_modes_falls_back_to_node_by_node():
+    """Nodes longer than the single-trip kernel takes (300, 212 rows), the staged fold and the fp32
+    path ignore the window: results equal those without it."""
+    wl, theta, x, y = _case("mlp_big_node_bf16")
+    assert run_gpu(wl, theta, x, y, flags=FUSED)["G"].tobytes() == \
+        run_gpu(wl, theta, x, y, flags=FUSED, fold_window=4)["G"].tobytes()
+    wl, theta, x, y = _case("mlp_mid_bn_bf16")
+    assert run_gpu(wl, theta, x, y, flags=0)["G"].tobytes() == \
+        run_gpu(wl, theta, x, y, flags=0, fold_window=4)["G"].tobytes()
+    wl, theta, x, y = _case("mlp_small_bn_f32")
+    assert run_gpu(wl, theta, x, y, flags=FUSED)["G"].tobytes() == \
+        run_gpu(wl, theta, x, y, flags=FUSED, fold_window=4)["G"].tobytes()
+
+
+def test_fold_window_against_the_oracle_at_benchmark_size():
+    wl, theta, x, y = _case("C2", jitter=0.0)
+    gpu = run_gpu(wl, theta, x, y, flags=FUSED, fold_window=8)
+    ref = oracle_steps(wl, theta, x, y)
+    check_against_oracle(wl, gpu, ref)
+
+
+def test_fold_window_workspace_does_not_depend_on_the_number_of_nodes():
+    wl, theta, x, y = _case("mlp_mid_bf16")
+    few = run_gpu(wl, theta, x, y, node_sizes=[120, 120], flags=FUSED, fold_window=4, max_node_size=128,
+                  max_batch=240, max_nodes=16)
+    many = run_gpu(wl, theta, x, y, node_sizes=[16] * 15, flags=FUSED, fold_window=4, max_node_size=128,
+                   max_batch=240, max_nodes=16)
+    assert few["workspace_bytes"] == many["workspace_bytes"]
+    assert np.linalg.norm(few["G"] - many["G"]) > 0          # different splits really ran
