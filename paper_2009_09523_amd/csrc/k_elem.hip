@@ -71,6 +71,29 @@ __global__ __launch_bounds__(256) void cast_weight_kernel(const float* __restric
   }
 }
 
+// The same transpose for every node of a fold window (blockIdx.z = node).
+__global__ __launch_bounds__(256) void transpose_nodes_kernel(NodeList nl, int64_t ldi, int64_t ldo, int C) {
+  __shared__ bf16_t tile[TS][TS + 2];
+  const int j = blockIdx.z;
+  const int R = nl.rows[j];
+  const int r0 = blockIdx.y * TS, c0 = blockIdx.x * TS;
+  if (r0 >= R) return;
+  const bf16_t* __restrict__ in = nl.src[j];
+  bf16_t* __restrict__ out = nl.dst[j];
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+#pragma unroll
+  for (int i = 0; i < TS; i += 8) {
+    const int r = r0 + ty + i, c = c0 + tx;
+    if (r < R && c < C) tile[ty + i][tx] = in[(int64_t)r * ldi + c];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < TS; i += 8) {
+    const int c = c0 + ty + i, r = r0 + tx;
+    if (r < R && c < C) out[(int64_t)c * ldo + r] = tile[tx][ty + i];
+  }
+}
+
 __global__ __launch_bounds__(256) void cast_kernel(const float* __restrict__ in, int64_t ldi,
                                                    bf16_t* __restrict__ out, int64_t ldo, int R, int C) {
   int c = blockIdx.x * 256 + threadIdx.x;
@@ -85,6 +108,19 @@ int launch_transpose_bf16(const bf16_t* in, int64_t ldi, bf16_t* out, int64_t ld
   if (R <= 0 || C <= 0) return VF_OK;
   dim3 grid((C + TS - 1) / TS, (R + TS - 1) / TS);
   transpose_kernel<bf16_t><<<grid, 256, 0, s>>>(in, ldi, out, ldo, nullptr, 0, R, C);
+  VF_LAUNCH_CHECK();
+  return VF_OK;
+}
+
+int launch_transpose_nodes(const NodeList& nl, int64_t ldi, int64_t ldo, int C, hipStream_t s) {
+  if (nl.count < 1 || nl.count > kFoldMax || C <= 0) return VF_EINVAL;
+  int max_rows = 0;
+  for (int j = 0; j < nl.count; ++j) {
+    if (!nl.src[j] || !nl.dst[j] || nl.rows[j] < 1 || nl.rows[j] > ldo || C > ldi) return VF_EINVAL;
+    max_rows = nl.rows[j] > max_rows ? nl.rows[j] : max_rows;
+  }
+  dim3 grid((C + TS - 1) / TS, (max_rows + TS - 1) / TS, nl.count);
+  transpose_nodes_kernel<<<grid, 256, 0, s>>>(nl, ldi, ldo, C);
   VF_LAUNCH_CHECK();
   return VF_OK;
 }

@@ -277,6 +277,22 @@ __global__ __launch_bounds__(256) void rowsum_kernel(const bf16_t* __restrict__ 
   if (lane == 0) grad_store(out, r, s);
 }
 
+// Bias gradients of a fold window: one wavefront per row, the nodes one after another.
+__global__ __launch_bounds__(256) void rowsum_nodes_kernel(NodeList nl, int64_t ld, int R, float* __restrict__ out) {
+  const int lane = threadIdx.x & 63;
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= R) return;
+  float c = nl.overwrite ? 0.f : out[r];
+  for (int j = 0; j < nl.count; ++j) {
+    const bf16_t* __restrict__ x = nl.src[j];
+    float s = 0.f;
+    for (int k = lane; k < nl.rows[j]; k += 64) s += bf16_to_f32(x[(int64_t)r * ld + k]);
+    s = wave_sum(s);
+    c = fmaf(nl.w[j], s, c);
+  }
+  if (lane == 0) out[r] = c;
+}
+
 }  // namespace
 
 int launch_bn_relu_fwd(const float* zp, int nsplit, int64_t slab, int64_t ldzp, int R, int C,
@@ -340,6 +356,15 @@ int launch_colsum(const void* x, int64_t ld, int x_is_bf16, int R, int C, GradOu
   int grid = (C + SCB - 1) / SCB;
   if (x_is_bf16) colsum_kernel<bf16_t><<<grid, 256, 0, s>>>(static_cast<const bf16_t*>(x), ld, R, C, out);
   else           colsum_kernel<float><<<grid, 256, 0, s>>>(static_cast<const float*>(x), ld, R, C, out);
+  VF_LAUNCH_CHECK();
+  return VF_OK;
+}
+
+int launch_rowsum_nodes(const NodeList& nl, int64_t ld, int R, float* out, hipStream_t s) {
+  if (nl.count < 1 || nl.count > kFoldMax || R <= 0 || !out) return VF_EINVAL;
+  for (int j = 0; j < nl.count; ++j)
+    if (!nl.src[j] || nl.rows[j] < 1 || nl.rows[j] > ld) return VF_EINVAL;
+  rowsum_nodes_kernel<<<(R + 3) / 4, 256, 0, s>>>(nl, ld, R, out);
   VF_LAUNCH_CHECK();
   return VF_OK;
 }

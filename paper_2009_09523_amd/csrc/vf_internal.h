@@ -106,6 +106,22 @@ struct FoldArgs {
 };
 int launch_gemm_bf16_fold(const FoldArgs& fa, int64_t ld, int M, int N, float* C, int64_t ldc, hipStream_t s);
 
+// The small per-node launches of a fold window, batched: `count` nodes, node j with rows[j] rows.
+struct NodeList {
+  const bf16_t* src[kFoldMax];
+  bf16_t* dst[kFoldMax];
+  int rows[kFoldMax];
+  float w[kFoldMax];
+  int count;
+  int overwrite;
+};
+// dst[j][c*ldo + r] = src[j][r*ldi + c] for every node j (r < rows[j], c < C): k_elem.hip
+int launch_transpose_nodes(const NodeList& nl, int64_t ldi, int64_t ldo, int C, hipStream_t s);
+// out[r] <- fma(w[count-1], S_{count-1}[r], ... fma(w[0], S_0[r], overwrite ? 0 : out[r])) with
+// S_j[r] = sum over c < rows[j] of src[j][r*ld + c], r < R (bias gradients of a window from the
+// transposed output gradients; the same chain as one launch per node): k_norm.hip
+int launch_rowsum_nodes(const NodeList& nl, int64_t ld, int R, float* out, hipStream_t s);
+
 // k_elem.hip
 // out[c*ldo + r] = in[r*ldi + c]  for r < R, c < C
 int launch_transpose_bf16(const bf16_t* in, int64_t ldi, bf16_t* out, int64_t ldo, int R, int C,

@@ -206,7 +206,23 @@ class Mlp final : public Model {
     for (int i = i0; i < i0 + count && fold; ++i) fold = s.sizes[i] <= 128;
     for (const Layer& L : layers_) fold = fold && (L.N & 3) == 0 && ((L.w_off & 3) == 0);
 
-    for (int i = i0; i < i0 + count; ++i) {
+    if (fold) {   // the window's small launches batched, then one fold per layer
+      NodeList xs{}, ds{};
+      xs.count = ds.count = count;
+      ds.overwrite = i0 == 0;
+      const Layer& last = layers_[nl - 1];
+      for (int j = 0; j < count; ++j) {
+        const int p = c.slot(i0 + j);
+        xs.src[j] = static_cast<const bf16_t*>(s.x) + (int64_t)s.off[i0 + j] * D;
+        xs.dst[j] = xT_[p];
+        ds.src[j] = last.dzT[p];
+        xs.rows[j] = ds.rows[j] = s.sizes[i0 + j];
+        ds.w[j] = s.w[i0 + j];
+      }
+      VF_KS(c, st, "transpose", launch_transpose_nodes(xs, D, ldb_, D, st));
+      VF_KS(c, st, "bias_grad", launch_rowsum_nodes(ds, ldb_, last.N, c.gbuf + last.b_off, st));
+    }
+    for (int i = i0; i < i0 + count && !fold; ++i) {
       const int p = c.slot(i);
       const int b = s.sizes[i];
       const int64_t row0 = s.off[i];
@@ -223,7 +239,6 @@ class Mlp final : public Model {
           if (bf16_) VF_KS(c, st, "bias_grad", launch_rowsum_bf16(L.dzT[p], ldb_, L.N, b, c.gout(L.b_off, w, i), st));
           else       VF_KS(c, st, "bias_grad", launch_colsum(L.dz, L.ld, 0, b, L.N, c.gout(L.b_off, w, i), st));
         }
-        if (fold) continue;
         GradOut go = c.gout(L.w_off, w, i);
         Epilogue ep;
         ep.C = go.dst; ep.ldc = L.N; ep.alpha = go.alpha;
@@ -236,7 +251,7 @@ class Mlp final : public Model {
                                                      static_cast<const float*>(L.dz), 1, L.ld, L.K, L.N, b, 1, 0, ep, st));
         }
       }
-      if (!fold) VF_TRY(c.fold(i, w, st));
+      VF_TRY(c.fold(i, w, st));
     }
     if (fold) {
       for (int l = nl - 1; l >= 0; --l) {
