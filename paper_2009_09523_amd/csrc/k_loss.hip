@@ -21,15 +21,6 @@ __device__ __forceinline__ float block_reduce(float v, bool is_max, float* red) 
 // memory is read once; otherwise the reduced logits are re-read from z.
 constexpr int CPT = 4;
 
-// Node-loss bookkeeping done by the last workgroup of a softmax launch to finish.
-struct LossTail {
-  float* node_loss;        // [max_nodes] or null (then a separate loss_reduce launch follows)
-  float* total;
-  unsigned int* ticket;    // zero between launches; the last workgroup resets it
-  float w;
-  int node;
-};
-
 template <int NS>
 __device__ __forceinline__ float slab_sum(const float* zp, int nsplit, int64_t slab, int64_t idx) {
   if (NS > 0) {
@@ -53,8 +44,7 @@ __global__ __launch_bounds__(256) void softmax_xent_kernel(const float* zp, int 
                                                            const int32_t* __restrict__ labels, int R,
                                                            int C, float* __restrict__ rowloss,
                                                            T* __restrict__ dz, int64_t lddz,
-                                                           bf16_t* __restrict__ dzT, int64_t ldt,
-                                                           LossTail tail) {
+                                                           bf16_t* __restrict__ dzT, int64_t ldt) {
   __shared__ float red[4];
   __shared__ float zlabel;
   const int r = blockIdx.x;
@@ -117,27 +107,6 @@ __global__ __launch_bounds__(256) void softmax_xent_kernel(const float* zp, int 
     }
   }
   if (threadIdx.x == 0) rowloss[r] = logf(sum) + mx - zlabel;   // zlabel: visible after the reductions' barriers
-  if (tail.node_loss == nullptr) return;
-  // The last workgroup to get here adds up the row losses in row order (so the result does
-  // not depend on which workgroup that is) and resets the ticket for the next launch.
-  __shared__ unsigned int last;
-  if (threadIdx.x == 0) {
-    __threadfence();                                     // rowloss[r] before the ticket
-    last = atomicAdd(tail.ticket, 1u) == (unsigned int)(R - 1);
-  }
-  __syncthreads();
-  if (!last) return;
-  __threadfence();
-  float s = 0.f;
-  for (int q = threadIdx.x; q < R; q += 256) s += __builtin_nontemporal_load(&rowloss[q]);
-  s = block_reduce(s, false, red);
-  if (threadIdx.x == 0) {
-    const float L = s / (float)R;
-    tail.node_loss[tail.node] = L;
-    const float old = tail.node == 0 ? 0.f : *tail.total;
-    *tail.total = fmaf(tail.w, L, old);
-    *tail.ticket = 0u;
-  }
 }
 
 __global__ __launch_bounds__(256) void loss_reduce_kernel(const float* __restrict__ rowloss, int R,
@@ -161,15 +130,14 @@ __global__ __launch_bounds__(256) void loss_reduce_kernel(const float* __restric
 int launch_softmax_xent(const float* zp, int nsplit, int64_t slab, int64_t ldzp, float* z, int64_t ldz,
                         const int32_t* labels, int R, int C, float* rowloss, void* dz, int64_t lddz,
                         int dz_is_bf16, bf16_t* dzT, int64_t ldt, float w, int node, float* node_loss,
-                        float* total, unsigned int* ticket, hipStream_t s) {
+                        float* total, hipStream_t s) {
   if (R <= 0 || C <= 0 || nsplit < 1) return VF_EINVAL;
   if (dzT && !dz_is_bf16) return VF_EINVAL;
-  if (node_loss && (!total || !ticket)) return VF_EINVAL;
+  if (node_loss && !total) return VF_EINVAL;
   const bool small = C <= 256 * CPT;
-  LossTail tail{node_loss, total, ticket, w, node};
 #define VF_SX3(TT, SM, NS)                                                                         \
   softmax_xent_kernel<TT, SM, NS><<<R, 256, 0, s>>>(zp, nsplit, slab, ldzp, z, ldz, labels, R, C,  \
-                                                    rowloss, static_cast<TT*>(dz), lddz, dzT, ldt, tail)
+                                                    rowloss, static_cast<TT*>(dz), lddz, dzT, ldt)
 #define VF_SX2(TT, SM)                                                                             \
   switch (nsplit) {                                                                                \
     case 1: VF_SX3(TT, SM, 1); break;                                                              \
@@ -184,6 +152,9 @@ int launch_softmax_xent(const float* zp, int nsplit, int64_t slab, int64_t ldzp,
 #undef VF_SX2
 #undef VF_SX3
   VF_LAUNCH_CHECK();
+  // the node's loss bookkeeping: a second, tiny launch (folding it into the last workgroup to
+  // finish costs a device-scope fence per workgroup, which is slower than the launch)
+  if (node_loss) return launch_loss_reduce(rowloss, R, w, node, node_loss, total, s);
   return VF_OK;
 }
 

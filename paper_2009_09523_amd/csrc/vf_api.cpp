@@ -299,7 +299,6 @@ int vf_init(const vf_config* cfg, vf_ctx** out) {
   arena.request(&c.rowloss, loss_rows);
   arena.request(&c.node_loss, (size_t)cfg->max_nodes);
   arena.request(&c.loss_total, 1);
-  arena.request(&c.loss_ticket, 1);
   c.model->request_buffers(arena);
   c.arena_bytes = arena.total();
   e = hipMalloc(reinterpret_cast<void**>(&c.arena), c.arena_bytes);

@@ -110,7 +110,6 @@ struct Ctx {
   float* rowloss = nullptr;   // per-row losses of the node in flight
   float* node_loss = nullptr; // [max_nodes]
   float* loss_total = nullptr;
-  unsigned int* loss_ticket = nullptr;   // arrival counter of the fused loss bookkeeping
 
   int64_t steps = 0;
   int32_t last_V = 0;

@@ -170,8 +170,7 @@ class Encoder final : public Model {
                                                   cfg_.ln_eps, rows_, d_, bf16_, meanf_, rstdf_, st));
     VF_TRY(lin_fwd(c, "gemm_head", out_, P, rows_, d_, Rm, logits_, ldV_, false, nullptr));
     VF_K(c, "softmax_xent", launch_softmax_xent(logits_, 1, 0, ldV_, logits_, ldV_, labels_, Rm, V_, c.rowloss,
-                                                dlogits_, ldV_, bf16_, nullptr, 0, w, i, c.node_loss, c.loss_total,
-                                                c.loss_ticket, st));
+                                                dlogits_, ldV_, bf16_, nullptr, 0, w, i, c.node_loss, c.loss_total, st));
 
     // ---- backward: output head -----------------------------------------------------------
     VF_K(c, "colsum", launch_colsum_rows(dlogits_, ldV_, bf16_, Rm, V_, red_, c.gout(out_.b_off, w, i), st));

@@ -165,13 +165,11 @@ int launch_colsum(const void* x, int64_t ld, int x_is_bf16, int R, int C, GradOu
 // of the logits (summed into z, which may be slab 0 itself):
 //   rowloss[r] = logsumexp(z_r) - z_r[label_r];  dz[r,c] = (softmax(z_r)[c] - [c==label_r]) / R
 // dzT (optional, bf16 only): the same gradient transposed, [C, ldt].
-// With node_loss != null the launch also does the node's loss bookkeeping (what
-// launch_loss_reduce does) in its last workgroup to finish; `ticket` is a zero-initialised
-// counter the kernel leaves at zero.
+// With node_loss != null the node's loss bookkeeping (launch_loss_reduce) follows.
 int launch_softmax_xent(const float* zp, int nsplit, int64_t slab, int64_t ldzp, float* z, int64_t ldz,
                         const int32_t* labels, int R, int C, float* rowloss, void* dz, int64_t lddz,
                         int dz_is_bf16, bf16_t* dzT, int64_t ldt, float w, int node, float* node_loss,
-                        float* total, unsigned int* ticket, hipStream_t s);
+                        float* total, hipStream_t s);
 // node_loss[i] = (1/R) sum_r rowloss[r];  total = (i == 0 ? 0 : total) + w * node_loss[i]
 int launch_loss_reduce(const float* rowloss, int R, float w, int node, float* node_loss,
                        float* total, hipStream_t s);

@@ -169,7 +169,7 @@ class Mlp final : public Model {
       else
         VF_KS(c, st, "softmax_xent", launch_softmax_xent(slab_, split, slab, L.ld, L.z, L.ld, y, b, L.N,
                                                          c.rowloss, L.dz, L.ld, bf16_, L.dzT[p], ldb_, w, i,
-                                                         c.node_loss, c.loss_total, c.loss_ticket, st));
+                                                         c.node_loss, c.loss_total, st));
     }
 
     for (int l = nl - 1; l >= 1; --l) {
