@@ -24,15 +24,16 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 matrix cores
 FP32_VECTOR_PEAK_TFLOPS = 157.3
 
 
-def algorithmic_work(wl, P, fused=False):
+def algorithmic_work(wl, P, fused=False, window=1):
     """Per step, per kernel tag: (bytes, flops, launches) the method itself needs.
     Bytes count each operand once per launch (fp32 = 4, bf16 = 2).  With the fused fold the
-    weight-gradient kernels read and write the gradient buffer (node 0 only writes it) and
-    there is no accumulate kernel."""
+    weight-gradient kernels read and write the gradient buffer once per fold window of `window`
+    nodes (the first window only writes it) and there is no accumulate kernel."""
     V, B = wl.n_nodes, wl.batch
     esz = 2 if wl.dtype == "bf16" else 4
     work = {} if fused else {"accumulate": ((12 * V - 4) * P, 2 * V * P, V)}
-    wg = (8 * V - 4) if fused else 4 * V          # fp32 bytes per matrix entry per step
+    nwin = -(-V // window) if fused else V        # passes over the gradient buffer per step
+    wg = (8 * nwin - 4) if fused else 4 * V       # fp32 bytes per matrix entry per step
     opt_bytes = (20 if wl.optimizer == "sgdm" else 28) * P
     work["optimizer"] = (opt_bytes, 4 * P, 1)
     if wl.kind == "mlp":
@@ -43,7 +44,7 @@ def algorithmic_work(wl, P, fused=False):
         act = sum(b * (k * esz + n * 4) for b in wl.node_sizes for k, n in mats)
         work["gemm_fwd"] = (V * W * esz + act, fwd_fl, V * len(mats))
         work["gemm_dgrad"] = (V * sum(k * n for k, n in mats[1:]) * esz + act, dgr_fl, V * (len(mats) - 1))
-        work["gemm_wgrad"] = (wg * W + act, fwd_fl, V * len(mats))
+        work["gemm_wgrad"] = (wg * W + act, fwd_fl, nwin * len(mats))
         work["cast_weight"] = (W * (4 + 2 * esz), 0, len(mats))
     else:
         d, f, T, Vc, m, nl = wl.d_model, wl.d_ffn, wl.seq_len, wl.vocab, wl.n_masked, wl.n_layers
@@ -132,11 +133,12 @@ def cpu_baseline(wl, theta, x, y, budget_s=12.0):
             "seconds": dt}
 
 
-def time_steps(vf, torch, wl, theta, x, y, flags, steps, warmup, max_node_size=None):
+def time_steps(vf, torch, wl, theta, x, y, flags, steps, warmup, max_node_size=None, fold_window=1):
     """(ms per step, workspace bytes) of `wl` on the device."""
     from paper_2009_09523_amd.binding import config_from_workload
     stream = torch.cuda.Stream()
-    eng = vf.VirtualNodeStep(config_from_workload(wl, flags=flags, stream=stream, max_node_size=max_node_size))
+    eng = vf.VirtualNodeStep(config_from_workload(wl, flags=flags, stream=stream, max_node_size=max_node_size,
+                                                  fold_window=fold_window))
     params = torch.from_numpy(theta).cuda()
     xt = torch.from_numpy(x).cuda()
     if wl.kind == "mlp" and wl.dtype == "bf16":
@@ -176,7 +178,7 @@ def vsweep(args):
         wl = replace(base, node_sizes=(b,) * V)
         theta = I.make_params(wl)
         x, y = I.make_batch(wl)
-        ms, ws = time_steps(vf, torch, wl, theta, x, y, flags, args.steps, args.warmup)
+        ms, ws = time_steps(vf, torch, wl, theta, x, y, flags, args.steps, args.warmup, fold_window=args.fold_window)
         grow.append({"V": V, "batch": b * V, "ms_per_step": ms, "samples_per_s": b * V / (ms * 1e-3),
                      "workspace_bytes": ws})
     B = base.batch
@@ -185,7 +187,7 @@ def vsweep(args):
     V = 1
     while B // V >= 16 and B % V == 0:
         wl = replace(base, node_sizes=(B // V,) * V)
-        ms, ws = time_steps(vf, torch, wl, theta, x, y, flags, args.steps, args.warmup)
+        ms, ws = time_steps(vf, torch, wl, theta, x, y, flags, args.steps, args.warmup, fold_window=args.fold_window)
         fits.append({"V": V, "node_size": B // V, "ms_per_step": ms, "samples_per_s": B / (ms * 1e-3),
                      "workspace_bytes": ws})
         V *= 2
@@ -194,6 +196,7 @@ def vsweep(args):
             r["throughput_vs_V1"] = r["samples_per_s"] / rows[0]["samples_per_s"]
             r["workspace_vs_V1"] = r["workspace_bytes"] / rows[0]["workspace_bytes"]
     print(json.dumps({"mode": "vsweep", "workload": base.name, "accumulate": args.accumulate,
+                      "fold_window": args.fold_window,
                       "growing_batch_fixed_node_size": grow, "fixed_batch": fits,
                       "paper_context": "Section 6.6 on one RTX 2080 Ti, normalised to TensorFlow: throughput "
                                        "-4.2 % to +31.4 % as virtual nodes are added at growing batch; at "
@@ -219,7 +222,7 @@ def het_profile(args):
         wl = replace(base, node_sizes=(b,) * V)
         theta = I.make_params(wl)
         x, y = I.make_batch(wl)
-        ms, _ = time_steps(vf, torch, wl, theta, x, y, flags, args.steps, args.warmup)
+        ms, _ = time_steps(vf, torch, wl, theta, x, y, flags, args.steps, args.warmup, fold_window=args.fold_window)
         curve.append({"node_batch": b, "ms_per_node": ms / V, "samples_per_s": b * V / (ms * 1e-3)})
     fast = [c["ms_per_node"] for c in curve]
     slow = [4.0 * t for t in fast]
@@ -249,8 +252,10 @@ def main():
                          "staged: per-node staging vector + the accumulate kernel")
     ap.add_argument("--no-alt", action="store_true", help="skip the timing of the other accumulate mode")
     ap.add_argument("--no-graph", action="store_true")
-    ap.add_argument("--fold-window", type=int, default=1,
-                    help="fused fold: weight gradients of this many consecutive nodes per pass over the buffer")
+    ap.add_argument("--fold-window", type=int, default=8,
+                    help="fused fold: the weight gradients of this many consecutive nodes (1..8) are folded "
+                         "into the gradient buffer in one pass (bitwise the same result as node by node; the "
+                         "workspace keeps that many nodes' transposed bf16 operands)")
     ap.add_argument("--overlap", action="store_true",
                     help="weight gradients on a second stream beside the next node's passes")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -292,6 +297,7 @@ def main():
             (vf.VF_FLAG_OVERLAP if args.overlap else 0)
     eng = vf.VirtualNodeStep(config_from_workload(wl, flags=flags, stream=stream, fold_window=args.fold_window))
     P = eng.num_params
+    window = eng.fold_window                      # the window in effect (1 where no windowed path exists)
     params = torch.from_numpy(theta).cuda()
     xt = torch.from_numpy(x).cuda()
     if wl.kind == "mlp" and wl.dtype == "bf16":
@@ -337,11 +343,12 @@ def main():
                    "global_batch": wl.batch, "virtual_nodes": wl.n_nodes,
                    "node_sizes": sizes if len(set(sizes)) > 1 else f"{wl.n_nodes}x{sizes[0]}",
                    "optimizer": wl.optimizer, "params": P, "accumulate": args.accumulate,
+                   "fold_window": window, "workspace_bytes": eng.workspace_bytes,
                    "graph": not args.no_graph, "overlap": bool(args.overlap)},
         "loss": loss,
     }
 
-    work = algorithmic_work(wl, P, fused=args.accumulate == "fused")
+    work = algorithmic_work(wl, P, fused=args.accumulate == "fused", window=window)
     total_bytes = sum(v[0] for v in work.values())
     total_flops = sum(v[1] for k, v in work.items() if k.startswith(("gemm", "attn")))
     floor_ms = max(total_bytes / (HBM_PEAK_GBS * 1e9), total_flops / (MFMA_BF16_PEAK_TFLOPS * 1e12)) * 1e3
@@ -368,6 +375,12 @@ def main():
                                    if kk in ("bound", "achieved", "peak", "unit", "frac")}
                                for k in kernels if k in work}
     eng.close()
+
+    if not args.no_alt and window > 1:
+        # the same fused fold node by node (window 1), for comparison (never `value`)
+        ms1, ws1 = time_steps(vf, torch, wl, theta, x, y, flags, args.steps, args.warmup)
+        out["alt_window_1"] = {"fold_window": 1, "ms_per_step": ms1, "value": wl.batch / (ms1 * 1e-3),
+                               "workspace_bytes": ws1}
 
     if not args.no_alt:
         # the other accumulate mode, same workload, for comparison (never `value`)

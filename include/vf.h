@@ -164,6 +164,8 @@ int vf_profile_stop(vf_ctx* ctx, char* json, size_t cap);
 
 /* Number of optimizer updates applied so far (one per successful vf_step). */
 int64_t vf_step_count(const vf_ctx* ctx);
+/* The fold window in effect (1 when the configuration's model, dtype or mode has no windowed path). */
+int32_t vf_fold_window(const vf_ctx* ctx);
 
 int64_t vf_num_params(const vf_ctx* ctx);
 
