@@ -414,6 +414,31 @@ def main():
         eng2.close()
         del p2
 
+    if not args.no_alt:
+        # The same steps with every batch coming from pinned host memory through the prefetching
+        # entry points (copy of batch t+1 beside step t): the PCIe-inclusive rate, never `value`.
+        eng3 = vf.VirtualNodeStep(config_from_workload(wl, flags=flags, stream=stream, fold_window=args.fold_window))
+        p3 = torch.from_numpy(theta).cuda()
+        hx, hy = xt.cpu().pin_memory(), yt.cpu().pin_memory()
+        eng3.prefetch(hx, hy)
+        for _ in range(args.warmup):
+            eng3.step_prefetched(p3, sizes)
+            eng3.prefetch(hx, hy)
+        stream.synchronize()
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        for _ in range(args.steps):
+            eng3.step_prefetched(p3, sizes)
+            eng3.prefetch(hx, hy)
+        stream.synchronize()
+        torch.cuda.synchronize()
+        pms = (time.perf_counter() - t2) * 1e3 / args.steps
+        out["host_input"] = {"ms_per_step": pms, "value": wl.batch / (pms * 1e-3),
+                             "bytes_per_step": hx.numel() * hx.element_size() + hy.numel() * hy.element_size(),
+                             "note": "batch copied from pinned host memory by vf_prefetch while the previous step runs"}
+        eng3.close()
+        del p3
+
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, theta, x, y)
     print(json.dumps(out))

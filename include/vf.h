@@ -135,6 +135,22 @@ int vf_init(const vf_config* cfg, vf_ctx** out);
 int vf_step(vf_ctx* ctx, void* params, const void* batch_x, const int32_t* batch_y,
             int32_t B, int32_t V, const int32_t* node_sizes);
 
+/* Input prefetch (Section 3.2 step 1 / Figure 4: while one batch is processed the next one is
+ * fetched in the background).  vf_prefetch copies the NEXT batch (same element types and layout
+ * as vf_step's batch_x / batch_y) from HOST memory into one of two device staging buffers of the
+ * context, on a copy stream of the library's own, and returns at once; the host buffers must
+ * stay untouched until that copy is done, and should be pinned (hipHostMalloc), else the copy
+ * is not asynchronous.  vf_step_prefetched runs vf_step on the staged batch (its stream waits
+ * for the copy) and frees the other pair of buffers for the next vf_prefetch, so the pattern is
+ *     vf_prefetch(b0); loop t: vf_step_prefetched(...); vf_prefetch(b_{t+1});   -- or prefetch first:
+ *     vf_prefetch(b_{t+1}) may be called as soon as vf_step_prefetched(t) has returned.
+ * At most one batch is staged ahead: a second vf_prefetch before the staged batch is consumed
+ * returns VF_ESTATE, as does vf_step_prefetched with nothing staged.  A rejected step
+ * (VF_EINVAL, as vf_step) leaves the batch staged.  The staging buffers are allocated at the
+ * first vf_prefetch (VF_ENOMEM if that fails) and sized for max_batch. */
+int vf_prefetch(vf_ctx* ctx, const void* host_x, const int32_t* host_y, int32_t B);
+int vf_step_prefetched(vf_ctx* ctx, void* params, int32_t V, const int32_t* node_sizes);
+
 /* Combined gradient G = sum_i (b_i/B) g_i of the last step (the value the update used),
  * fp32 [vf_num_params] copied to `out`, which may be a device or a host pointer.
  * Synchronises the stream.  VF_ESTATE before the first step. */

@@ -60,6 +60,8 @@ _SIGNATURES = {
     "vf_init": (C.c_int, [C.POINTER(VfConfig), C.POINTER(C.c_void_p)]),
     "vf_step": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                           C.POINTER(C.c_int32)]),
+    "vf_prefetch": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32]),
+    "vf_step_prefetched": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.POINTER(C.c_int32)]),
     "vf_grads": (C.c_int, [C.c_void_p, C.c_void_p]),
     "vf_loss": (C.c_int, [C.c_void_p, C.POINTER(C.c_float)]),
     "vf_node_losses": (C.c_int, [C.c_void_p, C.POINTER(C.c_float), C.c_int32]),
@@ -279,6 +281,16 @@ class VirtualNodeStep:
         B = int(batch_x.shape[0])
         rc = lib().vf_step(self._h, _ptr(params), _ptr(batch_x), _ptr(batch_y), B, V, sizes)
         _check(rc, "vf_step")
+
+    def prefetch(self, host_x, host_y):
+        """vf_prefetch: host_x, host_y are (pinned) host tensors laid out like step's batch."""
+        rc = lib().vf_prefetch(self._h, _ptr(host_x), _ptr(host_y), int(host_x.shape[0]))
+        _check(rc, "vf_prefetch")
+
+    def step_prefetched(self, params, node_sizes: Sequence[int]):
+        V = len(node_sizes)
+        sizes = (C.c_int32 * max(V, 1))(*[int(b) for b in node_sizes])
+        _check(lib().vf_step_prefetched(self._h, _ptr(params), V, sizes), "vf_step_prefetched")
 
     def step_raw(self, params_ptr: int, x_ptr: int, y_ptr: int, B: int, V: int, node_sizes) -> int:
         """vf_step with raw pointers and sizes; returns the status code (for error tests)."""

@@ -62,9 +62,16 @@ int validate_config(const vf_config& c) {
   return VF_EINVAL;
 }
 
-bool graph_matches(const Ctx& c, const StepArgs& a) {
-  return !c.graphs.empty() && c.graph_params == a.params && c.graph_x == a.x && c.graph_y == a.y &&
-         c.graph_sizes == a.sizes;
+bool set_matches(const Ctx::GraphSet& g, const StepArgs& a) {
+  return !g.graphs.empty() && g.params == a.params && g.x == a.x && g.y == a.y && g.sizes == a.sizes;
+}
+
+// Selects the captured set that fits this call, if there is one.
+bool graph_matches(Ctx& c, const StepArgs& a) {
+  if (set_matches(c.gs(), a)) return true;
+  if (set_matches(c.gsets[c.cur ^ 1], a)) { c.cur ^= 1; return true; }
+  if (!c.gs().graphs.empty()) c.cur ^= 1;      // capture into the older set, keep the latest one
+  return false;
 }
 
 void release_streams(Ctx& c) {
@@ -74,10 +81,55 @@ void release_streams(Ctx& c) {
   if (c.side) { (void)hipStreamDestroy(c.side); c.side = nullptr; }
 }
 
+void release_prefetch(Ctx& c) {
+  Ctx::Prefetch& p = c.pf;
+  for (int k = 0; k < 2; ++k) {
+    if (p.copied[k]) (void)hipEventDestroy(p.copied[k]);
+    if (p.consumed[k]) (void)hipEventDestroy(p.consumed[k]);
+    if (p.x[k]) (void)hipFree(p.x[k]);
+    if (p.y[k]) (void)hipFree(p.y[k]);
+    p.copied[k] = p.consumed[k] = nullptr;
+    p.x[k] = nullptr; p.y[k] = nullptr;
+  }
+  if (p.stream) (void)hipStreamDestroy(p.stream);
+  p.stream = nullptr;
+}
+
+// Bytes of one batch of B samples as vf_step reads it.
+size_t batch_x_bytes(const vf_config& f, int64_t B) {
+  if (f.model_kind == VF_MLP) return (size_t)B * f.dims[0] * (f.dtype == VF_BF16 ? 2 : 4);
+  return (size_t)B * f.seq_len * sizeof(int32_t);
+}
+size_t batch_y_bytes(const vf_config& f, int64_t B) {
+  if (f.model_kind == VF_MLP) return (size_t)B * sizeof(int32_t);
+  return (size_t)B * 2 * f.n_masked * sizeof(int32_t);
+}
+
+// First use: the copy stream (default priority), two pairs of device staging buffers sized for
+// max_batch, and the events that order copies against the steps that read them.
+int init_prefetch(Ctx& c) {
+  Ctx::Prefetch& p = c.pf;
+  if (p.stream) return VF_OK;
+  hipError_t e = hipStreamCreateWithFlags(&p.stream, hipStreamNonBlocking);
+  for (int k = 0; k < 2 && e == hipSuccess; ++k) {
+    e = hipEventCreateWithFlags(&p.copied[k], hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&p.consumed[k], hipEventDisableTiming);
+    if (e == hipSuccess) e = hipMalloc(&p.x[k], batch_x_bytes(c.cfg, c.cfg.max_batch));
+    if (e == hipSuccess) e = hipMalloc(&p.y[k], batch_y_bytes(c.cfg, c.cfg.max_batch));
+  }
+  if (e != hipSuccess) {
+    set_last_error("prefetch set-up", e, __FILE__, __LINE__);
+    (void)hipGetLastError();
+    release_prefetch(c);
+    return e == hipErrorOutOfMemory ? VF_ENOMEM : VF_EDEVICE;
+  }
+  return VF_OK;
+}
+
 void drop_graph(Ctx& c) {
-  for (hipGraphExec_t g : c.graphs)
+  for (hipGraphExec_t g : c.gs().graphs)
     if (g) (void)hipGraphExecDestroy(g);
-  c.graphs.clear();
+  c.gs().graphs.clear();
 }
 
 // The three kinds of launch sequence of a step; `part` 0 = weight preparation, 1 = main(i),
@@ -117,7 +169,7 @@ int enqueue_nodes(Ctx& c, const StepArgs& a, bool use_graph);
 // Without overlap the whole step (minus the update) is one single-stream chain: one graph.
 int capture_whole_step(Ctx& c, const StepArgs& a) {
   drop_graph(c);
-  c.graphs.assign(1, nullptr);
+  c.gs().graphs.assign(1, nullptr);
   hipGraph_t graph = nullptr;
   VF_HIP(hipStreamBeginCapture(c.stream, hipStreamCaptureModeThreadLocal));
   int rc = enqueue_nodes(c, a, false);
@@ -127,7 +179,7 @@ int capture_whole_step(Ctx& c, const StepArgs& a) {
     rc = VF_EDEVICE;
   }
   if (rc == VF_OK) {
-    e = hipGraphInstantiate(&c.graphs[0], graph, nullptr, nullptr, 0);
+    e = hipGraphInstantiate(&c.gs().graphs[0], graph, nullptr, nullptr, 0);
     if (e != hipSuccess) {
       set_last_error("hipGraphInstantiate", e, __FILE__, __LINE__);
       rc = VF_EDEVICE;
@@ -135,34 +187,34 @@ int capture_whole_step(Ctx& c, const StepArgs& a) {
   }
   if (graph) (void)hipGraphDestroy(graph);
   if (rc != VF_OK) {
-    c.graphs.clear();
+    c.gs().graphs.clear();
     return rc;
   }
-  c.graph_params = a.params; c.graph_x = a.x; c.graph_y = a.y; c.graph_sizes = a.sizes;
+  c.gs().params = a.params; c.gs().x = a.x; c.gs().y = a.y; c.gs().sizes = a.sizes;
   return VF_OK;
 }
 
 int capture_graphs(Ctx& c, const StepArgs& a) {
   if (!c.overlapping()) return capture_whole_step(c, a);
   drop_graph(c);
-  c.graphs.assign((size_t)1 + 2 * a.V, nullptr);
-  int rc = capture_part(c, a, 0, 0, &c.graphs[0]);
+  c.gs().graphs.assign((size_t)1 + 2 * a.V, nullptr);
+  int rc = capture_part(c, a, 0, 0, &c.gs().graphs[0]);
   for (int i = 0; i < a.V && rc == VF_OK; ++i) {
-    rc = capture_part(c, a, 1, i, &c.graphs[1 + 2 * i]);
-    if (rc == VF_OK) rc = capture_part(c, a, 2, i, &c.graphs[2 + 2 * i]);
+    rc = capture_part(c, a, 1, i, &c.gs().graphs[1 + 2 * i]);
+    if (rc == VF_OK) rc = capture_part(c, a, 2, i, &c.gs().graphs[2 + 2 * i]);
   }
   if (rc != VF_OK) {
     drop_graph(c);
     return rc;
   }
-  c.graph_params = a.params; c.graph_x = a.x; c.graph_y = a.y; c.graph_sizes = a.sizes;
+  c.gs().params = a.params; c.gs().x = a.x; c.gs().y = a.y; c.gs().sizes = a.sizes;
   return VF_OK;
 }
 
 // Run one part: replay its graph, or launch its kernels one by one.
 int run_part(Ctx& c, const StepArgs& a, bool use_graph, int part, int node, hipStream_t st) {
   if (!use_graph) return enqueue_part(c, a, part, node, st);
-  hipGraphExec_t g = c.graphs[part == 0 ? 0 : (size_t)part + 2 * node];
+  hipGraphExec_t g = c.gs().graphs[part == 0 ? 0 : (size_t)part + 2 * node];
   VF_HIP(hipGraphLaunch(g, st));
   return VF_OK;
 }
@@ -173,7 +225,7 @@ int run_part(Ctx& c, const StepArgs& a, bool use_graph, int part, int node, hipS
 int enqueue_nodes(Ctx& c, const StepArgs& a, bool use_graph) {
   const bool ov = c.overlapping();
   if (use_graph && !ov) {          // the whole step is one captured chain
-    VF_HIP(hipGraphLaunch(c.graphs[0], c.stream));
+    VF_HIP(hipGraphLaunch(c.gs().graphs[0], c.stream));
     return VF_OK;
   }
   hipStream_t side = ov ? c.side : c.stream;
@@ -325,16 +377,60 @@ int vf_init(const vf_config* cfg, vf_ctx** out) {
   return VF_OK;
 }
 
-int vf_step(vf_ctx* h, void* params, const void* batch_x, const int32_t* batch_y, int32_t B,
-            int32_t V, const int32_t* node_sizes) {
-  if (!h || !params || !batch_x || !batch_y) return VF_EINVAL;
-  Ctx& c = h->c;
+namespace {
+// Everything vf_step checks before any device work.
+int check_step(const Ctx& c, const void* params, int32_t B, int32_t V, const int32_t* node_sizes) {
   int rc = check_partition(node_sizes, V, B);
   if (rc != VF_OK) return rc;
   if (V > c.cfg.max_nodes || B > c.cfg.max_batch) return VF_EINVAL;
   for (int32_t i = 0; i < V; ++i)
     if (node_sizes[i] > c.cfg.max_node_size) return VF_EINVAL;
   if (reinterpret_cast<uintptr_t>(params) & 15) return VF_EINVAL;
+  return VF_OK;
+}
+}  // namespace
+
+int vf_prefetch(vf_ctx* h, const void* host_x, const int32_t* host_y, int32_t B) {
+  if (!h || !host_x || !host_y || B < 1 || B > h->c.cfg.max_batch) return VF_EINVAL;
+  Ctx& c = h->c;
+  Ctx::Prefetch& p = c.pf;
+  if (p.pending) return VF_ESTATE;                 // one batch ahead: the staged one has not been used
+  VF_TRY(init_prefetch(c));
+  const int k = p.next;
+  // the step that last read this pair of buffers has to be through with them
+  if (p.used[k]) VF_HIP(hipStreamWaitEvent(p.stream, p.consumed[k], 0));
+  VF_HIP(hipMemcpyAsync(p.x[k], host_x, batch_x_bytes(c.cfg, B), hipMemcpyHostToDevice, p.stream));
+  VF_HIP(hipMemcpyAsync(p.y[k], host_y, batch_y_bytes(c.cfg, B), hipMemcpyHostToDevice, p.stream));
+  VF_HIP(hipEventRecord(p.copied[k], p.stream));
+  p.pending = true;
+  p.pending_B = B;
+  return VF_OK;
+}
+
+int vf_step_prefetched(vf_ctx* h, void* params, int32_t V, const int32_t* node_sizes) {
+  if (!h || !params) return VF_EINVAL;
+  Ctx& c = h->c;
+  Ctx::Prefetch& p = c.pf;
+  if (!p.pending) return VF_ESTATE;
+  int rc = check_step(c, params, p.pending_B, V, node_sizes);
+  if (rc != VF_OK) return rc;                      // the staged batch stays staged
+  const int k = p.next;
+  VF_HIP(hipStreamWaitEvent(c.stream, p.copied[k], 0));
+  rc = vf_step(h, params, p.x[k], static_cast<const int32_t*>(p.y[k]), p.pending_B, V, node_sizes);
+  if (rc != VF_OK) return rc;
+  VF_HIP(hipEventRecord(p.consumed[k], c.stream));
+  p.used[k] = true;
+  p.pending = false;
+  p.next = k ^ 1;
+  return VF_OK;
+}
+
+int vf_step(vf_ctx* h, void* params, const void* batch_x, const int32_t* batch_y, int32_t B,
+            int32_t V, const int32_t* node_sizes) {
+  if (!h || !params || !batch_x || !batch_y) return VF_EINVAL;
+  Ctx& c = h->c;
+  int rc = check_step(c, params, B, V, node_sizes);
+  if (rc != VF_OK) return rc;
 
   StepArgs a;
   a.params = static_cast<float*>(params);
@@ -481,7 +577,10 @@ void vf_destroy(vf_ctx* h) {
     (void)hipStreamSynchronize(c.stream);
     if (c.side) (void)hipStreamSynchronize(c.side);
     drop_graph(c);
+    c.cur ^= 1;
+    drop_graph(c);
     release_streams(c);
+    release_prefetch(c);
     for (hipEvent_t e : c.prof.pool) (void)hipEventDestroy(e);
     (void)hipFree(c.arena);
   }

@@ -133,11 +133,33 @@ struct Ctx {
   // Graph replay: one captured launch sequence per part (weight preparation, main(i), side(i)),
   // each a single-stream chain, so replay keeps the two streams apart exactly as eager
   // launches do.
-  std::vector<hipGraphExec_t> graphs;     // [0] prepare, [1+2i] main(i), [2+2i] side(i)
-  std::vector<int32_t> graph_sizes;
-  const void* graph_params = nullptr;
-  const void* graph_x = nullptr;
-  const void* graph_y = nullptr;
+  // Two captured sets are kept (a caller that alternates between two input buffers, as the
+  // prefetching entry points do, replays instead of recapturing); `cur` is the one in use.
+  struct GraphSet {
+    std::vector<hipGraphExec_t> graphs;     // [0] prepare, [1+2i] main(i), [2+2i] side(i)
+    std::vector<int32_t> sizes;
+    const void* params = nullptr;
+    const void* x = nullptr;
+    const void* y = nullptr;
+  };
+  GraphSet gsets[2];
+  int cur = 0;
+  GraphSet& gs() { return gsets[cur]; }
+  const GraphSet& gs() const { return gsets[cur]; }
+
+  // Input prefetch (Section 3.2 step 1: the next batch is fetched while this one is processed):
+  // a copy stream and two pairs of device staging buffers, created on first use.
+  struct Prefetch {
+    hipStream_t stream = nullptr;
+    void* x[2] = {nullptr, nullptr};
+    void* y[2] = {nullptr, nullptr};
+    hipEvent_t copied[2] = {nullptr, nullptr};     // the copy into pair k is complete
+    hipEvent_t consumed[2] = {nullptr, nullptr};   // the step that read pair k is complete
+    bool used[2] = {false, false};
+    int next = 0;                                  // the pair the next prefetch fills / next step reads
+    bool pending = false;                          // a batch is staged and not yet consumed
+    int32_t pending_B = 0;
+  } pf;
 
   // Destination of node i's gradient entry at flat offset `off`.
   GradOut gout(int64_t off, float w, int node) const {

@@ -103,3 +103,8 @@ def test_state_size_of_a_null_context_is_zero_and_config_rejects_a_bad_share():
     cfg = config_from_workload(replace(I.workload("mlp_small_bn_f32"), bn_momentum=1.5))
     h = C.c_void_p()
     assert vf.lib().vf_init(C.byref(cfg), C.byref(h)) != 0 and not h
+
+
+def test_prefetch_entry_points_reject_null_arguments_without_a_device():
+    assert vf.lib().vf_prefetch(None, None, None, 4) != 0
+    assert vf.lib().vf_step_prefetched(None, None, 1, None) != 0
