@@ -253,3 +253,33 @@ def test_fold_window_workspace_does_not_depend_on_the_number_of_nodes():
                    max_batch=240, max_nodes=16)
     assert few["workspace_bytes"] == many["workspace_bytes"]
     assert np.linalg.norm(few["G"] - many["G"]) > 0          # different splits really ran
+
+
+def test_changing_the_split_between_steps_replays_the_right_graph():
+    """Three different splits of the same batch in rotation (more than the two captured sets the
+    context keeps), against the same calls launched kernel by kernel."""
+    import torch
+    import paper_2009_09523_amd as vf
+    from paper_2009_09523_amd.binding import config_from_workload
+    wl, theta, x, y = _case("mlp_mid_bn_bf16")
+    B = wl.batch
+    splits = [list(wl.node_sizes), [B // 2, B - B // 2], [64] * (B // 64) + ([B % 64] if B % 64 else [])]
+    order = [0, 1, 0, 2, 1, 0, 0, 2]
+
+    def run(flags):
+        stream = torch.cuda.Stream()
+        eng = vf.VirtualNodeStep(config_from_workload(wl, flags=flags, stream=stream, fold_window=2,
+                                                      max_node_size=max(max(s) for s in splits),
+                                                      max_nodes=max(len(s) for s in splits)))
+        from vfharness import to_device_batch
+        p = torch.from_numpy(theta).cuda()
+        xt, yt = to_device_batch(wl, x, y)
+        torch.cuda.synchronize()
+        for k in order:
+            eng.step(p, xt, yt, splits[k])
+        stream.synchronize()
+        out = p.cpu().numpy()
+        eng.close()
+        return out
+
+    assert run(FUSED).tobytes() == run(FUSED | NO_GRAPH).tobytes()
