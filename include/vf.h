@@ -66,12 +66,21 @@ extern "C" {
                                         element (one fused multiply-add), same node order */
 #define VF_FLAG_NO_GRAPH         2u  /* launch kernels one by one instead of replaying a
                                         captured HIP graph */
-#define VF_FLAG_OVERLAP          4u  /* run each node's weight gradients and the fold into the
-                                        gradient buffer on a second, library-owned stream beside
-                                        the next node's passes (bf16 MLP only; same results bit
-                                        for bit).  Off by default: the kernels already fill the
-                                        chip, so the measured gain is 2-3 percent, and with one
-                                        stream the whole step replays as a single graph. */
+#define VF_FLAG_OVERLAP          4u  /* two streams (bf16 MLP only; same results bit for bit):
+                                        the forward passes run on the caller's stream, the
+                                        backward passes and weight gradients on a second,
+                                        library-owned stream, so that node i+1's forward pass
+                                        runs beside node i's backward pass.  Nodes still start
+                                        and finish in order, and every accumulation whose order
+                                        matters stays on one stream; the tensors that pass from a
+                                        node's forward to its backward pass are kept twice. */
+#define VF_FLAG_ORDERED_FOLD     8u  /* inside a fold window keep the node-by-node chain of
+                                        roundings, G <- fma(b_i/B, g_i, G) node after node, also
+                                        when all its nodes have one size.  Without this flag such
+                                        a window (bf16 MLP) takes its weight gradients as ONE
+                                        product over all the window's rows, times the common
+                                        weight: the same sum with fewer roundings, equal to the
+                                        node-by-node result to fp32 rounding, not bit for bit. */
 
 typedef struct vf_ctx vf_ctx;
 
@@ -170,9 +179,11 @@ int vf_opt_state(vf_ctx* ctx, int32_t which, float* out);
 
 /* Per-kernel timing of the steps run between the two calls (the library's counterpart of the
  * offline profiling of Section 5.1.1: how long each part of a node's pass takes on this
- * device).  While enabled, every kernel launch is bracketed by two events on the context's
- * stream and launches are made one by one instead of by graph replay, so step time itself is
- * slower than normal.  vf_profile_stop synchronises and writes a JSON object
+ * device).  While enabled, every kernel launch is bracketed by two events on the stream it goes
+ * to and launches are made one by one instead of by graph replay, so step time itself is
+ * slower than normal.  With VF_FLAG_OVERLAP the two streams stay in use, so a kernel's time
+ * includes whatever it loses to the kernel running beside it.  vf_profile_stop synchronises and
+ * writes a JSON object
  * {"<kernel tag>": {"launches": n, "total_ms": t}, ...} into `json` (host, `cap` bytes,
  * NUL-terminated); VF_EINVAL if it does not fit. */
 int vf_profile_start(vf_ctx* ctx);

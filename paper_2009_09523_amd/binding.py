@@ -15,6 +15,7 @@ VF_MAX_DIMS = 16
 VF_FLAG_FUSED_ACCUMULATE = 1
 VF_FLAG_NO_GRAPH = 2
 VF_FLAG_OVERLAP = 4
+VF_FLAG_ORDERED_FOLD = 8
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 

@@ -75,9 +75,10 @@ bool graph_matches(Ctx& c, const StepArgs& a) {
 }
 
 void release_streams(Ctx& c) {
-  for (int k = 0; k < 2; ++k)
-    if (c.side_done[k]) { (void)hipEventDestroy(c.side_done[k]); c.side_done[k] = nullptr; }
-  if (c.main_done) { (void)hipEventDestroy(c.main_done); c.main_done = nullptr; }
+  hipEvent_t* evs[] = {&c.fwd_done[0], &c.fwd_done[1], &c.bwd_done[0], &c.bwd_done[1],
+                       &c.side_done[0], &c.side_done[1], &c.prep_done};
+  for (hipEvent_t* e : evs)
+    if (*e) { (void)hipEventDestroy(*e); *e = nullptr; }
   if (c.side) { (void)hipStreamDestroy(c.side); c.side = nullptr; }
 }
 
@@ -132,12 +133,14 @@ void drop_graph(Ctx& c) {
   c.gs().graphs.clear();
 }
 
-// The three kinds of launch sequence of a step; `part` 0 = weight preparation, 1 = main(i),
-// 2 = side(i).  Each runs on one stream.
-int enqueue_part(Ctx& c, const StepArgs& a, int part, int node, hipStream_t st) {
+// The kinds of launch sequence of a step; `part` 0 = weight preparation, 1 = fwd(i), 2 = bwd(i),
+// 3 = side(window i).  Each runs on one stream.
+int enqueue_part(Ctx& c, const StepArgs& a, int part, int idx, hipStream_t st) {
   if (part == 0) return c.model->prepare(c, a.params, st);
-  if (part == 1) return c.model->run_node_main(c, a, node, st);
-  return c.model->run_nodes_side(c, a, node, 1, st);
+  if (part == 1) return c.model->run_node_fwd(c, a, idx, st);
+  if (part == 2) return c.model->run_node_bwd(c, a, idx, st);
+  const int i0 = idx * c.window;
+  return c.model->run_nodes_side(c, a, i0, std::min(c.window, a.V - i0), st);
 }
 
 // Record one part into a graph (captured on the main stream; replayed on whichever stream).
@@ -197,12 +200,14 @@ int capture_whole_step(Ctx& c, const StepArgs& a) {
 int capture_graphs(Ctx& c, const StepArgs& a) {
   if (!c.overlapping()) return capture_whole_step(c, a);
   drop_graph(c);
-  c.gs().graphs.assign((size_t)1 + 2 * a.V, nullptr);
+  const int nwin = (a.V + c.window - 1) / c.window;
+  c.gs().graphs.assign((size_t)1 + 2 * a.V + nwin, nullptr);
   int rc = capture_part(c, a, 0, 0, &c.gs().graphs[0]);
   for (int i = 0; i < a.V && rc == VF_OK; ++i) {
     rc = capture_part(c, a, 1, i, &c.gs().graphs[1 + 2 * i]);
     if (rc == VF_OK) rc = capture_part(c, a, 2, i, &c.gs().graphs[2 + 2 * i]);
   }
+  for (int w = 0; w < nwin && rc == VF_OK; ++w) rc = capture_part(c, a, 3, w, &c.gs().graphs[1 + 2 * a.V + w]);
   if (rc != VF_OK) {
     drop_graph(c);
     return rc;
@@ -212,25 +217,24 @@ int capture_graphs(Ctx& c, const StepArgs& a) {
 }
 
 // Run one part: replay its graph, or launch its kernels one by one.
-int run_part(Ctx& c, const StepArgs& a, bool use_graph, int part, int node, hipStream_t st) {
-  if (!use_graph) return enqueue_part(c, a, part, node, st);
-  hipGraphExec_t g = c.gs().graphs[part == 0 ? 0 : (size_t)part + 2 * node];
-  VF_HIP(hipGraphLaunch(g, st));
+int run_part(Ctx& c, const StepArgs& a, bool use_graph, int part, int idx, hipStream_t st) {
+  if (!use_graph) return enqueue_part(c, a, part, idx, st);
+  const size_t at = part == 0 ? 0 : (part == 3 ? (size_t)1 + 2 * a.V + idx : (size_t)part + 2 * idx);
+  VF_HIP(hipGraphLaunch(c.gs().graphs[at], st));
   return VF_OK;
 }
 
-// Everything of one step except the optimizer update (Section 3.2 steps 1-3): the nodes one
-// after another on the main stream, each node's weight gradients (and fold) beside the next
-// node's passes on the side stream.
+// Everything of one step except the optimizer update (Section 3.2 steps 1-3).  One stream: the
+// nodes one after another, each window of nodes followed by its side part.  Two streams: the
+// forward parts on the caller's stream, the backward and side parts on the second one.
 int enqueue_nodes(Ctx& c, const StepArgs& a, bool use_graph) {
   const bool ov = c.overlapping();
   if (use_graph && !ov) {          // the whole step is one captured chain
     VF_HIP(hipGraphLaunch(c.gs().graphs[0], c.stream));
     return VF_OK;
   }
-  hipStream_t side = ov ? c.side : c.stream;
   VF_TRY(run_part(c, a, use_graph, 0, 0, c.stream));
-  if (!ov) {   // one stream: windows of nodes, each followed by one side part for the whole window
+  if (!ov) {
     for (int i0 = 0; i0 < a.V; i0 += c.window) {
       const int count = std::min(c.window, a.V - i0);
       for (int i = i0; i < i0 + count; ++i) VF_TRY(c.model->run_node_main(c, a, i, c.stream));
@@ -238,20 +242,32 @@ int enqueue_nodes(Ctx& c, const StepArgs& a, bool use_graph) {
     }
     return VF_OK;
   }
-  for (int i = 0; i < a.V; ++i) {
-    const int p = i & 1;
-    // copy p of the side part's operands was last read by side(i-2)
-    if (ov && i >= 2) VF_HIP(hipStreamWaitEvent(c.stream, c.side_done[p], 0));
-    VF_TRY(run_part(c, a, use_graph, 1, i, c.stream));
-    if (ov) {
-      VF_HIP(hipEventRecord(c.main_done, c.stream));
-      VF_HIP(hipStreamWaitEvent(side, c.main_done, 0));
+  VF_HIP(hipEventRecord(c.prep_done, c.stream));
+  VF_HIP(hipStreamWaitEvent(c.side, c.prep_done, 0));
+  const int nwin = (a.V + c.window - 1) / c.window;
+  const int reach = std::max(1, std::min(2, c.copies() / c.window));
+  for (int w = 0; w < nwin; ++w) {
+    const int i0 = w * c.window, i1 = std::min(a.V, i0 + c.window);
+    // This window's forward parts overwrite operand copies that an earlier side part reads: the
+    // one `reach` windows back, where `reach` windows fit into the copies.
+    if (w >= reach) VF_HIP(hipStreamWaitEvent(c.stream, c.side_done[(w - reach) & 1], 0));
+    for (int i = i0; i < i1; ++i) {
+      const int q = c.aset(i);
+      // the tensors of set q were last read by bwd(i-2)
+      if (i >= 2) VF_HIP(hipStreamWaitEvent(c.stream, c.bwd_done[q], 0));
+      VF_TRY(run_part(c, a, use_graph, 1, i, c.stream));
+      VF_HIP(hipEventRecord(c.fwd_done[q], c.stream));
+      VF_HIP(hipStreamWaitEvent(c.side, c.fwd_done[q], 0));
+      VF_TRY(run_part(c, a, use_graph, 2, i, c.side));
+      VF_HIP(hipEventRecord(c.bwd_done[q], c.side));
     }
-    VF_TRY(run_part(c, a, use_graph, 2, i, side));
-    if (ov) VF_HIP(hipEventRecord(c.side_done[p], side));
+    // The window's weight gradients follow its backward parts on the second stream (a staged
+    // node's gradient lives in the one staging vector that the next backward part writes again).
+    VF_TRY(run_part(c, a, use_graph, 3, w, c.side));
+    VF_HIP(hipEventRecord(c.side_done[w & 1], c.side));
   }
-  // join: the side stream is in order, so its latest event covers all nodes
-  if (ov) VF_HIP(hipStreamWaitEvent(c.stream, c.side_done[(a.V - 1) & 1], 0));
+  // join: the last side part is the last thing on the second stream
+  VF_HIP(hipStreamWaitEvent(c.stream, c.side_done[(nwin - 1) & 1], 0));
   return VF_OK;
 }
 
@@ -327,11 +343,13 @@ int vf_init(const vf_config* cfg, vf_ctx** out) {
   // stream reads (the bf16 MLP does).
   c.overlap = c.stream != nullptr && (cfg->flags & VF_FLAG_OVERLAP) && c.model->supports_overlap();
   // A window needs the fused fold: a staged node's gradient lives in one staging vector.
-  c.window = (c.overlap || !c.fused || cfg->fold_window < 1) ? 1 : std::min(cfg->fold_window, c.model->max_window());
+  c.window = (!c.fused || cfg->fold_window < 1) ? 1 : std::min(cfg->fold_window, c.model->max_window());
   if (c.overlap) {
     e = hipStreamCreateWithFlags(&c.side, hipStreamNonBlocking);
-    for (int k = 0; k < 2 && e == hipSuccess; ++k) e = hipEventCreateWithFlags(&c.side_done[k], hipEventDisableTiming);
-    if (e == hipSuccess) e = hipEventCreateWithFlags(&c.main_done, hipEventDisableTiming);
+    hipEvent_t* evs[] = {&c.fwd_done[0], &c.fwd_done[1], &c.bwd_done[0], &c.bwd_done[1],
+                         &c.side_done[0], &c.side_done[1], &c.prep_done};
+    for (hipEvent_t* ev : evs)
+      if (e == hipSuccess) e = hipEventCreateWithFlags(ev, hipEventDisableTiming);
     if (e != hipSuccess) {
       set_last_error("side stream set-up", e, __FILE__, __LINE__);
       release_streams(c);
@@ -343,7 +361,6 @@ int vf_init(const vf_config* cfg, vf_ctx** out) {
   Arena arena;
   arena.request(&c.gbuf, (size_t)c.P);
   if (!c.fused) arena.request(&c.gstage, (size_t)c.P);
-  if (!c.fused && c.overlap) arena.request(&c.gstage2, (size_t)c.P);
   arena.request(&c.opt0, (size_t)c.P);
   if (cfg->optimizer == VF_ADAM) arena.request(&c.opt1, (size_t)c.P);
   size_t loss_rows = (size_t)cfg->max_node_size;

@@ -1,6 +1,7 @@
 // The library context: configuration, parameter layout, device buffers, per-model runners.
 #pragma once
 
+#include <algorithm>
 #include <memory>
 #include <string>
 #include <vector>
@@ -48,18 +49,24 @@ class Model {
   virtual void request_buffers(Arena& a) = 0;
   // Refresh whatever the passes read instead of the fp32 master (bf16 weight copies).
   virtual int prepare(Ctx& c, const float* params, hipStream_t st) = 0;
-  // Node `i` (rows off..off+b) in two parts, each a plain sequence of launches on ONE stream:
-  //   main part: forward pass, loss bookkeeping, and the input-gradient chain of the backward
-  //              pass (everything the next node's passes have to wait for);
-  //   side part: what only the gradient buffer waits for -- weight gradients and, in staged
-  //              mode, the fold c.fold(i, ...).  It reads operands the main part left behind,
-  //              and covers `count` consecutive nodes i0 .. i0+count-1 (the fold window): a model
-  //              may fold their weight gradients into the buffer in one pass over it.
-  // The executor runs main(i0) .. main(i0+count-1), then side(i0, count); the main part of node i
-  // leaves its operands in copy c.slot(i).  With overlap (window 1) the side part goes to the
-  // second stream and runs beside main(i+1): nodes alternate between two copies and side(i) is
-  // complete before main(i+2).
+  // Node `i` (rows off..off+b), each part a plain sequence of launches on ONE stream:
+  //   forward part:  forward pass and loss bookkeeping (it also leaves the transposed operands of
+  //                  the weight gradients it produces in copy c.slot(i));
+  //   backward part: the input-gradient chain with the small-vector gradients (BatchNorm scale and
+  //                  shift, hidden biases) folded into the gradient buffer on the way;
+  //   side part:     what only the gradient buffer waits for -- weight gradients and, in staged
+  //                  mode, the fold c.fold(i, ...) -- for `count` consecutive nodes i0 .. i0+count-1
+  //                  (the fold window): a model may fold their weight gradients in one pass.
+  // One stream: fwd(i), bwd(i) for the nodes of a window, then side(window).  Two streams
+  // (overlap): the forward parts run on the caller's stream, the backward and side parts on the
+  // library's second stream, so that fwd(i+1) runs beside bwd(i); every chain whose order matters
+  // (moving statistics and loss in the forward parts, small-vector gradients in the backward
+  // parts) stays on one stream in node order.  A model that supports this keeps the tensors that
+  // pass from a node's forward to its backward part in two sets, c.aset(i).
+  // run_node_main = forward part + backward part on one stream.
   virtual int run_node_main(Ctx& c, const StepArgs& a, int i, hipStream_t st) = 0;
+  virtual int run_node_fwd(Ctx& c, const StepArgs& a, int i, hipStream_t st) { return run_node_main(c, a, i, st); }
+  virtual int run_node_bwd(Ctx&, const StepArgs&, int, hipStream_t) { return VF_OK; }
   virtual int run_nodes_side(Ctx& c, const StepArgs& a, int i0, int count, hipStream_t st) = 0;
   virtual bool supports_overlap() const { return false; }
   // Largest fold window the side part can take (it must keep that many nodes' operands).
@@ -114,21 +121,23 @@ struct Ctx {
   int64_t steps = 0;
   int32_t last_V = 0;
 
-  // Second stream (library-owned, default priority) for work off a node's critical path:
-  // weight gradients and the fold into the gradient buffer run there while the main stream
-  // goes on with the input-gradient chain and the next node's forward pass.
+  // Second stream (library-owned, default priority): with overlap the backward parts and the
+  // weight gradients run there while the caller's stream goes on with the next node's forward.
   hipStream_t side = nullptr;
   bool overlap = false;
-  float* gstage2 = nullptr;               // second staging vector (nodes alternate) when overlapping
-  hipEvent_t side_done[2] = {nullptr, nullptr};
-  hipEvent_t main_done = nullptr;
+  hipEvent_t fwd_done[2] = {nullptr, nullptr};   // forward part of the node using set q is complete
+  hipEvent_t bwd_done[2] = {nullptr, nullptr};   // backward part of the node using set q is complete
+  hipEvent_t side_done[2] = {nullptr, nullptr};  // side part of window w (parity) is complete
+  hipEvent_t prep_done = nullptr;                // weight preparation
 
   int window = 1;                         // nodes whose weight gradients are folded in one pass
-  int copies() const { return overlap ? 2 : window; }        // copies of the side part's operands
-  int slot(int node) const { return overlap ? (node & 1) : node % window; }
+  // copies of the side part's operands: one window's worth, and two with overlap at window 1
+  int copies() const { return overlap ? std::max(2, window) : window; }
+  int slot(int node) const { return node % copies(); }
+  int aset(int node) const { return overlap ? (node & 1) : 0; }           // forward -> backward tensor set
 
-  bool overlapping() const { return overlap && !prof.enabled; }
-  float* stage_for(int node) const { return (overlap && (node & 1)) ? gstage2 : gstage; }
+  bool overlapping() const { return overlap; }
+  float* stage_for(int) const { return gstage; }
 
   // Graph replay: one captured launch sequence per part (weight preparation, main(i), side(i)),
   // each a single-stream chain, so replay keeps the two streams apart exactly as eager
@@ -136,7 +145,7 @@ struct Ctx {
   // Two captured sets are kept (a caller that alternates between two input buffers, as the
   // prefetching entry points do, replays instead of recapturing); `cur` is the one in use.
   struct GraphSet {
-    std::vector<hipGraphExec_t> graphs;     // [0] prepare, [1+2i] main(i), [2+2i] side(i)
+    std::vector<hipGraphExec_t> graphs;     // one graph, or [0] prepare, [1+2i] fwd(i), [2+2i] bwd(i), [1+2V+w] side(w)
     std::vector<int32_t> sizes;
     const void* params = nullptr;
     const void* x = nullptr;

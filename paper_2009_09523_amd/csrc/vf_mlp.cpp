@@ -17,18 +17,24 @@ struct Layer {
   bf16_t* wnat = nullptr;          // bf16 W  [K, ldn]   (contraction = N: input gradients)
   bf16_t* wtr = nullptr;           // bf16 W^T [N, ldt]  (contraction = K: forward)
   int64_t ld = 0;                  // leading dim of this layer's [b, N] buffers (N rounded to 8)
-  float* z = nullptr;              // fp32 [max_b, ld]: Linear output (logits for the last layer)
-  float* mean = nullptr;           // [N]
-  float* rstd = nullptr;           // [N]
+  // Tensors that pass from a node's forward part to its backward part come in two sets
+  // (Ctx::aset): with two streams the next node's forward part runs beside this node's backward.
+  float* z[2] = {nullptr, nullptr};     // fp32 [max_b, ld]: Linear output (logits for the last layer)
+  float* mean[2] = {nullptr, nullptr};  // [N]
+  float* rstd[2] = {nullptr, nullptr};  // [N]
   int64_t s_off = 0;               // offset of this layer's moving statistics within a state half
-  void* a = nullptr;               // T [max_b, ld]: activation after BatchNorm/ReLU
-  void* dz = nullptr;              // T [max_b, ld]: gradient w.r.t. z
-  // Weight-gradient operands, transposed ([N, ldb], rows of the node contiguous).  Several
-  // copies (Ctx::copies): node i writes copy Ctx::slot(i), so that the operands of a whole fold
-  // window are still there when its weight gradients are taken in one pass, or (two streams) the
-  // side stream can read node i's operands while the main stream produces those of node i+1.
-  bf16_t* aT[kFoldMax] = {};     // a transposed
-  bf16_t* dzT[kFoldMax] = {};    // dz transposed
+  void* a[2] = {nullptr, nullptr};      // T [max_b, ld]: activation after BatchNorm/ReLU
+  // T [max_b, ld]: gradient w.r.t. z.  Two sets only for the last layer (the softmax of the
+  // forward part writes it); the hidden layers' are written and read by the backward part.
+  void* dz[2] = {nullptr, nullptr};
+  // Weight-gradient operands, transposed: one wide matrix [N, ldw] each, in which node i owns
+  // the columns of copy Ctx::slot(i) (Mlp::cols), its rows contiguous along the matrix row.  So
+  // the operands of a whole fold window are still there when its weight gradients are taken in
+  // one pass, or (two streams) the second stream can read node i's operands while the first
+  // produces those of node i+1; and the nodes of a window of equal sizes lie side by side, one
+  // long contraction.
+  bf16_t* aT = nullptr;      // a transposed
+  bf16_t* dzT = nullptr;     // dz transposed
 };
 
 class Mlp final : public Model {
@@ -36,7 +42,7 @@ class Mlp final : public Model {
   explicit Mlp(const vf_config& cfg) : cfg_(cfg) {
     bf16_ = cfg.dtype == VF_BF16;
     // as many copies of the weight-gradient operands as Ctx::copies() will ask for
-    copies_ = std::max(2, cfg.fold_window);
+    copies_ = std::max((cfg.flags & VF_FLAG_OVERLAP) ? 2 : 1, cfg.fold_window);
     const int nl = cfg.n_dims - 1;
     int64_t off = 0;
     layers_.resize(nl);
@@ -58,6 +64,8 @@ class Mlp final : public Model {
     for (Layer& L : layers_)
       if (L.has_bn) { L.s_off = bn_width_; bn_width_ += L.N; }
     ldb_ = round8(cfg.max_node_size);
+    ldw_ = ldb_ * copies_;
+    ordered_ = (cfg.flags & VF_FLAG_ORDERED_FOLD) != 0;
     // Scratch for GEMM outputs that arrive as partial slabs: the largest split * rows * ld
     // over the forward (N_l columns) and input-gradient (K_l columns) products.
     slab_elems_ = 0;
@@ -89,31 +97,32 @@ class Mlp final : public Model {
 
   int64_t num_params() const override { return P_; }
   bool supports_overlap() const override { return bf16_; }
-  int max_window() const override { return bf16_ ? copies_ : 1; }
+  int max_window() const override { return bf16_ ? kFoldMax : 1; }
 
   void request_buffers(Arena& a) override {
     const size_t mb = (size_t)cfg_.max_node_size;
     const size_t esz = bf16_ ? 2 : 4;
+    const int sets = (bf16_ && (cfg_.flags & VF_FLAG_OVERLAP)) ? 2 : 1;
     for (Layer& L : layers_) {
-      a.request(&L.z, mb * L.ld);
-      a.request(reinterpret_cast<char**>(&L.dz), mb * L.ld * esz);
-      if (L.hidden) {
-        a.request(&L.mean, (size_t)L.N);
-        a.request(&L.rstd, (size_t)L.N);
-        a.request(reinterpret_cast<char**>(&L.a), mb * L.ld * esz);
+      for (int q = 0; q < sets; ++q) {
+        a.request(&L.z[q], mb * L.ld);
+        if (q == 0 || !L.hidden) a.request(reinterpret_cast<char**>(&L.dz[q]), mb * L.ld * esz);
+        if (L.hidden) {
+          a.request(&L.mean[q], (size_t)L.N);
+          a.request(&L.rstd[q], (size_t)L.N);
+          a.request(reinterpret_cast<char**>(&L.a[q]), mb * L.ld * esz);
+        }
       }
       if (bf16_) {
         a.request(&L.wnat, (size_t)L.K * L.ldn);
         a.request(&L.wtr, (size_t)L.N * L.ldt);
-        for (int k = 0; k < copies_; ++k) {
-          a.request(&L.dzT[k], (size_t)L.N * ldb_);
-          if (L.hidden) a.request(&L.aT[k], (size_t)L.N * ldb_);
-        }
+        a.request(&L.dzT, (size_t)L.N * ldw_);
+        if (L.hidden) a.request(&L.aT, (size_t)L.N * ldw_);
       }
     }
-    if (bf16_)
-      for (int k = 0; k < copies_; ++k) a.request(&xT_[k], (size_t)cfg_.dims[0] * ldb_);
-    a.request(&slab_, (size_t)slab_elems_);
+    if (bf16_) a.request(&xT_, (size_t)cfg_.dims[0] * ldw_);
+    for (int q = 0; q < sets; ++q) a.request(&slab_[q], (size_t)slab_elems_);
+    sets_ = sets;
     if (bn_width_) a.request(&state_, (size_t)(2 * bn_width_));
   }
 
@@ -132,10 +141,16 @@ class Mlp final : public Model {
     return VF_OK;
   }
 
-  // Forward pass, loss, and the input-gradient chain (with the small-vector gradients the
-  // BatchNorm/ReLU backward kernels produce on the way).
   int run_node_main(Ctx& c, const StepArgs& s, int i, hipStream_t st) override {
-    const int p = c.slot(i);                 // which copy of the side part's operands
+    VF_TRY(run_node_fwd(c, s, i, st));
+    return run_node_bwd(c, s, i, st);
+  }
+
+  // Forward pass and loss of node i.
+  int run_node_fwd(Ctx& c, const StepArgs& s, int i, hipStream_t st) override {
+    const int64_t pc = cols(c, s, i);        // where node i's copy of the side part's operands starts
+    const int q = std::min(c.aset(i), sets_ - 1);
+    float* slab_buf = slab_[0];
     const int b = s.sizes[i];
     const int64_t row0 = s.off[i];
     const float w = s.w[i];
@@ -148,12 +163,12 @@ class Mlp final : public Model {
 
     for (int l = 0; l < nl; ++l) {
       Layer& L = layers_[l];
-      const void* in = l == 0 ? x : layers_[l - 1].a;
+      const void* in = l == 0 ? x : layers_[l - 1].a[q];
       const int64_t ldin = l == 0 ? D : layers_[l - 1].ld;
       const int split = split_for(b, L.N, L.K, L.ld);
       const int64_t slab = (int64_t)b * L.ld;
       Epilogue ep;
-      ep.C = slab_; ep.ldc = L.ld;
+      ep.C = slab_buf; ep.ldc = L.ld;
       if (L.has_bias) { ep.bias = P + L.b_off; ep.bias_round_bf16 = bf16_; }
       if (bf16_)
         VF_KS(c, st, "gemm_fwd", launch_gemm_bf16(static_cast<const bf16_t*>(in), ldin, L.wtr, L.ldt, b, L.N, L.K,
@@ -161,35 +176,48 @@ class Mlp final : public Model {
       else
         VF_KS(c, st, "gemm_fwd", launch_gemm_f32(static_cast<const float*>(in), ldin, 1, P + L.w_off, 1, L.N, b, L.N, L.K, split, slab, ep, st));
       if (L.hidden)
-        VF_KS(c, st, "bn_relu_fwd", launch_bn_relu_fwd(slab_, split, slab, L.ld, b, L.N,
+        VF_KS(c, st, "bn_relu_fwd", launch_bn_relu_fwd(slab_buf, split, slab, L.ld, b, L.N,
                                        L.has_bn ? P + L.g_off : nullptr, L.has_bn ? P + L.be_off : nullptr,
-                                       bf16_, cfg_.bn_eps, L.z, L.ld, L.a, L.ld, bf16_, L.aT[p], ldb_,
-                                       L.mean, L.rstd, L.has_bn ? state_ + L.s_off : nullptr,
+                                       bf16_, cfg_.bn_eps, L.z[q], L.ld, L.a[q], L.ld, bf16_, bf16_ ? L.aT + pc : nullptr, ldw_,
+                                       L.mean[q], L.rstd[q], L.has_bn ? state_ + L.s_off : nullptr,
                                        L.has_bn ? state_ + bn_width_ + L.s_off : nullptr, cfg_.bn_momentum, st));
       else
-        VF_KS(c, st, "softmax_xent", launch_softmax_xent(slab_, split, slab, L.ld, L.z, L.ld, y, b, L.N,
-                                                         c.rowloss, L.dz, L.ld, bf16_, L.dzT[p], ldb_, w, i,
+        VF_KS(c, st, "softmax_xent", launch_softmax_xent(slab_buf, split, slab, L.ld, L.z[q], L.ld, y, b, L.N,
+                                                         c.rowloss, L.dz[q], L.ld, bf16_, bf16_ ? L.dzT + pc : nullptr, ldw_, w, i,
                                                          c.node_loss, c.loss_total, st));
     }
+    return VF_OK;
+  }
 
+  // The input-gradient chain of node i (with the small-vector gradients the BatchNorm/ReLU
+  // backward kernels fold into the gradient buffer on the way).
+  int run_node_bwd(Ctx& c, const StepArgs& s, int i, hipStream_t st) override {
+    const int64_t pc = cols(c, s, i);
+    const int q = std::min(c.aset(i), sets_ - 1);
+    float* slab_buf = slab_[sets_ - 1];      // the backward stream's own scratch when there are two
+    const int b = s.sizes[i];
+    const float w = s.w[i];
+    const float* P = s.params;
+    const int nl = (int)layers_.size();
     for (int l = nl - 1; l >= 1; --l) {
       Layer& L = layers_[l];
       // input gradient da[l-1][b,K] = dz W^T, then through ReLU / BatchNorm of layer l-1
       Layer& Pv = layers_[l - 1];
+      const void* dz_in = L.hidden ? L.dz[0] : L.dz[q];
       const int split = split_for(b, L.K, L.N, Pv.ld);
       const int64_t slab = (int64_t)b * Pv.ld;
       Epilogue ed;
-      ed.C = slab_; ed.ldc = Pv.ld;
+      ed.C = slab_buf; ed.ldc = Pv.ld;
       if (bf16_)
-        VF_KS(c, st, "gemm_dgrad", launch_gemm_bf16(static_cast<const bf16_t*>(L.dz), L.ld, L.wnat, L.ldn, b, L.K, L.N,
+        VF_KS(c, st, "gemm_dgrad", launch_gemm_bf16(static_cast<const bf16_t*>(dz_in), L.ld, L.wnat, L.ldn, b, L.K, L.N,
                                                     split, slab, ed, st));
       else
-        VF_KS(c, st, "gemm_dgrad", launch_gemm_f32(static_cast<const float*>(L.dz), L.ld, 1, P + L.w_off, L.N, 1, b, L.K, L.N, split, slab, ed, st));
+        VF_KS(c, st, "gemm_dgrad", launch_gemm_f32(static_cast<const float*>(dz_in), L.ld, 1, P + L.w_off, L.N, 1, b, L.K, L.N, split, slab, ed, st));
       GradOut gg = Pv.has_bn ? c.gout(Pv.g_off, w, i) : GradOut{nullptr, 0.f, 0};
       GradOut gb = c.gout(Pv.has_bn ? Pv.be_off : Pv.b_off, w, i);
-      VF_KS(c, st, "bn_relu_bwd", launch_bn_relu_bwd(slab_, split, slab, Pv.ld, Pv.z, Pv.ld, b, Pv.N,
+      VF_KS(c, st, "bn_relu_bwd", launch_bn_relu_bwd(slab_buf, split, slab, Pv.ld, Pv.z[q], Pv.ld, b, Pv.N,
                                      Pv.has_bn ? P + Pv.g_off : nullptr, Pv.has_bn ? P + Pv.be_off : nullptr,
-                                     bf16_, Pv.mean, Pv.rstd, Pv.dz, Pv.ld, bf16_, bf16_ ? Pv.dzT[p] : nullptr, ldb_,
+                                     bf16_, Pv.mean[q], Pv.rstd[q], Pv.dz[0], Pv.ld, bf16_, bf16_ ? Pv.dzT + pc : nullptr, ldw_,
                                      gg, gb, st));
     }
     return VF_OK;
@@ -205,6 +233,10 @@ class Mlp final : public Model {
     bool fold = bf16_ && c.fused && count > 1;
     for (int i = i0; i < i0 + count && fold; ++i) fold = s.sizes[i] <= 128;
     for (const Layer& L : layers_) fold = fold && (L.N & 3) == 0 && ((L.w_off & 3) == 0);
+    // Nodes of one size have one weight w, and their operand copies lie side by side: the
+    // window's weighted sum is w times ONE product over all its rows.
+    const bool joined = side_by_side(c, s, i0, count);
+    if (joined) fold = false;
 
     if (fold) {   // the window's small launches batched, then one fold per layer
       NodeList xs{}, ds{};
@@ -212,43 +244,63 @@ class Mlp final : public Model {
       ds.overwrite = i0 == 0;
       const Layer& last = layers_[nl - 1];
       for (int j = 0; j < count; ++j) {
-        const int p = c.slot(i0 + j);
+        const int64_t pc = cols(c, s, i0 + j);
         xs.src[j] = static_cast<const bf16_t*>(s.x) + (int64_t)s.off[i0 + j] * D;
-        xs.dst[j] = xT_[p];
-        ds.src[j] = last.dzT[p];
+        xs.dst[j] = xT_ + pc;
+        ds.src[j] = last.dzT + pc;
         xs.rows[j] = ds.rows[j] = s.sizes[i0 + j];
         ds.w[j] = s.w[i0 + j];
       }
-      VF_KS(c, st, "transpose", launch_transpose_nodes(xs, D, ldb_, D, st));
-      VF_KS(c, st, "bias_grad", launch_rowsum_nodes(ds, ldb_, last.N, c.gbuf + last.b_off, st));
+      VF_KS(c, st, "transpose", launch_transpose_nodes(xs, D, ldw_, D, st));
+      VF_KS(c, st, "bias_grad", launch_rowsum_nodes(ds, ldw_, last.N, c.gbuf + last.b_off, st));
+    }
+    if (joined) {
+      // x of the whole window is one contiguous block of rows: one transpose
+      const int rows = count * s.sizes[i0];
+      const float w = s.w[i0];
+      const int64_t pc = cols(c, s, i0);
+      VF_KS(c, st, "transpose", launch_transpose_bf16(static_cast<const bf16_t*>(s.x) + (int64_t)s.off[i0] * D, D,
+                                                      xT_ + pc, ldw_, rows, D, st));
+      for (int l = nl - 1; l >= 0; --l) {
+        Layer& L = layers_[l];
+        GradOut go = c.gout(L.w_off, w, i0);
+        if (!L.hidden)
+          VF_KS(c, st, "bias_grad", launch_rowsum_bf16(L.dzT + pc, ldw_, L.N, rows, c.gout(L.b_off, w, i0), st));
+        Epilogue ep;
+        ep.C = go.dst; ep.ldc = L.N; ep.alpha = go.alpha;
+        if (go.accumulate) { ep.R = go.dst; ep.ldr = L.N; ep.beta = 1.f; }
+        VF_KS(c, st, "gemm_wgrad", launch_gemm_bf16((l == 0 ? xT_ : layers_[l - 1].aT) + pc, ldw_, L.dzT + pc, ldw_,
+                                                    L.K, L.N, rows, 1, 0, ep, st));
+      }
+      return VF_OK;
     }
     for (int i = i0; i < i0 + count && !fold; ++i) {
-      const int p = c.slot(i);
+      const int64_t pc = cols(c, s, i);
       const int b = s.sizes[i];
       const int64_t row0 = s.off[i];
       const float w = s.w[i];
       const void* x = bf16_ ? (const void*)(static_cast<const bf16_t*>(s.x) + row0 * D)
                             : (const void*)(static_cast<const float*>(s.x) + row0 * D);
       if (bf16_)
-        VF_KS(c, st, "transpose", launch_transpose_bf16(static_cast<const bf16_t*>(x), D, xT_[p], ldb_, b, D, st));
+        VF_KS(c, st, "transpose", launch_transpose_bf16(static_cast<const bf16_t*>(x), D, xT_ + pc, ldw_, b, D, st));
       for (int l = nl - 1; l >= 0; --l) {
         Layer& L = layers_[l];
-        const void* in = l == 0 ? x : layers_[l - 1].a;
+        const void* in = l == 0 ? x : layers_[l - 1].a[0];   // fp32 path: one tensor set
         const int64_t ldin = l == 0 ? D : layers_[l - 1].ld;
         if (!L.hidden) {   // last layer: bias gradient = sums over the node of dlogits
-          if (bf16_) VF_KS(c, st, "bias_grad", launch_rowsum_bf16(L.dzT[p], ldb_, L.N, b, c.gout(L.b_off, w, i), st));
-          else       VF_KS(c, st, "bias_grad", launch_colsum(L.dz, L.ld, 0, b, L.N, c.gout(L.b_off, w, i), st));
+          if (bf16_) VF_KS(c, st, "bias_grad", launch_rowsum_bf16(L.dzT + pc, ldw_, L.N, b, c.gout(L.b_off, w, i), st));
+          else       VF_KS(c, st, "bias_grad", launch_colsum(L.dz[0], L.ld, 0, b, L.N, c.gout(L.b_off, w, i), st));
         }
         GradOut go = c.gout(L.w_off, w, i);
         Epilogue ep;
         ep.C = go.dst; ep.ldc = L.N; ep.alpha = go.alpha;
         if (go.accumulate) { ep.R = go.dst; ep.ldr = L.N; ep.beta = 1.f; }
         if (bf16_) {
-          const bf16_t* inT = l == 0 ? xT_[p] : layers_[l - 1].aT[p];
-          VF_KS(c, st, "gemm_wgrad", launch_gemm_bf16(inT, ldb_, L.dzT[p], ldb_, L.K, L.N, b, 1, 0, ep, st));
+          const bf16_t* inT = (l == 0 ? xT_ : layers_[l - 1].aT) + pc;
+          VF_KS(c, st, "gemm_wgrad", launch_gemm_bf16(inT, ldw_, L.dzT + pc, ldw_, L.K, L.N, b, 1, 0, ep, st));
         } else {
           VF_KS(c, st, "gemm_wgrad", launch_gemm_f32(static_cast<const float*>(in), 1, ldin,
-                                                     static_cast<const float*>(L.dz), 1, L.ld, L.K, L.N, b, 1, 0, ep, st));
+                                                     static_cast<const float*>(L.dz[0]), 1, L.ld, L.K, L.N, b, 1, 0, ep, st));
         }
       }
       VF_TRY(c.fold(i, w, st));
@@ -260,27 +312,52 @@ class Mlp final : public Model {
         fa.count = count;
         fa.overwrite = i0 == 0;
         for (int j = 0; j < count; ++j) {
-          const int p = c.slot(i0 + j);
-          fa.A[j] = l == 0 ? xT_[p] : layers_[l - 1].aT[p];
-          fa.B[j] = L.dzT[p];
+          const int64_t pc = cols(c, s, i0 + j);
+          fa.A[j] = (l == 0 ? xT_ : layers_[l - 1].aT) + pc;
+          fa.B[j] = L.dzT + pc;
           fa.K[j] = s.sizes[i0 + j];
           fa.w[j] = s.w[i0 + j];
         }
-        VF_KS(c, st, "gemm_wgrad", launch_gemm_bf16_fold(fa, ldb_, L.K, L.N, c.gbuf + L.w_off, L.N, st));
+        VF_KS(c, st, "gemm_wgrad", launch_gemm_bf16_fold(fa, ldw_, L.K, L.N, c.gbuf + L.w_off, L.N, st));
       }
     }
     return VF_OK;
   }
 
  private:
+  // The window of node i (first node, node count).
+  static void window_of(const Ctx& c, const StepArgs& s, int i, int* i0, int* count) {
+    *i0 = i / c.window * c.window;
+    *count = std::min(c.window, s.V - *i0);
+  }
+  // True when the nodes i0 .. i0+count-1 form a window whose weighted gradient sum is taken as
+  // one product: several nodes of one size (hence one weight b_i/B) that keeps 16-byte alignment.
+  bool side_by_side(const Ctx& c, const StepArgs& s, int i0, int count) const {
+    if (!bf16_ || !c.fused || ordered_ || count < 2 || (s.sizes[i0] & 7)) return false;
+    for (int i = i0 + 1; i < i0 + count; ++i)
+      if (s.sizes[i] != s.sizes[i0]) return false;
+    return true;
+  }
+  // First column of node i's copy in the wide transposed operands: copies are ldb_ columns
+  // apart, or exactly the node size apart when the window's nodes are to lie side by side.
+  int64_t cols(const Ctx& c, const StepArgs& s, int i) const {
+    int i0, count;
+    window_of(c, s, i, &i0, &count);
+    const int64_t pitch = side_by_side(c, s, i0, count) ? s.sizes[i0] : ldb_;
+    return c.slot(i) * pitch;
+  }
+
   vf_config cfg_;
   bool bf16_ = false;
   int64_t P_ = 0;
   int64_t ldb_ = 0;
   std::vector<Layer> layers_;
   int copies_ = 2;
-  bf16_t* xT_[kFoldMax] = {};
-  float* slab_ = nullptr;
+  bf16_t* xT_ = nullptr;           // the batch rows of the nodes in flight, transposed [D, ldw_]
+  int64_t ldw_ = 0;                // leading dim of the wide transposed operands: copies_ * ldb_
+  bool ordered_ = false;           // VF_FLAG_ORDERED_FOLD
+  float* slab_[2] = {nullptr, nullptr};   // split-contraction scratch of the forward / backward stream
+  int sets_ = 1;
   int64_t slab_elems_ = 0;
   int64_t bn_width_ = 0;           // summed width of the BatchNorm layers
   float* state_ = nullptr;         // [2 * bn_width_]: moving means, then moving variances

@@ -208,6 +208,21 @@ def test_overlap_and_single_stream_agree_bitwise():
         assert base["loss"] == other["loss"], flags
 
 
+@pytest.mark.parametrize("window", [1, 2, 3, 8])
+@pytest.mark.parametrize("name", ["mlp_mid_bn_bf16", "mlp_mid_bf16", "mlp_big_node_bf16"])
+def test_two_streams_with_fold_windows_agree_bitwise(name, window):
+    """Forward passes on one stream, backward passes and weight gradients on the other, with and
+    without graph replay, three steps (buffer sets and operand copies are reused across steps)."""
+    wl, theta, x, y = _case(name)
+    base = run_gpu(wl, theta, x, y, flags=FUSED | NO_GRAPH, steps=3)
+    for flags in (FUSED | OVERLAP, FUSED | OVERLAP | NO_GRAPH):
+        other = run_gpu(wl, theta, x, y, flags=flags, steps=3, fold_window=window)
+        assert base["G"].tobytes() == other["G"].tobytes(), flags
+        assert base["theta"].tobytes() == other["theta"].tobytes(), flags
+        assert base["loss"] == other["loss"], flags
+        assert base["node_losses"].tobytes() == other["node_losses"].tobytes(), flags
+
+
 # ---- fold window: the weight gradients of several nodes folded in one pass over the buffer -------
 
 @pytest.mark.parametrize("window", [2, 3, 4, 8])
@@ -222,6 +237,36 @@ def test_fold_window_gives_the_node_by_node_result_bitwise(name, flags, window):
     assert one["G"].tobytes() == win["G"].tobytes()
     assert one["theta"].tobytes() == win["theta"].tobytes()
     assert one["loss"] == win["loss"]
+
+
+ORDERED = 8
+
+
+@pytest.mark.parametrize("window", [2, 4, 8])
+@pytest.mark.parametrize("name", ["mlp_mid_bn_bf16", "mlp_mid_bf16"])
+def test_window_of_equal_nodes_as_one_product(name, window):
+    """Nodes of one size share one weight b_i/B, and a window of them takes its weight gradients
+    as one product over all its rows (Section 5.2: the same weighted sum).  Against the oracle;
+    against the node-by-node chain to fp32 rounding; the ordered-fold flag restores that chain
+    bit for bit; two streams change nothing.  Six nodes: windows of 4 and 8 are ragged."""
+    wl, theta, x, y = _case(name)
+    b = 8 * max(1, wl.batch // 6 // 8)
+    sizes = [b] * 6
+    xs, ys = x[:6 * b], y[:6 * b]
+    one = run_gpu(wl, theta, xs, ys, node_sizes=sizes, flags=FUSED, steps=2)
+    joined = run_gpu(wl, theta, xs, ys, node_sizes=sizes, flags=FUSED, steps=2, fold_window=window)
+    ordered = run_gpu(wl, theta, xs, ys, node_sizes=sizes, flags=FUSED | ORDERED, steps=2, fold_window=window)
+    assert one["G"].tobytes() == ordered["G"].tobytes()
+    assert one["theta"].tobytes() == ordered["theta"].tobytes()
+    scale = np.abs(one["G"]).max()
+    assert np.abs(joined["G"] - one["G"]).max() <= 1e-5 * scale
+    assert joined["loss"] == one["loss"]
+    ref = oracle_steps(wl, theta, xs, ys, node_sizes=sizes, steps=2)
+    check_against_oracle(wl, joined, ref, tol=2 * TOL[wl.dtype])
+    for flags in (FUSED | OVERLAP, FUSED | OVERLAP | NO_GRAPH, FUSED | NO_GRAPH):
+        other = run_gpu(wl, theta, xs, ys, node_sizes=sizes, flags=flags, steps=2, fold_window=window)
+        assert joined["G"].tobytes() == other["G"].tobytes(), flags
+        assert joined["theta"].tobytes() == other["theta"].tobytes(), flags
 
 
 def test_fold_window_with_long_nodes_and_other_modes_falls_back_to_node_by_node():

@@ -30,7 +30,7 @@ def _setup(wl, jitter=0.1):
 
 
 @pytest.mark.parametrize("name", ["mlp_small_bn_f32", "mlp_mid_bn_bf16", "mlp_big_node_bf16"])
-@pytest.mark.parametrize("flags", [0, NO_GRAPH, FUSED])
+@pytest.mark.parametrize("flags", [0, NO_GRAPH, FUSED, FUSED | 4])
 def test_moving_statistics_match_the_oracle_after_two_steps(name, flags):
     import paper_2009_09523_amd as vf
     wl = I.workload(name)
