@@ -125,7 +125,37 @@ __global__ __launch_bounds__(256) void loss_reduce_kernel(const float* __restric
   }
 }
 
+// The same bookkeeping for a run of nodes in one launch: node j's rows start at off[j] of
+// `rowloss`; sums and the chain over the nodes are those of one launch per node, node by node.
+__global__ __launch_bounds__(256) void loss_reduce_nodes_kernel(const float* __restrict__ rowloss, LossNodes ln,
+                                                                float* __restrict__ node_loss,
+                                                                float* __restrict__ total) {
+  __shared__ float red[4];
+  float acc = ln.first == 0 ? 0.f : *total;
+  for (int j = 0; j < ln.count; ++j) {
+    const int R = ln.rows[j];
+    const float* __restrict__ p = rowloss + ln.off[j];
+    float s = 0.f;
+    for (int r = threadIdx.x; r < R; r += 256) s += p[r];
+    s = block_reduce(s, false, red);
+    const float L = s / (float)R;
+    if (threadIdx.x == 0) node_loss[ln.first + j] = L;
+    acc = fmaf(ln.w[j], L, acc);
+  }
+  if (threadIdx.x == 0) *total = acc;
+}
+
 }  // namespace
+
+int launch_loss_reduce_nodes(const float* rowloss, const LossNodes& ln, float* node_loss, float* total,
+                             hipStream_t s) {
+  if (ln.count < 1 || ln.count > kLossNodes || ln.first < 0 || !rowloss || !node_loss || !total) return VF_EINVAL;
+  for (int j = 0; j < ln.count; ++j)
+    if (ln.rows[j] < 1 || ln.off[j] < 0) return VF_EINVAL;
+  loss_reduce_nodes_kernel<<<1, 256, 0, s>>>(rowloss, ln, node_loss, total);
+  VF_LAUNCH_CHECK();
+  return VF_OK;
+}
 
 int launch_softmax_xent(const float* zp, int nsplit, int64_t slab, int64_t ldzp, float* z, int64_t ldz,
                         const int32_t* labels, int R, int C, float* rowloss, void* dz, int64_t lddz,

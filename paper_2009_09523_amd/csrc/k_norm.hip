@@ -79,6 +79,11 @@ __global__ __launch_bounds__(256) void bn_relu_fwd_kernel(const float* __restric
   const bool live = c < C;
   const bool bn = gamma != nullptr;
   float mean = 0.f, rstd = 1.f, g = 1.f, b = 0.f;
+  float rm = 0.f, rv = 0.f;
+  if (bn && live) {   // issued with the first row loads, needed only after the reductions
+    g = gamma[c]; b = beta[c];
+    if (run_mean && ty == 0) { rm = run_mean[c]; rv = run_var[c]; }
+  }
   float zr[RPT];
   // pass 1: reduce the slabs into z, column sums
   float s = 0.f;
@@ -120,13 +125,12 @@ __global__ __launch_bounds__(256) void bn_relu_fwd_kernel(const float* __restric
     const float var = col_reduce(q, red, tx, ty) / (float)R;
     rstd = 1.0f / sqrtf(var + eps);
     if (live) {
-      g = gamma[c]; b = beta[c];
       if (round_params) { g = round_bf16(g); b = round_bf16(b); }
       if (ty == 0) {
         mean_out[c] = mean; rstd_out[c] = rstd;
         if (run_mean) {   // moving statistics of this device: one blend per pass (Section 4.1)
-          run_mean[c] = fmaf(run_mix, mean - run_mean[c], run_mean[c]);
-          run_var[c] = fmaf(run_mix, var - run_var[c], run_var[c]);
+          run_mean[c] = fmaf(run_mix, mean - rm, rm);
+          run_var[c] = fmaf(run_mix, var - rv, rv);
         }
       }
     }

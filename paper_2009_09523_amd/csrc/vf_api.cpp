@@ -79,6 +79,9 @@ void release_streams(Ctx& c) {
                        &c.side_done[0], &c.side_done[1], &c.prep_done};
   for (hipEvent_t* e : evs)
     if (*e) { (void)hipEventDestroy(*e); *e = nullptr; }
+  for (hipEvent_t e : c.range_done)
+    if (e) (void)hipEventDestroy(e);
+  c.range_done.clear();
   if (c.side) { (void)hipStreamDestroy(c.side); c.side = nullptr; }
 }
 
@@ -233,7 +236,7 @@ int enqueue_nodes(Ctx& c, const StepArgs& a, bool use_graph) {
     VF_HIP(hipGraphLaunch(c.gs().graphs[0], c.stream));
     return VF_OK;
   }
-  VF_TRY(run_part(c, a, use_graph, 0, 0, c.stream));
+  if (!ov || use_graph) VF_TRY(run_part(c, a, use_graph, 0, 0, c.stream));
   if (!ov) {
     for (int i0 = 0; i0 < a.V; i0 += c.window) {
       const int count = std::min(c.window, a.V - i0);
@@ -242,8 +245,12 @@ int enqueue_nodes(Ctx& c, const StepArgs& a, bool use_graph) {
     }
     return VF_OK;
   }
+  // prep_done: the previous step's update is complete (and, replaying graphs, this step's
+  // preparation too)
   VF_HIP(hipEventRecord(c.prep_done, c.stream));
   VF_HIP(hipStreamWaitEvent(c.side, c.prep_done, 0));
+  if (!use_graph) VF_TRY(c.model->prepare_split(c, a.params, c.stream, c.side));
+  c.marking = !use_graph && !c.ranges.empty();
   const int nwin = (a.V + c.window - 1) / c.window;
   const int reach = std::max(1, std::min(2, c.copies() / c.window));
   for (int w = 0; w < nwin; ++w) {
@@ -266,22 +273,37 @@ int enqueue_nodes(Ctx& c, const StepArgs& a, bool use_graph) {
     VF_TRY(run_part(c, a, use_graph, 3, w, c.side));
     VF_HIP(hipEventRecord(c.side_done[w & 1], c.side));
   }
-  // join: the last side part is the last thing on the second stream
-  VF_HIP(hipStreamWaitEvent(c.stream, c.side_done[(nwin - 1) & 1], 0));
+  // join: the last side part is the last thing on the second stream (when the update goes
+  // stretch by stretch it joins after its last launch)
+  c.last_side = c.side_done[(nwin - 1) & 1];
+  if (!c.marking) VF_HIP(hipStreamWaitEvent(c.stream, c.last_side, 0));
   return VF_OK;
 }
 
-int enqueue_update(Ctx& c, float* params) {
+int update_stretch(Ctx& c, float* params, int64_t off, int64_t n) {
   const vf_config& f = c.cfg;
   if (f.optimizer == VF_SGDM) {
-    VF_K(c, "optimizer", launch_sgdm(params, c.opt0, c.gbuf, f.lr, f.momentum, c.P, c.stream));
+    VF_K(c, "optimizer", launch_sgdm(params + off, c.opt0 + off, c.gbuf + off, f.lr, f.momentum, n, c.stream));
     return VF_OK;
   }
   const double t = (double)(c.steps + 1);
   const float inv_c1 = (float)(1.0 / (1.0 - std::pow((double)f.beta1, t)));
   const float inv_c2 = (float)(1.0 / (1.0 - std::pow((double)f.beta2, t)));
-  VF_K(c, "optimizer", launch_adam(params, c.opt0, c.opt1, c.gbuf, f.lr, f.beta1, f.beta2, f.adam_eps,
-                                   inv_c1, inv_c2, c.P, c.stream));
+  VF_K(c, "optimizer", launch_adam(params + off, c.opt0 + off, c.opt1 + off, c.gbuf + off, f.lr, f.beta1, f.beta2,
+                                   f.adam_eps, inv_c1, inv_c2, n, c.stream));
+  return VF_OK;
+}
+
+// The one update of a step (Section 3.2 step 5): elementwise, so it may go stretch by stretch,
+// each as soon as its gradient is complete.
+int enqueue_update(Ctx& c, float* params) {
+  if (!c.marking) return update_stretch(c, params, 0, c.P);
+  c.marking = false;
+  for (size_t k = 0; k < c.ranges.size(); ++k) {
+    VF_HIP(hipStreamWaitEvent(c.stream, c.range_done[k], 0));
+    VF_TRY(update_stretch(c, params, c.ranges[k].off, c.ranges[k].n));
+  }
+  VF_HIP(hipStreamWaitEvent(c.stream, c.last_side, 0));
   return VF_OK;
 }
 
@@ -292,6 +314,12 @@ int copy_out(Ctx& c, const float* src, float* out, size_t count) {
 }
 
 }  // namespace
+
+int Ctx::mark_range(int k, hipStream_t st) {
+  if (!marking || k < 0 || k >= (int)range_done.size()) return VF_OK;
+  VF_HIP(hipEventRecord(range_done[k], st));
+  return VF_OK;
+}
 
 int Ctx::fold(int node, float w, hipStream_t st) {
   if (fused) return VF_OK;
@@ -350,6 +378,10 @@ int vf_init(const vf_config* cfg, vf_ctx** out) {
                          &c.side_done[0], &c.side_done[1], &c.prep_done};
     for (hipEvent_t* ev : evs)
       if (e == hipSuccess) e = hipEventCreateWithFlags(ev, hipEventDisableTiming);
+    c.model->update_ranges(&c.ranges);
+    c.range_done.assign(c.ranges.size(), nullptr);
+    for (hipEvent_t& ev : c.range_done)
+      if (e == hipSuccess) e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
     if (e != hipSuccess) {
       set_last_error("side stream set-up", e, __FILE__, __LINE__);
       release_streams(c);
@@ -363,8 +395,9 @@ int vf_init(const vf_config* cfg, vf_ctx** out) {
   if (!c.fused) arena.request(&c.gstage, (size_t)c.P);
   arena.request(&c.opt0, (size_t)c.P);
   if (cfg->optimizer == VF_ADAM) arena.request(&c.opt1, (size_t)c.P);
-  size_t loss_rows = (size_t)cfg->max_node_size;
-  if (cfg->model_kind == VF_ENCODER) loss_rows *= (size_t)cfg->n_masked;
+  // per-row losses: of the whole batch (MLP: reduced once, after the last node's forward pass)
+  size_t loss_rows = (size_t)cfg->max_batch;
+  if (cfg->model_kind == VF_ENCODER) loss_rows = (size_t)cfg->max_node_size * (size_t)cfg->n_masked;
   arena.request(&c.rowloss, loss_rows);
   arena.request(&c.node_loss, (size_t)cfg->max_nodes);
   arena.request(&c.loss_total, 1);

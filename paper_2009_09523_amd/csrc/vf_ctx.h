@@ -41,6 +41,9 @@ struct StepArgs {
 
 struct Ctx;
 
+// A stretch of the flat parameter vector whose gradient is complete before the rest is.
+struct UpdateRange { int64_t off = 0, n = 0; };
+
 // A model = parameter layout + buffers + the launch sequence of one virtual node.
 class Model {
  public:
@@ -68,7 +71,18 @@ class Model {
   virtual int run_node_fwd(Ctx& c, const StepArgs& a, int i, hipStream_t st) { return run_node_main(c, a, i, st); }
   virtual int run_node_bwd(Ctx&, const StepArgs&, int, hipStream_t) { return VF_OK; }
   virtual int run_nodes_side(Ctx& c, const StepArgs& a, int i0, int count, hipStream_t st) = 0;
+  // Two streams, launches made one by one: the same preparation with only what the first
+  // launch of node 0's forward part needs on `first`, the rest on `second` (the model then
+  // makes node 0's forward part wait for each piece where it first reads it).
+  virtual int prepare_split(Ctx& c, const float* params, hipStream_t first, hipStream_t second) {
+    (void)second;
+    return prepare(c, params, first);
+  }
   virtual bool supports_overlap() const { return false; }
+  // Stretches of the parameter vector (16-byte aligned starts, together all of it) in the order
+  // in which the last side part of a step completes their gradients; the model calls
+  // Ctx::mark_range(k) at that point.  Empty: the gradient is complete when the side part ends.
+  virtual void update_ranges(std::vector<UpdateRange>* out) const { out->clear(); }
   // Largest fold window the side part can take (it must keep that many nodes' operands).
   virtual int max_window() const { return 1; }
   // State that the passes themselves carry from step to step on this device (BatchNorm moving
@@ -178,6 +192,15 @@ struct Ctx {
   // Staged mode: fold node i's staging vector into the gradient buffer on stream `st`
   // (Section 3.2 step 3 with the weight of Section 5.2).  No-op in fused mode.
   int fold(int node, float w, hipStream_t st);
+
+  // Two streams, launches made one by one: the update of a stretch of the parameters
+  // (Section 3.2 step 5 is elementwise) starts on the first stream as soon as the second
+  // stream has completed that stretch's gradient, beside the weight gradients still to come.
+  std::vector<UpdateRange> ranges;
+  std::vector<hipEvent_t> range_done;
+  bool marking = false;          // this step's side part records range_done
+  hipEvent_t last_side = nullptr;   // the event that ends the second stream's work of this step
+  int mark_range(int k, hipStream_t st);
 };
 
 // Launch `call` (an expression returning a status) under the tag `name`; the launch goes to

@@ -171,6 +171,16 @@ int launch_softmax_xent(const float* zp, int nsplit, int64_t slab, int64_t ldzp,
                         int dz_is_bf16, bf16_t* dzT, int64_t ldt, float w, int node, float* node_loss,
                         float* total, hipStream_t s);
 // node_loss[i] = (1/R) sum_r rowloss[r];  total = (i == 0 ? 0 : total) + w * node_loss[i]
+// The same for nodes first .. first+count-1 in one launch (rows of node j at rowloss + off[j]).
+constexpr int kLossNodes = 32;
+struct LossNodes {
+  int32_t off[kLossNodes];
+  int32_t rows[kLossNodes];
+  float w[kLossNodes];
+  int32_t first, count;
+};
+int launch_loss_reduce_nodes(const float* rowloss, const LossNodes& ln, float* node_loss, float* total,
+                             hipStream_t s);
 int launch_loss_reduce(const float* rowloss, int R, float w, int node, float* node_loss,
                        float* total, hipStream_t s);
 

@@ -99,6 +99,24 @@ class Mlp final : public Model {
   bool supports_overlap() const override { return bf16_; }
   int max_window() const override { return bf16_ ? kFoldMax : 1; }
 
+  // The side part finishes the layers from the last to the first; a layer's stretch of the
+  // parameter vector (its weights and the small vectors after them) can be updated then.  A
+  // layer whose stretch does not start on a 16-byte boundary goes with the layer before it.
+  void update_ranges(std::vector<UpdateRange>* out) const override {
+    out->clear();
+    range_layer_.clear();
+    int64_t end = P_;
+    for (int l = (int)layers_.size() - 1; l >= 0; --l) {
+      const int64_t start = l == 0 ? 0 : layers_[l].w_off;
+      if (start & 3) continue;
+      UpdateRange r;
+      r.off = start; r.n = end - start;
+      out->push_back(r);
+      range_layer_.push_back(l);
+      end = start;
+    }
+  }
+
   void request_buffers(Arena& a) override {
     const size_t mb = (size_t)cfg_.max_node_size;
     const size_t esz = bf16_ ? 2 : 4;
@@ -141,6 +159,29 @@ class Mlp final : public Model {
     return VF_OK;
   }
 
+  // The first layer's copies on `first`; the others on `second`, each followed by an event that
+  // node 0's forward part waits for before that layer's product.  (The backward parts run on
+  // `second`, behind the copies.)
+  int prepare_split(Ctx& c, const float* params, hipStream_t first, hipStream_t second) override {
+    if (!bf16_) return VF_OK;
+    const int nl = (int)layers_.size();
+    for (int l = 0; l < nl; ++l) {
+      Layer& L = layers_[l];
+      hipStream_t st = l == 0 ? first : second;
+      VF_KS(c, st, "cast_weight", launch_cast_weight(params + L.w_off, L.K, L.N, L.wnat, L.ldn, L.wtr, L.ldt, st));
+      if (l == 0) continue;
+      if (!cast_done_[l]) VF_HIP(hipEventCreateWithFlags(&cast_done_[l], hipEventDisableTiming));
+      VF_HIP(hipEventRecord(cast_done_[l], st));
+    }
+    wait_casts_ = true;
+    return VF_OK;
+  }
+
+  ~Mlp() override {
+    for (hipEvent_t e : cast_done_)
+      if (e) (void)hipEventDestroy(e);
+  }
+
   int run_node_main(Ctx& c, const StepArgs& s, int i, hipStream_t st) override {
     VF_TRY(run_node_fwd(c, s, i, st));
     return run_node_bwd(c, s, i, st);
@@ -167,6 +208,7 @@ class Mlp final : public Model {
       const int64_t ldin = l == 0 ? D : layers_[l - 1].ld;
       const int split = split_for(b, L.N, L.K, L.ld);
       const int64_t slab = (int64_t)b * L.ld;
+      if (wait_casts_ && l >= 1) VF_HIP(hipStreamWaitEvent(st, cast_done_[l], 0));
       Epilogue ep;
       ep.C = slab_buf; ep.ldc = L.ld;
       if (L.has_bias) { ep.bias = P + L.b_off; ep.bias_round_bf16 = bf16_; }
@@ -183,8 +225,22 @@ class Mlp final : public Model {
                                        L.has_bn ? state_ + bn_width_ + L.s_off : nullptr, cfg_.bn_momentum, st));
       else
         VF_KS(c, st, "softmax_xent", launch_softmax_xent(slab_buf, split, slab, L.ld, L.z[q], L.ld, y, b, L.N,
-                                                         c.rowloss, L.dz[q], L.ld, bf16_, bf16_ ? L.dzT + pc : nullptr, ldw_, w, i,
-                                                         c.node_loss, c.loss_total, st));
+                                                         c.rowloss + row0, L.dz[q], L.ld, bf16_, bf16_ ? L.dzT + pc : nullptr, ldw_, w, i,
+                                                         nullptr, nullptr, st));
+    }
+    wait_casts_ = false;
+    // loss bookkeeping of the whole step after the last node's rows are in: node losses and
+    // their weighted sum (Section 5.2), in node order
+    if (i == s.V - 1) {
+      for (int first = 0; first < s.V; first += kLossNodes) {
+        LossNodes ln{};
+        ln.first = first;
+        ln.count = std::min(kLossNodes, s.V - first);
+        for (int j = 0; j < ln.count; ++j) {
+          ln.off[j] = s.off[first + j]; ln.rows[j] = s.sizes[first + j]; ln.w[j] = s.w[first + j];
+        }
+        VF_KS(c, st, "loss_reduce", launch_loss_reduce_nodes(c.rowloss, ln, c.node_loss, c.loss_total, st));
+      }
     }
     return VF_OK;
   }
@@ -237,6 +293,14 @@ class Mlp final : public Model {
     // window's weighted sum is w times ONE product over all its rows.
     const bool joined = side_by_side(c, s, i0, count);
     if (joined) fold = false;
+    // after the step's last window layer l's gradient is final
+    const bool last_window = i0 + count == s.V;
+    auto layer_done = [&](int l) -> int {
+      if (!last_window) return VF_OK;
+      for (size_t k = 0; k < range_layer_.size(); ++k)
+        if (range_layer_[k] == l) return c.mark_range((int)k, st);
+      return VF_OK;
+    };
 
     if (fold) {   // the window's small launches batched, then one fold per layer
       NodeList xs{}, ds{};
@@ -271,6 +335,7 @@ class Mlp final : public Model {
         if (go.accumulate) { ep.R = go.dst; ep.ldr = L.N; ep.beta = 1.f; }
         VF_KS(c, st, "gemm_wgrad", launch_gemm_bf16((l == 0 ? xT_ : layers_[l - 1].aT) + pc, ldw_, L.dzT + pc, ldw_,
                                                     L.K, L.N, rows, 1, 0, ep, st));
+        VF_TRY(layer_done(l));
       }
       return VF_OK;
     }
@@ -302,8 +367,11 @@ class Mlp final : public Model {
           VF_KS(c, st, "gemm_wgrad", launch_gemm_f32(static_cast<const float*>(in), 1, ldin,
                                                      static_cast<const float*>(L.dz[0]), 1, L.ld, L.K, L.N, b, 1, 0, ep, st));
         }
+        if (c.fused && i == i0 + count - 1) VF_TRY(layer_done(l));
       }
       VF_TRY(c.fold(i, w, st));
+      if (!c.fused && i == i0 + count - 1)
+        for (int l = nl - 1; l >= 0; --l) VF_TRY(layer_done(l));
     }
     if (fold) {
       for (int l = nl - 1; l >= 0; --l) {
@@ -319,6 +387,7 @@ class Mlp final : public Model {
           fa.w[j] = s.w[i0 + j];
         }
         VF_KS(c, st, "gemm_wgrad", launch_gemm_bf16_fold(fa, ldw_, L.K, L.N, c.gbuf + L.w_off, L.N, st));
+        VF_TRY(layer_done(l));
       }
     }
     return VF_OK;
@@ -356,6 +425,9 @@ class Mlp final : public Model {
   bf16_t* xT_ = nullptr;           // the batch rows of the nodes in flight, transposed [D, ldw_]
   int64_t ldw_ = 0;                // leading dim of the wide transposed operands: copies_ * ldb_
   bool ordered_ = false;           // VF_FLAG_ORDERED_FOLD
+  hipEvent_t cast_done_[VF_MAX_DIMS] = {};   // prepare_split: layer l's bf16 weight copies are written
+  bool wait_casts_ = false;                  // the next forward part waits for them
+  mutable std::vector<int> range_layer_;   // update_ranges: the layer that completes stretch k
   float* slab_[2] = {nullptr, nullptr};   // split-contraction scratch of the forward / backward stream
   int sets_ = 1;
   int64_t slab_elems_ = 0;
