@@ -2,6 +2,7 @@
 """Benchmark of the virtual-node training step on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2] [--accumulate staged|fused]
+                    [--streams 2|1] [--launch eager|graph] [--fold-window 8]
 
 A "step" is one pass of the whole hot path over one synthetic batch already resident in HBM:
 partition, V sequential node passes (forward, loss, backward), the size-weighted fold of each
@@ -109,7 +110,8 @@ def measured_traffic(workload, accumulate, tag):
 
 def cpu_baseline(wl, theta, x, y, budget_s=12.0):
     """The oracle as it stands, timed node by node on the host cores until about
-    `budget_s` seconds of work are done (at least one node)."""
+    `budget_s` seconds of work are done (at least one node; the nodes again from the first when
+    one pass over them is quicker than that)."""
     import numpy as np
     import oracle as O
     try:
@@ -120,17 +122,23 @@ def cpu_baseline(wl, theta, x, y, budget_s=12.0):
     t0 = time.perf_counter()
     done = 0
     samples = 0
-    for i in range(wl.n_nodes):
-        O.oracle_step(wl, theta, x, y, nodes=[i])
-        done += 1
-        samples += wl.node_sizes[i]
-        if time.perf_counter() - t0 >= budget_s:
-            break
+    while time.perf_counter() - t0 < budget_s:          # whole passes over the nodes, again if they are quick
+        for i in range(wl.n_nodes):
+            O.oracle_step(wl, theta, x, y, nodes=[i])
+            done += 1
+            samples += wl.node_sizes[i]
+            if time.perf_counter() - t0 >= budget_s:
+                break
     dt = time.perf_counter() - t0
     return {"value": samples / dt, "unit": "samples/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"{done} of {wl.n_nodes} virtual nodes ({samples} samples) of workload {wl.name}, "
-                      f"each with the combine and one optimizer update, {dt:.1f} s",
+            "sample": f"{done} virtual-node passes ({samples} samples; the workload has {wl.n_nodes} nodes) of "
+                      f"workload {wl.name}, each with the combine and one optimizer update, {dt:.1f} s",
             "seconds": dt}
+
+
+def mode_flags(vf, args):
+    return (vf.VF_FLAG_NO_GRAPH if args.launch == "eager" else 0) | \
+           (vf.VF_FLAG_OVERLAP if args.streams == 2 else 0)
 
 
 def time_steps(vf, torch, wl, theta, x, y, flags, steps, warmup, max_node_size=None, fold_window=1):
@@ -171,7 +179,7 @@ def vsweep(args):
     import paper_2009_09523_amd as vf
     import vf_inputs as I
     base = I.workload(args.workload)
-    flags = vf.VF_FLAG_FUSED_ACCUMULATE if args.accumulate == "fused" else 0
+    flags = (vf.VF_FLAG_FUSED_ACCUMULATE if args.accumulate == "fused" else 0) | mode_flags(vf, args)
     b = max(base.node_sizes)
     grow, fits = [], []
     for V in (1, 2, 4, 8, 16, 32):
@@ -214,7 +222,7 @@ def het_profile(args):
     import paper_2009_09523_amd as vf
     import vf_inputs as I
     base = I.workload(args.workload)
-    flags = vf.VF_FLAG_FUSED_ACCUMULATE if args.accumulate == "fused" else 0
+    flags = (vf.VF_FLAG_FUSED_ACCUMULATE if args.accumulate == "fused" else 0) | mode_flags(vf, args)
     V = 4                                   # several nodes per step so that the update is amortised
     sizes = [16, 24, 32, 48, 64, 96, 128, 192, 256]
     curve = []
@@ -251,13 +259,17 @@ def main():
                     help="fused (default): weight-gradient epilogues fold w_i*g_i into the gradient buffer; "
                          "staged: per-node staging vector + the accumulate kernel")
     ap.add_argument("--no-alt", action="store_true", help="skip the timing of the other accumulate mode")
-    ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--streams", type=int, choices=[1, 2], default=2,
+                    help="2 (default): the forward passes on one stream, the backward passes and weight "
+                         "gradients on a second one, so that node i+1's forward pass runs beside node i's "
+                         "backward pass (bf16 MLP; other models run on one stream); 1: everything in line")
+    ap.add_argument("--launch", choices=["eager", "graph"], default="eager",
+                    help="eager (default): kernels launched one by one; graph: the captured launch "
+                         "sequence replayed as HIP graphs")
     ap.add_argument("--fold-window", type=int, default=8,
                     help="fused fold: the weight gradients of this many consecutive nodes (1..8) are folded "
-                         "into the gradient buffer in one pass (bitwise the same result as node by node; the "
-                         "workspace keeps that many nodes' transposed bf16 operands)")
-    ap.add_argument("--overlap", action="store_true",
-                    help="weight gradients on a second stream beside the next node's passes")
+                         "into the gradient buffer in one pass (nodes of one size: one product over the "
+                         "window's rows; the workspace keeps that many nodes' transposed bf16 operands)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-profile", action="store_true")
     ap.add_argument("--vsweep", action="store_true",
@@ -292,9 +304,8 @@ def main():
     theta = I.make_params(wl)
     x, y = I.make_batch(wl)
     stream = torch.cuda.Stream()
-    flags = (vf.VF_FLAG_FUSED_ACCUMULATE if args.accumulate == "fused" else 0) | \
-            (vf.VF_FLAG_NO_GRAPH if args.no_graph else 0) | \
-            (vf.VF_FLAG_OVERLAP if args.overlap else 0)
+    mode = mode_flags(vf, args)
+    flags = (vf.VF_FLAG_FUSED_ACCUMULATE if args.accumulate == "fused" else 0) | mode
     eng = vf.VirtualNodeStep(config_from_workload(wl, flags=flags, stream=stream, fold_window=args.fold_window))
     P = eng.num_params
     window = eng.fold_window                      # the window in effect (1 where no windowed path exists)
@@ -344,7 +355,7 @@ def main():
                    "node_sizes": sizes if len(set(sizes)) > 1 else f"{wl.n_nodes}x{sizes[0]}",
                    "optimizer": wl.optimizer, "params": P, "accumulate": args.accumulate,
                    "fold_window": window, "workspace_bytes": eng.workspace_bytes,
-                   "graph": not args.no_graph, "overlap": bool(args.overlap)},
+                   "streams": eng.streams, "launch": args.launch},
         "loss": loss,
     }
 
@@ -357,11 +368,25 @@ def main():
                          "gemm_tflops_achieved": total_flops / (ms_per_step * 1e-3) / 1e12}
 
     if not args.no_kernel_profile:
-        # same steps again, launched one by one with an event pair around every kernel
-        eng.profile_start()
+        # The same steps again on ONE stream, launched one by one with an event pair around every
+        # kernel: each kernel's duration with nothing running beside it (with two streams a
+        # kernel's own time also holds what it loses to its neighbour, which says nothing about
+        # the kernel).
+        engp, pp = eng, params
+        if eng.streams == 2:
+            engp = vf.VirtualNodeStep(config_from_workload(wl, flags=flags & ~vf.VF_FLAG_OVERLAP, stream=stream,
+                                                           fold_window=args.fold_window))
+            pp = params.clone()
+            for _ in range(args.warmup):
+                engp.step(pp, xt, yt, sizes)
+        engp.profile_start()
         for _ in range(args.steps):
-            eng.step(params, xt, yt, sizes)
-        prof = eng.profile_stop()
+            engp.step(pp, xt, yt, sizes)
+        prof = engp.profile_stop()
+        if engp is not eng:
+            engp.close()
+            del pp
+        out["kernels_mode"] = "one stream, launched one by one, an event pair around every kernel"
         tot = sum(v["total_ms"] for v in prof.values())
         kernels = {k: {"launches_per_step": v["launches"] / args.steps,
                        "avg_launch_ms": v["total_ms"] / v["launches"],
@@ -382,11 +407,17 @@ def main():
         out["alt_window_1"] = {"fold_window": 1, "ms_per_step": ms1, "value": wl.batch / (ms1 * 1e-3),
                                "workspace_bytes": ws1}
 
+    if not args.no_alt and (args.streams != 1 or args.launch != "graph"):
+        # one stream, the whole step replayed as one HIP graph, for comparison (never `value`)
+        gflags = flags & ~(vf.VF_FLAG_NO_GRAPH | vf.VF_FLAG_OVERLAP)
+        msg, wsg = time_steps(vf, torch, wl, theta, x, y, gflags, args.steps, args.warmup, fold_window=args.fold_window)
+        out["alt_one_stream_graph"] = {"streams": 1, "launch": "graph", "ms_per_step": msg,
+                                       "value": wl.batch / (msg * 1e-3), "workspace_bytes": wsg}
+
     if not args.no_alt:
         # the other accumulate mode, same workload, for comparison (never `value`)
         alt_mode = "staged" if args.accumulate == "fused" else "fused"
-        aflags = (vf.VF_FLAG_FUSED_ACCUMULATE if alt_mode == "fused" else 0) | \
-                 (vf.VF_FLAG_NO_GRAPH if args.no_graph else 0)
+        aflags = (vf.VF_FLAG_FUSED_ACCUMULATE if alt_mode == "fused" else 0) | mode
         eng2 = vf.VirtualNodeStep(config_from_workload(wl, flags=aflags, stream=stream))
         p2 = torch.from_numpy(theta).cuda()
         for _ in range(args.warmup):

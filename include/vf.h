@@ -193,6 +193,9 @@ int vf_profile_stop(vf_ctx* ctx, char* json, size_t cap);
 int64_t vf_step_count(const vf_ctx* ctx);
 /* The fold window in effect (1 when the configuration's model, dtype or mode has no windowed path). */
 int32_t vf_fold_window(const vf_ctx* ctx);
+/* Streams the node passes of a step are spread over: 2 when VF_FLAG_OVERLAP is in effect
+ * (asked for, a non-default stream given, and the model supports it), else 1; 0 for NULL. */
+int32_t vf_streams(const vf_ctx* ctx);
 
 int64_t vf_num_params(const vf_ctx* ctx);
 

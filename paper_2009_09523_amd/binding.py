@@ -71,6 +71,7 @@ _SIGNATURES = {
     "vf_profile_stop": (C.c_int, [C.c_void_p, C.c_char_p, C.c_size_t]),
     "vf_step_count": (C.c_int64, [C.c_void_p]),
     "vf_fold_window": (C.c_int32, [C.c_void_p]),
+    "vf_streams": (C.c_int32, [C.c_void_p]),
     "vf_num_params": (C.c_int64, [C.c_void_p]),
     "vf_workspace_bytes": (C.c_size_t, [C.c_void_p]),
     "vf_destroy": (None, [C.c_void_p]),
@@ -270,6 +271,10 @@ class VirtualNodeStep:
     @property
     def fold_window(self) -> int:
         return int(lib().vf_fold_window(self._h))
+
+    @property
+    def streams(self) -> int:
+        return int(lib().vf_streams(self._h))
 
     @property
     def step_count(self) -> int:

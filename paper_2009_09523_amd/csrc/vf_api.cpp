@@ -617,6 +617,7 @@ int vf_state_import(vf_ctx* h, float* params, const void* src, int64_t bytes) {
 
 int64_t vf_step_count(const vf_ctx* h) { return h ? h->c.steps : 0; }
 int32_t vf_fold_window(const vf_ctx* h) { return h ? h->c.window : 0; }
+int32_t vf_streams(const vf_ctx* h) { return h ? (h->c.overlap ? 2 : 1) : 0; }
 int64_t vf_num_params(const vf_ctx* h) { return h ? h->c.P : 0; }
 size_t vf_workspace_bytes(const vf_ctx* h) { return h ? h->c.arena_bytes : 0; }
 
