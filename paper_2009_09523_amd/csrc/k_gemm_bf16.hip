@@ -46,6 +46,80 @@ __device__ __forceinline__ u32x4 load_vec(const bf16_t* __restrict__ base, int64
 
 // Workgroup tile BM x BN, waves arranged WGM x WGN, each wave owns (BM/WGM) x (BN/WGN)
 // made of 32x32 MFMA tiles.  blockIdx.z selects the contraction slice [z*kchunk, (z+1)*kchunk).
+// Epilogue shared by the kernels that keep the product in MFMA layout: a wavefront's TM x TN
+// tiles of 32 x 32 (accumulator register r of a lane holds row 8*(r/4) + 4*(lane/32) + r%4 and
+// column lane%32 of its tile), top-left corner (mbase, nbase):
+//     C = alpha * acc + (beta * R + bias)
+// A wavefront whose tiles lie wholly inside the matrix takes a path without per-element
+// branches, so that all its reads of R are in flight together (a weight gradient that adds
+// into the gradient buffer would otherwise pay one trip to memory per element).
+template <int TM, int TN>
+__device__ __forceinline__ void store_tiles(const f32x16 (&acc)[TM][TN], const Epilogue& ep, char* cbase,
+                                            bool first_slice, int mbase, int nbase, int M, int N, int lane) {
+  const int rowoff = 4 * (lane >> 5);
+  const int col = lane & 31;
+  if (mbase + TM * 32 <= M && nbase + TN * 32 <= N) {
+    float bias[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      bias[j] = 0.f;
+      if (ep.bias && first_slice) {
+        bias[j] = ep.bias[nbase + j * 32 + col];
+        if (ep.bias_round_bf16) bias[j] = round_bf16(bias[j]);
+      }
+    }
+    float add[TM][TN][16];
+    if (ep.R) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int m = mbase + i * 32 + 8 * (r >> 2) + rowoff + (r & 3);
+            add[i][j][r] = ep.R[(int64_t)m * ep.ldr + nbase + j * 32 + col];
+          }
+    }
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int m = mbase + i * 32 + 8 * (r >> 2) + rowoff + (r & 3);
+          const int n = nbase + j * 32 + col;
+          const float addend = ep.R ? fmaf(ep.beta, add[i][j][r], bias[j]) : bias[j];
+          const float v = fmaf(ep.alpha, acc[i][j][r], addend);
+          if (ep.c_is_bf16) reinterpret_cast<bf16_t*>(cbase)[(int64_t)m * ep.ldc + n] = f32_to_bf16(v);
+          else              reinterpret_cast<float*>(cbase)[(int64_t)m * ep.ldc + n] = v;
+        }
+    return;
+  }
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int n = nbase + j * 32 + col;
+      if (n >= N) continue;
+      float bias = 0.f;
+      if (ep.bias && first_slice) {
+        bias = ep.bias[n];
+        if (ep.bias_round_bf16) bias = round_bf16(bias);
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = mbase + i * 32 + 8 * (r >> 2) + rowoff + (r & 3);
+        if (m >= M) continue;
+        float addend = bias;
+        if (ep.R) addend = fmaf(ep.beta, ep.R[(int64_t)m * ep.ldr + n], bias);
+        const float v = fmaf(ep.alpha, acc[i][j][r], addend);
+        if (ep.c_is_bf16) reinterpret_cast<bf16_t*>(cbase)[(int64_t)m * ep.ldc + n] = f32_to_bf16(v);
+        else              reinterpret_cast<float*>(cbase)[(int64_t)m * ep.ldc + n] = v;
+      }
+    }
+  }
+}
+
 template <int BM, int BN, int WGM, int WGN>
 __global__ __launch_bounds__(NT) void gemm_bf16_kernel(const bf16_t* __restrict__ A, int64_t lda,
                                                        const bf16_t* __restrict__ B, int64_t ldb,
@@ -124,29 +198,7 @@ __global__ __launch_bounds__(NT) void gemm_bf16_kernel(const bf16_t* __restrict_
   const bool first_slice = blockIdx.z == 0;
   char* cbase = static_cast<char*>(ep.C) +
                 (int64_t)blockIdx.z * slab_stride * (ep.c_is_bf16 ? 2 : 4);
-#pragma unroll
-  for (int i = 0; i < TM; ++i) {
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int n = n0 + wn * WTN + j * 32 + (lane & 31);
-      if (n >= N) continue;
-      float bias = 0.f;
-      if (ep.bias && first_slice) {
-        bias = ep.bias[n];
-        if (ep.bias_round_bf16) bias = round_bf16(bias);
-      }
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wm * WTM + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        if (m >= M) continue;
-        float addend = bias;
-        if (ep.R) addend = fmaf(ep.beta, ep.R[(int64_t)m * ep.ldr + n], bias);
-        float v = fmaf(ep.alpha, acc[i][j][r], addend);
-        if (ep.c_is_bf16) reinterpret_cast<bf16_t*>(cbase)[(int64_t)m * ep.ldc + n] = f32_to_bf16(v);
-        else              reinterpret_cast<float*>(cbase)[(int64_t)m * ep.ldc + n] = v;
-      }
-    }
-  }
+  store_tiles<TM, TN>(acc, ep, cbase, first_slice, m0 + wm * WTM, n0 + wn * WTN, M, N, lane);
 }
 
 // ---- software-pipelined variant ---------------------------------------------------------------
@@ -303,29 +355,7 @@ __global__ __launch_bounds__(NT) void gemm_bf16_pipe_kernel(const bf16_t* __rest
   const bool first_slice = blockIdx.z == 0;
   char* cbase = static_cast<char*>(ep.C) +
                 (int64_t)blockIdx.z * slab_stride * (ep.c_is_bf16 ? 2 : 4);
-#pragma unroll
-  for (int i = 0; i < TM; ++i) {
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int n = n0 + wn * WTN + j * 32 + (lane & 31);
-      if (n >= N) continue;
-      float bias = 0.f;
-      if (ep.bias && first_slice) {
-        bias = ep.bias[n];
-        if (ep.bias_round_bf16) bias = round_bf16(bias);
-      }
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wm * WTM + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        if (m >= M) continue;
-        float addend = bias;
-        if (ep.R) addend = fmaf(ep.beta, ep.R[(int64_t)m * ep.ldr + n], bias);
-        float v = fmaf(ep.alpha, acc[i][j][r], addend);
-        if (ep.c_is_bf16) reinterpret_cast<bf16_t*>(cbase)[(int64_t)m * ep.ldc + n] = f32_to_bf16(v);
-        else              reinterpret_cast<float*>(cbase)[(int64_t)m * ep.ldc + n] = v;
-      }
-    }
-  }
+  store_tiles<TM, TN>(acc, ep, cbase, first_slice, m0 + wm * WTM, n0 + wn * WTN, M, N, lane);
 }
 
 // ---- LDS-direct variant -----------------------------------------------------------------------
@@ -417,24 +447,10 @@ __global__ __launch_bounds__(NT) void gemm_bf16_dl_kernel(const bf16_t* __restri
     wait_loads_but<0>();
   }
 
-  const int n = n0 + wn * 32 + (lane & 31);
-  if (n >= N) return;
   char* cbase = static_cast<char*>(ep.C) + (int64_t)blockIdx.z * slab_stride * (ep.c_is_bf16 ? 2 : 4);
-  float bias = 0.f;
-  if (ep.bias && blockIdx.z == 0) {
-    bias = ep.bias[n];
-    if (ep.bias_round_bf16) bias = round_bf16(bias);
-  }
-#pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    const int m = m0 + wm * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-    if (m >= M) continue;
-    float addend = bias;
-    if (ep.R) addend = fmaf(ep.beta, ep.R[(int64_t)m * ep.ldr + n], bias);
-    const float v = fmaf(ep.alpha, acc[r], addend);
-    if (ep.c_is_bf16) reinterpret_cast<bf16_t*>(cbase)[(int64_t)m * ep.ldc + n] = f32_to_bf16(v);
-    else              reinterpret_cast<float*>(cbase)[(int64_t)m * ep.ldc + n] = v;
-  }
+  f32x16 tiles[1][1];
+  tiles[0][0] = acc;
+  store_tiles<1, 1>(tiles, ep, cbase, blockIdx.z == 0, m0 + wm * 32, n0 + wn * 32, M, N, lane);
 }
 
 // Short contraction (K <= 2*BK = 128: the weight gradient of a node of up to 128 rows).  The
