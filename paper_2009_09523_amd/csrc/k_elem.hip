@@ -43,12 +43,18 @@ __global__ __launch_bounds__(256) void cast_weight_kernel(const float* __restric
   __shared__ bf16_t tile[64][64 + 2];
   const int q = threadIdx.x & 15, g = threadIdx.x >> 4;      // 16 quads per row, 16 row groups
   const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  // loads at clamped (always valid) positions first, all four in flight together (C % 4 == 0,
+  // so C - 4 starts a whole quad)
+  float4 vin[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    vin[i] = *reinterpret_cast<const float4*>(&in[(int64_t)min(r0 + g + 16 * i, R - 1) * ldi + min(c0 + 4 * q, C - 4)]);
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int rl = g + 16 * i, r = r0 + rl, c = c0 + 4 * q;
     bf16_t h[4] = {0, 0, 0, 0};
     if (r < R && c < C) {
-      const float4 v = *reinterpret_cast<const float4*>(&in[(int64_t)r * ldi + c]);
+      const float4 v = vin[i];
       h[0] = f32_to_bf16(v.x); h[1] = f32_to_bf16(v.y); h[2] = f32_to_bf16(v.z); h[3] = f32_to_bf16(v.w);
       uint2 pk;
       pk.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);

@@ -54,15 +54,20 @@ __global__ __launch_bounds__(256) void softmax_xent_kernel(const float* zp, int 
   float v[CPT];
   float mx = -INFINITY;
   if (SMALL) {
+    // loads at clamped (always valid) columns first, all in flight together; selection after
+#pragma unroll
+    for (int k = 0; k < CPT; ++k) {
+      const int c = min(threadIdx.x + 256 * k, C - 1);
+      v[k] = slab_sum<NS>(zp, nsplit, slab, (int64_t)r * ldzp + c);   // slabs in order
+    }
 #pragma unroll
     for (int k = 0; k < CPT; ++k) {
       const int c = threadIdx.x + 256 * k;
-      v[k] = -INFINITY;
       if (c < C) {
-        const float t = slab_sum<NS>(zp, nsplit, slab, (int64_t)r * ldzp + c);   // slabs in order
-        v[k] = t;
-        zr[c] = t;
-        if (c == label) zlabel = t;
+        zr[c] = v[k];
+        if (c == label) zlabel = v[k];
+      } else {
+        v[k] = -INFINITY;
       }
       mx = fmaxf(mx, v[k]);
     }

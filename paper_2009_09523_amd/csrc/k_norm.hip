@@ -88,10 +88,18 @@ __global__ __launch_bounds__(256) void bn_relu_fwd_kernel(const float* __restric
   // pass 1: reduce the slabs into z, column sums
   float s = 0.f;
   if (SMALL) {
+    // Loads at clamped (always valid) addresses, selection afterwards: no load sits behind a
+    // branch, so all of a thread's loads are in flight together.
+    const int cc = min(c, C - 1);
 #pragma unroll
     for (int k = 0; k < RPT; ++k) {
       const int r = ty + RL * k;
-      zr[k] = (live && r < R) ? sum_slabs<NS>(zp, slab, (int64_t)r * ldzp + c) : 0.f;
+      zr[k] = sum_slabs<NS>(zp, slab, (int64_t)min(r, R - 1) * ldzp + cc);
+    }
+#pragma unroll
+    for (int k = 0; k < RPT; ++k) {
+      const int r = ty + RL * k;
+      zr[k] = (live && r < R) ? zr[k] : 0.f;
       s += zr[k];
     }
 #pragma unroll
@@ -186,18 +194,23 @@ __global__ __launch_bounds__(256) void bn_relu_bwd_kernel(float* __restrict__ da
   float xr[RPT], dr[RPT];
   float sg = 0.f, sb = 0.f;
   if (SMALL) {
+    // loads at clamped (always valid) addresses first, all in flight together; selection after
+    const int cc = min(c, C - 1);
+#pragma unroll
+    for (int k = 0; k < RPT; ++k) {
+      const int rc = min(ty + RL * k, R - 1);
+      xr[k] = z[(int64_t)rc * ldz + cc];
+      dr[k] = sum_slabs<NS>(dap, slab, (int64_t)rc * ldda + cc);
+    }
 #pragma unroll
     for (int k = 0; k < RPT; ++k) {
       const int r = ty + RL * k;
-      xr[k] = 0.f; dr[k] = 0.f;
-      if (live && r < R) {
-        float zz = z[(int64_t)r * ldz + c];
-        float xhat = (zz - mean) * rstd;
-        float pre = bn ? fmaf(g, xhat, b) : zz;
-        float d = sum_slabs<NS>(dap, slab, (int64_t)r * ldda + c);
-        xr[k] = xhat;
-        dr[k] = pre > 0.f ? d : 0.f;
-      }
+      const float zz = xr[k];
+      const float xhat = (zz - mean) * rstd;
+      const float pre = bn ? fmaf(g, xhat, b) : zz;
+      const bool on = live && r < R;
+      xr[k] = on ? xhat : 0.f;
+      dr[k] = (on && pre > 0.f) ? dr[k] : 0.f;
       sg = fmaf(dr[k], xr[k], sg);
       sb += dr[k];
     }
