@@ -5,6 +5,7 @@ namespace vf {
 namespace {
 
 constexpr int TS = 32;   // tile side; 256 threads = 32 x 8
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // out[c*ldo + r] = in[r*ldi + c]
 template <typename TIN>
@@ -31,6 +32,36 @@ __global__ __launch_bounds__(256) void transpose_kernel(const TIN* __restrict__ 
   for (int i = 0; i < TS; i += 8) {
     int c = c0 + ty + i, r = r0 + tx;
     if (r < R && c < C) out[(int64_t)c * ldo + r] = tile[tx][ty + i];
+  }
+}
+
+// out[c*ldo + r] = in[r*ldi + c] for bf16, 64x64 tiles, 16 bytes per lane on both sides (eight
+// lanes cover 128 contiguous bytes of an input row, and of an output row).  Loads go to clamped,
+// always valid addresses and come first, so both of a thread's loads are in flight together.
+// Requires C % 8 == 0, ldi % 8 == 0, ldo % 8 == 0, 16-byte aligned bases, and output rows that
+// may be written up to R rounded to 8 (the rows past R receive copies of row R-1).
+__global__ __launch_bounds__(256) void transpose64_kernel(const bf16_t* __restrict__ in, int64_t ldi,
+                                                          bf16_t* __restrict__ out, int64_t ldo, int R, int C) {
+  __shared__ __attribute__((aligned(16))) bf16_t tile[64][64 + 8];
+  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  const int v = threadIdx.x & 7, row = threadIdx.x >> 3;     // 8 vectors per row, 32 rows per pass
+  u32x4 x[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+    x[i] = *reinterpret_cast<const u32x4*>(&in[(int64_t)min(r0 + row + 32 * i, R - 1) * ldi + min(c0 + 8 * v, C - 8)]);
+#pragma unroll
+  for (int i = 0; i < 2; ++i) *reinterpret_cast<u32x4*>(&tile[row + 32 * i][8 * v]) = x[i];
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int col = (threadIdx.x >> 3) + 32 * i;             // output row = input column
+    const int rb = 8 * (threadIdx.x & 7);                    // eight input rows -> one 16-byte vector
+    u32x4 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      o[e] = (uint32_t)tile[rb + 2 * e][col] | ((uint32_t)tile[rb + 2 * e + 1][col] << 16);
+    if (c0 + col < C && r0 + rb < R)
+      *reinterpret_cast<u32x4*>(&out[(int64_t)(c0 + col) * ldo + r0 + rb]) = o;
   }
 }
 
@@ -112,6 +143,14 @@ __global__ __launch_bounds__(256) void cast_kernel(const float* __restrict__ in,
 int launch_transpose_bf16(const bf16_t* in, int64_t ldi, bf16_t* out, int64_t ldo, int R, int C,
                           hipStream_t s) {
   if (R <= 0 || C <= 0) return VF_OK;
+  const bool wide = (C & 7) == 0 && (ldi & 7) == 0 && (ldo & 7) == 0 && ldo >= ((R + 7) & ~7) &&
+                    (reinterpret_cast<uintptr_t>(in) & 15) == 0 && (reinterpret_cast<uintptr_t>(out) & 15) == 0;
+  if (wide) {
+    dim3 grid64((C + 63) / 64, (R + 63) / 64);
+    transpose64_kernel<<<grid64, 256, 0, s>>>(in, ldi, out, ldo, R, C);
+    VF_LAUNCH_CHECK();
+    return VF_OK;
+  }
   dim3 grid((C + TS - 1) / TS, (R + TS - 1) / TS);
   transpose_kernel<bf16_t><<<grid, 256, 0, s>>>(in, ldi, out, ldo, nullptr, 0, R, C);
   VF_LAUNCH_CHECK();

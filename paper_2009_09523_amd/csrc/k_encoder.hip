@@ -123,6 +123,7 @@ __global__ __launch_bounds__(NT) void extract_masked_kernel(const int32_t* __res
 }
 
 // ---- LayerNorm: one wavefront per row ------------------------------------------------------
+constexpr int LN_JMAX = 16;     // columns per lane held in registers: d <= 64*LN_JMAX
 template <typename T>
 __global__ __launch_bounds__(NT) void layernorm_fwd_kernel(const float* __restrict__ x, int64_t ldx,
                                                            const int32_t* __restrict__ row_map, int R,
@@ -135,6 +136,35 @@ __global__ __launch_bounds__(NT) void layernorm_fwd_kernel(const float* __restri
   const int r = blockIdx.x * WAVES + (threadIdx.x >> 6);
   if (r >= R) return;
   const float* xr = x + (int64_t)(row_map ? row_map[r] : r) * ldx;
+  if (d <= 64 * LN_JMAX) {
+    // The row lives in registers.  Loads go to clamped (always valid) columns and come before
+    // any selection, so all of a lane's loads are in flight together; sums in column order.
+    float v[LN_JMAX], g[LN_JMAX], b[LN_JMAX];
+#pragma unroll
+    for (int j = 0; j < LN_JMAX; ++j) {
+      const int c = min(lane + 64 * j, d - 1);
+      v[j] = xr[c]; g[j] = gamma[c]; b[j] = beta[c];
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < LN_JMAX; ++j) s += (lane + 64 * j < d) ? v[j] : 0.f;
+    const float mean = wave_sum(s) / (float)d;
+    float q = 0.f;
+#pragma unroll
+    for (int j = 0; j < LN_JMAX; ++j) {
+      const float t = (lane + 64 * j < d) ? v[j] - mean : 0.f;
+      q = fmaf(t, t, q);
+    }
+    const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)d + eps);
+#pragma unroll
+    for (int j = 0; j < LN_JMAX; ++j) {
+      const int c = lane + 64 * j;
+      if (round_params) { g[j] = round_bf16(g[j]); b[j] = round_bf16(b[j]); }
+      if (c < d) store_f(&y[(int64_t)r * ldy + c], fmaf(g[j], (v[j] - mean) * rstd, b[j]));
+    }
+    if (lane == 0) { mean_out[r] = mean; rstd_out[r] = rstd; }
+    return;
+  }
   float s = 0.f;
   for (int c = lane; c < d; c += 64) s += xr[c];
   const float mean = wave_sum(s) / (float)d;
@@ -156,7 +186,6 @@ __global__ __launch_bounds__(NT) void layernorm_fwd_kernel(const float* __restri
 // row at a time).  Besides dx it produces this row chunk's contribution to dgamma and dbeta
 // (partial[0][chunk][c], partial[1][chunk][c]) so that no second pass over dy and x is needed;
 // layernorm_param_finish adds the chunks in order.
-constexpr int LN_JMAX = 16;     // columns per lane held in registers: d <= 64*LN_JMAX
 __global__ __launch_bounds__(NT) void layernorm_bwd_kernel(const float* __restrict__ dyp, int nsplit,
                                                            int64_t slab, int64_t lddy,
                                                            const float* __restrict__ x, int64_t ldx,
@@ -181,25 +210,32 @@ __global__ __launch_bounds__(NT) void layernorm_bwd_kernel(const float* __restri
     const int64_t orow = row_map ? row_map[r] : r;
     const float* xr = x + orow * ldx;
     const float mean = mean_in[r], rstd = rstd_in[r];
-    float dyv[LN_JMAX], xhv[LN_JMAX], resv[LN_JMAX];
+    float dyv[LN_JMAX], xhv[LN_JMAX], resv[LN_JMAX], gv[LN_JMAX];
     float s1 = 0.f, s2 = 0.f;
+    // All loads first, at clamped (always valid) columns, so that they are in flight together;
+    // the selection of the live columns follows.
 #pragma unroll
-    for (int j = 0; j < LN_JMAX; ++j) {          // the residual addend travels with the first loads
-      const int c = lane + 64 * j;
-      resv[j] = (dres && c < d) ? dres[orow * lddx + c] : 0.f;
+    for (int j = 0; j < LN_JMAX; ++j) {
+      const int c = min(lane + 64 * j, d - 1);
+      resv[j] = dres ? dres[orow * lddx + c] : 0.f;
+      dyv[j] = dyp[(int64_t)r * lddy + c];
+      xhv[j] = xr[c];
+      gv[j] = gamma[c];
+    }
+    for (int s = 1; s < nsplit; ++s) {            // the slabs in order
+#pragma unroll
+      for (int j = 0; j < LN_JMAX; ++j)
+        dyv[j] += dyp[(int64_t)s * slab + (int64_t)r * lddy + min(lane + 64 * j, d - 1)];
     }
 #pragma unroll
     for (int j = 0; j < LN_JMAX; ++j) {
-      const int c = lane + 64 * j;
-      dyv[j] = 0.f; xhv[j] = 0.f;
-      if (c < d) {
-        float dy = dyp[(int64_t)r * lddy + c];
-        for (int s = 1; s < nsplit; ++s) dy += dyp[(int64_t)s * slab + (int64_t)r * lddy + c];
-        float g = gamma[c];
-        if (round_params) g = round_bf16(g);
-        const float xh = (xr[c] - mean) * rstd;
-        dyv[j] = dy; xhv[j] = xh;
-        const float dxh = dy * g;
+      const bool on = lane + 64 * j < d;
+      if (round_params) gv[j] = round_bf16(gv[j]);
+      const float dy = on ? dyv[j] : 0.f;
+      const float xh = on ? (xhv[j] - mean) * rstd : 0.f;
+      dyv[j] = dy; xhv[j] = xh;
+      if (on) {
+        const float dxh = dy * gv[j];
         s1 += dxh;
         s2 = fmaf(dxh, xh, s2);
         pg[j] = fmaf(dy, xh, pg[j]);
@@ -212,9 +248,7 @@ __global__ __launch_bounds__(NT) void layernorm_bwd_kernel(const float* __restri
     for (int j = 0; j < LN_JMAX; ++j) {
       const int c = lane + 64 * j;
       if (c < d) {
-        float g = gamma[c];
-        if (round_params) g = round_bf16(g);
-        float v = (dyv[j] * g - s1 - xhv[j] * s2) * rstd;
+        float v = (dyv[j] * gv[j] - s1 - xhv[j] * s2) * rstd;
         dx[orow * lddx + c] = v + resv[j];
       }
     }
@@ -267,8 +301,17 @@ __global__ __launch_bounds__(NT) void colsum_partial_kernel(const T* __restrict_
   const int c = blockIdx.x * 32 + tx;
   const int rbeg = blockIdx.y * rows_per_chunk, rend = min(R, rbeg + rows_per_chunk);
   float s = 0.f;
-  if (c < C)
-    for (int r = rbeg + ty; r < rend; r += 8) s += load_f(&xin[(int64_t)r * ld + c]);
+  if (c < C) {
+    int r = rbeg + ty;
+    for (; r + 24 < rend; r += 32) {            // four loads in flight, added in row order
+      const float v0 = load_f(&xin[(int64_t)r * ld + c]);
+      const float v1 = load_f(&xin[(int64_t)(r + 8) * ld + c]);
+      const float v2 = load_f(&xin[(int64_t)(r + 16) * ld + c]);
+      const float v3 = load_f(&xin[(int64_t)(r + 24) * ld + c]);
+      s += v0; s += v1; s += v2; s += v3;
+    }
+    for (; r < rend; r += 8) s += load_f(&xin[(int64_t)r * ld + c]);
+  }
   red[ty][tx] = s;
   __syncthreads();
   if (ty == 0 && c < C) {
@@ -301,6 +344,49 @@ __global__ __launch_bounds__(NT) void gelu_fwd_kernel(const T* __restrict__ u, T
   for (; i < n; i += stride) {
     float v = load_f(&u[i]);
     store_f(&g[i], 0.5f * v * (1.0f + erff(v * 0.70710678118654752f)));
+  }
+}
+
+// Eight bf16 elements per lane and trip (16-byte accesses); n % 8 == 0, 16-byte aligned.
+__device__ __forceinline__ float gelu_f(float v) { return 0.5f * v * (1.0f + erff(v * 0.70710678118654752f)); }
+__device__ __forceinline__ float gelu_df(float v) {
+  const float cdf = 0.5f * (1.0f + erff(v * 0.70710678118654752f));
+  const float pdf = 0.3989422804014327f * expf(-0.5f * v * v);
+  return cdf + v * pdf;
+}
+__global__ __launch_bounds__(NT) void gelu_fwd8_kernel(const uint4* __restrict__ u, uint4* __restrict__ g, int64_t nvec) {
+  int64_t i = (int64_t)blockIdx.x * NT + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * NT;
+  for (; i < nvec; i += stride) {
+    const uint4 x = u[i];
+    const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+    uint32_t o[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float lo = gelu_f(bf16_to_f32((bf16_t)(w[e] & 0xffffu)));
+      const float hi = gelu_f(bf16_to_f32((bf16_t)(w[e] >> 16)));
+      o[e] = (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+    }
+    g[i] = make_uint4(o[0], o[1], o[2], o[3]);
+  }
+}
+__global__ __launch_bounds__(NT) void gelu_bwd8_kernel(const float4* __restrict__ dg, const uint4* __restrict__ u,
+                                                       uint4* __restrict__ du, int64_t nvec) {
+  int64_t i = (int64_t)blockIdx.x * NT + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * NT;
+  for (; i < nvec; i += stride) {
+    const uint4 x = u[i];
+    const float4 d0 = dg[2 * i], d1 = dg[2 * i + 1];
+    const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+    const float d[8] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
+    uint32_t o[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float lo = d[2 * e] * gelu_df(bf16_to_f32((bf16_t)(w[e] & 0xffffu)));
+      const float hi = d[2 * e + 1] * gelu_df(bf16_to_f32((bf16_t)(w[e] >> 16)));
+      o[e] = (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+    }
+    du[i] = make_uint4(o[0], o[1], o[2], o[3]);
   }
 }
 
@@ -447,6 +533,11 @@ int launch_colsum_rows(const void* x, int64_t ld, int x_is_bf16, int R, int C, f
 
 int launch_gelu_fwd(const void* u, void* g, int is_bf16, int64_t n, hipStream_t s) {
   if (n <= 0) return VF_OK;
+  if (is_bf16 && (n & 7) == 0 && ((reinterpret_cast<uintptr_t>(u) | reinterpret_cast<uintptr_t>(g)) & 15) == 0) {
+    gelu_fwd8_kernel<<<blocks_for(n / 8), NT, 0, s>>>(static_cast<const uint4*>(u), static_cast<uint4*>(g), n / 8);
+    VF_LAUNCH_CHECK();
+    return VF_OK;
+  }
   if (is_bf16) gelu_fwd_kernel<bf16_t><<<blocks_for(n), NT, 0, s>>>(static_cast<const bf16_t*>(u),
                                                                     static_cast<bf16_t*>(g), n);
   else         gelu_fwd_kernel<float><<<blocks_for(n), NT, 0, s>>>(static_cast<const float*>(u),
@@ -457,6 +548,13 @@ int launch_gelu_fwd(const void* u, void* g, int is_bf16, int64_t n, hipStream_t 
 
 int launch_gelu_bwd(const float* dg, const void* u, void* du, int is_bf16, int64_t n, hipStream_t s) {
   if (n <= 0) return VF_OK;
+  if (is_bf16 && (n & 7) == 0 &&
+      ((reinterpret_cast<uintptr_t>(u) | reinterpret_cast<uintptr_t>(du) | reinterpret_cast<uintptr_t>(dg)) & 15) == 0) {
+    gelu_bwd8_kernel<<<blocks_for(n / 8), NT, 0, s>>>(reinterpret_cast<const float4*>(dg), static_cast<const uint4*>(u),
+                                                      static_cast<uint4*>(du), n / 8);
+    VF_LAUNCH_CHECK();
+    return VF_OK;
+  }
   if (is_bf16) gelu_bwd_kernel<bf16_t><<<blocks_for(n), NT, 0, s>>>(dg, static_cast<const bf16_t*>(u),
                                                                     static_cast<bf16_t*>(du), n);
   else         gelu_bwd_kernel<float><<<blocks_for(n), NT, 0, s>>>(dg, static_cast<const float*>(u),

@@ -72,9 +72,24 @@ __global__ __launch_bounds__(256) void softmax_xent_kernel(const float* zp, int 
       mx = fmaxf(mx, v[k]);
     }
   } else {
-    for (int c = threadIdx.x; c < C; c += 256) {
+    // Long rows: four columns per trip, their loads issued together, handled in column order.
+    // When the logits are reduced in place (one slab that is z itself) nothing is written back.
+    const bool in_place = nsplit == 1 && zp + (int64_t)r * ldzp == zr;
+    int c = threadIdx.x;
+    for (; c + 768 < C; c += 1024) {
+      float t[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) t[k] = slab_sum<NS>(zp, nsplit, slab, (int64_t)r * ldzp + c + 256 * k);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        if (!in_place) zr[c + 256 * k] = t[k];
+        if (c + 256 * k == label) zlabel = t[k];
+        mx = fmaxf(mx, t[k]);
+      }
+    }
+    for (; c < C; c += 256) {
       const float t = slab_sum<NS>(zp, nsplit, slab, (int64_t)r * ldzp + c);
-      zr[c] = t;
+      if (!in_place) zr[c] = t;
       if (c == label) zlabel = t;
       mx = fmaxf(mx, t);
     }
@@ -88,7 +103,15 @@ __global__ __launch_bounds__(256) void softmax_xent_kernel(const float* zp, int 
       sum += v[k];
     }
   } else {
-    for (int c = threadIdx.x; c < C; c += 256) sum += expf(zr[c] - mx);
+    int c = threadIdx.x;
+    for (; c + 768 < C; c += 1024) {
+      float t[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) t[k] = zr[c + 256 * k];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) sum += expf(t[k] - mx);
+    }
+    for (; c < C; c += 256) sum += expf(zr[c] - mx);
   }
   sum = block_reduce(sum, false, red);
   const float inv = 1.0f / sum;
@@ -105,7 +128,20 @@ __global__ __launch_bounds__(256) void softmax_xent_kernel(const float* zp, int 
       }
     }
   } else {
-    for (int c = threadIdx.x; c < C; c += 256) {
+    int c = threadIdx.x;
+    for (; c + 768 < C; c += 1024) {
+      float t[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) t[k] = zr[c + 256 * k];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int cc = c + 256 * k;
+        const float d = (expf(t[k] - mx) * inv - (cc == label ? 1.f : 0.f)) * invR;
+        store_f(&dr[cc], d);
+        if (dzT) dzT[(int64_t)cc * ldt + r] = f32_to_bf16(d);
+      }
+    }
+    for (; c < C; c += 256) {
       float d = (expf(zr[c] - mx) * inv - (c == label ? 1.f : 0.f)) * invR;
       store_f(&dr[c], d);
       if (dzT) dzT[(int64_t)c * ldt + r] = f32_to_bf16(d);
