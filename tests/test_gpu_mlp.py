@@ -66,6 +66,20 @@ def test_graph_replay_is_repeatable():
     assert eager["theta"].tobytes() == graph["theta"].tobytes()
 
 
+@pytest.mark.parametrize("flags,window", [(0, 0), (FUSED, 0), (FUSED, 4), (FUSED | NO_GRAPH | 4, 4)])
+@pytest.mark.parametrize("name", ["mlp_mid_bn_bf16", "mlp_mid_bf16"])
+def test_ragged_node_sizes(name, flags, window):
+    """Node sizes that are no multiple of anything (13, 7, 1, 33, 50 rows) and one longer than the
+    register-resident BatchNorm path and the single-trip weight-gradient kernels take (136):
+    every 16-byte access of the transposed copies ends in padding, never in a neighbour's rows."""
+    wl, theta, x, y = _case(name)
+    sizes = [13, 7, 1, 33, 50, 136]
+    assert sum(sizes) == wl.batch
+    gpu = run_gpu(wl, theta, x, y, node_sizes=sizes, flags=flags, fold_window=window, steps=2)
+    ref = oracle_steps(wl, theta, x, y, node_sizes=sizes, steps=2)
+    check_against_oracle(wl, gpu, ref, tol=2 * TOL[wl.dtype])
+
+
 def test_partition_invariance_on_device_without_batchnorm():
     wl, theta, x, y = _case("mlp_small_f32")
     a = run_gpu(wl, theta, x, y, node_sizes=[wl.batch])
@@ -109,13 +123,17 @@ def test_rejected_step_leaves_state_untouched():
     eng.close()
 
 
-@pytest.mark.parametrize("name,flags", [("C2", 0), ("C3", 0), ("C3", FUSED)])
-def test_full_size_configurations(name, flags):
+BENCH = FUSED | NO_GRAPH | 4        # what bench.py times: fused fold, two streams, eager launches, window 8
+
+
+@pytest.mark.parametrize("name,flags,window", [("C2", BENCH, 8), ("C3", BENCH, 8), ("C2", 0, 0), ("C3", FUSED, 0)])
+def test_full_size_configurations(name, flags, window):
     """The benchmark configuration (C2) and the heterogeneous split (C3) at full size, in the
-    launch configuration bench.py times, every gradient entry against the oracle."""
-    print(f"full size {name} flags={flags}", flush=True)
+    launch configuration bench.py times (and in the plain staged / fused ones), every gradient
+    entry against the oracle."""
+    print(f"full size {name} flags={flags} window={window}", flush=True)
     wl, theta, x, y = _case(name, jitter=0.0)
-    gpu = run_gpu(wl, theta, x, y, flags=flags)
+    gpu = run_gpu(wl, theta, x, y, flags=flags, fold_window=window)
     ref = oracle_steps(wl, theta, x, y)
     check_against_oracle(wl, gpu, ref)
     check_update_from_own_gradient(wl, gpu, theta)
