@@ -141,3 +141,31 @@ def attention_bwd(do, q, k, v, p, operand=_identity):
     dq = (ds @ k) / np.sqrt(dh)
     dk = (np.swapaxes(ds, -1, -2) @ q) / np.sqrt(dh)
     return dq, dk, dv
+
+
+# ---- 3x3 convolution, stride 1, zero padding 1, NHWC ---------------------------------------
+# y[n,h,w,o] = sum_{kh,kw,c} xpad[n, h+kh, w+kw, c] * W[o, kh, kw, c]   (cross-correlation, as
+# deep-learning frameworks define "convolution"), xpad = x with one ring of zeros.
+
+def conv3x3_fwd(x, W):
+    n, H, Wd, _ = x.shape
+    xp = np.pad(x, ((0, 0), (1, 1), (1, 1), (0, 0)))
+    y = np.zeros((n, H, Wd, W.shape[0]))
+    for kh in range(3):
+        for kw in range(3):
+            y += xp[:, kh:kh + H, kw:kw + Wd, :] @ W[:, kh, kw, :].T
+    return y
+
+
+def conv3x3_bwd(x, W, dy, need_dx=True):
+    """(dx, dW) of conv3x3_fwd; dx is None when not needed (first layer)."""
+    n, H, Wd, _ = x.shape
+    xp = np.pad(x, ((0, 0), (1, 1), (1, 1), (0, 0)))
+    dW = np.zeros_like(W, dtype=np.float64)
+    dxp = np.zeros_like(xp, dtype=np.float64) if need_dx else None
+    for kh in range(3):
+        for kw in range(3):
+            dW[:, kh, kw, :] = np.tensordot(dy, xp[:, kh:kh + H, kw:kw + Wd, :], axes=([0, 1, 2], [0, 1, 2]))
+            if need_dx:
+                dxp[:, kh:kh + H, kw:kw + Wd, :] += dy @ W[:, kh, kw, :]
+    return (dxp[:, 1:-1, 1:-1, :] if need_dx else None), dW

@@ -25,6 +25,15 @@ def layout(wl):
                 out.append((f"l{l}.gamma", (n,)))
                 out.append((f"l{l}.beta", (n,)))
         return out
+    if wl.kind == "conv":
+        # filters [out channel, kh, kw, in channel]; every convolution feeds a BatchNorm (no bias)
+        c = wl.width
+        out += [("stem.W", (c, 3, 3, wl.in_ch)), ("stem.gamma", (c,)), ("stem.beta", (c,))]
+        for b in range(wl.n_blocks):
+            out += [(f"b{b}.W1", (c, 3, 3, c)), (f"b{b}.gamma1", (c,)), (f"b{b}.beta1", (c,)),
+                    (f"b{b}.W2", (c, 3, 3, c)), (f"b{b}.gamma2", (c,)), (f"b{b}.beta2", (c,))]
+        out += [("fc.W", (c, wl.classes)), ("fc.b", (wl.classes,))]
+        return out
     d, f = wl.d_model, wl.d_ffn
     out.append(("tok_emb", (wl.vocab, d)))
     out.append(("pos_emb", (wl.seq_len, d)))
@@ -105,6 +114,71 @@ def _mlp_node(wl, p, x, y, accum32=False):
             g[f"l{l}.b"] = dz.sum(axis=0)
         dh, g[f"l{l}.W"], _ = L.linear_bwd(h_in, p[f"l{l}.W"], q(dz), False)
     stats = [(c[2], c[3]) for _, _, c in saved] if wl.batchnorm else []
+    return loss, g, margin, stats
+
+
+def _bn_rows(z, gamma, beta, eps):
+    """BatchNorm of an NHWC tensor: statistics per channel over all rows (n, h, w) of the node."""
+    pre, cache = L.batchnorm_fwd(z.reshape(-1, z.shape[-1]), gamma, beta, eps)
+    return pre.reshape(z.shape), cache
+
+
+def _bn_rows_bwd(dpre, gamma, cache):
+    dz, dg, db = L.batchnorm_bwd(dpre.reshape(-1, dpre.shape[-1]), gamma, cache)
+    return dz.reshape(dpre.shape), dg, db
+
+
+def _conv_node(wl, p, x, y):
+    """Residual network of 3x3 convolutions on one node's images x [n, H, W, in_ch]:
+    stem (convolution, BatchNorm, ReLU); blocks of convolution-BatchNorm-ReLU-convolution-
+    BatchNorm, the block's input added, ReLU; mean over the positions; Linear; mean
+    cross-entropy over the node.  Every BatchNorm takes its statistics over the node's
+    n*H*W positions (Section 4.1).  bf16 workloads: the stored activations (operands of the
+    next convolution, and the addend of the skip connection), the pooled features and every
+    gradient handed to a backward contraction are rounded to bf16; convolution outputs,
+    statistics, sums and the gradients between contractions stay float64."""
+    q = _operand(wl)
+    n, H, Wd, _ = x.shape
+    rms = lambda t: float(np.min(np.abs(t)) / np.sqrt(np.mean(t * t)))
+    stats = []
+    h0 = np.asarray(x, dtype=np.float64)
+    z = L.conv3x3_fwd(h0, p["stem.W"])
+    pre, c0 = _bn_rows(z, p["stem.gamma"], p["stem.beta"], wl.bn_eps)
+    stats.append((c0[2], c0[3]))
+    margin = rms(pre)
+    a = q(L.relu_fwd(pre))
+    saved = []
+    for b in range(wl.n_blocks):
+        z1 = L.conv3x3_fwd(a, p[f"b{b}.W1"])
+        pre1, c1 = _bn_rows(z1, p[f"b{b}.gamma1"], p[f"b{b}.beta1"], wl.bn_eps)
+        a1 = q(L.relu_fwd(pre1))
+        z2 = L.conv3x3_fwd(a1, p[f"b{b}.W2"])
+        pre2, c2 = _bn_rows(z2, p[f"b{b}.gamma2"], p[f"b{b}.beta2"], wl.bn_eps)
+        s = pre2 + a                                   # skip connection: the block's (stored) input
+        stats += [(c1[2], c1[3]), (c2[2], c2[3])]
+        margin = min(margin, rms(pre1), rms(s))
+        saved.append((a, pre1, c1, a1, c2, s))
+        a = q(L.relu_fwd(s))
+    pooled = q(a.sum(axis=(1, 2)) / (H * Wd))          # [n, width]
+    logits = L.linear_fwd(pooled, p["fc.W"], p["fc.b"])
+    loss, dlogits = L.softmax_xent_fwd_bwd(logits, np.asarray(y, dtype=np.int64))
+
+    g = {}
+    dpooled, g["fc.W"], g["fc.b"] = L.linear_bwd(pooled, p["fc.W"], q(dlogits), True)
+    g["fc.b"] = dlogits.sum(axis=0)                    # bias gradient from the unrounded dlogits, as in the MLP
+    da = np.broadcast_to(dpooled[:, None, None, :] / (H * Wd), (n, H, Wd, dpooled.shape[1]))
+    for b in range(wl.n_blocks - 1, -1, -1):
+        a_in, pre1, c1, a1, c2, s = saved[b]
+        ds = L.relu_bwd(da, s)
+        dz2, g[f"b{b}.gamma2"], g[f"b{b}.beta2"] = _bn_rows_bwd(ds, p[f"b{b}.gamma2"], c2)
+        da1, g[f"b{b}.W2"] = L.conv3x3_bwd(a1, p[f"b{b}.W2"], q(dz2))
+        dpre1 = L.relu_bwd(da1, pre1)
+        dz1, g[f"b{b}.gamma1"], g[f"b{b}.beta1"] = _bn_rows_bwd(dpre1, p[f"b{b}.gamma1"], c1)
+        dconv, g[f"b{b}.W1"] = L.conv3x3_bwd(a_in, p[f"b{b}.W1"], q(dz1))
+        da = dconv + ds                                # through the convolutions + through the skip
+    dpre = L.relu_bwd(da, pre)
+    dz, g["stem.gamma"], g["stem.beta"] = _bn_rows_bwd(dpre, p["stem.gamma"], c0)
+    _, g["stem.W"] = L.conv3x3_bwd(h0, p["stem.W"], q(dz), need_dx=False)
     return loss, g, margin, stats
 
 
@@ -199,6 +273,8 @@ def node_loss_and_grads(wl, compute_params, x_node, y_node, diag=None, accum32=F
     p = unflatten(wl, compute_params)
     if wl.kind == "mlp":
         loss, g, margin, stats = _mlp_node(wl, p, x_node, y_node, accum32)
+    elif wl.kind == "conv":
+        loss, g, margin, stats = _conv_node(wl, p, np.asarray(x_node), y_node)
     else:
         loss, g, margin = _encoder_node(wl, p, x_node, y_node)
         stats = []
@@ -221,8 +297,8 @@ def compute_copy(wl, theta):
 
 def new_state(wl, n):
     st = {"t": 0, "v": np.zeros(n)} if wl.optimizer == "sgdm" else {"t": 0, "m": np.zeros(n), "u": np.zeros(n)}
-    if wl.kind == "mlp" and wl.batchnorm:      # moving statistics start at mean 0, variance 1
-        widths = wl.dims[1:-1]
+    if wl.kind in ("mlp", "conv") and wl.batchnorm:      # moving statistics start at mean 0, variance 1
+        widths = wl.dims[1:-1] if wl.kind == "mlp" else [wl.width] * (1 + 2 * wl.n_blocks)
         st["bn_mean"] = [np.zeros(n_) for n_ in widths]
         st["bn_var"] = [np.ones(n_) for n_ in widths]
     return st

@@ -56,6 +56,19 @@ def _enc_loss(wl, p, ids, y):
     return F.cross_entropy(z, y[:, 1, :].reshape(-1), reduction="mean")
 
 
+def _conv_loss(wl, p, x, y):
+    """Library convolution (NCHW, filters [out, in, kh, kw]), batch statistics per call."""
+    def conv_bn(h, W, gamma, beta):
+        z = F.conv2d(h, W.permute(0, 3, 1, 2), padding=1)
+        return F.batch_norm(z, None, None, gamma, beta, training=True, eps=wl.bn_eps)
+    h = F.relu(conv_bn(x.permute(0, 3, 1, 2), p["stem.W"], p["stem.gamma"], p["stem.beta"]))
+    for b in range(wl.n_blocks):
+        t = F.relu(conv_bn(h, p[f"b{b}.W1"], p[f"b{b}.gamma1"], p[f"b{b}.beta1"]))
+        h = F.relu(conv_bn(t, p[f"b{b}.W2"], p[f"b{b}.gamma2"], p[f"b{b}.beta2"]) + h)
+    z = F.linear(h.mean(dim=(2, 3)), p["fc.W"].t(), p["fc.b"])
+    return F.cross_entropy(z, y, reduction="mean")
+
+
 def _autograd_step(wl, theta, x, y):
     sizes = wl.node_sizes
     B = sum(sizes)
@@ -69,6 +82,9 @@ def _autograd_step(wl, theta, x, y):
         if wl.kind == "mlp":
             li = _mlp_loss(wl, p, torch.tensor(x[lo:lo + b], dtype=torch.float64),
                            torch.tensor(y[lo:lo + b], dtype=torch.int64))
+        elif wl.kind == "conv":
+            li = _conv_loss(wl, p, torch.tensor(x[lo:lo + b], dtype=torch.float64),
+                            torch.tensor(y[lo:lo + b], dtype=torch.int64))
         else:
             li = _enc_loss(wl, p, torch.tensor(x[lo:lo + b], dtype=torch.int64),
                            torch.tensor(y[lo:lo + b], dtype=torch.int64))
@@ -81,7 +97,7 @@ def _autograd_step(wl, theta, x, y):
 
 
 @pytest.mark.parametrize("name", ["mlp_small_f32", "mlp_small_bn_f32", "mlp_mid_bn_bf16", "enc_tiny_f32",
-                                  "enc_small_bf16", "C1"])
+                                  "enc_small_bf16", "C1", "conv_tiny_bf16", "conv_small_bf16"])
 def test_oracle_matches_autograd_per_node(name):
     wl = replace(I.workload(name), dtype="f64")
     theta = I.make_params(wl, jitter=0.2).astype(np.float64)

@@ -18,6 +18,10 @@ Flat parameter layout (fp32, tensors in forward order):
            Wqkv[d, 3d], bqkv[3d], Wo[d, d], bo[d], ln2.gamma, ln2.beta,
            W1[d, ffn], b1[ffn], W2[ffn, d], b2[d]; then lnf.gamma, lnf.beta,
            Wout[d, vocab], bout[vocab].
+  conv:    (residual network of 3x3 convolutions, stride 1, zero padding 1, inputs NHWC)
+           stem.W[width, 3, 3, in_ch], stem.gamma[width], stem.beta[width]; per block b
+           b.W1[width, 3, 3, width], b.gamma1, b.beta1, b.W2[width, 3, 3, width], b.gamma2,
+           b.beta2; then fc.W[width, classes], fc.b[classes].
 """
 from __future__ import annotations
 
@@ -36,7 +40,7 @@ SEED_MASK = 9526
 class Workload:
     """One configuration of the step: model, batch split, numerics, optimizer."""
     name: str
-    kind: str                       # "mlp" | "encoder"
+    kind: str                       # "mlp" | "encoder" | "conv"
     # MLP
     dims: Tuple[int, ...] = ()      # [in, h1, ..., out]
     batchnorm: bool = False
@@ -48,6 +52,12 @@ class Workload:
     seq_len: int = 0
     vocab: int = 0
     n_masked: int = 0               # masked positions per sequence
+    # conv (residual network on img x img inputs with in_ch channels)
+    img: int = 0
+    in_ch: int = 0
+    width: int = 0                  # channels of every convolution
+    n_blocks: int = 0               # residual blocks of two 3x3 convolutions each
+    classes: int = 0
     # step
     node_sizes: Tuple[int, ...] = ()
     dtype: str = "f32"              # "f32" | "bf16"
@@ -84,6 +94,11 @@ def _enc(name, n_layers, d, h, ffn, T, vocab, node_sizes, dtype, **kw) -> Worklo
                     node_sizes=tuple(node_sizes), dtype=dtype, **kw)
 
 
+def _conv(name, img, in_ch, width, n_blocks, classes, node_sizes, dtype, **kw) -> Workload:
+    return Workload(name=name, kind="conv", img=img, in_ch=in_ch, width=width, n_blocks=n_blocks,
+                    classes=classes, batchnorm=True, node_sizes=tuple(node_sizes), dtype=dtype, **kw)
+
+
 # The five named configurations (C1..C5) and small relatives used by the tests.
 WORKLOADS: Dict[str, Workload] = {
     "C1": _mlp("C1", [784, 256, 10], False, [16] * 4, "f32", lr=0.1, momentum=0.9),
@@ -112,6 +127,12 @@ WORKLOADS: Dict[str, Workload] = {
                          optimizer="adam", lr=1e-4),
     "enc_small_f32": _enc("enc_small_f32", 2, 128, 2, 264, 32, 1003, [4, 2, 3], "f32",
                           optimizer="adam", lr=1e-4),
+    # second workload family: a residual network of 3x3 convolutions (the paper's headline
+    # workloads are ResNets); C6 = 32 x 32 x 3 inputs, width 64, two blocks, nodes as in C2
+    "C6": _conv("C6", 32, 3, 64, 2, 10, [128] * 8, "bf16"),
+    "conv_tiny_f64": _conv("conv_tiny_f64", 5, 2, 8, 1, 4, [3, 2], "f64"),
+    "conv_tiny_bf16": _conv("conv_tiny_bf16", 6, 3, 16, 1, 10, [5, 3, 8], "bf16"),
+    "conv_small_bf16": _conv("conv_small_bf16", 12, 3, 24, 2, 10, [9, 16, 7], "bf16"),
 }
 
 
@@ -125,8 +146,9 @@ def workload(name: str) -> Workload:
 
 def param_layout(wl: Workload) -> List[Tuple[str, Tuple[int, ...], str]]:
     """List of (name, shape, init) in flat order.  init is one of
-    'he' (normal, variance 2/fan_in with fan_in = shape[0]), 'emb' (normal,
-    std 0.02), 'zeros', 'ones'."""
+    'he' (normal, variance 2/fan_in with fan_in = shape[0]), 'he_conv' (the same with
+    fan_in = the entries of one output channel's filter), 'emb' (normal, std 0.02), 'zeros',
+    'ones'."""
     out: List[Tuple[str, Tuple[int, ...], str]] = []
     if wl.kind == "mlp":
         nl = len(wl.dims) - 1
@@ -152,6 +174,13 @@ def param_layout(wl: Workload) -> List[Tuple[str, Tuple[int, ...], str]]:
                     (f"l{l}.W2", (f, d), "he"), (f"l{l}.b2", (d,), "zeros")]
         out += [("lnf.gamma", (d,), "ones"), ("lnf.beta", (d,), "zeros"),
                 ("Wout", (d, wl.vocab), "he"), ("bout", (wl.vocab,), "zeros")]
+    elif wl.kind == "conv":
+        c = wl.width
+        out += [("stem.W", (c, 3, 3, wl.in_ch), "he_conv"), ("stem.gamma", (c,), "ones"), ("stem.beta", (c,), "zeros")]
+        for b in range(wl.n_blocks):
+            out += [(f"b{b}.W1", (c, 3, 3, c), "he_conv"), (f"b{b}.gamma1", (c,), "ones"), (f"b{b}.beta1", (c,), "zeros"),
+                    (f"b{b}.W2", (c, 3, 3, c), "he_conv"), (f"b{b}.gamma2", (c,), "ones"), (f"b{b}.beta2", (c,), "zeros")]
+        out += [("fc.W", (c, wl.classes), "he"), ("fc.b", (wl.classes,), "zeros")]
     else:
         raise ValueError(wl.kind)
     return out
@@ -171,6 +200,8 @@ def make_params(wl: Workload, seed: int = SEED_PARAMS, jitter: float = 0.0) -> n
         n = int(np.prod(shape))
         if init == "he":
             v = rng.standard_normal(n) * np.sqrt(2.0 / shape[0])
+        elif init == "he_conv":
+            v = rng.standard_normal(n) * np.sqrt(2.0 / int(np.prod(shape[1:])))
         elif init == "emb":
             v = rng.standard_normal(n) * 0.02
         elif init == "zeros":
@@ -195,6 +226,8 @@ def make_batch(wl: Workload, seed_x: int = SEED_INPUTS, seed_y: int = SEED_LABEL
 
     MLP:     x fp32 [B, D_in] ~ N(0,1) (bf16-representable when wl.dtype is
              bf16); y int32 [B] uniform in [0, n_classes).
+    conv:    x fp32 [B, img, img, in_ch] ~ N(0,1) (bf16-representable when wl.dtype is bf16);
+             y int32 [B] uniform in [0, classes).
     encoder: x int32 ids [B, T] uniform in [0, vocab) with the masked positions
              already replaced by id 0; y int32 [B, 2, n_masked] with
              y[:, 0, :] the masked positions (first n_masked entries of a seeded
@@ -209,6 +242,14 @@ def make_batch(wl: Workload, seed_x: int = SEED_INPUTS, seed_y: int = SEED_LABEL
         if wl.dtype == "bf16":
             x = _to_bf16_representable(x)
         y = ry.integers(0, wl.dims[-1], size=B, dtype=np.int64).astype(np.int32)
+        return x, y
+    if wl.kind == "conv":
+        rx = np.random.Generator(np.random.PCG64(seed_x))
+        ry = np.random.Generator(np.random.PCG64(seed_y))
+        x = rx.standard_normal((B, wl.img, wl.img, wl.in_ch)).astype(np.float32)
+        if wl.dtype == "bf16":
+            x = _to_bf16_representable(x)
+        y = ry.integers(0, wl.classes, size=B, dtype=np.int64).astype(np.int32)
         return x, y
     rx = np.random.Generator(np.random.PCG64(seed_x))
     rm = np.random.Generator(np.random.PCG64(seed_mask))
