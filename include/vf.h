@@ -28,6 +28,12 @@
  *   encoder: tok_emb[vocab,d], pos_emb[T,d]; per layer ln1.gamma, ln1.beta, Wqkv[d,3d],
  *            bqkv, Wo[d,d], bo, ln2.gamma, ln2.beta, W1[d,ffn], b1, W2[ffn,d], b2; then
  *            lnf.gamma, lnf.beta, Wout[d,vocab], bout.
+ *   conv:    a residual network of 3x3 convolutions (stride 1, zero padding 1, no bias, each
+ *            followed by BatchNorm over the node's n*img*img positions): stem filters
+ *            [width, 3, 3, in_ch], gamma, beta; per block filters1 [width, 3, 3, width], gamma1,
+ *            beta1, filters2, gamma2, beta2 (block: convolution, BatchNorm, ReLU, convolution,
+ *            BatchNorm, add the block's input, ReLU); then the classifier on the mean over the
+ *            positions: W[width, classes], bias.
  */
 #ifndef VF_H
 #define VF_H
@@ -49,6 +55,7 @@ extern "C" {
 
 #define VF_MLP      0
 #define VF_ENCODER  1
+#define VF_CONV     2
 
 #define VF_F32      0      /* fp32 operands and arithmetic throughout */
 #define VF_BF16     1      /* bf16 GEMM operands (round-to-nearest-even), fp32 accumulation,
@@ -86,13 +93,16 @@ typedef struct vf_ctx vf_ctx;
 
 /* Plain data, copied by vf_init. */
 typedef struct vf_config {
-  int32_t model_kind;            /* VF_MLP | VF_ENCODER */
+  int32_t model_kind;            /* VF_MLP | VF_ENCODER | VF_CONV */
   int32_t n_dims;                /* MLP: number of entries of dims (layers + 1), 2..VF_MAX_DIMS */
   int32_t dims[VF_MAX_DIMS];     /* MLP: [in, h1, ..., out] */
   int32_t batchnorm;             /* MLP: 1 = every hidden Linear (no bias) is followed by
                                     BatchNorm (statistics per virtual node) and ReLU;
                                     0 = Linear with bias, then ReLU */
   int32_t n_layers, d_model, n_heads, d_ffn, seq_len, vocab, n_masked;   /* encoder */
+  int32_t img, in_ch, width, n_blocks, classes;   /* conv: img x img inputs with in_ch channels,
+                                    `width` channels in every convolution (a multiple of 8, at
+                                    most 256), n_blocks residual blocks; VF_BF16 only */
   int32_t dtype;                 /* VF_F32 | VF_BF16 */
   int32_t optimizer;             /* VF_SGDM | VF_ADAM */
   float   lr, momentum, beta1, beta2, adam_eps, bn_eps, ln_eps;
@@ -132,7 +142,8 @@ int vf_init(const vf_config* cfg, vf_ctx** out);
  *   params      device, fp32 [vf_num_params], IN/OUT: master parameters, updated in place.
  *   batch_x     device. MLP: [B, dims[0]] row-major, fp32 for VF_F32, bf16 for VF_BF16.
  *               encoder: int32 token ids [B, seq_len], masked positions already replaced.
- *   batch_y     device, int32. MLP: [B] class labels in [0, dims[last]).
+ *               conv: bf16 [B, img, img, in_ch] (channels last).
+ *   batch_y     device, int32. MLP and conv: [B] class labels in [0, dims[last]) / [0, classes).
  *               encoder: [B, 2, n_masked]: [s,0,:] masked positions in [0, seq_len), distinct
  *               per sequence; [s,1,:] target ids in [0, vocab).
  *   B, V        batch size and number of virtual nodes.

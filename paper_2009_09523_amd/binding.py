@@ -8,7 +8,7 @@ from typing import Optional, Sequence
 import numpy as np
 
 VF_OK, VF_EINVAL, VF_ENOMEM, VF_EDEVICE, VF_ESTATE = 0, -1, -2, -3, -4
-VF_MLP, VF_ENCODER = 0, 1
+VF_MLP, VF_ENCODER, VF_CONV = 0, 1, 2
 VF_F32, VF_BF16 = 0, 1
 VF_SGDM, VF_ADAM = 0, 1
 VF_MAX_DIMS = 16
@@ -45,6 +45,8 @@ class VfConfig(C.Structure):
         ("batchnorm", C.c_int32),
         ("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32),
         ("d_ffn", C.c_int32), ("seq_len", C.c_int32), ("vocab", C.c_int32), ("n_masked", C.c_int32),
+        ("img", C.c_int32), ("in_ch", C.c_int32), ("width", C.c_int32), ("n_blocks", C.c_int32),
+        ("classes", C.c_int32),
         ("dtype", C.c_int32), ("optimizer", C.c_int32),
         ("lr", C.c_float), ("momentum", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float),
         ("adam_eps", C.c_float), ("bn_eps", C.c_float), ("ln_eps", C.c_float),
@@ -214,8 +216,10 @@ def config_from_workload(wl, max_batch: Optional[int] = None, max_node_size: Opt
     """Fills a vf_config from a workload description (an object with the attributes of
     vf_inputs.Workload)."""
     cfg = VfConfig()
-    cfg.model_kind = VF_MLP if wl.kind == "mlp" else VF_ENCODER
-    if wl.kind == "mlp":
+    cfg.model_kind = {"mlp": VF_MLP, "encoder": VF_ENCODER, "conv": VF_CONV}[wl.kind]
+    if wl.kind == "conv":
+        cfg.img, cfg.in_ch, cfg.width, cfg.n_blocks, cfg.classes = wl.img, wl.in_ch, wl.width, wl.n_blocks, wl.classes
+    elif wl.kind == "mlp":
         cfg.n_dims = len(wl.dims)
         for i, d in enumerate(wl.dims):
             cfg.dims[i] = int(d)

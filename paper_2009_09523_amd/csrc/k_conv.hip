@@ -1,0 +1,460 @@
+// Kernels of the convolutional workload family (a residual network of 3x3 convolutions, stride 1,
+// zero padding 1, NHWC): the convolution itself is a product (k_gemm_bf16.hip) over patch rows
+// written by im2col; here are im2col, the filter copies, BatchNorm over the positions of one
+// virtual node (Section 4.1: statistics of the pass that is running, i.e. of the node's n*H*W
+// rows), the mean over positions, and the folding of contraction slabs into a gradient.
+//
+// Tall-matrix reductions ([rows, C] with rows = n*H*W in the 10^5 and C <= 256) go in two steps:
+// per-chunk partial results, then one small kernel that combines the chunks in chunk order, so
+// results do not depend on scheduling.  Loads go to clamped, always valid addresses ahead of any
+// selection, so that all of a thread's loads are in flight together.
+#include "vf_device.h"
+
+namespace vf {
+namespace {
+
+constexpr int NT = 256;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// ---- im2col ---------------------------------------------------------------------------------
+// cols[r, (kh*3+kw)*C + c] = x[n, h+kh-1, w+kw-1, c] (0 outside the image), r = (n*H + h)*W + w;
+// columns 9C .. Kp-1 (padding of the row to a multiple of 8) are written as 0.
+// Vector form: C % 8 == 0, one 16-byte piece per thread.
+__global__ __launch_bounds__(NT) void im2col8_kernel(const bf16_t* __restrict__ x, int64_t rows, int H, int W, int C,
+                                                     bf16_t* __restrict__ cols, int64_t Kp) {
+  const int c8n = C >> 3;
+  const int64_t per_row = 9 * c8n;
+  const int64_t idx = (int64_t)blockIdx.x * NT + threadIdx.x;
+  if (idx >= rows * per_row) return;
+  const int64_t r = idx / per_row;
+  const int rem = (int)(idx - r * per_row);
+  const int tap = rem / c8n, c8 = rem - tap * c8n;
+  const int kh = tap / 3, kw = tap - 3 * kh;
+  const int w = (int)(r % W);
+  const int h = (int)((r / W) % H);
+  const int hh = h + kh - 1, ww = w + kw - 1;
+  const bool in = hh >= 0 && hh < H && ww >= 0 && ww < W;
+  // the source row of an inside tap is r + (kh-1)*W + (kw-1): same image, since hh and ww are inside
+  const int64_t src = in ? r + (int64_t)(kh - 1) * W + (kw - 1) : r;
+  u32x4 v = *reinterpret_cast<const u32x4*>(&x[src * C + 8 * c8]);
+  if (!in) v = u32x4{0u, 0u, 0u, 0u};
+  *reinterpret_cast<u32x4*>(&cols[r * Kp + (int64_t)tap * C + 8 * c8]) = v;
+}
+
+// Scalar form (any C; the first layer with 3 input channels): one thread per (row, column < Kp).
+__global__ __launch_bounds__(NT) void im2col1_kernel(const bf16_t* __restrict__ x, int64_t rows, int H, int W, int C,
+                                                     bf16_t* __restrict__ cols, int Kp) {
+  const int64_t idx = (int64_t)blockIdx.x * NT + threadIdx.x;
+  if (idx >= rows * Kp) return;
+  const int64_t r = idx / Kp;
+  const int k = (int)(idx - r * Kp);
+  bf16_t v = 0;
+  if (k < 9 * C) {
+    const int tap = k / C, c = k - tap * C;
+    const int kh = tap / 3, kw = tap - 3 * kh;
+    const int w = (int)(r % W);
+    const int h = (int)((r / W) % H);
+    const int hh = h + kh - 1, ww = w + kw - 1;
+    if (hh >= 0 && hh < H && ww >= 0 && ww < W) v = x[(r + (int64_t)(kh - 1) * W + (kw - 1)) * C + c];
+  }
+  cols[idx] = v;
+}
+
+// ---- filter copies ----------------------------------------------------------------------------
+// nat[o, k] = bf16(Wf[o, k]) for k < 9*Cin (row pitch Kp; the padding stays as it is: zero);
+// flip[c, (2-kh)*3*Cout + (2-kw)*Cout + o] = bf16(Wf[o, kh, kw, c]): the filters of the input
+// gradient, which is the 3x3 convolution of the output gradient with the filters turned by 180
+// degrees and input/output channels exchanged (row pitch Kpf).
+__global__ __launch_bounds__(NT) void conv_weight_copies_kernel(const float* __restrict__ Wf, int Cout, int Cin,
+                                                                bf16_t* __restrict__ nat, int Kp,
+                                                                bf16_t* __restrict__ flip, int Kpf) {
+  const int K = 9 * Cin;
+  const int idx = blockIdx.x * NT + threadIdx.x;
+  if (idx >= Cout * K) return;
+  const int o = idx / K, k = idx - o * K;
+  const bf16_t v = f32_to_bf16(Wf[idx]);
+  nat[(int64_t)o * Kp + k] = v;
+  if (flip) {
+    const int tap = k / Cin, c = k - tap * Cin;
+    const int kh = tap / 3, kw = tap - 3 * kh;
+    flip[(int64_t)c * Kpf + ((2 - kh) * 3 + (2 - kw)) * Cout + o] = v;
+  }
+}
+
+// ---- tall column reductions --------------------------------------------------------------------
+// A workgroup owns CHUNK consecutive rows; a thread owns 4 consecutive columns (float4) of every
+// RL-th row: NT threads = C/4 column groups x RL row lanes (C in {8, 16, 32, 64, 128, 256} uses
+// all 256 threads; other C leave the last few idle).  C % 4 == 0, C <= 256.
+constexpr int CHUNK = 256;       // rows per workgroup
+
+struct Tall {
+  int cg;        // column groups of 4 (C / 4)
+  int rl;        // row lanes = NT / cg (at least 1)
+  int passes;    // ceil(CHUNK / rl)
+};
+__device__ __forceinline__ Tall tall_shape(int C) {
+  Tall t;
+  t.cg = C >> 2;
+  t.rl = NT / t.cg;
+  if (t.rl < 1) t.rl = 1;
+  t.passes = (CHUNK + t.rl - 1) / t.rl;
+  return t;
+}
+
+// Combines the row lanes of one column group in lane order; result valid in row lane 0.
+// (Threads past the last row lane take part in the barriers only.)
+__device__ __forceinline__ float4 lanes_sum(float4 v, float4* red, int g, int lane, const Tall& t) {
+  if (lane < t.rl) red[lane * t.cg + g] = v;
+  __syncthreads();
+  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (lane == 0)
+    for (int l = 0; l < t.rl; ++l) {
+      const float4 a = red[l * t.cg + g];
+      s.x += a.x; s.y += a.y; s.z += a.z; s.w += a.w;
+    }
+  __syncthreads();
+  return s;
+}
+
+// Per chunk and column: the mean of the chunk's rows and the sum of squared deviations from it.
+// partial[(chunk*2 + 0)*C + c] = mean, partial[(chunk*2 + 1)*C + c] = M2.
+__global__ __launch_bounds__(NT) void bn2d_stats_partial_kernel(const float* __restrict__ y, int64_t rows, int C,
+                                                                float* __restrict__ partial) {
+  extern __shared__ float4 red[];
+  const Tall t = tall_shape(C);
+  const int g = threadIdx.x % t.cg, lane = threadIdx.x / t.cg;
+  const bool active = lane < t.rl;
+  const int64_t r0 = (int64_t)blockIdx.x * CHUNK;
+  const int n = (int)min((int64_t)CHUNK, rows - r0);
+  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (active)
+    for (int p = 0; p < t.passes; ++p) {
+      const int rr = lane + p * t.rl;
+      if (rr < n) {
+        const float4 v = *reinterpret_cast<const float4*>(&y[(r0 + rr) * C + 4 * g]);
+        s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+      }
+    }
+  __shared__ float4 mean_s[64];
+  float4 tot = lanes_sum(s, red, g, lane, t);
+  if (lane == 0) {
+    const float inv = 1.f / (float)n;
+    mean_s[g] = make_float4(tot.x * inv, tot.y * inv, tot.z * inv, tot.w * inv);
+  }
+  __syncthreads();
+  const float4 m = mean_s[g];
+  float4 q = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (active)
+    for (int p = 0; p < t.passes; ++p) {
+      const int rr = lane + p * t.rl;
+      if (rr < n) {
+        const float4 v = *reinterpret_cast<const float4*>(&y[(r0 + rr) * C + 4 * g]);   // second read: cache
+        const float dx = v.x - m.x, dy = v.y - m.y, dz = v.z - m.z, dw = v.w - m.w;
+        q.x = fmaf(dx, dx, q.x); q.y = fmaf(dy, dy, q.y); q.z = fmaf(dz, dz, q.z); q.w = fmaf(dw, dw, q.w);
+      }
+    }
+  const float4 m2 = lanes_sum(q, red, g, lane, t);
+  if (lane == 0) {
+    *reinterpret_cast<float4*>(&partial[((int64_t)blockIdx.x * 2 + 0) * C + 4 * g]) = m;
+    *reinterpret_cast<float4*>(&partial[((int64_t)blockIdx.x * 2 + 1) * C + 4 * g]) = m2;
+  }
+}
+
+// Chunks combined in chunk order (the pairwise update of mean and summed squared deviations for
+// two groups of rows): mean and biased variance over all rows; rstd; moving statistics of this
+// device blended once per pass (Section 4.1).
+__global__ __launch_bounds__(NT) void bn2d_stats_finish_kernel(const float* __restrict__ partial, int nchunk,
+                                                               int64_t rows, int C, float eps,
+                                                               float* __restrict__ mean_out, float* __restrict__ rstd_out,
+                                                               float* __restrict__ run_mean, float* __restrict__ run_var,
+                                                               float run_mix) {
+  const int c = blockIdx.x * NT + threadIdx.x;
+  if (c >= C) return;
+  float mean = 0.f, m2 = 0.f, cnt = 0.f;
+  for (int k = 0; k < nchunk; ++k) {
+    const float nb = (float)min((int64_t)CHUNK, rows - (int64_t)k * CHUNK);
+    const float mb = partial[((int64_t)k * 2 + 0) * C + c];
+    const float qb = partial[((int64_t)k * 2 + 1) * C + c];
+    const float tot = cnt + nb;
+    const float delta = mb - mean;
+    mean = fmaf(delta, nb / tot, mean);
+    m2 = m2 + qb + delta * delta * (cnt * nb / tot);
+    cnt = tot;
+  }
+  const float var = m2 / cnt;
+  mean_out[c] = mean;
+  rstd_out[c] = 1.0f / sqrtf(var + eps);
+  if (run_mean) {
+    run_mean[c] = fmaf(run_mix, mean - run_mean[c], run_mean[c]);
+    run_var[c] = fmaf(run_mix, var - run_var[c], run_var[c]);
+  }
+}
+
+__device__ __forceinline__ float4 unpack4(uint2 p) {
+  return make_float4(bf16_to_f32((bf16_t)(p.x & 0xffffu)), bf16_to_f32((bf16_t)(p.x >> 16)),
+                     bf16_to_f32((bf16_t)(p.y & 0xffffu)), bf16_to_f32((bf16_t)(p.y >> 16)));
+}
+__device__ __forceinline__ uint2 pack4(float4 v) {
+  uint2 p;
+  p.x = (uint32_t)f32_to_bf16(v.x) | ((uint32_t)f32_to_bf16(v.y) << 16);
+  p.y = (uint32_t)f32_to_bf16(v.z) | ((uint32_t)f32_to_bf16(v.w) << 16);
+  return p;
+}
+
+// a = relu(gamma * (y - mean) * rstd + beta (+ skip)), stored bf16; one float4 of y per thread.
+__global__ __launch_bounds__(NT) void bn2d_apply_fwd_kernel(const float* __restrict__ y, int64_t n4, int C,
+                                                            const float* __restrict__ gamma, const float* __restrict__ beta,
+                                                            int round_params, const float* __restrict__ mean,
+                                                            const float* __restrict__ rstd, const bf16_t* __restrict__ skip,
+                                                            bf16_t* __restrict__ a) {
+  const int64_t i = (int64_t)blockIdx.x * NT + threadIdx.x;
+  if (i >= n4) return;
+  const int c = (int)((i * 4) % C);
+  const float4 v = reinterpret_cast<const float4*>(y)[i];
+  float4 g = *reinterpret_cast<const float4*>(&gamma[c]);
+  float4 b = *reinterpret_cast<const float4*>(&beta[c]);
+  const float4 m = *reinterpret_cast<const float4*>(&mean[c]);
+  const float4 r = *reinterpret_cast<const float4*>(&rstd[c]);
+  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (skip) s = unpack4(reinterpret_cast<const uint2*>(skip)[i]);
+  if (round_params) {
+    g.x = round_bf16(g.x); g.y = round_bf16(g.y); g.z = round_bf16(g.z); g.w = round_bf16(g.w);
+    b.x = round_bf16(b.x); b.y = round_bf16(b.y); b.z = round_bf16(b.z); b.w = round_bf16(b.w);
+  }
+  float4 o;
+  o.x = fmaxf(fmaf(g.x, (v.x - m.x) * r.x, b.x) + s.x, 0.f);
+  o.y = fmaxf(fmaf(g.y, (v.y - m.y) * r.y, b.y) + s.y, 0.f);
+  o.z = fmaxf(fmaf(g.z, (v.z - m.z) * r.z, b.z) + s.z, 0.f);
+  o.w = fmaxf(fmaf(g.w, (v.w - m.w) * r.w, b.w) + s.w, 0.f);
+  reinterpret_cast<uint2*>(a)[i] = pack4(o);
+}
+
+// Backward, step 1: per chunk and column, the sums over the chunk's rows of dpre and of
+// dpre * xhat, with dpre = da where the ReLU was open (its stored output a > 0) and
+// xhat = (y - mean) * rstd.  partial[(chunk*2 + 0)*C + c] = sum dpre, [.. + 1 ..] = sum dpre*xhat.
+__global__ __launch_bounds__(NT) void bn2d_bwd_partial_kernel(const float* __restrict__ da, const bf16_t* __restrict__ a,
+                                                              const float* __restrict__ y, int64_t rows, int C,
+                                                              const float* __restrict__ mean, const float* __restrict__ rstd,
+                                                              float* __restrict__ partial) {
+  extern __shared__ float4 red[];
+  const Tall t = tall_shape(C);
+  const int g = threadIdx.x % t.cg, lane = threadIdx.x / t.cg;
+  const bool active = lane < t.rl;
+  const int64_t r0 = (int64_t)blockIdx.x * CHUNK;
+  const int n = (int)min((int64_t)CHUNK, rows - r0);
+  const float4 m = *reinterpret_cast<const float4*>(&mean[4 * g]);
+  const float4 rs = *reinterpret_cast<const float4*>(&rstd[4 * g]);
+  float4 sb = make_float4(0.f, 0.f, 0.f, 0.f), sg = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (active)
+    for (int p = 0; p < t.passes; ++p) {
+      const int rr = lane + p * t.rl;
+      if (rr < n) {
+        const int64_t at = (r0 + rr) * C + 4 * g;
+        const float4 d = *reinterpret_cast<const float4*>(&da[at]);
+        const float4 v = *reinterpret_cast<const float4*>(&y[at]);
+        const float4 o = unpack4(*reinterpret_cast<const uint2*>(&a[at]));
+        const float dx = o.x > 0.f ? d.x : 0.f, dy = o.y > 0.f ? d.y : 0.f;
+        const float dz = o.z > 0.f ? d.z : 0.f, dw = o.w > 0.f ? d.w : 0.f;
+        sb.x += dx; sb.y += dy; sb.z += dz; sb.w += dw;
+        sg.x = fmaf(dx, (v.x - m.x) * rs.x, sg.x); sg.y = fmaf(dy, (v.y - m.y) * rs.y, sg.y);
+        sg.z = fmaf(dz, (v.z - m.z) * rs.z, sg.z); sg.w = fmaf(dw, (v.w - m.w) * rs.w, sg.w);
+      }
+    }
+  const float4 tb = lanes_sum(sb, red, g, lane, t);
+  const float4 tg = lanes_sum(sg, red, g, lane, t);
+  if (lane == 0) {
+    *reinterpret_cast<float4*>(&partial[((int64_t)blockIdx.x * 2 + 0) * C + 4 * g]) = tb;
+    *reinterpret_cast<float4*>(&partial[((int64_t)blockIdx.x * 2 + 1) * C + 4 * g]) = tg;
+  }
+}
+
+// Step 2: chunks added in chunk order; the sums go to sums[0][c] (dbeta) and sums[1][c] (dgamma)
+// for the apply kernel, and, weighted, into the gradient (Section 3.2 step 3, Section 5.2).
+__global__ __launch_bounds__(NT) void bn2d_bwd_finish_kernel(const float* __restrict__ partial, int nchunk, int C,
+                                                             float* __restrict__ sums, GradOut gout_g, GradOut gout_b) {
+  const int c = blockIdx.x * NT + threadIdx.x;
+  if (c >= C) return;
+  float sb = 0.f, sg = 0.f;
+  for (int k = 0; k < nchunk; ++k) {
+    sb += partial[((int64_t)k * 2 + 0) * C + c];
+    sg += partial[((int64_t)k * 2 + 1) * C + c];
+  }
+  sums[c] = sb;
+  sums[C + c] = sg;
+  grad_store(gout_b, c, sb);
+  grad_store(gout_g, c, sg);
+}
+
+// Step 3: dy = gamma * rstd * (dpre - sum_b/R - xhat * sum_g/R), stored bf16 (operand of the
+// backward products); with keep_dpre the masked gradient dpre replaces da (it also flows through
+// the skip connection).
+__global__ __launch_bounds__(NT) void bn2d_bwd_apply_kernel(float* __restrict__ da, const bf16_t* __restrict__ a,
+                                                            const float* __restrict__ y, int64_t n4, int C, float inv_rows,
+                                                            const float* __restrict__ gamma, int round_params,
+                                                            const float* __restrict__ mean, const float* __restrict__ rstd,
+                                                            const float* __restrict__ sums, int keep_dpre,
+                                                            bf16_t* __restrict__ dy) {
+  const int64_t i = (int64_t)blockIdx.x * NT + threadIdx.x;
+  if (i >= n4) return;
+  const int c = (int)((i * 4) % C);
+  const float4 d = reinterpret_cast<const float4*>(da)[i];
+  const float4 v = reinterpret_cast<const float4*>(y)[i];
+  const float4 o = unpack4(reinterpret_cast<const uint2*>(a)[i]);
+  float4 g = *reinterpret_cast<const float4*>(&gamma[c]);
+  const float4 m = *reinterpret_cast<const float4*>(&mean[c]);
+  const float4 r = *reinterpret_cast<const float4*>(&rstd[c]);
+  const float4 sb = *reinterpret_cast<const float4*>(&sums[c]);
+  const float4 sg = *reinterpret_cast<const float4*>(&sums[C + c]);
+  if (round_params) { g.x = round_bf16(g.x); g.y = round_bf16(g.y); g.z = round_bf16(g.z); g.w = round_bf16(g.w); }
+  float4 dp;
+  dp.x = o.x > 0.f ? d.x : 0.f; dp.y = o.y > 0.f ? d.y : 0.f;
+  dp.z = o.z > 0.f ? d.z : 0.f; dp.w = o.w > 0.f ? d.w : 0.f;
+  float4 out;
+  out.x = g.x * r.x * (dp.x - sb.x * inv_rows - (v.x - m.x) * r.x * sg.x * inv_rows);
+  out.y = g.y * r.y * (dp.y - sb.y * inv_rows - (v.y - m.y) * r.y * sg.y * inv_rows);
+  out.z = g.z * r.z * (dp.z - sb.z * inv_rows - (v.z - m.z) * r.z * sg.z * inv_rows);
+  out.w = g.w * r.w * (dp.w - sb.w * inv_rows - (v.w - m.w) * r.w * sg.w * inv_rows);
+  reinterpret_cast<uint2*>(dy)[i] = pack4(out);
+  if (keep_dpre) reinterpret_cast<float4*>(da)[i] = dp;
+}
+
+// ---- mean over the positions of an image -------------------------------------------------------
+// pooled[n, c] = (1/HW) sum_p a[n, p, c], stored bf16 (operand of the classifier's product).
+// One workgroup per image: threads = C/4 column groups x row lanes, lanes combined in order.
+__global__ __launch_bounds__(NT) void avgpool_fwd_kernel(const bf16_t* __restrict__ a, int HW, int C,
+                                                         bf16_t* __restrict__ pooled, int64_t ldp) {
+  extern __shared__ float4 red[];
+  Tall t = tall_shape(C);
+  const int g = threadIdx.x % t.cg, lane = threadIdx.x / t.cg;
+  const bool active = lane < t.rl;
+  const int64_t base = (int64_t)blockIdx.x * HW * C;
+  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (active)
+    for (int p = lane; p < HW; p += t.rl) {
+      const float4 v = unpack4(*reinterpret_cast<const uint2*>(&a[base + (int64_t)p * C + 4 * g]));
+      s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+    }
+  const float4 tot = lanes_sum(s, red, g, lane, t);
+  if (lane == 0) {
+    const float inv = 1.f / (float)HW;
+    *reinterpret_cast<uint2*>(&pooled[(int64_t)blockIdx.x * ldp + 4 * g]) =
+        pack4(make_float4(tot.x * inv, tot.y * inv, tot.z * inv, tot.w * inv));
+  }
+}
+
+// da[n, p, c] = dpooled[n, c] / HW.
+__global__ __launch_bounds__(NT) void avgpool_bwd_kernel(const float* __restrict__ dpooled, int64_t ldd, int HW, int C,
+                                                         int64_t n4, float* __restrict__ da) {
+  const int64_t i = (int64_t)blockIdx.x * NT + threadIdx.x;
+  if (i >= n4) return;
+  const int64_t e = i * 4;
+  const int c = (int)(e % C);
+  const int64_t img = e / ((int64_t)HW * C);
+  const float inv = 1.f / (float)HW;
+  const float4 d = *reinterpret_cast<const float4*>(&dpooled[img * ldd + c]);
+  reinterpret_cast<float4*>(da)[i] = make_float4(d.x * inv, d.y * inv, d.z * inv, d.w * inv);
+}
+
+// ---- contraction slabs folded into a gradient ----------------------------------------------------
+// out[p] (+)= alpha * (slab_0[p] + slab_1[p] + ...), slabs in order.
+__global__ __launch_bounds__(NT) void fold_slabs_kernel(const float* __restrict__ slabs, int nsplit, int64_t stride,
+                                                        int64_t n, GradOut out) {
+  const int64_t i = (int64_t)blockIdx.x * NT + threadIdx.x;
+  if (i >= n) return;
+  float v = slabs[i];
+  for (int s = 1; s < nsplit; ++s) v += slabs[(int64_t)s * stride + i];
+  grad_store(out, i, v);
+}
+
+inline int64_t blocks(int64_t n) { return (n + NT - 1) / NT; }
+inline bool tall_ok(int C) { return C >= 8 && C <= 256 && (C & 3) == 0; }
+inline size_t tall_lds(int C) {
+  const int cg = C >> 2;
+  const int rl = NT / cg < 1 ? 1 : NT / cg;
+  return (size_t)cg * rl * sizeof(float4);
+}
+
+}  // namespace
+
+int conv_chunks(int64_t rows) { return (int)((rows + CHUNK - 1) / CHUNK); }
+
+int launch_im2col3x3(const bf16_t* x, int64_t rows, int H, int W, int C, bf16_t* cols, int64_t Kp, hipStream_t s) {
+  if (rows <= 0 || H <= 0 || W <= 0 || C <= 0 || Kp < 9 * C || (Kp & 7) || rows % ((int64_t)H * W)) return VF_EINVAL;
+  if ((C & 7) == 0 && Kp == 9 * C && (reinterpret_cast<uintptr_t>(x) & 15) == 0 && (reinterpret_cast<uintptr_t>(cols) & 15) == 0) {
+    im2col8_kernel<<<(unsigned)blocks(rows * 9 * (C >> 3)), NT, 0, s>>>(x, rows, H, W, C, cols, Kp);
+  } else {
+    im2col1_kernel<<<(unsigned)blocks(rows * Kp), NT, 0, s>>>(x, rows, H, W, C, cols, (int)Kp);
+  }
+  VF_LAUNCH_CHECK();
+  return VF_OK;
+}
+
+int launch_conv_weight_copies(const float* Wf, int Cout, int Cin, bf16_t* nat, int Kp, bf16_t* flip, int Kpf,
+                              hipStream_t s) {
+  if (Cout <= 0 || Cin <= 0 || Kp < 9 * Cin || (flip && Kpf < 9 * Cout)) return VF_EINVAL;
+  conv_weight_copies_kernel<<<(unsigned)blocks((int64_t)Cout * 9 * Cin), NT, 0, s>>>(Wf, Cout, Cin, nat, Kp, flip, Kpf);
+  VF_LAUNCH_CHECK();
+  return VF_OK;
+}
+
+int launch_bn2d_stats(const float* y, int64_t rows, int C, float eps, float* partial, float* mean, float* rstd,
+                      float* run_mean, float* run_var, float run_mix, hipStream_t s) {
+  if (rows <= 0 || !tall_ok(C) || !partial) return VF_EINVAL;
+  if ((run_mean == nullptr) != (run_var == nullptr)) return VF_EINVAL;
+  const int nchunk = conv_chunks(rows);
+  bn2d_stats_partial_kernel<<<nchunk, NT, tall_lds(C), s>>>(y, rows, C, partial);
+  VF_LAUNCH_CHECK();
+  bn2d_stats_finish_kernel<<<(C + NT - 1) / NT, NT, 0, s>>>(partial, nchunk, rows, C, eps, mean, rstd, run_mean,
+                                                            run_var, run_mix);
+  VF_LAUNCH_CHECK();
+  return VF_OK;
+}
+
+int launch_bn2d_apply_fwd(const float* y, int64_t rows, int C, const float* gamma, const float* beta, int round_params,
+                          const float* mean, const float* rstd, const bf16_t* skip, bf16_t* a, hipStream_t s) {
+  if (rows <= 0 || !tall_ok(C)) return VF_EINVAL;
+  const int64_t n4 = rows * C / 4;
+  bn2d_apply_fwd_kernel<<<(unsigned)blocks(n4), NT, 0, s>>>(y, n4, C, gamma, beta, round_params, mean, rstd, skip, a);
+  VF_LAUNCH_CHECK();
+  return VF_OK;
+}
+
+int launch_bn2d_bwd(float* da, const bf16_t* a, const float* y, int64_t rows, int C, const float* gamma,
+                    int round_params, const float* mean, const float* rstd, float* partial, float* sums,
+                    int keep_dpre, bf16_t* dy, GradOut gout_g, GradOut gout_b, hipStream_t s) {
+  if (rows <= 0 || !tall_ok(C) || !partial || !sums) return VF_EINVAL;
+  const int nchunk = conv_chunks(rows);
+  bn2d_bwd_partial_kernel<<<nchunk, NT, tall_lds(C), s>>>(da, a, y, rows, C, mean, rstd, partial);
+  VF_LAUNCH_CHECK();
+  bn2d_bwd_finish_kernel<<<(C + NT - 1) / NT, NT, 0, s>>>(partial, nchunk, C, sums, gout_g, gout_b);
+  VF_LAUNCH_CHECK();
+  const int64_t n4 = rows * C / 4;
+  bn2d_bwd_apply_kernel<<<(unsigned)blocks(n4), NT, 0, s>>>(da, a, y, n4, C, 1.0f / (float)rows, gamma, round_params,
+                                                            mean, rstd, sums, keep_dpre, dy);
+  VF_LAUNCH_CHECK();
+  return VF_OK;
+}
+
+int launch_avgpool_fwd(const bf16_t* a, int n_img, int HW, int C, bf16_t* pooled, int64_t ldp, hipStream_t s) {
+  if (n_img <= 0 || HW <= 0 || !tall_ok(C) || ldp < C || (ldp & 3)) return VF_EINVAL;
+  avgpool_fwd_kernel<<<n_img, NT, tall_lds(C), s>>>(a, HW, C, pooled, ldp);
+  VF_LAUNCH_CHECK();
+  return VF_OK;
+}
+
+int launch_avgpool_bwd(const float* dpooled, int64_t ldd, int n_img, int HW, int C, float* da, hipStream_t s) {
+  if (n_img <= 0 || HW <= 0 || !tall_ok(C) || ldd < C || (ldd & 3)) return VF_EINVAL;
+  const int64_t n4 = (int64_t)n_img * HW * C / 4;
+  avgpool_bwd_kernel<<<(unsigned)blocks(n4), NT, 0, s>>>(dpooled, ldd, HW, C, n4, da);
+  VF_LAUNCH_CHECK();
+  return VF_OK;
+}
+
+int launch_fold_slabs(const float* slabs, int nsplit, int64_t stride, int64_t n, GradOut out, hipStream_t s) {
+  if (n <= 0 || nsplit < 1 || !slabs || !out.dst) return VF_EINVAL;
+  fold_slabs_kernel<<<(unsigned)blocks(n), NT, 0, s>>>(slabs, nsplit, stride, n, out);
+  VF_LAUNCH_CHECK();
+  return VF_OK;
+}
+
+}  // namespace vf

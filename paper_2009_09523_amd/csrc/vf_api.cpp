@@ -59,6 +59,12 @@ int validate_config(const vf_config& c) {
       return VF_EINVAL;
     return VF_OK;
   }
+  if (c.model_kind == VF_CONV) {
+    if (c.dtype != VF_BF16) return VF_EINVAL;
+    if (c.img < 1 || c.img > 1024 || c.in_ch < 1 || c.n_blocks < 0 || c.n_blocks > 64 || c.classes < 1) return VF_EINVAL;
+    if (c.width < 8 || c.width > 256 || (c.width % 8)) return VF_EINVAL;
+    return VF_OK;
+  }
   return VF_EINVAL;
 }
 
@@ -102,10 +108,11 @@ void release_prefetch(Ctx& c) {
 // Bytes of one batch of B samples as vf_step reads it.
 size_t batch_x_bytes(const vf_config& f, int64_t B) {
   if (f.model_kind == VF_MLP) return (size_t)B * f.dims[0] * (f.dtype == VF_BF16 ? 2 : 4);
+  if (f.model_kind == VF_CONV) return (size_t)B * f.img * f.img * f.in_ch * 2;
   return (size_t)B * f.seq_len * sizeof(int32_t);
 }
 size_t batch_y_bytes(const vf_config& f, int64_t B) {
-  if (f.model_kind == VF_MLP) return (size_t)B * sizeof(int32_t);
+  if (f.model_kind != VF_ENCODER) return (size_t)B * sizeof(int32_t);
   return (size_t)B * 2 * f.n_masked * sizeof(int32_t);
 }
 
@@ -364,7 +371,7 @@ int vf_init(const vf_config* cfg, vf_ctx** out) {
     delete h;
     return VF_EDEVICE;
   }
-  c.model = cfg->model_kind == VF_MLP ? make_mlp(*cfg) : make_encoder(*cfg);
+  c.model = cfg->model_kind == VF_MLP ? make_mlp(*cfg) : cfg->model_kind == VF_CONV ? make_conv(*cfg) : make_encoder(*cfg);
   if (!c.model) { delete h; return VF_EINVAL; }
   c.P = c.model->num_params();
   // Overlap needs a capturable main stream and a model that double-buffers what the side

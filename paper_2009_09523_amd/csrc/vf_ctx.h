@@ -223,6 +223,7 @@ struct Ctx {
 
 std::unique_ptr<Model> make_mlp(const vf_config& cfg);
 std::unique_ptr<Model> make_encoder(const vf_config& cfg);
+std::unique_ptr<Model> make_conv(const vf_config& cfg);
 
 }  // namespace vf
 

@@ -160,6 +160,31 @@ int launch_rowsum_bf16(const bf16_t* x, int64_t ld, int R, int C, GradOut out, h
 int launch_colsum(const void* x, int64_t ld, int x_is_bf16, int R, int C, GradOut out,
                   hipStream_t s);
 
+// k_conv.hip -- the convolutional family: 3x3 convolutions (stride 1, zero padding 1, NHWC) as
+// products over patch rows, BatchNorm over a node's n*H*W positions in chunks of rows.
+int conv_chunks(int64_t rows);     // row chunks of the tall reductions: sizes their partial buffers (2*C floats each)
+// cols[r, (kh*3+kw)*C + c] = x[n, h+kh-1, w+kw-1, c] or 0; row pitch Kp >= 9C, a multiple of 8
+int launch_im2col3x3(const bf16_t* x, int64_t rows, int H, int W, int C, bf16_t* cols, int64_t Kp, hipStream_t s);
+// bf16 copies of fp32 filters [Cout, 3, 3, Cin]: as they are (row pitch Kp) and, if flip != null,
+// turned by 180 degrees with the channel roles exchanged, [Cin, 3, 3, Cout] (row pitch Kpf)
+int launch_conv_weight_copies(const float* Wf, int Cout, int Cin, bf16_t* nat, int Kp, bf16_t* flip, int Kpf,
+                              hipStream_t s);
+// per-column mean and 1/sqrt(biased variance + eps) of y [rows, C]; moving statistics blended
+int launch_bn2d_stats(const float* y, int64_t rows, int C, float eps, float* partial, float* mean, float* rstd,
+                      float* run_mean, float* run_var, float run_mix, hipStream_t s);
+// a = relu(gamma * (y - mean) * rstd + beta (+ skip)) as bf16
+int launch_bn2d_apply_fwd(const float* y, int64_t rows, int C, const float* gamma, const float* beta, int round_params,
+                          const float* mean, const float* rstd, const bf16_t* skip, bf16_t* a, hipStream_t s);
+// backward of the above given da (gradient w.r.t. a): dgamma, dbeta into the gradient; dy (bf16)
+// the gradient w.r.t. y; with keep_dpre, da is replaced by the gradient w.r.t. the ReLU's input
+int launch_bn2d_bwd(float* da, const bf16_t* a, const float* y, int64_t rows, int C, const float* gamma,
+                    int round_params, const float* mean, const float* rstd, float* partial, float* sums,
+                    int keep_dpre, bf16_t* dy, GradOut gout_g, GradOut gout_b, hipStream_t s);
+int launch_avgpool_fwd(const bf16_t* a, int n_img, int HW, int C, bf16_t* pooled, int64_t ldp, hipStream_t s);
+int launch_avgpool_bwd(const float* dpooled, int64_t ldd, int n_img, int HW, int C, float* da, hipStream_t s);
+// out (+)= alpha * (slab 0 + slab 1 + ...), slabs in order
+int launch_fold_slabs(const float* slabs, int nsplit, int64_t stride, int64_t n, GradOut out, hipStream_t s);
+
 // k_loss.hip
 // Softmax cross-entropy over R rows of fp32 logits with C classes.  zp: nsplit partial slabs
 // of the logits (summed into z, which may be slab 0 itself):

@@ -61,7 +61,7 @@ def test_zero_share_freezes_the_moving_statistics():
     assert np.all(st["bn_mean"] == 0.0) and np.all(st["bn_var"] == 1.0)
 
 
-@pytest.mark.parametrize("name", ["mlp_mid_bn_bf16", "mlp_small_f32", "enc_tiny_f32"])
+@pytest.mark.parametrize("name", ["mlp_mid_bn_bf16", "mlp_small_f32", "enc_tiny_f32", "conv_small_bf16"])
 def test_export_import_round_trip_continues_bitwise(name):
     """Two steps, export, two more steps -- against a fresh context that imports the payload
     (through a device buffer) and runs the same two steps: identical bits everywhere."""

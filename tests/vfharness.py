@@ -13,7 +13,7 @@ TOL = {"f32": 1e-4, "bf16": 2e-2}
 
 def to_device_batch(wl, x, y, device="cuda"):
     import torch
-    if wl.kind == "mlp":
+    if wl.kind in ("mlp", "conv"):
         xt = torch.from_numpy(x).to(device)
         if wl.dtype == "bf16":
             xt = xt.to(torch.bfloat16)          # exact: the generator made x bf16-representable
