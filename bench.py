@@ -47,6 +47,24 @@ def algorithmic_work(wl, P, fused=False, window=1):
         work["gemm_dgrad"] = (V * sum(k * n for k, n in mats[1:]) * esz + act, dgr_fl, V * (len(mats) - 1))
         work["gemm_wgrad"] = (wg * W + act, fwd_fl, nwin * len(mats))
         work["cast_weight"] = (W * (4 + 2 * esz), 0, len(mats))
+    elif wl.kind == "conv":
+        # a 3x3 convolution as a product over patch rows: per position 2 * 9 Cin * Cout flops; the
+        # method needs the activations in (bf16) and out (fp32) once and the filters once per launch
+        HW, C = wl.img * wl.img, wl.width
+        convs = [(wl.in_ch, C)] + [(C, C)] * (2 * wl.n_blocks)
+        R = B * HW
+        fl = sum(2 * R * 9 * ci * co for ci, co in convs)
+        fl_d = sum(2 * R * 9 * ci * co for ci, co in convs[1:])
+        wbytes = sum(9 * ci * co * esz for ci, co in convs)
+        act = sum(R * (ci * esz + co * 4) for ci, co in convs)
+        act_d = sum(R * (co * esz + ci * 4) for ci, co in convs[1:])
+        work["gemm_fwd"] = (V * wbytes + act, fl, V * len(convs))
+        work["gemm_dgrad"] = (V * wbytes + act_d, fl_d, V * (len(convs) - 1))
+        work["gemm_wgrad"] = (sum(R * (ci + co) * esz for ci, co in convs) + wg * sum(9 * ci * co for ci, co in convs),
+                              fl, V * len(convs))
+        # element-wise passes over [positions, C]: statistics + apply forward, reduce + apply backward
+        work["bn_apply"] = (R * C * (4 + esz) * len(convs), 0, V * len(convs))
+        work["bn_bwd"] = (R * C * (2 * (4 + 4 + esz) + esz) * len(convs), 0, V * len(convs))
     else:
         d, f, T, Vc, m, nl = wl.d_model, wl.d_ffn, wl.seq_len, wl.vocab, wl.n_masked, wl.n_layers
         R, Rm = B * T, B * m                       # tokens and masked rows per step
@@ -149,7 +167,7 @@ def time_steps(vf, torch, wl, theta, x, y, flags, steps, warmup, max_node_size=N
                                                   fold_window=fold_window))
     params = torch.from_numpy(theta).cuda()
     xt = torch.from_numpy(x).cuda()
-    if wl.kind == "mlp" and wl.dtype == "bf16":
+    if wl.kind in ("mlp", "conv") and wl.dtype == "bf16":
         xt = xt.to(torch.bfloat16)
     yt = torch.from_numpy(y).cuda()
     sizes = list(wl.node_sizes)
@@ -311,7 +329,7 @@ def main():
     window = eng.fold_window                      # the window in effect (1 where no windowed path exists)
     params = torch.from_numpy(theta).cuda()
     xt = torch.from_numpy(x).cuda()
-    if wl.kind == "mlp" and wl.dtype == "bf16":
+    if wl.kind in ("mlp", "conv") and wl.dtype == "bf16":
         xt = xt.to(torch.bfloat16)
     yt = torch.from_numpy(y).cuda()
     sizes = list(wl.node_sizes)
@@ -347,10 +365,12 @@ def main():
         "dtype": "bf16" if wl.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": wl.name, "model": wl.kind, "dims": list(wl.dims) if wl.kind == "mlp" else None,
                    "batchnorm": bool(wl.batchnorm),
-                   "encoder": None if wl.kind == "mlp" else {"layers": wl.n_layers, "d_model": wl.d_model,
-                                                             "heads": wl.n_heads, "d_ffn": wl.d_ffn,
-                                                             "seq_len": wl.seq_len, "vocab": wl.vocab,
-                                                             "masked_per_seq": wl.n_masked},
+                   "encoder": None if wl.kind != "encoder" else {"layers": wl.n_layers, "d_model": wl.d_model,
+                                                                 "heads": wl.n_heads, "d_ffn": wl.d_ffn,
+                                                                 "seq_len": wl.seq_len, "vocab": wl.vocab,
+                                                                 "masked_per_seq": wl.n_masked},
+                   "conv": None if wl.kind != "conv" else {"img": wl.img, "in_ch": wl.in_ch, "width": wl.width,
+                                                           "blocks": wl.n_blocks, "classes": wl.classes},
                    "global_batch": wl.batch, "virtual_nodes": wl.n_nodes,
                    "node_sizes": sizes if len(set(sizes)) > 1 else f"{wl.n_nodes}x{sizes[0]}",
                    "optimizer": wl.optimizer, "params": P, "accumulate": args.accumulate,

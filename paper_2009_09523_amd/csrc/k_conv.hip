@@ -116,27 +116,35 @@ __device__ __forceinline__ float4 lanes_sum(float4 v, float4* red, int g, int la
   return s;
 }
 
+// Rows of a chunk are read PB per thread at a time, at clamped (always valid) row indices and
+// ahead of the selection, so that PB loads per operand are in flight per thread.
+constexpr int PB = 8;
+
 // Per chunk and column: the mean of the chunk's rows and the sum of squared deviations from it.
 // partial[(chunk*2 + 0)*C + c] = mean, partial[(chunk*2 + 1)*C + c] = M2.
 __global__ __launch_bounds__(NT) void bn2d_stats_partial_kernel(const float* __restrict__ y, int64_t rows, int C,
                                                                 float* __restrict__ partial) {
   extern __shared__ float4 red[];
+  __shared__ float4 mean_s[64];
   const Tall t = tall_shape(C);
   const int g = threadIdx.x % t.cg, lane = threadIdx.x / t.cg;
   const bool active = lane < t.rl;
   const int64_t r0 = (int64_t)blockIdx.x * CHUNK;
   const int n = (int)min((int64_t)CHUNK, rows - r0);
+  const float* yb = y + r0 * C + 4 * g;
   float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-  if (active)
-    for (int p = 0; p < t.passes; ++p) {
-      const int rr = lane + p * t.rl;
-      if (rr < n) {
-        const float4 v = *reinterpret_cast<const float4*>(&y[(r0 + rr) * C + 4 * g]);
-        s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+  for (int p0 = 0; p0 < t.passes; p0 += PB) {
+    float4 v[PB];
+#pragma unroll
+    for (int u = 0; u < PB; ++u)
+      v[u] = *reinterpret_cast<const float4*>(&yb[(int64_t)min(lane + (p0 + u) * t.rl, n - 1) * C]);
+#pragma unroll
+    for (int u = 0; u < PB; ++u)
+      if (active && p0 + u < t.passes && lane + (p0 + u) * t.rl < n) {
+        s.x += v[u].x; s.y += v[u].y; s.z += v[u].z; s.w += v[u].w;
       }
-    }
-  __shared__ float4 mean_s[64];
-  float4 tot = lanes_sum(s, red, g, lane, t);
+  }
+  const float4 tot = lanes_sum(s, red, g, lane, t);
   if (lane == 0) {
     const float inv = 1.f / (float)n;
     mean_s[g] = make_float4(tot.x * inv, tot.y * inv, tot.z * inv, tot.w * inv);
@@ -144,15 +152,18 @@ __global__ __launch_bounds__(NT) void bn2d_stats_partial_kernel(const float* __r
   __syncthreads();
   const float4 m = mean_s[g];
   float4 q = make_float4(0.f, 0.f, 0.f, 0.f);
-  if (active)
-    for (int p = 0; p < t.passes; ++p) {
-      const int rr = lane + p * t.rl;
-      if (rr < n) {
-        const float4 v = *reinterpret_cast<const float4*>(&y[(r0 + rr) * C + 4 * g]);   // second read: cache
-        const float dx = v.x - m.x, dy = v.y - m.y, dz = v.z - m.z, dw = v.w - m.w;
+  for (int p0 = 0; p0 < t.passes; p0 += PB) {            // second read of the chunk: from the caches
+    float4 v[PB];
+#pragma unroll
+    for (int u = 0; u < PB; ++u)
+      v[u] = *reinterpret_cast<const float4*>(&yb[(int64_t)min(lane + (p0 + u) * t.rl, n - 1) * C]);
+#pragma unroll
+    for (int u = 0; u < PB; ++u)
+      if (active && p0 + u < t.passes && lane + (p0 + u) * t.rl < n) {
+        const float dx = v[u].x - m.x, dy = v[u].y - m.y, dz = v[u].z - m.z, dw = v[u].w - m.w;
         q.x = fmaf(dx, dx, q.x); q.y = fmaf(dy, dy, q.y); q.z = fmaf(dz, dz, q.z); q.w = fmaf(dw, dw, q.w);
       }
-    }
+  }
   const float4 m2 = lanes_sum(q, red, g, lane, t);
   if (lane == 0) {
     *reinterpret_cast<float4*>(&partial[((int64_t)blockIdx.x * 2 + 0) * C + 4 * g]) = m;
@@ -160,27 +171,54 @@ __global__ __launch_bounds__(NT) void bn2d_stats_partial_kernel(const float* __r
   }
 }
 
-// Chunks combined in chunk order (the pairwise update of mean and summed squared deviations for
-// two groups of rows): mean and biased variance over all rows; rstd; moving statistics of this
-// device blended once per pass (Section 4.1).
+// The two-group update of a mean and a sum of squared deviations: group B (nb rows, mean mb,
+// deviations qb) joins group A (cnt, mean, m2).
+__device__ __forceinline__ void join_stats(float& cnt, float& mean, float& m2, float nb, float mb, float qb) {
+  if (nb <= 0.f) return;
+  const float tot = cnt + nb;
+  const float delta = mb - mean;
+  mean = fmaf(delta, nb / tot, mean);
+  m2 = m2 + qb + delta * delta * (cnt * nb / tot);
+  cnt = tot;
+}
+
+// Chunks combined in a fixed order: one workgroup, thread = (column, lane); a lane joins a
+// contiguous run of chunks in chunk order, then the lanes are joined in lane order.  Mean and
+// biased variance over all rows; rstd; moving statistics of this device blended once per pass
+// (Section 4.1).  C <= 256.
 __global__ __launch_bounds__(NT) void bn2d_stats_finish_kernel(const float* __restrict__ partial, int nchunk,
                                                                int64_t rows, int C, float eps,
                                                                float* __restrict__ mean_out, float* __restrict__ rstd_out,
                                                                float* __restrict__ run_mean, float* __restrict__ run_var,
                                                                float run_mix) {
-  const int c = blockIdx.x * NT + threadIdx.x;
-  if (c >= C) return;
+  __shared__ float sm[3][NT];
+  const int nl = NT / C;                       // lanes per column
+  const int c = threadIdx.x % C, lane = threadIdx.x / C;
+  const bool active = lane < nl;
+  const int per = (nchunk + nl - 1) / nl;
+  const int k0 = lane * per, k1 = min(nchunk, k0 + per);
   float mean = 0.f, m2 = 0.f, cnt = 0.f;
-  for (int k = 0; k < nchunk; ++k) {
-    const float nb = (float)min((int64_t)CHUNK, rows - (int64_t)k * CHUNK);
-    const float mb = partial[((int64_t)k * 2 + 0) * C + c];
-    const float qb = partial[((int64_t)k * 2 + 1) * C + c];
-    const float tot = cnt + nb;
-    const float delta = mb - mean;
-    mean = fmaf(delta, nb / tot, mean);
-    m2 = m2 + qb + delta * delta * (cnt * nb / tot);
-    cnt = tot;
+  if (active) {
+    int k = k0;
+    for (; k + 3 < k1; k += 4) {               // four chunks' values in flight, joined in order
+      float mb[4], qb[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        mb[u] = partial[((int64_t)(k + u) * 2 + 0) * C + c];
+        qb[u] = partial[((int64_t)(k + u) * 2 + 1) * C + c];
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        join_stats(cnt, mean, m2, (float)min((int64_t)CHUNK, rows - (int64_t)(k + u) * CHUNK), mb[u], qb[u]);
+    }
+    for (; k < k1; ++k)
+      join_stats(cnt, mean, m2, (float)min((int64_t)CHUNK, rows - (int64_t)k * CHUNK),
+                 partial[((int64_t)k * 2 + 0) * C + c], partial[((int64_t)k * 2 + 1) * C + c]);
   }
+  sm[0][threadIdx.x] = cnt; sm[1][threadIdx.x] = mean; sm[2][threadIdx.x] = m2;
+  __syncthreads();
+  if (lane != 0) return;
+  for (int l = 1; l < nl; ++l) join_stats(cnt, mean, m2, sm[0][l * C + c], sm[1][l * C + c], sm[2][l * C + c]);
   const float var = m2 / cnt;
   mean_out[c] = mean;
   rstd_out[c] = 1.0f / sqrtf(var + eps);
@@ -242,24 +280,31 @@ __global__ __launch_bounds__(NT) void bn2d_bwd_partial_kernel(const float* __res
   const bool active = lane < t.rl;
   const int64_t r0 = (int64_t)blockIdx.x * CHUNK;
   const int n = (int)min((int64_t)CHUNK, rows - r0);
+  const int64_t base = r0 * C + 4 * g;
   const float4 m = *reinterpret_cast<const float4*>(&mean[4 * g]);
   const float4 rs = *reinterpret_cast<const float4*>(&rstd[4 * g]);
   float4 sb = make_float4(0.f, 0.f, 0.f, 0.f), sg = make_float4(0.f, 0.f, 0.f, 0.f);
-  if (active)
-    for (int p = 0; p < t.passes; ++p) {
-      const int rr = lane + p * t.rl;
-      if (rr < n) {
-        const int64_t at = (r0 + rr) * C + 4 * g;
-        const float4 d = *reinterpret_cast<const float4*>(&da[at]);
-        const float4 v = *reinterpret_cast<const float4*>(&y[at]);
-        const float4 o = unpack4(*reinterpret_cast<const uint2*>(&a[at]));
-        const float dx = o.x > 0.f ? d.x : 0.f, dy = o.y > 0.f ? d.y : 0.f;
-        const float dz = o.z > 0.f ? d.z : 0.f, dw = o.w > 0.f ? d.w : 0.f;
-        sb.x += dx; sb.y += dy; sb.z += dz; sb.w += dw;
-        sg.x = fmaf(dx, (v.x - m.x) * rs.x, sg.x); sg.y = fmaf(dy, (v.y - m.y) * rs.y, sg.y);
-        sg.z = fmaf(dz, (v.z - m.z) * rs.z, sg.z); sg.w = fmaf(dw, (v.w - m.w) * rs.w, sg.w);
-      }
+  for (int p0 = 0; p0 < t.passes; p0 += PB) {
+    float4 d[PB], v[PB];
+    uint2 o2[PB];
+#pragma unroll
+    for (int u = 0; u < PB; ++u) {
+      const int64_t at = base + (int64_t)min(lane + (p0 + u) * t.rl, n - 1) * C;
+      d[u] = *reinterpret_cast<const float4*>(&da[at]);
+      v[u] = *reinterpret_cast<const float4*>(&y[at]);
+      o2[u] = *reinterpret_cast<const uint2*>(&a[at]);
     }
+#pragma unroll
+    for (int u = 0; u < PB; ++u)
+      if (active && p0 + u < t.passes && lane + (p0 + u) * t.rl < n) {
+        const float4 o = unpack4(o2[u]);
+        const float dx = o.x > 0.f ? d[u].x : 0.f, dy = o.y > 0.f ? d[u].y : 0.f;
+        const float dz = o.z > 0.f ? d[u].z : 0.f, dw = o.w > 0.f ? d[u].w : 0.f;
+        sb.x += dx; sb.y += dy; sb.z += dz; sb.w += dw;
+        sg.x = fmaf(dx, (v[u].x - m.x) * rs.x, sg.x); sg.y = fmaf(dy, (v[u].y - m.y) * rs.y, sg.y);
+        sg.z = fmaf(dz, (v[u].z - m.z) * rs.z, sg.z); sg.w = fmaf(dw, (v[u].w - m.w) * rs.w, sg.w);
+      }
+  }
   const float4 tb = lanes_sum(sb, red, g, lane, t);
   const float4 tg = lanes_sum(sg, red, g, lane, t);
   if (lane == 0) {
@@ -268,17 +313,39 @@ __global__ __launch_bounds__(NT) void bn2d_bwd_partial_kernel(const float* __res
   }
 }
 
-// Step 2: chunks added in chunk order; the sums go to sums[0][c] (dbeta) and sums[1][c] (dgamma)
-// for the apply kernel, and, weighted, into the gradient (Section 3.2 step 3, Section 5.2).
+// Step 2: one workgroup, thread = (column, lane); a lane adds a contiguous run of chunks in chunk
+// order, the lanes are added in lane order.  The sums go to sums[0][c] (dbeta) and sums[1][c]
+// (dgamma) for the apply kernel, and, weighted, into the gradient (Section 3.2 step 3,
+// Section 5.2).  C <= 256.
 __global__ __launch_bounds__(NT) void bn2d_bwd_finish_kernel(const float* __restrict__ partial, int nchunk, int C,
                                                              float* __restrict__ sums, GradOut gout_g, GradOut gout_b) {
-  const int c = blockIdx.x * NT + threadIdx.x;
-  if (c >= C) return;
+  __shared__ float sm[2][NT];
+  const int nl = NT / C;
+  const int c = threadIdx.x % C, lane = threadIdx.x / C;
+  const int per = (nchunk + nl - 1) / nl;
+  const int k0 = lane * per, k1 = min(nchunk, k0 + per);
   float sb = 0.f, sg = 0.f;
-  for (int k = 0; k < nchunk; ++k) {
-    sb += partial[((int64_t)k * 2 + 0) * C + c];
-    sg += partial[((int64_t)k * 2 + 1) * C + c];
+  if (lane < nl) {
+    int k = k0;
+    for (; k + 3 < k1; k += 4) {
+      float b4[4], g4[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        b4[u] = partial[((int64_t)(k + u) * 2 + 0) * C + c];
+        g4[u] = partial[((int64_t)(k + u) * 2 + 1) * C + c];
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) { sb += b4[u]; sg += g4[u]; }
+    }
+    for (; k < k1; ++k) {
+      sb += partial[((int64_t)k * 2 + 0) * C + c];
+      sg += partial[((int64_t)k * 2 + 1) * C + c];
+    }
   }
+  sm[0][threadIdx.x] = sb; sm[1][threadIdx.x] = sg;
+  __syncthreads();
+  if (lane != 0) return;
+  for (int l = 1; l < nl; ++l) { sb += sm[0][l * C + c]; sg += sm[1][l * C + c]; }
   sums[c] = sb;
   sums[C + c] = sg;
   grad_store(gout_b, c, sb);
@@ -404,8 +471,7 @@ int launch_bn2d_stats(const float* y, int64_t rows, int C, float eps, float* par
   const int nchunk = conv_chunks(rows);
   bn2d_stats_partial_kernel<<<nchunk, NT, tall_lds(C), s>>>(y, rows, C, partial);
   VF_LAUNCH_CHECK();
-  bn2d_stats_finish_kernel<<<(C + NT - 1) / NT, NT, 0, s>>>(partial, nchunk, rows, C, eps, mean, rstd, run_mean,
-                                                            run_var, run_mix);
+  bn2d_stats_finish_kernel<<<1, NT, 0, s>>>(partial, nchunk, rows, C, eps, mean, rstd, run_mean, run_var, run_mix);
   VF_LAUNCH_CHECK();
   return VF_OK;
 }
@@ -426,7 +492,7 @@ int launch_bn2d_bwd(float* da, const bf16_t* a, const float* y, int64_t rows, in
   const int nchunk = conv_chunks(rows);
   bn2d_bwd_partial_kernel<<<nchunk, NT, tall_lds(C), s>>>(da, a, y, rows, C, mean, rstd, partial);
   VF_LAUNCH_CHECK();
-  bn2d_bwd_finish_kernel<<<(C + NT - 1) / NT, NT, 0, s>>>(partial, nchunk, C, sums, gout_g, gout_b);
+  bn2d_bwd_finish_kernel<<<1, NT, 0, s>>>(partial, nchunk, C, sums, gout_g, gout_b);
   VF_LAUNCH_CHECK();
   const int64_t n4 = rows * C / 4;
   bn2d_bwd_apply_kernel<<<(unsigned)blocks(n4), NT, 0, s>>>(da, a, y, n4, C, 1.0f / (float)rows, gamma, round_params,
