@@ -24,22 +24,22 @@ constexpr int NT = 256;          // 4 wavefronts
 constexpr int BK = 64;           // contraction elements per LDS stage
 constexpr int LDS_LD = BK + 8;   // padded row (144 bytes) keeps 16-byte reads conflict-free
 
-// 16-byte global load of 8 consecutive bf16 of row `row` at contraction offset k, zero
-// beyond the matrix (rows >= nrows, k >= kend); a vector straddling kend is masked by element.
+// 16-byte global load of 8 consecutive bf16 of row `row` at contraction offset k (a multiple of
+// 8), zero beyond the matrix (rows >= nrows, k >= kend); a vector straddling kend is masked by
+// element.  The load itself is unconditional, at an address clamped into the matrix (one that an
+// in-range call would read), and the selection comes after it: a caller that issues several of
+// these before using any has them all in flight.  Requires nrows >= 1, kend >= 1.
 __device__ __forceinline__ u32x4 load_vec(const bf16_t* __restrict__ base, int64_t ld, int row,
                                           int nrows, int k, int kend) {
-  u32x4 v = {0u, 0u, 0u, 0u};
-  if (row < nrows && k < kend) {
-    v = *reinterpret_cast<const u32x4*>(base + (int64_t)row * ld + k);
-    int valid = kend - k;              // >= 1
-    if (valid < 8) {
+  const int rc = min(row, nrows - 1);
+  const int kc = min(k, ((kend - 1) >> 3) << 3);
+  u32x4 v = *reinterpret_cast<const u32x4*>(base + (int64_t)rc * ld + kc);
+  const int valid = (row < nrows && k < kend) ? kend - k : 0;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        int e = 2 * j;                 // elements e, e+1 live in dword j
-        uint32_t keep = (e + 1 < valid) ? 0xffffffffu : (e < valid ? 0x0000ffffu : 0u);
-        v[j] &= keep;
-      }
-    }
+  for (int j = 0; j < 4; ++j) {
+    const int e = 2 * j;                 // elements e, e+1 live in dword j
+    const uint32_t keep = (e + 1 < valid) ? 0xffffffffu : (e < valid ? 0x0000ffffu : 0u);
+    v[j] &= keep;
   }
   return v;
 }

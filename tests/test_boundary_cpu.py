@@ -108,3 +108,41 @@ def test_state_size_of_a_null_context_is_zero_and_config_rejects_a_bad_share():
 def test_prefetch_entry_points_reject_null_arguments_without_a_device():
     assert vf.lib().vf_prefetch(None, None, None, 4) != 0
     assert vf.lib().vf_step_prefetched(None, None, 1, None) != 0
+
+
+@pytest.mark.parametrize("kw", [dict(width=12), dict(width=512), dict(width=0), dict(img=0), dict(in_ch=0),
+                                dict(classes=0), dict(n_blocks=-1), dict(dtype=binding.VF_F32)])
+def test_conv_config_rejects_what_the_kernels_do_not_take(kw):
+    """Width a multiple of 8 up to 256 (16-byte channel vectors, one column group per four
+    channels), bf16 only."""
+    cfg = binding.config_from_workload(I.workload("conv_tiny_bf16"))
+    for k, v in kw.items():
+        setattr(cfg, k, v)
+    h = C.c_void_p(123)
+    assert vf.lib().vf_init(C.byref(cfg), C.byref(h)) == binding.VF_EINVAL
+    assert not h.value
+
+
+def test_null_context_queries():
+    L = vf.lib()
+    assert L.vf_streams(None) == 0 and L.vf_fold_window(None) == 0
+    cfg = _cfg(fold_window=9)
+    h = C.c_void_p(5)
+    assert L.vf_init(C.byref(cfg), C.byref(h)) == binding.VF_EINVAL and not h.value
+
+
+def test_config_struct_matches_the_header_field_for_field():
+    """The binding's structure lists the fields of vf_config in the header's order."""
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    text = open(os.path.join(root, "include", "vf.h")).read()
+    body = text[text.index("typedef struct vf_config {"):text.index("} vf_config;")]
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    names = []
+    for decl in body.split(";"):
+        decl = decl.strip().replace("typedef struct vf_config {", "").strip()
+        parts = decl.split(None, 1)
+        if len(parts) < 2:
+            continue
+        for n in parts[1].split(","):
+            names.append(re.sub(r"\[.*\]", "", n.strip().lstrip("*")))
+    assert names == [f[0] for f in binding.VfConfig._fields_]
