@@ -372,11 +372,21 @@ __global__ __launch_bounds__(NT) void gemm_bf16_pipe_kernel(const bf16_t* __rest
 // are clamped into the matrix, their products never stored; nothing is masked).
 __device__ __forceinline__ int dl_swizzle(int r) { return (r & 7) ^ ((r >> 3) & 1); }
 
-template <int NS>
+//
+// CONV: the first operand is not stored as a matrix.  Row r = (n*H + h)*W + w of it is the 3x3
+// neighbourhood of position (h, w) of a channels-last image stack A[rows, Cin] (Cin a multiple
+// of 64): element (r, tap*Cin + c) = A[r + (kh-1)*W + (kw-1), c] for tap = 3 kh + kw inside the
+// image, 0 outside.  A 64-element stage lies within one tap, so a lane's 16 bytes of a stage come
+// from the shifted row or, outside the image, from a block of zeros (`zeros`, 128 bytes): the
+// convolution (stride 1, zero padding 1) as a product without a patch matrix.
+struct ConvOperand { int H, W, Cin; const bf16_t* zeros; };
+
+template <int NS, bool CONV = false>
 __global__ __launch_bounds__(NT) void gemm_bf16_dl_kernel(const bf16_t* __restrict__ A, int64_t lda,
                                                           const bf16_t* __restrict__ B, int64_t ldb,
                                                           int M, int N, int K, int kchunk,
-                                                          int64_t slab_stride, Epilogue ep) {
+                                                          int64_t slab_stride, Epilogue ep,
+                                                          ConvOperand cv = ConvOperand{0, 0, 0, nullptr}) {
   constexpr int TILE = 64 * BK;                 // elements of one operand tile (8 KB)
   constexpr int STAGE = 2 * TILE;
   constexpr int LPS = 4;                        // loads per lane and stage (2 for A, 2 for B)
@@ -394,18 +404,45 @@ __global__ __launch_bounds__(NT) void gemm_bf16_dl_kernel(const bf16_t* __restri
   // this lane's source of each of its loads: row (8 rows per wavefront instruction), permuted chunk
   const bf16_t* ga[2];
   const bf16_t* gb[2];
+  int ah[2], aw[2];                             // CONV: image position of this lane's rows
+  const bf16_t* az[2];                          // CONV: this lane's 16 bytes of the block of zeros
 #pragma unroll
   for (int q = 0; q < 2; ++q) {
     const int row = (wave * 2 + q) * 8 + (lane >> 3);
     const int chunk = (lane & 7) ^ dl_swizzle(row);
-    ga[q] = A + (int64_t)min(m0 + row, M - 1) * lda + kbeg + chunk * 8;
+    const int r = min(m0 + row, M - 1);
+    if (CONV) {
+      ga[q] = A + (int64_t)r * cv.Cin + chunk * 8;
+      aw[q] = r % cv.W;
+      ah[q] = (r / cv.W) % cv.H;
+      az[q] = cv.zeros + chunk * 8;
+    } else {
+      ga[q] = A + (int64_t)r * lda + kbeg + chunk * 8;
+      ah[q] = aw[q] = 0; az[q] = nullptr;
+    }
     gb[q] = B + (int64_t)min(n0 + row, N - 1) * ldb + kbeg + chunk * 8;
   }
+  const int per_tap = CONV ? cv.Cin / BK : 1;   // stages per tap
   auto issue = [&](int stage, int slot) {
     const int k = stage * BK;
+    const bf16_t* src[2];
+    if (CONV) {
+      const int gs = kbeg / BK + stage;         // stage index within the whole contraction
+      const int tap = gs / per_tap, c0 = (gs - tap * per_tap) * BK;
+      const int kh = tap / 3, kw = tap - 3 * kh;
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        const int hh = ah[q] + kh - 1, ww = aw[q] + kw - 1;
+        const bool inside = hh >= 0 && hh < cv.H && ww >= 0 && ww < cv.W;
+        // an inside tap of row r is row r + (kh-1)*W + (kw-1) of the same image
+        src[q] = inside ? ga[q] + ((int64_t)(kh - 1) * cv.W + (kw - 1)) * cv.Cin + c0 : az[q];
+      }
+    } else {
+      src[0] = ga[0] + k; src[1] = ga[1] + k;
+    }
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
-      __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(ga[q] + k),
+      __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(src[q]),
                                        (void __attribute__((address_space(3)))*)&lds[slot * STAGE + (wave * 2 + q) * 512],
                                        16, 0, 0);
       __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(gb[q] + k),
@@ -816,6 +853,24 @@ int launch_gemm_bf16(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb,
     return VF_OK;
   }
   return launch_cfg<64, 64, 2, 2>(g, ep, s);
+}
+
+// C[r, n] = sum over the 3x3 neighbourhood and the channels of x (rows = images * H * W
+// positions, channels last, Cin a multiple of 64) times Wk[n, (kh, kw, c)] (row pitch ldb):
+// a 3x3 convolution, stride 1, zero padding 1, without a patch matrix.  `zeros`: 128 bytes of 0.
+int launch_conv3x3_bf16(const bf16_t* x, int64_t rows, int H, int W, int Cin, const bf16_t* Wk, int64_t ldb, int N,
+                        const Epilogue& ep, const bf16_t* zeros, hipStream_t s) {
+  if (!x || !Wk || !ep.C || !zeros || rows <= 0 || rows > 0x7fffffff || H <= 0 || W <= 0 || N <= 0) return VF_EINVAL;
+  if ((Cin % BK) || rows % ((int64_t)H * W) || (ldb & 7) || ldb < 9 * Cin) return VF_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(x) & 15) || (reinterpret_cast<uintptr_t>(Wk) & 15) ||
+      (reinterpret_cast<uintptr_t>(zeros) & 15))
+    return VF_EINVAL;
+  const int K = 9 * Cin;
+  dim3 grid((N + 63) / 64, (unsigned)((rows + 63) / 64), 1);
+  ConvOperand cv{H, W, Cin, zeros};
+  gemm_bf16_dl_kernel<4, true><<<grid, NT, 0, s>>>(x, Cin, Wk, ldb, (int)rows, N, K, K, 0, ep, cv);
+  VF_LAUNCH_CHECK();
+  return VF_OK;
 }
 
 int launch_gemm_bf16_fold(const FoldArgs& fa, int64_t ld, int M, int N, float* C, int64_t ldc, hipStream_t s) {

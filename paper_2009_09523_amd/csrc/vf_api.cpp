@@ -421,7 +421,14 @@ int vf_init(const vf_config* cfg, vf_ctx** out) {
   }
   arena.assign(c.arena);
   // optimizer state and loss cells start at zero
-  e = hipMemsetAsync(c.arena, 0, c.arena_bytes, c.stream);
+  if (Arena::guard()) {
+    e = hipMemsetAsync(c.arena, 0x7f, c.arena_bytes, c.stream);
+    arena.for_each_buffer([&](size_t off, size_t bytes) {
+      if (e == hipSuccess && bytes) e = hipMemsetAsync(c.arena + off, 0, bytes, c.stream);
+    });
+  } else {
+    e = hipMemsetAsync(c.arena, 0, c.arena_bytes, c.stream);
+  }
   if (e == hipSuccess && c.model->init_state(c.stream) != VF_OK) e = hipErrorUnknown;
   if (e == hipSuccess) e = hipStreamSynchronize(c.stream);
   if (e != hipSuccess) {

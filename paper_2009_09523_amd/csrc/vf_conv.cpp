@@ -2,14 +2,17 @@
 // of one virtual node (forward, loss, backward), Section 3.2 steps 1-3.  Every BatchNorm takes
 // its statistics over the n*H*W positions of the node that is running (Section 4.1).
 //
-// A convolution is a product over patch rows: im2col writes, per output position, the 3x3
-// neighbourhood of the (bf16, channels-last) input as one row of 9*Cin values; forward is
-// patches x filters^T.  The input gradient is the same convolution of the output gradient with
-// the filters turned by 180 degrees and the channel roles exchanged (a second bf16 copy of the
-// filters, made once per step), the weight gradient the product of the transposed output gradient
-// with the transposed patches, its long contraction (all positions of the node) cut into slabs
-// that are added in order.
+// A convolution is a product over patch rows (per output position the 3x3 neighbourhood of the
+// bf16, channels-last input: 9*Cin values) with the filters.  When the input channels are a
+// multiple of 64 the product kernel reads the patches straight from the activation (no patch
+// matrix); otherwise (the first layer) im2col writes them.  The input gradient is the same
+// convolution of the output gradient with the filters turned by 180 degrees and the channel roles
+// exchanged (a second bf16 copy of the filters, made once per step).  The weight gradient is the
+// product of the transposed output gradient with the transposed patch matrix (written by im2col
+// in the backward pass, from the stored input), its long contraction (all positions of the node)
+// cut into slabs that are added in order.
 #include <algorithm>
+#include <cstdlib>
 
 #include "vf_ctx.h"
 
@@ -26,7 +29,7 @@ struct ConvLayer {
   int64_t s_off = 0;               // offset of the moving statistics within a state half
   bf16_t* wnat = nullptr;          // [C, Kp]    filters as they are
   bf16_t* wflip = nullptr;         // [Cin, Kpf] turned filters
-  bf16_t* cols = nullptr;          // [rows, Kp] patches of the input (kept for the weight gradient)
+  const bf16_t* in = nullptr;      // the input of the node in flight ([rows, Cin], set by the forward pass)
   float* y = nullptr;              // [rows, C]  convolution output
   float* mean = nullptr;           // [C]
   float* rstd = nullptr;           // [C]
@@ -70,14 +73,14 @@ class Conv final : public Model {
     for (ConvLayer& L : layers_) {
       a.request(&L.wnat, (size_t)L.C * L.Kp);
       if (L.Kpf) a.request(&L.wflip, (size_t)L.Cin * L.Kpf);
-      a.request(&L.cols, rows * L.Kp);
       a.request(&L.y, rows * L.C);
       a.request(&L.mean, (size_t)L.C);
       a.request(&L.rstd, (size_t)L.C);
       a.request(&L.a, rows * L.C);
-      kp_max = std::max(kp_max, L.Kp);
+      kp_max = std::max(kp_max, std::max(L.Kp, L.Kpf));
     }
-    a.request(&colsd_, rows * 9 * C_);
+    a.request(&cols_, rows * (size_t)kp_max);
+    a.request(&zeros_, (size_t)64);
     a.request(&colsT_, (size_t)kp_max * ldr_);
     a.request(&dyT_, (size_t)C_ * ldr_);
     a.request(&dy_, rows * C_);
@@ -131,10 +134,15 @@ class Conv final : public Model {
   // y = patches(in) x filters^T; statistics over the node's rows; a = relu(BatchNorm(y) (+ skip))
   int conv_bn_relu(Ctx& c, ConvLayer& L, const bf16_t* in, const bf16_t* skip, int rows, const float* P,
                    hipStream_t st) {
-    VF_KS(c, st, "im2col", launch_im2col3x3(in, rows, H_, H_, L.Cin, L.cols, L.Kp, st));
+    L.in = in;
     Epilogue ep;
     ep.C = L.y; ep.ldc = L.C;
-    VF_KS(c, st, "gemm_fwd", launch_gemm_bf16(L.cols, L.Kp, L.wnat, L.Kp, rows, L.C, L.Kp, 1, 0, ep, st));
+    if (L.Cin % 64 == 0 && !explicit_) {
+      VF_KS(c, st, "gemm_fwd", launch_conv3x3_bf16(in, rows, H_, H_, L.Cin, L.wnat, L.Kp, L.C, ep, zeros_, st));
+    } else {
+      VF_KS(c, st, "im2col", launch_im2col3x3(in, rows, H_, H_, L.Cin, cols_, L.Kp, st));
+      VF_KS(c, st, "gemm_fwd", launch_gemm_bf16(cols_, L.Kp, L.wnat, L.Kp, rows, L.C, L.Kp, 1, 0, ep, st));
+    }
     const int64_t S = (int64_t)layers_.size() * C_;
     VF_KS(c, st, "bn_stats", launch_bn2d_stats(L.y, rows, L.C, cfg_.bn_eps, partial_, L.mean, L.rstd,
                                                state_ + L.s_off, state_ + S + L.s_off, cfg_.bn_momentum, st));
@@ -179,7 +187,8 @@ class Conv final : public Model {
 
   // dW[o, (kh,kw,c)] = sum over the node's positions of dy[r, o] * patches[r, (kh,kw,c)]
   int conv_wgrad(Ctx& c, ConvLayer& L, int rows, float w, int node, hipStream_t st) {
-    VF_KS(c, st, "transpose", launch_transpose_bf16(L.cols, L.Kp, colsT_, ldr_, rows, L.Kp, st));
+    VF_KS(c, st, "im2col", launch_im2col3x3(L.in, rows, H_, H_, L.Cin, cols_, L.Kp, st));
+    VF_KS(c, st, "transpose", launch_transpose_bf16(cols_, L.Kp, colsT_, ldr_, rows, L.Kp, st));
     VF_KS(c, st, "transpose", launch_transpose_bf16(dy_, L.C, dyT_, ldr_, rows, L.C, st));
     int split = std::min(kMaxSplit, gemm_bf16_pick_split(L.C, L.Kc, rows));
     const int64_t slab = (int64_t)L.C * L.Kc;
@@ -192,11 +201,15 @@ class Conv final : public Model {
 
   // out = (addend +) the convolution of dy with the turned filters
   int conv_dgrad(Ctx& c, ConvLayer& L, int rows, float* out, const float* addend, hipStream_t st) {
-    VF_KS(c, st, "im2col", launch_im2col3x3(dy_, rows, H_, H_, L.C, colsd_, L.Kpf, st));
     Epilogue ep;
     ep.C = out; ep.ldc = L.Cin;
     if (addend) { ep.R = addend; ep.ldr = L.Cin; ep.beta = 1.f; }
-    VF_KS(c, st, "gemm_dgrad", launch_gemm_bf16(colsd_, L.Kpf, L.wflip, L.Kpf, rows, L.Cin, L.Kpf, 1, 0, ep, st));
+    if (L.C % 64 == 0 && !explicit_) {
+      VF_KS(c, st, "gemm_dgrad", launch_conv3x3_bf16(dy_, rows, H_, H_, L.C, L.wflip, L.Kpf, L.Cin, ep, zeros_, st));
+    } else {
+      VF_KS(c, st, "im2col", launch_im2col3x3(dy_, rows, H_, H_, L.C, cols_, L.Kpf, st));
+      VF_KS(c, st, "gemm_dgrad", launch_gemm_bf16(cols_, L.Kpf, L.wflip, L.Kpf, rows, L.Cin, L.Kpf, 1, 0, ep, st));
+    }
     return VF_OK;
   }
 
@@ -212,7 +225,13 @@ class Conv final : public Model {
     const int rows = b * HW_;
     const float w = s.w[i];
     const float* P = s.params;
-    // classifier: bias and weight gradients, gradient of the pooled features
+    // classifier: the gradient of the pooled features first (right behind the kernel that wrote
+    // dz), then the bias and weight gradients
+    {
+      Epilogue ep;
+      ep.C = dpooled_; ep.ldc = ldc_;
+      VF_KS(c, st, "gemm_dgrad", launch_gemm_bf16(dz_, ldz_, fc_wnat_, ldz_, b, C_, cfg_.classes, 1, 0, ep, st));
+    }
     VF_KS(c, st, "bias_grad", launch_rowsum_bf16(dzT_, ldb_, cfg_.classes, b, c.gout(fc_b_off_, w, i), st));
     VF_KS(c, st, "transpose", launch_transpose_bf16(pooled_, ldc_, pooledT_, ldb_, b, C_, st));
     {
@@ -221,11 +240,6 @@ class Conv final : public Model {
       ep.C = go.dst; ep.ldc = cfg_.classes; ep.alpha = go.alpha;
       if (go.accumulate) { ep.R = go.dst; ep.ldr = cfg_.classes; ep.beta = 1.f; }
       VF_KS(c, st, "gemm_wgrad", launch_gemm_bf16(pooledT_, ldb_, dzT_, ldb_, C_, cfg_.classes, b, 1, 0, ep, st));
-    }
-    {
-      Epilogue ep;
-      ep.C = dpooled_; ep.ldc = ldc_;
-      VF_KS(c, st, "gemm_dgrad", launch_gemm_bf16(dz_, ldz_, fc_wnat_, ldz_, b, C_, cfg_.classes, 1, 0, ep, st));
     }
     VF_KS(c, st, "avgpool", launch_avgpool_bwd(dpooled_, ldc_, b, HW_, C_, gA_, st));
     for (int blk = cfg_.n_blocks - 1; blk >= 0; --blk) {
@@ -246,13 +260,15 @@ class Conv final : public Model {
   }
 
   vf_config cfg_;
+  bool explicit_ = std::getenv("VF_CONV_EXPLICIT") != nullptr;   // tuning aid: always write the patch matrix
   int H_ = 0, HW_ = 0, C_ = 0;
   int64_t P_ = 0, rows_max_ = 0;
   int64_t ldr_ = 0;                // pitch of the transposed [channels, rows] operands
   int64_t ldb_ = 0, ldc_ = 0, ldz_ = 0;   // pitches: node rows, channels, classes (rounded to 8)
   int64_t fc_w_off_ = 0, fc_b_off_ = 0;
   std::vector<ConvLayer> layers_;
-  bf16_t* colsd_ = nullptr;        // [rows, 9C] patches of an output gradient
+  bf16_t* cols_ = nullptr;         // [rows, Kp] patch matrix (of a layer's input, or of an output gradient)
+  bf16_t* zeros_ = nullptr;        // 128 bytes of 0: what the product kernel reads outside the image
   bf16_t* colsT_ = nullptr;        // [Kp, ldr]  patches transposed
   bf16_t* dyT_ = nullptr;          // [C, ldr]   output gradient transposed
   bf16_t* dy_ = nullptr;           // [rows, C]  gradient w.r.t. a convolution output

@@ -2,6 +2,7 @@
 #pragma once
 
 #include <algorithm>
+#include <cstdlib>
 #include <memory>
 #include <string>
 #include <vector>
@@ -16,16 +17,28 @@ class Arena {
   template <typename T>
   void request(T** target, size_t count) {
     size_t bytes = (count * sizeof(T) + 255) & ~size_t(255);
-    reqs_.push_back({reinterpret_cast<void**>(target), total_});
-    total_ += bytes;
+    reqs_.push_back({reinterpret_cast<void**>(target), total_, count * sizeof(T)});
+    total_ += bytes + guard();
   }
   size_t total() const { return total_; }
   void assign(char* base) {
     for (auto& r : reqs_) *r.target = base + r.offset;
   }
+  // Debugging aid: VF_ARENA_GUARD=<bytes> (a multiple of 256) leaves that much room after every
+  // buffer; vf_init then fills the whole arena with the byte 0x7f (huge values in every
+  // floating-point type) and zeroes exactly the bytes each buffer asked for, so that a read past
+  // a buffer's end shows in the results.
+  static size_t guard() {
+    static const size_t g = std::getenv("VF_ARENA_GUARD") ? (size_t)std::atoll(std::getenv("VF_ARENA_GUARD")) & ~size_t(255) : 0;
+    return g;
+  }
+  template <typename F>
+  void for_each_buffer(F f) const {
+    for (const auto& r : reqs_) f(r.offset, r.bytes);
+  }
 
  private:
-  struct Req { void** target; size_t offset; };
+  struct Req { void** target; size_t offset; size_t bytes; };
   std::vector<Req> reqs_;
   size_t total_ = 0;
 };
@@ -203,6 +216,16 @@ struct Ctx {
   int mark_range(int k, hipStream_t st);
 };
 
+// Debugging aid: with VF_SYNC_EACH set in the environment the host waits after every launch
+// (VF_SYNC_EACH=all), or after the launches whose tag the variable names (comma separated).
+inline bool debug_sync_each(const char* tag) {
+  static const char* spec = std::getenv("VF_SYNC_EACH");
+  if (!spec) return false;
+  const std::string s(spec);
+  if (s == "all") return true;
+  return ("," + s + ",").find("," + std::string(tag) + ",") != std::string::npos;
+}
+
 // Launch `call` (an expression returning a status) under the tag `name`; the launch goes to
 // stream `strm` (VF_K: the context's main stream).
 #define VF_K(ctx, name, call) VF_KS(ctx, (ctx).stream, name, call)
@@ -218,6 +241,7 @@ struct Ctx {
       (ctx).prof.recs.push_back(r__);                                     \
     } else {                                                              \
       VF_TRY(call);                                                       \
+      if (::vf::debug_sync_each(name)) VF_HIP(hipStreamSynchronize((strm))); \
     }                                                                     \
   } while (0)
 

@@ -105,6 +105,12 @@ struct FoldArgs {
   int overwrite;
 };
 int launch_gemm_bf16_fold(const FoldArgs& fa, int64_t ld, int M, int N, float* C, int64_t ldc, hipStream_t s);
+// 3x3 convolution (stride 1, zero padding 1) of a channels-last bf16 image stack x [rows, Cin],
+// rows = images*H*W, Cin % 64 == 0, with filters Wk [N, 9*Cin] (row pitch ldb), as a product
+// whose first operand is read straight from x; epilogue as launch_gemm_bf16.  zeros: 128 bytes
+// of device memory holding 0.
+int launch_conv3x3_bf16(const bf16_t* x, int64_t rows, int H, int W, int Cin, const bf16_t* Wk, int64_t ldb, int N,
+                        const Epilogue& ep, const bf16_t* zeros, hipStream_t s);
 
 // The small per-node launches of a fold window, batched: `count` nodes, node j with rows[j] rows.
 struct NodeList {

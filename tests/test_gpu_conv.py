@@ -20,7 +20,7 @@ def _case(name, jitter=0.1):
 
 
 @pytest.mark.parametrize("flags", [NO_GRAPH, 0, FUSED | NO_GRAPH, FUSED])
-@pytest.mark.parametrize("name", ["conv_tiny_bf16", "conv_small_bf16"])
+@pytest.mark.parametrize("name", ["conv_tiny_bf16", "conv_small_bf16", "conv_w64_bf16"])
 def test_conv_step_matches_oracle(name, flags):
     print(f"case {name} flags={flags}", flush=True)
     wl, theta, x, y = _case(name)
@@ -59,8 +59,9 @@ def test_second_step_of_the_deeper_network_within_the_oracles_own_sensitivity():
     assert gpu["t"] == 2
 
 
-def test_fused_staged_graph_and_eager_agree_bitwise():
-    wl, theta, x, y = _case("conv_small_bf16")
+@pytest.mark.parametrize("name", ["conv_small_bf16", "conv_w64_bf16"])
+def test_fused_staged_graph_and_eager_agree_bitwise(name):
+    wl, theta, x, y = _case(name)
     base = run_gpu(wl, theta, x, y, flags=NO_GRAPH, steps=2)
     for flags in (0, FUSED, FUSED | NO_GRAPH):
         other = run_gpu(wl, theta, x, y, flags=flags, steps=2)
@@ -121,3 +122,16 @@ def test_benchmark_configuration_sampled_against_the_oracle():
     gpu = run_gpu(one, theta, x[:b], y[:b], flags=FUSED | NO_GRAPH)
     ref = oracle_steps(one, theta, x[:b], y[:b])
     check_against_oracle(one, gpu, ref)
+
+
+def test_eager_launches_are_repeatable():
+    """The same step launched kernel by kernel many times: identical bits every time.  (With the
+    classifier's input gradient launched after its bias and weight gradients, about one run in a
+    thousand came out with different convolution gradients on this machine; see the measurement
+    notes of the design document.)"""
+    wl, theta, x, y = _case("conv_w64_bf16")
+    base = run_gpu(wl, theta, x, y, flags=FUSED | NO_GRAPH)
+    for flags in (FUSED | NO_GRAPH, NO_GRAPH):
+        for _ in range(1500):
+            r = run_gpu(wl, theta, x, y, flags=flags)
+            assert r["G"].tobytes() == base["G"].tobytes() and r["loss"] == base["loss"], flags

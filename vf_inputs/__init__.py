@@ -133,6 +133,7 @@ WORKLOADS: Dict[str, Workload] = {
     "conv_tiny_f64": _conv("conv_tiny_f64", 5, 2, 8, 1, 4, [3, 2], "f64"),
     "conv_tiny_bf16": _conv("conv_tiny_bf16", 6, 3, 16, 1, 10, [5, 3, 8], "bf16"),
     "conv_small_bf16": _conv("conv_small_bf16", 12, 3, 24, 2, 10, [9, 16, 7], "bf16"),
+    "conv_w64_bf16": _conv("conv_w64_bf16", 6, 3, 64, 1, 10, [3, 2, 4], "bf16"),
 }
 
 
