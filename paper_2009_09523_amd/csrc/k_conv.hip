@@ -60,6 +60,38 @@ __global__ __launch_bounds__(NT) void im2col1_kernel(const bf16_t* __restrict__ 
   cols[idx] = v;
 }
 
+// The transposed patch matrix straight from the transposed activation xT [C, ldx] (row c holds
+// channel c of all positions): colsT[(tap*C + c), r] = xT[c, r + (kh-1)*W + (kw-1)] inside the
+// image, 0 outside and for r >= rows (the padding of a row up to ldo).  Row (tap, c) is row c
+// shifted by the tap's offset, so reads and writes both run along the row; one thread writes 8
+// consecutive positions (16 bytes).  ldo % 8 == 0.
+__global__ __launch_bounds__(NT) void im2colT_kernel(const bf16_t* __restrict__ xT, int64_t ldx, int64_t rows, int H, int W,
+                                                     int C, bf16_t* __restrict__ colsT, int64_t ldo) {
+  const int64_t nvec = (rows + 7) >> 3;
+  const int64_t idx = (int64_t)blockIdx.x * NT + threadIdx.x;
+  if (idx >= (int64_t)9 * C * nvec) return;
+  const int k = (int)(idx / nvec);
+  const int64_t r0 = (idx - (int64_t)k * nvec) << 3;
+  const int tap = k / C, c = k - tap * C;
+  const int kh = tap / 3, kw = tap - 3 * kh;
+  const int64_t shift = (int64_t)(kh - 1) * W + (kw - 1);
+  const bf16_t* src = xT + (int64_t)c * ldx;
+  int w = (int)(r0 % W);
+  int h = (int)((r0 / W) % H);
+  uint32_t out[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int64_t r = r0 + e;
+    const int hh = h + kh - 1, ww = w + kw - 1;
+    const bool in = r < rows && hh >= 0 && hh < H && ww >= 0 && ww < W;
+    // an inside tap of position r is position r + shift of the same image; otherwise read r0 (valid) and drop it
+    const bf16_t v = src[in ? r + shift : r0];
+    out[e >> 1] |= in ? ((uint32_t)v << (16 * (e & 1))) : 0u;
+    if (++w == W) { w = 0; if (++h == H) h = 0; }
+  }
+  *reinterpret_cast<u32x4*>(&colsT[(int64_t)k * ldo + r0]) = u32x4{out[0], out[1], out[2], out[3]};
+}
+
 // ---- filter copies ----------------------------------------------------------------------------
 // nat[o, k] = bf16(Wf[o, k]) for k < 9*Cin (row pitch Kp; the padding stays as it is: zero);
 // flip[c, (2-kh)*3*Cout + (2-kw)*Cout + o] = bf16(Wf[o, kh, kw, c]): the filters of the input
@@ -452,6 +484,16 @@ int launch_im2col3x3(const bf16_t* x, int64_t rows, int H, int W, int C, bf16_t*
   } else {
     im2col1_kernel<<<(unsigned)blocks(rows * Kp), NT, 0, s>>>(x, rows, H, W, C, cols, (int)Kp);
   }
+  VF_LAUNCH_CHECK();
+  return VF_OK;
+}
+
+int launch_im2col3x3_transposed(const bf16_t* xT, int64_t ldx, int64_t rows, int H, int W, int C, bf16_t* colsT,
+                                int64_t ldo, hipStream_t s) {
+  if (rows <= 0 || H <= 0 || W <= 0 || C <= 0 || rows % ((int64_t)H * W) || ldx < rows || (ldo & 7) ||
+      ldo < ((rows + 7) & ~int64_t(7)) || (reinterpret_cast<uintptr_t>(colsT) & 15))
+    return VF_EINVAL;
+  im2colT_kernel<<<(unsigned)blocks((int64_t)9 * C * ((rows + 7) >> 3)), NT, 0, s>>>(xT, ldx, rows, H, W, C, colsT, ldo);
   VF_LAUNCH_CHECK();
   return VF_OK;
 }

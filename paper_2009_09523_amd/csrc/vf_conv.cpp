@@ -10,7 +10,8 @@
 // exchanged (a second bf16 copy of the filters, made once per step).  The weight gradient is the
 // product of the transposed output gradient with the transposed patch matrix (written by im2col
 // in the backward pass, from the stored input), its long contraction (all positions of the node)
-// cut into slabs that are added in order.
+// cut into slabs that are added in order.  The transposed patch matrix is written directly, row
+// by row, from the transposed input.
 #include <algorithm>
 #include <cstdlib>
 
@@ -83,6 +84,7 @@ class Conv final : public Model {
     a.request(&zeros_, (size_t)64);
     a.request(&colsT_, (size_t)kp_max * ldr_);
     a.request(&dyT_, (size_t)C_ * ldr_);
+    a.request(&inT_, (size_t)std::max(C_, cfg_.in_ch) * ldr_);
     a.request(&dy_, rows * C_);
     a.request(&gA_, rows * C_);
     a.request(&gB_, rows * C_);
@@ -187,8 +189,8 @@ class Conv final : public Model {
 
   // dW[o, (kh,kw,c)] = sum over the node's positions of dy[r, o] * patches[r, (kh,kw,c)]
   int conv_wgrad(Ctx& c, ConvLayer& L, int rows, float w, int node, hipStream_t st) {
-    VF_KS(c, st, "im2col", launch_im2col3x3(L.in, rows, H_, H_, L.Cin, cols_, L.Kp, st));
-    VF_KS(c, st, "transpose", launch_transpose_bf16(cols_, L.Kp, colsT_, ldr_, rows, L.Kp, st));
+    VF_KS(c, st, "transpose", launch_transpose_bf16(L.in, L.Cin, inT_, ldr_, rows, L.Cin, st));
+    VF_KS(c, st, "im2col", launch_im2col3x3_transposed(inT_, ldr_, rows, H_, H_, L.Cin, colsT_, ldr_, st));
     VF_KS(c, st, "transpose", launch_transpose_bf16(dy_, L.C, dyT_, ldr_, rows, L.C, st));
     int split = std::min(kMaxSplit, gemm_bf16_pick_split(L.C, L.Kc, rows));
     const int64_t slab = (int64_t)L.C * L.Kc;
@@ -271,6 +273,7 @@ class Conv final : public Model {
   bf16_t* zeros_ = nullptr;        // 128 bytes of 0: what the product kernel reads outside the image
   bf16_t* colsT_ = nullptr;        // [Kp, ldr]  patches transposed
   bf16_t* dyT_ = nullptr;          // [C, ldr]   output gradient transposed
+  bf16_t* inT_ = nullptr;          // [Cin, ldr] a layer's input transposed
   bf16_t* dy_ = nullptr;           // [rows, C]  gradient w.r.t. a convolution output
   float* gA_ = nullptr;            // [rows, C]  gradients w.r.t. activations (two, alternating)
   float* gB_ = nullptr;

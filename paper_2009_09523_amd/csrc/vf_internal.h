@@ -171,6 +171,10 @@ int launch_colsum(const void* x, int64_t ld, int x_is_bf16, int R, int C, GradOu
 int conv_chunks(int64_t rows);     // row chunks of the tall reductions: sizes their partial buffers (2*C floats each)
 // cols[r, (kh*3+kw)*C + c] = x[n, h+kh-1, w+kw-1, c] or 0; row pitch Kp >= 9C, a multiple of 8
 int launch_im2col3x3(const bf16_t* x, int64_t rows, int H, int W, int C, bf16_t* cols, int64_t Kp, hipStream_t s);
+// the same patches transposed, [9C, ldo] (positions along the row), from the transposed input
+// xT [C, ldx]; the padding of a row up to ldo is written as 0
+int launch_im2col3x3_transposed(const bf16_t* xT, int64_t ldx, int64_t rows, int H, int W, int C, bf16_t* colsT,
+                                int64_t ldo, hipStream_t s);
 // bf16 copies of fp32 filters [Cout, 3, 3, Cin]: as they are (row pitch Kp) and, if flip != null,
 // turned by 180 degrees with the channel roles exchanged, [Cin, 3, 3, Cout] (row pitch Kpf)
 int launch_conv_weight_copies(const float* Wf, int Cout, int Cin, bf16_t* nat, int Kp, bf16_t* flip, int Kpf,
