@@ -127,8 +127,8 @@ def test_benchmark_configuration_sampled_against_the_oracle():
 def test_eager_launches_are_repeatable():
     """The same step launched kernel by kernel many times: identical bits every time.  (With the
     classifier's input gradient launched after its bias and weight gradients, about one run in a
-    thousand came out with different convolution gradients on this machine; see the measurement
-    notes of the design document.)"""
+    thousand came out with different convolution gradients on this machine, only for launches
+    made one by one; it is launched first since.)"""
     wl, theta, x, y = _case("conv_w64_bf16")
     base = run_gpu(wl, theta, x, y, flags=FUSED | NO_GRAPH)
     for flags in (FUSED | NO_GRAPH, NO_GRAPH):
