@@ -82,7 +82,9 @@ def test_adam_kernel(n):
 
 GEMM_SHAPES = [(128, 4096 // 8, 1024 // 4), (48, 1000, 520), (16, 392, 1000), (8, 520, 256), (40, 264, 392),
                (300, 100, 392), (392, 1000, 128), (520, 392, 48), (256, 520, 16), (256, 520, 8), (1, 8, 8),
-               (33, 65, 72), (129, 257, 264), (304, 1003, 128), (2048, 2304, 768)]
+               (33, 65, 72), (129, 257, 264), (304, 1003, 128), (2048, 2304, 768),
+               # enough 256 x 256 tiles to fill the machine: the wide LDS-direct kernel, ragged on both sides
+               (4000, 3585, 192)]
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
@@ -117,7 +119,9 @@ def test_gemm_against_float64_matmul(M, N, K, dtype):
                                          (128, 264, 72, 2), (300, 100, 1000, 8),
                                          # whole 64-element stages per slice: the LDS-direct kernel
                                          (128, 4096, 4096, 4), (100, 1000, 1024, 8), (70, 130, 192, 3),
-                                         (65, 64, 64, 1), (48, 392, 64, 2), (128, 1000, 4096, 16)])
+                                         (65, 64, 64, 1), (48, 392, 64, 2), (128, 1000, 4096, 16),
+                                         # 256 x 256 tiles, sliced contraction
+                                         (1100, 1030, 2048, 16)])
 def test_gemm_split_contraction_slabs_sum_to_product(M, N, K, nsplit):
     import torch
     import paper_2009_09523_amd as vf
