@@ -336,6 +336,106 @@ __global__ __launch_bounds__(NT) void colsum_finish_kernel(const float* __restri
   if (q == 0 && c < C) grad_store(out, c, (red[0][tx] + red[1][tx]) + (red[2][tx] + red[3][tx]));
 }
 
+// One pass over a gradient matrix dy [R, C] that feeds a Linear layer's backward pass, 64 x 64
+// tiles: the transposed bf16 copy the weight-gradient product reads, (fp32 input) the bf16 copy
+// in place the input-gradient product reads, and per-tile column sums of the values as read
+// (partial[tile row][c]), which colsum_finish_kernel adds in tile order: the bias gradient.
+// Loads come first, at clamped positions; rows at or past R add nothing.
+// fp32 input: C % 4 == 0, ld % 4 == 0.  Every thread reads 16 bytes, writes 8 in both orientations.
+__global__ __launch_bounds__(NT) void dy_f32_prepare_kernel(const float* __restrict__ in, int64_t ldi,
+                                                            bf16_t* __restrict__ nat, int64_t ldn,
+                                                            bf16_t* __restrict__ tr, int64_t ldt,
+                                                            float* __restrict__ partial, int R, int C) {
+  __shared__ bf16_t tile[64][64 + 2];
+  __shared__ float red[16][64];
+  const int q = threadIdx.x & 15, g = threadIdx.x >> 4;      // 16 quads per row, 16 row groups
+  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  float4 vin[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    vin[i] = *reinterpret_cast<const float4*>(&in[(int64_t)min(r0 + g + 16 * i, R - 1) * ldi + min(c0 + 4 * q, C - 4)]);
+  float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int rl = g + 16 * i, r = r0 + rl, c = c0 + 4 * q;
+    bf16_t h[4] = {0, 0, 0, 0};
+    if (r < R && c < C) {
+      const float4 v = vin[i];
+      sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+      h[0] = f32_to_bf16(v.x); h[1] = f32_to_bf16(v.y); h[2] = f32_to_bf16(v.z); h[3] = f32_to_bf16(v.w);
+      uint2 pk;
+      pk.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
+      pk.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
+      *reinterpret_cast<uint2*>(&nat[(int64_t)r * ldn + c]) = pk;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) tile[rl][4 * q + u] = h[u];
+  }
+  red[g][4 * q] = sum.x; red[g][4 * q + 1] = sum.y; red[g][4 * q + 2] = sum.z; red[g][4 * q + 3] = sum.w;
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int cl = g + 16 * i, c = c0 + cl, r = r0 + 4 * q;
+    if (c < C && r < R) {      // rows past R inside the quad are padding of ldt
+      uint2 pk;
+      pk.x = (uint32_t)tile[4 * q][cl] | ((uint32_t)tile[4 * q + 1][cl] << 16);
+      pk.y = (uint32_t)tile[4 * q + 2][cl] | ((uint32_t)tile[4 * q + 3][cl] << 16);
+      *reinterpret_cast<uint2*>(&tr[(int64_t)c * ldt + r]) = pk;
+    }
+  }
+  if (threadIdx.x < 64 && c0 + threadIdx.x < C) {
+    float t = 0.f;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) t += red[k][threadIdx.x];
+    partial[(int64_t)blockIdx.y * C + c0 + threadIdx.x] = t;
+  }
+}
+
+// bf16 input: C % 8 == 0, ldi % 8 == 0, ldt % 8 == 0 and ldt >= R rounded up to 8 (the transposed
+// rows are written in whole 16-byte vectors; the columns past R receive copies of row R-1).
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(NT) void dy_bf16_prepare_kernel(const bf16_t* __restrict__ in, int64_t ldi,
+                                                             bf16_t* __restrict__ tr, int64_t ldt,
+                                                             float* __restrict__ partial, int R, int C) {
+  __shared__ __attribute__((aligned(16))) bf16_t tile[64][64 + 8];
+  __shared__ float red[4][64];
+  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  const int v = threadIdx.x & 7, row = threadIdx.x >> 3;     // 8 vectors per row, 32 rows per pass
+  u32x4 x[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+    x[i] = *reinterpret_cast<const u32x4*>(&in[(int64_t)min(r0 + row + 32 * i, R - 1) * ldi + min(c0 + 8 * v, C - 8)]);
+#pragma unroll
+  for (int i = 0; i < 2; ++i) *reinterpret_cast<u32x4*>(&tile[row + 32 * i][8 * v]) = x[i];
+  __syncthreads();
+  {
+    const int col = threadIdx.x & 63, part = threadIdx.x >> 6;   // 16 rows of one column, in row order
+    float t = 0.f;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+      const int rl = part * 16 + k;
+      const float val = bf16_to_f32(tile[rl][col]);
+      t += (r0 + rl < R) ? val : 0.f;
+    }
+    red[part][col] = t;
+  }
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int col = (threadIdx.x >> 3) + 32 * i;             // output row = input column
+    const int rb = 8 * (threadIdx.x & 7);                    // eight input rows -> one 16-byte vector
+    u32x4 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      o[e] = (uint32_t)tile[rb + 2 * e][col] | ((uint32_t)tile[rb + 2 * e + 1][col] << 16);
+    if (c0 + col < C && r0 + rb < R)
+      *reinterpret_cast<u32x4*>(&tr[(int64_t)(c0 + col) * ldt + r0 + rb]) = o;
+  }
+  __syncthreads();
+  if (threadIdx.x < 64 && c0 + threadIdx.x < C)
+    partial[(int64_t)blockIdx.y * C + c0 + threadIdx.x] =
+        (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
+}
+
 // ---- GELU (exact) ---------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(NT) void gelu_fwd_kernel(const T* __restrict__ u, T* __restrict__ g, int64_t n) {
@@ -527,6 +627,30 @@ int launch_colsum_rows(const void* x, int64_t ld, int x_is_bf16, int R, int C, f
     colsum_partial_kernel<float><<<grid, NT, 0, s>>>(static_cast<const float*>(x), ld, R, C, rows_per_chunk, scratch);
   VF_LAUNCH_CHECK();
   colsum_finish_kernel<<<(C + 63) / 64, NT, 0, s>>>(scratch, nchunk, C, out);
+  VF_LAUNCH_CHECK();
+  return VF_OK;
+}
+
+bool dy_prepare_fits(int is_f32, int64_t ldi, int64_t ldn, int64_t ldt, int R, int C) {
+  if (R <= 0 || C <= 0 || (R + 63) / 64 > kReduceChunks) return false;
+  if (is_f32) return (C & 3) == 0 && (ldi & 3) == 0 && (ldn & 3) == 0 && (ldt & 3) == 0 && ldt >= ((R + 3) & ~3);
+  return (C & 7) == 0 && (ldi & 7) == 0 && (ldt & 7) == 0 && ldt >= ((R + 7) & ~7);
+}
+
+int launch_dy_prepare(const void* dy, int dy_is_f32, int64_t ldi, int R, int C, bf16_t* nat, int64_t ldn,
+                      bf16_t* tr, int64_t ldt, float* scratch, GradOut out, hipStream_t s) {
+  if (!dy || !tr || !scratch || (dy_is_f32 && !nat)) return VF_EINVAL;
+  if (!dy_prepare_fits(dy_is_f32, ldi, ldn, ldt, R, C)) return VF_EINVAL;
+  const uintptr_t bits = reinterpret_cast<uintptr_t>(dy) | reinterpret_cast<uintptr_t>(tr) |
+                         (dy_is_f32 ? reinterpret_cast<uintptr_t>(nat) : 0);
+  if (bits & 15) return VF_EINVAL;
+  dim3 grid((C + 63) / 64, (R + 63) / 64);
+  if (dy_is_f32)
+    dy_f32_prepare_kernel<<<grid, NT, 0, s>>>(static_cast<const float*>(dy), ldi, nat, ldn, tr, ldt, scratch, R, C);
+  else
+    dy_bf16_prepare_kernel<<<grid, NT, 0, s>>>(static_cast<const bf16_t*>(dy), ldi, tr, ldt, scratch, R, C);
+  VF_LAUNCH_CHECK();
+  colsum_finish_kernel<<<(C + 63) / 64, NT, 0, s>>>(scratch, (int)grid.y, C, out);
   VF_LAUNCH_CHECK();
   return VF_OK;
 }

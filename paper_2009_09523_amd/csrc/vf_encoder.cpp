@@ -188,28 +188,22 @@ class Encoder final : public Model {
       Block& B = blocks_[l];
       // FFN
       const void* dh_op = dh_buf_;
-      if (bf16_) {
-        VF_K(c, "cast", launch_cast_bf16(dh_buf_, d_, static_cast<bf16_t*>(cast_), d_, R, d_, st));
-        dh_op = cast_;
-      }
-      VF_K(c, "colsum", launch_colsum_rows(dh_buf_, d_, 0, R, d_, red_, c.gout(B.w2.b_off, w, i), st));
-      VF_TRY(lin_bwd_w(c, "gemm_wgrad", B.w2, B.g, f_, dh_op, d_, R, c.gout(B.w2.w_off, w, i)));
+      bool dyT = false;
+      VF_TRY(prepare_dy(c, dh_buf_, true, d_, R, d_, c.gout(B.w2.b_off, w, i), &dh_op, &dyT));
+      VF_TRY(lin_bwd_w(c, "gemm_wgrad", B.w2, B.g, f_, dh_op, d_, R, c.gout(B.w2.w_off, w, i), dyT));
       VF_TRY(lin_bwd_x(c, "gemm_dgrad", B.w2, P, dh_op, d_, R, tmp32_, f_, nullptr));
       VF_K(c, "gelu_bwd", launch_gelu_bwd(tmp32_, B.u, du_, bf16_, (int64_t)R * f_, st));
-      VF_K(c, "colsum", launch_colsum_rows(du_, f_, bf16_, R, f_, red_, c.gout(B.w1.b_off, w, i), st));
-      VF_TRY(lin_bwd_w(c, "gemm_wgrad", B.w1, B.f, d_, du_, f_, R, c.gout(B.w1.w_off, w, i)));
+      const void* du_op = du_;
+      VF_TRY(prepare_dy(c, du_, !bf16_, f_, R, f_, c.gout(B.w1.b_off, w, i), &du_op, &dyT));
+      VF_TRY(lin_bwd_w(c, "gemm_wgrad", B.w1, B.f, d_, du_, f_, R, c.gout(B.w1.w_off, w, i), dyT));
       VF_TRY(lin_bwd_x(c, "gemm_dgrad", B.w1, P, du_, f_, R, tmp32_, d_, nullptr));
       VF_K(c, "layernorm_bwd", launch_layernorm_bwd(tmp32_, 1, 0, d_, B.hmid, d_, nullptr, R, d_, P + B.ln2_g,
                                                     bf16_, B.mean2, B.rstd2, dh_buf_, dmid_, d_, red_,
                                                     c.gout(B.ln2_g, w, i), c.gout(B.ln2_b, w, i), st));
       // attention
       const void* dmid_op = dmid_;
-      if (bf16_) {
-        VF_K(c, "cast", launch_cast_bf16(dmid_, d_, static_cast<bf16_t*>(cast_), d_, R, d_, st));
-        dmid_op = cast_;
-      }
-      VF_K(c, "colsum", launch_colsum_rows(dmid_, d_, 0, R, d_, red_, c.gout(B.o.b_off, w, i), st));
-      VF_TRY(lin_bwd_w(c, "gemm_wgrad", B.o, B.om, d_, dmid_op, d_, R, c.gout(B.o.w_off, w, i)));
+      VF_TRY(prepare_dy(c, dmid_, true, d_, R, d_, c.gout(B.o.b_off, w, i), &dmid_op, &dyT));
+      VF_TRY(lin_bwd_w(c, "gemm_wgrad", B.o, B.om, d_, dmid_op, d_, R, c.gout(B.o.w_off, w, i), dyT));
       VF_TRY(lin_bwd_x(c, "gemm_dgrad", B.o, P, dmid_op, d_, R, tmp32_, d_, nullptr));   // d(om), fp32
       // dP = dO V^T ; dV = P^T dO ; dS = P (dP - rowsum(dP P)) ; dQ = dS K / sqrt(dh) ; dK = dS^T Q / sqrt(dh)
       if (mfma_attn_) {
@@ -227,8 +221,9 @@ class Encoder final : public Model {
       VF_K(c, "attn_bwd_dk", launch_bgemm(score_mat(scores_, 1, false, true), kt_mat(B.qkv_act, 0), qkv_mat(dqkv_, 1),
                                           T_, dh_, T_, heads, nh_, scale, st));
       }
-      VF_K(c, "colsum", launch_colsum_rows(dqkv_, 3 * d_, bf16_, R, 3 * d_, red_, c.gout(B.qkv.b_off, w, i), st));
-      VF_TRY(lin_bwd_w(c, "gemm_wgrad", B.qkv, B.a, d_, dqkv_, 3 * d_, R, c.gout(B.qkv.w_off, w, i)));
+      const void* dqkv_op = dqkv_;
+      VF_TRY(prepare_dy(c, dqkv_, !bf16_, 3 * d_, R, 3 * d_, c.gout(B.qkv.b_off, w, i), &dqkv_op, &dyT));
+      VF_TRY(lin_bwd_w(c, "gemm_wgrad", B.qkv, B.a, d_, dqkv_, 3 * d_, R, c.gout(B.qkv.w_off, w, i), dyT));
       VF_TRY(lin_bwd_x(c, "gemm_dgrad", B.qkv, P, dqkv_, 3 * d_, R, tmp32_, d_, nullptr));
       VF_K(c, "layernorm_bwd", launch_layernorm_bwd(tmp32_, 1, 0, d_, B.hin, d_, nullptr, R, d_, P + B.ln1_g,
                                                     bf16_, B.mean1, B.rstd1, dmid_, dh_buf_, d_, red_,
@@ -286,16 +281,42 @@ class Encoder final : public Model {
     return VF_OK;
   }
 
-  // dW[K, N] = in^T dy through GradOut
+  // The gradient dy [R, C] at a Linear layer's output (fp32, or the workload's type), readied for
+  // that layer's backward pass: the bias gradient through gb, *op = what the products read as dy
+  // (a bf16 copy of an fp32 dy in bf16 workloads), *transposed = whether tB_ already holds dy^T
+  // for the weight gradient.  bf16 workloads whose shapes qualify get all of it from one pass.
+  int prepare_dy(Ctx& c, const void* dy, bool dy_is_f32, int64_t lddy, int R, int C, GradOut gb,
+                 const void** op, bool* transposed) {
+    hipStream_t st = stream_;
+    const int64_t ldr = round8(R);
+    *op = dy;
+    *transposed = false;
+    if (bf16_ && dy_prepare_fits(dy_is_f32, lddy, lddy, ldr, R, C)) {
+      VF_K(c, "dy_prepare", launch_dy_prepare(dy, dy_is_f32, lddy, R, C, static_cast<bf16_t*>(cast_), lddy, tB_, ldr,
+                                              red_, gb, st));
+      if (dy_is_f32) *op = cast_;
+      *transposed = true;
+      return VF_OK;
+    }
+    if (bf16_ && dy_is_f32) {
+      VF_K(c, "cast", launch_cast_bf16(static_cast<const float*>(dy), lddy, static_cast<bf16_t*>(cast_), lddy, R, C, st));
+      *op = cast_;
+    }
+    VF_K(c, "colsum", launch_colsum_rows(dy, lddy, dy_is_f32 ? 0 : bf16_, R, C, red_, gb, st));
+    return VF_OK;
+  }
+
+  // dW[K, N] = in^T dy through GradOut (dy_transposed: tB_ already holds dy^T)
   int lin_bwd_w(Ctx& c, const char* tag, const Lin& L, const void* in, int64_t ldin, const void* dy,
-                int64_t lddy, int R, GradOut go) {
+                int64_t lddy, int R, GradOut go, bool dy_transposed = false) {
     Epilogue ep;
     ep.C = go.dst; ep.ldc = L.N; ep.alpha = go.alpha;
     if (go.accumulate) { ep.R = go.dst; ep.ldr = L.N; ep.beta = 1.f; }
     if (bf16_) {
       const int64_t ldr = round8(R);
       VF_K(c, "transpose", launch_transpose_bf16(static_cast<const bf16_t*>(in), ldin, tA_, ldr, R, L.K, stream_));
-      VF_K(c, "transpose", launch_transpose_bf16(static_cast<const bf16_t*>(dy), lddy, tB_, ldr, R, L.N, stream_));
+      if (!dy_transposed)
+        VF_K(c, "transpose", launch_transpose_bf16(static_cast<const bf16_t*>(dy), lddy, tB_, ldr, R, L.N, stream_));
       VF_K(c, tag, launch_gemm_bf16(tA_, ldr, tB_, ldr, L.K, L.N, R, 1, 0, ep, stream_));
     } else {
       VF_K(c, tag, launch_gemm_f32(static_cast<const float*>(in), 1, ldin, static_cast<const float*>(dy), 1, lddy,

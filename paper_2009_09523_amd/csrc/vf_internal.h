@@ -273,6 +273,14 @@ int launch_layernorm_bwd(const float* dyp, int nsplit, int64_t slab, int64_t ldd
 // scratch: kReduceChunks * C floats.
 int launch_colsum_rows(const void* x, int64_t ld, int x_is_bf16, int R, int C, float* scratch, GradOut out,
                        hipStream_t s);
+// The gradient dy [R, C] at the output of a Linear layer, prepared for that layer's backward pass
+// in one pass: transposed bf16 copy tr [C, ldt], (fp32 dy) bf16 copy nat [R, ldn], and the column
+// sums (the bias gradient) through GradOut, 64-row tiles added in order.  dy_prepare_fits says
+// whether the shapes qualify (alignment of the leading dimensions, at most kReduceChunks row
+// tiles); bases 16-byte aligned; scratch: kReduceChunks * C floats.
+bool dy_prepare_fits(int dy_is_f32, int64_t ldi, int64_t ldn, int64_t ldt, int R, int C);
+int launch_dy_prepare(const void* dy, int dy_is_f32, int64_t ldi, int R, int C, bf16_t* nat, int64_t ldn,
+                      bf16_t* tr, int64_t ldt, float* scratch, GradOut out, hipStream_t s);
 // exact GELU: g = 0.5 u (1 + erf(u / sqrt 2))
 int launch_gelu_fwd(const void* u, void* g, int is_bf16, int64_t n, hipStream_t s);
 // du = dg * (Phi(u) + u phi(u));  dg fp32, u and du T
