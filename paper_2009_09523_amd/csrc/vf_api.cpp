@@ -375,7 +375,7 @@ int vf_init(const vf_config* cfg, vf_ctx** out) {
   if (!c.model) { delete h; return VF_EINVAL; }
   c.P = c.model->num_params();
   // Overlap needs a capturable main stream and a model that double-buffers what the side
-  // stream reads (the bf16 MLP does).
+  // stream reads (the bf16 MLP and the bf16 encoder do).
   c.overlap = c.stream != nullptr && (cfg->flags & VF_FLAG_OVERLAP) && c.model->supports_overlap();
   // A window needs the fused fold: a staged node's gradient lives in one staging vector.
   c.window = (!c.fused || cfg->fold_window < 1) ? 1 : std::min(cfg->fold_window, c.model->max_window());

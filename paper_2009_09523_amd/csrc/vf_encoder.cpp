@@ -21,9 +21,8 @@ struct Lin {
   bf16_t* wtr = nullptr;    // bf16 W^T [N, ldt]
 };
 
-struct Block {
-  int64_t ln1_g, ln1_b, ln2_g, ln2_b;
-  Lin qkv, o, w1, w2;
+// What a node's forward part leaves for its backward part, per block (one set per node in flight).
+struct BlockActs {
   float* hin = nullptr;                 // fp32 [R, d] input of the block (residual stream)
   float *mean1 = nullptr, *rstd1 = nullptr, *mean2 = nullptr, *rstd2 = nullptr;
   void* a = nullptr;                    // T [R, d]   LN1 output
@@ -34,6 +33,21 @@ struct Block {
   void* f = nullptr;                    // T [R, d]   LN2 output
   void* u = nullptr;                    // T [R, ffn] FFN pre-activation
   void* g = nullptr;                    // T [R, ffn] gelu(u)
+};
+
+struct Block {
+  int64_t ln1_g, ln1_b, ln2_g, ln2_b;
+  Lin qkv, o, w1, w2;
+  BlockActs x[2];
+};
+
+// ... and after the blocks: the masked rows, their statistics, labels and logit gradients.
+struct HeadActs {
+  float* hlast = nullptr;               // fp32 [R, d] output of the last block
+  int32_t *rowidx = nullptr, *labels = nullptr;
+  float *meanf = nullptr, *rstdf = nullptr;
+  void* rows = nullptr;                 // T [Rm, d] final LayerNorm of the masked rows
+  void* dlogits = nullptr;              // T [Rm, ldV]
 };
 
 class Encoder final : public Model {
@@ -70,28 +84,37 @@ class Encoder final : public Model {
     ldV_ = round8(V_);
     out_split_max_ = 32;
     mfma_attn_ = bf16_ && attn_mfma_supported(T_, dh_);
+    // two nodes in flight (forward of one beside the backward of the other) need two sets of
+    // what passes from a forward to its backward part
+    sets_ = (supports_overlap() && (cfg.flags & VF_FLAG_OVERLAP)) ? 2 : 1;
   }
 
   int64_t num_params() const override { return P_; }
+  // the forward part of the fp32 / non-MFMA attention path shares its score scratch with the backward part
+  bool supports_overlap() const override { return bf16_ && mfma_attn_; }
 
   void request_buffers(Arena& a) override {
     const size_t esz = bf16_ ? 2 : 4;
     const size_t R = (size_t)maxR_, Rm = (size_t)maxRm_;
     const size_t heads = (size_t)cfg_.max_node_size * nh_;
     auto act = [&](void** p, size_t n) { a.request(reinterpret_cast<char**>(p), n * esz); };
-    for (Block& B : blocks_) {
-      a.request(&B.hin, R * d_);
-      a.request(&B.mean1, R); a.request(&B.rstd1, R); a.request(&B.mean2, R); a.request(&B.rstd2, R);
-      act(&B.a, R * d_); act(&B.qkv_act, R * 3 * d_); act(&B.prob, heads * T_ * T_); act(&B.om, R * d_);
-      a.request(&B.hmid, R * d_);
-      act(&B.f, R * d_); act(&B.u, R * f_); act(&B.g, R * f_);
+    for (int q = 0; q < sets_; ++q) {
+      for (Block& B : blocks_) {
+        BlockActs& X = B.x[q];
+        a.request(&X.hin, R * d_);
+        a.request(&X.mean1, R); a.request(&X.rstd1, R); a.request(&X.mean2, R); a.request(&X.rstd2, R);
+        act(&X.a, R * d_); act(&X.qkv_act, R * 3 * d_); act(&X.prob, heads * T_ * T_); act(&X.om, R * d_);
+        a.request(&X.hmid, R * d_);
+        act(&X.f, R * d_); act(&X.u, R * f_); act(&X.g, R * f_);
+      }
+      HeadActs& H = head_[q];
+      a.request(&H.hlast, R * d_);
+      a.request(&H.rowidx, Rm); a.request(&H.labels, Rm);
+      a.request(&H.meanf, Rm); a.request(&H.rstdf, Rm);
+      act(&H.rows, Rm * d_);
+      act(&H.dlogits, Rm * ldV_);
     }
-    a.request(&hlast_, R * d_);
-    a.request(&rowidx_, Rm); a.request(&labels_, Rm);
-    a.request(&meanf_, Rm); a.request(&rstdf_, Rm);
-    act(&rows_, Rm * d_);
     a.request(&logits_, Rm * ldV_);
-    act(&dlogits_, Rm * ldV_);
     a.request(&scores_, heads * T_ * T_);
     a.request(&dh_buf_, R * d_);
     a.request(&dmid_, R * d_);
@@ -127,7 +150,15 @@ class Encoder final : public Model {
   }
 
   int run_node_main(Ctx& c, const StepArgs& s, int i, hipStream_t st) override {
+    VF_TRY(run_node_fwd(c, s, i, st));
+    return run_node_bwd(c, s, i, st);
+  }
+
+  // Forward pass and loss of node i.
+  int run_node_fwd(Ctx& c, const StepArgs& s, int i, hipStream_t st) override {
     stream_ = st;
+    const int q = std::min(c.aset(i), sets_ - 1);
+    HeadActs& H = head_[q];
     const int b = s.sizes[i];
     const int64_t row0 = s.off[i];
     const float w = s.w[i];
@@ -140,100 +171,121 @@ class Encoder final : public Model {
     const float scale = 1.0f / std::sqrt((float)dh_);
 
     // ---- forward -----------------------------------------------------------------------
-    VF_K(c, "extract_masked", launch_extract_masked(y, b, m_, T_, V_, rowidx_, labels_, st));
-    VF_K(c, "embed_fwd", launch_embed_fwd(ids, P + tok_off_, P + pos_off_, R, T_, d_, V_, bf16_,
-                                          blocks_[0].hin, st));
+    VF_KS(c, st, "extract_masked", launch_extract_masked(y, b, m_, T_, V_, H.rowidx, H.labels, st));
+    VF_KS(c, st, "embed_fwd", launch_embed_fwd(ids, P + tok_off_, P + pos_off_, R, T_, d_, V_, bf16_,
+                                          blocks_[0].x[q].hin, st));
     for (int l = 0; l < nl; ++l) {
       Block& B = blocks_[l];
-      float* hnext = l + 1 < nl ? blocks_[l + 1].hin : hlast_;
-      VF_K(c, "layernorm_fwd", launch_layernorm_fwd(B.hin, d_, nullptr, R, d_, P + B.ln1_g, P + B.ln1_b, bf16_,
-                                                    cfg_.ln_eps, B.a, d_, bf16_, B.mean1, B.rstd1, st));
-      VF_TRY(lin_fwd(c, "gemm_fwd", B.qkv, P, B.a, d_, R, B.qkv_act, 3 * d_, true, nullptr));
+      BlockActs& X = B.x[q];
+      float* hnext = l + 1 < nl ? blocks_[l + 1].x[q].hin : H.hlast;
+      VF_KS(c, st, "layernorm_fwd", launch_layernorm_fwd(X.hin, d_, nullptr, R, d_, P + B.ln1_g, P + B.ln1_b, bf16_,
+                                                    cfg_.ln_eps, X.a, d_, bf16_, X.mean1, X.rstd1, st));
+      VF_TRY(lin_fwd(c, "gemm_fwd", B.qkv, P, X.a, d_, R, X.qkv_act, 3 * d_, true, nullptr));
       if (mfma_attn_) {
-        VF_K(c, "attn_fwd", launch_attn_fwd(static_cast<const bf16_t*>(B.qkv_act), b, T_, d_, nh_,
-                                            static_cast<bf16_t*>(B.prob), static_cast<bf16_t*>(B.om), scale, st));
+        VF_KS(c, st, "attn_fwd", launch_attn_fwd(static_cast<const bf16_t*>(X.qkv_act), b, T_, d_, nh_,
+                                            static_cast<bf16_t*>(X.prob), static_cast<bf16_t*>(X.om), scale, st));
       } else {
-        VF_K(c, "attn_scores", launch_bgemm(qkv_mat(B.qkv_act, 0), qkv_mat(B.qkv_act, 1), score_mat(scores_, 0, false),
+        VF_KS(c, st, "attn_scores", launch_bgemm(qkv_mat(X.qkv_act, 0), qkv_mat(X.qkv_act, 1), score_mat(scores_, 0, false),
                                             T_, T_, dh_, heads, nh_, scale, st));
-        VF_K(c, "attn_softmax", launch_softmax_rows(scores_, B.prob, bf16_, (int64_t)heads * T_, T_, st));
-        VF_K(c, "attn_pv", launch_bgemm(score_mat(B.prob, 0, bf16_), vt_mat(B.qkv_act), merged_mat(B.om, bf16_),
+        VF_KS(c, st, "attn_softmax", launch_softmax_rows(scores_, X.prob, bf16_, (int64_t)heads * T_, T_, st));
+        VF_KS(c, st, "attn_pv", launch_bgemm(score_mat(X.prob, 0, bf16_), vt_mat(X.qkv_act), merged_mat(X.om, bf16_),
                                         T_, dh_, T_, heads, nh_, 1.0f, st));
       }
-      VF_TRY(lin_fwd(c, "gemm_fwd", B.o, P, B.om, d_, R, B.hmid, d_, false, B.hin));
-      VF_K(c, "layernorm_fwd", launch_layernorm_fwd(B.hmid, d_, nullptr, R, d_, P + B.ln2_g, P + B.ln2_b, bf16_,
-                                                    cfg_.ln_eps, B.f, d_, bf16_, B.mean2, B.rstd2, st));
-      VF_TRY(lin_fwd(c, "gemm_fwd", B.w1, P, B.f, d_, R, B.u, f_, true, nullptr));
-      VF_K(c, "gelu_fwd", launch_gelu_fwd(B.u, B.g, bf16_, (int64_t)R * f_, st));
-      VF_TRY(lin_fwd(c, "gemm_fwd", B.w2, P, B.g, f_, R, hnext, d_, false, B.hmid));
+      VF_TRY(lin_fwd(c, "gemm_fwd", B.o, P, X.om, d_, R, X.hmid, d_, false, X.hin));
+      VF_KS(c, st, "layernorm_fwd", launch_layernorm_fwd(X.hmid, d_, nullptr, R, d_, P + B.ln2_g, P + B.ln2_b, bf16_,
+                                                    cfg_.ln_eps, X.f, d_, bf16_, X.mean2, X.rstd2, st));
+      VF_TRY(lin_fwd(c, "gemm_fwd", B.w1, P, X.f, d_, R, X.u, f_, true, nullptr));
+      VF_KS(c, st, "gelu_fwd", launch_gelu_fwd(X.u, X.g, bf16_, (int64_t)R * f_, st));
+      VF_TRY(lin_fwd(c, "gemm_fwd", B.w2, P, X.g, f_, R, hnext, d_, false, X.hmid));
     }
-    VF_K(c, "layernorm_fwd", launch_layernorm_fwd(hlast_, d_, rowidx_, Rm, d_, P + lnf_g_, P + lnf_b_, bf16_,
-                                                  cfg_.ln_eps, rows_, d_, bf16_, meanf_, rstdf_, st));
-    VF_TRY(lin_fwd(c, "gemm_head", out_, P, rows_, d_, Rm, logits_, ldV_, false, nullptr));
-    VF_K(c, "softmax_xent", launch_softmax_xent(logits_, 1, 0, ldV_, logits_, ldV_, labels_, Rm, V_, c.rowloss,
-                                                dlogits_, ldV_, bf16_, nullptr, 0, w, i, c.node_loss, c.loss_total, st));
+    VF_KS(c, st, "layernorm_fwd", launch_layernorm_fwd(H.hlast, d_, H.rowidx, Rm, d_, P + lnf_g_, P + lnf_b_, bf16_,
+                                                  cfg_.ln_eps, H.rows, d_, bf16_, H.meanf, H.rstdf, st));
+    VF_TRY(lin_fwd(c, "gemm_head", out_, P, H.rows, d_, Rm, logits_, ldV_, false, nullptr));
+    VF_KS(c, st, "softmax_xent", launch_softmax_xent(logits_, 1, 0, ldV_, logits_, ldV_, H.labels, Rm, V_, c.rowloss,
+                                                H.dlogits, ldV_, bf16_, nullptr, 0, w, i, c.node_loss, c.loss_total, st));
+
+    return VF_OK;
+  }
+
+  // Backward pass of node i: every gradient through GradOut, in node order on one stream.
+  int run_node_bwd(Ctx& c, const StepArgs& s, int i, hipStream_t st) override {
+    stream_ = st;
+    const int q = std::min(c.aset(i), sets_ - 1);
+    HeadActs& H = head_[q];
+    const int b = s.sizes[i];
+    const int64_t row0 = s.off[i];
+    const float w = s.w[i];
+    const float* P = s.params;
+    const int R = b * T_, Rm = b * m_;
+    const int nl = (int)blocks_.size();
+    const int heads = b * nh_;
+    const int32_t* ids = static_cast<const int32_t*>(s.x) + row0 * T_;
+    const float scale = 1.0f / std::sqrt((float)dh_);
+    (void)heads;
 
     // ---- backward: output head -----------------------------------------------------------
-    VF_K(c, "colsum", launch_colsum_rows(dlogits_, ldV_, bf16_, Rm, V_, red_, c.gout(out_.b_off, w, i), st));
-    VF_TRY(lin_bwd_w(c, "gemm_head_wgrad", out_, rows_, d_, dlogits_, ldV_, Rm, c.gout(out_.w_off, w, i)));
+    VF_KS(c, st, "colsum", launch_colsum_rows(H.dlogits, ldV_, bf16_, Rm, V_, red_, c.gout(out_.b_off, w, i), st));
+    VF_TRY(lin_bwd_w(c, "gemm_head_wgrad", out_, H.rows, d_, H.dlogits, ldV_, Rm, c.gout(out_.w_off, w, i)));
     int osplit = 1;
-    VF_TRY(lin_bwd_x(c, "gemm_head_dgrad", out_, P, dlogits_, ldV_, Rm, drows_, d_, &osplit));
+    VF_TRY(lin_bwd_x(c, "gemm_head_dgrad", out_, P, H.dlogits, ldV_, Rm, drows_, d_, &osplit));
     const int64_t oslab = (int64_t)Rm * d_;
-    VF_K(c, "fill", launch_fill_f32(dh_buf_, 0.f, (int64_t)R * d_, st));
-    VF_K(c, "layernorm_bwd", launch_layernorm_bwd(drows_, osplit, oslab, d_, hlast_, d_, rowidx_, Rm, d_,
-                                                  P + lnf_g_, bf16_, meanf_, rstdf_, nullptr, dh_buf_, d_, red_,
+    VF_KS(c, st, "fill", launch_fill_f32(dh_buf_, 0.f, (int64_t)R * d_, st));
+    VF_KS(c, st, "layernorm_bwd", launch_layernorm_bwd(drows_, osplit, oslab, d_, H.hlast, d_, H.rowidx, Rm, d_,
+                                                  P + lnf_g_, bf16_, H.meanf, H.rstdf, nullptr, dh_buf_, d_, red_,
                                                   c.gout(lnf_g_, w, i), c.gout(lnf_b_, w, i), st));
 
     // ---- backward: blocks -------------------------------------------------------------------
     for (int l = nl - 1; l >= 0; --l) {
       Block& B = blocks_[l];
+      BlockActs& X = B.x[q];
       // FFN
       const void* dh_op = dh_buf_;
       bool dyT = false;
       VF_TRY(prepare_dy(c, dh_buf_, true, d_, R, d_, c.gout(B.w2.b_off, w, i), &dh_op, &dyT));
-      VF_TRY(lin_bwd_w(c, "gemm_wgrad", B.w2, B.g, f_, dh_op, d_, R, c.gout(B.w2.w_off, w, i), dyT));
+      VF_TRY(lin_bwd_w(c, "gemm_wgrad", B.w2, X.g, f_, dh_op, d_, R, c.gout(B.w2.w_off, w, i), dyT));
       VF_TRY(lin_bwd_x(c, "gemm_dgrad", B.w2, P, dh_op, d_, R, tmp32_, f_, nullptr));
-      VF_K(c, "gelu_bwd", launch_gelu_bwd(tmp32_, B.u, du_, bf16_, (int64_t)R * f_, st));
+      VF_KS(c, st, "gelu_bwd", launch_gelu_bwd(tmp32_, X.u, du_, bf16_, (int64_t)R * f_, st));
       const void* du_op = du_;
       VF_TRY(prepare_dy(c, du_, !bf16_, f_, R, f_, c.gout(B.w1.b_off, w, i), &du_op, &dyT));
-      VF_TRY(lin_bwd_w(c, "gemm_wgrad", B.w1, B.f, d_, du_, f_, R, c.gout(B.w1.w_off, w, i), dyT));
+      VF_TRY(lin_bwd_w(c, "gemm_wgrad", B.w1, X.f, d_, du_, f_, R, c.gout(B.w1.w_off, w, i), dyT));
       VF_TRY(lin_bwd_x(c, "gemm_dgrad", B.w1, P, du_, f_, R, tmp32_, d_, nullptr));
-      VF_K(c, "layernorm_bwd", launch_layernorm_bwd(tmp32_, 1, 0, d_, B.hmid, d_, nullptr, R, d_, P + B.ln2_g,
-                                                    bf16_, B.mean2, B.rstd2, dh_buf_, dmid_, d_, red_,
+      VF_KS(c, st, "layernorm_bwd", launch_layernorm_bwd(tmp32_, 1, 0, d_, X.hmid, d_, nullptr, R, d_, P + B.ln2_g,
+                                                    bf16_, X.mean2, X.rstd2, dh_buf_, dmid_, d_, red_,
                                                     c.gout(B.ln2_g, w, i), c.gout(B.ln2_b, w, i), st));
       // attention
       const void* dmid_op = dmid_;
       VF_TRY(prepare_dy(c, dmid_, true, d_, R, d_, c.gout(B.o.b_off, w, i), &dmid_op, &dyT));
-      VF_TRY(lin_bwd_w(c, "gemm_wgrad", B.o, B.om, d_, dmid_op, d_, R, c.gout(B.o.w_off, w, i), dyT));
+      VF_TRY(lin_bwd_w(c, "gemm_wgrad", B.o, X.om, d_, dmid_op, d_, R, c.gout(B.o.w_off, w, i), dyT));
       VF_TRY(lin_bwd_x(c, "gemm_dgrad", B.o, P, dmid_op, d_, R, tmp32_, d_, nullptr));   // d(om), fp32
       // dP = dO V^T ; dV = P^T dO ; dS = P (dP - rowsum(dP P)) ; dQ = dS K / sqrt(dh) ; dK = dS^T Q / sqrt(dh)
       if (mfma_attn_) {
-        VF_K(c, "attn_bwd", launch_attn_bwd(tmp32_, static_cast<const bf16_t*>(B.qkv_act),
-                                            static_cast<const bf16_t*>(B.prob), b, T_, d_, nh_,
+        VF_KS(c, st, "attn_bwd", launch_attn_bwd(tmp32_, static_cast<const bf16_t*>(X.qkv_act),
+                                            static_cast<const bf16_t*>(X.prob), b, T_, d_, nh_,
                                             static_cast<bf16_t*>(dqkv_), scale, st));
       } else {
-      VF_K(c, "attn_bwd_dp", launch_bgemm(merged_mat(tmp32_, false, true), qkv_mat(B.qkv_act, 2), score_mat(scores_, 0, false),
+      VF_KS(c, st, "attn_bwd_dp", launch_bgemm(merged_mat(tmp32_, false, true), qkv_mat(X.qkv_act, 2), score_mat(scores_, 0, false),
                                           T_, T_, dh_, heads, nh_, 1.0f, st));
-      VF_K(c, "attn_bwd_dv", launch_bgemm(score_mat(B.prob, 1, bf16_), merged_t_mat(tmp32_), qkv_mat(dqkv_, 2),
+      VF_KS(c, st, "attn_bwd_dv", launch_bgemm(score_mat(X.prob, 1, bf16_), merged_t_mat(tmp32_), qkv_mat(dqkv_, 2),
                                           T_, dh_, T_, heads, nh_, 1.0f, st));
-      VF_K(c, "attn_softmax_bwd", launch_softmax_rows_bwd(scores_, B.prob, bf16_, (int64_t)heads * T_, T_, st));
-      VF_K(c, "attn_bwd_dq", launch_bgemm(score_mat(scores_, 0, false, true), kt_mat(B.qkv_act, 1), qkv_mat(dqkv_, 0),
+      VF_KS(c, st, "attn_softmax_bwd", launch_softmax_rows_bwd(scores_, X.prob, bf16_, (int64_t)heads * T_, T_, st));
+      VF_KS(c, st, "attn_bwd_dq", launch_bgemm(score_mat(scores_, 0, false, true), kt_mat(X.qkv_act, 1), qkv_mat(dqkv_, 0),
                                           T_, dh_, T_, heads, nh_, scale, st));
-      VF_K(c, "attn_bwd_dk", launch_bgemm(score_mat(scores_, 1, false, true), kt_mat(B.qkv_act, 0), qkv_mat(dqkv_, 1),
+      VF_KS(c, st, "attn_bwd_dk", launch_bgemm(score_mat(scores_, 1, false, true), kt_mat(X.qkv_act, 0), qkv_mat(dqkv_, 1),
                                           T_, dh_, T_, heads, nh_, scale, st));
       }
       const void* dqkv_op = dqkv_;
       VF_TRY(prepare_dy(c, dqkv_, !bf16_, 3 * d_, R, 3 * d_, c.gout(B.qkv.b_off, w, i), &dqkv_op, &dyT));
-      VF_TRY(lin_bwd_w(c, "gemm_wgrad", B.qkv, B.a, d_, dqkv_, 3 * d_, R, c.gout(B.qkv.w_off, w, i), dyT));
+      VF_TRY(lin_bwd_w(c, "gemm_wgrad", B.qkv, X.a, d_, dqkv_, 3 * d_, R, c.gout(B.qkv.w_off, w, i), dyT));
       VF_TRY(lin_bwd_x(c, "gemm_dgrad", B.qkv, P, dqkv_, 3 * d_, R, tmp32_, d_, nullptr));
-      VF_K(c, "layernorm_bwd", launch_layernorm_bwd(tmp32_, 1, 0, d_, B.hin, d_, nullptr, R, d_, P + B.ln1_g,
-                                                    bf16_, B.mean1, B.rstd1, dmid_, dh_buf_, d_, red_,
+      VF_KS(c, st, "layernorm_bwd", launch_layernorm_bwd(tmp32_, 1, 0, d_, X.hin, d_, nullptr, R, d_, P + B.ln1_g,
+                                                    bf16_, X.mean1, X.rstd1, dmid_, dh_buf_, d_, red_,
                                                     c.gout(B.ln1_g, w, i), c.gout(B.ln1_b, w, i), st));
     }
     // ---- backward: embeddings ----------------------------------------------------------------
-    VF_K(c, "embed_bwd", launch_embed_pos_bwd(dh_buf_, b, T_, d_, c.gout(pos_off_, w, i), st));
+    VF_KS(c, st, "embed_bwd", launch_embed_pos_bwd(dh_buf_, b, T_, d_, c.gout(pos_off_, w, i), st));
     GradOut gt = c.gout(tok_off_, w, i);
-    if (!c.fused || i == 0) VF_K(c, "fill", launch_fill_f32(gt.dst, 0.f, (int64_t)V_ * d_, st));
-    VF_K(c, "embed_bwd", launch_embed_tok_bwd(ids, dh_buf_, R, d_, V_, gt, st));
+    if (!c.fused || i == 0) VF_KS(c, st, "fill", launch_fill_f32(gt.dst, 0.f, (int64_t)V_ * d_, st));
+    VF_KS(c, st, "embed_bwd", launch_embed_tok_bwd(ids, dh_buf_, R, d_, V_, gt, st));
     return VF_OK;
   }
 
@@ -273,10 +325,10 @@ class Encoder final : public Model {
     ep.bias = P + L.b_off; ep.bias_round_bf16 = bf16_;
     if (residual) { ep.R = residual; ep.ldr = ldo; ep.beta = 1.f; }
     if (bf16_)
-      VF_K(c, tag, launch_gemm_bf16(static_cast<const bf16_t*>(in), ldin, L.wtr, L.ldt, R, L.N, L.K, 1, 0, ep,
+      VF_KS(c, stream_, tag, launch_gemm_bf16(static_cast<const bf16_t*>(in), ldin, L.wtr, L.ldt, R, L.N, L.K, 1, 0, ep,
                                     stream_));
     else
-      VF_K(c, tag, launch_gemm_f32(static_cast<const float*>(in), ldin, 1, P + L.w_off, 1, L.N, R, L.N, L.K, 1, 0, ep,
+      VF_KS(c, stream_, tag, launch_gemm_f32(static_cast<const float*>(in), ldin, 1, P + L.w_off, 1, L.N, R, L.N, L.K, 1, 0, ep,
                                    stream_));
     return VF_OK;
   }
@@ -292,17 +344,17 @@ class Encoder final : public Model {
     *op = dy;
     *transposed = false;
     if (bf16_ && dy_prepare_fits(dy_is_f32, lddy, lddy, ldr, R, C)) {
-      VF_K(c, "dy_prepare", launch_dy_prepare(dy, dy_is_f32, lddy, R, C, static_cast<bf16_t*>(cast_), lddy, tB_, ldr,
+      VF_KS(c, stream_, "dy_prepare", launch_dy_prepare(dy, dy_is_f32, lddy, R, C, static_cast<bf16_t*>(cast_), lddy, tB_, ldr,
                                               red_, gb, st));
       if (dy_is_f32) *op = cast_;
       *transposed = true;
       return VF_OK;
     }
     if (bf16_ && dy_is_f32) {
-      VF_K(c, "cast", launch_cast_bf16(static_cast<const float*>(dy), lddy, static_cast<bf16_t*>(cast_), lddy, R, C, st));
+      VF_KS(c, stream_, "cast", launch_cast_bf16(static_cast<const float*>(dy), lddy, static_cast<bf16_t*>(cast_), lddy, R, C, st));
       *op = cast_;
     }
-    VF_K(c, "colsum", launch_colsum_rows(dy, lddy, dy_is_f32 ? 0 : bf16_, R, C, red_, gb, st));
+    VF_KS(c, stream_, "colsum", launch_colsum_rows(dy, lddy, dy_is_f32 ? 0 : bf16_, R, C, red_, gb, st));
     return VF_OK;
   }
 
@@ -314,12 +366,12 @@ class Encoder final : public Model {
     if (go.accumulate) { ep.R = go.dst; ep.ldr = L.N; ep.beta = 1.f; }
     if (bf16_) {
       const int64_t ldr = round8(R);
-      VF_K(c, "transpose", launch_transpose_bf16(static_cast<const bf16_t*>(in), ldin, tA_, ldr, R, L.K, stream_));
+      VF_KS(c, stream_, "transpose", launch_transpose_bf16(static_cast<const bf16_t*>(in), ldin, tA_, ldr, R, L.K, stream_));
       if (!dy_transposed)
-        VF_K(c, "transpose", launch_transpose_bf16(static_cast<const bf16_t*>(dy), lddy, tB_, ldr, R, L.N, stream_));
-      VF_K(c, tag, launch_gemm_bf16(tA_, ldr, tB_, ldr, L.K, L.N, R, 1, 0, ep, stream_));
+        VF_KS(c, stream_, "transpose", launch_transpose_bf16(static_cast<const bf16_t*>(dy), lddy, tB_, ldr, R, L.N, stream_));
+      VF_KS(c, stream_, tag, launch_gemm_bf16(tA_, ldr, tB_, ldr, L.K, L.N, R, 1, 0, ep, stream_));
     } else {
-      VF_K(c, tag, launch_gemm_f32(static_cast<const float*>(in), 1, ldin, static_cast<const float*>(dy), 1, lddy,
+      VF_KS(c, stream_, tag, launch_gemm_f32(static_cast<const float*>(in), 1, ldin, static_cast<const float*>(dy), 1, lddy,
                                    L.K, L.N, R, 1, 0, ep, stream_));
     }
     return VF_OK;
@@ -336,11 +388,11 @@ class Encoder final : public Model {
         ns = std::min(gemm_bf16_pick_split(R, L.K, L.N), out_split_max_);
         *split = ns;
       }
-      VF_K(c, tag, launch_gemm_bf16(static_cast<const bf16_t*>(dy), lddy, L.wnat, L.ldn, R, L.K, L.N, ns,
+      VF_KS(c, stream_, tag, launch_gemm_bf16(static_cast<const bf16_t*>(dy), lddy, L.wnat, L.ldn, R, L.K, L.N, ns,
                                     (int64_t)R * lddx, ep, stream_));
     } else {
       if (split) *split = 1;
-      VF_K(c, tag, launch_gemm_f32(static_cast<const float*>(dy), lddy, 1, P + L.w_off, L.N, 1, R, L.K, L.N, 1, 0, ep,
+      VF_KS(c, stream_, tag, launch_gemm_f32(static_cast<const float*>(dy), lddy, 1, P + L.w_off, L.N, 1, R, L.K, L.N, 1, 0, ep,
                                    stream_));
     }
     return VF_OK;
@@ -357,12 +409,9 @@ class Encoder final : public Model {
   std::vector<Block> blocks_;
   std::vector<Lin*> lins_;
   Lin out_;
-  float* hlast_ = nullptr;
-  int32_t *rowidx_ = nullptr, *labels_ = nullptr;
-  float *meanf_ = nullptr, *rstdf_ = nullptr;
-  void* rows_ = nullptr;
+  HeadActs head_[2];
+  int sets_ = 1;
   float* logits_ = nullptr;
-  void* dlogits_ = nullptr;
   float* scores_ = nullptr;
   float *dh_buf_ = nullptr, *dmid_ = nullptr, *tmp32_ = nullptr;
   void *du_ = nullptr, *dqkv_ = nullptr, *cast_ = nullptr;

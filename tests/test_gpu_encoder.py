@@ -39,6 +39,36 @@ def test_encoder_fused_and_staged_agree_bitwise():
     assert a["G"].tobytes() == b["G"].tobytes()
 
 
+OVERLAP = 4
+
+
+@pytest.mark.parametrize("name,sizes", [("enc_small_bf16", None), ("enc_small_bf16", [2, 2, 1, 3, 1]),
+                                        ("enc_mid_bf16", [1, 1, 1, 1, 1])])
+def test_encoder_two_streams_agree_bitwise(name, sizes):
+    """Forward passes on one stream, backward passes on the other (two sets of what passes from a
+    node's forward to its backward part), staged and fused, replayed and launched one by one,
+    three steps: the same bits as one stream."""
+    print(f"case {name} sizes={sizes}", flush=True)
+    wl, theta, x, y = _case(name)
+    if sizes is not None:
+        assert sum(sizes) == wl.batch
+    base = run_gpu(wl, theta, x, y, node_sizes=sizes, flags=FUSED | NO_GRAPH, steps=3)
+    assert base["streams"] == 1
+    for flags in (OVERLAP, OVERLAP | NO_GRAPH, FUSED | OVERLAP, FUSED | OVERLAP | NO_GRAPH):
+        other = run_gpu(wl, theta, x, y, node_sizes=sizes, flags=flags, steps=3)
+        assert other["streams"] == 2, flags
+        assert base["G"].tobytes() == other["G"].tobytes(), flags
+        assert base["theta"].tobytes() == other["theta"].tobytes(), flags
+        assert base["loss"] == other["loss"], flags
+        assert base["node_losses"].tobytes() == other["node_losses"].tobytes(), flags
+
+
+def test_encoder_fp32_keeps_one_stream():
+    """The fp32 attention path shares its score scratch between the two passes: no second stream."""
+    wl, theta, x, y = _case("enc_small_f32")
+    assert run_gpu(wl, theta, x, y, flags=FUSED | OVERLAP | NO_GRAPH)["streams"] == 1
+
+
 def test_encoder_two_steps():
     wl, theta, x, y = _case("enc_small_f32")
     gpu = run_gpu(wl, theta, x, y, steps=2)
@@ -57,7 +87,9 @@ def test_c4_full_size():
     """4-layer encoder 768/12/3072, T=128, vocab 30522, B=256 in 16 nodes of 16, Adam."""
     print("full size C4", flush=True)
     wl, theta, x, y = _case("C4", jitter=0.0)
-    gpu = run_gpu(wl, theta, x, y)
     ref = oracle_steps(wl, theta, x, y)
-    check_against_oracle(wl, gpu, ref)
-    check_update_from_own_gradient(wl, gpu, theta, tol=1e-4)
+    for flags in (0, FUSED | OVERLAP | NO_GRAPH):      # the second is what bench.py times
+        print(f"flags {flags}", flush=True)
+        gpu = run_gpu(wl, theta, x, y, flags=flags)
+        check_against_oracle(wl, gpu, ref)
+        check_update_from_own_gradient(wl, gpu, theta, tol=1e-4)

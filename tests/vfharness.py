@@ -45,7 +45,7 @@ def run_gpu(wl, theta, x, y, node_sizes=None, flags=0, steps=1, max_node_size=No
     G = torch.empty_like(params)
     eng.grads(G)
     out = {"G": G.cpu().numpy(), "loss": eng.loss(), "node_losses": eng.node_losses(len(sizes)),
-           "t": eng.step_count, "workspace_bytes": eng.workspace_bytes}
+           "t": eng.step_count, "workspace_bytes": eng.workspace_bytes, "streams": eng.streams}
     s0 = torch.empty_like(params)
     eng.opt_state(0, s0)
     out["s0"] = s0.cpu().numpy()
