@@ -260,6 +260,30 @@ int enqueue_nodes(Ctx& c, const StepArgs& a, bool use_graph) {
   c.marking = !use_graph && !c.ranges.empty();
   const int nwin = (a.V + c.window - 1) / c.window;
   const int reach = std::max(1, std::min(2, c.copies() / c.window));
+  // Side part i on the forward stream, behind forward part i+1: it reads tensor set i & 1, which
+  // forward part i+2 -- enqueued after it on the same stream -- writes next, and what backward
+  // part i left for it, which backward part i+2 overwrites only after forward part i+2.
+  const bool beside = c.window == 1 && c.model->side_beside_forward(c);
+  if (beside) {
+    for (int i = 0; i < a.V; ++i) {
+      const int q = c.aset(i);
+      if (i >= 2) VF_HIP(hipStreamWaitEvent(c.stream, c.bwd_done[q], 0));
+      VF_TRY(run_part(c, a, use_graph, 1, i, c.stream));
+      VF_HIP(hipEventRecord(c.fwd_done[q], c.stream));
+      VF_HIP(hipStreamWaitEvent(c.side, c.fwd_done[q], 0));
+      VF_TRY(run_part(c, a, use_graph, 2, i, c.side));
+      VF_HIP(hipEventRecord(c.bwd_done[q], c.side));
+      if (i >= 1) {
+        VF_HIP(hipStreamWaitEvent(c.stream, c.bwd_done[q ^ 1], 0));
+        VF_TRY(run_part(c, a, use_graph, 3, i - 1, c.stream));
+      }
+    }
+    // join: the last backward part ends the second stream's work
+    c.last_side = c.bwd_done[c.aset(a.V - 1)];
+    VF_HIP(hipStreamWaitEvent(c.stream, c.last_side, 0));
+    VF_TRY(run_part(c, a, use_graph, 3, a.V - 1, c.stream));
+    return VF_OK;
+  }
   for (int w = 0; w < nwin; ++w) {
     const int i0 = w * c.window, i1 = std::min(a.V, i0 + c.window);
     // This window's forward parts overwrite operand copies that an earlier side part reads: the

@@ -92,6 +92,10 @@ class Model {
     return prepare(c, params, first);
   }
   virtual bool supports_overlap() const { return false; }
+  // Two streams: whether the side part of node i goes onto the forward stream, behind the forward
+  // part of node i+1 (and after waiting for backward part i), instead of following backward part
+  // i on the second stream.  For models whose backward part is the longer one.  Window 1 only.
+  virtual bool side_beside_forward(const Ctx&) const { return false; }
   // Stretches of the parameter vector (16-byte aligned starts, together all of it) in the order
   // in which the last side part of a step completes their gradients; the model calls
   // Ctx::mark_range(k) at that point.  Empty: the gradient is complete when the side part ends.

@@ -33,6 +33,9 @@ struct BlockActs {
   void* f = nullptr;                    // T [R, d]   LN2 output
   void* u = nullptr;                    // T [R, ffn] FFN pre-activation
   void* g = nullptr;                    // T [R, ffn] gelu(u)
+  // ... and what its backward part leaves for weight gradients taken later (deferred mode):
+  // the transposed output gradients [N, ldR] of w2, w1, o, qkv
+  bf16_t* dyT[4] = {nullptr, nullptr, nullptr, nullptr};
 };
 
 struct Block {
@@ -106,6 +109,10 @@ class Encoder final : public Model {
         act(&X.a, R * d_); act(&X.qkv_act, R * 3 * d_); act(&X.prob, heads * T_ * T_); act(&X.om, R * d_);
         a.request(&X.hmid, R * d_);
         act(&X.f, R * d_); act(&X.u, R * f_); act(&X.g, R * f_);
+        if (sets_ == 2) {
+          const int widths[4] = {d_, f_, d_, 3 * d_};
+          for (int k = 0; k < 4; ++k) a.request(&X.dyT[k], (size_t)widths[k] * ldR_);
+        }
       }
       HeadActs& H = head_[q];
       a.request(&H.hlast, R * d_);
@@ -128,6 +135,10 @@ class Encoder final : public Model {
       const size_t maxdim = (size_t)std::max(std::max(d_, f_), 3 * d_);
       a.request(&tA_, maxdim * ldR_);
       a.request(&tB_, std::max(maxdim * (size_t)ldR_, (size_t)V_ * round8(maxRm_)));
+      if (sets_ == 2) {   // the deferred weight gradients run beside a backward part: scratch of their own
+        a.request(&tA2_, maxdim * ldR_);
+        a.request(&tB2_, std::max(maxdim * (size_t)ldR_, (size_t)V_ * round8(maxRm_)));
+      }
       for (Lin* L : lins_) {
         a.request(&L->wnat, (size_t)L->K * L->ldn);
         a.request(&L->wtr, (size_t)L->N * L->ldt);
@@ -143,9 +154,17 @@ class Encoder final : public Model {
     return VF_OK;
   }
 
-  // The encoder keeps its whole node on one stream: the side part is only the fold.
+  // Two streams and the fused fold: the weight gradients of node i are not taken inside its
+  // backward part (the longer of the two parts) but as its side part, which the step enqueues on
+  // the forward stream behind the next node's forward part.  The backward part leaves them the
+  // transposed output gradients; the layers' inputs are still in the node's tensor set.
+  bool side_beside_forward(const Ctx& c) const override { return sets_ == 2 && c.overlap && c.fused; }
+
   int run_nodes_side(Ctx& c, const StepArgs& s, int i0, int count, hipStream_t st) override {
-    for (int i = i0; i < i0 + count; ++i) VF_TRY(c.fold(i, s.w[i], st));
+    for (int i = i0; i < i0 + count; ++i) {
+      if (side_beside_forward(c)) VF_TRY(deferred_wgrads(c, s, i, st));
+      VF_TRY(c.fold(i, s.w[i], st));   // staged mode only
+    }
     return VF_OK;
   }
 
@@ -225,6 +244,8 @@ class Encoder final : public Model {
 
     // ---- backward: output head -----------------------------------------------------------
     VF_KS(c, st, "colsum", launch_colsum_rows(H.dlogits, ldV_, bf16_, Rm, V_, red_, c.gout(out_.b_off, w, i), st));
+    const bool defer = side_beside_forward(c);
+    sA_ = tA_; sB_ = tB_;
     VF_TRY(lin_bwd_w(c, "gemm_head_wgrad", out_, H.rows, d_, H.dlogits, ldV_, Rm, c.gout(out_.w_off, w, i)));
     int osplit = 1;
     VF_TRY(lin_bwd_x(c, "gemm_head_dgrad", out_, P, H.dlogits, ldV_, Rm, drows_, d_, &osplit));
@@ -241,21 +262,21 @@ class Encoder final : public Model {
       // FFN
       const void* dh_op = dh_buf_;
       bool dyT = false;
-      VF_TRY(prepare_dy(c, dh_buf_, true, d_, R, d_, c.gout(B.w2.b_off, w, i), &dh_op, &dyT));
-      VF_TRY(lin_bwd_w(c, "gemm_wgrad", B.w2, X.g, f_, dh_op, d_, R, c.gout(B.w2.w_off, w, i), dyT));
+      VF_TRY(prepare_dy(c, dh_buf_, true, d_, R, d_, c.gout(B.w2.b_off, w, i), defer ? X.dyT[0] : nullptr, &dh_op, &dyT));
+      if (!(defer && dyT)) VF_TRY(lin_bwd_w(c, "gemm_wgrad", B.w2, X.g, f_, dh_op, d_, R, c.gout(B.w2.w_off, w, i), dyT));
       VF_TRY(lin_bwd_x(c, "gemm_dgrad", B.w2, P, dh_op, d_, R, tmp32_, f_, nullptr));
       VF_KS(c, st, "gelu_bwd", launch_gelu_bwd(tmp32_, X.u, du_, bf16_, (int64_t)R * f_, st));
       const void* du_op = du_;
-      VF_TRY(prepare_dy(c, du_, !bf16_, f_, R, f_, c.gout(B.w1.b_off, w, i), &du_op, &dyT));
-      VF_TRY(lin_bwd_w(c, "gemm_wgrad", B.w1, X.f, d_, du_, f_, R, c.gout(B.w1.w_off, w, i), dyT));
+      VF_TRY(prepare_dy(c, du_, !bf16_, f_, R, f_, c.gout(B.w1.b_off, w, i), defer ? X.dyT[1] : nullptr, &du_op, &dyT));
+      if (!(defer && dyT)) VF_TRY(lin_bwd_w(c, "gemm_wgrad", B.w1, X.f, d_, du_, f_, R, c.gout(B.w1.w_off, w, i), dyT));
       VF_TRY(lin_bwd_x(c, "gemm_dgrad", B.w1, P, du_, f_, R, tmp32_, d_, nullptr));
       VF_KS(c, st, "layernorm_bwd", launch_layernorm_bwd(tmp32_, 1, 0, d_, X.hmid, d_, nullptr, R, d_, P + B.ln2_g,
                                                     bf16_, X.mean2, X.rstd2, dh_buf_, dmid_, d_, red_,
                                                     c.gout(B.ln2_g, w, i), c.gout(B.ln2_b, w, i), st));
       // attention
       const void* dmid_op = dmid_;
-      VF_TRY(prepare_dy(c, dmid_, true, d_, R, d_, c.gout(B.o.b_off, w, i), &dmid_op, &dyT));
-      VF_TRY(lin_bwd_w(c, "gemm_wgrad", B.o, X.om, d_, dmid_op, d_, R, c.gout(B.o.w_off, w, i), dyT));
+      VF_TRY(prepare_dy(c, dmid_, true, d_, R, d_, c.gout(B.o.b_off, w, i), defer ? X.dyT[2] : nullptr, &dmid_op, &dyT));
+      if (!(defer && dyT)) VF_TRY(lin_bwd_w(c, "gemm_wgrad", B.o, X.om, d_, dmid_op, d_, R, c.gout(B.o.w_off, w, i), dyT));
       VF_TRY(lin_bwd_x(c, "gemm_dgrad", B.o, P, dmid_op, d_, R, tmp32_, d_, nullptr));   // d(om), fp32
       // dP = dO V^T ; dV = P^T dO ; dS = P (dP - rowsum(dP P)) ; dQ = dS K / sqrt(dh) ; dK = dS^T Q / sqrt(dh)
       if (mfma_attn_) {
@@ -274,8 +295,8 @@ class Encoder final : public Model {
                                           T_, dh_, T_, heads, nh_, scale, st));
       }
       const void* dqkv_op = dqkv_;
-      VF_TRY(prepare_dy(c, dqkv_, !bf16_, 3 * d_, R, 3 * d_, c.gout(B.qkv.b_off, w, i), &dqkv_op, &dyT));
-      VF_TRY(lin_bwd_w(c, "gemm_wgrad", B.qkv, X.a, d_, dqkv_, 3 * d_, R, c.gout(B.qkv.w_off, w, i), dyT));
+      VF_TRY(prepare_dy(c, dqkv_, !bf16_, 3 * d_, R, 3 * d_, c.gout(B.qkv.b_off, w, i), defer ? X.dyT[3] : nullptr, &dqkv_op, &dyT));
+      if (!(defer && dyT)) VF_TRY(lin_bwd_w(c, "gemm_wgrad", B.qkv, X.a, d_, dqkv_, 3 * d_, R, c.gout(B.qkv.w_off, w, i), dyT));
       VF_TRY(lin_bwd_x(c, "gemm_dgrad", B.qkv, P, dqkv_, 3 * d_, R, tmp32_, d_, nullptr));
       VF_KS(c, st, "layernorm_bwd", launch_layernorm_bwd(tmp32_, 1, 0, d_, X.hin, d_, nullptr, R, d_, P + B.ln1_g,
                                                     bf16_, X.mean1, X.rstd1, dmid_, dh_buf_, d_, red_,
@@ -336,16 +357,18 @@ class Encoder final : public Model {
   // The gradient dy [R, C] at a Linear layer's output (fp32, or the workload's type), readied for
   // that layer's backward pass: the bias gradient through gb, *op = what the products read as dy
   // (a bf16 copy of an fp32 dy in bf16 workloads), *transposed = whether tB_ already holds dy^T
-  // for the weight gradient.  bf16 workloads whose shapes qualify get all of it from one pass.
+  // (or `keep`, if given) for the weight gradient.  bf16 workloads whose shapes qualify get all of
+  // it from one pass.
   int prepare_dy(Ctx& c, const void* dy, bool dy_is_f32, int64_t lddy, int R, int C, GradOut gb,
-                 const void** op, bool* transposed) {
+                 bf16_t* keep, const void** op, bool* transposed) {
     hipStream_t st = stream_;
     const int64_t ldr = round8(R);
     *op = dy;
     *transposed = false;
     if (bf16_ && dy_prepare_fits(dy_is_f32, lddy, lddy, ldr, R, C)) {
-      VF_KS(c, stream_, "dy_prepare", launch_dy_prepare(dy, dy_is_f32, lddy, R, C, static_cast<bf16_t*>(cast_), lddy, tB_, ldr,
-                                              red_, gb, st));
+      // `keep`: where the transposed copy goes when the weight gradient is taken later
+      VF_KS(c, stream_, "dy_prepare", launch_dy_prepare(dy, dy_is_f32, lddy, R, C, static_cast<bf16_t*>(cast_), lddy,
+                                              keep ? keep : sB_, ldr, red_, gb, st));
       if (dy_is_f32) *op = cast_;
       *transposed = true;
       return VF_OK;
@@ -358,21 +381,48 @@ class Encoder final : public Model {
     return VF_OK;
   }
 
-  // dW[K, N] = in^T dy through GradOut (dy_transposed: tB_ already holds dy^T)
+  // dW[K, N] = in^T dy through GradOut.  dy_transposed: dy^T is already there, in `dyT` if given,
+  // else in the scratch sB_.
   int lin_bwd_w(Ctx& c, const char* tag, const Lin& L, const void* in, int64_t ldin, const void* dy,
-                int64_t lddy, int R, GradOut go, bool dy_transposed = false) {
+                int64_t lddy, int R, GradOut go, bool dy_transposed = false, const bf16_t* dyT = nullptr) {
     Epilogue ep;
     ep.C = go.dst; ep.ldc = L.N; ep.alpha = go.alpha;
     if (go.accumulate) { ep.R = go.dst; ep.ldr = L.N; ep.beta = 1.f; }
     if (bf16_) {
       const int64_t ldr = round8(R);
-      VF_KS(c, stream_, "transpose", launch_transpose_bf16(static_cast<const bf16_t*>(in), ldin, tA_, ldr, R, L.K, stream_));
+      VF_KS(c, stream_, "transpose", launch_transpose_bf16(static_cast<const bf16_t*>(in), ldin, sA_, ldr, R, L.K, stream_));
       if (!dy_transposed)
-        VF_KS(c, stream_, "transpose", launch_transpose_bf16(static_cast<const bf16_t*>(dy), lddy, tB_, ldr, R, L.N, stream_));
-      VF_KS(c, stream_, tag, launch_gemm_bf16(tA_, ldr, tB_, ldr, L.K, L.N, R, 1, 0, ep, stream_));
+        VF_KS(c, stream_, "transpose", launch_transpose_bf16(static_cast<const bf16_t*>(dy), lddy, sB_, ldr, R, L.N, stream_));
+      VF_KS(c, stream_, tag, launch_gemm_bf16(sA_, ldr, dy_transposed && dyT ? dyT : sB_, ldr, L.K, L.N, R, 1, 0, ep, stream_));
     } else {
       VF_KS(c, stream_, tag, launch_gemm_f32(static_cast<const float*>(in), 1, ldin, static_cast<const float*>(dy), 1, lddy,
                                    L.K, L.N, R, 1, 0, ep, stream_));
+    }
+    return VF_OK;
+  }
+
+  // The blocks' weight gradients that node i's backward part left out (see side_beside_forward),
+  // in the order the backward part would have taken them.
+  int deferred_wgrads(Ctx& c, const StepArgs& s, int i, hipStream_t st) {
+    stream_ = st;
+    sA_ = tA2_; sB_ = tB2_;
+    const int q = std::min(c.aset(i), sets_ - 1);
+    const float w = s.w[i];
+    const int R = s.sizes[i] * T_;
+    const int64_t ldr = round8(R);
+    for (int l = (int)blocks_.size() - 1; l >= 0; --l) {
+      Block& B = blocks_[l];
+      BlockActs& X = B.x[q];
+      const Lin* lins[4] = {&B.w2, &B.w1, &B.o, &B.qkv};
+      const void* ins[4] = {X.g, X.f, X.om, X.a};
+      const int64_t ldins[4] = {f_, d_, d_, d_};
+      const bool f32dy[4] = {true, false, true, false};
+      for (int k = 0; k < 4; ++k) {
+        const Lin& L = *lins[k];
+        // the backward part took this one itself when its shapes did not qualify for the one-pass preparation
+        if (!dy_prepare_fits(f32dy[k], L.N, L.N, ldr, R, L.N)) continue;
+        VF_TRY(lin_bwd_w(c, "gemm_wgrad", L, ins[k], ldins[k], nullptr, 0, R, c.gout(L.w_off, w, i), true, X.dyT[k]));
+      }
     }
     return VF_OK;
   }
@@ -418,6 +468,8 @@ class Encoder final : public Model {
   float* drows_ = nullptr;
   float* red_ = nullptr;                // scratch of the row-chunked reductions
   bf16_t *tA_ = nullptr, *tB_ = nullptr;
+  bf16_t *tA2_ = nullptr, *tB2_ = nullptr;   // the same scratch for weight gradients taken beside a backward part
+  bf16_t *sA_ = nullptr, *sB_ = nullptr;     // the scratch pair of the part being enqueued
 };
 
 }  // namespace
