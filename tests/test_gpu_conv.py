@@ -132,6 +132,8 @@ def test_eager_launches_are_repeatable():
     wl, theta, x, y = _case("conv_w64_bf16")
     base = run_gpu(wl, theta, x, y, flags=FUSED | NO_GRAPH)
     for flags in (FUSED | NO_GRAPH, NO_GRAPH):
-        for _ in range(1500):
+        for k in range(1500):
+            if k % 250 == 0:
+                print(f"flags {flags}: run {k}", flush=True)
             r = run_gpu(wl, theta, x, y, flags=flags)
             assert r["G"].tobytes() == base["G"].tobytes() and r["loss"] == base["loss"], flags
