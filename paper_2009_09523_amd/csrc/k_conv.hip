@@ -8,6 +8,8 @@
 // per-chunk partial results, then one small kernel that combines the chunks in chunk order, so
 // results do not depend on scheduling.  Loads go to clamped, always valid addresses ahead of any
 // selection, so that all of a thread's loads are in flight together.
+#include <algorithm>
+
 #include "vf_device.h"
 
 namespace vf {
@@ -465,12 +467,199 @@ __global__ __launch_bounds__(NT) void fold_slabs_kernel(const float* __restrict_
   grad_store(out, i, v);
 }
 
+// The same for many slabs: eight lanes per group of four elements, lane g adding slabs
+// g * per .. (g + 1) * per - 1 in order (eight 16-byte loads in flight), the eight sums then added in
+// lane order.  Requires n % 4 == 0, stride % 4 == 0, 16-byte aligned slabs.
+__global__ __launch_bounds__(NT) void fold_slabs_wide_kernel(const float* __restrict__ slabs, int nsplit, int64_t stride,
+                                                             int64_t n4, GradOut out) {
+  __shared__ float4 part[8][32];
+  const int q = threadIdx.x & 31, g = threadIdx.x >> 5;
+  const int64_t i4 = (int64_t)blockIdx.x * 32 + q;
+  const int per = (nsplit + 7) / 8;
+  const int sbeg = g * per, send = min(nsplit, sbeg + per);
+  float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (i4 < n4) {
+    const float4* base = reinterpret_cast<const float4*>(slabs) + i4;
+    const int64_t st4 = stride / 4;
+    int sl = sbeg;
+    for (; sl + 8 <= send; sl += 8) {
+      float4 t[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) t[u] = base[(int64_t)(sl + u) * st4];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) { v.x += t[u].x; v.y += t[u].y; v.z += t[u].z; v.w += t[u].w; }
+    }
+    for (; sl < send; ++sl) {
+      const float4 t = base[(int64_t)sl * st4];
+      v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
+    }
+  }
+  part[g][q] = v;
+  __syncthreads();
+  if (g == 0 && i4 < n4) {
+    float4 a = part[0][q];
+#pragma unroll
+    for (int k = 1; k < 8; ++k) { const float4 b = part[k][q]; a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w; }
+    grad_store(out, 4 * i4, a.x); grad_store(out, 4 * i4 + 1, a.y);
+    grad_store(out, 4 * i4 + 2, a.z); grad_store(out, 4 * i4 + 3, a.w);
+  }
+}
+
 inline int64_t blocks(int64_t n) { return (n + NT - 1) / NT; }
 inline bool tall_ok(int C) { return C >= 8 && C <= 256 && (C & 3) == 0; }
 inline size_t tall_lds(int C) {
   const int cg = C >> 2;
   const int rl = NT / cg < 1 ? 1 : NT / cg;
   return (size_t)cg * rl * sizeof(float4);
+}
+
+
+// ---- weight gradient of a 3x3 convolution straight from the stored tensors -------------------
+//   dW[o, tap, c] = sum over positions r of dy[r, o] * x[r + (kh-1) W + (kw-1), c]   (tap = 3 kh + kw;
+//   terms whose source lies outside r's image are 0)
+// for one 64 x 64 block of (o, c), all nine taps, and a slice of the positions.  The contraction
+// runs over positions, which both tensors store as ROWS (channels are contiguous), so neither is
+// in the orientation the matrix cores read (eight consecutive contraction elements per lane).
+// Instead of transposing both through memory and writing a transposed patch matrix, a stage of
+// 64 positions (64 / W image rows, W a power of two from 8 to 64) is staged in LDS as it is: the
+// 64 rows of dy, and the image rows of x from one above to one below the stage, each image row
+// with one empty position before and after it.  Image rows outside the image are fetched from a
+// block of zeros and the empty positions are cleared once, so every shifted read finds either
+// its value or 0 at a fixed offset: no masks.  Every lane gathers its operand elements with
+// 2-byte LDS reads (element j of a lane = position 16 kk + 2 j + lane/32 of the stage: the two
+// half-waves read rows of different parity, i.e. different halves of the LDS banks); the dy
+// operand of a contraction step serves all nine taps.
+// Workgroup (block, slice z) writes slab z of [Cout, 9 Cin]; the slabs are added in order
+// afterwards.  Requires Cout % 64 == 0, Cin % 64 == 0, H % (64 / W) == 0 (a stage lies within
+// one image), rows % 64 == 0.
+typedef __bf16 wg_bf16x8 __attribute__((ext_vector_type(8)));
+typedef float wg_f32x16 __attribute__((ext_vector_type(16)));
+
+// One stage of 64 positions for taps T0 .. T0+NTAP-1: A and B point at this lane's first element
+// of the dy rows and of the stored x positions.
+template <int W, int T0, int NTAP>
+__device__ __forceinline__ void wgrad_stage(const unsigned short* A, const unsigned short* B, wg_f32x16 (&acc)[5]) {
+  constexpr int PW = W + 2;
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) {
+    uint32_t av[4];
+#pragma unroll
+    for (int j = 0; j < 8; j += 2) {
+      const uint32_t lo = A[(16 * kk + 2 * j) * 64];
+      const uint32_t hi = A[(16 * kk + 2 * j + 2) * 64];
+      av[j >> 1] = lo | (hi << 16);
+    }
+    wg_bf16x8 a;
+    __builtin_memcpy(&a, av, 16);
+#pragma unroll
+    for (int tt = 0; tt < NTAP; ++tt) {
+      const int kh = (T0 + tt) / 3, kw = (T0 + tt) % 3;
+      uint32_t bv[4];
+#pragma unroll
+      for (int j = 0; j < 8; j += 2) {
+        // stored position of stage position e under this tap: image row e / W + kh, column e % W + kw
+        const int e0 = 16 * kk + 2 * j, e1 = e0 + 2;
+        const int p0 = (e0 / W + kh) * PW + e0 % W + kw;
+        const int p1 = (e1 / W + kh) * PW + e1 % W + kw;
+        const uint32_t lo = B[p0 * 64];
+        const uint32_t hi = B[p1 * 64];
+        bv[j >> 1] = lo | (hi << 16);
+      }
+      wg_bf16x8 b;
+      __builtin_memcpy(&b, bv, 16);
+      acc[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[tt], 0, 0, 0);
+    }
+  }
+}
+
+constexpr int WG_NT = 512;       // eight waves: 2 x 2 over the 64 x 64 block, times two groups of taps
+template <int W>
+__global__ __launch_bounds__(WG_NT) void conv_wgrad_kernel(const bf16_t* __restrict__ dy, int Cout,
+                                                        const bf16_t* __restrict__ x, int Cin, int H,
+                                                        const bf16_t* __restrict__ zeros, int nstages,
+                                                        int stages_per_wg, float* __restrict__ slabs,
+                                                        int64_t slab_stride) {
+  static_assert(W == 8 || W == 16 || W == 32 || W == 64, "image width");
+  constexpr int IR = 64 / W;                               // image rows per stage
+  constexpr int PW = W + 2;                                // positions of a stored image row
+  constexpr int XR = (IR + 2) * PW;                        // stored positions of x per stage
+  constexpr int BUF = (64 + XR) * 64;                      // elements of one stage buffer
+  constexpr int NI = 8 + (IR + 2) * (W / 8);               // load instructions per stage (8 rows of 128 bytes each)
+  extern __shared__ __attribute__((aligned(1024))) bf16_t wg_lds[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = (wave >> 1) & 1, wn = wave & 1, khalf = lane >> 5, lc = lane & 31;
+  const int tgroup = wave >> 2;                            // taps 0..4 or 5..8
+  const int ctiles = Cin / 64;
+  const int o0 = (blockIdx.x / ctiles) * 64, c0 = (blockIdx.x % ctiles) * 64;
+  const int sbeg = blockIdx.y * stages_per_wg, send = min(nstages, sbeg + stages_per_wg);
+  const unsigned short* L16 = reinterpret_cast<const unsigned short*>(wg_lds);
+
+  // the empty positions before and after every stored image row, both buffers (32 dwords each)
+  for (int k = tid; k < 2 * (IR + 2) * 2 * 32; k += WG_NT) {
+    const int dword = k & 31, which = k >> 5;              // which = ((buf * (IR + 2)) + image row) * 2 + side
+    const int side = which & 1, irow = (which >> 1) % (IR + 2), buf = (which >> 1) / (IR + 2);
+    const int pos = irow * PW + (side ? PW - 1 : 0);
+    reinterpret_cast<uint32_t*>(wg_lds + buf * BUF + (64 + pos) * 64)[dword] = 0u;
+  }
+
+  auto issue = [&](int stage, int buf) {
+    for (int idx = wave; idx < NI; idx += 8) {
+      const bf16_t* src;
+      int dst;                                             // element offset in the buffer of this instruction's first row
+      if (idx < 8) {
+        src = dy + ((int64_t)stage * 64 + idx * 8 + (lane >> 3)) * Cout + o0 + (lane & 7) * 8;
+        dst = idx * 512;
+      } else {
+        const int k = idx - 8, ir = k / (W / 8) - 1, sub = k % (W / 8);
+        const int g = stage * IR + ir;                     // image row among all images' rows; the stage starts at row h0
+        const int hh = (stage * IR) % H + ir;
+        src = (hh >= 0 && hh < H) ? x + ((int64_t)g * W + sub * 8 + (lane >> 3)) * Cin + c0 + (lane & 7) * 8
+                                  : zeros + (lane & 7) * 8;
+        dst = (64 + (ir + 1) * PW + 1 + sub * 8) * 64;
+      }
+      __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)src,
+                                       (void __attribute__((address_space(3)))*)&wg_lds[buf * BUF + dst],
+                                       16, 0, 0);
+    }
+  };
+
+  wg_f32x16 acc[5];
+#pragma unroll
+  for (int t = 0; t < 5; ++t)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+
+  // this lane's element offsets inside a stage buffer (one position = 64 elements)
+  const int a_off = khalf * 64 + wm * 32 + lc;
+  const int b_off = (64 + khalf) * 64 + wn * 32 + lc;
+
+  if (sbeg < send) issue(sbeg, 0);
+  for (int st = sbeg; st < send; ++st) {
+    const int buf = (st - sbeg) & 1;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();                                       // stage st is in LDS; everybody is done with the other buffer
+    if (st + 1 < send) issue(st + 1, buf ^ 1);
+    const unsigned short* A = L16 + buf * BUF + a_off;
+    const unsigned short* B = L16 + buf * BUF + b_off;
+    if (tgroup == 0) wgrad_stage<W, 0, 5>(A, B, acc);
+    else             wgrad_stage<W, 5, 4>(A, B, acc);
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+
+  // accumulator register q of a lane: row 8 (q/4) + 4 (lane/32) + q%4 (an output channel o), column lane%32 (c)
+  float* out = slabs + (int64_t)blockIdx.y * slab_stride;
+  const int64_t Kc = 9 * (int64_t)Cin;
+#pragma unroll
+  for (int tt = 0; tt < 5; ++tt) {
+    const int t = tgroup * 5 + tt;
+    if (t < 9) {
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        const int o = o0 + wm * 32 + 8 * (q >> 2) + 4 * khalf + (q & 3);
+        out[(int64_t)o * Kc + (int64_t)t * Cin + c0 + wn * 32 + lc] = acc[tt][q];
+      }
+    }
+  }
 }
 
 }  // namespace
@@ -558,9 +747,64 @@ int launch_avgpool_bwd(const float* dpooled, int64_t ldd, int n_img, int HW, int
   return VF_OK;
 }
 
+// Weight gradient of a 3x3 convolution (stride 1, zero padding 1) from dy [rows, Cout] and the
+// layer's input x [rows, Cin] (bf16, channels last): slabs [nsplit][Cout, 9 Cin] of partial sums
+// over slices of the positions, to be added in order.  *nsplit_out = the number of slabs written.
+bool conv_wgrad_direct_fits(int Cout, int Cin, int H, int W, int64_t rows) {
+  if (Cout % 64 || Cin % 64 || rows % 64) return false;
+  if (W != 8 && W != 16 && W != 32 && W != 64) return false;
+  return H >= 64 / W && H % (64 / W) == 0;
+}
+
+template <int W>
+int launch_conv_wgrad_w(const bf16_t* dy, int Cout, const bf16_t* x, int Cin, int H, const bf16_t* zeros, int nstages,
+                        int spw, int nsplit, float* slabs, int64_t slab_stride, hipStream_t s) {
+  constexpr int bytes = 2 * (64 + (64 / W + 2) * (W + 2)) * 128;
+  static bool ready = false;
+  if (!ready) {
+    VF_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_wgrad_kernel<W>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
+    ready = true;
+  }
+  dim3 grid((Cout / 64) * (Cin / 64), nsplit);
+  conv_wgrad_kernel<W><<<grid, WG_NT, bytes, s>>>(dy, Cout, x, Cin, H, zeros, nstages, spw, slabs, slab_stride);
+  VF_LAUNCH_CHECK();
+  return VF_OK;
+}
+
+int launch_conv_wgrad_direct(const bf16_t* dy, int Cout, const bf16_t* x, int Cin, int64_t rows, int H, int W,
+                             const bf16_t* zeros, float* slabs, int64_t slab_stride, int max_split, int* nsplit_out,
+                             hipStream_t s) {
+  if (!dy || !x || !zeros || !slabs || !nsplit_out || rows <= 0 || rows > 0x7fffffff || max_split < 1) return VF_EINVAL;
+  if (!conv_wgrad_direct_fits(Cout, Cin, H, W, rows) || rows % ((int64_t)H * W) ||
+      slab_stride < (int64_t)Cout * 9 * Cin)
+    return VF_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(dy) & 15) || (reinterpret_cast<uintptr_t>(x) & 15) ||
+      (reinterpret_cast<uintptr_t>(zeros) & 15))
+    return VF_EINVAL;
+  const int nstages = (int)(rows / 64);
+  const int tiles = (Cout / 64) * (Cin / 64);
+  // about 256 workgroups, at least 4 stages each
+  const int want = std::max(1, std::min(max_split, std::min((nstages + 3) / 4, (256 + tiles - 1) / tiles)));
+  const int spw = (nstages + want - 1) / want;
+  const int nsplit = (nstages + spw - 1) / spw;
+  int rc;
+  switch (W) {
+    case 8: rc = launch_conv_wgrad_w<8>(dy, Cout, x, Cin, H, zeros, nstages, spw, nsplit, slabs, slab_stride, s); break;
+    case 16: rc = launch_conv_wgrad_w<16>(dy, Cout, x, Cin, H, zeros, nstages, spw, nsplit, slabs, slab_stride, s); break;
+    case 32: rc = launch_conv_wgrad_w<32>(dy, Cout, x, Cin, H, zeros, nstages, spw, nsplit, slabs, slab_stride, s); break;
+    default: rc = launch_conv_wgrad_w<64>(dy, Cout, x, Cin, H, zeros, nstages, spw, nsplit, slabs, slab_stride, s); break;
+  }
+  if (rc == VF_OK) *nsplit_out = nsplit;
+  return rc;
+}
+
 int launch_fold_slabs(const float* slabs, int nsplit, int64_t stride, int64_t n, GradOut out, hipStream_t s) {
   if (n <= 0 || nsplit < 1 || !slabs || !out.dst) return VF_EINVAL;
-  fold_slabs_kernel<<<(unsigned)blocks(n), NT, 0, s>>>(slabs, nsplit, stride, n, out);
+  if (nsplit >= 64 && (n & 3) == 0 && (stride & 3) == 0 && (reinterpret_cast<uintptr_t>(slabs) & 15) == 0)
+    fold_slabs_wide_kernel<<<(unsigned)((n / 4 + 31) / 32), NT, 0, s>>>(slabs, nsplit, stride, n / 4, out);
+  else
+    fold_slabs_kernel<<<(unsigned)blocks(n), NT, 0, s>>>(slabs, nsplit, stride, n, out);
   VF_LAUNCH_CHECK();
   return VF_OK;
 }

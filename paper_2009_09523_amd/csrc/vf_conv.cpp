@@ -90,7 +90,11 @@ class Conv final : public Model {
     a.request(&gB_, rows * C_);
     a.request(&partial_, (size_t)conv_chunks(rows_max_) * 2 * C_);
     a.request(&sums_, (size_t)2 * C_);
-    a.request(&slabs_, (size_t)kMaxSplit * C_ * (kp_max > 9 * C_ ? kp_max : 9 * C_));
+    // contraction slabs of a weight gradient: up to kMaxSplit from the product over the transposed
+    // patch matrix, up to kDirectSplit per 64 x 64 channel block from the direct kernel
+    const size_t per_slab = (size_t)C_ * (kp_max > 9 * C_ ? kp_max : 9 * C_);
+    const int blocks64 = std::max(1, (C_ / 64) * (C_ / 64));
+    a.request(&slabs_, per_slab * (size_t)std::max(kMaxSplit, (kDirectSplit + blocks64 - 1) / blocks64));
     a.request(&fc_wnat_, (size_t)C_ * ldz_);
     a.request(&fc_wtr_, (size_t)cfg_.classes * ldc_);
     a.request(&pooled_, (size_t)cfg_.max_node_size * ldc_);
@@ -132,6 +136,7 @@ class Conv final : public Model {
 
  private:
   static constexpr int kMaxSplit = 32;
+  static constexpr int kDirectSplit = 256;
 
   // y = patches(in) x filters^T; statistics over the node's rows; a = relu(BatchNorm(y) (+ skip))
   int conv_bn_relu(Ctx& c, ConvLayer& L, const bf16_t* in, const bf16_t* skip, int rows, const float* P,
@@ -189,11 +194,20 @@ class Conv final : public Model {
 
   // dW[o, (kh,kw,c)] = sum over the node's positions of dy[r, o] * patches[r, (kh,kw,c)]
   int conv_wgrad(Ctx& c, ConvLayer& L, int rows, float w, int node, hipStream_t st) {
+    const int64_t slab = (int64_t)L.C * L.Kc;
+    if (!explicit_ && conv_wgrad_direct_fits(L.C, L.Cin, H_, H_, rows)) {
+      // straight from dy and the stored input: no transposes, no patch matrix
+      const int blocks64 = (L.C / 64) * (L.Cin / 64);
+      int split = 0;
+      VF_KS(c, st, "gemm_wgrad", launch_conv_wgrad_direct(dy_, L.C, L.in, L.Cin, rows, H_, H_, zeros_, slabs_, slab,
+                                                          std::max(1, kDirectSplit / blocks64), &split, st));
+      VF_KS(c, st, "fold_slabs", launch_fold_slabs(slabs_, split, slab, slab, c.gout(L.w_off, w, node), st));
+      return VF_OK;
+    }
     VF_KS(c, st, "transpose", launch_transpose_bf16(L.in, L.Cin, inT_, ldr_, rows, L.Cin, st));
     VF_KS(c, st, "im2col", launch_im2col3x3_transposed(inT_, ldr_, rows, H_, H_, L.Cin, colsT_, ldr_, st));
     VF_KS(c, st, "transpose", launch_transpose_bf16(dy_, L.C, dyT_, ldr_, rows, L.C, st));
     int split = std::min(kMaxSplit, gemm_bf16_pick_split(L.C, L.Kc, rows));
-    const int64_t slab = (int64_t)L.C * L.Kc;
     Epilogue ep;
     ep.C = slabs_; ep.ldc = L.Kc;
     VF_KS(c, st, "gemm_wgrad", launch_gemm_bf16(dyT_, ldr_, colsT_, ldr_, L.C, L.Kc, rows, split, slab, ep, st));

@@ -192,6 +192,16 @@ int launch_bn2d_bwd(float* da, const bf16_t* a, const float* y, int64_t rows, in
                     int keep_dpre, bf16_t* dy, GradOut gout_g, GradOut gout_b, hipStream_t s);
 int launch_avgpool_fwd(const bf16_t* a, int n_img, int HW, int C, bf16_t* pooled, int64_t ldp, hipStream_t s);
 int launch_avgpool_bwd(const float* dpooled, int64_t ldd, int n_img, int HW, int C, float* da, hipStream_t s);
+// dW[o, (kh, kw, c)] = sum over positions of dy[r, o] * x[r + (kh-1) W + (kw-1), c] (0 outside the
+// image) straight from dy [rows, Cout] and x [rows, Cin] (bf16, channels last), as up to max_split
+// slabs [Cout, 9 Cin] (slab_stride floats apart) of partial sums over slices of the positions, to
+// be added in order; *nsplit_out slabs are written.  `zeros`: 128 bytes of 0.
+// conv_wgrad_direct_fits: Cout % 64 == 0, Cin % 64 == 0, W in {8, 16, 32, 64}, H a multiple of
+// 64 / W, rows a multiple of 64.
+bool conv_wgrad_direct_fits(int Cout, int Cin, int H, int W, int64_t rows);
+int launch_conv_wgrad_direct(const bf16_t* dy, int Cout, const bf16_t* x, int Cin, int64_t rows, int H, int W,
+                             const bf16_t* zeros, float* slabs, int64_t slab_stride, int max_split, int* nsplit_out,
+                             hipStream_t s);
 // out (+)= alpha * (slab 0 + slab 1 + ...), slabs in order
 int launch_fold_slabs(const float* slabs, int nsplit, int64_t stride, int64_t n, GradOut out, hipStream_t s);
 

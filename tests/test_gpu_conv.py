@@ -20,7 +20,8 @@ def _case(name, jitter=0.1):
 
 
 @pytest.mark.parametrize("flags", [NO_GRAPH, 0, FUSED | NO_GRAPH, FUSED])
-@pytest.mark.parametrize("name", ["conv_tiny_bf16", "conv_small_bf16", "conv_w64_bf16"])
+@pytest.mark.parametrize("name", ["conv_tiny_bf16", "conv_small_bf16", "conv_w64_bf16", "conv_w64_img8_bf16",
+                                  "conv_w64_img16_bf16"])
 def test_conv_step_matches_oracle(name, flags):
     print(f"case {name} flags={flags}", flush=True)
     wl, theta, x, y = _case(name)
@@ -59,7 +60,7 @@ def test_second_step_of_the_deeper_network_within_the_oracles_own_sensitivity():
     assert gpu["t"] == 2
 
 
-@pytest.mark.parametrize("name", ["conv_small_bf16", "conv_w64_bf16"])
+@pytest.mark.parametrize("name", ["conv_small_bf16", "conv_w64_bf16", "conv_w64_img16_bf16"])
 def test_fused_staged_graph_and_eager_agree_bitwise(name):
     wl, theta, x, y = _case(name)
     base = run_gpu(wl, theta, x, y, flags=NO_GRAPH, steps=2)

@@ -134,6 +134,9 @@ WORKLOADS: Dict[str, Workload] = {
     "conv_tiny_bf16": _conv("conv_tiny_bf16", 6, 3, 16, 1, 10, [5, 3, 8], "bf16"),
     "conv_small_bf16": _conv("conv_small_bf16", 12, 3, 24, 2, 10, [9, 16, 7], "bf16"),
     "conv_w64_bf16": _conv("conv_w64_bf16", 6, 3, 64, 1, 10, [3, 2, 4], "bf16"),
+    # image sides that are powers of two: a stage of 64 positions is a whole image (8) or a quarter of one (16)
+    "conv_w64_img8_bf16": _conv("conv_w64_img8_bf16", 8, 3, 64, 1, 10, [3, 2, 4], "bf16"),
+    "conv_w64_img16_bf16": _conv("conv_w64_img16_bf16", 16, 3, 64, 1, 10, [2, 1], "bf16"),
 }
 
 
