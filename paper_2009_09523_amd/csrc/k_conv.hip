@@ -154,6 +154,17 @@ __device__ __forceinline__ float4 lanes_sum(float4 v, float4* red, int g, int la
 // ahead of the selection, so that PB loads per operand are in flight per thread.
 constexpr int PB = 8;
 
+// The two-group update of a mean and a sum of squared deviations: group B (nb rows, mean mb,
+// deviations qb) joins group A (cnt, mean, m2).
+__device__ __forceinline__ void join_stats(float& cnt, float& mean, float& m2, float nb, float mb, float qb) {
+  if (nb <= 0.f) return;
+  const float tot = cnt + nb;
+  const float delta = mb - mean;
+  mean = fmaf(delta, nb / tot, mean);
+  m2 = m2 + qb + delta * delta * (cnt * nb / tot);
+  cnt = tot;
+}
+
 // Per chunk and column: the mean of the chunk's rows and the sum of squared deviations from it.
 // partial[(chunk*2 + 0)*C + c] = mean, partial[(chunk*2 + 1)*C + c] = M2.
 __global__ __launch_bounds__(NT) void bn2d_stats_partial_kernel(const float* __restrict__ y, int64_t rows, int C,
@@ -205,28 +216,19 @@ __global__ __launch_bounds__(NT) void bn2d_stats_partial_kernel(const float* __r
   }
 }
 
-// The two-group update of a mean and a sum of squared deviations: group B (nb rows, mean mb,
-// deviations qb) joins group A (cnt, mean, m2).
-__device__ __forceinline__ void join_stats(float& cnt, float& mean, float& m2, float nb, float mb, float qb) {
-  if (nb <= 0.f) return;
-  const float tot = cnt + nb;
-  const float delta = mb - mean;
-  mean = fmaf(delta, nb / tot, mean);
-  m2 = m2 + qb + delta * delta * (cnt * nb / tot);
-  cnt = tot;
-}
-
-// Chunks combined in a fixed order: one workgroup, thread = (column, lane); a lane joins a
-// contiguous run of chunks in chunk order, then the lanes are joined in lane order.  Mean and
+// Chunks combined in a fixed order: one workgroup of NTF threads, thread = (column, lane); a lane
+// joins a contiguous run of chunks in chunk order (eight chunks' values in flight), then the lanes
+// are joined in lane order.  Mean and
 // biased variance over all rows; rstd; moving statistics of this device blended once per pass
 // (Section 4.1).  C <= 256.
-__global__ __launch_bounds__(NT) void bn2d_stats_finish_kernel(const float* __restrict__ partial, int nchunk,
+constexpr int NTF = 1024;
+__global__ __launch_bounds__(NTF) void bn2d_stats_finish_kernel(const float* __restrict__ partial, int nchunk,
                                                                int64_t rows, int C, float eps,
                                                                float* __restrict__ mean_out, float* __restrict__ rstd_out,
                                                                float* __restrict__ run_mean, float* __restrict__ run_var,
                                                                float run_mix) {
-  __shared__ float sm[3][NT];
-  const int nl = NT / C;                       // lanes per column
+  __shared__ float sm[3][NTF];
+  const int nl = NTF / C;                      // lanes per column
   const int c = threadIdx.x % C, lane = threadIdx.x / C;
   const bool active = lane < nl;
   const int per = (nchunk + nl - 1) / nl;
@@ -234,15 +236,15 @@ __global__ __launch_bounds__(NT) void bn2d_stats_finish_kernel(const float* __re
   float mean = 0.f, m2 = 0.f, cnt = 0.f;
   if (active) {
     int k = k0;
-    for (; k + 3 < k1; k += 4) {               // four chunks' values in flight, joined in order
-      float mb[4], qb[4];
+    for (; k + 7 < k1; k += 8) {               // eight chunks' values in flight, joined in order
+      float mb[8], qb[8];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      for (int u = 0; u < 8; ++u) {
         mb[u] = partial[((int64_t)(k + u) * 2 + 0) * C + c];
         qb[u] = partial[((int64_t)(k + u) * 2 + 1) * C + c];
       }
 #pragma unroll
-      for (int u = 0; u < 4; ++u)
+      for (int u = 0; u < 8; ++u)
         join_stats(cnt, mean, m2, (float)min((int64_t)CHUNK, rows - (int64_t)(k + u) * CHUNK), mb[u], qb[u]);
     }
     for (; k < k1; ++k)
@@ -351,25 +353,25 @@ __global__ __launch_bounds__(NT) void bn2d_bwd_partial_kernel(const float* __res
 // order, the lanes are added in lane order.  The sums go to sums[0][c] (dbeta) and sums[1][c]
 // (dgamma) for the apply kernel, and, weighted, into the gradient (Section 3.2 step 3,
 // Section 5.2).  C <= 256.
-__global__ __launch_bounds__(NT) void bn2d_bwd_finish_kernel(const float* __restrict__ partial, int nchunk, int C,
+__global__ __launch_bounds__(NTF) void bn2d_bwd_finish_kernel(const float* __restrict__ partial, int nchunk, int C,
                                                              float* __restrict__ sums, GradOut gout_g, GradOut gout_b) {
-  __shared__ float sm[2][NT];
-  const int nl = NT / C;
+  __shared__ float sm[2][NTF];
+  const int nl = NTF / C;
   const int c = threadIdx.x % C, lane = threadIdx.x / C;
   const int per = (nchunk + nl - 1) / nl;
   const int k0 = lane * per, k1 = min(nchunk, k0 + per);
   float sb = 0.f, sg = 0.f;
   if (lane < nl) {
     int k = k0;
-    for (; k + 3 < k1; k += 4) {
-      float b4[4], g4[4];
+    for (; k + 7 < k1; k += 8) {
+      float b8[8], g8[8];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        b4[u] = partial[((int64_t)(k + u) * 2 + 0) * C + c];
-        g4[u] = partial[((int64_t)(k + u) * 2 + 1) * C + c];
+      for (int u = 0; u < 8; ++u) {
+        b8[u] = partial[((int64_t)(k + u) * 2 + 0) * C + c];
+        g8[u] = partial[((int64_t)(k + u) * 2 + 1) * C + c];
       }
 #pragma unroll
-      for (int u = 0; u < 4; ++u) { sb += b4[u]; sg += g4[u]; }
+      for (int u = 0; u < 8; ++u) { sb += b8[u]; sg += g8[u]; }
     }
     for (; k < k1; ++k) {
       sb += partial[((int64_t)k * 2 + 0) * C + c];
@@ -702,7 +704,7 @@ int launch_bn2d_stats(const float* y, int64_t rows, int C, float eps, float* par
   const int nchunk = conv_chunks(rows);
   bn2d_stats_partial_kernel<<<nchunk, NT, tall_lds(C), s>>>(y, rows, C, partial);
   VF_LAUNCH_CHECK();
-  bn2d_stats_finish_kernel<<<1, NT, 0, s>>>(partial, nchunk, rows, C, eps, mean, rstd, run_mean, run_var, run_mix);
+  bn2d_stats_finish_kernel<<<1, NTF, 0, s>>>(partial, nchunk, rows, C, eps, mean, rstd, run_mean, run_var, run_mix);
   VF_LAUNCH_CHECK();
   return VF_OK;
 }
@@ -723,7 +725,7 @@ int launch_bn2d_bwd(float* da, const bf16_t* a, const float* y, int64_t rows, in
   const int nchunk = conv_chunks(rows);
   bn2d_bwd_partial_kernel<<<nchunk, NT, tall_lds(C), s>>>(da, a, y, rows, C, mean, rstd, partial);
   VF_LAUNCH_CHECK();
-  bn2d_bwd_finish_kernel<<<1, NT, 0, s>>>(partial, nchunk, C, sums, gout_g, gout_b);
+  bn2d_bwd_finish_kernel<<<1, NTF, 0, s>>>(partial, nchunk, C, sums, gout_g, gout_b);
   VF_LAUNCH_CHECK();
   const int64_t n4 = rows * C / 4;
   bn2d_bwd_apply_kernel<<<(unsigned)blocks(n4), NT, 0, s>>>(da, a, y, n4, C, 1.0f / (float)rows, gamma, round_params,
