@@ -8,6 +8,7 @@
 // contraction is cut into `nsplit` slices (blockIdx.z); slice s writes its partial product
 // to slab s of the output ([nsplit][M][ldc]) and the consumer kernel adds the slabs in a
 // fixed order, so results do not depend on scheduling.
+#include <algorithm>
 #include <cstdlib>
 #include <cstring>
 
@@ -490,6 +491,118 @@ __global__ __launch_bounds__(NT) void gemm_bf16_dl_kernel(const bf16_t* __restri
   store_tiles<1, 1>(tiles, ep, cbase, blockIdx.z == 0, m0 + wm * 32, n0 + wn * 32, M, N, lane);
 }
 
+// ---- 3x3 convolution with the filters resident in LDS -------------------------------------------
+// 64 input channels (one 128-byte row per position), 64 output channels per workgroup, image width
+// W a power of two from 8 to 64.  The workgroup keeps its 64 x 576 filters in LDS (nine 64 x 64 tiles,
+// one per tap) and walks over stages of 64 consecutive positions (64 / W image rows).  A stage's
+// input is staged once: the image rows from one above to one below the stage, each with one empty
+// position before and after it; rows outside the image come from a block of zeros and the empty
+// positions are cleared once, so the nine shifted reads of a position find their value or 0 at
+// fixed offsets.  Per stage a workgroup then fetches 64 + 2 W positions instead of nine times 64
+// (and no filters): a ninth of what the patch-free product kernel pulls through the L2s.
+// Rows are stored with the same 16-byte chunk permutation as the other LDS-direct kernels
+// (by stored position for the input, by output channel for the filters).
+// Requires H % (64 / W) == 0 (a stage lies within one image) and rows % 64 == 0.
+template <int W>
+__global__ __launch_bounds__(NT) void conv3x3_lds_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ Wk,
+                                                         int64_t ldb, int H, const bf16_t* __restrict__ zeros,
+                                                         int nstages, int stages_per_wg, int N, Epilogue ep) {
+  static_assert(W == 8 || W == 16 || W == 32 || W == 64, "image width");
+  constexpr int IR = 64 / W;                     // image rows per stage
+  constexpr int PW = W + 2;                      // stored positions per image row
+  constexpr int XR = (IR + 2) * PW;              // stored positions per stage
+  constexpr int XB = XR * 64;                    // elements of one input buffer
+  constexpr int FE = 9 * 64 * 64;                // elements of the filters
+  constexpr int NI = (IR + 2) * (W / 8);         // load instructions per stage (8 positions each)
+  extern __shared__ __attribute__((aligned(1024))) bf16_t lds_dyn[];
+  bf16_t* F = lds_dyn;
+  bf16_t* X = lds_dyn + FE;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1, hi = lane >> 5, m = lane & 31;
+  const int n0 = blockIdx.x * 64;
+  const int sbeg = blockIdx.y * stages_per_wg, send = min(nstages, sbeg + stages_per_wg);
+
+  // filters: tile t = tap, 64 rows (output channels) of 64 channels, 8 rows per instruction
+  for (int i = wave; i < 72; i += 4) {
+    const int t = i >> 3, row = (i & 7) * 8 + (lane >> 3);
+    const int chunk = (lane & 7) ^ dl_swizzle(row);
+    const bf16_t* src = Wk + (int64_t)min(n0 + row, N - 1) * ldb + t * 64 + chunk * 8;
+    __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)src,
+                                     (void __attribute__((address_space(3)))*)&F[i * 512], 16, 0, 0);
+  }
+  // the empty positions before and after every stored image row, both buffers (32 dwords each)
+  for (int k = tid; k < 2 * (IR + 2) * 2 * 32; k += NT) {
+    const int dword = k & 31, which = k >> 5;
+    const int side = which & 1, irow = (which >> 1) % (IR + 2), buf = (which >> 1) / (IR + 2);
+    const int pos = irow * PW + (side ? PW - 1 : 0);
+    reinterpret_cast<uint32_t*>(X + buf * XB + pos * 64)[dword] = 0u;
+  }
+
+  auto issue = [&](int stage, int buf) {
+    for (int idx = wave; idx < NI; idx += 4) {
+      const int ir = idx / (W / 8) - 1, sub = idx % (W / 8);
+      const int p = (ir + 1) * PW + 1 + sub * 8 + (lane >> 3);      // stored position of this lane's row
+      const int chunk = (lane & 7) ^ dl_swizzle(p);
+      const int g = stage * IR + ir;                                // image row among all images' rows
+      const int hh = (stage * IR) % H + ir;
+      const bf16_t* src = (hh >= 0 && hh < H) ? x + ((int64_t)g * W + sub * 8 + (lane >> 3)) * 64 + chunk * 8
+                                              : zeros + chunk * 8;
+      __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)src,
+                                       (void __attribute__((address_space(3)))*)&X[buf * XB + ((ir + 1) * PW + 1 + sub * 8) * 64],
+                                       16, 0, 0);
+    }
+  };
+
+  // this lane's operand rows: stage position e under tap t sits at stored position
+  // (e / W + kh) * PW + e % W + kw; its filter row is output channel wn * 32 + m of tile t
+  const int e = wm * 32 + m;
+  int pa[9], fa[9];
+#pragma unroll
+  for (int t = 0; t < 9; ++t) {
+    const int p = (e / W + t / 3) * PW + e % W + t % 3;
+    pa[t] = p * 64;
+    fa[t] = dl_swizzle(p);
+  }
+  const int brow = (wn * 32 + m) * 64, fb = dl_swizzle(wn * 32 + m);
+
+  if (sbeg < send) issue(sbeg, 0);
+  for (int st = sbeg; st < send; ++st) {
+    const int buf = (st - sbeg) & 1;
+    wait_loads_but<0>();
+    __syncthreads();                               // stage st (and the filters) are in LDS; everybody is done with the other buffer
+    if (st + 1 < send) issue(st + 1, buf ^ 1);
+    const bf16_t* xs = X + buf * XB;
+    f32x16 acc0, acc1;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { acc0[r] = 0.f; acc1[r] = 0.f; }
+    // 36 MFMAs (9 taps x 4 contraction steps); the operand reads of step i + AHEAD are issued
+    // before the MFMA of step i (one wave per SIMD: nobody else covers the LDS latency)
+    constexpr int AHEAD = 3, SLOTS = AHEAD + 1;
+    bf16x8 fa_[SLOTS], fb_[SLOTS];
+    auto read_step = [&](int i, int slot) {
+      const int t = i >> 2, ci = 2 * (i & 3) + hi;
+      fa_[slot] = *reinterpret_cast<const bf16x8*>(&xs[pa[t] + ((ci ^ fa[t]) * 8)]);
+      fb_[slot] = *reinterpret_cast<const bf16x8*>(&F[t * 4096 + brow + ((ci ^ fb) * 8)]);
+    };
+#pragma unroll
+    for (int i = 0; i < AHEAD; ++i) read_step(i, i);
+#pragma unroll
+    for (int i = 0; i < 36; ++i) {
+      if (i + AHEAD < 36) read_step(i + AHEAD, (i + AHEAD) % SLOTS);
+      __builtin_amdgcn_sched_barrier(0);
+      if (i & 1) acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa_[i % SLOTS], fb_[i % SLOTS], acc1, 0, 0, 0);
+      else       acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa_[i % SLOTS], fb_[i % SLOTS], acc0, 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    f32x16 tiles[1][1];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) tiles[0][0][r] = acc0[r] + acc1[r];
+    store_tiles<1, 1>(tiles, ep, static_cast<char*>(ep.C), true, st * 64 + wm * 32, n0 + wn * 32, nstages * 64, N, lane);
+  }
+  wait_loads_but<0>();
+}
+
 // Short contraction (K <= 2*BK = 128: the weight gradient of a node of up to 128 rows).  The
 // cost of such a product is one trip to memory for the operands and the write (or
 // read-modify-write) of the fp32 output, so everything is issued at once: both stages of
@@ -866,6 +979,28 @@ int launch_conv3x3_bf16(const bf16_t* x, int64_t rows, int H, int W, int Cin, co
       (reinterpret_cast<uintptr_t>(zeros) & 15))
     return VF_EINVAL;
   const int K = 9 * Cin;
+  // filters resident in LDS, the input staged once per 64 positions
+  static const bool lds_path = !(std::getenv("VF_CONV_LDS") && std::getenv("VF_CONV_LDS")[0] == '0');
+  if (lds_path && Cin == 64 && (W == 8 || W == 16 || W == 32 || W == 64) && H % (64 / W) == 0 && rows % 64 == 0) {
+    const int nstages = (int)(rows / 64), otiles = (N + 63) / 64;
+    const int spw = std::max(1, (int)(((int64_t)nstages * otiles + 255) / 256));
+    dim3 grid(otiles, (nstages + spw - 1) / spw);
+#define VF_CONV_LDS(WW)                                                                                   \
+  case WW: {                                                                                              \
+    constexpr int bytes = (9 * 64 * 64 + 2 * (64 / WW + 2) * (WW + 2) * 64) * 2;                          \
+    static bool ready = false;                                                                            \
+    if (!ready) {                                                                                         \
+      VF_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&conv3x3_lds_kernel<WW>),                  \
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, bytes));                     \
+      ready = true;                                                                                       \
+    }                                                                                                     \
+    conv3x3_lds_kernel<WW><<<grid, NT, bytes, s>>>(x, Wk, ldb, H, zeros, nstages, spw, N, ep);            \
+  } break;
+    switch (W) { VF_CONV_LDS(8) VF_CONV_LDS(16) VF_CONV_LDS(32) default: VF_CONV_LDS(64) }
+#undef VF_CONV_LDS
+    VF_LAUNCH_CHECK();
+    return VF_OK;
+  }
   dim3 grid((N + 63) / 64, (unsigned)((rows + 63) / 64), 1);
   ConvOperand cv{H, W, Cin, zeros};
   gemm_bf16_dl_kernel<4, true><<<grid, NT, 0, s>>>(x, Cin, Wk, ldb, (int)rows, N, K, K, 0, ep, cv);
