@@ -223,7 +223,7 @@ __global__ __launch_bounds__(NT) void bn2d_stats_partial_kernel(const float* __r
 // (Section 4.1).  C <= 256.
 constexpr int NTF = 1024;
 __global__ __launch_bounds__(NTF) void bn2d_stats_finish_kernel(const float* __restrict__ partial, int nchunk,
-                                                               int64_t rows, int C, float eps,
+                                                               int rpc, int64_t rows, int C, float eps,
                                                                float* __restrict__ mean_out, float* __restrict__ rstd_out,
                                                                float* __restrict__ run_mean, float* __restrict__ run_var,
                                                                float run_mix) {
@@ -245,10 +245,10 @@ __global__ __launch_bounds__(NTF) void bn2d_stats_finish_kernel(const float* __r
       }
 #pragma unroll
       for (int u = 0; u < 8; ++u)
-        join_stats(cnt, mean, m2, (float)min((int64_t)CHUNK, rows - (int64_t)(k + u) * CHUNK), mb[u], qb[u]);
+        join_stats(cnt, mean, m2, (float)min((int64_t)rpc, rows - (int64_t)(k + u) * rpc), mb[u], qb[u]);
     }
     for (; k < k1; ++k)
-      join_stats(cnt, mean, m2, (float)min((int64_t)CHUNK, rows - (int64_t)k * CHUNK),
+      join_stats(cnt, mean, m2, (float)min((int64_t)rpc, rows - (int64_t)k * rpc),
                  partial[((int64_t)k * 2 + 0) * C + c], partial[((int64_t)k * 2 + 1) * C + c]);
   }
   sm[0][threadIdx.x] = cnt; sm[1][threadIdx.x] = mean; sm[2][threadIdx.x] = m2;
@@ -704,7 +704,18 @@ int launch_bn2d_stats(const float* y, int64_t rows, int C, float eps, float* par
   const int nchunk = conv_chunks(rows);
   bn2d_stats_partial_kernel<<<nchunk, NT, tall_lds(C), s>>>(y, rows, C, partial);
   VF_LAUNCH_CHECK();
-  bn2d_stats_finish_kernel<<<1, NTF, 0, s>>>(partial, nchunk, rows, C, eps, mean, rstd, run_mean, run_var, run_mix);
+  bn2d_stats_finish_kernel<<<1, NTF, 0, s>>>(partial, nchunk, CHUNK, rows, C, eps, mean, rstd, run_mean, run_var, run_mix);
+  VF_LAUNCH_CHECK();
+  return VF_OK;
+}
+
+int launch_bn2d_stats_finish(const float* partial, int nchunk, int rows_per_chunk, int64_t rows, int C, float eps,
+                             float* mean, float* rstd, float* run_mean, float* run_var, float run_mix, hipStream_t s) {
+  if (rows <= 0 || !tall_ok(C) || !partial || nchunk < 1 || rows_per_chunk < 1) return VF_EINVAL;
+  if ((int64_t)nchunk * rows_per_chunk < rows || (int64_t)(nchunk - 1) * rows_per_chunk >= rows) return VF_EINVAL;
+  if ((run_mean == nullptr) != (run_var == nullptr)) return VF_EINVAL;
+  bn2d_stats_finish_kernel<<<1, NTF, 0, s>>>(partial, nchunk, rows_per_chunk, rows, C, eps, mean, rstd, run_mean, run_var,
+                                             run_mix);
   VF_LAUNCH_CHECK();
   return VF_OK;
 }

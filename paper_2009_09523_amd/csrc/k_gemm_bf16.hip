@@ -503,10 +503,16 @@ __global__ __launch_bounds__(NT) void gemm_bf16_dl_kernel(const bf16_t* __restri
 // Rows are stored with the same 16-byte chunk permutation as the other LDS-direct kernels
 // (by stored position for the input, by output channel for the filters).
 // Requires H % (64 / W) == 0 (a stage lies within one image) and rows % 64 == 0.
+// With `stats` (plain epilogue only: what is stored is the product itself) the workgroup also
+// leaves, per output channel, the mean of the values it stored and their sum of squared
+// deviations from it -- stats[(blockIdx.y * 2 + 0) * N + n] and [.. + 1 ..] -- for a per-channel
+// normalisation over all positions: every lane keeps shifted sums over its own values (shift =
+// its first value), and the four lanes that share a channel are joined in a fixed order.
 template <int W>
 __global__ __launch_bounds__(NT) void conv3x3_lds_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ Wk,
                                                          int64_t ldb, int H, const bf16_t* __restrict__ zeros,
-                                                         int nstages, int stages_per_wg, int N, Epilogue ep) {
+                                                         int nstages, int stages_per_wg, int N, Epilogue ep,
+                                                         float* __restrict__ stats) {
   static_assert(W == 8 || W == 16 || W == 32 || W == 64, "image width");
   constexpr int IR = 64 / W;                     // image rows per stage
   constexpr int PW = W + 2;                      // stored positions per image row
@@ -566,6 +572,7 @@ __global__ __launch_bounds__(NT) void conv3x3_lds_kernel(const bf16_t* __restric
   }
   const int brow = (wn * 32 + m) * 64, fb = dl_swizzle(wn * 32 + m);
 
+  float shift = 0.f, sd = 0.f, sq = 0.f;           // stats: this lane's values v as sums of (v - shift) and (v - shift)^2
   if (sbeg < send) issue(sbeg, 0);
   for (int st = sbeg; st < send; ++st) {
     const int buf = (st - sbeg) & 1;
@@ -599,8 +606,38 @@ __global__ __launch_bounds__(NT) void conv3x3_lds_kernel(const bf16_t* __restric
 #pragma unroll
     for (int r = 0; r < 16; ++r) tiles[0][0][r] = acc0[r] + acc1[r];
     store_tiles<1, 1>(tiles, ep, static_cast<char*>(ep.C), true, st * 64 + wm * 32, n0 + wn * 32, nstages * 64, N, lane);
+    if (stats) {
+      if (st == sbeg) shift = tiles[0][0][0];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float d = tiles[0][0][r] - shift;
+        sd += d;
+        sq = fmaf(d, d, sq);
+      }
+    }
   }
   wait_loads_but<0>();
+  if (stats && sbeg < send) {
+    __shared__ float st_m[4][64], st_q[4][64];
+    const float cnt = 16.f * (float)(send - sbeg);           // values per lane
+    const float dm = sd / cnt;
+    st_m[wm * 2 + hi][wn * 32 + m] = shift + dm;
+    st_q[wm * 2 + hi][wn * 32 + m] = sq - sd * dm;
+    __syncthreads();
+    if (tid < 64 && n0 + tid < N) {
+      // the two-group update of a mean and a sum of squared deviations, groups of equal size joined in order
+      float mean = st_m[0][tid], m2 = st_q[0][tid], have = cnt;
+#pragma unroll
+      for (int g = 1; g < 4; ++g) {
+        const float tot = have + cnt, delta = st_m[g][tid] - mean;
+        mean = fmaf(delta, cnt / tot, mean);
+        m2 = m2 + st_q[g][tid] + delta * delta * (have * cnt / tot);
+        have = tot;
+      }
+      stats[((int64_t)blockIdx.y * 2 + 0) * N + n0 + tid] = mean;
+      stats[((int64_t)blockIdx.y * 2 + 1) * N + n0 + tid] = m2;
+    }
+  }
 }
 
 // Short contraction (K <= 2*BK = 128: the weight gradient of a node of up to 128 rows).  The
@@ -972,7 +1009,9 @@ int launch_gemm_bf16(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb,
 // positions, channels last, Cin a multiple of 64) times Wk[n, (kh, kw, c)] (row pitch ldb):
 // a 3x3 convolution, stride 1, zero padding 1, without a patch matrix.  `zeros`: 128 bytes of 0.
 int launch_conv3x3_bf16(const bf16_t* x, int64_t rows, int H, int W, int Cin, const bf16_t* Wk, int64_t ldb, int N,
-                        const Epilogue& ep, const bf16_t* zeros, hipStream_t s) {
+                        const Epilogue& ep, const bf16_t* zeros, hipStream_t s, float* stats, int* stats_chunks,
+                        int* stats_rows) {
+  if (stats_chunks) *stats_chunks = 0;
   if (!x || !Wk || !ep.C || !zeros || rows <= 0 || rows > 0x7fffffff || H <= 0 || W <= 0 || N <= 0) return VF_EINVAL;
   if ((Cin % BK) || rows % ((int64_t)H * W) || (ldb & 7) || ldb < 9 * Cin) return VF_EINVAL;
   if ((reinterpret_cast<uintptr_t>(x) & 15) || (reinterpret_cast<uintptr_t>(Wk) & 15) ||
@@ -985,6 +1024,11 @@ int launch_conv3x3_bf16(const bf16_t* x, int64_t rows, int H, int W, int Cin, co
     const int nstages = (int)(rows / 64), otiles = (N + 63) / 64;
     const int spw = std::max(1, (int)(((int64_t)nstages * otiles + 255) / 256));
     dim3 grid(otiles, (nstages + spw - 1) / spw);
+    // per-channel statistics of what is stored, if asked for and if that is the product itself
+    float* st = (stats && stats_chunks && stats_rows && ep.alpha == 1.f && !ep.R && !ep.bias && !ep.c_is_bf16 &&
+                 (int)grid.y <= kConvStatsChunks)
+                    ? stats : nullptr;
+    if (st) { *stats_chunks = (int)grid.y; *stats_rows = spw * 64; }
 #define VF_CONV_LDS(WW)                                                                                   \
   case WW: {                                                                                              \
     constexpr int bytes = (9 * 64 * 64 + 2 * (64 / WW + 2) * (WW + 2) * 64) * 2;                          \
@@ -994,7 +1038,7 @@ int launch_conv3x3_bf16(const bf16_t* x, int64_t rows, int H, int W, int Cin, co
                                  hipFuncAttributeMaxDynamicSharedMemorySize, bytes));                     \
       ready = true;                                                                                       \
     }                                                                                                     \
-    conv3x3_lds_kernel<WW><<<grid, NT, bytes, s>>>(x, Wk, ldb, H, zeros, nstages, spw, N, ep);            \
+    conv3x3_lds_kernel<WW><<<grid, NT, bytes, s>>>(x, Wk, ldb, H, zeros, nstages, spw, N, ep, st);            \
   } break;
     switch (W) { VF_CONV_LDS(8) VF_CONV_LDS(16) VF_CONV_LDS(32) default: VF_CONV_LDS(64) }
 #undef VF_CONV_LDS

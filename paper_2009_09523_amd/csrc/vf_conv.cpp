@@ -88,7 +88,7 @@ class Conv final : public Model {
     a.request(&dy_, rows * C_);
     a.request(&gA_, rows * C_);
     a.request(&gB_, rows * C_);
-    a.request(&partial_, (size_t)conv_chunks(rows_max_) * 2 * C_);
+    a.request(&partial_, (size_t)std::max(conv_chunks(rows_max_), kConvStatsChunks) * 2 * C_);
     a.request(&sums_, (size_t)2 * C_);
     // contraction slabs of a weight gradient: up to kMaxSplit from the product over the transposed
     // patch matrix, up to kDirectSplit per 64 x 64 channel block from the direct kernel
@@ -144,15 +144,21 @@ class Conv final : public Model {
     L.in = in;
     Epilogue ep;
     ep.C = L.y; ep.ldc = L.C;
+    int chunks = 0, chunk_rows = 0;     // statistics partials that the convolution kernel leaves, if it does
     if (L.Cin % 64 == 0 && !explicit_) {
-      VF_KS(c, st, "gemm_fwd", launch_conv3x3_bf16(in, rows, H_, H_, L.Cin, L.wnat, L.Kp, L.C, ep, zeros_, st));
+      VF_KS(c, st, "gemm_fwd", launch_conv3x3_bf16(in, rows, H_, H_, L.Cin, L.wnat, L.Kp, L.C, ep, zeros_, st, partial_,
+                                                   &chunks, &chunk_rows));
     } else {
       VF_KS(c, st, "im2col", launch_im2col3x3(in, rows, H_, H_, L.Cin, cols_, L.Kp, st));
       VF_KS(c, st, "gemm_fwd", launch_gemm_bf16(cols_, L.Kp, L.wnat, L.Kp, rows, L.C, L.Kp, 1, 0, ep, st));
     }
     const int64_t S = (int64_t)layers_.size() * C_;
-    VF_KS(c, st, "bn_stats", launch_bn2d_stats(L.y, rows, L.C, cfg_.bn_eps, partial_, L.mean, L.rstd,
-                                               state_ + L.s_off, state_ + S + L.s_off, cfg_.bn_momentum, st));
+    if (chunks > 0)
+      VF_KS(c, st, "bn_stats", launch_bn2d_stats_finish(partial_, chunks, chunk_rows, rows, L.C, cfg_.bn_eps, L.mean, L.rstd,
+                                                        state_ + L.s_off, state_ + S + L.s_off, cfg_.bn_momentum, st));
+    else
+      VF_KS(c, st, "bn_stats", launch_bn2d_stats(L.y, rows, L.C, cfg_.bn_eps, partial_, L.mean, L.rstd,
+                                                 state_ + L.s_off, state_ + S + L.s_off, cfg_.bn_momentum, st));
     VF_KS(c, st, "bn_apply", launch_bn2d_apply_fwd(L.y, rows, L.C, P + L.g_off, P + L.be_off, 1, L.mean, L.rstd,
                                                    skip, L.a, st));
     return VF_OK;

@@ -108,9 +108,14 @@ int launch_gemm_bf16_fold(const FoldArgs& fa, int64_t ld, int M, int N, float* C
 // 3x3 convolution (stride 1, zero padding 1) of a channels-last bf16 image stack x [rows, Cin],
 // rows = images*H*W, Cin % 64 == 0, with filters Wk [N, 9*Cin] (row pitch ldb), as a product
 // whose first operand is read straight from x; epilogue as launch_gemm_bf16.  zeros: 128 bytes
-// of device memory holding 0.
+// of device memory holding 0.  With `stats` (room for kConvStatsChunks * 2 * N floats) the kernel
+// that takes the shape may also leave per-chunk, per-channel (mean, sum of squared deviations) of
+// what it stored, chunk k covering rows [k * *stats_rows, (k + 1) * *stats_rows): *stats_chunks
+// chunks (0: none were written), in the layout launch_bn2d_stats_finish reads.
+constexpr int kConvStatsChunks = 256;
 int launch_conv3x3_bf16(const bf16_t* x, int64_t rows, int H, int W, int Cin, const bf16_t* Wk, int64_t ldb, int N,
-                        const Epilogue& ep, const bf16_t* zeros, hipStream_t s);
+                        const Epilogue& ep, const bf16_t* zeros, hipStream_t s, float* stats = nullptr,
+                        int* stats_chunks = nullptr, int* stats_rows = nullptr);
 
 // The small per-node launches of a fold window, batched: `count` nodes, node j with rows[j] rows.
 struct NodeList {
@@ -182,6 +187,10 @@ int launch_conv_weight_copies(const float* Wf, int Cout, int Cin, bf16_t* nat, i
 // per-column mean and 1/sqrt(biased variance + eps) of y [rows, C]; moving statistics blended
 int launch_bn2d_stats(const float* y, int64_t rows, int C, float eps, float* partial, float* mean, float* rstd,
                       float* run_mean, float* run_var, float run_mix, hipStream_t s);
+// the second half of the above alone: per-chunk (mean, sum of squared deviations) already in
+// `partial` ([chunk][2][C]), chunk k covering rows [k * rows_per_chunk, (k + 1) * rows_per_chunk)
+int launch_bn2d_stats_finish(const float* partial, int nchunk, int rows_per_chunk, int64_t rows, int C, float eps,
+                             float* mean, float* rstd, float* run_mean, float* run_var, float run_mix, hipStream_t s);
 // a = relu(gamma * (y - mean) * rstd + beta (+ skip)) as bf16
 int launch_bn2d_apply_fwd(const float* y, int64_t rows, int C, const float* gamma, const float* beta, int round_params,
                           const float* mean, const float* rstd, const bf16_t* skip, bf16_t* a, hipStream_t s);
