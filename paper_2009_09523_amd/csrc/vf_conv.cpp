@@ -4,14 +4,17 @@
 //
 // A convolution is a product over patch rows (per output position the 3x3 neighbourhood of the
 // bf16, channels-last input: 9*Cin values) with the filters.  When the input channels are a
-// multiple of 64 the product kernel reads the patches straight from the activation (no patch
-// matrix); otherwise (the first layer) im2col writes them.  The input gradient is the same
-// convolution of the output gradient with the filters turned by 180 degrees and the channel roles
-// exchanged (a second bf16 copy of the filters, made once per step).  The weight gradient is the
-// product of the transposed output gradient with the transposed patch matrix (written by im2col
-// in the backward pass, from the stored input), its long contraction (all positions of the node)
-// cut into slabs that are added in order.  The transposed patch matrix is written directly, row
-// by row, from the transposed input.
+// multiple of 64 the kernels read the patches straight from the activation (no patch matrix) --
+// with 64 channels and an image side of 8 to 64, a kernel that keeps the filters in LDS and
+// stages the input once per 64 positions; otherwise (the first layer) im2col writes them.  The
+// input gradient is the same convolution of the output gradient with the filters turned by 180
+// degrees and the channel roles exchanged (a second bf16 copy of the filters, made once per
+// step).  The weight gradient contracts over all positions of the node, cut into slabs that are
+// added in order: channel counts that are multiples of 64 (and image sides of 8 to 64) take a
+// kernel that reads the output gradient and the stored input as they are; the others the product
+// of the transposed output gradient with the transposed patch matrix (written row by row from
+// the transposed input).  Where the convolution kernel supports it, it also leaves the
+// BatchNorm statistics partials of what it stored.
 #include <algorithm>
 #include <cstdlib>
 
