@@ -31,6 +31,14 @@ def test_conv_step_matches_oracle(name, flags):
     check_update_from_own_gradient(wl, gpu, theta)
 
 
+def test_image_side_64_one_image_row_per_stage():
+    """The widest image side the LDS-staged convolution kernels take: a stage of 64 positions is one image row."""
+    wl, theta, x, y = _case("conv_w64_img64_bf16")
+    gpu = run_gpu(wl, theta, x, y, flags=FUSED | NO_GRAPH)
+    ref = oracle_steps(wl, theta, x, y)
+    check_against_oracle(wl, gpu, ref)
+
+
 def test_two_steps_carry_momentum():
     wl, theta, x, y = _case("conv_tiny_bf16")
     gpu = run_gpu(wl, theta, x, y, flags=FUSED, steps=2)

@@ -137,6 +137,7 @@ WORKLOADS: Dict[str, Workload] = {
     # image sides that are powers of two: a stage of 64 positions is a whole image (8) or a quarter of one (16)
     "conv_w64_img8_bf16": _conv("conv_w64_img8_bf16", 8, 3, 64, 1, 10, [3, 2, 4], "bf16"),
     "conv_w64_img16_bf16": _conv("conv_w64_img16_bf16", 16, 3, 64, 1, 10, [2, 1], "bf16"),
+    "conv_w64_img64_bf16": _conv("conv_w64_img64_bf16", 64, 3, 64, 1, 10, [1, 2], "bf16"),
 }
 
 
