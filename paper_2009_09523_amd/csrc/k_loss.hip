@@ -44,7 +44,7 @@ __global__ __launch_bounds__(256) void softmax_xent_kernel(const float* zp, int 
                                                            const int32_t* __restrict__ labels, int R,
                                                            int C, float* __restrict__ rowloss,
                                                            T* __restrict__ dz, int64_t lddz,
-                                                           bf16_t* __restrict__ dzT, int64_t ldt) {
+                                                           bf16_t* __restrict__ dzT, int64_t ldt, float tscale) {
   __shared__ float red[4];
   __shared__ float zlabel;
   const int r = blockIdx.x;
@@ -124,7 +124,7 @@ __global__ __launch_bounds__(256) void softmax_xent_kernel(const float* zp, int 
       if (c < C) {
         float d = (v[k] * inv - (c == label ? 1.f : 0.f)) * invR;
         store_f(&dr[c], d);
-        if (dzT) dzT[(int64_t)c * ldt + r] = f32_to_bf16(d);
+        if (dzT) dzT[(int64_t)c * ldt + r] = f32_to_bf16(d * tscale);
       }
     }
   } else {
@@ -138,13 +138,13 @@ __global__ __launch_bounds__(256) void softmax_xent_kernel(const float* zp, int 
         const int cc = c + 256 * k;
         const float d = (expf(t[k] - mx) * inv - (cc == label ? 1.f : 0.f)) * invR;
         store_f(&dr[cc], d);
-        if (dzT) dzT[(int64_t)cc * ldt + r] = f32_to_bf16(d);
+        if (dzT) dzT[(int64_t)cc * ldt + r] = f32_to_bf16(d * tscale);
       }
     }
     for (; c < C; c += 256) {
       float d = (expf(zr[c] - mx) * inv - (c == label ? 1.f : 0.f)) * invR;
       store_f(&dr[c], d);
-      if (dzT) dzT[(int64_t)c * ldt + r] = f32_to_bf16(d);
+      if (dzT) dzT[(int64_t)c * ldt + r] = f32_to_bf16(d * tscale);
     }
   }
   if (threadIdx.x == 0) rowloss[r] = logf(sum) + mx - zlabel;   // zlabel: visible after the reductions' barriers
@@ -201,14 +201,14 @@ int launch_loss_reduce_nodes(const float* rowloss, const LossNodes& ln, float* n
 int launch_softmax_xent(const float* zp, int nsplit, int64_t slab, int64_t ldzp, float* z, int64_t ldz,
                         const int32_t* labels, int R, int C, float* rowloss, void* dz, int64_t lddz,
                         int dz_is_bf16, bf16_t* dzT, int64_t ldt, float w, int node, float* node_loss,
-                        float* total, hipStream_t s) {
+                        float* total, hipStream_t s, float tscale) {
   if (R <= 0 || C <= 0 || nsplit < 1) return VF_EINVAL;
   if (dzT && !dz_is_bf16) return VF_EINVAL;
   if (node_loss && !total) return VF_EINVAL;
   const bool small = C <= 256 * CPT;
 #define VF_SX3(TT, SM, NS)                                                                         \
   softmax_xent_kernel<TT, SM, NS><<<R, 256, 0, s>>>(zp, nsplit, slab, ldzp, z, ldz, labels, R, C,  \
-                                                    rowloss, static_cast<TT*>(dz), lddz, dzT, ldt)
+                                                    rowloss, static_cast<TT*>(dz), lddz, dzT, ldt, tscale)
 #define VF_SX2(TT, SM)                                                                             \
   switch (nsplit) {                                                                                \
     case 1: VF_SX3(TT, SM, 1); break;                                                              \

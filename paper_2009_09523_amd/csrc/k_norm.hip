@@ -176,7 +176,7 @@ __global__ __launch_bounds__(256) void bn_relu_bwd_kernel(float* __restrict__ da
                                                           const float* __restrict__ rstd_in,
                                                           T* __restrict__ dz, int64_t lddz,
                                                           bf16_t* __restrict__ dzT, int64_t ldt,
-                                                          GradOut gout_g, GradOut gout_b) {
+                                                          GradOut gout_g, GradOut gout_b, float tscale) {
   __shared__ float red[RL][CB + 1];
   __shared__ __attribute__((aligned(16))) bf16_t tile[CB][RCH + 8];
   const int tx = threadIdx.x % CB, ty = threadIdx.x / CB;
@@ -252,7 +252,7 @@ __global__ __launch_bounds__(256) void bn_relu_bwd_kernel(float* __restrict__ da
         v = bn ? kk * (dout - sb * invR - xhat * sg * invR) : dout;
         store_f(&dz[(int64_t)r * lddz + c], v);
       }
-      if (dzT) tile[tx][rl] = f32_to_bf16(v);
+      if (dzT) tile[tx][rl] = f32_to_bf16(v * tscale);
     }
     if (dzT) {
       __syncthreads();
@@ -344,14 +344,14 @@ int launch_bn_relu_bwd(float* dap, int nsplit, int64_t slab, int64_t ldda, const
                        int64_t ldz, int R, int C, const float* gamma, const float* beta,
                        int round_params, const float* mean, const float* rstd, void* dz, int64_t lddz,
                        int dz_is_bf16, bf16_t* dzT, int64_t ldt, GradOut gout_g, GradOut gout_b,
-                       hipStream_t s) {
+                       hipStream_t s, float tscale) {
   if (R <= 0 || C <= 0 || nsplit < 1) return VF_EINVAL;
   if (dzT && ((ldt & 7) || !dz_is_bf16)) return VF_EINVAL;
   const int grid = (C + CB - 1) / CB;
   const bool small = R <= RCH;
 #define VF_BWD2(TT, NS, SM)                                                                        \
   bn_relu_bwd_kernel<TT, NS, SM><<<grid, 256, 0, s>>>(dap, slab, ldda, z, ldz, R, C, gamma, beta,  \
-      round_params, mean, rstd, static_cast<TT*>(dz), lddz, dzT, ldt, gout_g, gout_b)
+      round_params, mean, rstd, static_cast<TT*>(dz), lddz, dzT, ldt, gout_g, gout_b, tscale)
 #define VF_BWD(NS)                                                                                 \
   case NS:                                                                                         \
     if (dz_is_bf16) { if (small) VF_BWD2(bf16_t, NS, true); else VF_BWD2(bf16_t, NS, false); }     \

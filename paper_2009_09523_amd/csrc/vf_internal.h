@@ -160,11 +160,12 @@ int launch_bn_relu_fwd(const float* zp, int nsplit, int64_t slab, int64_t ldzp, 
 // overwritten when nsplit > 1).  Writes dz (T), dzT (optional, bf16, [C, ldt]) and, with
 // BatchNorm, dgamma/dbeta through GradOut; without BatchNorm (gamma == nullptr) the bias
 // gradient (column sums of dz) through gout_b.  nsplit must be a power of two <= 32.
+// tscale: the transposed copy holds tscale * dz (rounded once, from the fp32 value).
 int launch_bn_relu_bwd(float* dap, int nsplit, int64_t slab, int64_t ldda, const float* z,
                        int64_t ldz, int R, int C, const float* gamma, const float* beta,
                        int round_params, const float* mean, const float* rstd, void* dz, int64_t lddz,
                        int dz_is_bf16, bf16_t* dzT, int64_t ldt, GradOut gout_g, GradOut gout_b,
-                       hipStream_t s);
+                       hipStream_t s, float tscale = 1.f);
 // out[r] = sum_c x[r*ld + c] through GradOut (bias gradient from a transposed bf16 gradient)
 int launch_rowsum_bf16(const bf16_t* x, int64_t ld, int R, int C, GradOut out, hipStream_t s);
 // out[c] = sum_r x[r*ld + c] through GradOut (x is T)
@@ -218,12 +219,13 @@ int launch_fold_slabs(const float* slabs, int nsplit, int64_t stride, int64_t n,
 // Softmax cross-entropy over R rows of fp32 logits with C classes.  zp: nsplit partial slabs
 // of the logits (summed into z, which may be slab 0 itself):
 //   rowloss[r] = logsumexp(z_r) - z_r[label_r];  dz[r,c] = (softmax(z_r)[c] - [c==label_r]) / R
-// dzT (optional, bf16 only): the same gradient transposed, [C, ldt].
+// dzT (optional, bf16 only): tscale times the same gradient (rounded once, from the fp32 value),
+// transposed, [C, ldt].
 // With node_loss != null the node's loss bookkeeping (launch_loss_reduce) follows.
 int launch_softmax_xent(const float* zp, int nsplit, int64_t slab, int64_t ldzp, float* z, int64_t ldz,
                         const int32_t* labels, int R, int C, float* rowloss, void* dz, int64_t lddz,
                         int dz_is_bf16, bf16_t* dzT, int64_t ldt, float w, int node, float* node_loss,
-                        float* total, hipStream_t s);
+                        float* total, hipStream_t s, float tscale = 1.f);
 // node_loss[i] = (1/R) sum_r rowloss[r];  total = (i == 0 ? 0 : total) + w * node_loss[i]
 // The same for nodes first .. first+count-1 in one launch (rows of node j at rowloss + off[j]).
 constexpr int kLossNodes = 32;

@@ -226,7 +226,7 @@ class Mlp final : public Model {
       else
         VF_KS(c, st, "softmax_xent", launch_softmax_xent(slab_buf, split, slab, L.ld, L.z[q], L.ld, y, b, L.N,
                                                          c.rowloss + row0, L.dz[q], L.ld, bf16_, bf16_ ? L.dzT + pc : nullptr, ldw_, w, i,
-                                                         nullptr, nullptr, st));
+                                                         nullptr, nullptr, st, tscale(c, s, i)));
     }
     wait_casts_ = false;
     // loss bookkeeping of the whole step after the last node's rows are in: node losses and
@@ -274,7 +274,7 @@ class Mlp final : public Model {
       VF_KS(c, st, "bn_relu_bwd", launch_bn_relu_bwd(slab_buf, split, slab, Pv.ld, Pv.z[q], Pv.ld, b, Pv.N,
                                      Pv.has_bn ? P + Pv.g_off : nullptr, Pv.has_bn ? P + Pv.be_off : nullptr,
                                      bf16_, Pv.mean[q], Pv.rstd[q], Pv.dz[0], Pv.ld, bf16_, bf16_ ? Pv.dzT + pc : nullptr, ldw_,
-                                     gg, gb, st));
+                                     gg, gb, st, tscale(c, s, i)));
     }
     return VF_OK;
   }
@@ -291,7 +291,8 @@ class Mlp final : public Model {
     for (const Layer& L : layers_) fold = fold && (L.N & 3) == 0 && ((L.w_off & 3) == 0);
     // Nodes of one size have one weight w, and their operand copies lie side by side: the
     // window's weighted sum is w times ONE product over all its rows.
-    const bool joined = side_by_side(c, s, i0, count);
+    const int kind = join_kind(c, s, i0, count);
+    const bool joined = kind != kJoinNone;
     if (joined) fold = false;
     // after the step's last window layer l's gradient is final
     const bool last_window = i0 + count == s.V;
@@ -320,8 +321,8 @@ class Mlp final : public Model {
     }
     if (joined) {
       // x of the whole window is one contiguous block of rows: one transpose
-      const int rows = count * s.sizes[i0];
-      const float w = s.w[i0];
+      const int rows = (int)(s.off[i0 + count - 1] + s.sizes[i0 + count - 1] - s.off[i0]);
+      const float w = kind == kJoinScaled ? 1.f : s.w[i0];    // scaled: the weights are in the operand
       const int64_t pc = cols(c, s, i0);
       VF_KS(c, st, "transpose", launch_transpose_bf16(static_cast<const bf16_t*>(s.x) + (int64_t)s.off[i0] * D, D,
                                                       xT_ + pc, ldw_, rows, D, st));
@@ -399,21 +400,43 @@ class Mlp final : public Model {
     *i0 = i / c.window * c.window;
     *count = std::min(c.window, s.V - *i0);
   }
-  // True when the nodes i0 .. i0+count-1 form a window whose weighted gradient sum is taken as
-  // one product: several nodes of one size (hence one weight b_i/B) that keeps 16-byte alignment.
+  // How the weighted gradient sum of the window i0 .. i0+count-1 is taken:
+  //   kJoinNone    node by node (or the chain kernel),
+  //   kJoinEqual   several nodes of ONE size (hence one weight b_i/B): the weight times one product
+  //                over all the window's rows,
+  //   kJoinScaled  nodes of several sizes: one product over all the window's rows, each node's rows
+  //                of the transposed output gradients holding w_i dz (the per-sample gradient of the
+  //                step's loss, Section 5.2) instead of dz.
+  // Both joined kinds need node sizes that keep the operand copies 16-byte aligned.
+  enum { kJoinNone = 0, kJoinEqual = 1, kJoinScaled = 2 };
+  int join_kind(const Ctx& c, const StepArgs& s, int i0, int count) const {
+    if (!bf16_ || !c.fused || ordered_ || count < 2) return kJoinNone;
+    bool equal = true;
+    for (int i = i0; i < i0 + count; ++i) {
+      if (s.sizes[i] & 7) return kJoinNone;
+      equal = equal && s.sizes[i] == s.sizes[i0];
+    }
+    return equal ? kJoinEqual : kJoinScaled;
+  }
   bool side_by_side(const Ctx& c, const StepArgs& s, int i0, int count) const {
-    if (!bf16_ || !c.fused || ordered_ || count < 2 || (s.sizes[i0] & 7)) return false;
-    for (int i = i0 + 1; i < i0 + count; ++i)
-      if (s.sizes[i] != s.sizes[i0]) return false;
-    return true;
+    return join_kind(c, s, i0, count) != kJoinNone;
+  }
+  // What the transposed output gradients of node i are scaled by (see join_kind).
+  float tscale(const Ctx& c, const StepArgs& s, int i) const {
+    int i0, count;
+    window_of(c, s, i, &i0, &count);
+    return join_kind(c, s, i0, count) == kJoinScaled ? s.w[i] : 1.f;
   }
   // First column of node i's copy in the wide transposed operands: copies are ldb_ columns
-  // apart, or exactly the node size apart when the window's nodes are to lie side by side.
+  // apart, or packed one after the other when the window's nodes are to lie side by side.
   int64_t cols(const Ctx& c, const StepArgs& s, int i) const {
     int i0, count;
     window_of(c, s, i, &i0, &count);
-    const int64_t pitch = side_by_side(c, s, i0, count) ? s.sizes[i0] : ldb_;
-    return c.slot(i) * pitch;
+    switch (join_kind(c, s, i0, count)) {
+      case kJoinEqual: return (int64_t)c.slot(i) * s.sizes[i0];
+      case kJoinScaled: return (int64_t)c.slot(i0) * ldb_ + (s.off[i] - s.off[i0]);
+      default: return (int64_t)c.slot(i) * ldb_;
+    }
   }
 
   vf_config cfg_;

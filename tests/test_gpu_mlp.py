@@ -230,9 +230,10 @@ def test_overlap_and_single_stream_agree_bitwise():
 @pytest.mark.parametrize("name", ["mlp_mid_bn_bf16", "mlp_mid_bf16", "mlp_big_node_bf16"])
 def test_two_streams_with_fold_windows_agree_bitwise(name, window):
     """Forward passes on one stream, backward passes and weight gradients on the other, with and
-    without graph replay, three steps (buffer sets and operand copies are reused across steps)."""
+    without graph replay, three steps (buffer sets and operand copies are reused across steps):
+    the same bits as one stream with the same window."""
     wl, theta, x, y = _case(name)
-    base = run_gpu(wl, theta, x, y, flags=FUSED | NO_GRAPH, steps=3)
+    base = run_gpu(wl, theta, x, y, flags=FUSED | NO_GRAPH, steps=3, fold_window=window)
     for flags in (FUSED | OVERLAP, FUSED | OVERLAP | NO_GRAPH):
         other = run_gpu(wl, theta, x, y, flags=flags, steps=3, fold_window=window)
         assert base["G"].tobytes() == other["G"].tobytes(), flags
@@ -247,11 +248,17 @@ def test_two_streams_with_fold_windows_agree_bitwise(name, window):
 @pytest.mark.parametrize("name,flags", [("mlp_mid_bn_bf16", FUSED), ("mlp_mid_bf16", FUSED),
                                         ("mlp_mid_bn_bf16", FUSED | NO_GRAPH)])
 def test_fold_window_gives_the_node_by_node_result_bitwise(name, flags, window):
-    """Same chain of fused multiply-adds, so the same bits: five unequal nodes (the last window is
-    ragged), two steps so that the buffer is overwritten, not accumulated, by the second."""
+    """The ordered fold: the same chain of fused multiply-adds, so the same bits: five unequal nodes
+    (the last window is ragged), two steps so that the buffer is overwritten, not accumulated, by
+    the second.  Also with node sizes that are no multiples of 8, where it is the only windowed path."""
     wl, theta, x, y = _case(name)
     one = run_gpu(wl, theta, x, y, flags=flags, steps=2)
-    win = run_gpu(wl, theta, x, y, flags=flags, steps=2, fold_window=window)
+    win = run_gpu(wl, theta, x, y, flags=flags | 8, steps=2, fold_window=window)
+    odd = [44, 20, 125, 43, 8]
+    assert sum(odd) == wl.batch
+    one_odd = run_gpu(wl, theta, x, y, node_sizes=odd, flags=flags, steps=2)
+    win_odd = run_gpu(wl, theta, x, y, node_sizes=odd, flags=flags, steps=2, fold_window=window)
+    assert one_odd["G"].tobytes() == win_odd["G"].tobytes()
     assert one["G"].tobytes() == win["G"].tobytes()
     assert one["theta"].tobytes() == win["theta"].tobytes()
     assert one["loss"] == win["loss"]
@@ -283,6 +290,33 @@ def test_window_of_equal_nodes_as_one_product(name, window):
     check_against_oracle(wl, joined, ref, tol=2 * TOL[wl.dtype])
     for flags in (FUSED | OVERLAP, FUSED | OVERLAP | NO_GRAPH, FUSED | NO_GRAPH):
         other = run_gpu(wl, theta, xs, ys, node_sizes=sizes, flags=flags, steps=2, fold_window=window)
+        assert joined["G"].tobytes() == other["G"].tobytes(), flags
+        assert joined["theta"].tobytes() == other["theta"].tobytes(), flags
+
+
+@pytest.mark.parametrize("window", [2, 3, 8])
+@pytest.mark.parametrize("name", ["mlp_mid_bn_bf16", "mlp_mid_bf16"])
+def test_window_of_unequal_nodes_as_one_product(name, window):
+    """Unequal nodes whose sizes are multiples of 8: the window's weighted gradient sum as one
+    product over all its rows, node i's rows of the transposed output gradients holding
+    (b_i/B) dz -- the per-sample gradient of the step's loss (Section 5.2) -- rounded to bf16
+    once.  Against the oracle, against the ordered chain (one bf16 rounding apart), and the same
+    bits on two streams, replayed or launched one by one."""
+    wl, theta, x, y = _case(name)
+    assert all(b % 8 == 0 for b in wl.node_sizes) and len(set(wl.node_sizes)) > 1
+    first = run_gpu(wl, theta, x, y, flags=FUSED, fold_window=window)
+    ordered = run_gpu(wl, theta, x, y, flags=FUSED | ORDERED, fold_window=window)
+    scale = np.abs(ordered["G"]).max()
+    print("joined - ordered, largest entry relative to the largest gradient:",
+          np.abs(first["G"] - ordered["G"]).max() / scale, flush=True)
+    assert np.abs(first["G"] - ordered["G"]).max() <= 1e-2 * scale     # two bf16 roundings of 2^-9 each, over the rows
+    assert first["G"].tobytes() != ordered["G"].tobytes()
+    assert first["loss"] == ordered["loss"]
+    joined = run_gpu(wl, theta, x, y, flags=FUSED, steps=2, fold_window=window)
+    ref = oracle_steps(wl, theta, x, y, steps=2)
+    check_against_oracle(wl, joined, ref, tol=2 * TOL[wl.dtype])
+    for flags in (FUSED | OVERLAP, FUSED | OVERLAP | NO_GRAPH, FUSED | NO_GRAPH):
+        other = run_gpu(wl, theta, x, y, flags=flags, steps=2, fold_window=window)
         assert joined["G"].tobytes() == other["G"].tobytes(), flags
         assert joined["theta"].tobytes() == other["theta"].tobytes(), flags
 
