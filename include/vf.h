@@ -73,7 +73,8 @@ extern "C" {
                                         element (one fused multiply-add), same node order */
 #define VF_FLAG_NO_GRAPH         2u  /* launch kernels one by one instead of replaying a
                                         captured HIP graph */
-#define VF_FLAG_OVERLAP          4u  /* two streams (bf16 MLP only; same results bit for bit):
+#define VF_FLAG_OVERLAP          4u  /* two streams (bf16 MLP and bf16 encoder; same results bit
+                                        for bit as one stream):
                                         the forward passes run on the caller's stream, the
                                         backward passes and weight gradients on a second,
                                         library-owned stream, so that node i+1's forward pass
@@ -82,12 +83,16 @@ extern "C" {
                                         matters stays on one stream; the tensors that pass from a
                                         node's forward to its backward pass are kept twice. */
 #define VF_FLAG_ORDERED_FOLD     8u  /* inside a fold window keep the node-by-node chain of
-                                        roundings, G <- fma(b_i/B, g_i, G) node after node, also
-                                        when all its nodes have one size.  Without this flag such
-                                        a window (bf16 MLP) takes its weight gradients as ONE
-                                        product over all the window's rows, times the common
-                                        weight: the same sum with fewer roundings, equal to the
-                                        node-by-node result to fp32 rounding, not bit for bit. */
+                                        roundings, G <- fma(b_i/B, g_i, G) node after node.
+                                        Without this flag a window (bf16 MLP) whose node sizes
+                                        are multiples of 8 takes its weight gradients as ONE
+                                        product over all the window's rows.  Nodes of one size:
+                                        times the common weight, the same sum with fewer
+                                        roundings, equal to the node-by-node result to fp32
+                                        rounding.  Nodes of several sizes: with b_i/B folded into
+                                        the bf16 output gradients of node i before the product
+                                        (rounded once from fp32), one bf16 rounding apart from
+                                        the node-by-node result.  Neither is bit for bit. */
 
 typedef struct vf_ctx vf_ctx;
 
