@@ -527,48 +527,44 @@ inline size_t tall_lds(int C) {
 // 64 rows of dy, and the image rows of x from one above to one below the stage, each image row
 // with one empty position before and after it.  Image rows outside the image are fetched from a
 // block of zeros and the empty positions are cleared once, so every shifted read finds either
-// its value or 0 at a fixed offset: no masks.  Every lane gathers its operand elements with
-// 2-byte LDS reads (element j of a lane = position 16 kk + 2 j + lane/32 of the stage: the two
-// half-waves read rows of different parity, i.e. different halves of the LDS banks); the dy
-// operand of a contraction step serves all nine taps.
+// its value or 0 at a fixed offset: no masks.  The operands come out of LDS through the
+// transposing read (wg_read8: two reads give a lane its eight consecutive contraction elements
+// -- positions -- of one channel); the dy operand of a contraction step serves all nine taps.
 // Workgroup (block, slice z) writes slab z of [Cout, 9 Cin]; the slabs are added in order
 // afterwards.  Requires Cout % 64 == 0, Cin % 64 == 0, H % (64 / W) == 0 (a stage lies within
 // one image), rows % 64 == 0.
 typedef __bf16 wg_bf16x8 __attribute__((ext_vector_type(8)));
 typedef float wg_f32x16 __attribute__((ext_vector_type(16)));
 
-// One stage of 64 positions for taps T0 .. T0+NTAP-1: A and B point at this lane's first element
-// of the dy rows and of the stored x positions.
+// Transposing LDS read (ds_read_b64_tr_b16): within each group of 16 lanes, lane 4a + b receives
+// element b of the four 64-bit words that lanes a, a + 4, a + 8, a + 12 point at.  With source lane
+// s pointing at position s / 4 (of four consecutive positions), channels 4 (s % 4) .. + 3, lane i
+// of the group receives channel i at those four positions: four consecutive contraction
+// elements of one operand row, which is what the matrix cores read.
+typedef short wg_s16x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ wg_bf16x8 wg_read8(const bf16_t* first4, const bf16_t* next4) {
+  const wg_s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((wg_s16x4 __attribute__((address_space(3)))*)first4);
+  const wg_s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((wg_s16x4 __attribute__((address_space(3)))*)next4);
+  wg_bf16x8 r;
+  __builtin_memcpy(&r, &lo, 8);
+  __builtin_memcpy(reinterpret_cast<char*>(&r) + 8, &hi, 8);
+  return r;
+}
+
+// One stage of 64 positions for taps T0 .. T0+NTAP-1.  A: this lane's source address in the dy rows
+// for contraction step 0, first half; B[kk][r]: its source address in the stored x positions for
+// step kk, half r, tap (0, 0).
 template <int W, int T0, int NTAP>
-__device__ __forceinline__ void wgrad_stage(const unsigned short* A, const unsigned short* B, wg_f32x16 (&acc)[5]) {
+__device__ __forceinline__ void wgrad_stage(const bf16_t* A, const bf16_t* const (&B)[4][2], wg_f32x16 (&acc)[5]) {
   constexpr int PW = W + 2;
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk) {
-    uint32_t av[4];
-#pragma unroll
-    for (int j = 0; j < 8; j += 2) {
-      const uint32_t lo = A[(16 * kk + 2 * j) * 64];
-      const uint32_t hi = A[(16 * kk + 2 * j + 2) * 64];
-      av[j >> 1] = lo | (hi << 16);
-    }
-    wg_bf16x8 a;
-    __builtin_memcpy(&a, av, 16);
+    const wg_bf16x8 a = wg_read8(A + (16 * kk) * 64, A + (16 * kk + 4) * 64);
 #pragma unroll
     for (int tt = 0; tt < NTAP; ++tt) {
       const int kh = (T0 + tt) / 3, kw = (T0 + tt) % 3;
-      uint32_t bv[4];
-#pragma unroll
-      for (int j = 0; j < 8; j += 2) {
-        // stored position of stage position e under this tap: image row e / W + kh, column e % W + kw
-        const int e0 = 16 * kk + 2 * j, e1 = e0 + 2;
-        const int p0 = (e0 / W + kh) * PW + e0 % W + kw;
-        const int p1 = (e1 / W + kh) * PW + e1 % W + kw;
-        const uint32_t lo = B[p0 * 64];
-        const uint32_t hi = B[p1 * 64];
-        bv[j >> 1] = lo | (hi << 16);
-      }
-      wg_bf16x8 b;
-      __builtin_memcpy(&b, bv, 16);
+      const int shift = (kh * PW + kw) * 64;
+      const wg_bf16x8 b = wg_read8(B[kk][0] + shift, B[kk][1] + shift);
       acc[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[tt], 0, 0, 0);
     }
   }
@@ -594,7 +590,6 @@ __global__ __launch_bounds__(WG_NT) void conv_wgrad_kernel(const bf16_t* __restr
   const int ctiles = Cin / 64;
   const int o0 = (blockIdx.x / ctiles) * 64, c0 = (blockIdx.x % ctiles) * 64;
   const int sbeg = blockIdx.y * stages_per_wg, send = min(nstages, sbeg + stages_per_wg);
-  const unsigned short* L16 = reinterpret_cast<const unsigned short*>(wg_lds);
 
   // the empty positions before and after every stored image row, both buffers (32 dwords each)
   for (int k = tid; k < 2 * (IR + 2) * 2 * 32; k += WG_NT) {
@@ -631,9 +626,19 @@ __global__ __launch_bounds__(WG_NT) void conv_wgrad_kernel(const bf16_t* __restr
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
 
-  // this lane's element offsets inside a stage buffer (one position = 64 elements)
-  const int a_off = khalf * 64 + wm * 32 + lc;
-  const int b_off = (64 + khalf) * 64 + wn * 32 + lc;
+  // this lane as a SOURCE of the transposing reads (see wg_read8): position j of four, channels 4 a .. 4 a + 3
+  // of the 16-channel half its group of 16 lanes serves; element offsets inside a stage buffer
+  // (one position = 64 elements).  Stage position e is stored at (e / W + kh) * PW + e % W + kw under tap (kh, kw).
+  const int srcj = (lane & 15) >> 2, srca = lane & 3, half16 = (lane >> 4) & 1;
+  const int a_off = (8 * khalf + srcj) * 64 + wm * 32 + 16 * half16 + 4 * srca;
+  int b_off[4][2];
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+      const int e = 16 * kk + 8 * khalf + 4 * r + srcj;
+      b_off[kk][r] = (64 + (e / W) * PW + e % W) * 64 + wn * 32 + 16 * half16 + 4 * srca;
+    }
 
   if (sbeg < send) issue(sbeg, 0);
   for (int st = sbeg; st < send; ++st) {
@@ -641,8 +646,10 @@ __global__ __launch_bounds__(WG_NT) void conv_wgrad_kernel(const bf16_t* __restr
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();                                       // stage st is in LDS; everybody is done with the other buffer
     if (st + 1 < send) issue(st + 1, buf ^ 1);
-    const unsigned short* A = L16 + buf * BUF + a_off;
-    const unsigned short* B = L16 + buf * BUF + b_off;
+    const bf16_t* A = wg_lds + buf * BUF + a_off;
+    const bf16_t* B[4][2];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) { B[kk][0] = wg_lds + buf * BUF + b_off[kk][0]; B[kk][1] = wg_lds + buf * BUF + b_off[kk][1]; }
     if (tgroup == 0) wgrad_stage<W, 0, 5>(A, B, acc);
     else             wgrad_stage<W, 5, 4>(A, B, acc);
   }
