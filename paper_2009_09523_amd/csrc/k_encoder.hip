@@ -3,6 +3,8 @@
 // All statistics and reductions in fp32; one wavefront per row where a row is reduced.
 #include <algorithm>
 
+#include <cstdlib>
+
 #include "vf_device.h"
 
 namespace vf {
@@ -198,7 +200,7 @@ __global__ __launch_bounds__(NT) void layernorm_bwd_kernel(const float* __restri
                                                            float* __restrict__ dx, int64_t lddx,
                                                            int rows_per_wg, float* __restrict__ partial,
                                                            int64_t pstride) {
-  extern __shared__ float wsum[];            // [2][WAVES][d]
+  extern __shared__ __attribute__((aligned(16))) float wsum[];   // [2][WAVES][d]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int chunk = blockIdx.x;
   const int rbeg = chunk * rows_per_wg;
@@ -258,6 +260,109 @@ __global__ __launch_bounds__(NT) void layernorm_bwd_kernel(const float* __restri
   for (int j = 0; j < LN_JMAX; ++j) {
     const int c = lane + 64 * j;
     if (c < d) { wsum[(0 * WAVES + wave) * d + c] = pg[j]; wsum[(1 * WAVES + wave) * d + c] = pb[j]; }
+  }
+  __syncthreads();
+  for (int c = threadIdx.x; c < d; c += NT) {
+    float a = 0.f, b = 0.f;
+#pragma unroll
+    for (int wv = 0; wv < WAVES; ++wv) { a += wsum[(0 * WAVES + wv) * d + c]; b += wsum[(1 * WAVES + wv) * d + c]; }
+    partial[(int64_t)chunk * d + c] = a;
+    partial[pstride + (int64_t)chunk * d + c] = b;
+  }
+}
+
+// The same with 16-byte accesses: a lane owns columns 4 lane + 256 j .. + 3 (j < 4: d <= 1024).
+// Requires d % 4 == 0, leading dimensions multiples of 4, 16-byte aligned bases.
+__global__ __launch_bounds__(NT) void layernorm_bwd4_kernel(const float* __restrict__ dyp, int nsplit,
+                                                            int64_t slab, int64_t lddy,
+                                                            const float* __restrict__ x, int64_t ldx,
+                                                            const int32_t* __restrict__ row_map, int R,
+                                                            int d, const float* __restrict__ gamma,
+                                                            int round_params,
+                                                            const float* __restrict__ mean_in,
+                                                            const float* __restrict__ rstd_in,
+                                                            const float* __restrict__ dres,
+                                                            float* __restrict__ dx, int64_t lddx,
+                                                            int rows_per_wg, float* __restrict__ partial,
+                                                            int64_t pstride) {
+  extern __shared__ __attribute__((aligned(16))) float wsum[];   // [2][WAVES][d]
+  constexpr int JQ = 4;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int chunk = blockIdx.x;
+  const int rbeg = chunk * rows_per_wg;
+  const int rend = min(R, rbeg + rows_per_wg);
+  float4 pg[JQ], pb[JQ], gv[JQ];
+#pragma unroll
+  for (int j = 0; j < JQ; ++j) {
+    pg[j] = make_float4(0.f, 0.f, 0.f, 0.f); pb[j] = pg[j];
+    const int c = min(4 * lane + 256 * j, d - 4);
+    gv[j] = *reinterpret_cast<const float4*>(&gamma[c]);
+    if (round_params) { gv[j].x = round_bf16(gv[j].x); gv[j].y = round_bf16(gv[j].y); gv[j].z = round_bf16(gv[j].z); gv[j].w = round_bf16(gv[j].w); }
+  }
+  for (int r = rbeg + wave; r < rend; r += WAVES) {
+    const int64_t orow = row_map ? row_map[r] : r;
+    const float* xr = x + orow * ldx;
+    const float mean = mean_in[r], rstd = rstd_in[r];
+    float4 dyv[JQ], xhv[JQ], resv[JQ];
+    // all loads first, at clamped (always valid) columns, so that they are in flight together
+#pragma unroll
+    for (int j = 0; j < JQ; ++j) {
+      const int c = min(4 * lane + 256 * j, d - 4);
+      resv[j] = dres ? *reinterpret_cast<const float4*>(&dres[orow * lddx + c]) : make_float4(0.f, 0.f, 0.f, 0.f);
+      dyv[j] = *reinterpret_cast<const float4*>(&dyp[(int64_t)r * lddy + c]);
+      xhv[j] = *reinterpret_cast<const float4*>(&xr[c]);
+    }
+    for (int s = 1; s < nsplit; ++s) {            // the slabs in order
+#pragma unroll
+      for (int j = 0; j < JQ; ++j) {
+        const float4 t = *reinterpret_cast<const float4*>(&dyp[(int64_t)s * slab + (int64_t)r * lddy + min(4 * lane + 256 * j, d - 4)]);
+        dyv[j].x += t.x; dyv[j].y += t.y; dyv[j].z += t.z; dyv[j].w += t.w;
+      }
+    }
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int j = 0; j < JQ; ++j) {
+      const bool on = 4 * lane + 256 * j < d;
+      float* dyp4 = reinterpret_cast<float*>(&dyv[j]);
+      float* xh4 = reinterpret_cast<float*>(&xhv[j]);
+      const float* g4 = reinterpret_cast<const float*>(&gv[j]);
+      float* pg4 = reinterpret_cast<float*>(&pg[j]);
+      float* pb4 = reinterpret_cast<float*>(&pb[j]);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float dy = on ? dyp4[e] : 0.f;
+        const float xh = on ? (xh4[e] - mean) * rstd : 0.f;
+        dyp4[e] = dy; xh4[e] = xh;
+        const float dxh = dy * g4[e];
+        s1 += dxh;
+        s2 = fmaf(dxh, xh, s2);
+        pg4[e] = fmaf(dy, xh, pg4[e]);
+        pb4[e] += dy;
+      }
+    }
+    s1 = wave_sum(s1) / (float)d;
+    s2 = wave_sum(s2) / (float)d;
+#pragma unroll
+    for (int j = 0; j < JQ; ++j) {
+      const int c = 4 * lane + 256 * j;
+      if (c < d) {
+        float4 o;
+        o.x = (dyv[j].x * gv[j].x - s1 - xhv[j].x * s2) * rstd + resv[j].x;
+        o.y = (dyv[j].y * gv[j].y - s1 - xhv[j].y * s2) * rstd + resv[j].y;
+        o.z = (dyv[j].z * gv[j].z - s1 - xhv[j].z * s2) * rstd + resv[j].z;
+        o.w = (dyv[j].w * gv[j].w - s1 - xhv[j].w * s2) * rstd + resv[j].w;
+        *reinterpret_cast<float4*>(&dx[orow * lddx + c]) = o;
+      }
+    }
+  }
+  if (!partial) return;
+#pragma unroll
+  for (int j = 0; j < JQ; ++j) {
+    const int c = 4 * lane + 256 * j;
+    if (c < d) {
+      *reinterpret_cast<float4*>(&wsum[(0 * WAVES + wave) * d + c]) = pg[j];
+      *reinterpret_cast<float4*>(&wsum[(1 * WAVES + wave) * d + c]) = pb[j];
+    }
   }
   __syncthreads();
   for (int c = threadIdx.x; c < d; c += NT) {
@@ -602,13 +707,23 @@ int launch_layernorm_bwd(const float* dyp, int nsplit, int64_t slab, int64_t ldd
                          float* dx, int64_t lddx, float* scratch, GradOut gout_g, GradOut gout_b,
                          hipStream_t s) {
   if (R <= 0 || d <= 0 || nsplit < 1 || d > 64 * LN_JMAX || !scratch) return VF_EINVAL;
-  const int rows_per_wg = std::max(WAVES, (R + kLnChunks - 1) / kLnChunks);
+  // about one workgroup per compute unit: fewer row chunks for the finish kernel to add up
+  static const int ln_wgs = std::getenv("VF_LN_WGS") ? std::atoi(std::getenv("VF_LN_WGS")) : 256;
+  const int rows_per_wg = std::max(std::max(WAVES, (R + kLnChunks - 1) / kLnChunks), (R + ln_wgs - 1) / ln_wgs);
   const int nchunk = (R + rows_per_wg - 1) / rows_per_wg;
   const int64_t pstride = (int64_t)kLnChunks * d;
   const size_t lds = (size_t)2 * WAVES * d * sizeof(float);
-  layernorm_bwd_kernel<<<nchunk, NT, lds, s>>>(dyp, nsplit, slab, lddy, x, ldx, row_map, R, d, gamma,
-                                               round_params, mean, rstd, dres, dx, lddx, rows_per_wg,
-                                               scratch, pstride);
+  const bool vec4 = (d & 3) == 0 && (lddy & 3) == 0 && (ldx & 3) == 0 && (lddx & 3) == 0 && (slab & 3) == 0 &&
+                    ((reinterpret_cast<uintptr_t>(dyp) | reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(dx) |
+                      reinterpret_cast<uintptr_t>(gamma) | reinterpret_cast<uintptr_t>(dres)) & 15) == 0;
+  if (vec4)
+    layernorm_bwd4_kernel<<<nchunk, NT, lds, s>>>(dyp, nsplit, slab, lddy, x, ldx, row_map, R, d, gamma,
+                                                  round_params, mean, rstd, dres, dx, lddx, rows_per_wg,
+                                                  scratch, pstride);
+  else
+    layernorm_bwd_kernel<<<nchunk, NT, lds, s>>>(dyp, nsplit, slab, lddy, x, ldx, row_map, R, d, gamma,
+                                                 round_params, mean, rstd, dres, dx, lddx, rows_per_wg,
+                                                 scratch, pstride);
   VF_LAUNCH_CHECK();
   layernorm_param_finish_kernel<<<(d + 15) / 16, NT, 0, s>>>(scratch, pstride, nchunk, d, gout_g, gout_b);
   VF_LAUNCH_CHECK();
