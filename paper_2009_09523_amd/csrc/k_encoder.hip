@@ -34,7 +34,15 @@ __global__ __launch_bounds__(NT) void embed_pos_bwd_kernel(const float* __restri
   const int t = blockIdx.x;
   for (int c = threadIdx.x; c < d; c += NT) {
     float s = 0.f;
-    for (int q = 0; q < nseq; ++q) s += dh[((int64_t)q * T + t) * d + c];
+    int q = 0;
+    for (; q + 8 <= nseq; q += 8) {              // eight sequences' values in flight, added in sequence order
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = dh[((int64_t)(q + u) * T + t) * d + c];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) s += v[u];
+    }
+    for (; q < nseq; ++q) s += dh[((int64_t)q * T + t) * d + c];
     grad_store(out, (int64_t)t * d + c, s);
   }
 }
@@ -58,12 +66,18 @@ __global__ __launch_bounds__(NT) void embed_tok_bwd_kernel(const int32_t* __rest
   if (threadIdx.x == 0) earlier = 0;
   for (int wd = threadIdx.x; wd < nwords; wd += NT) match[wd] = 0u;
   __syncthreads();
-  for (int q0 = 0; q0 < R; q0 += NT) {
-    const int q = q0 + threadIdx.x;
-    const bool hit = q < R && clampi(ids[q], 0, vocab - 1) == id;
-    if (hit) {
-      if (q < r) earlier = 1;                       // benign race: every writer stores 1
-      else atomicOr(&match[q >> 5], 1u << (q & 31));  // LDS bit set; order does not matter
+  for (int q0 = 0; q0 < R; q0 += 8 * NT) {          // eight loads of ids in flight per thread
+    int other[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) other[u] = ids[min(q0 + u * NT + (int)threadIdx.x, R - 1)];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int q = q0 + u * NT + threadIdx.x;
+      const bool hit = q < R && clampi(other[u], 0, vocab - 1) == id;
+      if (hit) {
+        if (q < r) earlier = 1;                       // benign race: every writer stores 1
+        else atomicOr(&match[q >> 5], 1u << (q & 31));  // LDS bit set; order does not matter
+      }
     }
   }
   __syncthreads();
