@@ -457,6 +457,8 @@ int vf_init(const vf_config* cfg, vf_ctx** out) {
   if (e == hipSuccess) e = hipStreamSynchronize(c.stream);
   if (e != hipSuccess) {
     set_last_error("hipMemsetAsync", e, __FILE__, __LINE__);
+    (void)hipGetLastError();
+    release_streams(c);
     (void)hipFree(c.arena);
     delete h;
     return VF_EDEVICE;

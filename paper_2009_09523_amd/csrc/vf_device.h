@@ -22,6 +22,11 @@ __device__ __forceinline__ float load_f(const float* p) { return *p; }
 __device__ __forceinline__ float load_f(const bf16_t* p) { return bf16_to_f32(*p); }
 __device__ __forceinline__ void store_f(float* p, float v) { *p = v; }
 __device__ __forceinline__ void store_f(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+// two consecutive elements at an address aligned for the pair
+__device__ __forceinline__ void store_f2(float* p, float a, float b) { *reinterpret_cast<float2*>(p) = make_float2(a, b); }
+__device__ __forceinline__ void store_f2(bf16_t* p, float a, float b) {
+  *reinterpret_cast<uint32_t*>(p) = (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
+}
 
 __device__ __forceinline__ void grad_store(const GradOut& g, int64_t p, float v) {
   float old = g.accumulate ? g.dst[p] : 0.f;

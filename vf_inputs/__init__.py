@@ -127,6 +127,11 @@ WORKLOADS: Dict[str, Workload] = {
                          optimizer="adam", lr=1e-4),
     "enc_small_f32": _enc("enc_small_f32", 2, 128, 2, 264, 32, 1003, [4, 2, 3], "f32",
                           optimizer="adam", lr=1e-4),
+    # vocabularies beyond 1024 entries, odd, so the logits' rows end inside a pair of columns
+    "enc_vocab_f32": _enc("enc_vocab_f32", 1, 64, 2, 136, 16, 4099, [2, 1, 3], "f32",
+                          optimizer="adam", lr=1e-3),
+    "enc_vocab_bf16": _enc("enc_vocab_bf16", 1, 64, 2, 136, 16, 9001, [2, 1, 3], "bf16",
+                           optimizer="adam", lr=1e-4),
     # second workload family: a residual network of 3x3 convolutions (the paper's headline
     # workloads are ResNets); C6 = 32 x 32 x 3 inputs, width 64, two blocks, nodes as in C2
     "C6": _conv("C6", 32, 3, 64, 2, 10, [128] * 8, "bf16"),
