@@ -127,6 +127,123 @@ __global__ __launch_bounds__(NT) void embed_tok_bwd_kernel(const int32_t* __rest
   }
 }
 
+// The same with 16-byte accesses (d a multiple of 4, d <= 1024) and the matching rows dealt out
+// to the four wavefronts: wavefront w adds the matches k = w, w + 4, w + 8, .. of the increasing
+// list, eight rows in flight per lane (read at clamped list positions, selected afterwards, so no
+// load waits behind a branch), and the four partial sums are joined in wavefront order.  An id
+// that many tokens share (the id that stands in for masked positions: 15 % of a node's tokens)
+// is the launch's critical path: 32 rows in flight for it instead of 8.  The order of the
+// additions is fixed, so the result is the same on every run.
+__global__ __launch_bounds__(NT) void embed_tok_bwd4_kernel(const int32_t* __restrict__ ids,
+                                                            const float* __restrict__ dh, int R, int d,
+                                                            int vocab, GradOut out) {
+  __shared__ uint32_t match[MAX_TOK_WORDS];
+  __shared__ int list[256];
+  __shared__ int nlist, next_word;
+  __shared__ int earlier;
+  __shared__ __attribute__((aligned(16))) float part[3 * 1024];
+  const int r = blockIdx.x;
+  const int id = clampi(ids[r], 0, vocab - 1);
+  const int nwords = (R + 31) / 32;
+  if (threadIdx.x == 0) earlier = 0;
+  for (int wd = threadIdx.x; wd < nwords; wd += NT) match[wd] = 0u;
+  __syncthreads();
+  for (int q0 = 0; q0 < R; q0 += 8 * NT) {
+    int other[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) other[u] = ids[min(q0 + u * NT + (int)threadIdx.x, R - 1)];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int q = q0 + u * NT + threadIdx.x;
+      const bool hit = q < R && clampi(other[u], 0, vocab - 1) == id;
+      if (hit) {
+        if (q < r) earlier = 1;
+        else atomicOr(&match[q >> 5], 1u << (q & 31));
+      }
+    }
+  }
+  __syncthreads();
+  if (earlier) return;
+  constexpr int CPL = 4;                            // 16-byte columns per lane: d <= 1024
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  float4 acc[CPL];
+#pragma unroll
+  for (int j = 0; j < CPL; ++j) acc[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (threadIdx.x == 0) next_word = r >> 5;
+  __syncthreads();
+  while (true) {
+    if (threadIdx.x == 0) {
+      int n = 0, wd = next_word;
+      for (; wd < nwords && n <= 256 - 32; ++wd) {
+        uint32_t bits = match[wd];
+        while (bits) {
+          list[n++] = (wd << 5) + __ffs(bits) - 1;
+          bits &= bits - 1;
+        }
+      }
+      nlist = n;
+      next_word = wd;
+    }
+    __syncthreads();
+    const int n = nlist;
+    const bool last = next_word >= nwords;
+    for (int k0 = 0; k0 < n; k0 += 32) {
+      int row[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) row[u] = list[min(k0 + 4 * u + wave, n - 1)];
+#pragma unroll
+      for (int j = 0; j < CPL; ++j) {
+        const int c = min(4 * lane + 256 * j, d - 4);
+        float4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const float4*>(&dh[(int64_t)row[u] * d + c]);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {               // padding adds +0
+          const bool live = k0 + 4 * u + wave < n;
+          acc[j].x += live ? v[u].x : 0.f;
+          acc[j].y += live ? v[u].y : 0.f;
+          acc[j].z += live ? v[u].z : 0.f;
+          acc[j].w += live ? v[u].w : 0.f;
+        }
+      }
+    }
+    __syncthreads();
+    if (last) break;
+  }
+  // join the wavefronts' sums in wavefront order; wavefront 0 writes the table row
+  if (wave > 0) {
+#pragma unroll
+    for (int j = 0; j < CPL; ++j) {
+      const int c = 4 * lane + 256 * j;
+      if (c < d) *reinterpret_cast<float4*>(&part[(wave - 1) * 1024 + c]) = acc[j];
+    }
+  }
+  __syncthreads();
+  if (wave > 0) return;
+  float4 old[CPL];
+#pragma unroll
+  for (int j = 0; j < CPL; ++j) {
+    const int c = min(4 * lane + 256 * j, d - 4);
+    old[j] = *reinterpret_cast<const float4*>(&out.dst[(int64_t)id * d + c]);
+  }
+#pragma unroll
+  for (int j = 0; j < CPL; ++j) {
+    const int c = 4 * lane + 256 * j;
+    if (c < d) {
+      float4 t = acc[j];
+#pragma unroll
+      for (int w = 0; w < 3; ++w) {
+        const float4 p = *reinterpret_cast<const float4*>(&part[w * 1024 + c]);
+        t.x += p.x; t.y += p.y; t.z += p.z; t.w += p.w;
+      }
+      const float4 o = out.accumulate ? old[j] : make_float4(0.f, 0.f, 0.f, 0.f);
+      *reinterpret_cast<float4*>(&out.dst[(int64_t)id * d + c]) =
+          make_float4(fmaf(out.alpha, t.x, o.x), fmaf(out.alpha, t.y, o.y), fmaf(out.alpha, t.z, o.z),
+                      fmaf(out.alpha, t.w, o.w));
+    }
+  }
+}
+
 __global__ __launch_bounds__(NT) void extract_masked_kernel(const int32_t* __restrict__ y, int nseq, int m,
                                                             int T, int vocab, int32_t* __restrict__ rowidx,
                                                             int32_t* __restrict__ labels) {
@@ -688,7 +805,10 @@ int launch_embed_pos_bwd(const float* dh, int nseq, int T, int d, GradOut out, h
 
 int launch_embed_tok_bwd(const int32_t* ids, const float* dh, int R, int d, int vocab, GradOut out,
                          hipStream_t s) {
-  embed_tok_bwd_kernel<<<R, NT, 0, s>>>(ids, dh, R, d, vocab, out);
+  if (R <= 0 || d <= 0 || d > 1024 || (int64_t)R > 32 * (int64_t)MAX_TOK_WORDS) return VF_EINVAL;
+  const bool vec4 = (d & 3) == 0 && ((reinterpret_cast<uintptr_t>(dh) | reinterpret_cast<uintptr_t>(out.dst)) & 15) == 0;
+  if (vec4) embed_tok_bwd4_kernel<<<R, NT, 0, s>>>(ids, dh, R, d, vocab, out);
+  else embed_tok_bwd_kernel<<<R, NT, 0, s>>>(ids, dh, R, d, vocab, out);
   VF_LAUNCH_CHECK();
   return VF_OK;
 }

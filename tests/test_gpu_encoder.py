@@ -21,7 +21,7 @@ def _case(name, jitter=0.1):
 
 @pytest.mark.parametrize("flags", [NO_GRAPH, 0, FUSED])
 @pytest.mark.parametrize("name", ["enc_tiny_f32", "enc_small_f32", "enc_small_bf16", "enc_mid_bf16", "enc_vocab_f32",
-                                  "enc_vocab_bf16"])
+                                  "enc_vocab_bf16", "enc_odd_f32"])
 def test_encoder_step_matches_oracle(name, flags):
     print(f"case {name} flags={flags}", flush=True)
     wl, theta, x, y = _case(name)

@@ -127,6 +127,9 @@ WORKLOADS: Dict[str, Workload] = {
                          optimizer="adam", lr=1e-4),
     "enc_small_f32": _enc("enc_small_f32", 2, 128, 2, 264, 32, 1003, [4, 2, 3], "f32",
                           optimizer="adam", lr=1e-4),
+    # widths that are not multiples of 4: the kernels' scalar paths
+    "enc_odd_f32": _enc("enc_odd_f32", 1, 66, 2, 70, 8, 37, [2, 1, 1], "f32",
+                        optimizer="adam", lr=1e-3),
     # vocabularies beyond 1024 entries, odd, so the logits' rows end inside a pair of columns
     "enc_vocab_f32": _enc("enc_vocab_f32", 1, 64, 2, 136, 16, 4099, [2, 1, 3], "f32",
                           optimizer="adam", lr=1e-3),
