@@ -21,7 +21,7 @@ def _case(name, jitter=0.1):
 
 @pytest.mark.parametrize("flags", [NO_GRAPH, 0, FUSED])
 @pytest.mark.parametrize("name", ["enc_tiny_f32", "enc_small_f32", "enc_small_bf16", "enc_mid_bf16", "enc_vocab_f32",
-                                  "enc_vocab_bf16", "enc_odd_f32"])
+                                  "enc_vocab_bf16", "enc_odd_f32", "enc_wide_bf16"])
 def test_encoder_step_matches_oracle(name, flags):
     print(f"case {name} flags={flags}", flush=True)
     wl, theta, x, y = _case(name)
@@ -44,7 +44,7 @@ OVERLAP = 4
 
 
 @pytest.mark.parametrize("name,sizes", [("enc_small_bf16", None), ("enc_small_bf16", [2, 2, 1, 3, 1]),
-                                        ("enc_mid_bf16", [1, 1, 1, 1, 1])])
+                                        ("enc_mid_bf16", [1, 1, 1, 1, 1]), ("enc_wide_bf16", None)])
 def test_encoder_two_streams_agree_bitwise(name, sizes):
     """Forward passes on one stream, backward passes on the other (two sets of what passes from a
     node's forward to its backward part), staged and fused, replayed and launched one by one,

@@ -127,6 +127,10 @@ WORKLOADS: Dict[str, Workload] = {
                          optimizer="adam", lr=1e-4),
     "enc_small_f32": _enc("enc_small_f32", 2, 128, 2, 264, 32, 1003, [4, 2, 3], "f32",
                           optimizer="adam", lr=1e-4),
+    # nodes of 1024 and 1088 token rows, feed-forward width 1024: products on the 128 x 128 tiles, the
+    # second node ending inside a tile
+    "enc_wide_bf16": _enc("enc_wide_bf16", 1, 512, 8, 1024, 64, 1003, [16, 17], "bf16",
+                          optimizer="adam", lr=1e-4),
     # widths that are not multiples of 4: the kernels' scalar paths
     "enc_odd_f32": _enc("enc_odd_f32", 1, 66, 2, 70, 8, 37, [2, 1, 1], "f32",
                         optimizer="adam", lr=1e-3),
