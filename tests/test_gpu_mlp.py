@@ -21,7 +21,7 @@ def _case(name, jitter=0.1):
 
 @pytest.mark.parametrize("flags", [NO_GRAPH, 0, FUSED | NO_GRAPH, FUSED])
 @pytest.mark.parametrize("name", ["C1", "mlp_small_f32", "mlp_small_bn_f32", "mlp_mid_bf16", "mlp_mid_bn_bf16",
-                                  "mlp_big_node_bf16"])
+                                  "mlp_big_node_bf16", "mlp_classes_f32"])
 def test_mlp_step_matches_oracle(name, flags):
     print(f"case {name} flags={flags}", flush=True)
     wl, theta, x, y = _case(name)

@@ -113,6 +113,9 @@ WORKLOADS: Dict[str, Workload] = {
                           lr=0.1),
     "mlp_small_bn_f32": _mlp("mlp_small_bn_f32", [200, 136, 72, 10], True, [16, 7, 2, 23], "f32",
                              lr=0.1),
+    # more than 1024 classes, an odd number of them: the loss kernel that keeps a row in registers,
+    # writing the reduced logits to a buffer of their own
+    "mlp_classes_f32": _mlp("mlp_classes_f32", [40, 48, 2051], False, [5, 3, 1, 7], "f32", lr=0.1),
     "mlp_mid_bn_bf16": _mlp("mlp_mid_bn_bf16", [256, 520, 392, 1000], True,
                             [48, 16, 128, 40, 8], "bf16"),
     "mlp_mid_bf16": _mlp("mlp_mid_bf16", [256, 520, 392, 1000], False,
