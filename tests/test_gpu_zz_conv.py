@@ -1,5 +1,7 @@
 """GPU parity: the convolutional workload family (a residual network of 3x3 convolutions with
-per-node BatchNorm) through the C ABI against the CPU oracle."""
+per-node BatchNorm) through the C ABI against the CPU oracle.  (The file name sorts behind the
+tests of the MLP and encoder paths, so a run that stops at the first failure has been through
+those first.)"""
 import numpy as np
 import pytest
 
