@@ -507,12 +507,12 @@ __global__ __launch_bounds__(NT) void layernorm_bwd4_kernel(const float* __restr
 
 // out_g[c] = sum over chunks of partial[0][chunk][c]; out_b likewise from partial[1].
 // 16 columns per workgroup, 16 chunk lanes (lane q adds chunks q, q+16, ...), combined in lane order.
-__global__ __launch_bounds__(NT) void layernorm_param_finish_kernel(const float* __restrict__ partial,
-                                                                    int64_t pstride, int nchunk, int d,
-                                                                    GradOut gout_g, GradOut gout_b) {
+__device__ __forceinline__ void layernorm_param_finish_body(const float* __restrict__ partial, int64_t pstride,
+                                                            int nchunk, int d, GradOut gout_g, GradOut gout_b,
+                                                            int wg) {
   __shared__ float red[2][16][17];
   const int tx = threadIdx.x & 15, q = threadIdx.x >> 4;
-  const int c = blockIdx.x * 16 + tx;
+  const int c = wg * 16 + tx;
   float a = 0.f, b = 0.f;
   if (c < d)
     for (int k = q; k < nchunk; k += 16) { a += partial[(int64_t)k * d + c]; b += partial[pstride + (int64_t)k * d + c]; }
@@ -526,6 +526,12 @@ __global__ __launch_bounds__(NT) void layernorm_param_finish_kernel(const float*
     grad_store(gout_g, c, sa);
     grad_store(gout_b, c, sb);
   }
+}
+
+__global__ __launch_bounds__(NT) void layernorm_param_finish_kernel(const float* __restrict__ partial,
+                                                                    int64_t pstride, int nchunk, int d,
+                                                                    GradOut gout_g, GradOut gout_b) {
+  layernorm_param_finish_body(partial, pstride, nchunk, d, gout_g, gout_b, blockIdx.x);
 }
 
 // Column sums over many rows in two steps: partial sums per row chunk, then the chunks in order.
@@ -559,17 +565,37 @@ __global__ __launch_bounds__(NT) void colsum_partial_kernel(const T* __restrict_
 }
 
 // 64 columns per workgroup, 4 chunk lanes (lane q adds chunks q, q+4, ...), combined in lane order.
-__global__ __launch_bounds__(NT) void colsum_finish_kernel(const float* __restrict__ partial, int nchunk, int C,
-                                                           GradOut out) {
+__device__ __forceinline__ void colsum_finish_body(const float* __restrict__ partial, int nchunk, int C,
+                                                   GradOut out, int wg) {
   __shared__ float red[4][64];
   const int tx = threadIdx.x & 63, q = threadIdx.x >> 6;
-  const int c = blockIdx.x * 64 + tx;
+  const int c = wg * 64 + tx;
   float a = 0.f;
   if (c < C)
     for (int k = q; k < nchunk; k += 4) a += partial[(int64_t)k * C + c];
   red[q][tx] = a;
   __syncthreads();
   if (q == 0 && c < C) grad_store(out, c, (red[0][tx] + red[1][tx]) + (red[2][tx] + red[3][tx]));
+}
+__global__ __launch_bounds__(NT) void colsum_finish_kernel(const float* __restrict__ partial, int nchunk, int C,
+                                                           GradOut out) {
+  colsum_finish_body(partial, nchunk, C, out, blockIdx.x);
+}
+
+// Several finish steps in one launch: workgroup w belongs to the job whose range of workgroups
+// holds it (wg_end = running totals) and does what that job's own kernel would do.
+struct FinishArgs {
+  FinishJob job[kFinishJobs];
+  int wg_end[kFinishJobs];
+  int count;
+};
+__global__ __launch_bounds__(NT) void finish_jobs_kernel(FinishArgs fa) {
+  int j = 0;
+  while (j < fa.count - 1 && (int)blockIdx.x >= fa.wg_end[j]) ++j;
+  const int wg = blockIdx.x - (j ? fa.wg_end[j - 1] : 0);
+  const FinishJob& J = fa.job[j];
+  if (J.kind == 0) colsum_finish_body(J.partial, J.nchunk, J.C, J.a, wg);
+  else layernorm_param_finish_body(J.partial, J.pstride, J.nchunk, J.C, J.a, J.b, wg);
 }
 
 // One pass over a gradient matrix dy [R, C] that feeds a Linear layer's backward pass, 64 x 64
@@ -839,13 +865,18 @@ int launch_layernorm_bwd(const float* dyp, int nsplit, int64_t slab, int64_t ldd
                          int64_t ldx, const int32_t* row_map, int R, int d, const float* gamma,
                          int round_params, const float* mean, const float* rstd, const float* dres,
                          float* dx, int64_t lddx, float* scratch, GradOut gout_g, GradOut gout_b,
-                         hipStream_t s) {
+                         hipStream_t s, FinishList* defer) {
   if (R <= 0 || d <= 0 || nsplit < 1 || d > 64 * LN_JMAX || !scratch) return VF_EINVAL;
   // about one workgroup per compute unit: fewer row chunks for the finish kernel to add up
   static const int ln_wgs = std::getenv("VF_LN_WGS") ? std::atoi(std::getenv("VF_LN_WGS")) : 256;
   const int rows_per_wg = std::max(std::max(WAVES, (R + kLnChunks - 1) / kLnChunks), (R + ln_wgs - 1) / ln_wgs);
   const int nchunk = (R + rows_per_wg - 1) / rows_per_wg;
-  const int64_t pstride = (int64_t)kLnChunks * d;
+  int64_t pstride = (int64_t)kLnChunks * d;
+  float* later = defer ? defer->take((size_t)2 * nchunk * d) : nullptr;
+  if (later) {
+    scratch = later;
+    pstride = (int64_t)nchunk * d;
+  }
   const size_t lds = (size_t)2 * WAVES * d * sizeof(float);
   const bool vec4 = (d & 3) == 0 && (lddy & 3) == 0 && (ldx & 3) == 0 && (lddx & 3) == 0 && (slab & 3) == 0 &&
                     ((reinterpret_cast<uintptr_t>(dyp) | reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(dx) |
@@ -859,22 +890,50 @@ int launch_layernorm_bwd(const float* dyp, int nsplit, int64_t slab, int64_t ldd
                                                  round_params, mean, rstd, dres, dx, lddx, rows_per_wg,
                                                  scratch, pstride);
   VF_LAUNCH_CHECK();
+  if (later) {
+    defer->job[defer->count++] = FinishJob{scratch, pstride, nchunk, d, 1, gout_g, gout_b};
+    return VF_OK;
+  }
   layernorm_param_finish_kernel<<<(d + 15) / 16, NT, 0, s>>>(scratch, pstride, nchunk, d, gout_g, gout_b);
   VF_LAUNCH_CHECK();
   return VF_OK;
 }
 
+int launch_finish_jobs(FinishList& list, hipStream_t s) {
+  if (list.count == 0) return VF_OK;
+  FinishArgs fa;
+  int total = 0;
+  for (int j = 0; j < list.count; ++j) {
+    fa.job[j] = list.job[j];
+    total += list.job[j].kind == 0 ? (list.job[j].C + 63) / 64 : (list.job[j].C + 15) / 16;
+    fa.wg_end[j] = total;
+  }
+  for (int j = list.count; j < kFinishJobs; ++j) { fa.job[j] = list.job[0]; fa.wg_end[j] = total; }
+  fa.count = list.count;
+  list.count = 0;
+  list.used = 0;       // launches that follow on this stream may take the slices again
+  finish_jobs_kernel<<<total, NT, 0, s>>>(fa);
+  VF_LAUNCH_CHECK();
+  return VF_OK;
+}
+
 int launch_colsum_rows(const void* x, int64_t ld, int x_is_bf16, int R, int C, float* scratch, GradOut out,
-                       hipStream_t s) {
+                       hipStream_t s, FinishList* defer) {
   if (R <= 0 || C <= 0 || !scratch) return VF_EINVAL;
   const int rows_per_chunk = std::max(32, (R + kReduceChunks - 1) / kReduceChunks);
   const int nchunk = (R + rows_per_chunk - 1) / rows_per_chunk;
+  float* later = defer ? defer->take((size_t)nchunk * C) : nullptr;
+  if (later) scratch = later;
   dim3 grid((C + 31) / 32, nchunk);
   if (x_is_bf16)
     colsum_partial_kernel<bf16_t><<<grid, NT, 0, s>>>(static_cast<const bf16_t*>(x), ld, R, C, rows_per_chunk, scratch);
   else
     colsum_partial_kernel<float><<<grid, NT, 0, s>>>(static_cast<const float*>(x), ld, R, C, rows_per_chunk, scratch);
   VF_LAUNCH_CHECK();
+  if (later) {
+    defer->job[defer->count++] = FinishJob{scratch, 0, nchunk, C, 0, out, out};
+    return VF_OK;
+  }
   colsum_finish_kernel<<<(C + 63) / 64, NT, 0, s>>>(scratch, nchunk, C, out);
   VF_LAUNCH_CHECK();
   return VF_OK;
@@ -887,18 +946,24 @@ bool dy_prepare_fits(int is_f32, int64_t ldi, int64_t ldn, int64_t ldt, int R, i
 }
 
 int launch_dy_prepare(const void* dy, int dy_is_f32, int64_t ldi, int R, int C, bf16_t* nat, int64_t ldn,
-                      bf16_t* tr, int64_t ldt, float* scratch, GradOut out, hipStream_t s) {
+                      bf16_t* tr, int64_t ldt, float* scratch, GradOut out, hipStream_t s, FinishList* defer) {
   if (!dy || !tr || !scratch || (dy_is_f32 && !nat)) return VF_EINVAL;
   if (!dy_prepare_fits(dy_is_f32, ldi, ldn, ldt, R, C)) return VF_EINVAL;
   const uintptr_t bits = reinterpret_cast<uintptr_t>(dy) | reinterpret_cast<uintptr_t>(tr) |
                          (dy_is_f32 ? reinterpret_cast<uintptr_t>(nat) : 0);
   if (bits & 15) return VF_EINVAL;
   dim3 grid((C + 63) / 64, (R + 63) / 64);
+  float* later = defer ? defer->take((size_t)grid.y * C) : nullptr;
+  if (later) scratch = later;
   if (dy_is_f32)
     dy_f32_prepare_kernel<<<grid, NT, 0, s>>>(static_cast<const float*>(dy), ldi, nat, ldn, tr, ldt, scratch, R, C);
   else
     dy_bf16_prepare_kernel<<<grid, NT, 0, s>>>(static_cast<const bf16_t*>(dy), ldi, tr, ldt, scratch, R, C);
   VF_LAUNCH_CHECK();
+  if (later) {
+    defer->job[defer->count++] = FinishJob{scratch, 0, (int)grid.y, C, 0, out, out};
+    return VF_OK;
+  }
   colsum_finish_kernel<<<(C + 63) / 64, NT, 0, s>>>(scratch, (int)grid.y, C, out);
   VF_LAUNCH_CHECK();
   return VF_OK;

@@ -130,6 +130,15 @@ class Encoder final : public Model {
     act(&dqkv_, R * 3 * d_);
     a.request(&drows_, (size_t)out_split_max_ * Rm * d_);
     a.request(&red_, std::max((size_t)kReduceChunks * std::max(std::max(V_, 3 * d_), f_), (size_t)2 * kLnChunks * d_));
+    // room for one node's put-off finish steps (bias and LayerNorm-parameter gradients): the head's
+    // column sums, 2 LayerNorms per block + 1, four Linear layers per block
+    {
+      const size_t ln_chunks = std::min<size_t>(kLnChunks, (size_t)(maxR_ + 3) / 4);
+      const size_t nl = blocks_.size();
+      fin_.cap = (size_t)kReduceChunks * V_ + (2 * nl + 1) * 2 * ln_chunks * d_ +
+                 nl * (size_t)((maxR_ + 63) / 64) * (size_t)(6 * d_ + f_) + 4 * kFinishJobs;
+      a.request(&fin_.scratch, fin_.cap);
+    }
     if (bf16_) {
       act(&cast_, R * d_);
       const size_t maxdim = (size_t)std::max(std::max(d_, f_), 3 * d_);
@@ -243,7 +252,7 @@ class Encoder final : public Model {
     (void)heads;
 
     // ---- backward: output head -----------------------------------------------------------
-    VF_KS(c, st, "colsum", launch_colsum_rows(H.dlogits, ldV_, bf16_, Rm, V_, red_, c.gout(out_.b_off, w, i), st));
+    VF_KS(c, st, "colsum", launch_colsum_rows(H.dlogits, ldV_, bf16_, Rm, V_, red_, c.gout(out_.b_off, w, i), st, &fin_));
     const bool defer = side_beside_forward(c);
     sA_ = tA_; sB_ = tB_;
     VF_TRY(lin_bwd_w(c, "gemm_head_wgrad", out_, H.rows, d_, H.dlogits, ldV_, Rm, c.gout(out_.w_off, w, i)));
@@ -253,7 +262,7 @@ class Encoder final : public Model {
     VF_KS(c, st, "fill", launch_fill_f32(dh_buf_, 0.f, (int64_t)R * d_, st));
     VF_KS(c, st, "layernorm_bwd", launch_layernorm_bwd(drows_, osplit, oslab, d_, H.hlast, d_, H.rowidx, Rm, d_,
                                                   P + lnf_g_, bf16_, H.meanf, H.rstdf, nullptr, dh_buf_, d_, red_,
-                                                  c.gout(lnf_g_, w, i), c.gout(lnf_b_, w, i), st));
+                                                  c.gout(lnf_g_, w, i), c.gout(lnf_b_, w, i), st, &fin_));
 
     // ---- backward: blocks -------------------------------------------------------------------
     for (int l = nl - 1; l >= 0; --l) {
@@ -272,7 +281,7 @@ class Encoder final : public Model {
       VF_TRY(lin_bwd_x(c, "gemm_dgrad", B.w1, P, du_, f_, R, tmp32_, d_, nullptr));
       VF_KS(c, st, "layernorm_bwd", launch_layernorm_bwd(tmp32_, 1, 0, d_, X.hmid, d_, nullptr, R, d_, P + B.ln2_g,
                                                     bf16_, X.mean2, X.rstd2, dh_buf_, dmid_, d_, red_,
-                                                    c.gout(B.ln2_g, w, i), c.gout(B.ln2_b, w, i), st));
+                                                    c.gout(B.ln2_g, w, i), c.gout(B.ln2_b, w, i), st, &fin_));
       // attention
       const void* dmid_op = dmid_;
       VF_TRY(prepare_dy(c, dmid_, true, d_, R, d_, c.gout(B.o.b_off, w, i), defer ? X.dyT[2] : nullptr, &dmid_op, &dyT));
@@ -300,13 +309,15 @@ class Encoder final : public Model {
       VF_TRY(lin_bwd_x(c, "gemm_dgrad", B.qkv, P, dqkv_, 3 * d_, R, tmp32_, d_, nullptr));
       VF_KS(c, st, "layernorm_bwd", launch_layernorm_bwd(tmp32_, 1, 0, d_, X.hin, d_, nullptr, R, d_, P + B.ln1_g,
                                                     bf16_, X.mean1, X.rstd1, dmid_, dh_buf_, d_, red_,
-                                                    c.gout(B.ln1_g, w, i), c.gout(B.ln1_b, w, i), st));
+                                                    c.gout(B.ln1_g, w, i), c.gout(B.ln1_b, w, i), st, &fin_));
     }
     // ---- backward: embeddings ----------------------------------------------------------------
     VF_KS(c, st, "embed_bwd", launch_embed_pos_bwd(dh_buf_, b, T_, d_, c.gout(pos_off_, w, i), st));
     GradOut gt = c.gout(tok_off_, w, i);
     if (!c.fused || i == 0) VF_KS(c, st, "fill", launch_fill_f32(gt.dst, 0.f, (int64_t)V_ * d_, st));
     VF_KS(c, st, "embed_bwd", launch_embed_tok_bwd(ids, dh_buf_, R, d_, V_, gt, st));
+    // the put-off finish steps of this node's bias and LayerNorm-parameter gradients, one launch
+    VF_KS(c, st, "grad_finish", launch_finish_jobs(fin_, st));
     return VF_OK;
   }
 
@@ -368,7 +379,7 @@ class Encoder final : public Model {
     if (bf16_ && dy_prepare_fits(dy_is_f32, lddy, lddy, ldr, R, C)) {
       // `keep`: where the transposed copy goes when the weight gradient is taken later
       VF_KS(c, stream_, "dy_prepare", launch_dy_prepare(dy, dy_is_f32, lddy, R, C, static_cast<bf16_t*>(cast_), lddy,
-                                              keep ? keep : sB_, ldr, red_, gb, st));
+                                              keep ? keep : sB_, ldr, red_, gb, st, &fin_));
       if (dy_is_f32) *op = cast_;
       *transposed = true;
       return VF_OK;
@@ -377,7 +388,7 @@ class Encoder final : public Model {
       VF_KS(c, stream_, "cast", launch_cast_bf16(static_cast<const float*>(dy), lddy, static_cast<bf16_t*>(cast_), lddy, R, C, st));
       *op = cast_;
     }
-    VF_KS(c, stream_, "colsum", launch_colsum_rows(dy, lddy, dy_is_f32 ? 0 : bf16_, R, C, red_, gb, st));
+    VF_KS(c, stream_, "colsum", launch_colsum_rows(dy, lddy, dy_is_f32 ? 0 : bf16_, R, C, red_, gb, st, &fin_));
     return VF_OK;
   }
 
@@ -467,6 +478,7 @@ class Encoder final : public Model {
   void *du_ = nullptr, *dqkv_ = nullptr, *cast_ = nullptr;
   float* drows_ = nullptr;
   float* red_ = nullptr;                // scratch of the row-chunked reductions
+  FinishList fin_;                      // their finish steps of one node's backward pass, run as one launch
   bf16_t *tA_ = nullptr, *tB_ = nullptr;
   bf16_t *tA2_ = nullptr, *tB2_ = nullptr;   // the same scratch for weight gradients taken beside a backward part
   bf16_t *sA_ = nullptr, *sB_ = nullptr;     // the scratch pair of the part being enqueued

@@ -282,6 +282,34 @@ int launch_layernorm_fwd(const float* x, int64_t ldx, const int32_t* row_map, in
 // LayerNorm backward one of 2 * kLnChunks * d floats.
 constexpr int kReduceChunks = 64;
 constexpr int kLnChunks = 1024;
+// The second, small kernel of a row-chunked reduction (chunk partials of a column added in a
+// fixed order, result through GradOut) can be put off: a launcher that is handed a FinishList and
+// finds room in it writes its partials to a slice of the list's scratch, notes the job and
+// returns; launch_finish_jobs then runs all noted jobs in ONE launch -- each with the arithmetic
+// of the kernel it stands for -- and empties the list.  Everything on one stream; a job's target
+// must not be read before that launch.  A full list (jobs or scratch) makes the launcher finish
+// at once, as without a list.
+struct FinishJob {
+  const float* partial;
+  int64_t pstride;       // LayerNorm parameters: distance from the gamma partials to the beta partials
+  int nchunk, C, kind;   // kind 0: column sums (GradOut a); 1: LayerNorm gamma (a) and beta (b)
+  GradOut a, b;
+};
+constexpr int kFinishJobs = 32;
+struct FinishList {
+  FinishJob job[kFinishJobs];
+  int count = 0;
+  float* scratch = nullptr;
+  size_t cap = 0, used = 0;          // floats
+  float* take(size_t n) {
+    if (!scratch || count >= kFinishJobs || used + n > cap) return nullptr;
+    float* p = scratch + used;
+    used += (n + 3) & ~(size_t)3;    // slices stay 16-byte aligned
+    return p;
+  }
+};
+int launch_finish_jobs(FinishList& list, hipStream_t s);
+
 // dx[orow] = LNbwd(sum of dy slabs)[r] (+ dres[orow]),  orow = row_map ? row_map[r] : r; also
 // dgamma[c] = sum_r dy[r,c]*xhat[r,c] and dbeta[c] = sum_r dy[r,c] through GradOut (row chunks
 // added in order).  d <= 1024.  scratch: 2 * kLnChunks * d floats.
@@ -289,11 +317,11 @@ int launch_layernorm_bwd(const float* dyp, int nsplit, int64_t slab, int64_t ldd
                          int64_t ldx, const int32_t* row_map, int R, int d, const float* gamma,
                          int round_params, const float* mean, const float* rstd, const float* dres,
                          float* dx, int64_t lddx, float* scratch, GradOut gout_g, GradOut gout_b,
-                         hipStream_t s);
+                         hipStream_t s, FinishList* defer = nullptr);
 // out[c] = sum_r x[r*ld + c] for many rows: partial sums per row chunk, then the chunks in order.
 // scratch: kReduceChunks * C floats.
 int launch_colsum_rows(const void* x, int64_t ld, int x_is_bf16, int R, int C, float* scratch, GradOut out,
-                       hipStream_t s);
+                       hipStream_t s, FinishList* defer = nullptr);
 // The gradient dy [R, C] at the output of a Linear layer, prepared for that layer's backward pass
 // in one pass: transposed bf16 copy tr [C, ldt], (fp32 dy) bf16 copy nat [R, ldn], and the column
 // sums (the bias gradient) through GradOut, 64-row tiles added in order.  dy_prepare_fits says
@@ -301,7 +329,8 @@ int launch_colsum_rows(const void* x, int64_t ld, int x_is_bf16, int R, int C, f
 // tiles); bases 16-byte aligned; scratch: kReduceChunks * C floats.
 bool dy_prepare_fits(int dy_is_f32, int64_t ldi, int64_t ldn, int64_t ldt, int R, int C);
 int launch_dy_prepare(const void* dy, int dy_is_f32, int64_t ldi, int R, int C, bf16_t* nat, int64_t ldn,
-                      bf16_t* tr, int64_t ldt, float* scratch, GradOut out, hipStream_t s);
+                      bf16_t* tr, int64_t ldt, float* scratch, GradOut out, hipStream_t s,
+                      FinishList* defer = nullptr);
 // exact GELU: g = 0.5 u (1 + erf(u / sqrt 2))
 int launch_gelu_fwd(const void* u, void* g, int is_bf16, int64_t n, hipStream_t s);
 // du = dg * (Phi(u) + u phi(u));  dg fp32, u and du T
