@@ -40,10 +40,10 @@ __global__ __launch_bounds__(256) void transpose_kernel(const TIN* __restrict__ 
 // always valid addresses and come first, so both of a thread's loads are in flight together.
 // Requires C % 8 == 0, ldi % 8 == 0, ldo % 8 == 0, 16-byte aligned bases, and output rows that
 // may be written up to R rounded to 8 (the rows past R receive copies of row R-1).
-__global__ __launch_bounds__(256) void transpose64_kernel(const bf16_t* __restrict__ in, int64_t ldi,
-                                                          bf16_t* __restrict__ out, int64_t ldo, int R, int C) {
+__device__ __forceinline__ void transpose64_body(const bf16_t* __restrict__ in, int64_t ldi,
+                                                 bf16_t* __restrict__ out, int64_t ldo, int R, int C, int bx, int by) {
   __shared__ __attribute__((aligned(16))) bf16_t tile[64][64 + 8];
-  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  const int r0 = by * 64, c0 = bx * 64;
   const int v = threadIdx.x & 7, row = threadIdx.x >> 3;     // 8 vectors per row, 32 rows per pass
   u32x4 x[2];
 #pragma unroll
@@ -63,6 +63,17 @@ __global__ __launch_bounds__(256) void transpose64_kernel(const bf16_t* __restri
     if (c0 + col < C && r0 + rb < R)
       *reinterpret_cast<u32x4*>(&out[(int64_t)(c0 + col) * ldo + r0 + rb]) = o;
   }
+}
+
+__global__ __launch_bounds__(256) void transpose64_kernel(const bf16_t* __restrict__ in, int64_t ldi,
+                                                          bf16_t* __restrict__ out, int64_t ldo, int R, int C) {
+  transpose64_body(in, ldi, out, ldo, R, C, blockIdx.x, blockIdx.y);
+}
+// Several matrices of R rows in one launch: blockIdx.x runs over the column tiles of all of them.
+__global__ __launch_bounds__(256) void transpose64_jobs_kernel(TransposeJobs tj) {
+  int j = 0, first = 0;
+  while (j < tj.count - 1 && (int)blockIdx.x >= first + (tj.C[j] + 63) / 64) { first += (tj.C[j] + 63) / 64; ++j; }
+  transpose64_body(tj.in[j], tj.ldi[j], tj.out[j], tj.ldo, tj.R, tj.C[j], blockIdx.x - first, blockIdx.y);
 }
 
 // fp32 [R, C] -> bf16 natural copy [R, ldn] and transposed copy [C, ldt], 64x64 tiles.
@@ -153,6 +164,21 @@ int launch_transpose_bf16(const bf16_t* in, int64_t ldi, bf16_t* out, int64_t ld
   }
   dim3 grid((C + TS - 1) / TS, (R + TS - 1) / TS);
   transpose_kernel<bf16_t><<<grid, 256, 0, s>>>(in, ldi, out, ldo, nullptr, 0, R, C);
+  VF_LAUNCH_CHECK();
+  return VF_OK;
+}
+
+int launch_transpose_bf16_jobs(const TransposeJobs& tj, hipStream_t s) {
+  if (tj.count < 1 || tj.count > kTransposeJobs || tj.R <= 0 || (tj.ldo & 7) || tj.ldo < ((tj.R + 7) & ~7)) return VF_EINVAL;
+  int tiles = 0;
+  for (int j = 0; j < tj.count; ++j) {
+    if (!tj.in[j] || !tj.out[j] || tj.C[j] <= 0 || (tj.C[j] & 7) || (tj.ldi[j] & 7) || tj.ldi[j] < tj.C[j] ||
+        (reinterpret_cast<uintptr_t>(tj.in[j]) & 15) || (reinterpret_cast<uintptr_t>(tj.out[j]) & 15))
+      return VF_EINVAL;
+    tiles += (tj.C[j] + 63) / 64;
+  }
+  dim3 grid(tiles, (tj.R + 63) / 64);
+  transpose64_jobs_kernel<<<grid, 256, 0, s>>>(tj);
   VF_LAUNCH_CHECK();
   return VF_OK;
 }

@@ -145,7 +145,7 @@ class Encoder final : public Model {
       a.request(&tA_, maxdim * ldR_);
       a.request(&tB_, std::max(maxdim * (size_t)ldR_, (size_t)V_ * round8(maxRm_)));
       if (sets_ == 2) {   // the deferred weight gradients run beside a backward part: scratch of their own
-        a.request(&tA2_, maxdim * ldR_);
+        a.request(&tA2_, (size_t)(f_ + 3 * d_) * ldR_);   // the four transposed inputs of a block side by side
         a.request(&tB2_, std::max(maxdim * (size_t)ldR_, (size_t)V_ * round8(maxRm_)));
       }
       for (Lin* L : lins_) {
@@ -393,18 +393,21 @@ class Encoder final : public Model {
   }
 
   // dW[K, N] = in^T dy through GradOut.  dy_transposed: dy^T is already there, in `dyT` if given,
-  // else in the scratch sB_.
+  // else in the scratch sB_; inT: in^T is already there (row pitch R rounded up to 8).
   int lin_bwd_w(Ctx& c, const char* tag, const Lin& L, const void* in, int64_t ldin, const void* dy,
-                int64_t lddy, int R, GradOut go, bool dy_transposed = false, const bf16_t* dyT = nullptr) {
+                int64_t lddy, int R, GradOut go, bool dy_transposed = false, const bf16_t* dyT = nullptr,
+                const bf16_t* inT = nullptr) {
     Epilogue ep;
     ep.C = go.dst; ep.ldc = L.N; ep.alpha = go.alpha;
     if (go.accumulate) { ep.R = go.dst; ep.ldr = L.N; ep.beta = 1.f; }
     if (bf16_) {
       const int64_t ldr = round8(R);
-      VF_KS(c, stream_, "transpose", launch_transpose_bf16(static_cast<const bf16_t*>(in), ldin, sA_, ldr, R, L.K, stream_));
+      if (!inT)
+        VF_KS(c, stream_, "transpose", launch_transpose_bf16(static_cast<const bf16_t*>(in), ldin, sA_, ldr, R, L.K, stream_));
       if (!dy_transposed)
         VF_KS(c, stream_, "transpose", launch_transpose_bf16(static_cast<const bf16_t*>(dy), lddy, sB_, ldr, R, L.N, stream_));
-      VF_KS(c, stream_, tag, launch_gemm_bf16(sA_, ldr, dy_transposed && dyT ? dyT : sB_, ldr, L.K, L.N, R, 1, 0, ep, stream_));
+      VF_KS(c, stream_, tag, launch_gemm_bf16(inT ? inT : sA_, ldr, dy_transposed && dyT ? dyT : sB_, ldr, L.K, L.N, R, 1, 0, ep,
+                                              stream_));
     } else {
       VF_KS(c, stream_, tag, launch_gemm_f32(static_cast<const float*>(in), 1, ldin, static_cast<const float*>(dy), 1, lddy,
                                    L.K, L.N, R, 1, 0, ep, stream_));
@@ -428,11 +431,31 @@ class Encoder final : public Model {
       const void* ins[4] = {X.g, X.f, X.om, X.a};
       const int64_t ldins[4] = {f_, d_, d_, d_};
       const bool f32dy[4] = {true, false, true, false};
+      // the backward part took a gradient itself when its shapes did not qualify for the one-pass preparation
+      bool mine[4];
+      bool all = true;
+      for (int k = 0; k < 4; ++k) {
+        mine[k] = dy_prepare_fits(f32dy[k], lins[k]->N, lins[k]->N, ldr, R, lins[k]->N);
+        all = all && mine[k];
+      }
+      // all four: their inputs are transposed by one launch, side by side in the scratch
+      const bf16_t* inT[4] = {nullptr, nullptr, nullptr, nullptr};
+      if (all) {
+        TransposeJobs tj{};
+        size_t off = 0;
+        for (int k = 0; k < 4; ++k) {
+          tj.in[k] = static_cast<const bf16_t*>(ins[k]); tj.ldi[k] = ldins[k];
+          tj.out[k] = tA2_ + off; tj.C[k] = lins[k]->K;
+          off += (size_t)lins[k]->K * ldr;
+          inT[k] = tj.out[k];
+        }
+        tj.count = 4; tj.R = R; tj.ldo = ldr;
+        VF_KS(c, st, "transpose", launch_transpose_bf16_jobs(tj, st));
+      }
       for (int k = 0; k < 4; ++k) {
         const Lin& L = *lins[k];
-        // the backward part took this one itself when its shapes did not qualify for the one-pass preparation
-        if (!dy_prepare_fits(f32dy[k], L.N, L.N, ldr, R, L.N)) continue;
-        VF_TRY(lin_bwd_w(c, "gemm_wgrad", L, ins[k], ldins[k], nullptr, 0, R, c.gout(L.w_off, w, i), true, X.dyT[k]));
+        if (!mine[k]) continue;
+        VF_TRY(lin_bwd_w(c, "gemm_wgrad", L, ins[k], ldins[k], nullptr, 0, R, c.gout(L.w_off, w, i), true, X.dyT[k], inT[k]));
       }
     }
     return VF_OK;

@@ -135,6 +135,20 @@ int launch_rowsum_nodes(const NodeList& nl, int64_t ld, int R, float* out, hipSt
 
 // k_elem.hip
 // out[c*ldo + r] = in[r*ldi + c]  for r < R, c < C
+// Up to kTransposeJobs bf16 matrices [R, C_j] (row pitch ldi_j) transposed in one launch into
+// out_j [C_j, ldo]: column counts and pitches multiples of 8, ldo >= R rounded up to 8, bases
+// 16-byte aligned (VF_EINVAL otherwise: the caller transposes one by one).
+constexpr int kTransposeJobs = 4;
+struct TransposeJobs {
+  const bf16_t* in[kTransposeJobs];
+  int64_t ldi[kTransposeJobs];
+  bf16_t* out[kTransposeJobs];
+  int C[kTransposeJobs];
+  int count;
+  int R;
+  int64_t ldo;
+};
+int launch_transpose_bf16_jobs(const TransposeJobs& tj, hipStream_t s);
 int launch_transpose_bf16(const bf16_t* in, int64_t ldi, bf16_t* out, int64_t ldo, int R, int C,
                           hipStream_t s);
 // fp32 [R,C] (ld = C) -> bf16 natural copy [R, ldn] and transposed copy [C, ldt]
