@@ -251,6 +251,7 @@ class Encoder final : public Model {
     const float scale = 1.0f / std::sqrt((float)dh_);
     (void)heads;
 
+    fin_.count = 0; fin_.used = 0;   // nothing is left over from a pass that ended in an error
     // ---- backward: output head -----------------------------------------------------------
     VF_KS(c, st, "colsum", launch_colsum_rows(H.dlogits, ldV_, bf16_, Rm, V_, red_, c.gout(out_.b_off, w, i), st, &fin_));
     const bool defer = side_beside_forward(c);
