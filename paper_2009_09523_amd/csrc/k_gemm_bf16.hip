@@ -11,6 +11,7 @@
 #include <algorithm>
 #include <cstdlib>
 #include <cstring>
+#include <type_traits>
 
 #include "vf_device.h"
 
@@ -221,6 +222,25 @@ template <int N>
 __device__ __forceinline__ void wait_loads_but() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
+// The same wait for loads whose destinations are registers (load_vec_async).  The compiler takes
+// the output of the load statement as defined at once, and a statement that only clobbers
+// memory orders memory accesses, not register arithmetic: a v_and of the edge masking below was
+// scheduled ahead of the bare wait and read its register before the data had landed (rare wrong
+// products whenever the contraction length was no multiple of 8 and the operand was not yet in
+// a near cache).  So the wait takes the stage's registers as read-write operands: everything
+// derived from them depends on the wait itself.
+template <int N>
+__device__ __forceinline__ void wait_loads_into(u32x4 (&r)[1]) {
+  asm volatile("s_waitcnt vmcnt(%1)" : "+v"(r[0]) : "n"(N) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_loads_into(u32x4 (&r)[2]) {
+  asm volatile("s_waitcnt vmcnt(%2)" : "+v"(r[0]), "+v"(r[1]) : "n"(N) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_loads_into(u32x4 (&r)[4]) {
+  asm volatile("s_waitcnt vmcnt(%4)" : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]) : "n"(N) : "memory");
+}
 
 __device__ __forceinline__ u32x4 mask_vec(u32x4 v, bool row_ok, int k, int kend) {
   const int valid = row_ok ? kend - k : 0;
@@ -327,18 +347,32 @@ __global__ __launch_bounds__(NT) void gemm_bf16_pipe_kernel(const bf16_t* __rest
     // data is never used, they only keep the count of outstanding loads uniform)
 #pragma unroll
     for (int s = 0; s < NS; ++s) issue(s, min(s, nstage - 1));
-    for (int base = 0; base < nstage; base += NS) {
-#pragma unroll
-      for (int s = 0; s < NS; ++s) {
-        const int it = base + s;
-        if (it < nstage) {
-          // outstanding: stages it .. it+NS-1 (NS of them); stage `it` is the oldest
-          wait_loads_but<(NS - 1) * VPS>();
-          to_lds(s, it, it & 1);
-          // refill the slot; past the end this re-reads the last stage's lines (cache hits)
-          issue(s, min(it + NS, nstage - 1));
-          __syncthreads();
-          compute(it & 1);
+    // outstanding on entry to a stage: stages it .. it+NS-1 (NS of them); stage `it` is the oldest
+    auto stage = [&](auto slot_c, int it) {
+      constexpr int s = decltype(slot_c)::value;
+      wait_loads_into<(NS - 1) * VPS>(ra[s]);
+      wait_loads_into<(NS - 1) * VPS>(rb[s]);
+      to_lds(s, it, it & 1);
+      // refill the slot; past the end this re-reads the last stage's lines (cache hits)
+      issue(s, min(it + NS, nstage - 1));
+      __syncthreads();
+      compute(it & 1);
+    };
+    // whole rounds of NS stages without a branch inside, then the last stages one inside the
+    // other: every path through the ring in the compiled code is one that can be taken
+    int base = 0;
+    for (; base + NS <= nstage; base += NS) {
+      stage(std::integral_constant<int, 0>{}, base);
+      stage(std::integral_constant<int, 1>{}, base + 1);
+      if constexpr (NS > 2) stage(std::integral_constant<int, 2>{}, base + 2);
+      if constexpr (NS > 3) stage(std::integral_constant<int, 3>{}, base + 3);
+    }
+    if (base < nstage) {
+      stage(std::integral_constant<int, 0>{}, base);
+      if (base + 1 < nstage) {
+        stage(std::integral_constant<int, 1>{}, base + 1);
+        if constexpr (NS > 3) {
+          if (base + 2 < nstage) stage(std::integral_constant<int, 2>{}, base + 2);
         }
       }
     }

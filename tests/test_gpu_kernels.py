@@ -137,3 +137,30 @@ def test_gemm_split_contraction_slabs_sum_to_product(M, N, K, nsplit):
     want = A.double().cpu().numpy() @ B.double().cpu().numpy().T
     assert np.all(got[:, :, N:] == 3.0)
     assert np.max(np.abs(got[:, :, :N].sum(axis=0) - want)) <= 1e-5 * np.sqrt(K) * np.max(np.abs(want))
+
+
+@pytest.mark.parametrize("M,N,K", [(8, 32, 10), (128, 64, 10), (3, 64, 10), (64, 10, 127), (40, 24, 75)])
+def test_gemm_ragged_contraction_with_cold_operands(M, N, K):
+    """A contraction length that is no multiple of 8 (the last 16-byte vector of a row is masked
+    by element), with the operands pushed out of the caches before every launch: the masking must
+    not depend on when the loads land."""
+    import torch
+    import paper_2009_09523_amd as vf
+    print(f"gemm cold M={M} N={N} K={K}", flush=True)
+    rng = np.random.Generator(np.random.PCG64(M * 11 + N * 5 + K))
+    lda = ((K + 7) // 8) * 8
+    A = torch.from_numpy(rng.standard_normal((M, lda)).astype(np.float32)).to(torch.bfloat16).cuda()
+    B = torch.from_numpy(rng.standard_normal((N, lda)).astype(np.float32)).to(torch.bfloat16).cuda()
+    want = A[:, :K].double().cpu().numpy() @ B[:, :K].double().cpu().numpy().T
+    flush = torch.empty(768 * 1024 * 1024 // 4, device="cuda")        # larger than every cache level
+    first = None
+    for k in range(20):
+        Cd = torch.full((M, N), 5.0, device="cuda")
+        flush.fill_(float(k))
+        vf.vf_gemm(A[:, :K], B[:, :K], Cd, M, N, K)
+        torch.cuda.synchronize()
+        got = Cd.cpu().numpy()
+        assert np.max(np.abs(got - want)) <= 1e-5 * np.sqrt(K) * np.max(np.abs(want)), k
+        if first is None:
+            first = got
+        assert got.tobytes() == first.tobytes(), k
