@@ -258,6 +258,26 @@ int vf_gemm(int32_t dtype, const void* A, int64_t lda, const void* B, int64_t ld
             int64_t ldc, int32_t M, int32_t N, int32_t K, float alpha, int32_t accumulate,
             int32_t nsplit, void* stream);
 
+/* The sliced contraction of vf_gemm for callers that cannot allocate device memory: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Computes
+ *     C[m,n] = alpha * sum_k A[m*lda + k] * B[n*ldb + k]  (+ C[m,n] if accumulate != 0)
+ * for bf16 A, B (device, 16-byte aligned, lda and ldb multiples of 8) and a DENSE fp32 C [M, N]
+ * (device, row pitch N), with the contraction cut into nsplit slices exactly as vf_gemm cuts it;
+ * the slabs of partial products, which vf_gemm hands to its caller, stay in a device array of
+ * VF_NOALLOC_SCRATCH_BYTES that is part of the library's image (every GPU the library runs on
+ * holds it until the process ends) and are added in slab order: C = fma(alpha, slab_0 + slab_1
+ * + ... , accumulate ? C : 0), bit for bit what a caller of vf_gemm gets who adds the slabs in
+ * that order.  The call allocates nothing (no hipMalloc / hipFree, no allocating library
+ * routine); all work is enqueued on `stream`.  VF_EINVAL, with nothing enqueued, if
+ * nsplit * M * N * 4 exceeds VF_NOALLOC_SCRATCH_BYTES or an argument is malformed.
+ * All calls on one GPU share that GPU's array: calls that may overlap in time on one GPU (two
+ * streams, two threads) race; calls on one stream are ordered and safe.  Nothing needs to be
+ * cleared between calls (every slice overwrites its whole slab). */
+#define VF_NOALLOC_SCRATCH_BYTES (32 * 1024 * 1024)
+int vf_gemm_noalloc(const void* A, int64_t lda, const void* B, int64_t ldb, float* C, int32_t M,
+                    int32_t N, int32_t K, float alpha, int32_t accumulate, int32_t nsplit,
+                    void* stream);
+
 /* ---- training state of this device (Section 4.1) ---------------------------------------
  * What a device that joins a job has to receive before it can continue the job's steps: the
  * master parameters, the optimizer state, and the state the passes themselves carry (the

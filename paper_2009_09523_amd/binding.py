@@ -86,6 +86,8 @@ _SIGNATURES = {
                                  C.c_float, C.c_float, C.c_int64, C.c_int64, C.c_void_p]),
     "vf_gemm": (C.c_int, [C.c_int32, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
                           C.c_int32, C.c_int32, C.c_int32, C.c_float, C.c_int32, C.c_int32, C.c_void_p]),
+    "vf_gemm_noalloc": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int32,
+                                  C.c_int32, C.c_int32, C.c_float, C.c_int32, C.c_int32, C.c_void_p]),
     "vf_state_bytes": (C.c_int64, [C.c_void_p]),
     "vf_state_export": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64]),
     "vf_state_import": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64]),
@@ -176,6 +178,20 @@ def vf_gemm(A, B, Cout, M: int, N: int, K: int, alpha: float = 1.0, accumulate: 
     _check(lib().vf_gemm(dtype, _ptr(A), A.stride(0), _ptr(B), B.stride(0), _ptr(Cout), ldc,
                          M, N, K, float(alpha), int(bool(accumulate)), int(nsplit),
                          _stream_handle(stream)), "vf_gemm")
+
+
+VF_NOALLOC_SCRATCH_BYTES = 32 * 1024 * 1024
+
+
+def vf_gemm_noalloc(A, B, Cout, M: int, N: int, K: int, alpha: float = 1.0, accumulate: bool = False,
+                    nsplit: int = 1, stream=None):
+    """Cout[M,N] (fp32, dense) = alpha * A[M,K] B[N,K]^T (+ Cout), contraction in nsplit slices whose
+    partial products stay in the library's static device scratch.  Returns the status code."""
+    import torch
+    assert A.dtype == torch.bfloat16 and B.dtype == torch.bfloat16 and Cout.dtype == torch.float32
+    assert A.stride(-1) == 1 and B.stride(-1) == 1 and Cout.is_contiguous()
+    return lib().vf_gemm_noalloc(_ptr(A), A.stride(0), _ptr(B), B.stride(0), _ptr(Cout), M, N, K,
+                                 float(alpha), int(bool(accumulate)), int(nsplit), _stream_handle(stream))
 
 
 def parse_state(payload: np.ndarray) -> dict:
