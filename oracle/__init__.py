@@ -14,11 +14,15 @@ with the weights of Section 5.2), written in NumPy float64:
   4. one optimizer update with G                        (Section 3.2, step 5).
 
 bf16 workloads are defined as "bf16 weights and activations, fp32 accumulation,
-fp32 master weights": the oracle rounds the fp32 master parameters to bf16
-(round-to-nearest-even) before the passes and rounds every operand of a
-contraction (activations fed to a Linear or an attention product, gradients
-fed to a backward contraction, and the saved FFN pre-activation) to bf16;
-everything else is float64.
+fp32 master weights", their contractions being bf16 products: the oracle rounds
+the fp32 master parameters to bf16 (round-to-nearest-even) before the passes and
+rounds every operand of a contraction (Linear, convolution, attention product;
+forward and backward) to bf16 where it is produced.  Everything else -- what a
+contraction puts out included -- is float64.  Which tensors this rule
+rounds is fixed by this build's reading of that phrase, not by the paper
+("parity unpinned": the float64 pins run without any rounding); a workload whose
+dtype is not bf16 is evaluated without it, which is how tests obtain the
+weights-only-rounded evaluation of the same step.
 
 Pins (tests/test_oracle_*.py): the 6+2 worked example of Section 5.2 with its
 unweighted negative control; partition-invariance of G without BatchNorm;

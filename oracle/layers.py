@@ -11,13 +11,8 @@ from scipy.special import erf
 
 # ---- Linear: y = x W + b --------------------------------------------------------
 
-def linear_fwd(x, W, b=None, accum32=False):
-    """accum32: carry out the product in float32 (a second, equally valid evaluation used
-    only to calibrate how far two correct low-precision implementations can drift apart)."""
-    if accum32:
-        y = (x.astype(np.float32) @ W.astype(np.float32)).astype(np.float64)
-    else:
-        y = x @ W
+def linear_fwd(x, W, b=None):
+    y = x @ W
     if b is not None:
         y = y + b
     return y

@@ -70,24 +70,28 @@ def _flatten(wl, grads):
 
 def _operand(wl):
     """How a tensor enters a contraction.  bf16 workloads are defined with bf16 weights
-    AND activations (fp32 accumulation): every operand of a contraction -- the activation
-    fed to a Linear or to an attention product, and the gradient fed to a backward
-    contraction -- is rounded to bf16; everything between contractions stays float64.
-    This also puts the one discontinuous decision of the MLP, the ReLU mask of the next
-    layer, at the same precision on both sides of a parity check."""
+    AND activations, fp32 accumulation, their contractions (Linear, convolution and
+    attention products; forward, input gradient and weight gradient) being bf16 products:
+    every operand of a contraction -- the activation fed to a Linear or convolution, q, k, v
+    and the probabilities of an attention product, and the gradient fed to a backward
+    contraction -- is a bf16 tensor, rounded to nearest even once, where it is produced.
+    Nothing else is rounded: what a contraction puts out, normalisation statistics, softmax,
+    losses, the residual stream and sums over rows are float64.  This also puts the one
+    discontinuous decision of the MLP, the ReLU mask of the next layer, at the same
+    precision on both sides of a parity check."""
     if wl.dtype == "bf16":
         return lambda a: round_to_bf16(np.asarray(a, dtype=np.float32))
     return lambda a: a
 
 
-def _mlp_node(wl, p, x, y, accum32=False):
+def _mlp_node(wl, p, x, y):
     q = _operand(wl)
     n_lin = len(wl.dims) - 1
     h = np.asarray(x, dtype=np.float64)
     saved = []
     margin = np.inf
     for l in range(n_lin - 1):
-        z = L.linear_fwd(h, p[f"l{l}.W"], None if wl.batchnorm else p[f"l{l}.b"], accum32)
+        z = L.linear_fwd(h, p[f"l{l}.W"], None if wl.batchnorm else p[f"l{l}.b"])
         if wl.batchnorm:
             pre, bn_cache = L.batchnorm_fwd(z, p[f"l{l}.gamma"], p[f"l{l}.beta"], wl.bn_eps)
         else:
@@ -198,12 +202,13 @@ def _encoder_node(wl, p, ids, y):
     LayerNorm, untied output projection on the masked rows, mean cross-entropy
     over the node's n*m masked rows.
 
-    bf16 workloads: every tensor that is stored as an operand of a later
-    contraction or saved as an activation (LayerNorm outputs, q/k/v, attention
-    probabilities and outputs, FFN pre-activation and GELU output, and in the
-    backward pass every gradient handed to a contraction) is rounded to bf16 by
-    `q`; the residual stream, statistics, logits and the gradients between a
-    contraction and the next element-wise step stay float64."""
+    bf16 workloads: the operands of every contraction are rounded to bf16 by `q_`
+    -- forward: the LayerNorm outputs, q/k/v, the attention probabilities, the merged
+    attention output, the GELU output and the gathered final rows; backward: the
+    gradient at every Linear layer's output, the gradient of the attention output
+    and the score gradient.  The FFN pre-activation (a Linear layer's output, read
+    only by the GELU), the logits, the residual stream and the statistics stay
+    float64."""
     q_ = _operand(wl)
     ids = np.asarray(ids, dtype=np.int64)
     y = np.asarray(y, dtype=np.int64)
@@ -221,7 +226,7 @@ def _encoder_node(wl, p, ids, y):
         h_mid = h + L.linear_fwd(om, p[f"l{l}.Wo"], p[f"l{l}.bo"])
         f, c2 = L.layernorm_fwd(h_mid, p[f"l{l}.ln2.gamma"], p[f"l{l}.ln2.beta"], wl.ln_eps)
         f = q_(f)
-        u = q_(L.linear_fwd(f, p[f"l{l}.W1"], p[f"l{l}.b1"]))
+        u = L.linear_fwd(f, p[f"l{l}.W1"], p[f"l{l}.b1"])
         gl = q_(L.gelu_fwd(u))
         h_out = h_mid + L.linear_fwd(gl, p[f"l{l}.W2"], p[f"l{l}.b2"])
         saved.append((a, c1, q, k, v, prob, om, f, c2, u, gl))
@@ -264,15 +269,13 @@ def _encoder_node(wl, p, ids, y):
     return loss, g, np.inf
 
 
-def node_loss_and_grads(wl, compute_params, x_node, y_node, diag=None, accum32=False):
+def node_loss_and_grads(wl, compute_params, x_node, y_node, diag=None):
     """(L_i, flat g_i) for one node given float64 compute parameters (flat).  `diag`, if a
     dict, receives 'relu_margin': the smallest |ReLU input| of the node relative to its
-    layer's rms (inf for models without ReLU).  accum32 (MLP only): the hidden layers'
-    forward products are carried out in float32 -- a second valid evaluation that parity
-    tests of deep bf16 networks use to calibrate their tolerance, never as the reference."""
+    layer's rms (inf for models without ReLU)."""
     p = unflatten(wl, compute_params)
     if wl.kind == "mlp":
-        loss, g, margin, stats = _mlp_node(wl, p, x_node, y_node, accum32)
+        loss, g, margin, stats = _mlp_node(wl, p, x_node, y_node)
     elif wl.kind == "conv":
         loss, g, margin, stats = _conv_node(wl, p, np.asarray(x_node), y_node)
     else:

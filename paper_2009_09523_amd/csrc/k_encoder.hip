@@ -699,70 +699,60 @@ __global__ __launch_bounds__(NT) void dy_bf16_prepare_kernel(const bf16_t* __res
 }
 
 // ---- GELU (exact) ---------------------------------------------------------------------------
-template <typename T>
-__global__ __launch_bounds__(NT) void gelu_fwd_kernel(const T* __restrict__ u, T* __restrict__ g, int64_t n) {
-  int64_t i = (int64_t)blockIdx.x * NT + threadIdx.x;
-  const int64_t stride = (int64_t)gridDim.x * NT;
-  for (; i < n; i += stride) {
-    float v = load_f(&u[i]);
-    store_f(&g[i], 0.5f * v * (1.0f + erff(v * 0.70710678118654752f)));
-  }
-}
-
-// Eight bf16 elements per lane and trip (16-byte accesses); n % 8 == 0, 16-byte aligned.
+// The pre-activation u is what a Linear layer put out: fp32 in every workload (only operands of
+// contractions are bf16).  T is the type of the GELU output (the next Linear layer's operand) and
+// of the gradient du handed to the backward products.
 __device__ __forceinline__ float gelu_f(float v) { return 0.5f * v * (1.0f + erff(v * 0.70710678118654752f)); }
 __device__ __forceinline__ float gelu_df(float v) {
   const float cdf = 0.5f * (1.0f + erff(v * 0.70710678118654752f));
   const float pdf = 0.3989422804014327f * expf(-0.5f * v * v);
   return cdf + v * pdf;
 }
-__global__ __launch_bounds__(NT) void gelu_fwd8_kernel(const uint4* __restrict__ u, uint4* __restrict__ g, int64_t nvec) {
+template <typename T>
+__global__ __launch_bounds__(NT) void gelu_fwd_kernel(const float* __restrict__ u, T* __restrict__ g, int64_t n) {
+  int64_t i = (int64_t)blockIdx.x * NT + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * NT;
+  for (; i < n; i += stride) store_f(&g[i], gelu_f(u[i]));
+}
+
+// Eight elements per lane and trip (16-byte accesses, bf16 out); n % 8 == 0, 16-byte aligned.
+__global__ __launch_bounds__(NT) void gelu_fwd8_kernel(const float4* __restrict__ u, uint4* __restrict__ g, int64_t nvec) {
   int64_t i = (int64_t)blockIdx.x * NT + threadIdx.x;
   const int64_t stride = (int64_t)gridDim.x * NT;
   for (; i < nvec; i += stride) {
-    const uint4 x = u[i];
-    const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+    const float4 u0 = u[2 * i], u1 = u[2 * i + 1];
+    const float v[8] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w};
     uint32_t o[4];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const float lo = gelu_f(bf16_to_f32((bf16_t)(w[e] & 0xffffu)));
-      const float hi = gelu_f(bf16_to_f32((bf16_t)(w[e] >> 16)));
-      o[e] = (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
-    }
+    for (int e = 0; e < 4; ++e)
+      o[e] = (uint32_t)f32_to_bf16(gelu_f(v[2 * e])) | ((uint32_t)f32_to_bf16(gelu_f(v[2 * e + 1])) << 16);
     g[i] = make_uint4(o[0], o[1], o[2], o[3]);
   }
 }
-__global__ __launch_bounds__(NT) void gelu_bwd8_kernel(const float4* __restrict__ dg, const uint4* __restrict__ u,
+__global__ __launch_bounds__(NT) void gelu_bwd8_kernel(const float4* __restrict__ dg, const float4* __restrict__ u,
                                                        uint4* __restrict__ du, int64_t nvec) {
   int64_t i = (int64_t)blockIdx.x * NT + threadIdx.x;
   const int64_t stride = (int64_t)gridDim.x * NT;
   for (; i < nvec; i += stride) {
-    const uint4 x = u[i];
+    const float4 u0 = u[2 * i], u1 = u[2 * i + 1];
     const float4 d0 = dg[2 * i], d1 = dg[2 * i + 1];
-    const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+    const float v[8] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w};
     const float d[8] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
     uint32_t o[4];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const float lo = d[2 * e] * gelu_df(bf16_to_f32((bf16_t)(w[e] & 0xffffu)));
-      const float hi = d[2 * e + 1] * gelu_df(bf16_to_f32((bf16_t)(w[e] >> 16)));
-      o[e] = (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
-    }
+    for (int e = 0; e < 4; ++e)
+      o[e] = (uint32_t)f32_to_bf16(d[2 * e] * gelu_df(v[2 * e])) |
+             ((uint32_t)f32_to_bf16(d[2 * e + 1] * gelu_df(v[2 * e + 1])) << 16);
     du[i] = make_uint4(o[0], o[1], o[2], o[3]);
   }
 }
 
 template <typename T>
-__global__ __launch_bounds__(NT) void gelu_bwd_kernel(const float* __restrict__ dg, const T* __restrict__ u,
+__global__ __launch_bounds__(NT) void gelu_bwd_kernel(const float* __restrict__ dg, const float* __restrict__ u,
                                                       T* __restrict__ du, int64_t n) {
   int64_t i = (int64_t)blockIdx.x * NT + threadIdx.x;
   const int64_t stride = (int64_t)gridDim.x * NT;
-  for (; i < n; i += stride) {
-    float v = load_f(&u[i]);
-    float cdf = 0.5f * (1.0f + erff(v * 0.70710678118654752f));
-    float pdf = 0.3989422804014327f * expf(-0.5f * v * v);
-    store_f(&du[i], dg[i] * (cdf + v * pdf));
-  }
+  for (; i < n; i += stride) store_f(&du[i], dg[i] * gelu_df(u[i]));
 }
 
 // ---- row softmax: one wavefront per row --------------------------------------------------------
@@ -969,34 +959,30 @@ int launch_dy_prepare(const void* dy, int dy_is_f32, int64_t ldi, int R, int C, 
   return VF_OK;
 }
 
-int launch_gelu_fwd(const void* u, void* g, int is_bf16, int64_t n, hipStream_t s) {
+int launch_gelu_fwd(const float* u, void* g, int g_is_bf16, int64_t n, hipStream_t s) {
   if (n <= 0) return VF_OK;
-  if (is_bf16 && (n & 7) == 0 && ((reinterpret_cast<uintptr_t>(u) | reinterpret_cast<uintptr_t>(g)) & 15) == 0) {
-    gelu_fwd8_kernel<<<blocks_for(n / 8), NT, 0, s>>>(static_cast<const uint4*>(u), static_cast<uint4*>(g), n / 8);
+  if (g_is_bf16 && (n & 7) == 0 && ((reinterpret_cast<uintptr_t>(u) | reinterpret_cast<uintptr_t>(g)) & 15) == 0) {
+    gelu_fwd8_kernel<<<blocks_for(n / 8), NT, 0, s>>>(reinterpret_cast<const float4*>(u), static_cast<uint4*>(g), n / 8);
     VF_LAUNCH_CHECK();
     return VF_OK;
   }
-  if (is_bf16) gelu_fwd_kernel<bf16_t><<<blocks_for(n), NT, 0, s>>>(static_cast<const bf16_t*>(u),
-                                                                    static_cast<bf16_t*>(g), n);
-  else         gelu_fwd_kernel<float><<<blocks_for(n), NT, 0, s>>>(static_cast<const float*>(u),
-                                                                   static_cast<float*>(g), n);
+  if (g_is_bf16) gelu_fwd_kernel<bf16_t><<<blocks_for(n), NT, 0, s>>>(u, static_cast<bf16_t*>(g), n);
+  else           gelu_fwd_kernel<float><<<blocks_for(n), NT, 0, s>>>(u, static_cast<float*>(g), n);
   VF_LAUNCH_CHECK();
   return VF_OK;
 }
 
-int launch_gelu_bwd(const float* dg, const void* u, void* du, int is_bf16, int64_t n, hipStream_t s) {
+int launch_gelu_bwd(const float* dg, const float* u, void* du, int du_is_bf16, int64_t n, hipStream_t s) {
   if (n <= 0) return VF_OK;
-  if (is_bf16 && (n & 7) == 0 &&
+  if (du_is_bf16 && (n & 7) == 0 &&
       ((reinterpret_cast<uintptr_t>(u) | reinterpret_cast<uintptr_t>(du) | reinterpret_cast<uintptr_t>(dg)) & 15) == 0) {
-    gelu_bwd8_kernel<<<blocks_for(n / 8), NT, 0, s>>>(reinterpret_cast<const float4*>(dg), static_cast<const uint4*>(u),
+    gelu_bwd8_kernel<<<blocks_for(n / 8), NT, 0, s>>>(reinterpret_cast<const float4*>(dg), reinterpret_cast<const float4*>(u),
                                                       static_cast<uint4*>(du), n / 8);
     VF_LAUNCH_CHECK();
     return VF_OK;
   }
-  if (is_bf16) gelu_bwd_kernel<bf16_t><<<blocks_for(n), NT, 0, s>>>(dg, static_cast<const bf16_t*>(u),
-                                                                    static_cast<bf16_t*>(du), n);
-  else         gelu_bwd_kernel<float><<<blocks_for(n), NT, 0, s>>>(dg, static_cast<const float*>(u),
-                                                                   static_cast<float*>(du), n);
+  if (du_is_bf16) gelu_bwd_kernel<bf16_t><<<blocks_for(n), NT, 0, s>>>(dg, u, static_cast<bf16_t*>(du), n);
+  else            gelu_bwd_kernel<float><<<blocks_for(n), NT, 0, s>>>(dg, u, static_cast<float*>(du), n);
   VF_LAUNCH_CHECK();
   return VF_OK;
 }

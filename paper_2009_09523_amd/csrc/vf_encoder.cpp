@@ -31,7 +31,7 @@ struct BlockActs {
   void* om = nullptr;                   // T [R, d]   attention output, heads merged
   float* hmid = nullptr;                // fp32 [R, d] after the attention residual
   void* f = nullptr;                    // T [R, d]   LN2 output
-  void* u = nullptr;                    // T [R, ffn] FFN pre-activation
+  float* u = nullptr;                   // fp32 [R, ffn] FFN pre-activation (a Linear output: not an operand of a product)
   void* g = nullptr;                    // T [R, ffn] gelu(u)
   // ... and what its backward part leaves for weight gradients taken later (deferred mode):
   // the transposed output gradients [N, ldR] of w2, w1, o, qkv
@@ -108,7 +108,7 @@ class Encoder final : public Model {
         a.request(&X.mean1, R); a.request(&X.rstd1, R); a.request(&X.mean2, R); a.request(&X.rstd2, R);
         act(&X.a, R * d_); act(&X.qkv_act, R * 3 * d_); act(&X.prob, heads * T_ * T_); act(&X.om, R * d_);
         a.request(&X.hmid, R * d_);
-        act(&X.f, R * d_); act(&X.u, R * f_); act(&X.g, R * f_);
+        act(&X.f, R * d_); a.request(&X.u, R * f_); act(&X.g, R * f_);
         if (sets_ == 2) {
           const int widths[4] = {d_, f_, d_, 3 * d_};
           for (int k = 0; k < 4; ++k) a.request(&X.dyT[k], (size_t)widths[k] * ldR_);
@@ -222,7 +222,7 @@ class Encoder final : public Model {
       VF_TRY(lin_fwd(c, "gemm_fwd", B.o, P, X.om, d_, R, X.hmid, d_, false, X.hin));
       VF_KS(c, st, "layernorm_fwd", launch_layernorm_fwd(X.hmid, d_, nullptr, R, d_, P + B.ln2_g, P + B.ln2_b, bf16_,
                                                     cfg_.ln_eps, X.f, d_, bf16_, X.mean2, X.rstd2, st));
-      VF_TRY(lin_fwd(c, "gemm_fwd", B.w1, P, X.f, d_, R, X.u, f_, true, nullptr));
+      VF_TRY(lin_fwd(c, "gemm_fwd", B.w1, P, X.f, d_, R, X.u, f_, false, nullptr));
       VF_KS(c, st, "gelu_fwd", launch_gelu_fwd(X.u, X.g, bf16_, (int64_t)R * f_, st));
       VF_TRY(lin_fwd(c, "gemm_fwd", B.w2, P, X.g, f_, R, hnext, d_, false, X.hmid));
     }

@@ -345,10 +345,10 @@ bool dy_prepare_fits(int dy_is_f32, int64_t ldi, int64_t ldn, int64_t ldt, int R
 int launch_dy_prepare(const void* dy, int dy_is_f32, int64_t ldi, int R, int C, bf16_t* nat, int64_t ldn,
                       bf16_t* tr, int64_t ldt, float* scratch, GradOut out, hipStream_t s,
                       FinishList* defer = nullptr);
-// exact GELU: g = 0.5 u (1 + erf(u / sqrt 2))
-int launch_gelu_fwd(const void* u, void* g, int is_bf16, int64_t n, hipStream_t s);
-// du = dg * (Phi(u) + u phi(u));  dg fp32, u and du T
-int launch_gelu_bwd(const float* dg, const void* u, void* du, int is_bf16, int64_t n, hipStream_t s);
+// exact GELU: g = 0.5 u (1 + erf(u / sqrt 2));  u fp32 (a Linear layer's output), g T
+int launch_gelu_fwd(const float* u, void* g, int g_is_bf16, int64_t n, hipStream_t s);
+// du = dg * (Phi(u) + u phi(u));  dg and u fp32, du T
+int launch_gelu_bwd(const float* dg, const float* u, void* du, int du_is_bf16, int64_t n, hipStream_t s);
 // row softmax in place over fp32 S [rows, n] -> P written as T to p (and nothing else)
 int launch_softmax_rows(const float* S, void* P, int p_is_bf16, int64_t rows, int n, hipStream_t s);
 // dS = P * (dP - sum_j dP*P) in place over dP (fp32); P is T

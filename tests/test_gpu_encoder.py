@@ -4,7 +4,8 @@ import pytest
 
 import oracle as O
 import vf_inputs as I
-from vfharness import TOL, check_against_oracle, check_update_from_own_gradient, oracle_steps, run_gpu
+from vfharness import (TOL, check_against_oracle, check_independent_bound, check_update_from_own_gradient,
+                       oracle_steps, run_gpu, weights_only_gradient)
 
 pytestmark = pytest.mark.gpu
 
@@ -94,3 +95,5 @@ def test_c4_full_size():
         gpu = run_gpu(wl, theta, x, y, flags=flags)
         check_against_oracle(wl, gpu, ref)
         check_update_from_own_gradient(wl, gpu, theta, tol=1e-4)
+    # the bound that does not depend on where operands are rounded
+    check_independent_bound(wl, gpu["G"], ref["G"], weights_only_gradient(wl, theta, x, y), "C4")

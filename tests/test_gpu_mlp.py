@@ -4,7 +4,8 @@ import pytest
 
 import oracle as O
 import vf_inputs as I
-from vfharness import (TOL, check_against_oracle, check_update_from_own_gradient, oracle_steps, run_gpu)
+from vfharness import (TOL, check_against_oracle, check_independent_bound, check_update_from_own_gradient,
+                       float32_products, oracle_steps, run_gpu, weights_only_gradient)
 
 pytestmark = pytest.mark.gpu
 
@@ -141,74 +142,75 @@ def test_full_size_configurations(name, flags, window):
     import paper_2009_09523_amd as vf
     off2, w2 = vf.vf_partition(wl.node_sizes, wl.batch)
     assert off.tobytes() == off2.tobytes() and w.tobytes() == w2.tobytes()
-
-
-def _calibrated_bounds(wl, ref, alt, tol):
-    """Per tensor: max(tol, 2 x the distance between two valid CPU evaluations)."""
-    from vfharness import tensor_errors
-    return {n: max(tol, 2.0 * r) for n, r, _ in tensor_errors(wl, alt, ref)}
+    if flags == BENCH:
+        check_independent_bound(wl, gpu["G"], ref["G"], weights_only_gradient(wl, theta, x, y), name)
 
 
 def test_c5_full_size_launch_configuration():
-    """Large-batch emulation: MLP 2048-8192x6-1000 + BatchNorm, 64 nodes of 128 (B = 8192).
-    The oracle can afford single nodes of this model, so: (a) the step is run in the launch
-    configuration bench.py times (V = 64) on a batch whose 64 nodes all hold the rows of
-    node 0 -- the combined gradient must then equal the oracle's g_0, and the update the
-    oracle's update with it; (b) two different nodes (V = 2) against (g_0 + g_1)/2.
+    """Large-batch emulation: MLP 2048-8192x6-1000 + BatchNorm, 64 nodes of 128 (B = 8192), in the
+    launch configuration bench.py times (fused fold, two streams, launches one by one, eight
+    windows of 8 nodes).  The oracle can afford single nodes of this model: it evaluates the four
+    distinct nodes 0..3, and the device runs V = 64 nodes of which node i holds the rows of node
+    i mod 4 -- the combined gradient is then (g_0 + g_1 + g_2 + g_3)/4 (Section 5.2 with 64 weights
+    of 1/64), every fold of step 3 and the update of step 5 run over all 64 nodes.
 
-    Tolerance.  Six BatchNorm+ReLU layers with bf16 activations are sensitive to rounding:
-    a perturbation delta of a pre-activation changes about delta/ulp of the bf16 roundings
-    of the layer's output, i.e. it leaves the layer with size sqrt(delta*ulp), so ANY two
-    correct evaluations (different summation order is enough) drift apart layer by layer
-    until they differ at the bf16 ulp level (measured: 0.1 % of the gradient norm at depth
-    2, 1 % at depth 3, 2.6 % at depth 4, 6 % at depth 6, independent of width).  The bound is
-    therefore calibrated by the oracle itself: per tensor, the device may be no further from
-    the float64 oracle than twice the distance of a second CPU evaluation whose forward
-    products accumulate in float32 (and never less strict than needed: at least 2e-2).  The
-    loss and the last layer, which no rounding decision upstream dominates, keep 2e-2."""
+    Tolerance.  Six BatchNorm+ReLU layers with bf16 operands are sensitive to rounding: a
+    difference delta of a pre-activation moves about delta/ulp of the bf16 roundings of the
+    layer's output, i.e. it leaves the layer with size sqrt(delta*ulp), so ANY two correct
+    evaluations (a different summation order is enough) drift apart layer by layer until they
+    differ at the bf16 ulp level.  Per tensor the test therefore first measures, on the CPU, how
+    far a second valid evaluation (the oracle with its forward products in float32) lies from
+    the oracle: tensors for which that distance is below half of 2e-2 are held to 2e-2; the
+    others -- stated as NOT meeting 2e-2, here and in the design notes -- to twice that distance.
+    The loss is held to 1e-3."""
     print("full size C5", flush=True)
+    from oracle.step import compute_copy
     from vfharness import tensor_errors
     wl = I.workload("C5")
     theta = I.make_params(wl)
     x, y = I.make_batch(wl)
-    from oracle.step import compute_copy
     cp = compute_copy(wl, theta)
-    L0, g0 = O.node_loss_and_grads(wl, cp, x[:128], y[:128])
-    _, g0_alt = O.node_loss_and_grads(wl, cp, x[:128], y[:128], accum32=True)
-    print("oracle node 0 done", flush=True)
-    L1, g1 = O.node_loss_and_grads(wl, cp, x[128:256], y[128:256])
-    print("oracle node 1 done", flush=True)
+    K = 4
+    Ls, gs, galt = [], [], []
+    for k in range(K):
+        lo, hi = 128 * k, 128 * (k + 1)
+        L_k, g_k = O.node_loss_and_grads(wl, cp, x[lo:hi], y[lo:hi])
+        with float32_products():
+            _, a_k = O.node_loss_and_grads(wl, cp, x[lo:hi], y[lo:hi])
+        Ls.append(L_k); gs.append(g_k); galt.append(a_k)
+        print(f"oracle node {k} done", flush=True)
     del cp
+    want, alt = sum(gs) / K, sum(galt) / K
+    Lw = sum(Ls) / K
     tol = TOL["bf16"]
-    bounds = _calibrated_bounds(wl, g0, g0_alt, tol)
-    print("calibrated bounds", {k: round(v, 4) for k, v in bounds.items() if k.endswith("W")}, flush=True)
+    second = {n: r for n, r, _ in tensor_errors(wl, alt, want)}
+    bounds = {n: (tol if r <= tol / 2 else 2.0 * r) for n, r in second.items()}
+    print("second CPU evaluation, rel-L2 per tensor:", {k: round(v, 4) for k, v in second.items()}, flush=True)
+    print("tensors held to 2e-2:", sorted(n for n, b in bounds.items() if b == tol), flush=True)
+    print("tensors NOT held to 2e-2 (bound = twice the second evaluation's distance):",
+          {n: round(b, 4) for n, b in bounds.items() if b != tol}, flush=True)
     assert bounds["l6.W"] == tol and bounds["l6.b"] == tol
 
-    def check(G, want, what):
-        errs = tensor_errors(wl, G, want)
-        print(what, {n: round(r, 4) for n, r, _ in errs if n.endswith("W")}, flush=True)
-        bad = [(n, r, bounds[n]) for n, r, _ in errs if r > bounds[n]]
-        assert not bad, f"{what}: {bad}"
-        assert max(r for _, r, _ in errs) < 0.15
-
-    # (a)
-    xa, ya = np.tile(x[:128], (64, 1)), np.tile(y[:128], 64)
-    gpu = run_gpu(wl, theta, xa, ya)
-    assert abs(gpu["loss"] - L0) <= 1e-3 * abs(L0)
-    np.testing.assert_allclose(gpu["node_losses"], np.full(64, L0), rtol=1e-3)
-    check(gpu["G"], g0, "G (64 equal nodes)")
+    xa = np.tile(x[:128 * K], (64 // K, 1))
+    ya = np.tile(y[:128 * K], 64 // K)
+    gpu = run_gpu(wl, theta, xa, ya, flags=BENCH, fold_window=8)
+    assert gpu["streams"] == 2
+    assert abs(gpu["loss"] - Lw) <= 1e-3 * abs(Lw)
+    np.testing.assert_allclose(gpu["node_losses"], np.tile(np.array(Ls), 64 // K), rtol=1e-3)
+    errs = tensor_errors(wl, gpu["G"], want)
+    print("device, rel-L2 per tensor:", {n: round(r, 4) for n, r, _ in errs}, flush=True)
+    bad = [(n, r, bounds[n]) for n, r, _ in errs if r > bounds[n]]
+    assert not bad, bad
     check_update_from_own_gradient(wl, gpu, theta)
     G64 = gpu["G"].copy()
     del gpu, xa, ya
-    # the same node once: 64 folds of g/64 must reproduce one fold of g (fp32 rounding only)
-    one = run_gpu(wl.with_nodes([128]), theta, x[:128], y[:128])
-    assert np.linalg.norm(G64 - one["G"]) <= 1e-6 * np.linalg.norm(one["G"])
-    del one, G64
-    # (b)
-    w2 = wl.with_nodes([128, 128])
-    gpu = run_gpu(w2, theta, x[:256], y[:256])
-    assert abs(gpu["loss"] - 0.5 * (L0 + L1)) <= 1e-3 * abs(L0)
-    check(gpu["G"], 0.5 * (g0 + g1), "G (two nodes)")
+    # the same four nodes once: 64 folds of g/64 against 4 folds of g/4 (fp32 rounding only)
+    four = run_gpu(wl.with_nodes([128] * K), theta, x[:128 * K], y[:128 * K], flags=BENCH, fold_window=8)
+    assert np.linalg.norm(G64 - four["G"]) <= 1e-6 * np.linalg.norm(four["G"])
+    del four
+    # the bound that does not depend on where operands are rounded (node 0 .. 3, weights only)
+    gw = weights_only_gradient(wl.with_nodes([128] * K), theta, x[:128 * K], y[:128 * K])
+    check_independent_bound(wl, G64, want, gw, "C5")
 
 
 OVERLAP = 4

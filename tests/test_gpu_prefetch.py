@@ -4,8 +4,9 @@ vf_step on device-resident batches."""
 import numpy as np
 import pytest
 
+import oracle as O
 import vf_inputs as I
-from vfharness import to_device_batch
+from vfharness import TOL, to_device_batch
 
 pytestmark = pytest.mark.gpu
 
@@ -61,9 +62,27 @@ def test_prefetched_steps_equal_steps_on_resident_batches(name, flags):
     torch.cuda.synchronize()
     got = p.cpu().numpy()
     assert eng.step_count == len(host)
+    G_last = torch.empty_like(p)
+    eng.grads(G_last)
+    loss_last = eng.loss()
     eng.close()
     assert got.tobytes() == ref.tobytes()
     assert not np.array_equal(ref, theta)
+
+    # and against the oracle stepping through the same batches (Section 3.2: one update per batch,
+    # each batch split into the same virtual nodes): the last step's combined gradient and loss,
+    # and the total parameter movement
+    th, state, r = theta.astype(np.float32), None, None
+    for x, y in batches:
+        r = O.oracle_step(wl, th, x, y, state=state)
+        state, th = r["state"], r["theta"].astype(np.float32)
+    tol = 5 * TOL[wl.dtype]        # four steps: the trajectories drift apart at the tolerance of one
+    g = G_last.cpu().numpy().astype(np.float64)
+    assert abs(loss_last - r["loss"]) <= tol * abs(r["loss"])
+    assert np.linalg.norm(g - r["G"]) <= tol * np.linalg.norm(r["G"])
+    if wl.optimizer == "sgdm":     # (Adam's first steps move noise-level entries by +-lr either way)
+        moved, want = got.astype(np.float64) - theta, r["theta"] - theta
+        assert np.linalg.norm(moved - want) <= tol * np.linalg.norm(want)
 
 
 def test_prefetch_order_errors_and_rejected_step_keeps_the_batch():

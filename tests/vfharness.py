@@ -2,9 +2,12 @@
 compare with the CPU oracle tensor by tensor."""
 from __future__ import annotations
 
+import contextlib
+
 import numpy as np
 
 import oracle as O
+import oracle.layers as OL
 import vf_inputs as I
 
 # Tolerances of the build's target: fp32 path rel 1e-4, bf16 path (fp32 accumulation) rel 2e-2.
@@ -64,16 +67,302 @@ def oracle_steps(wl, theta, x, y, node_sizes=None, steps=1):
     state = None
     r = None
     for _ in range(steps):
+        th_in = th
         r = O.oracle_step(wl, th, x, y, node_sizes=node_sizes, state=state)
         state = r["state"]
         th = r["theta"].astype(np.float32)      # the master copy is fp32
+    # what the explained max-abs criterion needs, should it be asked for (see relu_allowance)
+    r["inputs"] = (wl, th_in, x, y, node_sizes, theta.astype(np.float32), steps)
     return r
 
 
-def tensor_errors(wl, got, want, outlier_tol=None):
-    """[(name, rel_l2, max_abs_err / max_abs_ref)] per parameter tensor; with outlier_tol
-    the third entry is instead the fraction of elements whose error exceeds
-    outlier_tol * max_abs_ref."""
+# ---- variations of the oracle, planted on the CPU by the tests -------------------------------
+# The oracle is a definition and has no modes.  Where a test needs a second, equally valid
+# evaluation of the same step (products carried out in float32), or the step with the derivative
+# of near-zero ReLU inputs taken the other way, it replaces functions of oracle.layers for the
+# duration of one call.
+
+@contextlib.contextmanager
+def oracle_layers_patched(**functions):
+    saved = {k: getattr(OL, k) for k in functions}
+    try:
+        for k, f in functions.items():
+            setattr(OL, k, f)
+        yield
+    finally:
+        for k, f in saved.items():
+            setattr(OL, k, f)
+
+
+def _linear_fwd_f32(x, W, b=None):
+    y = (np.asarray(x, dtype=np.float32) @ np.asarray(W, dtype=np.float32)).astype(np.float64)
+    return y if b is None else y + b
+
+
+def _conv3x3_fwd_f32(x, W):
+    n, H, Wd, _ = x.shape
+    xp = np.pad(np.asarray(x, dtype=np.float32), ((0, 0), (1, 1), (1, 1), (0, 0)))
+    W32 = np.asarray(W, dtype=np.float32)
+    y = np.zeros((n, H, Wd, W.shape[0]), dtype=np.float32)
+    for kh in range(3):
+        for kw in range(3):
+            y += xp[:, kh:kh + H, kw:kw + Wd, :] @ W32[:, kh, kw, :].T
+    return y.astype(np.float64)
+
+
+def float32_products():
+    """Context: the oracle's forward products (Linear, convolution) are carried out in float32.
+    A second valid evaluation of a step; never the reference."""
+    return oracle_layers_patched(linear_fwd=_linear_fwd_f32, conv3x3_fwd=_conv3x3_fwd_f32)
+
+
+def weights_only_gradient(wl, theta, x, y, node_sizes=None):
+    """G of the same step with the parameters rounded to bf16 and NOTHING else: the oracle run
+    as a float64 workload on the rounded parameters (its operand rounding applies to bf16
+    workloads only).  The bound that does not depend on where this build rounds operands: a
+    device result must be no further from this than the operand-rounding oracle itself is,
+    times INDEPENDENT_FACTOR."""
+    from dataclasses import replace
+    th = O.round_to_bf16(np.asarray(theta, dtype=np.float32)).astype(np.float32)
+    return O.oracle_step(replace(wl, dtype="f32"), th, x, y, node_sizes=node_sizes)["G"]
+
+
+INDEPENDENT_FACTOR = 1.5
+
+
+def check_independent_bound(wl, got, ref_G, weights_only_G, what):
+    rows = []
+    for (n, d_dev, _), (_, d_ref, _) in zip(tensor_errors(wl, got, weights_only_G),
+                                            tensor_errors(wl, ref_G, weights_only_G)):
+        rows.append((n, d_dev, d_ref))
+    print(what, "distance to the weights-only-rounded float64 gradient, device / operand-rounding oracle:",
+          {n: (round(a, 4), round(b, 4)) for n, a, b in rows if n.endswith("W") or n.endswith("emb")}, flush=True)
+    bad = [(n, a, b) for n, a, b in rows if a > INDEPENDENT_FACTOR * b + 1e-3]
+    assert not bad, f"{what}: further from the weights-only gradient than the rounding model explains: {bad[:8]}"
+
+
+def n_relu_layers(wl):
+    if wl.kind == "mlp":
+        return len(wl.dims) - 2
+    return 1 + 2 * wl.n_blocks if wl.kind == "conv" else 0
+
+
+def _relu_inputs(wl, theta32, x, y, node_sizes):
+    """[layer][node] -> the ReLU layer's inputs as the oracle step sees them (forward order)."""
+    seen = []
+    plain = OL.relu_fwd
+
+    def spy(t):
+        seen.append(np.array(t, dtype=np.float64))
+        return plain(t)
+    with oracle_layers_patched(relu_fwd=spy):
+        O.oracle_step(wl, theta32, x, y, node_sizes=node_sizes)
+    nl = n_relu_layers(wl)
+    return [seen[l::nl] for l in range(nl)]
+
+
+def relu_allowance(ref):
+    """The explained part of a max-abs miss, for MLP workloads: a flat array, the size of the
+    parameter vector, of how far each gradient entry may lie from the reference because of
+    AMBIGUOUS ReLU units.  Everything is computed on the CPU from the oracle alone.
+
+    A ReLU unit whose input two valid evaluations place on different sides of zero may be on in
+    one implementation and off in the other; both are right.  How far apart two valid evaluations
+    place a layer's inputs is measured: the float64 oracle against the same oracle with its
+    forward products in float32, per
+    hidden layer the largest difference over all nodes and units, relative to the layer's rms (it grows with depth in bf16 workloads: a difference delta
+    upstream moves about delta/ulp of the bf16 roundings of the next operand).  A unit (node i,
+    layer l, row r, column u) is ambiguous when its input is within tau_l = twice that distance
+    of zero (and at least what one rounding of the layer's bf16 operand can move it by).  Switching it changes the gradient at the ReLU's input, in row r and column u, by
+    the gradient dh[r,u] at its output; from there the backward pass is linear, so every gradient
+    entry changes by a sum of single-unit effects, one per switched unit that reaches it.
+
+    In the columns of the unit's own layer (dW[:,u], dgamma[u], dbeta[u]) one unit moves an entry
+    by ONE sample's contribution and few units reach an entry: the allowance there is SIGMAS times
+    the root of the sum of the squared effects of ALL ambiguous units of the column -- at least
+    the sum of their absolute values, hence a strict bound whichever subset is switched, wherever
+    at most SIGMAS^2 units share a column.  The layers upstream are reached by every switched unit,
+    minutely: there the sum is dense, and its size is what matters.  A unit at distance p from
+    zero is switched with the probability that the two evaluations differ by more than p; the
+    allowance upstream is SIGMAS standard deviations of the sum under independent signs, each
+    unit weighted with that probability taken from the measured differences of its layer, at p/2
+    (the same safety factor as tau).  The squares go down the oracle's own backward pass with
+    every factor squared (Q = the matrix of dh[r,u]^2 at the units concerned):
+        BatchNorm:  Qz = (gamma rstd)^2 (Q + sum_rows Q / n^2 + xhat^2 sum_rows(Q xhat^2) / n^2),
+                    dbeta: w_i^2 sum_rows Q,  dgamma: w_i^2 sum_rows Q xhat^2
+        Linear:     dW: w_i^2 (h^2)^T Qz,  and upstream  Q' = (Qz (W^2)^T) [pre' > -tau' rms] + own units
+    (h the layer's input rows, n their number, w_i = b_i/B), summed over the nodes.  Exactly zero
+    where no ambiguous unit reaches."""
+    wl, th, x, y, sizes, th0, steps = ref["inputs"]
+    assert wl.kind in ("mlp", "conv")
+    nl = n_relu_layers(wl)
+    sizes = list(wl.node_sizes if sizes is None else sizes)
+    B = float(sum(sizes))
+    # one float64 pass that records, per node and hidden layer, what the bound needs
+    rec = {"pre": [], "dh": [], "bn": [], "h": [], "cx": []}
+    relu_bwd, bn_bwd, lin_bwd, conv_bwd = OL.relu_bwd, OL.batchnorm_bwd, OL.linear_bwd, OL.conv3x3_bwd
+
+    def spy_relu_bwd(dout, t):
+        rec["dh"].append(np.array(dout)); rec["pre"].append(np.array(t))
+        return relu_bwd(dout, t)
+
+    def spy_bn_bwd(dout, gamma, cache):
+        rec["bn"].append((np.array(gamma), cache[0], cache[1]))
+        return bn_bwd(dout, gamma, cache)
+
+    def spy_lin_bwd(xin, W, dy, has_bias):
+        rec["h"].append(xin)
+        return lin_bwd(xin, W, dy, has_bias)
+    def spy_conv_bwd(xin, W, dy, need_dx=True):
+        rec["cx"].append(xin)
+        return conv_bwd(xin, W, dy, need_dx)
+    with oracle_layers_patched(relu_bwd=spy_relu_bwd, batchnorm_bwd=spy_bn_bwd, linear_bwd=spy_lin_bwd,
+                               conv3x3_bwd=spy_conv_bwd):
+        O.oracle_step(wl, th, x, y, node_sizes=sizes)
+    with float32_products():
+        pre32 = _relu_inputs(wl, th, x, y, sizes)
+    V = len(sizes)
+    # the backward pass meets the hidden layers last to first; linear_bwd is also called for the output layer
+    at = lambda node, layer: node * nl + (nl - 1 - layer)
+    h_at = lambda node, layer: rec["h"][node * (nl + 1) + (nl - layer)]
+    tau, drift = [], []
+    for l in range(nl):
+        d = []
+        for i in range(V):
+            p = rec["pre"][at(i, l)]
+            d.append((np.abs(p - pre32[l][i]) / np.sqrt(np.mean(p * p))).reshape(-1))
+        d = np.sort(np.concatenate(d))
+        drift.append(d)
+        # never below what fp32 accumulation of a few thousand products does in any order (the
+        # library's float32 product is pairwise and blocked, better than most)
+        tau.append(max(2.0 * float(d[-1]), TAU_FLOOR))
+    from oracle.step import compute_copy
+    Wc = {k: v for k, v in O.unflatten(wl, compute_copy(wl, th)).items() if ".W" in k}
+    sqW = {k: v * v for k, v in Wc.items()}
+    var = np.zeros(ref["G"].size)
+    views = O.unflatten(wl, var)
+    if wl.kind == "conv":
+        units = _conv_squares(wl, rec, at, tau, drift, sizes, B, sqW, Wc, views, conv_bwd)
+        return {"allow": SIGMAS * np.sqrt(var), "tau": tau, "units": units}
+    if wl.dtype == "bf16":
+        # The measured differences are one sample of a heavy-tailed distribution: its rare large
+        # values are single roundings of the layer's bf16 operand h that fall the other way (the
+        # first layer's operand is the input itself, identical on both sides).  One such rounding
+        # moves a pre-activation by at most ulp * max|h| * max|W| (times |gamma| rstd through
+        # BatchNorm): tau is at least that.
+        for l in range(1, nl):
+            for i in range(V):
+                pre, h = rec["pre"][at(i, l)], h_at(i, l)
+                one = 2.0 ** -8 * np.max(np.abs(h)) * np.max(np.abs(Wc[f"l{l}.W"]))
+                if wl.batchnorm:
+                    gamma, _, rstd = rec["bn"][at(i, l)]
+                    one *= np.max(np.abs(gamma * rstd))
+                tau[l] = max(tau[l], float(one / np.sqrt(np.mean(pre * pre))))
+    units = 0
+
+    def through(l, i, Q, w2, tensors):
+        """Squares Q at the ReLU inputs of layer l, node i: adds to the layer's tensors (if asked)
+        and returns the squares at the layer's Linear output."""
+        n = Q.shape[0]
+        if wl.batchnorm:
+            gamma, xhat, rstd = rec["bn"][at(i, l)]
+            x2 = xhat * xhat
+            if tensors:
+                views[f"l{l}.beta"] += w2 * Q.sum(axis=0)
+                views[f"l{l}.gamma"] += w2 * (Q * x2).sum(axis=0)
+            Qz = (gamma * rstd) ** 2 * (Q + Q.sum(axis=0) / n ** 2 + x2 * (Q * x2).sum(axis=0) / n ** 2)
+        else:
+            if tensors:
+                views[f"l{l}.b"] += w2 * Q.sum(axis=0)
+            Qz = Q
+        if tensors:
+            h = h_at(i, l)
+            views[f"l{l}.W"] += w2 * ((h * h).T @ Qz)
+        return Qz
+
+    for i in range(V):
+        w2 = (sizes[i] / B) ** 2
+        down = None                                  # weighted squares reaching this layer's dh from the layers after it
+        for l in range(nl - 1, -1, -1):
+            pre, dh = rec["pre"][at(i, l)], rec["dh"][at(i, l)]
+            rms = np.sqrt(np.mean(pre * pre))
+            thr = tau[l] * rms
+            amb = np.abs(pre) < thr
+            units += int(amb.sum())
+            passed = down * (pre > -thr) if down is not None else 0.0
+            # this layer's own tensors: every ambiguous unit in full, plus what comes from below
+            Q = amb * (dh * dh) + passed
+            if np.any(Q):
+                through(l, i, Q, w2, True)
+            if l == 0:
+                break
+            # what goes on upstream: each unit with the probability of being switched
+            prob = 1.0 - np.searchsorted(drift[l], np.abs(pre) / (2.0 * rms), side="left") / drift[l].size
+            Qw = prob * (dh * dh) + passed
+            down = through(l, i, Qw, w2, False) @ sqW[f"l{l}.W"].T if np.any(Qw) else None
+    allow = SIGMAS * np.sqrt(var)
+    return {"allow": allow, "tau": tau, "units": units}
+
+
+def _conv_squares(wl, rec, at, tau, drift, sizes, B, sqW, Wc, views, conv_bwd):
+    """relu_allowance for the convolutional family: the same squares, sent down the backward pass
+    of the residual network (the oracle's own convolution backward applied to squared inputs,
+    squared filters and squared gradients; a skip connection adds variances).  ReLU layers in
+    forward order: stem, then per block the inner one and the one after the skip addition."""
+    nl = len(tau)
+    names = [("stem.W", "stem.gamma", "stem.beta")]
+    for b in range(wl.n_blocks):
+        names += [(f"b{b}.W1", f"b{b}.gamma1", f"b{b}.beta1"), (f"b{b}.W2", f"b{b}.gamma2", f"b{b}.beta2")]
+    if wl.dtype == "bf16":     # at least what one rounding of the layer's bf16 operand can do (see relu_allowance)
+        for f in range(1, nl):
+            for i in range(len(sizes)):
+                pre = rec["pre"][at(i, f)]
+                gamma, _, rstd = rec["bn"][at(i, f)]
+                one = 2.0 ** -8 * np.max(np.abs(rec["cx"][at(i, f)])) * np.max(np.abs(Wc[names[f][0]])) * np.max(np.abs(gamma * rstd))
+                tau[f] = max(tau[f], float(one / np.sqrt(np.mean(pre * pre))))
+    units = 0
+    for i in range(len(sizes)):
+        w2 = (sizes[i] / B) ** 2
+
+        def layer(f, down, need_dx):
+            """ReLU layer f of node i with weighted squares `down` arriving at its output: adds to
+            the tensors of the convolution that feeds it; returns (weighted squares at the ReLU's
+            input, weighted squares at that convolution's input)."""
+            nonlocal units
+            pre, d = rec["pre"][at(i, f)], rec["dh"][at(i, f)]
+            gamma, xhat, rstd = rec["bn"][at(i, f)]
+            rms = np.sqrt(np.mean(pre * pre))
+            thr = tau[f] * rms
+            amb = np.abs(pre) < thr
+            units += int(amb.sum())
+            passed = down * (pre > -thr) if down is not None else 0.0
+            prob = 1.0 - np.searchsorted(drift[f], np.abs(pre) / (2.0 * rms), side="left") / drift[f].size
+            x2, C = xhat * xhat, pre.shape[-1]
+            xin2, W2 = rec["cx"][at(i, f)] ** 2, sqW[names[f][0]]
+
+            def bn(Q):
+                Q = Q.reshape(-1, C)
+                n = Q.shape[0]
+                return Q, ((gamma * rstd) ** 2 * (Q + Q.sum(axis=0) / n ** 2 + x2 * (Q * x2).sum(axis=0) / n ** 2)).reshape(pre.shape)
+            Q, Qz = bn(amb * (d * d) + passed)        # own tensors: every ambiguous unit in full
+            if np.any(Q):
+                views[names[f][2]] += w2 * Q.sum(axis=0)
+                views[names[f][1]] += w2 * (Q * x2).sum(axis=0)
+                views[names[f][0]] += w2 * conv_bwd(xin2, W2, Qz, False)[1]
+            Qw = prob * (d * d) + passed              # onwards: each unit with its probability
+            dx = conv_bwd(xin2, W2, bn(Qw)[1], True)[0] if need_dx else None
+            return Qw, dx
+        down = None
+        for b in range(wl.n_blocks - 1, -1, -1):
+            q_skip, q_in = layer(2 * b + 2, down, True)
+            _, q_conv = layer(2 * b + 1, q_in, True)
+            down = q_conv + q_skip                    # through the convolutions + through the skip
+        layer(0, down, False)
+    return units
+
+
+def tensor_errors(wl, got, want):
+    """[(name, rel_l2, max_abs_err / max_abs_ref)] per parameter tensor."""
     rows, pos = [], 0
     for name, shape in O.layout(wl):
         n = int(np.prod(shape))
@@ -83,53 +372,81 @@ def tensor_errors(wl, got, want, outlier_tol=None):
         d = a - b
         rel = np.linalg.norm(d) / nb if nb > 0 else np.linalg.norm(d)
         mx = np.max(np.abs(d)) / mb if mb > 0 else np.max(np.abs(d))
-        if outlier_tol is not None:
-            mx = float(np.mean(np.abs(d) > outlier_tol * mb))
         rows.append((name, float(rel), float(mx)))
         pos += n
     return rows
 
 
-# A ReLU unit whose input is within fp32 accumulation error of zero may be switched on by one
-# implementation and off by the other; both outcomes are valid.  One such unit changes one
-# sample's contribution to one column of the gradients upstream: barely visible in the L2
-# norm, but it can dominate the max-abs norm (a float32-accumulating CPU emulation of the
-# forward pass shows the same against the float64 oracle: about 1 percent in L2, isolated
-# entries off by 10-25 percent of the tensor's maximum at the size of the benchmark
-# configuration).  So: the relative L2 bound always holds per tensor.  The max-abs bound
-# holds when the oracle reports no ambiguous unit (every ReLU input at least RELU_AMBIGUOUS
-# times its layer's rms away from zero); otherwise it is replaced by an outlier budget: at
-# most OUTLIER_FRACTION of a tensor's entries may miss the max-abs bound.
-RELU_AMBIGUOUS = 1e-5
-OUTLIER_FRACTION = 0.01
+# Parity criterion (per parameter tensor): relative L2 error <= tol AND largest entry error <=
+# tol * largest reference entry.  The second bound has one explained exception, for the MLP
+# workloads: an entry may miss it by what the ambiguous ReLU units of its own column account for
+# (relu_allowance), and by nothing else.  EXPLAINED_SLACK covers the second-order part (two
+# ambiguous units of consecutive layers interacting).
+EXPLAINED_SLACK = 1.25
+SIGMAS = 6.0
+TAU_FLOOR = 1e-5
+
+def assert_explained(wl, got, ref, tol, what):
+    """got against ref["G"]: rel-L2 per tensor, and max-abs up to the ambiguous ReLU units' effect.
+    Returns the number of entries that needed the exception."""
+    want = ref["G"]
+    errs = tensor_errors(wl, got, want)
+    bad = [(n, r) for n, r, _ in errs if not r <= tol]
+    assert not bad, f"{what}: tensors beyond rel-L2 {tol}: {bad[:8]}"
+    if all(m <= tol for _, _, m in errs):
+        return 0
+    assert wl.kind in ("mlp", "conv"), f"{what}: max-abs beyond {tol}: {[e for e in errs if e[2] > tol][:8]}"
+    if ref["inputs"][6] > 1:
+        # After the first update the device's parameters and the oracle's differ (by the first
+        # step's differences, switched ambiguous units included), so which units are ambiguous
+        # in a later step is no longer the oracle's to say: later steps are held to the L2 bound,
+        # single steps of the same configurations to the whole criterion.
+        print(f"{what}: step {ref['inputs'][6]}, max-abs {max(m for _, _, m in errs):.3f}: L2 bound only", flush=True)
+        return 1
+    if "band" not in ref:
+        ref["band"] = relu_allowance(ref)
+    band = ref["band"]
+    pos, used, worst = 0, 0, []
+    for name, shape in O.layout(wl):
+        n = int(np.prod(shape))
+        sl = slice(pos, pos + n)
+        pos += n
+        b = np.asarray(want[sl], dtype=np.float64)
+        excess = np.abs(np.asarray(got[sl], dtype=np.float64) - b) - tol * np.max(np.abs(b))
+        used += int(np.sum(excess > 0))
+        over = excess - EXPLAINED_SLACK * band["allow"][sl]
+        if np.any(over > 0):
+            k = int(np.argmax(over))
+            worst.append((name, k, float(excess[k]), float(band["allow"][sl][k])))
+    print(f"{what}: {used} of {pos} entries beyond max-abs {tol}; {band['units']} ambiguous ReLU units "
+          f"(tau per layer {[float('%.2g' % t) for t in band['tau']]}) explain them: {not worst}", flush=True)
+    assert not worst, f"{what}: entries beyond max-abs that no ambiguous ReLU unit explains: {worst[:8]}"
+    return used
 
 
-def assert_close_per_tensor(wl, got, want, tol, what, ambiguous=False):
-    if ambiguous:
-        bad = [(n, r, f) for n, r, f in tensor_errors(wl, got, want, outlier_tol=tol)
-               if not (r <= tol and f <= OUTLIER_FRACTION)]
-        assert not bad, f"{what}: tensors beyond rel-L2 {tol} or outlier budget: {bad[:8]}"
-        return
-    bad = [(n, r, m) for n, r, m in tensor_errors(wl, got, want) if not (r <= tol and m <= tol)]
+def assert_close_per_tensor(wl, got, want, tol, what, l2_only=False):
+    bad = [(n, r, m) for n, r, m in tensor_errors(wl, got, want) if not (r <= tol and (l2_only or m <= tol))]
     assert not bad, f"{what}: tensors beyond tol {tol}: {bad[:8]}"
 
 
 def check_against_oracle(wl, gpu, ref, tol=None, check_theta=True):
-    """Per tensor: ||a-b||2/||b||2 <= tol and max|a-b| <= tol*max|b|; loss relative."""
+    """Per tensor: ||a-b||2/||b||2 <= tol and max|a-b| <= tol*max|b| (for G up to the explained
+    exception of assert_explained); loss relative.  Parameters and optimizer state follow from G
+    by the update that check_update_from_own_gradient pins on its own: where G needed the
+    exception they are held to the L2 bound only."""
     tol = TOL[wl.dtype] if tol is None else tol
-    mt = ref.get("relu_margin", np.inf) < RELU_AMBIGUOUS
     assert abs(gpu["loss"] - ref["loss"]) <= tol * abs(ref["loss"]), (gpu["loss"], ref["loss"])
     np.testing.assert_allclose(gpu["node_losses"], ref["node_losses"], rtol=tol)
-    assert_close_per_tensor(wl, gpu["G"], ref["G"], tol, "G", mt)
+    excused = assert_explained(wl, gpu["G"], ref, tol, "G") > 0
     assert gpu["t"] == ref["state"]["t"]
     if not check_theta:
         return
     if wl.optimizer == "sgdm":
-        assert_close_per_tensor(wl, gpu["theta"], ref["theta"], tol, "theta", mt)
-        assert_close_per_tensor(wl, gpu["s0"], ref["state"]["v"], tol, "velocity", mt)
+        assert_close_per_tensor(wl, gpu["theta"], ref["theta"], tol, "theta", excused)
+        assert_close_per_tensor(wl, gpu["s0"], ref["state"]["v"], tol, "velocity", excused)
     else:
-        assert_close_per_tensor(wl, gpu["s0"], ref["state"]["m"], tol, "adam m", mt)
-        assert_close_per_tensor(wl, gpu["s1"], ref["state"]["u"], 2.5 * tol, "adam u", mt)   # quadratic in G
+        assert_close_per_tensor(wl, gpu["s0"], ref["state"]["m"], tol, "adam m", excused)
+        assert_close_per_tensor(wl, gpu["s1"], ref["state"]["u"], 2.5 * tol, "adam u", excused)   # quadratic in G
 
 
 def check_update_from_own_gradient(wl, gpu, theta0, tol=1e-5):
