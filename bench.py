@@ -25,7 +25,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 matrix cores
 FP32_VECTOR_PEAK_TFLOPS = 157.3
 
 
-def algorithmic_work(wl, P, fused=False, window=1):
+def algorithmic_work(wl, P, fused=False, window=1, group=1):
     """Per step, per kernel tag: (bytes, flops, launches) the method itself needs.
     Bytes count each operand once per launch (fp32 = 4, bf16 = 2).  With the fused fold the
     weight-gradient kernels read and write the gradient buffer once per fold window of `window`
@@ -33,7 +33,12 @@ def algorithmic_work(wl, P, fused=False, window=1):
     V, B = wl.n_nodes, wl.batch
     esz = 2 if wl.dtype == "bf16" else 4
     work = {} if fused else {"accumulate": ((12 * V - 4) * P, 2 * V * P, V)}
-    nwin = -(-V // window) if fused else V        # passes over the gradient buffer per step
+    # With node groups a launch takes `group` nodes at once.  The bytes stay the method's: every
+    # node streams the weights once (Section 3.2: the nodes run one after another), so a launch
+    # that serves several nodes is credited with the stream of each of them -- what the kernel
+    # really reads is the counter figure `traffic`.
+    U = pass_units(wl, group)                     # units that go through the passes
+    nwin = -(-U // window) if fused else V        # passes over the gradient buffer per step
     wg = (8 * nwin - 4) if fused else 4 * V       # fp32 bytes per matrix entry per step
     opt_bytes = (20 if wl.optimizer == "sgdm" else 28) * P
     work["optimizer"] = (opt_bytes, 4 * P, 1)
@@ -43,8 +48,8 @@ def algorithmic_work(wl, P, fused=False, window=1):
         fwd_fl = 2 * B * W
         dgr_fl = 2 * B * sum(k * n for k, n in mats[1:])
         act = sum(b * (k * esz + n * 4) for b in wl.node_sizes for k, n in mats)
-        work["gemm_fwd"] = (V * W * esz + act, fwd_fl, V * len(mats))
-        work["gemm_dgrad"] = (V * sum(k * n for k, n in mats[1:]) * esz + act, dgr_fl, V * (len(mats) - 1))
+        work["gemm_fwd"] = (V * W * esz + act, fwd_fl, U * len(mats))
+        work["gemm_dgrad"] = (V * sum(k * n for k, n in mats[1:]) * esz + act, dgr_fl, U * (len(mats) - 1))
         work["gemm_wgrad"] = (wg * W + act, fwd_fl, nwin * len(mats))
         work["cast_weight"] = (W * (4 + 2 * esz), 0, len(mats))
     elif wl.kind == "conv":
@@ -71,21 +76,41 @@ def algorithmic_work(wl, P, fused=False, window=1):
         Wl = 4 * d * d + 2 * d * f                 # matrix entries of one block
         lin_fl = 2 * R * Wl * nl                   # one pass over the four Linears of all blocks
         act_f = nl * R * (2 * d + 3 * d + d + f + f + d) * esz   # operands read / written once
-        work["gemm_fwd"] = (V * nl * Wl * esz + act_f, lin_fl, V * nl * 4)
-        work["gemm_dgrad"] = (V * nl * Wl * esz + act_f, lin_fl, V * nl * 4)
-        work["gemm_wgrad"] = (wg * nl * Wl + act_f, lin_fl, V * nl * 4)
+        work["gemm_fwd"] = (V * nl * Wl * esz + act_f, lin_fl, U * nl * 4)
+        work["gemm_dgrad"] = (V * nl * Wl * esz + act_f, lin_fl, U * nl * 4)
+        work["gemm_wgrad"] = (wg * nl * Wl + act_f, lin_fl, U * nl * 4)
         head_fl = 2 * Rm * d * Vc
-        work["gemm_head"] = (V * d * Vc * esz + Rm * Vc * 4, head_fl, V)
-        work["gemm_head_dgrad"] = (V * d * Vc * esz + Rm * Vc * esz, head_fl, V)
-        work["gemm_head_wgrad"] = (wg * d * Vc + Rm * Vc * esz, head_fl, V)
+        work["gemm_head"] = (V * d * Vc * esz + Rm * Vc * 4, head_fl, U)
+        work["gemm_head_dgrad"] = (V * d * Vc * esz + Rm * Vc * esz, head_fl, U)
+        work["gemm_head_wgrad"] = (wg * d * Vc + Rm * Vc * esz, head_fl, U)
         att = 2 * T * T * d * B * nl               # one [T,T,d_head] product over all heads, all blocks
         for tag in ("attn_scores", "attn_pv", "attn_bwd_dp", "attn_bwd_dv", "attn_bwd_dq", "attn_bwd_dk"):
-            work[tag] = (nl * (3 * R * d * esz + B * wl.n_heads * T * T * 4), att, V * nl)
+            work[tag] = (nl * (3 * R * d * esz + B * wl.n_heads * T * T * 4), att, U * nl)
         # fused matrix-core kernels: 2 products forward, 4 backward, per head
-        work["attn_fwd"] = (nl * (4 * R * d * esz + B * wl.n_heads * T * T * esz), 2 * att, V * nl)
-        work["attn_bwd"] = (nl * (6 * R * d * esz + R * d * 4 + B * wl.n_heads * T * T * esz), 4 * att, V * nl)
+        work["attn_fwd"] = (nl * (4 * R * d * esz + B * wl.n_heads * T * T * esz), 2 * att, U * nl)
+        work["attn_bwd"] = (nl * (6 * R * d * esz + R * d * 4 + B * wl.n_heads * T * T * esz), 4 * att, U * nl)
         work["cast_weight"] = ((nl * Wl + d * Vc) * (4 + 2 * esz), 0, 4 * nl + 1)
     return work
+
+
+def pass_units(wl, group):
+    """Units that go through the passes of a step: the nodes, or (the library's rule) runs of 2 or 4
+    consecutive equal-sized nodes where the model takes groups (bf16 MLP with nodes of at most 128
+    rows, a multiple of 8; the encoder)."""
+    sizes, ok = list(wl.node_sizes), False
+    if group > 1:
+        ok = wl.kind == "encoder" or (wl.kind == "mlp" and wl.dtype == "bf16")
+    units, i = 0, 0
+    while i < len(sizes):
+        take = 1
+        if ok and (wl.kind == "encoder" or (sizes[i] <= 128 and sizes[i] % 8 == 0)):
+            run = 1
+            while i + run < len(sizes) and run < group and sizes[i + run] == sizes[i]:
+                run += 1
+            take = 4 if run >= 4 else (2 if run >= 2 else 1)
+        units += 1
+        i += take
+    return units
 
 
 def roofline_for(tag, work, avg_ms):
@@ -149,6 +174,7 @@ def cpu_baseline(wl, theta, x, y, budget_s=12.0):
                 break
     dt = time.perf_counter() - t0
     return {"value": samples / dt, "unit": "samples/s", "cores": int(cores), "kind": "oracle",
+            "threads": "cores = the BLAS threads of the NumPy float64 oracle (threadpoolctl); its Python parts run on one",
             "sample": f"{done} virtual-node passes ({samples} samples; the workload has {wl.n_nodes} nodes) of "
                       f"workload {wl.name}, each with the combine and one optimizer update, {dt:.1f} s",
             "seconds": dt}
@@ -159,12 +185,12 @@ def mode_flags(vf, args):
            (vf.VF_FLAG_OVERLAP if args.streams == 2 else 0)
 
 
-def time_steps(vf, torch, wl, theta, x, y, flags, steps, warmup, max_node_size=None, fold_window=1):
+def time_steps(vf, torch, wl, theta, x, y, flags, steps, warmup, max_node_size=None, fold_window=1, node_group=1):
     """(ms per step, workspace bytes) of `wl` on the device."""
     from paper_2009_09523_amd.binding import config_from_workload
     stream = torch.cuda.Stream()
     eng = vf.VirtualNodeStep(config_from_workload(wl, flags=flags, stream=stream, max_node_size=max_node_size,
-                                                  fold_window=fold_window))
+                                                  fold_window=fold_window, node_group=node_group))
     params = torch.from_numpy(theta).cuda()
     xt = torch.from_numpy(x).cuda()
     if wl.kind in ("mlp", "conv") and wl.dtype == "bf16":
@@ -204,7 +230,7 @@ def vsweep(args):
         wl = replace(base, node_sizes=(b,) * V)
         theta = I.make_params(wl)
         x, y = I.make_batch(wl)
-        ms, ws = time_steps(vf, torch, wl, theta, x, y, flags, args.steps, args.warmup, fold_window=args.fold_window)
+        ms, ws = time_steps(vf, torch, wl, theta, x, y, flags, args.steps, args.warmup, fold_window=args.fold_window, node_group=args.node_group)
         grow.append({"V": V, "batch": b * V, "ms_per_step": ms, "samples_per_s": b * V / (ms * 1e-3),
                      "workspace_bytes": ws})
     B = base.batch
@@ -213,7 +239,7 @@ def vsweep(args):
     V = 1
     while B // V >= 16 and B % V == 0:
         wl = replace(base, node_sizes=(B // V,) * V)
-        ms, ws = time_steps(vf, torch, wl, theta, x, y, flags, args.steps, args.warmup, fold_window=args.fold_window)
+        ms, ws = time_steps(vf, torch, wl, theta, x, y, flags, args.steps, args.warmup, fold_window=args.fold_window, node_group=args.node_group)
         fits.append({"V": V, "node_size": B // V, "ms_per_step": ms, "samples_per_s": B / (ms * 1e-3),
                      "workspace_bytes": ws})
         V *= 2
@@ -248,7 +274,7 @@ def het_profile(args):
         wl = replace(base, node_sizes=(b,) * V)
         theta = I.make_params(wl)
         x, y = I.make_batch(wl)
-        ms, _ = time_steps(vf, torch, wl, theta, x, y, flags, args.steps, args.warmup, fold_window=args.fold_window)
+        ms, _ = time_steps(vf, torch, wl, theta, x, y, flags, args.steps, args.warmup, fold_window=args.fold_window, node_group=args.node_group)
         curve.append({"node_batch": b, "ms_per_node": ms / V, "samples_per_s": b * V / (ms * 1e-3)})
     fast = [c["ms_per_node"] for c in curve]
     slow = [4.0 * t for t in fast]
@@ -270,9 +296,14 @@ def het_profile(args):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="C2")
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default=None,
+                    help="the workload `value` is measured on (default C5: the largest configuration that one "
+                         "GPU holds)")
+    ap.add_argument("--also", default="C2,C4",
+                    help="comma-separated workloads measured as well and reported under other_workloads "
+                         "(default C2,C4; empty: none)")
     ap.add_argument("--accumulate", choices=["staged", "fused"], default="fused",
                     help="fused (default): weight-gradient epilogues fold w_i*g_i into the gradient buffer; "
                          "staged: per-node staging vector + the accumulate kernel")
@@ -288,6 +319,10 @@ def main():
                     help="fused fold: the weight gradients of this many consecutive nodes (1..8) are folded "
                          "into the gradient buffer in one pass (nodes of one size: one product over the "
                          "window's rows; the workspace keeps that many nodes' transposed bf16 operands)")
+    ap.add_argument("--node-group", type=int, choices=[1, 2, 4], default=4,
+                    help="up to this many consecutive equal-sized nodes go through their passes together "
+                         "(one operand of every product, so the weights are read once per group; BatchNorm "
+                         "statistics, node losses and weights stay per node); 1: node after node")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-profile", action="store_true")
     ap.add_argument("--vsweep", action="store_true",
@@ -297,6 +332,8 @@ def main():
                     help="instead of the benchmark line: the offline profile (time per virtual node "
                          "against node batch size) and the heterogeneous split it gives on a synthetic mix")
     args = ap.parse_args()
+    if args.workload is None:     # the sweeps are defined on the configuration whose step takes about 1 ms
+        args.workload = "C2" if (args.vsweep or args.het_profile) else "C5"
     if args.gpus != 1:
         print("bench.py: this build runs the virtual-node step on ONE GPU; --gpus above 1 is not "
               "supported (no collectives are part of it).", file=sys.stderr)
@@ -318,13 +355,33 @@ def main():
     if args.het_profile:
         het_profile(args)
         return
-    wl = I.workload(args.workload)
+    out = bench_workload(args.workload, args, primary=True)
+    # the other named configurations that fit one GPU, each with its own roofline and floor
+    # (never `value`): C2 is the one whose weights stay cache resident, C4 the one where the
+    # matrix cores are the binding roof
+    others = [w for w in args.also.split(",") if w and w != args.workload]
+    if others:
+        out["other_workloads"] = {w: bench_workload(w, args, primary=False) for w in others}
+    print(json.dumps(out))
+
+
+def bench_workload(name, args, primary):
+    """One benchmark record of workload `name` (see the module docstring for what a step is)."""
+    import numpy as np
+    import torch
+    import paper_2009_09523_amd as vf
+    import vf_inputs as I
+    from paper_2009_09523_amd.binding import config_from_workload
+    wl = I.workload(name)
+    # a secondary record of a small workload is timed over more steps (its step takes about 1 ms)
+    steps = args.steps if primary or name in ("C4", "C5") else max(args.steps, 50)
+    warmup = args.warmup
     theta = I.make_params(wl)
     x, y = I.make_batch(wl)
     stream = torch.cuda.Stream()
     mode = mode_flags(vf, args)
     flags = (vf.VF_FLAG_FUSED_ACCUMULATE if args.accumulate == "fused" else 0) | mode
-    eng = vf.VirtualNodeStep(config_from_workload(wl, flags=flags, stream=stream, fold_window=args.fold_window))
+    eng = vf.VirtualNodeStep(config_from_workload(wl, flags=flags, stream=stream, fold_window=args.fold_window, node_group=args.node_group))
     P = eng.num_params
     window = eng.fold_window                      # the window in effect (1 where no windowed path exists)
     params = torch.from_numpy(theta).cuda()
@@ -344,23 +401,23 @@ def main():
     stream.synchronize()
     del cal_src, cal_dst
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         eng.step(params, xt, yt, sizes)
     stream.synchronize()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         eng.step(params, xt, yt, sizes)
     stream.synchronize()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    ms_per_step = dt * 1e3 / args.steps
+    ms_per_step = dt * 1e3 / steps
     loss = eng.loss()
 
     out = {
         "metric": "samples/sec per training step at V virtual nodes on 1 MI355X",
         "value": wl.batch / (ms_per_step * 1e-3), "unit": "samples/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if wl.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": wl.name, "model": wl.kind, "dims": list(wl.dims) if wl.kind == "mlp" else None,
@@ -375,11 +432,19 @@ def main():
                    "node_sizes": sizes if len(set(sizes)) > 1 else f"{wl.n_nodes}x{sizes[0]}",
                    "optimizer": wl.optimizer, "params": P, "accumulate": args.accumulate,
                    "fold_window": window, "workspace_bytes": eng.workspace_bytes,
-                   "streams": eng.streams, "launch": args.launch},
+                   "streams": eng.streams, "launch": args.launch,
+                   "node_group": args.node_group, "pass_units": pass_units(wl, args.node_group),
+                   "value_is": ("%d units of up to %d equal-sized nodes go through the passes one after another "
+                                "(a group's rows are one operand of every product; BatchNorm statistics, losses "
+                                "and weights b_i/B per node); fused fold with a window of %d units: the weight "
+                                "gradients of a window are ONE product over its rows (the weighted sum of "
+                                "Section 5.2).  alt_window_1 is the same step node after node (groups of 1, "
+                                "window 1), alt the form with the stand-alone accumulate kernel of Section 3.2 "
+                                "step 3" % (pass_units(wl, args.node_group), args.node_group, window))},
         "loss": loss,
     }
 
-    work = algorithmic_work(wl, P, fused=args.accumulate == "fused", window=window)
+    work = algorithmic_work(wl, P, fused=args.accumulate == "fused", window=window, group=args.node_group)
     total_bytes = sum(v[0] for v in work.values())
     total_flops = sum(v[1] for k, v in work.items() if k.startswith(("gemm", "attn")))
     floor_ms = max(total_bytes / (HBM_PEAK_GBS * 1e9), total_flops / (MFMA_BF16_PEAK_TFLOPS * 1e12)) * 1e3
@@ -395,12 +460,12 @@ def main():
         engp, pp = eng, params
         if eng.streams == 2:
             engp = vf.VirtualNodeStep(config_from_workload(wl, flags=flags & ~vf.VF_FLAG_OVERLAP, stream=stream,
-                                                           fold_window=args.fold_window))
+                                                           fold_window=args.fold_window, node_group=args.node_group))
             pp = params.clone()
-            for _ in range(args.warmup):
+            for _ in range(warmup):
                 engp.step(pp, xt, yt, sizes)
         engp.profile_start()
-        for _ in range(args.steps):
+        for _ in range(steps):
             engp.step(pp, xt, yt, sizes)
         prof = engp.profile_stop()
         if engp is not eng:
@@ -408,9 +473,9 @@ def main():
             del pp
         out["kernels_mode"] = "one stream, launched one by one, an event pair around every kernel"
         tot = sum(v["total_ms"] for v in prof.values())
-        kernels = {k: {"launches_per_step": v["launches"] / args.steps,
+        kernels = {k: {"launches_per_step": v["launches"] / steps,
                        "avg_launch_ms": v["total_ms"] / v["launches"],
-                       "ms_per_step": v["total_ms"] / args.steps,
+                       "ms_per_step": v["total_ms"] / steps,
                        "share": v["total_ms"] / tot} for k, v in prof.items()}
         out["kernels"] = kernels
         dom = max((k for k in kernels if k in work), key=lambda k: kernels[k]["ms_per_step"])
@@ -423,37 +488,37 @@ def main():
 
     if not args.no_alt and window > 1:
         # the same fused fold node by node (window 1), for comparison (never `value`)
-        ms1, ws1 = time_steps(vf, torch, wl, theta, x, y, flags, args.steps, args.warmup)
+        ms1, ws1 = time_steps(vf, torch, wl, theta, x, y, flags, steps, warmup)
         out["alt_window_1"] = {"fold_window": 1, "ms_per_step": ms1, "value": wl.batch / (ms1 * 1e-3),
                                "workspace_bytes": ws1}
 
-    if not args.no_alt and (args.streams != 1 or args.launch != "graph"):
+    if primary and not args.no_alt and (args.streams != 1 or args.launch != "graph"):
         # one stream, the whole step replayed as one HIP graph, for comparison (never `value`)
         gflags = flags & ~(vf.VF_FLAG_NO_GRAPH | vf.VF_FLAG_OVERLAP)
-        msg, wsg = time_steps(vf, torch, wl, theta, x, y, gflags, args.steps, args.warmup, fold_window=args.fold_window)
+        msg, wsg = time_steps(vf, torch, wl, theta, x, y, gflags, steps, warmup, fold_window=args.fold_window, node_group=args.node_group)
         out["alt_one_stream_graph"] = {"streams": 1, "launch": "graph", "ms_per_step": msg,
                                        "value": wl.batch / (msg * 1e-3), "workspace_bytes": wsg}
 
-    if not args.no_alt:
+    if primary and not args.no_alt:
         # the other accumulate mode, same workload, for comparison (never `value`)
         alt_mode = "staged" if args.accumulate == "fused" else "fused"
         aflags = (vf.VF_FLAG_FUSED_ACCUMULATE if alt_mode == "fused" else 0) | mode
         eng2 = vf.VirtualNodeStep(config_from_workload(wl, flags=aflags, stream=stream))
         p2 = torch.from_numpy(theta).cuda()
-        for _ in range(args.warmup):
+        for _ in range(warmup):
             eng2.step(p2, xt, yt, sizes)
         stream.synchronize()
         torch.cuda.synchronize()
         t1 = time.perf_counter()
-        for _ in range(args.steps):
+        for _ in range(steps):
             eng2.step(p2, xt, yt, sizes)
         stream.synchronize()
         torch.cuda.synchronize()
-        ams = (time.perf_counter() - t1) * 1e3 / args.steps
+        ams = (time.perf_counter() - t1) * 1e3 / steps
         alt = {"accumulate": alt_mode, "ms_per_step": ams, "value": wl.batch / (ams * 1e-3)}
         if alt_mode == "staged" and not args.no_kernel_profile:
             eng2.profile_start()
-            for _ in range(args.steps):
+            for _ in range(steps):
                 eng2.step(p2, xt, yt, sizes)
             pr = eng2.profile_stop()
             w2 = algorithmic_work(wl, P, fused=False)
@@ -465,34 +530,34 @@ def main():
         eng2.close()
         del p2
 
-    if not args.no_alt:
+    if primary and not args.no_alt:
         # The same steps with every batch coming from pinned host memory through the prefetching
         # entry points (copy of batch t+1 beside step t): the PCIe-inclusive rate, never `value`.
-        eng3 = vf.VirtualNodeStep(config_from_workload(wl, flags=flags, stream=stream, fold_window=args.fold_window))
+        eng3 = vf.VirtualNodeStep(config_from_workload(wl, flags=flags, stream=stream, fold_window=args.fold_window, node_group=args.node_group))
         p3 = torch.from_numpy(theta).cuda()
         hx, hy = xt.cpu().pin_memory(), yt.cpu().pin_memory()
         eng3.prefetch(hx, hy)
-        for _ in range(args.warmup):
+        for _ in range(warmup):
             eng3.step_prefetched(p3, sizes)
             eng3.prefetch(hx, hy)
         stream.synchronize()
         torch.cuda.synchronize()
         t2 = time.perf_counter()
-        for _ in range(args.steps):
+        for _ in range(steps):
             eng3.step_prefetched(p3, sizes)
             eng3.prefetch(hx, hy)
         stream.synchronize()
         torch.cuda.synchronize()
-        pms = (time.perf_counter() - t2) * 1e3 / args.steps
+        pms = (time.perf_counter() - t2) * 1e3 / steps
         out["host_input"] = {"ms_per_step": pms, "value": wl.batch / (pms * 1e-3),
                              "bytes_per_step": hx.numel() * hx.element_size() + hy.numel() * hy.element_size(),
                              "note": "batch copied from pinned host memory by vf_prefetch while the previous step runs"}
         eng3.close()
         del p3
 
-    if not args.no_cpu_baseline:
+    if primary and not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, theta, x, y)
-    print(json.dumps(out))
+    return out
 
 
 if __name__ == "__main__":

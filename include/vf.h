@@ -124,6 +124,15 @@ typedef struct vf_config {
                                     buffer traffic; the transposed bf16 operands of the window's
                                     nodes are kept until then, so the workspace grows with the
                                     window (not with V). */
+  int32_t node_group;            /* MLP (bf16) and encoder: up to this many CONSECUTIVE nodes of one
+                                    size (1, 2 or 4; 0 = 1) are taken through their passes together:
+                                    their rows form one operand of every product, so the weights
+                                    are read once per group instead of once per node.  Everything a
+                                    node owns stays per node -- BatchNorm statistics and their
+                                    moving averages (node after node), the node losses, the weight
+                                    b_i/B -- so the step computes what it computes node by node, up
+                                    to the order of additions.  The per-node workspace grows by
+                                    this factor (not with V).  MLP: nodes of at most 128 rows. */
   uint32_t flags;                /* VF_FLAG_* */
   void*   stream;                /* hipStream_t; NULL = the default stream */
 } vf_config;

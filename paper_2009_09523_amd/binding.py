@@ -53,6 +53,7 @@ class VfConfig(C.Structure):
         ("bn_momentum", C.c_float),
         ("max_batch", C.c_int32), ("max_node_size", C.c_int32), ("max_nodes", C.c_int32),
         ("fold_window", C.c_int32),
+        ("node_group", C.c_int32),
         ("flags", C.c_uint32), ("stream", C.c_void_p),
     ]
 
@@ -228,7 +229,7 @@ def vf_solve_split(types, B: int, comm: float = 0.0):
 
 def config_from_workload(wl, max_batch: Optional[int] = None, max_node_size: Optional[int] = None,
                          max_nodes: Optional[int] = None, flags: int = 0, stream=None,
-                         fold_window: int = 0) -> VfConfig:
+                         fold_window: int = 0, node_group: int = 0) -> VfConfig:
     """Fills a vf_config from a workload description (an object with the attributes of
     vf_inputs.Workload)."""
     cfg = VfConfig()
@@ -253,6 +254,7 @@ def config_from_workload(wl, max_batch: Optional[int] = None, max_node_size: Opt
     cfg.max_nodes = int(max_nodes if max_nodes is not None else len(wl.node_sizes))
     cfg.flags = int(flags)
     cfg.fold_window = int(fold_window)
+    cfg.node_group = int(node_group)
     cfg.stream = _stream_handle(stream)
     return cfg
 

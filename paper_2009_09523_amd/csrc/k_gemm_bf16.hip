@@ -525,6 +525,164 @@ __global__ __launch_bounds__(NT) void gemm_bf16_dl_kernel(const bf16_t* __restri
   store_tiles<1, 1>(tiles, ep, cbase, blockIdx.z == 0, m0 + wm * 32, n0 + wn * 32, M, N, lane);
 }
 
+// ---- wide LDS-direct variant: 256 x BN tiles, eight wavefronts ---------------------------------
+// For products with at least a few hundred rows (two or more virtual nodes taken as one product,
+// the weight gradients of a fold window, the token products of the encoder).  What bounds a
+// product here is the volume a compute unit has to pull through its vector memory path per flop,
+// (1/BM + 1/BN) operand elements per multiply-add, so the tile is as large as LDS allows:
+// 256 x 128 or 256 x 256, one workgroup per compute unit, eight wavefronts as 4 x 2, each owning
+// 64 x BN/2 (two per SIMD: one wavefront's LDS reads run beside the other's MFMAs; within a
+// wavefront the fragments of MFMA step k+1 are read while the MFMAs of step k run).
+// Operand tiles go from global memory straight into LDS in stages of KS contraction elements
+// (KS = 64: rows of 128 bytes, eight 16-byte chunks; KS = 32: rows of 64 bytes, four chunks), the
+// chunks of a row permuted so that the 16-byte operand reads of 32 consecutive rows spread over
+// all banks.  A ring of NS stages: NS-1 stages are on their way while one is consumed, and a
+// stage's loads are not issued in one burst but spread over the MFMA steps of the stage before
+// (a wavefront never sits on a full memory queue with its matrix work waiting behind it).  What
+// matters is how long before its use a stage is requested: 256 x 256 tiles take stages of 32
+// (32 KB) so that four of them fit, 256 x 128 tiles three stages of 64 (48 KB).
+// Workgroup numbering: XCD x (workgroup index modulo 8) takes a contiguous run of the tile order
+// "eight row tiles down, then one column right", so the 32 tiles that run side by side on one
+// XCD form an 8 x 4 block sharing 8 + 4 operand panels on that XCD's L2.
+// Requires whole stages in every contraction slice; operand rows are clamped into the matrix
+// (their products never stored).
+template <int KS>
+__device__ __forceinline__ int wide_swizzle(int r) {
+  return KS == 64 ? ((r & 7) ^ ((r >> 3) & 1)) : ((r >> 2) & 3);
+}
+
+template <int BN, int KS, int NS>
+__global__ __launch_bounds__(512) void gemm_bf16_wide_kernel(const bf16_t* __restrict__ A, int64_t lda,
+                                                             const bf16_t* __restrict__ B, int64_t ldb,
+                                                             int M, int N, int K, int kchunk,
+                                                             int64_t slab_stride, Epilogue ep, int tiles_m,
+                                                             int tiles_n) {
+  static_assert(BN == 128 || BN == 256, "tile width");
+  static_assert(KS == 64 || KS == 32, "stage depth");
+  constexpr int BM = 256;
+  constexpr int CPR = KS / 8;                            // 16-byte chunks per row
+  constexpr int RPI = 64 / CPR;                          // rows one load instruction of a wavefront fills
+  constexpr int ATILE = BM * KS, BTILE = BN * KS;        // elements
+  constexpr int STAGE = ATILE + BTILE;
+  constexpr int AL = BM / (8 * RPI), BL = BN / (8 * RPI);   // load instructions per lane and stage (8 waves)
+  constexpr int LPS = AL + BL;
+  constexpr int STEPS = KS / 16;                         // MFMA steps per stage
+  constexpr int TN = BN / 64;                            // 32-column MFMA tiles per wavefront (2 row tiles)
+  static_assert(NS * STAGE * 2 <= 160 * 1024 && NS >= 2, "LDS");
+  extern __shared__ __attribute__((aligned(1024))) bf16_t lds_wide[];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  // this workgroup's tile
+  const int ntile = tiles_m * tiles_n;
+  const int per = (ntile + 7) >> 3;
+  const int local = blockIdx.x >> 3;
+  if (local >= per) return;
+  const int t = (blockIdx.x & 7) * per + local;
+  if (t >= ntile) return;
+  const int panel = t / (8 * tiles_n);
+  const int in_panel = t - panel * 8 * tiles_n;
+  const int prow = min(8, tiles_m - panel * 8);
+  const int m0 = (panel * 8 + in_panel % prow) * BM, n0 = (in_panel / prow) * BN;
+  const int kbeg = blockIdx.z * kchunk;
+  const int kend = min(K, kbeg + kchunk);
+  const int nstage = kend > kbeg ? (kend - kbeg) / KS : 0;
+
+  const bf16_t* ga[AL];
+  const bf16_t* gb[BL];
+#pragma unroll
+  for (int q = 0; q < AL; ++q) {
+    const int row = (wave + 8 * q) * RPI + lane / CPR;
+    ga[q] = A + (int64_t)min(m0 + row, M - 1) * lda + kbeg + (((lane % CPR) ^ wide_swizzle<KS>(row)) * 8);
+  }
+#pragma unroll
+  for (int q = 0; q < BL; ++q) {
+    const int row = (wave + 8 * q) * RPI + lane / CPR;
+    gb[q] = B + (int64_t)min(n0 + row, N - 1) * ldb + kbeg + (((lane % CPR) ^ wide_swizzle<KS>(row)) * 8);
+  }
+  // load number j (0 .. LPS-1) of a stage: first the A rows, then the B rows
+  auto issue_one = [&](int j, int stage, int slot) {
+    const int k = stage * KS;
+    bf16_t* base = &lds_wide[slot * STAGE];
+    if (j < AL)
+      __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(ga[j] + k),
+                                       (void __attribute__((address_space(3)))*)(base + (wave + 8 * j) * 512), 16, 0, 0);
+    else
+      __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(gb[j - AL] + k),
+                                       (void __attribute__((address_space(3)))*)(base + ATILE + (wave + 8 * (j - AL)) * 512),
+                                       16, 0, 0);
+  };
+
+  f32x16 acc[2][TN];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  int arow[2], asw[2], brow[TN], bsw[TN];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) { arow[i] = wm * 64 + i * 32 + (lane & 31); asw[i] = wide_swizzle<KS>(arow[i]); }
+#pragma unroll
+  for (int j = 0; j < TN; ++j) { brow[j] = wn * (BN / 2) + j * 32 + (lane & 31); bsw[j] = wide_swizzle<KS>(brow[j]); }
+
+  if (nstage > 0) {
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s)
+#pragma unroll
+      for (int j = 0; j < LPS; ++j) issue_one(j, min(s, nstage - 1), s);
+    for (int it = 0; it < nstage; ++it) {
+      // loads complete in order: stage `it` has landed when at most NS-2 stages are outstanding
+      wait_loads_but<(NS - 2) * LPS>();
+      // every wave's part of stage `it` is in LDS and every wave is done reading stage it-1, whose
+      // slot the loads issued below overwrite
+      __builtin_amdgcn_s_barrier();
+      asm volatile("" ::: "memory");
+      const int nxt = min(it + NS - 1, nstage - 1), slot = (it + NS - 1) % NS;
+      const bf16_t* as = &lds_wide[(it % NS) * STAGE];
+      const bf16_t* bs = as + ATILE;
+      bf16x8 a[2][2], b[2][TN];
+      auto read_frags = [&](int kk, int buf) {
+        const int cidx = 2 * kk + (lane >> 5);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) a[buf][i] = *reinterpret_cast<const bf16x8*>(&as[arow[i] * KS + ((cidx ^ asw[i]) * 8)]);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) b[buf][j] = *reinterpret_cast<const bf16x8*>(&bs[brow[j] * KS + ((cidx ^ bsw[j]) * 8)]);
+      };
+      read_frags(0, 0);
+#pragma unroll
+      for (int kk = 0; kk < STEPS; ++kk) {
+        if (kk + 1 < STEPS) read_frags(kk + 1, (kk + 1) & 1);
+        // a share of the loads of the stage NS-1 ahead per MFMA step
+#pragma unroll
+        for (int j = kk * LPS / STEPS; j < (kk + 1) * LPS / STEPS; ++j) issue_one(j, nxt, slot);
+        __builtin_amdgcn_sched_barrier(0);      // the reads above stay ahead of the MFMAs below
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk & 1][i], b[kk & 1][j], acc[i][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    wait_loads_but<0>();
+  }
+
+  char* cbase = static_cast<char*>(ep.C) + (int64_t)blockIdx.z * slab_stride * (ep.c_is_bf16 ? 2 : 4);
+  // one row of 32 x 32 tiles at a time (the addend of a whole wavefront tile would not fit in registers)
+  auto store_row = [&](auto ic) {
+    constexpr int i = decltype(ic)::value;
+    f32x16 row[1][TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) row[0][j] = acc[i][j];
+    store_tiles<1, TN>(row, ep, cbase, blockIdx.z == 0, m0 + wm * 64 + i * 32, n0 + wn * (BN / 2), M, N, lane);
+  };
+  store_row(std::integral_constant<int, 0>{});
+  store_row(std::integral_constant<int, 1>{});
+}
+
 // ---- 3x3 convolution with the filters resident in LDS -------------------------------------------
 // 64 input channels (one 128-byte row per position), 64 output channels per workgroup, image width
 // W a power of two from 8 to 64.  The workgroup keeps its 64 x 576 filters in LDS (nine 64 x 64 tiles,
@@ -972,13 +1130,46 @@ int pipe_depth() {
   return cached;
 }
 
+int launch_wide(const Shape& g, const Epilogue& ep, hipStream_t s);
+
 }  // namespace
 
 // Compute-bound shapes take the big tile; everything else (few rows, or a short contraction
 // whose cost is writing the output) does better with many small workgroups in flight.
 static bool use_big_tile(int M, int N, int K) { return M >= 1024 && N >= 1024 && K >= 512; }
 
+// The wide kernel takes products of more than 128 rows whose contraction slices are whole stages.
+// Tuning aid: VF_GEMM_WIDE=0 switches it off, 128 / 256 forces the tile width.
+static int wide_mode() {
+  static int cached = -1;
+  if (cached < 0) {
+    const char* e = std::getenv("VF_GEMM_WIDE");
+    cached = e ? std::atoi(e) : 1;
+  }
+  return cached;
+}
+static int wide_tile_n(int M, int N) {
+  const int mode = wide_mode();
+  if (mode == 128 || mode == 256) return mode;
+  const int64_t tm = (M + 255) / 256;
+  // 256 x 256 once that still gives every compute unit a tile; narrow matrices keep 128
+  return (N >= 256 && tm * ((N + 255) / 256) >= 256) ? 256 : 128;
+}
+static bool wide_fits(int M, int N, int K, int nsplit) {
+  if (!wide_mode() || M <= 128 || N < 128 || (K % BK)) return false;
+  const int kchunk = ((K + nsplit - 1) / nsplit + BK - 1) / BK * BK;
+  return (K % kchunk) == 0 || nsplit == 1;
+}
+
 int gemm_bf16_pick_split(int M, int N, int K) {
+  if (wide_fits(M, N, K, 1)) {
+    // one workgroup per compute unit: slices until about 256 workgroups, each at least 8 stages long
+    const int bn = wide_tile_n(M, N);
+    const int64_t tiles = (int64_t)((M + 255) / 256) * ((N + bn - 1) / bn);
+    int split = 1;
+    while (tiles * split * 2 <= 256 && K / (split * 2) >= 8 * BK && (K / BK) % (split * 2) == 0 && split < 32) split *= 2;
+    return split;
+  }
   // Measured on the node-sized products (128 x 4096 x 4096 and relatives) with the
   // pipelined kernel: about two 64x64 workgroups per compute unit, slices no shorter than
   // 3 LDS stages.
@@ -991,6 +1182,47 @@ int gemm_bf16_pick_split(int M, int N, int K) {
   while (tiles * split < target && K / (split * 2) >= 3 * BK && split < 32) split *= 2;
   return split;
 }
+
+namespace {
+template <int BN, int KS, int NS>
+int launch_wide_cfg(const Shape& g, const Epilogue& ep, hipStream_t s) {
+  constexpr int bytes = NS * (256 + BN) * KS * 2;
+  static bool ready = false;
+  if (!ready) {
+    VF_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_wide_kernel<BN, KS, NS>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
+    ready = true;
+  }
+  const int kchunk = ((g.K + g.nsplit - 1) / g.nsplit + BK - 1) / BK * BK;
+  const int tiles_m = (g.M + 255) / 256, tiles_n = (g.N + BN - 1) / BN;
+  const int ntile = tiles_m * tiles_n;
+  dim3 grid(((ntile + 7) / 8) * 8, 1, g.nsplit);
+  gemm_bf16_wide_kernel<BN, KS, NS><<<grid, 512, bytes, s>>>(g.A, g.lda, g.B, g.ldb, g.M, g.N, g.K, kchunk, g.slab, ep,
+                                                             tiles_m, tiles_n);
+  VF_LAUNCH_CHECK();
+  return VF_OK;
+}
+int wide_variant() {   // tuning aid: VF_GEMM_WIDE_V=<n> picks another ring for the 256-wide tile
+  static int cached = -1;
+  if (cached < 0) {
+    const char* e = std::getenv("VF_GEMM_WIDE_V");
+    cached = e ? std::atoi(e) : 0;
+  }
+  return cached;
+}
+int launch_wide(const Shape& g, const Epilogue& ep, hipStream_t s) {
+  if (wide_tile_n(g.M, g.N) == 256) {
+    switch (wide_variant()) {
+      case 1: return launch_wide_cfg<256, 64, 2>(g, ep, s);
+      case 2: return launch_wide_cfg<256, 32, 5>(g, ep, s);
+      case 3: return launch_wide_cfg<256, 32, 3>(g, ep, s);
+      default: return launch_wide_cfg<256, 32, 4>(g, ep, s);
+    }
+  }
+  if (wide_variant() == 4) return launch_wide_cfg<128, 32, 6>(g, ep, s);
+  return launch_wide_cfg<128, 64, 3>(g, ep, s);
+}
+}  // namespace
 
 int launch_gemm_bf16(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, int M, int N,
                      int K, int nsplit, int64_t slab_stride, const Epilogue& ep, hipStream_t s) {
@@ -1020,6 +1252,7 @@ int launch_gemm_bf16(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb,
     VF_LAUNCH_CHECK();
     return VF_OK;
   }
+  if (wide_fits(M, N, K, nsplit)) return launch_wide(g, ep, s);
   if (use_big_tile(M, N, K)) return launch_cfg<128, 128, 2, 2>(g, ep, s);
   if (M <= 32) return launch_cfg<32, 128, 1, 4>(g, ep, s);
   if (N <= 32) return launch_cfg<128, 32, 4, 1>(g, ep, s);

@@ -58,7 +58,12 @@ __device__ __forceinline__ void store_transposed(const bf16_t (*tile)[RCH + 8], 
 }
 
 // SMALL: R <= RCH, rows live in registers.
-template <typename T, int NS, bool SMALL>
+// G > 1 (SMALL only): the rows are G virtual nodes of R rows each, one after the other (a group of
+// equal-sized nodes whose products were taken as one): statistics, normalisation and the moving
+// statistics' blend are per node, in node order, exactly as G launches would do them; all nodes'
+// rows are loaded up front, so the group costs one trip to memory.  mean_out / rstd_out hold G
+// vectors of C, the transposed copy node g's rows at columns g*R .. g*R + R-1.
+template <typename T, int NS, bool SMALL, int G>
 __global__ __launch_bounds__(256) void bn_relu_fwd_kernel(const float* __restrict__ zp, int64_t slab,
                                                           int64_t ldzp, int R, int C,
                                                           const float* __restrict__ gamma,
@@ -71,6 +76,7 @@ __global__ __launch_bounds__(256) void bn_relu_fwd_kernel(const float* __restric
                                                           float* __restrict__ rstd_out,
                                                           float* __restrict__ run_mean,
                                                           float* __restrict__ run_var, float run_mix) {
+  static_assert(G == 1 || SMALL, "groups of nodes only on the register-resident path");
   __shared__ float red[RL][CB + 1];
   __shared__ __attribute__((aligned(16))) bf16_t tile[CB][RCH + 8];
   const int tx = threadIdx.x % CB, ty = threadIdx.x / CB;
@@ -78,94 +84,102 @@ __global__ __launch_bounds__(256) void bn_relu_fwd_kernel(const float* __restric
   const int c = c0 + tx;
   const bool live = c < C;
   const bool bn = gamma != nullptr;
-  float mean = 0.f, rstd = 1.f, g = 1.f, b = 0.f;
+  float g = 1.f, b = 0.f;
   float rm = 0.f, rv = 0.f;
   if (bn && live) {   // issued with the first row loads, needed only after the reductions
     g = gamma[c]; b = beta[c];
     if (run_mean && ty == 0) { rm = run_mean[c]; rv = run_var[c]; }
   }
-  float zr[RPT];
-  // pass 1: reduce the slabs into z, column sums
-  float s = 0.f;
+  float zr[G][RPT];
   if (SMALL) {
     // Loads at clamped (always valid) addresses, selection afterwards: no load sits behind a
     // branch, so all of a thread's loads are in flight together.
     const int cc = min(c, C - 1);
 #pragma unroll
-    for (int k = 0; k < RPT; ++k) {
-      const int r = ty + RL * k;
-      zr[k] = sum_slabs<NS>(zp, slab, (int64_t)min(r, R - 1) * ldzp + cc);
-    }
+    for (int n = 0; n < G; ++n)
 #pragma unroll
-    for (int k = 0; k < RPT; ++k) {
-      const int r = ty + RL * k;
-      zr[k] = (live && r < R) ? zr[k] : 0.f;
-      s += zr[k];
-    }
-#pragma unroll
-    for (int k = 0; k < RPT; ++k) {
-      const int r = ty + RL * k;
-      if (live && r < R) z[(int64_t)r * ldz + c] = zr[k];
-    }
-  } else if (live) {
-    for (int r = ty; r < R; r += RL) {
-      float v = sum_slabs<NS>(zp, slab, (int64_t)r * ldzp + c);
-      z[(int64_t)r * ldz + c] = v;
-      s += v;
-    }
+      for (int k = 0; k < RPT; ++k) {
+        const int r = ty + RL * k;
+        zr[n][k] = sum_slabs<NS>(zp, slab, (int64_t)(n * R + min(r, R - 1)) * ldzp + cc);
+      }
   }
-  if (bn) {
-    mean = col_reduce(s, red, tx, ty) / (float)R;
-    float q = 0.f;
+  if (bn && live && round_params) { g = round_bf16(g); b = round_bf16(b); }
+#pragma unroll
+  for (int n = 0; n < G; ++n) {
+    const int rb = n * R;                       // first row of this node
+    float mean = 0.f, rstd = 1.f;
+    // pass 1: reduce the slabs into z, column sums
+    float s = 0.f;
     if (SMALL) {
 #pragma unroll
       for (int k = 0; k < RPT; ++k) {
         const int r = ty + RL * k;
-        float d = (live && r < R) ? zr[k] - mean : 0.f;
-        q = fmaf(d, d, q);
+        zr[n][k] = (live && r < R) ? zr[n][k] : 0.f;
+        s += zr[n][k];
+      }
+#pragma unroll
+      for (int k = 0; k < RPT; ++k) {
+        const int r = ty + RL * k;
+        if (live && r < R) z[(int64_t)(rb + r) * ldz + c] = zr[n][k];
       }
     } else if (live) {
       for (int r = ty; r < R; r += RL) {
-        float d = z[(int64_t)r * ldz + c] - mean;
-        q = fmaf(d, d, q);
+        float v = sum_slabs<NS>(zp, slab, (int64_t)r * ldzp + c);
+        z[(int64_t)r * ldz + c] = v;
+        s += v;
       }
     }
-    const float var = col_reduce(q, red, tx, ty) / (float)R;
-    rstd = 1.0f / sqrtf(var + eps);
-    if (live) {
-      if (round_params) { g = round_bf16(g); b = round_bf16(b); }
-      if (ty == 0) {
-        mean_out[c] = mean; rstd_out[c] = rstd;
+    if (bn) {
+      mean = col_reduce(s, red, tx, ty) / (float)R;
+      float q = 0.f;
+      if (SMALL) {
+#pragma unroll
+        for (int k = 0; k < RPT; ++k) {
+          const int r = ty + RL * k;
+          float d = (live && r < R) ? zr[n][k] - mean : 0.f;
+          q = fmaf(d, d, q);
+        }
+      } else if (live) {
+        for (int r = ty; r < R; r += RL) {
+          float d = z[(int64_t)r * ldz + c] - mean;
+          q = fmaf(d, d, q);
+        }
+      }
+      const float var = col_reduce(q, red, tx, ty) / (float)R;
+      rstd = 1.0f / sqrtf(var + eps);
+      if (live && ty == 0) {
+        mean_out[(int64_t)n * C + c] = mean; rstd_out[(int64_t)n * C + c] = rstd;
         if (run_mean) {   // moving statistics of this device: one blend per pass (Section 4.1)
-          run_mean[c] = fmaf(run_mix, mean - rm, rm);
-          run_var[c] = fmaf(run_mix, var - rv, rv);
+          rm = fmaf(run_mix, mean - rm, rm);
+          rv = fmaf(run_mix, var - rv, rv);
         }
       }
     }
-  }
-  // pass 2: activation, in chunks of RCH rows so the transposed copy can go through LDS
-  for (int r0 = 0; r0 < R; r0 += RCH) {
+    // pass 2: activation, in chunks of RCH rows so the transposed copy can go through LDS
+    for (int r0 = 0; r0 < R; r0 += RCH) {
 #pragma unroll
-    for (int k = 0; k < RPT; ++k) {
-      const int rl = ty + RL * k;
-      const int r = r0 + rl;
-      float v = 0.f;
-      if (live && r < R) {
-        float zz = SMALL ? zr[k] : z[(int64_t)r * ldz + c];
-        v = bn ? fmaxf(fmaf(g, (zz - mean) * rstd, b), 0.f) : fmaxf(zz, 0.f);
-        store_f(&a[(int64_t)r * lda + c], v);
+      for (int k = 0; k < RPT; ++k) {
+        const int rl = ty + RL * k;
+        const int r = r0 + rl;
+        float v = 0.f;
+        if (live && r < R) {
+          float zz = SMALL ? zr[n][k] : z[(int64_t)r * ldz + c];
+          v = bn ? fmaxf(fmaf(g, (zz - mean) * rstd, b), 0.f) : fmaxf(zz, 0.f);
+          store_f(&a[(int64_t)(rb + r) * lda + c], v);
+        }
+        if (aT) tile[tx][rl] = f32_to_bf16(v);
       }
-      if (aT) tile[tx][rl] = f32_to_bf16(v);
-    }
-    if (aT) {
-      __syncthreads();
-      store_transposed(tile, aT, ldt, c0, C, r0, R);
-      __syncthreads();
+      if (aT) {
+        __syncthreads();
+        store_transposed(tile, aT + rb, ldt, c0, C, r0, R);
+        __syncthreads();
+      }
     }
   }
+  if (bn && live && ty == 0 && run_mean) { run_mean[c] = rm; run_var[c] = rv; }
 }
 
-template <typename T, int NS, bool SMALL>
+template <typename T, int NS, bool SMALL, int G>
 __global__ __launch_bounds__(256) void bn_relu_bwd_kernel(float* __restrict__ dap, int64_t slab,
                                                           int64_t ldda, const float* __restrict__ z,
                                                           int64_t ldz, int R, int C,
@@ -177,6 +191,7 @@ __global__ __launch_bounds__(256) void bn_relu_bwd_kernel(float* __restrict__ da
                                                           T* __restrict__ dz, int64_t lddz,
                                                           bf16_t* __restrict__ dzT, int64_t ldt,
                                                           GradOut gout_g, GradOut gout_b, float tscale) {
+  static_assert(G == 1 || SMALL, "groups of nodes only on the register-resident path");
   __shared__ float red[RL][CB + 1];
   __shared__ __attribute__((aligned(16))) bf16_t tile[CB][RCH + 8];
   const int tx = threadIdx.x % CB, ty = threadIdx.x / CB;
@@ -184,80 +199,96 @@ __global__ __launch_bounds__(256) void bn_relu_bwd_kernel(float* __restrict__ da
   const int c = c0 + tx;
   const bool live = c < C;
   const bool bn = gamma != nullptr;
-  float g = 1.f, b = 0.f, mean = 0.f, rstd = 1.f;
+  float g = 1.f, b = 0.f, mean[G], rstd[G];
+#pragma unroll
+  for (int n = 0; n < G; ++n) { mean[n] = 0.f; rstd[n] = 1.f; }
   if (live && bn) {
     g = gamma[c]; b = beta[c];
     if (round_params) { g = round_bf16(g); b = round_bf16(b); }
-    mean = mean_in[c]; rstd = rstd_in[c];
+#pragma unroll
+    for (int n = 0; n < G; ++n) { mean[n] = mean_in[(int64_t)n * C + c]; rstd[n] = rstd_in[(int64_t)n * C + c]; }
   }
-  // pass 1: sum dout*xhat, sum dout  (dout = da where the ReLU was open)
-  float xr[RPT], dr[RPT];
-  float sg = 0.f, sb = 0.f;
+  float xr[G][RPT], dr[G][RPT];
   if (SMALL) {
     // loads at clamped (always valid) addresses first, all in flight together; selection after
     const int cc = min(c, C - 1);
 #pragma unroll
-    for (int k = 0; k < RPT; ++k) {
-      const int rc = min(ty + RL * k, R - 1);
-      xr[k] = z[(int64_t)rc * ldz + cc];
-      dr[k] = sum_slabs<NS>(dap, slab, (int64_t)rc * ldda + cc);
-    }
+    for (int n = 0; n < G; ++n)
 #pragma unroll
-    for (int k = 0; k < RPT; ++k) {
-      const int r = ty + RL * k;
-      const float zz = xr[k];
-      const float xhat = (zz - mean) * rstd;
-      const float pre = bn ? fmaf(g, xhat, b) : zz;
-      const bool on = live && r < R;
-      xr[k] = on ? xhat : 0.f;
-      dr[k] = (on && pre > 0.f) ? dr[k] : 0.f;
-      sg = fmaf(dr[k], xr[k], sg);
-      sb += dr[k];
-    }
-  } else if (live) {
-    for (int r = ty; r < R; r += RL) {
-      float zz = z[(int64_t)r * ldz + c];
-      float xhat = (zz - mean) * rstd;
-      float pre = bn ? fmaf(g, xhat, b) : zz;
-      float d = sum_slabs<NS>(dap, slab, (int64_t)r * ldda + c);
-      float dout = pre > 0.f ? d : 0.f;
-      dap[(int64_t)r * ldda + c] = dout;   // keep the reduced, masked value in slab 0
-      sg = fmaf(dout, xhat, sg);
-      sb += dout;
-    }
-  }
-  sg = col_reduce(sg, red, tx, ty);
-  sb = col_reduce(sb, red, tx, ty);
-  if (live && ty == 0) {
-    if (bn) grad_store(gout_g, c, sg);
-    if (gout_b.dst) grad_store(gout_b, c, sb);
-  }
-  const float invR = 1.0f / (float)R;
-  const float kk = g * rstd;
-  // pass 2: dz (and its transposed copy)
-  for (int r0 = 0; r0 < R; r0 += RCH) {
-#pragma unroll
-    for (int k = 0; k < RPT; ++k) {
-      const int rl = ty + RL * k;
-      const int r = r0 + rl;
-      float v = 0.f;
-      if (live && r < R) {
-        float xhat, dout;
-        if (SMALL) {
-          xhat = xr[k]; dout = dr[k];
-        } else {
-          xhat = (z[(int64_t)r * ldz + c] - mean) * rstd;
-          dout = dap[(int64_t)r * ldda + c];           // written by this thread in pass 1
-        }
-        v = bn ? kk * (dout - sb * invR - xhat * sg * invR) : dout;
-        store_f(&dz[(int64_t)r * lddz + c], v);
+      for (int k = 0; k < RPT; ++k) {
+        const int rc = n * R + min(ty + RL * k, R - 1);
+        xr[n][k] = z[(int64_t)rc * ldz + cc];
+        dr[n][k] = sum_slabs<NS>(dap, slab, (int64_t)rc * ldda + cc);
       }
-      if (dzT) tile[tx][rl] = f32_to_bf16(v * tscale);
+  }
+  // the nodes of a group have one weight: their small-vector gradients are added up in node order
+  // and folded in once (what the staged path does with its staging vector, bit for bit)
+  float tg = 0.f, tb = 0.f;
+#pragma unroll
+  for (int n = 0; n < G; ++n) {
+    const int rb = n * R;
+    // pass 1: sum dout*xhat, sum dout  (dout = da where the ReLU was open)
+    float sg = 0.f, sb = 0.f;
+    if (SMALL) {
+#pragma unroll
+      for (int k = 0; k < RPT; ++k) {
+        const int r = ty + RL * k;
+        const float zz = xr[n][k];
+        const float xhat = (zz - mean[n]) * rstd[n];
+        const float pre = bn ? fmaf(g, xhat, b) : zz;
+        const bool on = live && r < R;
+        xr[n][k] = on ? xhat : 0.f;
+        dr[n][k] = (on && pre > 0.f) ? dr[n][k] : 0.f;
+        sg = fmaf(dr[n][k], xr[n][k], sg);
+        sb += dr[n][k];
+      }
+    } else if (live) {
+      for (int r = ty; r < R; r += RL) {
+        float zz = z[(int64_t)r * ldz + c];
+        float xhat = (zz - mean[n]) * rstd[n];
+        float pre = bn ? fmaf(g, xhat, b) : zz;
+        float d = sum_slabs<NS>(dap, slab, (int64_t)r * ldda + c);
+        float dout = pre > 0.f ? d : 0.f;
+        dap[(int64_t)r * ldda + c] = dout;   // keep the reduced, masked value in slab 0
+        sg = fmaf(dout, xhat, sg);
+        sb += dout;
+      }
     }
-    if (dzT) {
-      __syncthreads();
-      store_transposed(tile, dzT, ldt, c0, C, r0, R);
-      __syncthreads();
+    sg = col_reduce(sg, red, tx, ty);
+    sb = col_reduce(sb, red, tx, ty);
+    tg = n ? tg + sg : sg;
+    tb = n ? tb + sb : sb;
+    if (n == G - 1 && live && ty == 0) {
+      if (bn) grad_store(gout_g, c, tg);
+      if (gout_b.dst) grad_store(gout_b, c, tb);
+    }
+    const float invR = 1.0f / (float)R;
+    const float kk = g * rstd[n];
+    // pass 2: dz (and its transposed copy)
+    for (int r0 = 0; r0 < R; r0 += RCH) {
+#pragma unroll
+      for (int k = 0; k < RPT; ++k) {
+        const int rl = ty + RL * k;
+        const int r = r0 + rl;
+        float v = 0.f;
+        if (live && r < R) {
+          float xhat, dout;
+          if (SMALL) {
+            xhat = xr[n][k]; dout = dr[n][k];
+          } else {
+            xhat = (z[(int64_t)r * ldz + c] - mean[n]) * rstd[n];
+            dout = dap[(int64_t)r * ldda + c];           // written by this thread in pass 1
+          }
+          v = bn ? kk * (dout - sb * invR - xhat * sg * invR) : dout;
+          store_f(&dz[(int64_t)(rb + r) * lddz + c], v);
+        }
+        if (dzT) tile[tx][rl] = f32_to_bf16(v * tscale);
+      }
+      if (dzT) {
+        __syncthreads();
+        store_transposed(tile, dzT + rb, ldt, c0, C, r0, R);
+        __syncthreads();
+      }
     }
   }
 }
@@ -316,19 +347,22 @@ int launch_bn_relu_fwd(const float* zp, int nsplit, int64_t slab, int64_t ldzp, 
                        const float* gamma, const float* beta, int round_params, float eps, float* z,
                        int64_t ldz, void* a, int64_t lda, int a_is_bf16, bf16_t* aT, int64_t ldt,
                        float* mean, float* rstd, float* run_mean, float* run_var, float run_mix,
-                       hipStream_t s) {
+                       hipStream_t s, int group) {
   if (R <= 0 || C <= 0 || nsplit < 1) return VF_EINVAL;
   if ((run_mean == nullptr) != (run_var == nullptr)) return VF_EINVAL;
   if (aT && ((ldt & 7) || !a_is_bf16)) return VF_EINVAL;
   const int grid = (C + CB - 1) / CB;
   const bool small = R <= RCH;
-#define VF_FWD2(TT, NS, SM)                                                                        \
-  bn_relu_fwd_kernel<TT, NS, SM><<<grid, 256, 0, s>>>(zp, slab, ldzp, R, C, gamma, beta, round_params, \
+  if (group != 1 && (!small || !a_is_bf16 || (group != 2 && group != 4) || (aT && (R & 7)))) return VF_EINVAL;
+#define VF_FWD2(TT, NS, SM, GG)                                                                    \
+  bn_relu_fwd_kernel<TT, NS, SM, GG><<<grid, 256, 0, s>>>(zp, slab, ldzp, R, C, gamma, beta, round_params, \
       eps, z, ldz, static_cast<TT*>(a), lda, aT, ldt, mean, rstd, run_mean, run_var, run_mix)
 #define VF_FWD(NS)                                                                                 \
   case NS:                                                                                         \
-    if (a_is_bf16) { if (small) VF_FWD2(bf16_t, NS, true); else VF_FWD2(bf16_t, NS, false); }      \
-    else           { if (small) VF_FWD2(float, NS, true);  else VF_FWD2(float, NS, false); }       \
+    if (group == 2) VF_FWD2(bf16_t, NS, true, 2);                                                  \
+    else if (group == 4) VF_FWD2(bf16_t, NS, true, 4);                                             \
+    else if (a_is_bf16) { if (small) VF_FWD2(bf16_t, NS, true, 1); else VF_FWD2(bf16_t, NS, false, 1); } \
+    else           { if (small) VF_FWD2(float, NS, true, 1);  else VF_FWD2(float, NS, false, 1); } \
     break;
   switch (nsplit) {
     VF_FWD(1) VF_FWD(2) VF_FWD(4) VF_FWD(8) VF_FWD(16) VF_FWD(32)
@@ -344,18 +378,21 @@ int launch_bn_relu_bwd(float* dap, int nsplit, int64_t slab, int64_t ldda, const
                        int64_t ldz, int R, int C, const float* gamma, const float* beta,
                        int round_params, const float* mean, const float* rstd, void* dz, int64_t lddz,
                        int dz_is_bf16, bf16_t* dzT, int64_t ldt, GradOut gout_g, GradOut gout_b,
-                       hipStream_t s, float tscale) {
+                       hipStream_t s, float tscale, int group) {
   if (R <= 0 || C <= 0 || nsplit < 1) return VF_EINVAL;
   if (dzT && ((ldt & 7) || !dz_is_bf16)) return VF_EINVAL;
   const int grid = (C + CB - 1) / CB;
   const bool small = R <= RCH;
-#define VF_BWD2(TT, NS, SM)                                                                        \
-  bn_relu_bwd_kernel<TT, NS, SM><<<grid, 256, 0, s>>>(dap, slab, ldda, z, ldz, R, C, gamma, beta,  \
+  if (group != 1 && (!small || !dz_is_bf16 || (group != 2 && group != 4) || (dzT && (R & 7)))) return VF_EINVAL;
+#define VF_BWD2(TT, NS, SM, GG)                                                                    \
+  bn_relu_bwd_kernel<TT, NS, SM, GG><<<grid, 256, 0, s>>>(dap, slab, ldda, z, ldz, R, C, gamma, beta,  \
       round_params, mean, rstd, static_cast<TT*>(dz), lddz, dzT, ldt, gout_g, gout_b, tscale)
 #define VF_BWD(NS)                                                                                 \
   case NS:                                                                                         \
-    if (dz_is_bf16) { if (small) VF_BWD2(bf16_t, NS, true); else VF_BWD2(bf16_t, NS, false); }     \
-    else            { if (small) VF_BWD2(float, NS, true);  else VF_BWD2(float, NS, false); }      \
+    if (group == 2) VF_BWD2(bf16_t, NS, true, 2);                                                  \
+    else if (group == 4) VF_BWD2(bf16_t, NS, true, 4);                                             \
+    else if (dz_is_bf16) { if (small) VF_BWD2(bf16_t, NS, true, 1); else VF_BWD2(bf16_t, NS, false, 1); } \
+    else            { if (small) VF_BWD2(float, NS, true, 1);  else VF_BWD2(float, NS, false, 1); } \
     break;
   switch (nsplit) {
     VF_BWD(1) VF_BWD(2) VF_BWD(4) VF_BWD(8) VF_BWD(16) VF_BWD(32)

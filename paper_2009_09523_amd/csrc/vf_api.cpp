@@ -39,6 +39,7 @@ int validate_config(const vf_config& c) {
   if (c.max_node_size > c.max_batch) return VF_EINVAL;
   if (!(c.bn_momentum >= 0.f && c.bn_momentum <= 1.f)) return VF_EINVAL;
   if (c.fold_window < 0 || c.fold_window > kFoldMax) return VF_EINVAL;
+  if (c.node_group != 0 && c.node_group != 1 && c.node_group != 2 && c.node_group != 4) return VF_EINVAL;
   if (c.model_kind == VF_MLP) {
     if (c.n_dims < 2 || c.n_dims > VF_MAX_DIMS) return VF_EINVAL;
     for (int i = 0; i < c.n_dims; ++i)
@@ -53,7 +54,7 @@ int validate_config(const vf_config& c) {
       return VF_EINVAL;
     if (c.d_model % c.n_heads) return VF_EINVAL;
     if (c.d_model > 1024) return VF_EINVAL;                       // LayerNorm kernels keep a row in registers
-    if ((int64_t)c.max_node_size * c.seq_len > 65536) return VF_EINVAL;   // token bitmap of the embedding backward
+    if ((int64_t)c.max_node_size * std::max(1, c.node_group) * c.seq_len > 65536) return VF_EINVAL;   // token bitmap of the embedding backward
     if (c.n_masked > c.seq_len) return VF_EINVAL;
     if (c.dtype == VF_BF16 && ((c.d_model % 8) || (c.d_ffn % 8) || ((c.d_model / c.n_heads) % 8)))
       return VF_EINVAL;
@@ -69,7 +70,8 @@ int validate_config(const vf_config& c) {
 }
 
 bool set_matches(const Ctx::GraphSet& g, const StepArgs& a) {
-  return !g.graphs.empty() && g.params == a.params && g.x == a.x && g.y == a.y && g.sizes == a.sizes;
+  return !g.graphs.empty() && g.params == a.params && g.x == a.x && g.y == a.y && g.sizes == a.sizes &&
+         g.seg == a.seg;
 }
 
 // Selects the captured set that fits this call, if there is one.
@@ -203,7 +205,7 @@ int capture_whole_step(Ctx& c, const StepArgs& a) {
     c.gs().graphs.clear();
     return rc;
   }
-  c.gs().params = a.params; c.gs().x = a.x; c.gs().y = a.y; c.gs().sizes = a.sizes;
+  c.gs().params = a.params; c.gs().x = a.x; c.gs().y = a.y; c.gs().sizes = a.sizes; c.gs().seg = a.seg;
   return VF_OK;
 }
 
@@ -222,7 +224,7 @@ int capture_graphs(Ctx& c, const StepArgs& a) {
     drop_graph(c);
     return rc;
   }
-  c.gs().params = a.params; c.gs().x = a.x; c.gs().y = a.y; c.gs().sizes = a.sizes;
+  c.gs().params = a.params; c.gs().x = a.x; c.gs().y = a.y; c.gs().sizes = a.sizes; c.gs().seg = a.seg;
   return VF_OK;
 }
 
@@ -398,6 +400,7 @@ int vf_init(const vf_config* cfg, vf_ctx** out) {
   c.model = cfg->model_kind == VF_MLP ? make_mlp(*cfg) : cfg->model_kind == VF_CONV ? make_conv(*cfg) : make_encoder(*cfg);
   if (!c.model) { delete h; return VF_EINVAL; }
   c.P = c.model->num_params();
+  c.group = std::max(1, cfg->node_group);
   // Overlap needs a capturable main stream and a model that double-buffers what the side
   // stream reads (the bf16 MLP and the bf16 encoder do).
   c.overlap = c.stream != nullptr && (cfg->flags & VF_FLAG_OVERLAP) && c.model->supports_overlap();
@@ -428,7 +431,7 @@ int vf_init(const vf_config* cfg, vf_ctx** out) {
   if (cfg->optimizer == VF_ADAM) arena.request(&c.opt1, (size_t)c.P);
   // per-row losses: of the whole batch (MLP: reduced once, after the last node's forward pass)
   size_t loss_rows = (size_t)cfg->max_batch;
-  if (cfg->model_kind == VF_ENCODER) loss_rows = (size_t)cfg->max_node_size * (size_t)cfg->n_masked;
+  if (cfg->model_kind == VF_ENCODER) loss_rows = (size_t)cfg->max_node_size * c.group * (size_t)cfg->n_masked;
   arena.request(&c.rowloss, loss_rows);
   arena.request(&c.node_loss, (size_t)cfg->max_nodes);
   arena.request(&c.loss_total, 1);
@@ -524,11 +527,29 @@ int vf_step(vf_ctx* h, void* params, const void* batch_x, const int32_t* batch_y
 
   StepArgs a;
   a.params = static_cast<float*>(params);
-  a.x = batch_x; a.y = batch_y; a.B = B; a.V = V;
-  a.sizes.assign(node_sizes, node_sizes + V);
-  a.off.resize(V + 1);
-  a.w.resize(V);
-  vf_partition(node_sizes, V, B, a.off.data(), a.w.data());
+  a.x = batch_x; a.y = batch_y; a.B = B;
+  a.nodes = V;
+  a.node_sizes.assign(node_sizes, node_sizes + V);
+  a.node_off.resize(V + 1);
+  a.node_w.resize(V);
+  vf_partition(node_sizes, V, B, a.node_off.data(), a.node_w.data());
+  // the units of the passes: the nodes, or runs of up to `group` equal-sized nodes (2 or 4 at a time)
+  for (int32_t i = 0; i < V;) {
+    int take = 1;
+    if (c.group > 1 && c.model->supports_group(node_sizes[i])) {
+      int run = 1;
+      while (i + run < V && run < c.group && node_sizes[i + run] == node_sizes[i]) ++run;
+      take = run >= 4 ? 4 : (run >= 2 ? 2 : 1);
+    }
+    a.sizes.push_back(take * node_sizes[i]);
+    a.seg.push_back(node_sizes[i]);
+    a.first.push_back(i);
+    i += take;
+  }
+  a.V = (int32_t)a.sizes.size();
+  a.off.resize(a.V + 1);
+  a.w.resize(a.V);
+  vf_partition(a.sizes.data(), a.V, B, a.off.data(), a.w.data());
 
   const bool use_graph = !((c.cfg.flags & VF_FLAG_NO_GRAPH) || c.prof.enabled);
   if (use_graph && !graph_matches(c, a)) VF_TRY(capture_graphs(c, a));

@@ -43,6 +43,12 @@ class Arena {
   size_t total_ = 0;
 };
 
+// What the passes of a step iterate over.  V, sizes, off, w describe the UNITS that go through the
+// passes one after another: the virtual nodes themselves, or -- with node_group > 1 -- groups of
+// consecutive equal-sized nodes taken together (sizes[i] rows = seg[i] rows per node times the
+// nodes in the group; w[i] = sizes[i] / B, the sum of its nodes' weights, so a unit's loss is the
+// mean over all its rows).  What stays per node reads seg[i] (BatchNorm statistics) and the node
+// lists (losses).
 struct StepArgs {
   float* params;
   const void* x;
@@ -50,6 +56,12 @@ struct StepArgs {
   int32_t B, V;
   std::vector<int32_t> sizes, off;
   std::vector<float> w;
+  std::vector<int32_t> seg;               // rows per node within unit i (== sizes[i] without groups)
+  std::vector<int32_t> first;             // index of unit i's first node
+  int32_t nodes;                          // the virtual nodes of the step ...
+  std::vector<int32_t> node_sizes, node_off;
+  std::vector<float> node_w;              // ... with their offsets and weights b_i/B
+  int group(int i) const { return sizes[i] / seg[i]; }
 };
 
 struct Ctx;
@@ -102,6 +114,8 @@ class Model {
   virtual void update_ranges(std::vector<UpdateRange>* out) const { out->clear(); }
   // Largest fold window the side part can take (it must keep that many nodes' operands).
   virtual int max_window() const { return 1; }
+  // Whether the passes take a group of equal-sized nodes of `rows` rows each as one unit.
+  virtual bool supports_group(int rows) const { (void)rows; return false; }
   // State that the passes themselves carry from step to step on this device (BatchNorm moving
   // mean and variance, Section 4.1): `state_floats` fp32 values at `state_ptr`, laid out as all
   // layers' means then all layers' variances; init_state sets the starting values.
@@ -161,6 +175,7 @@ struct Ctx {
   hipEvent_t side_done[2] = {nullptr, nullptr};  // side part of window w (parity) is complete
   hipEvent_t prep_done = nullptr;                // weight preparation
 
+  int group = 1;                          // consecutive equal-sized nodes taken through their passes together
   int window = 1;                         // nodes whose weight gradients are folded in one pass
   // copies of the side part's operands: one window's worth, and two with overlap at window 1
   int copies() const { return overlap ? std::max(2, window) : window; }
@@ -177,7 +192,7 @@ struct Ctx {
   // prefetching entry points do, replays instead of recapturing); `cur` is the one in use.
   struct GraphSet {
     std::vector<hipGraphExec_t> graphs;     // one graph, or [0] prepare, [1+2i] fwd(i), [2+2i] bwd(i), [1+2V+w] side(w)
-    std::vector<int32_t> sizes;
+    std::vector<int32_t> sizes, seg;
     const void* params = nullptr;
     const void* x = nullptr;
     const void* y = nullptr;

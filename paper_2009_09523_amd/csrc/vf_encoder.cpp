@@ -81,8 +81,11 @@ class Encoder final : public Model {
     lnf_g_ = off; off += d_; lnf_b_ = off; off += d_;
     lin(out_, d_, V_);
     P_ = off;
-    maxR_ = (int64_t)cfg.max_node_size * T_;
-    maxRm_ = (int64_t)cfg.max_node_size * m_;
+    // a unit of the passes is up to node_group nodes (their sequences are independent: only the
+    // loss bookkeeping tells them apart): every per-unit buffer is sized for that many sequences
+    max_seqs_ = cfg.max_node_size * std::max(1, cfg.node_group);
+    maxR_ = (int64_t)max_seqs_ * T_;
+    maxRm_ = (int64_t)max_seqs_ * m_;
     ldR_ = round8(maxR_);
     ldV_ = round8(V_);
     out_split_max_ = 32;
@@ -93,13 +96,14 @@ class Encoder final : public Model {
   }
 
   int64_t num_params() const override { return P_; }
+  bool supports_group(int) const override { return true; }
   // the forward part of the fp32 / non-MFMA attention path shares its score scratch with the backward part
   bool supports_overlap() const override { return bf16_ && mfma_attn_; }
 
   void request_buffers(Arena& a) override {
     const size_t esz = bf16_ ? 2 : 4;
     const size_t R = (size_t)maxR_, Rm = (size_t)maxRm_;
-    const size_t heads = (size_t)cfg_.max_node_size * nh_;
+    const size_t heads = (size_t)max_seqs_ * nh_;
     auto act = [&](void** p, size_t n) { a.request(reinterpret_cast<char**>(p), n * esz); };
     for (int q = 0; q < sets_; ++q) {
       for (Block& B : blocks_) {
@@ -144,6 +148,16 @@ class Encoder final : public Model {
       const size_t maxdim = (size_t)std::max(std::max(d_, f_), 3 * d_);
       a.request(&tA_, maxdim * ldR_);
       a.request(&tB_, std::max(maxdim * (size_t)ldR_, (size_t)V_ * round8(maxRm_)));
+      // contraction slabs of a weight gradient whose tile grid alone would leave most compute
+      // units idle (few output tiles, long contraction): one set per stream that takes such products
+      wslab_elems_ = 0;
+      for (const Lin* L : lins_)
+        if (L != &out_)
+          wslab_elems_ = std::max(wslab_elems_, (size_t)gemm_bf16_pick_split(L->K, L->N, (int)maxR_) * L->K * L->N);
+      if (wslab_elems_) {
+        a.request(&wslab_[0], wslab_elems_);
+        if (sets_ == 2) a.request(&wslab_[1], wslab_elems_);
+      }
       if (sets_ == 2) {   // the deferred weight gradients run beside a backward part: scratch of their own
         a.request(&tA2_, (size_t)(f_ + 3 * d_) * ldR_);   // the four transposed inputs of a block side by side
         a.request(&tB2_, std::max(maxdim * (size_t)ldR_, (size_t)V_ * round8(maxRm_)));
@@ -230,7 +244,13 @@ class Encoder final : public Model {
                                                   cfg_.ln_eps, H.rows, d_, bf16_, H.meanf, H.rstdf, st));
     VF_TRY(lin_fwd(c, "gemm_head", out_, P, H.rows, d_, Rm, logits_, ldV_, false, nullptr));
     VF_KS(c, st, "softmax_xent", launch_softmax_xent(logits_, 1, 0, ldV_, logits_, ldV_, H.labels, Rm, V_, c.rowloss,
-                                                H.dlogits, ldV_, bf16_, nullptr, 0, w, i, c.node_loss, c.loss_total, st));
+                                                H.dlogits, ldV_, bf16_, nullptr, 0, w, i, nullptr, nullptr, st));
+    // loss bookkeeping per virtual node (Section 5.2), in node order
+    for (int j = 0; j < s.group(i); ++j) {
+      const int node = s.first[i] + j, rows = s.seg[i] * m_;
+      VF_KS(c, st, "loss_reduce", launch_loss_reduce(c.rowloss + (int64_t)j * rows, rows, s.node_w[node], node, c.node_loss,
+                                                     c.loss_total, st));
+    }
 
     return VF_OK;
   }
@@ -407,8 +427,21 @@ class Encoder final : public Model {
         VF_KS(c, stream_, "transpose", launch_transpose_bf16(static_cast<const bf16_t*>(in), ldin, sA_, ldr, R, L.K, stream_));
       if (!dy_transposed)
         VF_KS(c, stream_, "transpose", launch_transpose_bf16(static_cast<const bf16_t*>(dy), lddy, sB_, ldr, R, L.N, stream_));
-      VF_KS(c, stream_, tag, launch_gemm_bf16(inT ? inT : sA_, ldr, dy_transposed && dyT ? dyT : sB_, ldr, L.K, L.N, R, 1, 0, ep,
-                                              stream_));
+      const bf16_t* At = inT ? inT : sA_;
+      const bf16_t* Bt = dy_transposed && dyT ? dyT : sB_;
+      float* slabs = wslab_[sA_ == tA2_ && tA2_ ? 1 : 0];
+      const int64_t each = (int64_t)L.K * L.N;
+      int ns = (slabs && &L != &out_) ? gemm_bf16_pick_split(L.K, L.N, R) : 1;
+      while (ns > 1 && (size_t)ns * each > wslab_elems_) ns /= 2;
+      if (ns > 1) {
+        // slices of the contraction into slabs, added in slab order into the gradient
+        Epilogue es;
+        es.C = slabs; es.ldc = L.N;
+        VF_KS(c, stream_, tag, launch_gemm_bf16(At, ldr, Bt, ldr, L.K, L.N, R, ns, each, es, stream_));
+        VF_KS(c, stream_, "fold_slabs", launch_fold_slabs(slabs, ns, each, each, go, stream_));
+      } else {
+        VF_KS(c, stream_, tag, launch_gemm_bf16(At, ldr, Bt, ldr, L.K, L.N, R, 1, 0, ep, stream_));
+      }
     } else {
       VF_KS(c, stream_, tag, launch_gemm_f32(static_cast<const float*>(in), 1, ldin, static_cast<const float*>(dy), 1, lddy,
                                    L.K, L.N, R, 1, 0, ep, stream_));
@@ -488,6 +521,7 @@ class Encoder final : public Model {
   bool bf16_ = false;
   int d_ = 0, f_ = 0, T_ = 0, V_ = 0, m_ = 0, nh_ = 0, dh_ = 0;
   int64_t P_ = 0, tok_off_ = 0, pos_off_ = 0, lnf_g_ = 0, lnf_b_ = 0;
+  int max_seqs_ = 0;               // sequences of the largest unit of the passes
   int64_t maxR_ = 0, maxRm_ = 0, ldR_ = 0, ldV_ = 0;
   int out_split_max_ = 32;
   bool mfma_attn_ = false;              // fused matrix-core attention kernels apply
@@ -505,6 +539,8 @@ class Encoder final : public Model {
   FinishList fin_;                      // their finish steps of one node's backward pass, run as one launch
   bf16_t *tA_ = nullptr, *tB_ = nullptr;
   bf16_t *tA2_ = nullptr, *tB2_ = nullptr;   // the same scratch for weight gradients taken beside a backward part
+  float* wslab_[2] = {nullptr, nullptr};     // contraction slabs of weight gradients ([1]: those taken beside a backward part)
+  size_t wslab_elems_ = 0;
   bf16_t *sA_ = nullptr, *sB_ = nullptr;     // the scratch pair of the part being enqueued
 };
 

@@ -165,11 +165,15 @@ int launch_cast_bf16(const float* in, int64_t ldi, bf16_t* out, int64_t ldo, int
 // transposed, [C, ldt].  Saves mean, rstd.  With gamma == nullptr: a = relu(z).
 // run_mean / run_var (both or neither): moving statistics, blended in place with the pass's
 // own: run += run_mix * (stat - run), biased variance.
+// group = 2 or 4 (bf16, R <= 128, R a multiple of 8 when aT is given): the rows are `group` nodes
+// of R rows each, one after the other; statistics, the blend of the moving statistics and (in the
+// backward kernel) the small-vector gradients are taken per node in node order; mean and rstd
+// hold `group` vectors of C, the transposed copies node g's rows at columns g*R.
 int launch_bn_relu_fwd(const float* zp, int nsplit, int64_t slab, int64_t ldzp, int R, int C,
                        const float* gamma, const float* beta, int round_params, float eps, float* z,
                        int64_t ldz, void* a, int64_t lda, int a_is_bf16, bf16_t* aT, int64_t ldt,
                        float* mean, float* rstd, float* run_mean, float* run_var, float run_mix,
-                       hipStream_t s);
+                       hipStream_t s, int group = 1);
 // Backward of the above.  dap: nsplit partial slabs of the fp32 gradient w.r.t. a (slab 0 is
 // overwritten when nsplit > 1).  Writes dz (T), dzT (optional, bf16, [C, ldt]) and, with
 // BatchNorm, dgamma/dbeta through GradOut; without BatchNorm (gamma == nullptr) the bias
@@ -179,7 +183,7 @@ int launch_bn_relu_bwd(float* dap, int nsplit, int64_t slab, int64_t ldda, const
                        int64_t ldz, int R, int C, const float* gamma, const float* beta,
                        int round_params, const float* mean, const float* rstd, void* dz, int64_t lddz,
                        int dz_is_bf16, bf16_t* dzT, int64_t ldt, GradOut gout_g, GradOut gout_b,
-                       hipStream_t s, float tscale = 1.f);
+                       hipStream_t s, float tscale = 1.f, int group = 1);
 // out[r] = sum_c x[r*ld + c] through GradOut (bias gradient from a transposed bf16 gradient)
 int launch_rowsum_bf16(const bf16_t* x, int64_t ld, int R, int C, GradOut out, hipStream_t s);
 // out[c] = sum_r x[r*ld + c] through GradOut (x is T)
@@ -294,7 +298,7 @@ int launch_layernorm_fwd(const float* x, int64_t ldx, const int32_t* row_map, in
                          int64_t ldy, int y_is_bf16, float* mean, float* rstd, hipStream_t s);
 // Row-chunked reductions: column sums use a scratch of kReduceChunks * columns floats, the
 // LayerNorm backward one of 2 * kLnChunks * d floats.
-constexpr int kReduceChunks = 64;
+constexpr int kReduceChunks = 128;
 constexpr int kLnChunks = 1024;
 // The second, small kernel of a row-chunked reduction (chunk partials of a column added in a
 // fixed order, result through GradOut) can be put off: a launcher that is handed a FinishList and

@@ -41,6 +41,9 @@ class Mlp final : public Model {
  public:
   explicit Mlp(const vf_config& cfg) : cfg_(cfg) {
     bf16_ = cfg.dtype == VF_BF16;
+    // a unit of the passes is up to node_group nodes: every per-unit buffer is sized for that many rows
+    group_ = bf16_ ? std::max(1, cfg.node_group) : 1;
+    max_rows_ = cfg.max_node_size * group_;
     // as many copies of the weight-gradient operands as Ctx::copies() will ask for
     copies_ = std::max((cfg.flags & VF_FLAG_OVERLAP) ? 2 : 1, cfg.fold_window);
     const int nl = cfg.n_dims - 1;
@@ -63,15 +66,15 @@ class Mlp final : public Model {
     P_ = off;
     for (Layer& L : layers_)
       if (L.has_bn) { L.s_off = bn_width_; bn_width_ += L.N; }
-    ldb_ = round8(cfg.max_node_size);
+    ldb_ = round8(max_rows_);
     ldw_ = ldb_ * copies_;
     ordered_ = (cfg.flags & VF_FLAG_ORDERED_FOLD) != 0;
     // Scratch for GEMM outputs that arrive as partial slabs: the largest split * rows * ld
     // over the forward (N_l columns) and input-gradient (K_l columns) products.
     slab_elems_ = 0;
     for (const Layer& L : layers_) {
-      slab_elems_ = std::max(slab_elems_, slab_need(cfg.max_node_size, L.N, L.K, L.ld));
-      slab_elems_ = std::max(slab_elems_, slab_need(cfg.max_node_size, L.K, L.N, round8(L.K)));
+      slab_elems_ = std::max(slab_elems_, slab_need(max_rows_, L.N, L.K, L.ld));
+      slab_elems_ = std::max(slab_elems_, slab_need(max_rows_, L.K, L.N, round8(L.K)));
     }
   }
 
@@ -97,6 +100,9 @@ class Mlp final : public Model {
 
   int64_t num_params() const override { return P_; }
   bool supports_overlap() const override { return bf16_; }
+  // groups of nodes: the BatchNorm kernels keep a node of up to 128 rows in registers, and the
+  // transposed copies want node boundaries on 16-byte boundaries
+  bool supports_group(int rows) const override { return bf16_ && rows <= 128 && (rows & 7) == 0; }
   int max_window() const override { return bf16_ ? kFoldMax : 1; }
 
   // The side part finishes the layers from the last to the first; a layer's stretch of the
@@ -118,7 +124,7 @@ class Mlp final : public Model {
   }
 
   void request_buffers(Arena& a) override {
-    const size_t mb = (size_t)cfg_.max_node_size;
+    const size_t mb = (size_t)max_rows_;
     const size_t esz = bf16_ ? 2 : 4;
     const int sets = (bf16_ && (cfg_.flags & VF_FLAG_OVERLAP)) ? 2 : 1;
     for (Layer& L : layers_) {
@@ -126,8 +132,8 @@ class Mlp final : public Model {
         a.request(&L.z[q], mb * L.ld);
         if (q == 0 || !L.hidden) a.request(reinterpret_cast<char**>(&L.dz[q]), mb * L.ld * esz);
         if (L.hidden) {
-          a.request(&L.mean[q], (size_t)L.N);
-          a.request(&L.rstd[q], (size_t)L.N);
+          a.request(&L.mean[q], (size_t)L.N * group_);      // per node of a group
+          a.request(&L.rstd[q], (size_t)L.N * group_);
           a.request(reinterpret_cast<char**>(&L.a[q]), mb * L.ld * esz);
         }
       }
@@ -218,11 +224,12 @@ class Mlp final : public Model {
       else
         VF_KS(c, st, "gemm_fwd", launch_gemm_f32(static_cast<const float*>(in), ldin, 1, P + L.w_off, 1, L.N, b, L.N, L.K, split, slab, ep, st));
       if (L.hidden)
-        VF_KS(c, st, "bn_relu_fwd", launch_bn_relu_fwd(slab_buf, split, slab, L.ld, b, L.N,
+        VF_KS(c, st, "bn_relu_fwd", launch_bn_relu_fwd(slab_buf, split, slab, L.ld, s.seg[i], L.N,
                                        L.has_bn ? P + L.g_off : nullptr, L.has_bn ? P + L.be_off : nullptr,
                                        bf16_, cfg_.bn_eps, L.z[q], L.ld, L.a[q], L.ld, bf16_, bf16_ ? L.aT + pc : nullptr, ldw_,
                                        L.mean[q], L.rstd[q], L.has_bn ? state_ + L.s_off : nullptr,
-                                       L.has_bn ? state_ + bn_width_ + L.s_off : nullptr, cfg_.bn_momentum, st));
+                                       L.has_bn ? state_ + bn_width_ + L.s_off : nullptr, cfg_.bn_momentum, st,
+                                       s.group(i)));
       else
         VF_KS(c, st, "softmax_xent", launch_softmax_xent(slab_buf, split, slab, L.ld, L.z[q], L.ld, y, b, L.N,
                                                          c.rowloss + row0, L.dz[q], L.ld, bf16_, bf16_ ? L.dzT + pc : nullptr, ldw_, w, i,
@@ -232,12 +239,12 @@ class Mlp final : public Model {
     // loss bookkeeping of the whole step after the last node's rows are in: node losses and
     // their weighted sum (Section 5.2), in node order
     if (i == s.V - 1) {
-      for (int first = 0; first < s.V; first += kLossNodes) {
+      for (int first = 0; first < s.nodes; first += kLossNodes) {
         LossNodes ln{};
         ln.first = first;
-        ln.count = std::min(kLossNodes, s.V - first);
+        ln.count = std::min(kLossNodes, s.nodes - first);
         for (int j = 0; j < ln.count; ++j) {
-          ln.off[j] = s.off[first + j]; ln.rows[j] = s.sizes[first + j]; ln.w[j] = s.w[first + j];
+          ln.off[j] = s.node_off[first + j]; ln.rows[j] = s.node_sizes[first + j]; ln.w[j] = s.node_w[first + j];
         }
         VF_KS(c, st, "loss_reduce", launch_loss_reduce_nodes(c.rowloss, ln, c.node_loss, c.loss_total, st));
       }
@@ -271,10 +278,10 @@ class Mlp final : public Model {
         VF_KS(c, st, "gemm_dgrad", launch_gemm_f32(static_cast<const float*>(dz_in), L.ld, 1, P + L.w_off, L.N, 1, b, L.K, L.N, split, slab, ed, st));
       GradOut gg = Pv.has_bn ? c.gout(Pv.g_off, w, i) : GradOut{nullptr, 0.f, 0};
       GradOut gb = c.gout(Pv.has_bn ? Pv.be_off : Pv.b_off, w, i);
-      VF_KS(c, st, "bn_relu_bwd", launch_bn_relu_bwd(slab_buf, split, slab, Pv.ld, Pv.z[q], Pv.ld, b, Pv.N,
+      VF_KS(c, st, "bn_relu_bwd", launch_bn_relu_bwd(slab_buf, split, slab, Pv.ld, Pv.z[q], Pv.ld, s.seg[i], Pv.N,
                                      Pv.has_bn ? P + Pv.g_off : nullptr, Pv.has_bn ? P + Pv.be_off : nullptr,
                                      bf16_, Pv.mean[q], Pv.rstd[q], Pv.dz[0], Pv.ld, bf16_, bf16_ ? Pv.dzT + pc : nullptr, ldw_,
-                                     gg, gb, st, tscale(c, s, i)));
+                                     gg, gb, st, tscale(c, s, i), s.group(i)));
     }
     return VF_OK;
   }
@@ -448,6 +455,8 @@ class Mlp final : public Model {
   bf16_t* xT_ = nullptr;           // the batch rows of the nodes in flight, transposed [D, ldw_]
   int64_t ldw_ = 0;                // leading dim of the wide transposed operands: copies_ * ldb_
   bool ordered_ = false;           // VF_FLAG_ORDERED_FOLD
+  int group_ = 1;                  // nodes per unit of the passes (vf_config::node_group)
+  int max_rows_ = 0;               // rows of the largest unit
   hipEvent_t cast_done_[VF_MAX_DIMS] = {};   // prepare_split: layer l's bf16 weight copies are written
   bool wait_casts_ = false;                  // the next forward part waits for them
   mutable std::vector<int> range_layer_;   // update_ranges: the layer that completes stretch k

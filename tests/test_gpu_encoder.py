@@ -90,10 +90,30 @@ def test_c4_full_size():
     print("full size C4", flush=True)
     wl, theta, x, y = _case("C4", jitter=0.0)
     ref = oracle_steps(wl, theta, x, y)
-    for flags in (0, FUSED | OVERLAP | NO_GRAPH):      # the second is what bench.py times
-        print(f"flags {flags}", flush=True)
-        gpu = run_gpu(wl, theta, x, y, flags=flags)
+    for flags, group in ((0, 0), (FUSED | OVERLAP | NO_GRAPH, 4)):      # the second is what bench.py times
+        print(f"flags {flags} group {group}", flush=True)
+        gpu = run_gpu(wl, theta, x, y, flags=flags, node_group=group)
         check_against_oracle(wl, gpu, ref)
         check_update_from_own_gradient(wl, gpu, theta, tol=1e-4)
     # the bound that does not depend on where operands are rounded
     check_independent_bound(wl, gpu["G"], ref["G"], weights_only_gradient(wl, theta, x, y), "C4")
+
+
+@pytest.mark.parametrize("group", [2, 4])
+@pytest.mark.parametrize("name,sizes", [("enc_small_bf16", [2, 2, 2, 1, 1, 1]), ("enc_small_f32", [1] * 9),
+                                        ("enc_mid_bf16", [1, 1, 1, 1, 1])])
+def test_encoder_node_groups_match_the_oracle(name, sizes, group):
+    """Groups of equal-sized nodes as one unit of the passes (the sequences of an encoder node are
+    independent: only the loss bookkeeping tells the nodes apart): per-node losses and the combined
+    gradient against the oracle, one and two streams bitwise equal."""
+    wl, theta, x, y = _case(name)
+    assert sum(sizes) == wl.batch
+    ref = oracle_steps(wl, theta, x, y, node_sizes=sizes)
+    base = None
+    for flags in (FUSED, FUSED | NO_GRAPH, FUSED | OVERLAP | NO_GRAPH, 0):
+        gpu = run_gpu(wl, theta, x, y, node_sizes=sizes, flags=flags, node_group=group)
+        check_against_oracle(wl, gpu, ref)
+        if base is None:
+            base = gpu
+        assert gpu["G"].tobytes() == base["G"].tobytes(), flags
+        assert gpu["node_losses"].tobytes() == base["node_losses"].tobytes(), flags

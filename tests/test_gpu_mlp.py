@@ -127,14 +127,18 @@ def test_rejected_step_leaves_state_untouched():
 BENCH = FUSED | NO_GRAPH | 4        # what bench.py times: fused fold, two streams, eager launches, window 8
 
 
-@pytest.mark.parametrize("name,flags,window", [("C2", BENCH, 8), ("C3", BENCH, 8), ("C2", 0, 0), ("C3", FUSED, 0)])
-def test_full_size_configurations(name, flags, window):
-    """The benchmark configuration (C2) and the heterogeneous split (C3) at full size, in the
-    launch configuration bench.py times (and in the plain staged / fused ones), every gradient
-    entry against the oracle."""
-    print(f"full size {name} flags={flags} window={window}", flush=True)
+BENCH_GROUP = 4                     # ... and up to 4 equal-sized nodes through their passes together
+
+
+@pytest.mark.parametrize("name,flags,window,group", [("C2", BENCH, 8, BENCH_GROUP), ("C3", BENCH, 8, BENCH_GROUP),
+                                                     ("C2", BENCH, 8, 1), ("C2", 0, 0, 0), ("C3", FUSED, 0, 0)])
+def test_full_size_configurations(name, flags, window, group):
+    """The 8 x 128 configuration (C2) and the heterogeneous split (C3) at full size, in the
+    launch configuration bench.py times (and node after node, and in the plain staged / fused
+    modes), every gradient entry against the oracle."""
+    print(f"full size {name} flags={flags} window={window} group={group}", flush=True)
     wl, theta, x, y = _case(name, jitter=0.0)
-    gpu = run_gpu(wl, theta, x, y, flags=flags, fold_window=window)
+    gpu = run_gpu(wl, theta, x, y, flags=flags, fold_window=window, node_group=group)
     ref = oracle_steps(wl, theta, x, y)
     check_against_oracle(wl, gpu, ref)
     check_update_from_own_gradient(wl, gpu, theta)
@@ -142,14 +146,14 @@ def test_full_size_configurations(name, flags, window):
     import paper_2009_09523_amd as vf
     off2, w2 = vf.vf_partition(wl.node_sizes, wl.batch)
     assert off.tobytes() == off2.tobytes() and w.tobytes() == w2.tobytes()
-    if flags == BENCH:
+    if flags == BENCH and group == BENCH_GROUP:
         check_independent_bound(wl, gpu["G"], ref["G"], weights_only_gradient(wl, theta, x, y), name)
 
 
 def test_c5_full_size_launch_configuration():
     """Large-batch emulation: MLP 2048-8192x6-1000 + BatchNorm, 64 nodes of 128 (B = 8192), in the
-    launch configuration bench.py times (fused fold, two streams, launches one by one, eight
-    windows of 8 nodes).  The oracle can afford single nodes of this model: it evaluates the four
+    launch configuration bench.py times (fused fold, two streams, launches one by one, groups
+    of 4 nodes per pass, windows of 8 groups).  The oracle can afford single nodes of this model: it evaluates the four
     distinct nodes 0..3, and the device runs V = 64 nodes of which node i holds the rows of node
     i mod 4 -- the combined gradient is then (g_0 + g_1 + g_2 + g_3)/4 (Section 5.2 with 64 weights
     of 1/64), every fold of step 3 and the update of step 5 run over all 64 nodes.
@@ -193,7 +197,7 @@ def test_c5_full_size_launch_configuration():
 
     xa = np.tile(x[:128 * K], (64 // K, 1))
     ya = np.tile(y[:128 * K], 64 // K)
-    gpu = run_gpu(wl, theta, xa, ya, flags=BENCH, fold_window=8)
+    gpu = run_gpu(wl, theta, xa, ya, flags=BENCH, fold_window=8, node_group=BENCH_GROUP)
     assert gpu["streams"] == 2
     assert abs(gpu["loss"] - Lw) <= 1e-3 * abs(Lw)
     np.testing.assert_allclose(gpu["node_losses"], np.tile(np.array(Ls), 64 // K), rtol=1e-3)
@@ -205,7 +209,9 @@ def test_c5_full_size_launch_configuration():
     G64 = gpu["G"].copy()
     del gpu, xa, ya
     # the same four nodes once: 64 folds of g/64 against 4 folds of g/4 (fp32 rounding only)
-    four = run_gpu(wl.with_nodes([128] * K), theta, x[:128 * K], y[:128 * K], flags=BENCH, fold_window=8)
+    # the same four nodes once (one group): 16 folds of g/16 against one fold of g (fp32 rounding only)
+    four = run_gpu(wl.with_nodes([128] * K), theta, x[:128 * K], y[:128 * K], flags=BENCH, fold_window=8,
+                   node_group=BENCH_GROUP)
     assert np.linalg.norm(G64 - four["G"]) <= 1e-6 * np.linalg.norm(four["G"])
     del four
     # the bound that does not depend on where operands are rounded (node 0 .. 3, weights only)
@@ -382,3 +388,44 @@ def test_changing_the_split_between_steps_replays_the_right_graph():
         return out
 
     assert run(FUSED).tobytes() == run(FUSED | NO_GRAPH).tobytes()
+
+
+# ---- node groups: consecutive equal-sized nodes through their passes together ---------------------
+
+@pytest.mark.parametrize("group", [2, 4])
+@pytest.mark.parametrize("name,sizes", [("mlp_mid_bn_bf16", [40] * 6), ("mlp_mid_bf16", [40] * 6),
+                                        ("mlp_mid_bn_bf16", [40, 40, 40, 16, 16, 8, 8, 8, 8, 56]),
+                                        ("mlp_mid_bn_bf16", [112, 112, 16])])
+def test_node_groups_match_the_oracle(name, sizes, group):
+    """Runs of equal-sized nodes taken 2 or 4 at a time (a run of 3 goes as 2 + 1, sizes that are
+    no multiple of 8 would go one by one), in every fold mode, on one and two streams, replayed and
+    launched one by one: BatchNorm statistics, node losses and the weights b_i/B stay per node, so
+    the oracle's node-by-node result must come out; the modes agree bitwise with one another."""
+    wl, theta, x, y = _case(name)
+    B = sum(sizes)
+    x, y = x[:B], y[:B]
+    ref = oracle_steps(wl, theta, x, y, node_sizes=sizes)
+    plain = run_gpu(wl, theta, x, y, node_sizes=sizes, flags=FUSED)
+    base = None
+    for flags, window in ((FUSED, 0), (FUSED | NO_GRAPH, 0), (FUSED | NO_GRAPH | OVERLAP, 0), (FUSED | OVERLAP, 0), (0, 0),
+                          (FUSED | ORDERED, 4)):
+        gpu = run_gpu(wl, theta, x, y, node_sizes=sizes, flags=flags, fold_window=window, node_group=group)
+        check_against_oracle(wl, gpu, ref)
+        np.testing.assert_allclose(gpu["node_losses"], plain["node_losses"], rtol=1e-5)
+        if base is None:
+            base = gpu
+        assert gpu["G"].tobytes() == base["G"].tobytes(), (flags, window)
+        assert gpu["theta"].tobytes() == base["theta"].tobytes(), (flags, window)
+    # a windowed product over groups against the oracle as well
+    gpu = run_gpu(wl, theta, x, y, node_sizes=sizes, flags=FUSED | NO_GRAPH | OVERLAP, fold_window=4, node_group=group)
+    check_against_oracle(wl, gpu, ref)
+    assert np.linalg.norm(gpu["G"] - plain["G"]) <= 2e-2 * np.linalg.norm(plain["G"])
+
+
+def test_node_groups_keep_the_workspace_independent_of_the_node_count():
+    wl, theta, x, y = _case("mlp_mid_bn_bf16")
+    few = run_gpu(wl, theta, x[:80], y[:80], node_sizes=[40, 40], flags=FUSED, node_group=4, max_node_size=40,
+                  max_batch=240, max_nodes=6)
+    many = run_gpu(wl, theta, x, y, node_sizes=[40] * 6, flags=FUSED, node_group=4, max_node_size=40,
+                   max_batch=240, max_nodes=6)
+    assert few["workspace_bytes"] == many["workspace_bytes"]

@@ -13,12 +13,12 @@ pytestmark = pytest.mark.gpu
 NO_GRAPH, FUSED = 2, 1
 
 
-def _engine(wl, flags=0):
+def _engine(wl, flags=0, node_group=0):
     import torch
     import paper_2009_09523_amd as vf
     from paper_2009_09523_amd.binding import config_from_workload
     stream = torch.cuda.Stream()
-    return vf.VirtualNodeStep(config_from_workload(wl, flags=flags, stream=stream)), stream
+    return vf.VirtualNodeStep(config_from_workload(wl, flags=flags, stream=stream, node_group=node_group)), stream
 
 
 def _setup(wl, jitter=0.1):
@@ -46,6 +46,25 @@ def test_moving_statistics_match_the_oracle_after_two_steps(name, flags):
     want_mean = np.concatenate(ref["state"]["bn_mean"])
     want_var = np.concatenate(ref["state"]["bn_var"])
     assert st["bn_mean"].size == want_mean.size == sum(wl.dims[1:-1])
+    assert np.max(np.abs(st["bn_mean"] - want_mean)) <= tol * np.max(np.abs(want_mean))
+    assert np.max(np.abs(st["bn_var"] - want_var)) <= tol * np.max(np.abs(want_var))
+
+
+@pytest.mark.parametrize("group", [2, 4])
+def test_moving_statistics_of_grouped_nodes_are_blended_node_after_node(group):
+    """Five equal nodes taken 2 or 4 at a time: every node still blends its own statistics into the
+    moving ones, in node order (Section 4.1), so the oracle's values come out."""
+    import paper_2009_09523_amd as vf
+    wl = I.workload("mlp_mid_bn_bf16").with_nodes([48] * 5)
+    theta, x, y, params, xt, yt = _setup(wl)
+    eng, stream = _engine(wl, FUSED, node_group=group)
+    for _ in range(2):
+        eng.step(params, xt, yt, list(wl.node_sizes))
+    st = vf.parse_state(eng.state_export(params))
+    eng.close()
+    ref = oracle_steps(wl, theta, x, y, steps=2)
+    want_mean, want_var = np.concatenate(ref["state"]["bn_mean"]), np.concatenate(ref["state"]["bn_var"])
+    tol = TOL[wl.dtype]
     assert np.max(np.abs(st["bn_mean"] - want_mean)) <= tol * np.max(np.abs(want_mean))
     assert np.max(np.abs(st["bn_var"] - want_var)) <= tol * np.max(np.abs(want_var))
 

@@ -27,7 +27,7 @@ def to_device_batch(wl, x, y, device="cuda"):
 
 
 def run_gpu(wl, theta, x, y, node_sizes=None, flags=0, steps=1, max_node_size=None, max_nodes=None,
-            max_batch=None, fold_window=0):
+            max_batch=None, fold_window=0, node_group=0):
     """Runs `steps` vf_step calls on the same batch; returns the results of the last one."""
     import torch
     import paper_2009_09523_amd as vf
@@ -37,7 +37,7 @@ def run_gpu(wl, theta, x, y, node_sizes=None, flags=0, steps=1, max_node_size=No
     cfg = config_from_workload(wl, flags=flags, stream=stream,
                                max_node_size=max_node_size or max(sizes),
                                max_nodes=max_nodes or len(sizes), max_batch=max_batch or sum(sizes),
-                               fold_window=fold_window)
+                               fold_window=fold_window, node_group=node_group)
     eng = vf.VirtualNodeStep(cfg)
     assert eng.num_params == theta.size
     params = torch.from_numpy(theta.astype(np.float32)).cuda()
