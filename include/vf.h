@@ -17,7 +17,8 @@
  *     "host" pointers are ordinary host memory;
  *   - the caller owns params, batch and output buffers; the library owns its context
  *     (workspace, gradient buffer, staging, optimizer state, bf16 weight copies), all
- *     allocated in vf_init and freed in vf_destroy; vf_step allocates nothing;
+ *     allocated in vf_init and freed in vf_destroy; vf_step allocates no device memory
+ *     (on the host it fills a few small vectors of node sizes, offsets and weights);
  *   - all device work is enqueued on the stream given in the configuration.
  *
  * Flat parameter layout (fp32, also the layout of vf_grads and vf_opt_state):
@@ -34,6 +35,28 @@
  *            beta1, filters2, gamma2, beta2 (block: convolution, BatchNorm, ReLU, convolution,
  *            BatchNorm, add the block's input, ReLU); then the classifier on the mean over the
  *            positions: W[width, classes], bias.
+ *
+ * Environment variables.  None is needed in normal use; the kernel choices change at most the
+ * order of floating-point sums inside a product, never which operation is computed.  They
+ * are read once per process, when the code that looks at them first runs.
+ *   debugging
+ *     VF_SYNC_EACH=all | tag[,tag...]   the host waits for the stream after every kernel launch
+ *                        (or after the launches with one of the named profile tags), so that a
+ *                        device error is reported by the launch that caused it
+ *     VF_ARENA_GUARD=<bytes>            leaves that many bytes (rounded down to 256), filled with a
+ *                        pattern that is no valid float, between the buffers of the workspace, so
+ *                        that a read past a buffer's end shows in the results
+ *   kernel selection, for measurements (every choice gives results that pass the same tests)
+ *     VF_GEMM_TILE=128x128|128x64|64x128|64x64|32x128   forces one tile of the general bf16 product
+ *     VF_GEMM_SHORTK=0     weight gradients go to the general kernel, not the short-contraction one
+ *     VF_GEMM_DL=0|3|4|5   LDS-direct product kernel off, or its ring depth (default 4)
+ *     VF_GEMM_PIPE=0..4    ring depth of the register-staged product kernel (default 3, 0 = off)
+ *     VF_GEMM_SPLIT_TARGET=<n>   workgroups a small product is sliced up to (default 256)
+ *     VF_GEMM_WIDE=0|1|128|256   256-row product kernel off / on (default) / with 128 or 256 columns
+ *     VF_GEMM_WIDE_V=<n>   another ring (depth, slice length) for the 256-row kernel
+ *     VF_CONV_LDS=0        3x3 convolutions without the filters-resident-in-LDS kernel
+ *     VF_CONV_EXPLICIT=1   convolutions always write the patch matrix and call the product kernel
+ *     VF_LN_WGS=<n>        workgroups of the LayerNorm backward kernel (default 256)
  */
 #ifndef VF_H
 #define VF_H
@@ -185,13 +208,16 @@ int vf_step(vf_ctx* ctx, void* params, const void* batch_x, const int32_t* batch
 int vf_prefetch(vf_ctx* ctx, const void* host_x, const int32_t* host_y, int32_t B);
 int vf_step_prefetched(vf_ctx* ctx, void* params, int32_t V, const int32_t* node_sizes);
 
-/* Combined gradient G = sum_i (b_i/B) g_i of the last step (the value the update used),
+/* Combined gradient G = sum_i (b_i/B) g_i of the last step (the value the update used): the
+ * node gradients folded with the size weights of Section 5.2, which make G the gradient over the
+ * whole batch also when the nodes differ in size (Section 3.2 step 3 has the fold itself),
  * fp32 [vf_num_params] copied to `out`, which may be a device or a host pointer.
  * Synchronises the stream.  VF_ESTATE before the first step. */
 int vf_grads(vf_ctx* ctx, float* out);
 
 /* Combined loss L = sum_i (b_i/B) L_i of the last step, L_i the mean loss over node i's
- * samples (encoder: over its masked positions).  out: host, one float.  Synchronises. */
+ * samples (encoder: over its masked positions); the weights are those of Section 5.2, so L is
+ * the mean over the batch for nodes of any sizes.  out: host, one float.  Synchronises. */
 int vf_loss(vf_ctx* ctx, float* out);
 
 /* Per-node mean losses L_i of the last step.  out: host, V floats (V of the last step). */
