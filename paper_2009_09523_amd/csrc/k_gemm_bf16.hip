@@ -539,8 +539,8 @@ __global__ __launch_bounds__(NT) void gemm_bf16_dl_kernel(const bf16_t* __restri
 // all banks.  A ring of NS stages: NS-1 stages are on their way while one is consumed, and a
 // stage's loads are not issued in one burst but spread over the MFMA steps of the stage before
 // (a wavefront never sits on a full memory queue with its matrix work waiting behind it).  What
-// matters is how long before its use a stage is requested: 256 x 256 tiles take stages of 32
-// (32 KB) so that four of them fit, 256 x 128 tiles three stages of 64 (48 KB).
+// matters is how long before its use a stage is requested: 256 x 256 tiles take three stages of 32
+// (32 KB each), 256 x 128 tiles three stages of 64 (48 KB each).
 // Workgroup numbering: XCD x (workgroup index modulo 8) takes a contiguous run of the tile order
 // "eight row tiles down, then one column right", so the 32 tiles that run side by side on one
 // XCD form an 8 x 4 block sharing 8 + 4 operand panels on that XCD's L2.
@@ -629,42 +629,81 @@ __global__ __launch_bounds__(512) void gemm_bf16_wide_kernel(const bf16_t* __res
   for (int j = 0; j < TN; ++j) { brow[j] = wn * (BN / 2) + j * 32 + (lane & 31); bsw[j] = wide_swizzle<KS>(brow[j]); }
 
   if (nstage > 0) {
+    // Schedule.  The fragments of a stage's first MFMA step are read one step EARLY, during the
+    // last step of the stage before: there the wavefront waits for the next stage's loads, meets
+    // the others at the barrier, issues those reads and only then starts the last step's MFMAs
+    // (whose operands are in registers already), so neither the barrier nor the LDS latency
+    // behind it leaves the matrix cores without queued work.  At that barrier every wavefront has
+    // read all of the current stage into registers, so its slot is free: the loads of the stage
+    // NS ahead go into it, half of them right there, half during the next step.
+    constexpr int H0 = LPS / 2;                        // loads issued behind the barrier
 #pragma unroll
     for (int s = 0; s < NS - 1; ++s)
 #pragma unroll
       for (int j = 0; j < LPS; ++j) issue_one(j, min(s, nstage - 1), s);
-    for (int it = 0; it < nstage; ++it) {
-      // loads complete in order: stage `it` has landed when at most NS-2 stages are outstanding
-      wait_loads_but<(NS - 2) * LPS>();
-      // every wave's part of stage `it` is in LDS and every wave is done reading stage it-1, whose
-      // slot the loads issued below overwrite
-      __builtin_amdgcn_s_barrier();
-      asm volatile("" ::: "memory");
-      const int nxt = min(it + NS - 1, nstage - 1), slot = (it + NS - 1) % NS;
-      const bf16_t* as = &lds_wide[(it % NS) * STAGE];
+    bf16x8 a[2][2], b[2][TN];
+    auto read_frags = [&](int stage, int kk, int buf) {
+      const bf16_t* as = &lds_wide[(stage % NS) * STAGE];
       const bf16_t* bs = as + ATILE;
-      bf16x8 a[2][2], b[2][TN];
-      auto read_frags = [&](int kk, int buf) {
-        const int cidx = 2 * kk + (lane >> 5);
+      const int cidx = 2 * kk + (lane >> 5);
 #pragma unroll
-        for (int i = 0; i < 2; ++i) a[buf][i] = *reinterpret_cast<const bf16x8*>(&as[arow[i] * KS + ((cidx ^ asw[i]) * 8)]);
+      for (int i = 0; i < 2; ++i) a[buf][i] = *reinterpret_cast<const bf16x8*>(&as[arow[i] * KS + ((cidx ^ asw[i]) * 8)]);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) b[buf][j] = *reinterpret_cast<const bf16x8*>(&bs[brow[j] * KS + ((cidx ^ bsw[j]) * 8)]);
-      };
-      read_frags(0, 0);
+      for (int j = 0; j < TN; ++j) b[buf][j] = *reinterpret_cast<const bf16x8*>(&bs[brow[j] * KS + ((cidx ^ bsw[j]) * 8)]);
+    };
+    // Names a buffer's fragments as used.  The compiler puts its wait for their LDS reads in front
+    // of the first use, and with LDS-direct loads in flight that wait is always "all LDS reads"; so
+    // the first use is placed BEFORE the next fragments' reads are issued, which leaves those a whole
+    // MFMA step to arrive (placed behind them, every step would wait for the reads it just issued).
+    auto arrived = [&](int buf) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i) asm volatile("" : "+v"(a[buf][i]));
+#pragma unroll
+      for (int j = 0; j < TN; ++j) asm volatile("" : "+v"(b[buf][j]));
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    auto mfmas = [&](int buf) {
+      __builtin_amdgcn_sched_barrier(0);      // the reads and loads issued before stay ahead of the MFMAs
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[buf][i], b[buf][j], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    // stage 0 has landed when at most NS-2 stages are outstanding (loads complete in order)
+    wait_loads_but<(NS - 2) * LPS>();
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    read_frags(0, 0, 0);
+    // the last ring slot is still empty: stage NS-1 goes there (first half now, second half in step 0)
+#pragma unroll
+    for (int j = 0; j < H0; ++j) issue_one(j, min(NS - 1, nstage - 1), NS - 1);
+    for (int it = 0; it < nstage; ++it) {
+      // the stage whose loads are being issued while stage `it` is consumed, and its slot
+      const int cur_ld = min(it + NS - 1, nstage - 1), cur_slot = (it + NS - 1) % NS;
+      const int nxt_ld = min(it + NS, nstage - 1), nxt_slot = it % NS;
 #pragma unroll
       for (int kk = 0; kk < STEPS; ++kk) {
-        if (kk + 1 < STEPS) read_frags(kk + 1, (kk + 1) & 1);
-        // a share of the loads of the stage NS-1 ahead per MFMA step
+        arrived(kk & 1);
+        if (kk + 1 < STEPS) {
+          read_frags(it, kk + 1, (kk + 1) & 1);
+          // the second half of the loads of stage it+NS-1, spread over the steps before the last
 #pragma unroll
-        for (int j = kk * LPS / STEPS; j < (kk + 1) * LPS / STEPS; ++j) issue_one(j, nxt, slot);
-        __builtin_amdgcn_sched_barrier(0);      // the reads above stay ahead of the MFMAs below
+          for (int j = H0 + kk * (LPS - H0) / (STEPS - 1); j < H0 + (kk + 1) * (LPS - H0) / (STEPS - 1); ++j)
+            issue_one(j, cur_ld, cur_slot);
+        } else if (it + 1 < nstage) {
+          // everything of stage it+1 must have landed: outstanding may be the stages it+2 .. it+NS-1
+          wait_loads_but<(NS - 2) * LPS>();
+          // (this wavefront's reads of stage `it` have all returned: its last fragments were named
+          // as used above, and LDS reads return in order)
+          __builtin_amdgcn_s_barrier();
+          asm volatile("" ::: "memory");
+          read_frags(it + 1, 0, 0);
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-          for (int j = 0; j < TN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk & 1][i], b[kk & 1][j], acc[i][j], 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
+          for (int j = 0; j < H0; ++j) issue_one(j, nxt_ld, nxt_slot);
+        }
+        mfmas(kk & 1);
       }
     }
     wait_loads_but<0>();
@@ -1215,11 +1254,13 @@ int launch_wide(const Shape& g, const Epilogue& ep, hipStream_t s) {
     switch (wide_variant()) {
       case 1: return launch_wide_cfg<256, 64, 2>(g, ep, s);
       case 2: return launch_wide_cfg<256, 32, 5>(g, ep, s);
-      case 3: return launch_wide_cfg<256, 32, 3>(g, ep, s);
-      default: return launch_wide_cfg<256, 32, 4>(g, ep, s);
+      case 3: return launch_wide_cfg<256, 32, 4>(g, ep, s);
+      default: return launch_wide_cfg<256, 32, 3>(g, ep, s);   // measured best on every shape tried (4 and 5 stages: 3 to 8 % slower)
     }
   }
   if (wide_variant() == 4) return launch_wide_cfg<128, 32, 6>(g, ep, s);
+  if (wide_variant() == 5) return launch_wide_cfg<128, 64, 2>(g, ep, s);
+  if (wide_variant() == 6) return launch_wide_cfg<128, 32, 4>(g, ep, s);
   return launch_wide_cfg<128, 64, 3>(g, ep, s);
 }
 }  // namespace

@@ -57,6 +57,18 @@ __device__ __forceinline__ void store_transposed(const bf16_t (*tile)[RCH + 8], 
         *reinterpret_cast<const uint4*>(&tile[col][rl]);
 }
 
+// Which block of CB columns workgroup b takes.  A block of 16 columns is half a 128-byte line of
+// an fp32 row and a quarter of a line of a bf16 row, and workgroups are dealt to the eight XCDs
+// (each with an L2 of its own) in turn, so with the identity mapping the parts of one line are
+// fetched into, and written back from, several L2s: the hardware counters showed twice the
+// algorithmic bytes fetched.  Within every whole group of 32 blocks, the four workgroups that one
+// XCD receives in a row (b, b+8, b+16, b+24) take four neighbouring blocks instead.
+__device__ __forceinline__ int xcd_column_block(int b, int nblocks) {
+  if (b >= (nblocks & ~31)) return b;
+  const int q = b >> 3, x = b & 7;
+  return (q >> 2) * 32 + x * 4 + (q & 3);
+}
+
 // SMALL: R <= RCH, rows live in registers.
 // G > 1 (SMALL only): the rows are G virtual nodes of R rows each, one after the other (a group of
 // equal-sized nodes whose products were taken as one): statistics, normalisation and the moving
@@ -80,7 +92,7 @@ __global__ __launch_bounds__(256) void bn_relu_fwd_kernel(const float* __restric
   __shared__ float red[RL][CB + 1];
   __shared__ __attribute__((aligned(16))) bf16_t tile[CB][RCH + 8];
   const int tx = threadIdx.x % CB, ty = threadIdx.x / CB;
-  const int c0 = blockIdx.x * CB;
+  const int c0 = xcd_column_block(blockIdx.x, gridDim.x) * CB;
   const int c = c0 + tx;
   const bool live = c < C;
   const bool bn = gamma != nullptr;
@@ -195,7 +207,7 @@ __global__ __launch_bounds__(256) void bn_relu_bwd_kernel(float* __restrict__ da
   __shared__ float red[RL][CB + 1];
   __shared__ __attribute__((aligned(16))) bf16_t tile[CB][RCH + 8];
   const int tx = threadIdx.x % CB, ty = threadIdx.x / CB;
-  const int c0 = blockIdx.x * CB;
+  const int c0 = xcd_column_block(blockIdx.x, gridDim.x) * CB;
   const int c = c0 + tx;
   const bool live = c < C;
   const bool bn = gamma != nullptr;
