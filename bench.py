@@ -33,10 +33,10 @@ def algorithmic_work(wl, P, fused=False, window=1, group=1):
     V, B = wl.n_nodes, wl.batch
     esz = 2 if wl.dtype == "bf16" else 4
     work = {} if fused else {"accumulate": ((12 * V - 4) * P, 2 * V * P, V)}
-    # With node groups a launch takes `group` nodes at once.  The bytes stay the method's: every
-    # node streams the weights once (Section 3.2: the nodes run one after another), so a launch
-    # that serves several nodes is credited with the stream of each of them -- what the kernel
-    # really reads is the counter figure `traffic`.
+    # With node groups a launch takes a unit of several nodes at once and needs the weights once:
+    # the bytes counted are those of the launches as they are made (weights once per unit), not
+    # the node-by-node stream of Section 3.2 (weights once per node), which a grouped launch does
+    # not perform -- credited with it, a launch would "exceed" the HBM peak.
     U = pass_units(wl, group)                     # units that go through the passes
     nwin = -(-U // window) if fused else V        # passes over the gradient buffer per step
     wg = (8 * nwin - 4) if fused else 4 * V       # fp32 bytes per matrix entry per step
@@ -48,8 +48,8 @@ def algorithmic_work(wl, P, fused=False, window=1, group=1):
         fwd_fl = 2 * B * W
         dgr_fl = 2 * B * sum(k * n for k, n in mats[1:])
         act = sum(b * (k * esz + n * 4) for b in wl.node_sizes for k, n in mats)
-        work["gemm_fwd"] = (V * W * esz + act, fwd_fl, U * len(mats))
-        work["gemm_dgrad"] = (V * sum(k * n for k, n in mats[1:]) * esz + act, dgr_fl, U * (len(mats) - 1))
+        work["gemm_fwd"] = (U * W * esz + act, fwd_fl, U * len(mats))
+        work["gemm_dgrad"] = (U * sum(k * n for k, n in mats[1:]) * esz + act, dgr_fl, U * (len(mats) - 1))
         work["gemm_wgrad"] = (wg * W + act, fwd_fl, nwin * len(mats))
         work["cast_weight"] = (W * (4 + 2 * esz), 0, len(mats))
     elif wl.kind == "conv":
@@ -76,12 +76,12 @@ def algorithmic_work(wl, P, fused=False, window=1, group=1):
         Wl = 4 * d * d + 2 * d * f                 # matrix entries of one block
         lin_fl = 2 * R * Wl * nl                   # one pass over the four Linears of all blocks
         act_f = nl * R * (2 * d + 3 * d + d + f + f + d) * esz   # operands read / written once
-        work["gemm_fwd"] = (V * nl * Wl * esz + act_f, lin_fl, U * nl * 4)
-        work["gemm_dgrad"] = (V * nl * Wl * esz + act_f, lin_fl, U * nl * 4)
+        work["gemm_fwd"] = (U * nl * Wl * esz + act_f, lin_fl, U * nl * 4)
+        work["gemm_dgrad"] = (U * nl * Wl * esz + act_f, lin_fl, U * nl * 4)
         work["gemm_wgrad"] = (wg * nl * Wl + act_f, lin_fl, U * nl * 4)
         head_fl = 2 * Rm * d * Vc
-        work["gemm_head"] = (V * d * Vc * esz + Rm * Vc * 4, head_fl, U)
-        work["gemm_head_dgrad"] = (V * d * Vc * esz + Rm * Vc * esz, head_fl, U)
+        work["gemm_head"] = (U * d * Vc * esz + Rm * Vc * 4, head_fl, U)
+        work["gemm_head_dgrad"] = (U * d * Vc * esz + Rm * Vc * esz, head_fl, U)
         work["gemm_head_wgrad"] = (wg * d * Vc + Rm * Vc * esz, head_fl, U)
         att = 2 * T * T * d * B * nl               # one [T,T,d_head] product over all heads, all blocks
         for tag in ("attn_scores", "attn_pv", "attn_bwd_dp", "attn_bwd_dv", "attn_bwd_dq", "attn_bwd_dk"):
@@ -104,10 +104,10 @@ def pass_units(wl, group):
     while i < len(sizes):
         take = 1
         if ok and (wl.kind == "encoder" or (sizes[i] <= 128 and sizes[i] % 8 == 0)):
-            run = 1
-            while i + run < len(sizes) and run < group and sizes[i + run] == sizes[i]:
+            run, most = 1, (min(group, 4) if wl.kind == "encoder" else group)
+            while i + run < len(sizes) and run < most and sizes[i + run] == sizes[i]:
                 run += 1
-            take = 4 if run >= 4 else (2 if run >= 2 else 1)
+            take = 8 if run >= 8 else (4 if run >= 4 else (2 if run >= 2 else 1))
         units += 1
         i += take
     return units
@@ -329,7 +329,7 @@ def main():
                     help="fused fold: the weight gradients of this many consecutive nodes (1..8) are folded "
                          "into the gradient buffer in one pass (nodes of one size: one product over the "
                          "window's rows; the workspace keeps that many nodes' transposed bf16 operands)")
-    ap.add_argument("--node-group", type=int, choices=[1, 2, 4], default=4,
+    ap.add_argument("--node-group", type=int, choices=[1, 2, 4, 8], default=8,
                     help="up to this many consecutive equal-sized nodes go through their passes together "
                          "(one operand of every product, so the weights are read once per group; BatchNorm "
                          "statistics, node losses and weights stay per node); 1: node after node")
@@ -492,11 +492,10 @@ def bench_workload(name, args, primary):
         out["roofline"] = roofline_for(dom, work, kernels[dom]["avg_launch_ms"])
         out["roofline"]["traffic"] = measured_traffic(wl.name, args.accumulate, dom)
         units = pass_units(wl, args.node_group)
-        if units != wl.n_nodes and out["roofline"]["bound"] == "hbm":
+        if units != wl.n_nodes:
             out["roofline"]["note"] = (
-                "algorithmic bytes are the method's: every node streams the weights once, and a launch that takes "
-                f"{wl.n_nodes // units} nodes is credited with each node's stream; the launch itself reads them once "
-                "(traffic), so what binds it is the matrix-core rate: mfma_tflops / mfma_frac")
+                f"a launch takes a unit of {wl.n_nodes // units} nodes and reads the weights once: bytes and flops "
+                "are those of the launch as made (node by node, the same weights would be streamed once per node)")
         out["roofline_all"] = {k: {kk: vv for kk, vv in roofline_for(k, work, kernels[k]["avg_launch_ms"]).items()
                                    if kk in ("bound", "achieved", "peak", "unit", "frac", "mfma_tflops", "mfma_frac")}
                                for k in kernels if k in work}

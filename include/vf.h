@@ -148,7 +148,7 @@ typedef struct vf_config {
                                     nodes are kept until then, so the workspace grows with the
                                     window (not with V). */
   int32_t node_group;            /* MLP (bf16) and encoder: up to this many CONSECUTIVE nodes of one
-                                    size (1, 2 or 4; 0 = 1) are taken through their passes together:
+                                    size (1, 2, 4 or 8; 0 = 1; the encoder takes at most 4) go through their passes together:
                                     their rows form one operand of every product, so the weights
                                     are read once per group instead of once per node.  Everything a
                                     node owns stays per node -- BatchNorm statistics and their

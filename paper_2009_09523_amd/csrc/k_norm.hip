@@ -365,7 +365,7 @@ int launch_bn_relu_fwd(const float* zp, int nsplit, int64_t slab, int64_t ldzp, 
   if (aT && ((ldt & 7) || !a_is_bf16)) return VF_EINVAL;
   const int grid = (C + CB - 1) / CB;
   const bool small = R <= RCH;
-  if (group != 1 && (!small || !a_is_bf16 || (group != 2 && group != 4) || (aT && (R & 7)))) return VF_EINVAL;
+  if (group != 1 && (!small || !a_is_bf16 || (group != 2 && group != 4 && group != 8) || (aT && (R & 7)))) return VF_EINVAL;
 #define VF_FWD2(TT, NS, SM, GG)                                                                    \
   bn_relu_fwd_kernel<TT, NS, SM, GG><<<grid, 256, 0, s>>>(zp, slab, ldzp, R, C, gamma, beta, round_params, \
       eps, z, ldz, static_cast<TT*>(a), lda, aT, ldt, mean, rstd, run_mean, run_var, run_mix)
@@ -373,6 +373,7 @@ int launch_bn_relu_fwd(const float* zp, int nsplit, int64_t slab, int64_t ldzp, 
   case NS:                                                                                         \
     if (group == 2) VF_FWD2(bf16_t, NS, true, 2);                                                  \
     else if (group == 4) VF_FWD2(bf16_t, NS, true, 4);                                             \
+    else if (group == 8) VF_FWD2(bf16_t, NS, true, 8);                                             \
     else if (a_is_bf16) { if (small) VF_FWD2(bf16_t, NS, true, 1); else VF_FWD2(bf16_t, NS, false, 1); } \
     else           { if (small) VF_FWD2(float, NS, true, 1);  else VF_FWD2(float, NS, false, 1); } \
     break;
@@ -395,7 +396,7 @@ int launch_bn_relu_bwd(float* dap, int nsplit, int64_t slab, int64_t ldda, const
   if (dzT && ((ldt & 7) || !dz_is_bf16)) return VF_EINVAL;
   const int grid = (C + CB - 1) / CB;
   const bool small = R <= RCH;
-  if (group != 1 && (!small || !dz_is_bf16 || (group != 2 && group != 4) || (dzT && (R & 7)))) return VF_EINVAL;
+  if (group != 1 && (!small || !dz_is_bf16 || (group != 2 && group != 4 && group != 8) || (dzT && (R & 7)))) return VF_EINVAL;
 #define VF_BWD2(TT, NS, SM, GG)                                                                    \
   bn_relu_bwd_kernel<TT, NS, SM, GG><<<grid, 256, 0, s>>>(dap, slab, ldda, z, ldz, R, C, gamma, beta,  \
       round_params, mean, rstd, static_cast<TT*>(dz), lddz, dzT, ldt, gout_g, gout_b, tscale)
@@ -403,6 +404,7 @@ int launch_bn_relu_bwd(float* dap, int nsplit, int64_t slab, int64_t ldda, const
   case NS:                                                                                         \
     if (group == 2) VF_BWD2(bf16_t, NS, true, 2);                                                  \
     else if (group == 4) VF_BWD2(bf16_t, NS, true, 4);                                             \
+    else if (group == 8) VF_BWD2(bf16_t, NS, true, 8);                                             \
     else if (dz_is_bf16) { if (small) VF_BWD2(bf16_t, NS, true, 1); else VF_BWD2(bf16_t, NS, false, 1); } \
     else            { if (small) VF_BWD2(float, NS, true, 1);  else VF_BWD2(float, NS, false, 1); } \
     break;

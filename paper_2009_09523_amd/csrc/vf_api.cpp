@@ -39,7 +39,7 @@ int validate_config(const vf_config& c) {
   if (c.max_node_size > c.max_batch) return VF_EINVAL;
   if (!(c.bn_momentum >= 0.f && c.bn_momentum <= 1.f)) return VF_EINVAL;
   if (c.fold_window < 0 || c.fold_window > kFoldMax) return VF_EINVAL;
-  if (c.node_group != 0 && c.node_group != 1 && c.node_group != 2 && c.node_group != 4) return VF_EINVAL;
+  if (c.node_group != 0 && c.node_group != 1 && c.node_group != 2 && c.node_group != 4 && c.node_group != 8) return VF_EINVAL;
   if (c.model_kind == VF_MLP) {
     if (c.n_dims < 2 || c.n_dims > VF_MAX_DIMS) return VF_EINVAL;
     for (int i = 0; i < c.n_dims; ++i)
@@ -54,7 +54,7 @@ int validate_config(const vf_config& c) {
       return VF_EINVAL;
     if (c.d_model % c.n_heads) return VF_EINVAL;
     if (c.d_model > 1024) return VF_EINVAL;                       // LayerNorm kernels keep a row in registers
-    if ((int64_t)c.max_node_size * std::max(1, c.node_group) * c.seq_len > 65536) return VF_EINVAL;   // token bitmap of the embedding backward
+    if ((int64_t)c.max_node_size * std::min(4, std::max(1, c.node_group)) * c.seq_len > 65536) return VF_EINVAL;   // token bitmap of the embedding backward
     if (c.n_masked > c.seq_len) return VF_EINVAL;
     if (c.dtype == VF_BF16 && ((c.d_model % 8) || (c.d_ffn % 8) || ((c.d_model / c.n_heads) % 8)))
       return VF_EINVAL;
@@ -401,6 +401,7 @@ int vf_init(const vf_config* cfg, vf_ctx** out) {
   if (!c.model) { delete h; return VF_EINVAL; }
   c.P = c.model->num_params();
   c.group = std::max(1, cfg->node_group);
+  if (cfg->model_kind == VF_ENCODER) c.group = std::min(c.group, 4);   // its units are at most four nodes
   // Overlap needs a capturable main stream and a model that double-buffers what the side
   // stream reads (the bf16 MLP and the bf16 encoder do).
   c.overlap = c.stream != nullptr && (cfg->flags & VF_FLAG_OVERLAP) && c.model->supports_overlap();
@@ -533,13 +534,14 @@ int vf_step(vf_ctx* h, void* params, const void* batch_x, const int32_t* batch_y
   a.node_off.resize(V + 1);
   a.node_w.resize(V);
   vf_partition(node_sizes, V, B, a.node_off.data(), a.node_w.data());
-  // the units of the passes: the nodes, or runs of up to `group` equal-sized nodes (2 or 4 at a time)
+  // the units of the passes: the nodes, or runs of up to `group` equal-sized nodes (2, 4 or 8 at a time)
   for (int32_t i = 0; i < V;) {
     int take = 1;
-    if (c.group > 1 && c.model->supports_group(node_sizes[i])) {
+    const int most = std::min(c.group, c.model->max_group(node_sizes[i]));
+    if (most > 1) {
       int run = 1;
-      while (i + run < V && run < c.group && node_sizes[i + run] == node_sizes[i]) ++run;
-      take = run >= 4 ? 4 : (run >= 2 ? 2 : 1);
+      while (i + run < V && run < most && node_sizes[i + run] == node_sizes[i]) ++run;
+      take = run >= 8 ? 8 : (run >= 4 ? 4 : (run >= 2 ? 2 : 1));
     }
     a.sizes.push_back(take * node_sizes[i]);
     a.seg.push_back(node_sizes[i]);

@@ -114,8 +114,8 @@ class Model {
   virtual void update_ranges(std::vector<UpdateRange>* out) const { out->clear(); }
   // Largest fold window the side part can take (it must keep that many nodes' operands).
   virtual int max_window() const { return 1; }
-  // Whether the passes take a group of equal-sized nodes of `rows` rows each as one unit.
-  virtual bool supports_group(int rows) const { (void)rows; return false; }
+  // How many equal-sized nodes of `rows` rows each the passes take as one unit at most (1: none).
+  virtual int max_group(int rows) const { (void)rows; return 1; }
   // State that the passes themselves carry from step to step on this device (BatchNorm moving
   // mean and variance, Section 4.1): `state_floats` fp32 values at `state_ptr`, laid out as all
   // layers' means then all layers' variances; init_state sets the starting values.

@@ -83,7 +83,7 @@ class Encoder final : public Model {
     P_ = off;
     // a unit of the passes is up to node_group nodes (their sequences are independent: only the
     // loss bookkeeping tells them apart): every per-unit buffer is sized for that many sequences
-    max_seqs_ = cfg.max_node_size * std::max(1, cfg.node_group);
+    max_seqs_ = cfg.max_node_size * std::min(4, std::max(1, cfg.node_group));
     maxR_ = (int64_t)max_seqs_ * T_;
     maxRm_ = (int64_t)max_seqs_ * m_;
     ldR_ = round8(maxR_);
@@ -96,7 +96,8 @@ class Encoder final : public Model {
   }
 
   int64_t num_params() const override { return P_; }
-  bool supports_group(int) const override { return true; }
+  // (the row-chunked reductions of the backward pass take units of up to 8192 tokens)
+  int max_group(int) const override { return 4; }
   // the forward part of the fp32 / non-MFMA attention path shares its score scratch with the backward part
   bool supports_overlap() const override { return bf16_ && mfma_attn_; }
 

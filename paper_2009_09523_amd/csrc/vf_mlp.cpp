@@ -102,7 +102,7 @@ class Mlp final : public Model {
   bool supports_overlap() const override { return bf16_; }
   // groups of nodes: the BatchNorm kernels keep a node of up to 128 rows in registers, and the
   // transposed copies want node boundaries on 16-byte boundaries
-  bool supports_group(int rows) const override { return bf16_ && rows <= 128 && (rows & 7) == 0; }
+  int max_group(int rows) const override { return (bf16_ && rows <= 128 && (rows & 7) == 0) ? 8 : 1; }
   int max_window() const override { return bf16_ ? kFoldMax : 1; }
 
   // The side part finishes the layers from the last to the first; a layer's stretch of the

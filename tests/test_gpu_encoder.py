@@ -90,7 +90,7 @@ def test_c4_full_size():
     print("full size C4", flush=True)
     wl, theta, x, y = _case("C4", jitter=0.0)
     ref = oracle_steps(wl, theta, x, y)
-    for flags, group in ((0, 0), (FUSED | OVERLAP | NO_GRAPH, 4)):      # the second is what bench.py times
+    for flags, group in ((0, 0), (FUSED | OVERLAP | NO_GRAPH, 8)):      # the second is what bench.py times (the encoder takes 4 of the 8)
         print(f"flags {flags} group {group}", flush=True)
         gpu = run_gpu(wl, theta, x, y, flags=flags, node_group=group)
         check_against_oracle(wl, gpu, ref)

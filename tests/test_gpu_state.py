@@ -50,12 +50,12 @@ def test_moving_statistics_match_the_oracle_after_two_steps(name, flags):
     assert np.max(np.abs(st["bn_var"] - want_var)) <= tol * np.max(np.abs(want_var))
 
 
-@pytest.mark.parametrize("group", [2, 4])
-def test_moving_statistics_of_grouped_nodes_are_blended_node_after_node(group):
-    """Five equal nodes taken 2 or 4 at a time: every node still blends its own statistics into the
+@pytest.mark.parametrize("group,nodes", [(2, [48] * 5), (4, [48] * 5), (8, [24] * 10)])
+def test_moving_statistics_of_grouped_nodes_are_blended_node_after_node(group, nodes):
+    """Equal nodes taken 2, 4 or 8 at a time: every node still blends its own statistics into the
     moving ones, in node order (Section 4.1), so the oracle's values come out."""
     import paper_2009_09523_amd as vf
-    wl = I.workload("mlp_mid_bn_bf16").with_nodes([48] * 5)
+    wl = I.workload("mlp_mid_bn_bf16").with_nodes(nodes)
     theta, x, y, params, xt, yt = _setup(wl)
     eng, stream = _engine(wl, FUSED, node_group=group)
     for _ in range(2):
