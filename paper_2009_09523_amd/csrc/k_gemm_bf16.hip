@@ -1192,7 +1192,13 @@ static int wide_tile_n(int M, int N) {
   if (mode == 128 || mode == 256) return mode;
   const int64_t tm = (M + 255) / 256;
   // 256 x 256 once that still gives every compute unit a tile; narrow matrices keep 128
-  return (N >= 256 && tm * ((N + 255) / 256) >= 256) ? 256 : 128;
+  const int64_t t256 = tm * ((N + 255) / 256), t128 = tm * ((N + 127) / 128);
+  if (N < 256 || t256 < 256) return 128;
+  // Every compute unit takes one tile at a time, so a grid runs in rounds of 256 tiles and the last
+  // round costs as much as a full one.  A 256-wide tile takes about 1.85 times as long as a
+  // 128-wide one (twice the work, somewhat better fed): take whichever needs less time in rounds.
+  const int64_t r256 = (t256 + 255) / 256, r128 = (t128 + 255) / 256;
+  return (r256 * 185 <= r128 * 100) ? 256 : 128;
 }
 static bool wide_fits(int M, int N, int K, int nsplit) {
   if (!wide_mode() || M <= 128 || N < 128 || (K % BK)) return false;

@@ -76,12 +76,12 @@ __device__ __forceinline__ int xcd_column_block(int b, int nblocks) {
 // rows are loaded up front, so the group costs one trip to memory.  mean_out / rstd_out hold G
 // vectors of C, the transposed copy node g's rows at columns g*R .. g*R + R-1.
 template <typename T, int NS, bool SMALL, int G>
-__global__ __launch_bounds__(256) void bn_relu_fwd_kernel(const float* __restrict__ zp, int64_t slab,
+__global__ __launch_bounds__(256) void bn_relu_fwd_kernel(const float* zp, int64_t slab,
                                                           int64_t ldzp, int R, int C,
                                                           const float* __restrict__ gamma,
                                                           const float* __restrict__ beta,
                                                           int round_params, float eps,
-                                                          float* __restrict__ z, int64_t ldz,
+                                                          float* z, int64_t ldz,
                                                           T* __restrict__ a, int64_t lda,
                                                           bf16_t* __restrict__ aT, int64_t ldt,
                                                           float* __restrict__ mean_out,
@@ -132,12 +132,12 @@ __global__ __launch_bounds__(256) void bn_relu_fwd_kernel(const float* __restric
 #pragma unroll
       for (int k = 0; k < RPT; ++k) {
         const int r = ty + RL * k;
-        if (live && r < R) z[(int64_t)(rb + r) * ldz + c] = zr[n][k];
+        if ((NS > 1 || zp != z) && live && r < R) z[(int64_t)(rb + r) * ldz + c] = zr[n][k];
       }
     } else if (live) {
       for (int r = ty; r < R; r += RL) {
         float v = sum_slabs<NS>(zp, slab, (int64_t)r * ldzp + c);
-        z[(int64_t)r * ldz + c] = v;
+        if (NS > 1 || zp != z) z[(int64_t)r * ldz + c] = v;
         s += v;
       }
     }

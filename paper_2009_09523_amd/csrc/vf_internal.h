@@ -161,11 +161,11 @@ int launch_cast_bf16(const float* in, int64_t ldi, bf16_t* out, int64_t ldo, int
 // k_norm.hip -- T is float or bf16_t (is_bf16 selects)
 // BatchNorm over the R rows given + ReLU.  zp: nsplit partial slabs (slab elements apart,
 // leading dimension ldzp) of the Linear output; their sum is written to z (saved for the
-// backward pass).  a = relu(gamma*xhat + beta) as T; aT (optional, bf16 only) the same
+// backward pass; with one slab, zp may be z itself and nothing is copied).  a = relu(gamma*xhat + beta) as T; aT (optional, bf16 only) the same
 // transposed, [C, ldt].  Saves mean, rstd.  With gamma == nullptr: a = relu(z).
 // run_mean / run_var (both or neither): moving statistics, blended in place with the pass's
 // own: run += run_mix * (stat - run), biased variance.
-// group = 2 or 4 (bf16, R <= 128, R a multiple of 8 when aT is given): the rows are `group` nodes
+// group = 2, 4 or 8 (bf16, R <= 128, R a multiple of 8 when aT is given): the rows are `group` nodes
 // of R rows each, one after the other; statistics, the blend of the moving statistics and (in the
 // backward kernel) the small-vector gradients are taken per node in node order; mean and rstd
 // hold `group` vectors of C, the transposed copies node g's rows at columns g*R.

@@ -215,8 +215,11 @@ class Mlp final : public Model {
       const int split = split_for(b, L.N, L.K, L.ld);
       const int64_t slab = (int64_t)b * L.ld;
       if (wait_casts_ && l >= 1) VF_HIP(hipStreamWaitEvent(st, cast_done_[l], 0));
+      // an unsliced product of a hidden layer writes the pre-activation where it is kept: the
+      // normalisation kernel then has nothing to copy
+      float* zsrc = (split == 1 && L.hidden) ? L.z[q] : slab_buf;
       Epilogue ep;
-      ep.C = slab_buf; ep.ldc = L.ld;
+      ep.C = zsrc; ep.ldc = L.ld;
       if (L.has_bias) { ep.bias = P + L.b_off; ep.bias_round_bf16 = bf16_; }
       if (bf16_)
         VF_KS(c, st, "gemm_fwd", launch_gemm_bf16(static_cast<const bf16_t*>(in), ldin, L.wtr, L.ldt, b, L.N, L.K,
@@ -224,7 +227,7 @@ class Mlp final : public Model {
       else
         VF_KS(c, st, "gemm_fwd", launch_gemm_f32(static_cast<const float*>(in), ldin, 1, P + L.w_off, 1, L.N, b, L.N, L.K, split, slab, ep, st));
       if (L.hidden)
-        VF_KS(c, st, "bn_relu_fwd", launch_bn_relu_fwd(slab_buf, split, slab, L.ld, s.seg[i], L.N,
+        VF_KS(c, st, "bn_relu_fwd", launch_bn_relu_fwd(zsrc, split, slab, L.ld, s.seg[i], L.N,
                                        L.has_bn ? P + L.g_off : nullptr, L.has_bn ? P + L.be_off : nullptr,
                                        bf16_, cfg_.bn_eps, L.z[q], L.ld, L.a[q], L.ld, bf16_, bf16_ ? L.aT + pc : nullptr, ldw_,
                                        L.mean[q], L.rstd[q], L.has_bn ? state_ + L.s_off : nullptr,
