@@ -33,6 +33,23 @@ __device__ __forceinline__ float col_reduce(float v, float (*red)[CB + 1], int t
   return s;
 }
 
+// The same sum for G values per thread at once (the G nodes of a group): one round trip through
+// LDS and two barriers for all of them, each value summed in the order col_reduce uses.
+template <int G>
+__device__ __forceinline__ void col_reduce_group(float (&v)[G], float (*red)[RL][CB + 1], int tx, int ty) {
+#pragma unroll
+  for (int n = 0; n < G; ++n) red[n][ty][tx] = v[n];
+  __syncthreads();
+#pragma unroll
+  for (int n = 0; n < G; ++n) {
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < RL; ++i) s += red[n][i][tx];
+    v[n] = s;
+  }
+  __syncthreads();
+}
+
 // Sum of the NS slabs at one element, in slab order; all loads are issued before the adds.
 template <int NS>
 __device__ __forceinline__ float sum_slabs(const float* __restrict__ p, int64_t stride, int64_t idx) {
@@ -89,8 +106,10 @@ __global__ __launch_bounds__(256) void bn_relu_fwd_kernel(const float* zp, int64
                                                           float* __restrict__ run_mean,
                                                           float* __restrict__ run_var, float run_mix) {
   static_assert(G == 1 || SMALL, "groups of nodes only on the register-resident path");
-  __shared__ float red[RL][CB + 1];
-  __shared__ __attribute__((aligned(16))) bf16_t tile[CB][RCH + 8];
+  __shared__ float redg[G][RL][CB + 1];
+  __shared__ __attribute__((aligned(16))) bf16_t tileg[G][CB][RCH + 8];
+  float (*red)[CB + 1] = redg[0];
+  bf16_t (*tile)[RCH + 8] = tileg[0];
   const int tx = threadIdx.x % CB, ty = threadIdx.x / CB;
   const int c0 = xcd_column_block(blockIdx.x, gridDim.x) * CB;
   const int c = c0 + tx;
@@ -116,6 +135,82 @@ __global__ __launch_bounds__(256) void bn_relu_fwd_kernel(const float* zp, int64
       }
   }
   if (bn && live && round_params) { g = round_bf16(g); b = round_bf16(b); }
+  if constexpr (G > 1) {
+    // The nodes of a group side by side: the arithmetic of every node is what the loop below does
+    // for it (same sums in the same order), but the column sums of all nodes go through LDS
+    // together and the transposed copies are written after one barrier: five barriers per
+    // workgroup instead of six per node.
+    float mean[G], rstd[G], var[G];
+#pragma unroll
+    for (int n = 0; n < G; ++n) {
+      float s = 0.f;
+#pragma unroll
+      for (int k = 0; k < RPT; ++k) {
+        const int r = ty + RL * k;
+        zr[n][k] = (live && r < R) ? zr[n][k] : 0.f;
+        s += zr[n][k];
+      }
+      mean[n] = s; rstd[n] = 1.f; var[n] = 0.f;
+      if (NS > 1 || zp != z) {
+#pragma unroll
+        for (int k = 0; k < RPT; ++k) {
+          const int r = ty + RL * k;
+          if (live && r < R) z[(int64_t)(n * R + r) * ldz + c] = zr[n][k];
+        }
+      }
+    }
+    if (bn) {
+      col_reduce_group<G>(mean, redg, tx, ty);
+#pragma unroll
+      for (int n = 0; n < G; ++n) {
+        mean[n] = mean[n] / (float)R;
+        float q = 0.f;
+#pragma unroll
+        for (int k = 0; k < RPT; ++k) {
+          const int r = ty + RL * k;
+          float d = (live && r < R) ? zr[n][k] - mean[n] : 0.f;
+          q = fmaf(d, d, q);
+        }
+        var[n] = q;
+      }
+      col_reduce_group<G>(var, redg, tx, ty);
+#pragma unroll
+      for (int n = 0; n < G; ++n) {
+        var[n] = var[n] / (float)R;
+        rstd[n] = 1.0f / sqrtf(var[n] + eps);
+        if (live && ty == 0) {
+          mean_out[(int64_t)n * C + c] = mean[n]; rstd_out[(int64_t)n * C + c] = rstd[n];
+          if (run_mean) {   // moving statistics of this device: one blend per pass, node after node (Section 4.1)
+            rm = fmaf(run_mix, mean[n] - rm, rm);
+            rv = fmaf(run_mix, var[n] - rv, rv);
+          }
+        }
+      }
+    } else {
+#pragma unroll
+      for (int n = 0; n < G; ++n) mean[n] = 0.f;
+    }
+#pragma unroll
+    for (int n = 0; n < G; ++n) {
+#pragma unroll
+      for (int k = 0; k < RPT; ++k) {
+        const int r = ty + RL * k;
+        float v = 0.f;
+        if (live && r < R) {
+          v = bn ? fmaxf(fmaf(g, (zr[n][k] - mean[n]) * rstd[n], b), 0.f) : fmaxf(zr[n][k], 0.f);
+          store_f(&a[(int64_t)(n * R + r) * lda + c], v);
+        }
+        if (aT) tileg[n][tx][r] = f32_to_bf16(v);
+      }
+    }
+    if (aT) {
+      __syncthreads();
+#pragma unroll
+      for (int n = 0; n < G; ++n) store_transposed(tileg[n], aT + n * R, ldt, c0, C, 0, R);
+    }
+    if (bn && live && ty == 0 && run_mean) { run_mean[c] = rm; run_var[c] = rv; }
+    return;
+  }
 #pragma unroll
   for (int n = 0; n < G; ++n) {
     const int rb = n * R;                       // first row of this node
@@ -204,8 +299,10 @@ __global__ __launch_bounds__(256) void bn_relu_bwd_kernel(float* __restrict__ da
                                                           bf16_t* __restrict__ dzT, int64_t ldt,
                                                           GradOut gout_g, GradOut gout_b, float tscale) {
   static_assert(G == 1 || SMALL, "groups of nodes only on the register-resident path");
-  __shared__ float red[RL][CB + 1];
-  __shared__ __attribute__((aligned(16))) bf16_t tile[CB][RCH + 8];
+  __shared__ float redg[G][RL][CB + 1];
+  __shared__ __attribute__((aligned(16))) bf16_t tileg[G][CB][RCH + 8];
+  float (*red)[CB + 1] = redg[0];
+  bf16_t (*tile)[RCH + 8] = tileg[0];
   const int tx = threadIdx.x % CB, ty = threadIdx.x / CB;
   const int c0 = xcd_column_block(blockIdx.x, gridDim.x) * CB;
   const int c = c0 + tx;
@@ -236,6 +333,59 @@ __global__ __launch_bounds__(256) void bn_relu_bwd_kernel(float* __restrict__ da
   // the nodes of a group have one weight: their small-vector gradients are added up in node order
   // and folded in once (what the staged path does with its staging vector, bit for bit)
   float tg = 0.f, tb = 0.f;
+  if constexpr (G > 1) {
+    // the nodes of a group side by side (see the forward kernel): same sums in the same order
+    float sg[G], sb[G];
+#pragma unroll
+    for (int n = 0; n < G; ++n) {
+      float ag = 0.f, ab = 0.f;
+#pragma unroll
+      for (int k = 0; k < RPT; ++k) {
+        const int r = ty + RL * k;
+        const float zz = xr[n][k];
+        const float xhat = (zz - mean[n]) * rstd[n];
+        const float pre = bn ? fmaf(g, xhat, b) : zz;
+        const bool on = live && r < R;
+        xr[n][k] = on ? xhat : 0.f;
+        dr[n][k] = (on && pre > 0.f) ? dr[n][k] : 0.f;
+        ag = fmaf(dr[n][k], xr[n][k], ag);
+        ab += dr[n][k];
+      }
+      sg[n] = ag; sb[n] = ab;
+    }
+    col_reduce_group<G>(sg, redg, tx, ty);
+    col_reduce_group<G>(sb, redg, tx, ty);
+#pragma unroll
+    for (int n = 0; n < G; ++n) {
+      tg = n ? tg + sg[n] : sg[n];
+      tb = n ? tb + sb[n] : sb[n];
+    }
+    if (live && ty == 0) {
+      if (bn) grad_store(gout_g, c, tg);
+      if (gout_b.dst) grad_store(gout_b, c, tb);
+    }
+    const float invR = 1.0f / (float)R;
+#pragma unroll
+    for (int n = 0; n < G; ++n) {
+      const float kk = g * rstd[n];
+#pragma unroll
+      for (int k = 0; k < RPT; ++k) {
+        const int r = ty + RL * k;
+        float v = 0.f;
+        if (live && r < R) {
+          v = bn ? kk * (dr[n][k] - sb[n] * invR - xr[n][k] * sg[n] * invR) : dr[n][k];
+          store_f(&dz[(int64_t)(n * R + r) * lddz + c], v);
+        }
+        if (dzT) tileg[n][tx][r] = f32_to_bf16(v * tscale);
+      }
+    }
+    if (dzT) {
+      __syncthreads();
+#pragma unroll
+      for (int n = 0; n < G; ++n) store_transposed(tileg[n], dzT + n * R, ldt, c0, C, 0, R);
+    }
+    return;
+  }
 #pragma unroll
   for (int n = 0; n < G; ++n) {
     const int rb = n * R;
