@@ -43,15 +43,21 @@ __device__ __forceinline__ void stage_rows(const bf16_t* __restrict__ g, int64_t
     *reinterpret_cast<u32x4*>(&lds[t * LDE + e8]) = *reinterpret_cast<const u32x4*>(&g[(int64_t)t * rs + e8]);
   }
 }
-// Stage the same window transposed: lds[e][t] (ld TS+8).
+// Stage the same window transposed: lds[e][t] (ld TS+8).  A thread takes two neighbouring rows
+// t, t+1 and eight columns, and writes the pairs (e, t), (e, t+1) as one 32-bit word each; the
+// threads of a wavefront run along t, so the words of one store instruction are neighbours in
+// LDS (one bank each) -- single 16-bit stores 272 bytes apart had put sixteen lanes on two banks.
+__device__ __forceinline__ uint32_t pick16(const u32x4& x, int u) { return (x[u >> 1] >> ((u & 1) * 16)) & 0xffffu; }
 template <int TS>
 __device__ __forceinline__ void stage_cols(const bf16_t* __restrict__ g, int64_t rs, bf16_t* lds) {
   constexpr int LDT = TS + 8;
-  for (int v = threadIdx.x; v < TS * (DH / 8); v += blockDim.x) {
-    const int t = v >> 3, e8 = (v & 7) * 8;
-    u32x4 x = *reinterpret_cast<const u32x4*>(&g[(int64_t)t * rs + e8]);
+  for (int v = threadIdx.x; v < (TS / 2) * (DH / 8); v += blockDim.x) {
+    const int t = 2 * (v % (TS / 2)), e8 = (v / (TS / 2)) * 8;
+    const u32x4 x0 = *reinterpret_cast<const u32x4*>(&g[(int64_t)t * rs + e8]);
+    const u32x4 x1 = *reinterpret_cast<const u32x4*>(&g[(int64_t)(t + 1) * rs + e8]);
 #pragma unroll
-    for (int u = 0; u < 8; ++u) lds[(e8 + u) * LDT + t] = (bf16_t)((x[u >> 1] >> ((u & 1) * 16)) & 0xffffu);
+    for (int u = 0; u < 8; ++u)
+      *reinterpret_cast<uint32_t*>(&lds[(e8 + u) * LDT + t]) = pick16(x0, u) | (pick16(x1, u) << 16);
   }
 }
 
@@ -164,27 +170,42 @@ __global__ __launch_bounds__(2 * TS) void attn_bwd_kernel(const float* __restric
   stage_cols<TS>(qg, rs, Qt);
   stage_cols<TS>(qg + d, rs, Kt);
   stage_rows<TS>(qg + 2 * d, rs, Vs);
-  // dO: fp32 [t][e] -> bf16, both orientations
+  // dO: fp32 [t][e] -> bf16, both orientations: rows as they are (16-byte stores), and transposed
+  // with the pair-of-rows mapping of stage_cols
   const float* dog = dO + (int64_t)seq * TS * d + head * DH;
   for (int v = threadIdx.x; v < TS * (DH / 8); v += blockDim.x) {
     const int t = v >> 3, e8 = (v & 7) * 8;
     const float4 a = *reinterpret_cast<const float4*>(&dog[(int64_t)t * d + e8]);
     const float4 b = *reinterpret_cast<const float4*>(&dog[(int64_t)t * d + e8 + 4]);
-    const float f[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const bf16_t h = f32_to_bf16(f[u]);
-      dOs[t * LDE + e8 + u] = h;
-      dOt[(e8 + u) * LDT + t] = h;
-    }
+    u32x4 h;
+    h[0] = (uint32_t)f32_to_bf16(a.x) | ((uint32_t)f32_to_bf16(a.y) << 16);
+    h[1] = (uint32_t)f32_to_bf16(a.z) | ((uint32_t)f32_to_bf16(a.w) << 16);
+    h[2] = (uint32_t)f32_to_bf16(b.x) | ((uint32_t)f32_to_bf16(b.y) << 16);
+    h[3] = (uint32_t)f32_to_bf16(b.z) | ((uint32_t)f32_to_bf16(b.w) << 16);
+    *reinterpret_cast<u32x4*>(&dOs[t * LDE + e8]) = h;
   }
-  // P: [q][j] in memory -> Pt[j][q]
-  const bf16_t* pg = prob + (int64_t)bh * TS * TS;
-  for (int v = threadIdx.x; v < TS * (TS / 8); v += blockDim.x) {
-    const int q = v / (TS / 8), j8 = (v % (TS / 8)) * 8;
-    u32x4 x = *reinterpret_cast<const u32x4*>(&pg[q * TS + j8]);
+  for (int v = threadIdx.x; v < (TS / 2) * (DH / 8); v += blockDim.x) {
+    const int t = 2 * (v % (TS / 2)), e8 = (v / (TS / 2)) * 8;
+    const float4 a0 = *reinterpret_cast<const float4*>(&dog[(int64_t)t * d + e8]);
+    const float4 b0 = *reinterpret_cast<const float4*>(&dog[(int64_t)t * d + e8 + 4]);
+    const float4 a1 = *reinterpret_cast<const float4*>(&dog[(int64_t)(t + 1) * d + e8]);
+    const float4 b1 = *reinterpret_cast<const float4*>(&dog[(int64_t)(t + 1) * d + e8 + 4]);
+    const float f0[8] = {a0.x, a0.y, a0.z, a0.w, b0.x, b0.y, b0.z, b0.w};
+    const float f1[8] = {a1.x, a1.y, a1.z, a1.w, b1.x, b1.y, b1.z, b1.w};
 #pragma unroll
-    for (int u = 0; u < 8; ++u) Pt[(j8 + u) * LDT + q] = (bf16_t)((x[u >> 1] >> ((u & 1) * 16)) & 0xffffu);
+    for (int u = 0; u < 8; ++u)
+      *reinterpret_cast<uint32_t*>(&dOt[(e8 + u) * LDT + t]) =
+          (uint32_t)f32_to_bf16(f0[u]) | ((uint32_t)f32_to_bf16(f1[u]) << 16);
+  }
+  // P: [q][j] in memory -> Pt[j][q], two query rows per thread, words along q
+  const bf16_t* pg = prob + (int64_t)bh * TS * TS;
+  for (int v = threadIdx.x; v < (TS / 2) * (TS / 8); v += blockDim.x) {
+    const int q = 2 * (v % (TS / 2)), j8 = (v / (TS / 2)) * 8;
+    const u32x4 x0 = *reinterpret_cast<const u32x4*>(&pg[q * TS + j8]);
+    const u32x4 x1 = *reinterpret_cast<const u32x4*>(&pg[(q + 1) * TS + j8]);
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      *reinterpret_cast<uint32_t*>(&Pt[(j8 + u) * LDT + q]) = pick16(x0, u) | (pick16(x1, u) << 16);
   }
   __syncthreads();
 
@@ -237,11 +258,12 @@ __global__ __launch_bounds__(2 * TS) void attn_bwd_kernel(const float* __restric
 #pragma unroll
   for (int jt = 0; jt < JT; ++jt)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
+    for (int r = 0; r < 16; r += 2) {               // registers r, r+1: query rows q, q+1 (q even)
       const int q = 32 * w + acc_row(r, lane), j = 32 * jt + (lane & 31);
-      const bf16_t h = f32_to_bf16(dp[jt][r]);
-      dSs[q * LDT + j] = h;
-      Pt[j * LDT + q] = h;                          // dS transposed, over P transposed
+      const bf16_t h0 = f32_to_bf16(dp[jt][r]), h1 = f32_to_bf16(dp[jt][r + 1]);
+      dSs[q * LDT + j] = h0;
+      dSs[(q + 1) * LDT + j] = h1;
+      *reinterpret_cast<uint32_t*>(&Pt[j * LDT + q]) = (uint32_t)h0 | ((uint32_t)h1 << 16);   // dS transposed, over P transposed
     }
   __syncthreads();
   // dQ[q, e] = scale sum_j dS[q, j] k[j, e];  dK[j, e] = scale sum_q dS[q, j] q[q, e]
