@@ -139,7 +139,7 @@ __global__ __launch_bounds__(NT) void embed_tok_bwd4_kernel(const int32_t* __res
                                                             int vocab, GradOut out) {
   __shared__ uint32_t match[MAX_TOK_WORDS];
   __shared__ int list[256];
-  __shared__ int nlist, next_word;
+  __shared__ int scan[NT];
   __shared__ int earlier;
   __shared__ __attribute__((aligned(16))) float part[3 * 1024];
   const int r = blockIdx.x;
@@ -169,46 +169,77 @@ __global__ __launch_bounds__(NT) void embed_tok_bwd4_kernel(const int32_t* __res
   float4 acc[CPL];
 #pragma unroll
   for (int j = 0; j < CPL; ++j) acc[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-  if (threadIdx.x == 0) next_word = r >> 5;
+  // The matching tokens in increasing order, 256 at a time.  Every thread owns eight words of the
+  // bitmap: it counts their bits, a scan over the threads gives each word the position of its
+  // first match in the whole list, and for each window of 256 positions a thread writes the
+  // matches of its words that fall into it (one thread walking the whole bitmap bit by bit was
+  // the critical path of the launch for an id that many tokens share).
+  constexpr int WPT = MAX_TOK_WORDS / NT;
+  int cnt[WPT], mine = 0;
+#pragma unroll
+  for (int i = 0; i < WPT; ++i) {
+    const int wd = threadIdx.x * WPT + i;
+    cnt[i] = wd < nwords ? __popc(match[wd]) : 0;
+    mine += cnt[i];
+  }
+  scan[threadIdx.x] = mine;
   __syncthreads();
-  while (true) {
-    if (threadIdx.x == 0) {
-      int n = 0, wd = next_word;
-      for (; wd < nwords && n <= 256 - 32; ++wd) {
+  for (int off = 1; off < NT; off <<= 1) {
+    const int add = (int)threadIdx.x >= off ? scan[threadIdx.x - off] : 0;
+    __syncthreads();
+    scan[threadIdx.x] += add;
+    __syncthreads();
+  }
+  const int first = scan[threadIdx.x] - mine;       // list position of this thread's first match
+  const int total = scan[NT - 1];
+  for (int base = 0; base < total; base += 256) {
+    int o = first;
+#pragma unroll
+    for (int i = 0; i < WPT; ++i) {
+      if (cnt[i] && o < base + 256 && o + cnt[i] > base) {
+        const int wd = threadIdx.x * WPT + i;
         uint32_t bits = match[wd];
+        int at = o;
         while (bits) {
-          list[n++] = (wd << 5) + __ffs(bits) - 1;
+          if (at >= base && at < base + 256) list[at - base] = (wd << 5) + __ffs(bits) - 1;
+          ++at;
           bits &= bits - 1;
         }
       }
-      nlist = n;
-      next_word = wd;
+      o += cnt[i];
     }
     __syncthreads();
-    const int n = nlist;
-    const bool last = next_word >= nwords;
+    const int n = min(256, total - base);
     for (int k0 = 0; k0 < n; k0 += 32) {
       int row[8];
 #pragma unroll
       for (int u = 0; u < 8; ++u) row[u] = list[min(k0 + 4 * u + wave, n - 1)];
+      // the loads of all column groups before the first addition (one trip to memory per 32
+      // rows, not one per column group); a column group beyond the row is skipped by everybody
+      float4 v[CPL][8];
 #pragma unroll
       for (int j = 0; j < CPL; ++j) {
-        const int c = min(4 * lane + 256 * j, d - 4);
-        float4 v[8];
+        if (256 * j < d) {
+          const int c = min(4 * lane + 256 * j, d - 4);
 #pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const float4*>(&dh[(int64_t)row[u] * d + c]);
+          for (int u = 0; u < 8; ++u) v[j][u] = *reinterpret_cast<const float4*>(&dh[(int64_t)row[u] * d + c]);
+        }
+      }
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {               // padding adds +0
-          const bool live = k0 + 4 * u + wave < n;
-          acc[j].x += live ? v[u].x : 0.f;
-          acc[j].y += live ? v[u].y : 0.f;
-          acc[j].z += live ? v[u].z : 0.f;
-          acc[j].w += live ? v[u].w : 0.f;
+      for (int j = 0; j < CPL; ++j) {
+        if (256 * j < d) {
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {             // padding adds +0
+            const bool live = k0 + 4 * u + wave < n;
+            acc[j].x += live ? v[j][u].x : 0.f;
+            acc[j].y += live ? v[j][u].y : 0.f;
+            acc[j].z += live ? v[j][u].z : 0.f;
+            acc[j].w += live ? v[j][u].w : 0.f;
+          }
         }
       }
     }
     __syncthreads();
-    if (last) break;
   }
   // join the wavefronts' sums in wavefront order; wavefront 0 writes the table row
   if (wave > 0) {
