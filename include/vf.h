@@ -57,6 +57,7 @@
  *     VF_CONV_LDS=0        3x3 convolutions without the filters-resident-in-LDS kernel
  *     VF_CONV_EXPLICIT=1   convolutions always write the patch matrix and call the product kernel
  *     VF_LN_WGS=<n>        workgroups of the LayerNorm backward kernel (default 256)
+ *     VF_BN_SUBGROUPS=2|4  sub-groups of 256 threads per workgroup of the grouped BatchNorm kernels
  */
 #ifndef VF_H
 #define VF_H

@@ -12,6 +12,8 @@
 // lanes, so a 4096-wide layer gives 256 workgroups (one per compute unit).  For nodes of up
 // to RPT*16 = 128 rows every thread keeps its rows in registers and global memory is read
 // exactly once; larger nodes re-read the reduced values.
+#include <cstdlib>
+
 #include "vf_device.h"
 
 namespace vf {
@@ -31,23 +33,6 @@ __device__ __forceinline__ float col_reduce(float v, float (*red)[CB + 1], int t
   for (int i = 0; i < RL; ++i) s += red[i][tx];
   __syncthreads();
   return s;
-}
-
-// The same sum for G values per thread at once (the G nodes of a group): one round trip through
-// LDS and two barriers for all of them, each value summed in the order col_reduce uses.
-template <int G>
-__device__ __forceinline__ void col_reduce_group(float (&v)[G], float (*red)[RL][CB + 1], int tx, int ty) {
-#pragma unroll
-  for (int n = 0; n < G; ++n) red[n][ty][tx] = v[n];
-  __syncthreads();
-#pragma unroll
-  for (int n = 0; n < G; ++n) {
-    float s = 0.f;
-#pragma unroll
-    for (int i = 0; i < RL; ++i) s += red[n][i][tx];
-    v[n] = s;
-  }
-  __syncthreads();
 }
 
 // Sum of the NS slabs at one element, in slab order; all loads are issued before the adds.
@@ -89,8 +74,8 @@ __device__ __forceinline__ int xcd_column_block(int b, int nblocks) {
 // SMALL: R <= RCH, rows live in registers.
 // G > 1 (SMALL only): the rows are G virtual nodes of R rows each, one after the other (a group of
 // equal-sized nodes whose products were taken as one): statistics, normalisation and the moving
-// statistics' blend are per node, in node order, exactly as G launches would do them; all nodes'
-// rows are loaded up front, so the group costs one trip to memory.  mean_out / rstd_out hold G
+// statistics' blend are per node, in node order, exactly as G launches would do them; the rows of
+// node n+1 are requested before node n is worked on.  mean_out / rstd_out hold G
 // vectors of C, the transposed copy node g's rows at columns g*R .. g*R + R-1.
 template <typename T, int NS, bool SMALL, int G>
 __global__ __launch_bounds__(256) void bn_relu_fwd_kernel(const float* zp, int64_t slab,
@@ -106,8 +91,8 @@ __global__ __launch_bounds__(256) void bn_relu_fwd_kernel(const float* zp, int64
                                                           float* __restrict__ run_mean,
                                                           float* __restrict__ run_var, float run_mix) {
   static_assert(G == 1 || SMALL, "groups of nodes only on the register-resident path");
-  __shared__ float redg[G][RL][CB + 1];
-  __shared__ __attribute__((aligned(16))) bf16_t tileg[G][CB][RCH + 8];
+  __shared__ float redg[1][RL][CB + 1];
+  __shared__ __attribute__((aligned(16))) bf16_t tileg[1][CB][RCH + 8];
   float (*red)[CB + 1] = redg[0];
   bf16_t (*tile)[RCH + 8] = tileg[0];
   const int tx = threadIdx.x % CB, ty = threadIdx.x / CB;
@@ -121,98 +106,22 @@ __global__ __launch_bounds__(256) void bn_relu_fwd_kernel(const float* zp, int64
     g = gamma[c]; b = beta[c];
     if (run_mean && ty == 0) { rm = run_mean[c]; rv = run_var[c]; }
   }
-  float zr[G][RPT];
+  float zr[1][RPT];
   if (SMALL) {
     // Loads at clamped (always valid) addresses, selection afterwards: no load sits behind a
     // branch, so all of a thread's loads are in flight together.
     const int cc = min(c, C - 1);
 #pragma unroll
-    for (int n = 0; n < G; ++n)
-#pragma unroll
-      for (int k = 0; k < RPT; ++k) {
-        const int r = ty + RL * k;
-        zr[n][k] = sum_slabs<NS>(zp, slab, (int64_t)(n * R + min(r, R - 1)) * ldzp + cc);
-      }
+    for (int k = 0; k < RPT; ++k) {             // (a group's further nodes are requested one node ahead, below)
+      const int r = ty + RL * k;
+      zr[0][k] = sum_slabs<NS>(zp, slab, (int64_t)min(r, R - 1) * ldzp + cc);
+    }
   }
   if (bn && live && round_params) { g = round_bf16(g); b = round_bf16(b); }
-  if constexpr (G > 1) {
-    // The nodes of a group side by side: the arithmetic of every node is what the loop below does
-    // for it (same sums in the same order), but the column sums of all nodes go through LDS
-    // together and the transposed copies are written after one barrier: five barriers per
-    // workgroup instead of six per node.
-    float mean[G], rstd[G], var[G];
+  static_assert(G == 1, "groups of nodes have kernels of their own");
+  constexpr int ONE = 1;
 #pragma unroll
-    for (int n = 0; n < G; ++n) {
-      float s = 0.f;
-#pragma unroll
-      for (int k = 0; k < RPT; ++k) {
-        const int r = ty + RL * k;
-        zr[n][k] = (live && r < R) ? zr[n][k] : 0.f;
-        s += zr[n][k];
-      }
-      mean[n] = s; rstd[n] = 1.f; var[n] = 0.f;
-      if (NS > 1 || zp != z) {
-#pragma unroll
-        for (int k = 0; k < RPT; ++k) {
-          const int r = ty + RL * k;
-          if (live && r < R) z[(int64_t)(n * R + r) * ldz + c] = zr[n][k];
-        }
-      }
-    }
-    if (bn) {
-      col_reduce_group<G>(mean, redg, tx, ty);
-#pragma unroll
-      for (int n = 0; n < G; ++n) {
-        mean[n] = mean[n] / (float)R;
-        float q = 0.f;
-#pragma unroll
-        for (int k = 0; k < RPT; ++k) {
-          const int r = ty + RL * k;
-          float d = (live && r < R) ? zr[n][k] - mean[n] : 0.f;
-          q = fmaf(d, d, q);
-        }
-        var[n] = q;
-      }
-      col_reduce_group<G>(var, redg, tx, ty);
-#pragma unroll
-      for (int n = 0; n < G; ++n) {
-        var[n] = var[n] / (float)R;
-        rstd[n] = 1.0f / sqrtf(var[n] + eps);
-        if (live && ty == 0) {
-          mean_out[(int64_t)n * C + c] = mean[n]; rstd_out[(int64_t)n * C + c] = rstd[n];
-          if (run_mean) {   // moving statistics of this device: one blend per pass, node after node (Section 4.1)
-            rm = fmaf(run_mix, mean[n] - rm, rm);
-            rv = fmaf(run_mix, var[n] - rv, rv);
-          }
-        }
-      }
-    } else {
-#pragma unroll
-      for (int n = 0; n < G; ++n) mean[n] = 0.f;
-    }
-#pragma unroll
-    for (int n = 0; n < G; ++n) {
-#pragma unroll
-      for (int k = 0; k < RPT; ++k) {
-        const int r = ty + RL * k;
-        float v = 0.f;
-        if (live && r < R) {
-          v = bn ? fmaxf(fmaf(g, (zr[n][k] - mean[n]) * rstd[n], b), 0.f) : fmaxf(zr[n][k], 0.f);
-          store_f(&a[(int64_t)(n * R + r) * lda + c], v);
-        }
-        if (aT) tileg[n][tx][r] = f32_to_bf16(v);
-      }
-    }
-    if (aT) {
-      __syncthreads();
-#pragma unroll
-      for (int n = 0; n < G; ++n) store_transposed(tileg[n], aT + n * R, ldt, c0, C, 0, R);
-    }
-    if (bn && live && ty == 0 && run_mean) { run_mean[c] = rm; run_var[c] = rv; }
-    return;
-  }
-#pragma unroll
-  for (int n = 0; n < G; ++n) {
+  for (int n = 0; n < ONE; ++n) {
     const int rb = n * R;                       // first row of this node
     float mean = 0.f, rstd = 1.f;
     // pass 1: reduce the slabs into z, column sums
@@ -299,8 +208,8 @@ __global__ __launch_bounds__(256) void bn_relu_bwd_kernel(float* __restrict__ da
                                                           bf16_t* __restrict__ dzT, int64_t ldt,
                                                           GradOut gout_g, GradOut gout_b, float tscale) {
   static_assert(G == 1 || SMALL, "groups of nodes only on the register-resident path");
-  __shared__ float redg[G][RL][CB + 1];
-  __shared__ __attribute__((aligned(16))) bf16_t tileg[G][CB][RCH + 8];
+  __shared__ float redg[1][RL][CB + 1];
+  __shared__ __attribute__((aligned(16))) bf16_t tileg[1][CB][RCH + 8];
   float (*red)[CB + 1] = redg[0];
   bf16_t (*tile)[RCH + 8] = tileg[0];
   const int tx = threadIdx.x % CB, ty = threadIdx.x / CB;
@@ -317,77 +226,25 @@ __global__ __launch_bounds__(256) void bn_relu_bwd_kernel(float* __restrict__ da
 #pragma unroll
     for (int n = 0; n < G; ++n) { mean[n] = mean_in[(int64_t)n * C + c]; rstd[n] = rstd_in[(int64_t)n * C + c]; }
   }
-  float xr[G][RPT], dr[G][RPT];
+  float xr[1][RPT], dr[1][RPT];
   if (SMALL) {
     // loads at clamped (always valid) addresses first, all in flight together; selection after
+    // (a group's further nodes are requested one node ahead, below)
     const int cc = min(c, C - 1);
 #pragma unroll
-    for (int n = 0; n < G; ++n)
-#pragma unroll
-      for (int k = 0; k < RPT; ++k) {
-        const int rc = n * R + min(ty + RL * k, R - 1);
-        xr[n][k] = z[(int64_t)rc * ldz + cc];
-        dr[n][k] = sum_slabs<NS>(dap, slab, (int64_t)rc * ldda + cc);
-      }
+    for (int k = 0; k < RPT; ++k) {
+      const int rc = min(ty + RL * k, R - 1);
+      xr[0][k] = z[(int64_t)rc * ldz + cc];
+      dr[0][k] = sum_slabs<NS>(dap, slab, (int64_t)rc * ldda + cc);
+    }
   }
   // the nodes of a group have one weight: their small-vector gradients are added up in node order
   // and folded in once (what the staged path does with its staging vector, bit for bit)
   float tg = 0.f, tb = 0.f;
-  if constexpr (G > 1) {
-    // the nodes of a group side by side (see the forward kernel): same sums in the same order
-    float sg[G], sb[G];
+  static_assert(G == 1, "groups of nodes have kernels of their own");
+  constexpr int ONE = 1;
 #pragma unroll
-    for (int n = 0; n < G; ++n) {
-      float ag = 0.f, ab = 0.f;
-#pragma unroll
-      for (int k = 0; k < RPT; ++k) {
-        const int r = ty + RL * k;
-        const float zz = xr[n][k];
-        const float xhat = (zz - mean[n]) * rstd[n];
-        const float pre = bn ? fmaf(g, xhat, b) : zz;
-        const bool on = live && r < R;
-        xr[n][k] = on ? xhat : 0.f;
-        dr[n][k] = (on && pre > 0.f) ? dr[n][k] : 0.f;
-        ag = fmaf(dr[n][k], xr[n][k], ag);
-        ab += dr[n][k];
-      }
-      sg[n] = ag; sb[n] = ab;
-    }
-    col_reduce_group<G>(sg, redg, tx, ty);
-    col_reduce_group<G>(sb, redg, tx, ty);
-#pragma unroll
-    for (int n = 0; n < G; ++n) {
-      tg = n ? tg + sg[n] : sg[n];
-      tb = n ? tb + sb[n] : sb[n];
-    }
-    if (live && ty == 0) {
-      if (bn) grad_store(gout_g, c, tg);
-      if (gout_b.dst) grad_store(gout_b, c, tb);
-    }
-    const float invR = 1.0f / (float)R;
-#pragma unroll
-    for (int n = 0; n < G; ++n) {
-      const float kk = g * rstd[n];
-#pragma unroll
-      for (int k = 0; k < RPT; ++k) {
-        const int r = ty + RL * k;
-        float v = 0.f;
-        if (live && r < R) {
-          v = bn ? kk * (dr[n][k] - sb[n] * invR - xr[n][k] * sg[n] * invR) : dr[n][k];
-          store_f(&dz[(int64_t)(n * R + r) * lddz + c], v);
-        }
-        if (dzT) tileg[n][tx][r] = f32_to_bf16(v * tscale);
-      }
-    }
-    if (dzT) {
-      __syncthreads();
-#pragma unroll
-      for (int n = 0; n < G; ++n) store_transposed(tileg[n], dzT + n * R, ldt, c0, C, 0, R);
-    }
-    return;
-  }
-#pragma unroll
-  for (int n = 0; n < G; ++n) {
+  for (int n = 0; n < ONE; ++n) {
     const int rb = n * R;
     // pass 1: sum dout*xhat, sum dout  (dout = da where the ReLU was open)
     float sg = 0.f, sb = 0.f;
@@ -455,6 +312,214 @@ __global__ __launch_bounds__(256) void bn_relu_bwd_kernel(float* __restrict__ da
   }
 }
 
+// ---- groups of nodes ------------------------------------------------------------------------------
+// The rows are G virtual nodes of R <= 128 rows each, one after the other (a group of equal-sized
+// nodes whose products were taken as one).  Statistics, normalisation, the blend of the moving
+// statistics and the small-vector gradients are per node, in node order, exactly as G launches of
+// the kernels above would do them (same sums, same order).  A workgroup owns CB columns as
+// above but has up to four sub-groups of 256 threads, each working on a node of its own at the
+// same time (G = 8: two rounds); what couples the nodes -- the moving statistics, blended node
+// after node, and the gamma / beta gradients, added up in node order and folded in once -- goes
+// through LDS and is finished by one thread per column.  mean_out / rstd_out hold G vectors of C,
+// the transposed copy node n's rows at columns n*R .. n*R + R-1.
+template <int G, int SG_> struct GroupShape {
+  static constexpr int SG = SG_ < G ? SG_ : G;   // sub-groups side by side
+  static constexpr int RND = G / SG;             // rounds
+  static constexpr int THREADS = 256 * SG;
+};
+
+__device__ __forceinline__ void store_transposed_sub(const bf16_t (*tile)[RCH + 8], bf16_t* __restrict__ outT,
+                                                     int64_t ldt, int c0, int C, int R, int t) {
+  const int col = t >> 4, seg = t & 15;          // 16 columns x 16 segments of 8 rows
+  const int c = c0 + col;
+  const int rl = seg * 8;
+  if (c < C && rl < R)
+    *reinterpret_cast<uint4*>(&outT[(int64_t)c * ldt + rl]) = *reinterpret_cast<const uint4*>(&tile[col][rl]);
+}
+
+template <int NS, int G, int SGP>
+__global__ __launch_bounds__((GroupShape<G, SGP>::THREADS)) void bn_relu_fwd_group_kernel(
+    const float* zp, int64_t slab, int64_t ldzp, int R, int C, const float* __restrict__ gamma,
+    const float* __restrict__ beta, int round_params, float eps, float* z, int64_t ldz,
+    bf16_t* __restrict__ a, int64_t lda, bf16_t* __restrict__ aT, int64_t ldt, float* __restrict__ mean_out,
+    float* __restrict__ rstd_out, float* __restrict__ run_mean, float* __restrict__ run_var, float run_mix) {
+  constexpr int SG = GroupShape<G, SGP>::SG, RND = GroupShape<G, SGP>::RND;
+  __shared__ float red[SG][RL][CB + 1];
+  __shared__ __attribute__((aligned(16))) bf16_t tile[SG][CB][RCH + 8];
+  __shared__ float stat[G][2][CB];
+  const int sub = threadIdx.x >> 8, t = threadIdx.x & 255;
+  const int tx = t % CB, ty = t / CB;
+  const int c0 = xcd_column_block(blockIdx.x, gridDim.x) * CB;
+  const int c = c0 + tx;
+  const bool live = c < C;
+  const bool bn = gamma != nullptr;
+  const int cc = min(c, C - 1);
+  float g = 1.f, b = 0.f;
+  if (bn && live) { g = gamma[c]; b = beta[c]; }
+  // all rows of this sub-group's nodes, at clamped (always valid) addresses
+  float zr[RND][RPT];
+#pragma unroll
+  for (int q = 0; q < RND; ++q)
+#pragma unroll
+    for (int k = 0; k < RPT; ++k) {
+      const int r = ty + RL * k;
+      zr[q][k] = sum_slabs<NS>(zp, slab, (int64_t)((q * SG + sub) * R + min(r, R - 1)) * ldzp + cc);
+    }
+  if (bn && live && round_params) { g = round_bf16(g); b = round_bf16(b); }
+#pragma unroll
+  for (int q = 0; q < RND; ++q) {
+    const int n = q * SG + sub;
+    float mean = 0.f, rstd = 1.f;
+    float s = 0.f;
+#pragma unroll
+    for (int k = 0; k < RPT; ++k) {
+      const int r = ty + RL * k;
+      zr[q][k] = (live && r < R) ? zr[q][k] : 0.f;
+      s += zr[q][k];
+    }
+    if (NS > 1 || zp != z) {
+#pragma unroll
+      for (int k = 0; k < RPT; ++k) {
+        const int r = ty + RL * k;
+        if (live && r < R) z[(int64_t)(n * R + r) * ldz + c] = zr[q][k];
+      }
+    }
+    if (bn) {
+      mean = col_reduce(s, red[sub], tx, ty) / (float)R;
+      float qq = 0.f;
+#pragma unroll
+      for (int k = 0; k < RPT; ++k) {
+        const int r = ty + RL * k;
+        float d = (live && r < R) ? zr[q][k] - mean : 0.f;
+        qq = fmaf(d, d, qq);
+      }
+      const float var = col_reduce(qq, red[sub], tx, ty) / (float)R;
+      rstd = 1.0f / sqrtf(var + eps);
+      if (ty == 0) {
+        stat[n][0][tx] = mean; stat[n][1][tx] = var;
+        if (live) { mean_out[(int64_t)n * C + c] = mean; rstd_out[(int64_t)n * C + c] = rstd; }
+      }
+    } else if (q > 0 && aT) {
+      __syncthreads();                            // the tile of the round before has been read
+    }
+#pragma unroll
+    for (int k = 0; k < RPT; ++k) {
+      const int r = ty + RL * k;
+      float v = 0.f;
+      if (live && r < R) {
+        v = bn ? fmaxf(fmaf(g, (zr[q][k] - mean) * rstd, b), 0.f) : fmaxf(zr[q][k], 0.f);
+        a[(int64_t)(n * R + r) * lda + c] = f32_to_bf16(v);
+      }
+      if (aT) tile[sub][tx][r] = f32_to_bf16(v);
+    }
+    if (aT) {
+      __syncthreads();
+      store_transposed_sub(tile[sub], aT + n * R, ldt, c0, C, R, t);
+    }
+  }
+  // moving statistics of this device: one blend per pass, node after node (Section 4.1)
+  if (bn && run_mean) {
+    __syncthreads();
+    if (sub == 0 && ty == 0 && live) {
+      float rm = run_mean[c], rv = run_var[c];
+#pragma unroll
+      for (int n = 0; n < G; ++n) {
+        rm = fmaf(run_mix, stat[n][0][tx] - rm, rm);
+        rv = fmaf(run_mix, stat[n][1][tx] - rv, rv);
+      }
+      run_mean[c] = rm; run_var[c] = rv;
+    }
+  }
+}
+
+template <int NS, int G, int SGP>
+__global__ __launch_bounds__((GroupShape<G, SGP>::THREADS)) void bn_relu_bwd_group_kernel(
+    float* __restrict__ dap, int64_t slab, int64_t ldda, const float* __restrict__ z, int64_t ldz, int R, int C,
+    const float* __restrict__ gamma, const float* __restrict__ beta, int round_params,
+    const float* __restrict__ mean_in, const float* __restrict__ rstd_in, bf16_t* __restrict__ dz, int64_t lddz,
+    bf16_t* __restrict__ dzT, int64_t ldt, GradOut gout_g, GradOut gout_b, float tscale) {
+  constexpr int SG = GroupShape<G, SGP>::SG, RND = GroupShape<G, SGP>::RND;
+  __shared__ float red[SG][RL][CB + 1];
+  __shared__ __attribute__((aligned(16))) bf16_t tile[SG][CB][RCH + 8];
+  __shared__ float sums[G][2][CB];
+  const int sub = threadIdx.x >> 8, t = threadIdx.x & 255;
+  const int tx = t % CB, ty = t / CB;
+  const int c0 = xcd_column_block(blockIdx.x, gridDim.x) * CB;
+  const int c = c0 + tx;
+  const bool live = c < C;
+  const bool bn = gamma != nullptr;
+  const int cc = min(c, C - 1);
+  float g = 1.f, b = 0.f, mean[RND], rstd[RND];
+#pragma unroll
+  for (int q = 0; q < RND; ++q) { mean[q] = 0.f; rstd[q] = 1.f; }
+  if (live && bn) {
+    g = gamma[c]; b = beta[c];
+    if (round_params) { g = round_bf16(g); b = round_bf16(b); }
+#pragma unroll
+    for (int q = 0; q < RND; ++q) {
+      mean[q] = mean_in[(int64_t)(q * SG + sub) * C + c]; rstd[q] = rstd_in[(int64_t)(q * SG + sub) * C + c];
+    }
+  }
+  float xr[RND][RPT], dr[RND][RPT];
+#pragma unroll
+  for (int q = 0; q < RND; ++q)
+#pragma unroll
+    for (int k = 0; k < RPT; ++k) {
+      const int rc = (q * SG + sub) * R + min(ty + RL * k, R - 1);
+      xr[q][k] = z[(int64_t)rc * ldz + cc];
+      dr[q][k] = sum_slabs<NS>(dap, slab, (int64_t)rc * ldda + cc);
+    }
+  const float invR = 1.0f / (float)R;
+#pragma unroll
+  for (int q = 0; q < RND; ++q) {
+    const int n = q * SG + sub;
+    float sg = 0.f, sb = 0.f;
+#pragma unroll
+    for (int k = 0; k < RPT; ++k) {
+      const int r = ty + RL * k;
+      const float zz = xr[q][k];
+      const float xhat = (zz - mean[q]) * rstd[q];
+      const float pre = bn ? fmaf(g, xhat, b) : zz;
+      const bool on = live && r < R;
+      xr[q][k] = on ? xhat : 0.f;
+      dr[q][k] = (on && pre > 0.f) ? dr[q][k] : 0.f;
+      sg = fmaf(dr[q][k], xr[q][k], sg);
+      sb += dr[q][k];
+    }
+    sg = col_reduce(sg, red[sub], tx, ty);
+    sb = col_reduce(sb, red[sub], tx, ty);
+    if (ty == 0) { sums[n][0][tx] = sg; sums[n][1][tx] = sb; }
+    const float kk = g * rstd[q];
+#pragma unroll
+    for (int k = 0; k < RPT; ++k) {
+      const int r = ty + RL * k;
+      float v = 0.f;
+      if (live && r < R) {
+        v = bn ? kk * (dr[q][k] - sb * invR - xr[q][k] * sg * invR) : dr[q][k];
+        dz[(int64_t)(n * R + r) * lddz + c] = f32_to_bf16(v);
+      }
+      if (dzT) tile[sub][tx][r] = f32_to_bf16(v * tscale);
+    }
+    if (dzT) {
+      __syncthreads();                            // (the next round writes the tile behind its reductions' barriers)
+      store_transposed_sub(tile[sub], dzT + n * R, ldt, c0, C, R, t);
+    }
+  }
+  // the nodes of a group have one weight: their small-vector gradients are added up in node order
+  // and folded in once (what the staged path does with its staging vector, bit for bit)
+  __syncthreads();
+  if (sub == 0 && ty == 0 && live) {
+    float tg = 0.f, tb = 0.f;
+#pragma unroll
+    for (int n = 0; n < G; ++n) {
+      tg = n ? tg + sums[n][0][tx] : sums[n][0][tx];
+      tb = n ? tb + sums[n][1][tx] : sums[n][1][tx];
+    }
+    if (bn) grad_store(gout_g, c, tg);
+    if (gout_b.dst) grad_store(gout_b, c, tb);
+  }
+}
+
 constexpr int SCB = 32, SRL = 8;
 template <typename T>
 __global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ x, int64_t ld, int R, int C,
@@ -505,6 +570,15 @@ __global__ __launch_bounds__(256) void rowsum_nodes_kernel(NodeList nl, int64_t 
 
 }  // namespace
 
+// Sub-groups of 256 threads per workgroup of the group kernels: four while that is what it takes to
+// give every compute unit enough threads, two for wide layers (whose column blocks alone do).
+// VF_BN_SUBGROUPS = 2 | 4 overrides (tuning aid).
+int group_subgroups(int grid) {
+  static const int forced = std::getenv("VF_BN_SUBGROUPS") ? std::atoi(std::getenv("VF_BN_SUBGROUPS")) : 0;
+  if (forced == 2 || forced == 4) return forced;
+  return grid <= 256 ? 4 : 2;
+}
+
 int launch_bn_relu_fwd(const float* zp, int nsplit, int64_t slab, int64_t ldzp, int R, int C,
                        const float* gamma, const float* beta, int round_params, float eps, float* z,
                        int64_t ldz, void* a, int64_t lda, int a_is_bf16, bf16_t* aT, int64_t ldt,
@@ -514,16 +588,22 @@ int launch_bn_relu_fwd(const float* zp, int nsplit, int64_t slab, int64_t ldzp, 
   if ((run_mean == nullptr) != (run_var == nullptr)) return VF_EINVAL;
   if (aT && ((ldt & 7) || !a_is_bf16)) return VF_EINVAL;
   const int grid = (C + CB - 1) / CB;
+  const int subgroups = group_subgroups(grid);
   const bool small = R <= RCH;
   if (group != 1 && (!small || !a_is_bf16 || (group != 2 && group != 4 && group != 8) || (aT && (R & 7)))) return VF_EINVAL;
 #define VF_FWD2(TT, NS, SM, GG)                                                                    \
   bn_relu_fwd_kernel<TT, NS, SM, GG><<<grid, 256, 0, s>>>(zp, slab, ldzp, R, C, gamma, beta, round_params, \
       eps, z, ldz, static_cast<TT*>(a), lda, aT, ldt, mean, rstd, run_mean, run_var, run_mix)
+#define VF_FWDG1(NS, GG, SS)                                                                        \
+  bn_relu_fwd_group_kernel<NS, GG, SS><<<grid, GroupShape<GG, SS>::THREADS, 0, s>>>(zp, slab, ldzp, R, C, gamma, beta, \
+      round_params, eps, z, ldz, static_cast<bf16_t*>(a), lda, aT, ldt, mean, rstd, run_mean, run_var, run_mix)
+#define VF_FWDG(NS, GG)                                                                            \
+  do { if (subgroups == 4) VF_FWDG1(NS, GG, 4); else VF_FWDG1(NS, GG, 2); } while (0)
 #define VF_FWD(NS)                                                                                 \
   case NS:                                                                                         \
-    if (group == 2) VF_FWD2(bf16_t, NS, true, 2);                                                  \
-    else if (group == 4) VF_FWD2(bf16_t, NS, true, 4);                                             \
-    else if (group == 8) VF_FWD2(bf16_t, NS, true, 8);                                             \
+    if (group == 2) VF_FWDG(NS, 2);                                                                \
+    else if (group == 4) VF_FWDG(NS, 4);                                                           \
+    else if (group == 8) VF_FWDG(NS, 8);                                                           \
     else if (a_is_bf16) { if (small) VF_FWD2(bf16_t, NS, true, 1); else VF_FWD2(bf16_t, NS, false, 1); } \
     else           { if (small) VF_FWD2(float, NS, true, 1);  else VF_FWD2(float, NS, false, 1); } \
     break;
@@ -532,6 +612,8 @@ int launch_bn_relu_fwd(const float* zp, int nsplit, int64_t slab, int64_t ldzp, 
     default: return VF_EINVAL;
   }
 #undef VF_FWD
+#undef VF_FWDG
+#undef VF_FWDG1
 #undef VF_FWD2
   VF_LAUNCH_CHECK();
   return VF_OK;
@@ -545,16 +627,22 @@ int launch_bn_relu_bwd(float* dap, int nsplit, int64_t slab, int64_t ldda, const
   if (R <= 0 || C <= 0 || nsplit < 1) return VF_EINVAL;
   if (dzT && ((ldt & 7) || !dz_is_bf16)) return VF_EINVAL;
   const int grid = (C + CB - 1) / CB;
+  const int subgroups = group_subgroups(grid);
   const bool small = R <= RCH;
   if (group != 1 && (!small || !dz_is_bf16 || (group != 2 && group != 4 && group != 8) || (dzT && (R & 7)))) return VF_EINVAL;
 #define VF_BWD2(TT, NS, SM, GG)                                                                    \
   bn_relu_bwd_kernel<TT, NS, SM, GG><<<grid, 256, 0, s>>>(dap, slab, ldda, z, ldz, R, C, gamma, beta,  \
       round_params, mean, rstd, static_cast<TT*>(dz), lddz, dzT, ldt, gout_g, gout_b, tscale)
+#define VF_BWDG1(NS, GG, SS)                                                                        \
+  bn_relu_bwd_group_kernel<NS, GG, SS><<<grid, GroupShape<GG, SS>::THREADS, 0, s>>>(dap, slab, ldda, z, ldz, R, C, gamma, \
+      beta, round_params, mean, rstd, static_cast<bf16_t*>(dz), lddz, dzT, ldt, gout_g, gout_b, tscale)
+#define VF_BWDG(NS, GG)                                                                            \
+  do { if (subgroups == 4) VF_BWDG1(NS, GG, 4); else VF_BWDG1(NS, GG, 2); } while (0)
 #define VF_BWD(NS)                                                                                 \
   case NS:                                                                                         \
-    if (group == 2) VF_BWD2(bf16_t, NS, true, 2);                                                  \
-    else if (group == 4) VF_BWD2(bf16_t, NS, true, 4);                                             \
-    else if (group == 8) VF_BWD2(bf16_t, NS, true, 8);                                             \
+    if (group == 2) VF_BWDG(NS, 2);                                                                \
+    else if (group == 4) VF_BWDG(NS, 4);                                                           \
+    else if (group == 8) VF_BWDG(NS, 8);                                                           \
     else if (dz_is_bf16) { if (small) VF_BWD2(bf16_t, NS, true, 1); else VF_BWD2(bf16_t, NS, false, 1); } \
     else            { if (small) VF_BWD2(float, NS, true, 1);  else VF_BWD2(float, NS, false, 1); } \
     break;
@@ -563,6 +651,8 @@ int launch_bn_relu_bwd(float* dap, int nsplit, int64_t slab, int64_t ldda, const
     default: return VF_EINVAL;
   }
 #undef VF_BWD
+#undef VF_BWDG
+#undef VF_BWDG1
 #undef VF_BWD2
   VF_LAUNCH_CHECK();
   return VF_OK;
