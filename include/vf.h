@@ -142,14 +142,20 @@ typedef struct vf_config {
   int32_t max_node_size;         /* largest b_i; sizes the per-node workspace */
   int32_t max_nodes;             /* largest V */
   int32_t fold_window;           /* MLP, bf16, fused fold: the weight gradients of this many
-                                    consecutive nodes (1..8; 0 = 1) are folded into the gradient
-                                    buffer in one pass over it.  Same chain of fused multiply-adds
-                                    as node by node (bitwise the same result), 1/window of the
-                                    buffer traffic; the transposed bf16 operands of the window's
-                                    nodes are kept until then, so the workspace grows with the
-                                    window (not with V). */
+                                    consecutive nodes (1..8; 0 = 1; with node_group > 1: of this
+                                    many units of grouped nodes) are folded into the gradient
+                                    buffer in one pass over it: nodes of one size (one weight
+                                    b_i/B) as ONE product over all their rows, nodes of several
+                                    sizes (multiples of 8) as one product with the weights folded
+                                    into the transposed output gradients, other sizes -- or any
+                                    with VF_FLAG_ORDERED_FOLD -- as the chain of fused
+                                    multiply-adds of the node-by-node fold (bitwise its result).
+                                    1/window of the buffer traffic; the transposed bf16 operands of
+                                    the window's nodes are kept until then, so the workspace grows
+                                    with the window (not with V). */
   int32_t node_group;            /* MLP (bf16) and encoder: up to this many CONSECUTIVE nodes of one
-                                    size (1, 2, 4 or 8; 0 = 1; the encoder takes at most 4) go through their passes together:
+                                    size (1, 2, 4 or 8; 0 = 1; the encoder takes at most 4) go through
+                                    their passes together:
                                     their rows form one operand of every product, so the weights
                                     are read once per group instead of once per node.  Everything a
                                     node owns stays per node -- BatchNorm statistics and their
