@@ -26,28 +26,30 @@ __global__ __launch_bounds__(kThreads) void accumulate_kernel(float* __restrict_
                                                               int64_t n) {
   const int64_t nvec = n >> 2;
   const int64_t base = (int64_t)blockIdx.x * (kThreads * kVecPerThread) + threadIdx.x;
-  float4 gv[kVecPerThread], bv[kVecPerThread];
+  if (nvec > 0) {   // (fewer than four elements: only the scalar tail below)
+    // loads at clamped (always valid) positions, so that none sits behind a branch and all of a
+    // thread's requests are in flight together; the stores below are guarded (n >= 4 here)
+    float4 gv[kVecPerThread], bv[kVecPerThread];
 #pragma unroll
-  for (int i = 0; i < kVecPerThread; ++i) {
-    int64_t v = base + (int64_t)i * kThreads;
-    if (v < nvec) {
+    for (int i = 0; i < kVecPerThread; ++i) {
+      const int64_t v = min(base + (int64_t)i * kThreads, nvec - 1);
       gv[i] = reinterpret_cast<const float4*>(g)[v];
       if (!FIRST) bv[i] = reinterpret_cast<const float4*>(buf)[v];
     }
-  }
 #pragma unroll
-  for (int i = 0; i < kVecPerThread; ++i) {
-    int64_t v = base + (int64_t)i * kThreads;
-    if (v < nvec) {
-      float4 o;
-      if (FIRST) {
-        o.x = fmaf(w, gv[i].x, 0.f); o.y = fmaf(w, gv[i].y, 0.f);
-        o.z = fmaf(w, gv[i].z, 0.f); o.w = fmaf(w, gv[i].w, 0.f);
-      } else {
-        o.x = fmaf(w, gv[i].x, bv[i].x); o.y = fmaf(w, gv[i].y, bv[i].y);
-        o.z = fmaf(w, gv[i].z, bv[i].z); o.w = fmaf(w, gv[i].w, bv[i].w);
+    for (int i = 0; i < kVecPerThread; ++i) {
+      int64_t v = base + (int64_t)i * kThreads;
+      if (v < nvec) {
+        float4 o;
+        if (FIRST) {
+          o.x = fmaf(w, gv[i].x, 0.f); o.y = fmaf(w, gv[i].y, 0.f);
+          o.z = fmaf(w, gv[i].z, 0.f); o.w = fmaf(w, gv[i].w, 0.f);
+        } else {
+          o.x = fmaf(w, gv[i].x, bv[i].x); o.y = fmaf(w, gv[i].y, bv[i].y);
+          o.z = fmaf(w, gv[i].z, bv[i].z); o.w = fmaf(w, gv[i].w, bv[i].w);
+        }
+        reinterpret_cast<float4*>(buf)[v] = o;
       }
-      reinterpret_cast<float4*>(buf)[v] = o;
     }
   }
   // scalar tail (n not a multiple of 4): handled by the last block's first threads
@@ -63,27 +65,27 @@ __global__ __launch_bounds__(kThreads) void sgdm_kernel(float* __restrict__ thet
                                                         float mu, int64_t n) {
   const int64_t nvec = n >> 2;
   const int64_t base = (int64_t)blockIdx.x * (kThreads * kVecPerThread) + threadIdx.x;
-  float4 gv[kVecPerThread], tv[kVecPerThread], vv[kVecPerThread];
+  if (nvec > 0) {   // (fewer than four elements: only the scalar tail below)
+    float4 gv[kVecPerThread], tv[kVecPerThread], vv[kVecPerThread];
 #pragma unroll
-  for (int i = 0; i < kVecPerThread; ++i) {
-    int64_t v = base + (int64_t)i * kThreads;
-    if (v < nvec) {
+    for (int i = 0; i < kVecPerThread; ++i) {       // clamped positions: no load behind a branch
+      const int64_t v = min(base + (int64_t)i * kThreads, nvec - 1);
       gv[i] = reinterpret_cast<const float4*>(G)[v];
       tv[i] = reinterpret_cast<const float4*>(theta)[v];
       vv[i] = reinterpret_cast<const float4*>(vel)[v];
     }
-  }
 #pragma unroll
-  for (int i = 0; i < kVecPerThread; ++i) {
-    int64_t v = base + (int64_t)i * kThreads;
-    if (v < nvec) {
-      float4 nv, nt;
-      nv.x = fmaf(mu, vv[i].x, gv[i].x); nv.y = fmaf(mu, vv[i].y, gv[i].y);
-      nv.z = fmaf(mu, vv[i].z, gv[i].z); nv.w = fmaf(mu, vv[i].w, gv[i].w);
-      nt.x = fmaf(-lr, nv.x, tv[i].x); nt.y = fmaf(-lr, nv.y, tv[i].y);
-      nt.z = fmaf(-lr, nv.z, tv[i].z); nt.w = fmaf(-lr, nv.w, tv[i].w);
-      reinterpret_cast<float4*>(vel)[v] = nv;
-      reinterpret_cast<float4*>(theta)[v] = nt;
+    for (int i = 0; i < kVecPerThread; ++i) {
+      int64_t v = base + (int64_t)i * kThreads;
+      if (v < nvec) {
+        float4 nv, nt;
+        nv.x = fmaf(mu, vv[i].x, gv[i].x); nv.y = fmaf(mu, vv[i].y, gv[i].y);
+        nv.z = fmaf(mu, vv[i].z, gv[i].z); nv.w = fmaf(mu, vv[i].w, gv[i].w);
+        nt.x = fmaf(-lr, nv.x, tv[i].x); nt.y = fmaf(-lr, nv.y, tv[i].y);
+        nt.z = fmaf(-lr, nv.z, tv[i].z); nt.w = fmaf(-lr, nv.w, tv[i].w);
+        reinterpret_cast<float4*>(vel)[v] = nv;
+        reinterpret_cast<float4*>(theta)[v] = nt;
+      }
     }
   }
   if (blockIdx.x == gridDim.x - 1) {
@@ -113,28 +115,28 @@ __global__ __launch_bounds__(kThreads) void adam_kernel(float* __restrict__ thet
                                                         float inv_c2, int64_t n) {
   const int64_t nvec = n >> 2;
   const int64_t base = (int64_t)blockIdx.x * (kThreads * kVecPerThread) + threadIdx.x;
-  float4 gv[kVecPerThread], tv[kVecPerThread], mv[kVecPerThread], uv[kVecPerThread];
+  if (nvec > 0) {   // (fewer than four elements: only the scalar tail below)
+    float4 gv[kVecPerThread], tv[kVecPerThread], mv[kVecPerThread], uv[kVecPerThread];
 #pragma unroll
-  for (int i = 0; i < kVecPerThread; ++i) {
-    int64_t v = base + (int64_t)i * kThreads;
-    if (v < nvec) {
+    for (int i = 0; i < kVecPerThread; ++i) {       // clamped positions: no load behind a branch
+      const int64_t v = min(base + (int64_t)i * kThreads, nvec - 1);
       gv[i] = reinterpret_cast<const float4*>(G)[v];
       tv[i] = reinterpret_cast<const float4*>(theta)[v];
       mv[i] = reinterpret_cast<const float4*>(m1)[v];
       uv[i] = reinterpret_cast<const float4*>(m2)[v];
     }
-  }
 #pragma unroll
-  for (int i = 0; i < kVecPerThread; ++i) {
-    int64_t v = base + (int64_t)i * kThreads;
-    if (v < nvec) {
-      adam_one(gv[i].x, tv[i].x, mv[i].x, uv[i].x, lr, b1, b2, eps, inv_c1, inv_c2);
-      adam_one(gv[i].y, tv[i].y, mv[i].y, uv[i].y, lr, b1, b2, eps, inv_c1, inv_c2);
-      adam_one(gv[i].z, tv[i].z, mv[i].z, uv[i].z, lr, b1, b2, eps, inv_c1, inv_c2);
-      adam_one(gv[i].w, tv[i].w, mv[i].w, uv[i].w, lr, b1, b2, eps, inv_c1, inv_c2);
-      reinterpret_cast<float4*>(m1)[v] = mv[i];
-      reinterpret_cast<float4*>(m2)[v] = uv[i];
-      reinterpret_cast<float4*>(theta)[v] = tv[i];
+    for (int i = 0; i < kVecPerThread; ++i) {
+      int64_t v = base + (int64_t)i * kThreads;
+      if (v < nvec) {
+        adam_one(gv[i].x, tv[i].x, mv[i].x, uv[i].x, lr, b1, b2, eps, inv_c1, inv_c2);
+        adam_one(gv[i].y, tv[i].y, mv[i].y, uv[i].y, lr, b1, b2, eps, inv_c1, inv_c2);
+        adam_one(gv[i].z, tv[i].z, mv[i].z, uv[i].z, lr, b1, b2, eps, inv_c1, inv_c2);
+        adam_one(gv[i].w, tv[i].w, mv[i].w, uv[i].w, lr, b1, b2, eps, inv_c1, inv_c2);
+        reinterpret_cast<float4*>(m1)[v] = mv[i];
+        reinterpret_cast<float4*>(m2)[v] = uv[i];
+        reinterpret_cast<float4*>(theta)[v] = tv[i];
+      }
     }
   }
   if (blockIdx.x == gridDim.x - 1) {
