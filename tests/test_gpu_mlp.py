@@ -153,10 +153,11 @@ def test_full_size_configurations(name, flags, window, group):
 def test_c5_full_size_launch_configuration():
     """Large-batch emulation: MLP 2048-8192x6-1000 + BatchNorm, 64 nodes of 128 (B = 8192), in the
     launch configuration bench.py times (fused fold, two streams, launches one by one, groups
-    of 8 nodes per pass, windows of 8 groups).  The oracle can afford single nodes of this model: it evaluates the four
-    distinct nodes 0..3, and the device runs V = 64 nodes of which node i holds the rows of node
-    i mod 4 -- the combined gradient is then (g_0 + g_1 + g_2 + g_3)/4 (Section 5.2 with 64 weights
-    of 1/64), every fold of step 3 and the update of step 5 run over all 64 nodes.
+    of 8 nodes per pass, windows of 8 groups).  The oracle can afford single nodes of this model: it
+    evaluates the eight distinct nodes 0..7 (one whole unit of the device's passes), and the device
+    runs V = 64 nodes of which node i holds the rows of node i mod 8 -- the combined gradient is then
+    (g_0 + .. + g_7)/8 (Section 5.2 with 64 weights of 1/64), every fold of step 3 and the update of
+    step 5 run over all 64 nodes.
 
     Tolerance.  Six BatchNorm+ReLU layers with bf16 operands are sensitive to rounding: a
     difference delta of a pre-activation moves about delta/ulp of the bf16 roundings of the
@@ -174,17 +175,19 @@ def test_c5_full_size_launch_configuration():
     theta = I.make_params(wl)
     x, y = I.make_batch(wl)
     cp = compute_copy(wl, theta)
-    K = 4
-    Ls, gs, galt = [], [], []
+    K = 8
+    Ls, want, alt = [], 0.0, 0.0
     for k in range(K):
         lo, hi = 128 * k, 128 * (k + 1)
         L_k, g_k = O.node_loss_and_grads(wl, cp, x[lo:hi], y[lo:hi])
         with float32_products():
             _, a_k = O.node_loss_and_grads(wl, cp, x[lo:hi], y[lo:hi])
-        Ls.append(L_k); gs.append(g_k); galt.append(a_k)
+        Ls.append(L_k)
+        want = want + g_k / K                     # (b_i / B with eight equal nodes)
+        alt = alt + a_k / K
+        del g_k, a_k
         print(f"oracle node {k} done", flush=True)
     del cp
-    want, alt = sum(gs) / K, sum(galt) / K
     Lw = sum(Ls) / K
     tol = TOL["bf16"]
     second = {n: r for n, r, _ in tensor_errors(wl, alt, want)}
@@ -208,16 +211,14 @@ def test_c5_full_size_launch_configuration():
     check_update_from_own_gradient(wl, gpu, theta)
     G64 = gpu["G"].copy()
     del gpu, xa, ya
-    # the same four nodes once: 64 folds of g/64 against 4 folds of g/4 (fp32 rounding only)
-    # the same four nodes as ONE group of eight: eight such groups in one window against that (fp32 rounding only)
-    # (one unit of the same shape, eight nodes: at this depth another shape of the products, which means
+    # the same eight nodes as ONE unit: eight such units in one window against that (fp32 rounding only;
+    # a unit of another shape would not do: at this depth another shape of the products, which means
     # another order of fp32 sums, already moves the early layers by percents)
-    reps = BENCH_GROUP // K
-    four = run_gpu(wl.with_nodes([128] * BENCH_GROUP), theta, np.tile(x[:128 * K], (reps, 1)), np.tile(y[:128 * K], reps),
-                   flags=BENCH, fold_window=8, node_group=BENCH_GROUP)
-    assert np.linalg.norm(G64 - four["G"]) <= 1e-6 * np.linalg.norm(four["G"])
-    del four
-    # the bound that does not depend on where operands are rounded (node 0 .. 3, weights only)
+    once = run_gpu(wl.with_nodes([128] * K), theta, x[:128 * K], y[:128 * K], flags=BENCH, fold_window=8,
+                   node_group=BENCH_GROUP)
+    assert np.linalg.norm(G64 - once["G"]) <= 1e-6 * np.linalg.norm(once["G"])
+    del once
+    # the bound that does not depend on where operands are rounded (nodes 0 .. 7, weights only)
     gw = weights_only_gradient(wl.with_nodes([128] * K), theta, x[:128 * K], y[:128 * K])
     check_independent_bound(wl, G64, want, gw, "C5")
 
