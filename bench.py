@@ -94,20 +94,22 @@ def algorithmic_work(wl, P, fused=False, window=1, group=1):
 
 
 def pass_units(wl, group):
-    """Units that go through the passes of a step: the nodes, or (the library's rule) runs of 2 or 4
-    consecutive equal-sized nodes where the model takes groups (bf16 MLP with nodes of at most 128
-    rows, a multiple of 8; the encoder)."""
-    sizes, ok = list(wl.node_sizes), False
-    if group > 1:
-        ok = wl.kind == "encoder" or (wl.kind == "mlp" and wl.dtype == "bf16")
-    units, i = 0, 0
+    """Units that go through the passes of a step: the nodes, or (the library's rule) runs of up to
+    `group` consecutive nodes where the model takes groups -- bf16 MLP: nodes of at most 128 rows, a
+    multiple of 8, of any mix of sizes; encoder: 2 or 4 nodes of one size."""
+    sizes, units, i = list(wl.node_sizes), 0, 0
+    mlp = wl.kind == "mlp" and wl.dtype == "bf16"
+    enc = wl.kind == "encoder"
     while i < len(sizes):
         take = 1
-        if ok and (wl.kind == "encoder" or (sizes[i] <= 128 and sizes[i] % 8 == 0)):
-            run, most = 1, (min(group, 4) if wl.kind == "encoder" else group)
+        if group > 1 and mlp and sizes[i] <= 128 and sizes[i] % 8 == 0:
+            while i + take < len(sizes) and take < group and sizes[i + take] <= 128 and sizes[i + take] % 8 == 0:
+                take += 1
+        elif group > 1 and enc:
+            run, most = 1, min(group, 4)
             while i + run < len(sizes) and run < most and sizes[i + run] == sizes[i]:
                 run += 1
-            take = 8 if run >= 8 else (4 if run >= 4 else (2 if run >= 2 else 1))
+            take = 4 if run >= 4 else (2 if run >= 2 else 1)
         units += 1
         i += take
     return units
@@ -330,7 +332,7 @@ def main():
                          "into the gradient buffer in one pass (nodes of one size: one product over the "
                          "window's rows; the workspace keeps that many nodes' transposed bf16 operands)")
     ap.add_argument("--node-group", type=int, choices=[1, 2, 4, 8], default=8,
-                    help="up to this many consecutive equal-sized nodes go through their passes together "
+                    help="up to this many consecutive nodes go through their passes together "
                          "(one operand of every product, so the weights are read once per group; BatchNorm "
                          "statistics, node losses and weights stay per node); 1: node after node")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -444,7 +446,7 @@ def bench_workload(name, args, primary):
                    "fold_window": window, "workspace_bytes": eng.workspace_bytes,
                    "streams": eng.streams, "launch": args.launch,
                    "node_group": args.node_group, "pass_units": pass_units(wl, args.node_group),
-                   "value_is": ("%d units of up to %d equal-sized nodes go through the passes one after another "
+                   "value_is": ("%d units of up to %d nodes go through the passes one after another "
                                 "(a group's rows are one operand of every product; BatchNorm statistics, losses "
                                 "and weights b_i/B per node); fused fold with a window of %d units: the weight "
                                 "gradients of a window are ONE product over its rows (the weighted sum of "

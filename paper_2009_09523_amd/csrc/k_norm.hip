@@ -322,6 +322,10 @@ __global__ __launch_bounds__(256) void bn_relu_bwd_kernel(float* __restrict__ da
 // after node, and the gamma / beta gradients, added up in node order and folded in once -- goes
 // through LDS and is finished by one thread per column.  mean_out / rstd_out hold G vectors of C,
 // the transposed copy node n's rows at columns n*R .. n*R + R-1.
+// Row ranges of the nodes of a unit: node n has rows[n] <= 128 rows starting at row base[n] of the
+// unit (a multiple of 8 when transposed copies are written); entries beyond the unit's nodes are 0.
+struct GroupRows { int base[8]; int rows[8]; };
+
 template <int G, int SG_> struct GroupShape {
   static constexpr int SG = SG_ < G ? SG_ : G;   // sub-groups side by side
   static constexpr int RND = G / SG;             // rounds
@@ -339,7 +343,7 @@ __device__ __forceinline__ void store_transposed_sub(const bf16_t (*tile)[RCH + 
 
 template <int NS, int G, int SGP>
 __global__ __launch_bounds__((GroupShape<G, SGP>::THREADS)) void bn_relu_fwd_group_kernel(
-    const float* zp, int64_t slab, int64_t ldzp, int R, int C, const float* __restrict__ gamma,
+    const float* zp, int64_t slab, int64_t ldzp, GroupRows gr, int count, int C, const float* __restrict__ gamma,
     const float* __restrict__ beta, int round_params, float eps, float* z, int64_t ldz,
     bf16_t* __restrict__ a, int64_t lda, bf16_t* __restrict__ aT, int64_t ldt, float* __restrict__ mean_out,
     float* __restrict__ rstd_out, float* __restrict__ run_mean, float* __restrict__ run_var, float run_mix) {
@@ -363,12 +367,14 @@ __global__ __launch_bounds__((GroupShape<G, SGP>::THREADS)) void bn_relu_fwd_gro
 #pragma unroll
     for (int k = 0; k < RPT; ++k) {
       const int r = ty + RL * k;
-      zr[q][k] = sum_slabs<NS>(zp, slab, (int64_t)((q * SG + sub) * R + min(r, R - 1)) * ldzp + cc);
+      const int n = q * SG + sub;
+      zr[q][k] = sum_slabs<NS>(zp, slab, (int64_t)(gr.base[n] + max(min(r, gr.rows[n] - 1), 0)) * ldzp + cc);
     }
   if (bn && live && round_params) { g = round_bf16(g); b = round_bf16(b); }
 #pragma unroll
   for (int q = 0; q < RND; ++q) {
     const int n = q * SG + sub;
+    const int R = gr.rows[n], rb = gr.base[n];    // (R = 0 behind the unit's last node: nothing is stored)
     float mean = 0.f, rstd = 1.f;
     float s = 0.f;
 #pragma unroll
@@ -381,7 +387,7 @@ __global__ __launch_bounds__((GroupShape<G, SGP>::THREADS)) void bn_relu_fwd_gro
 #pragma unroll
       for (int k = 0; k < RPT; ++k) {
         const int r = ty + RL * k;
-        if (live && r < R) z[(int64_t)(n * R + r) * ldz + c] = zr[q][k];
+        if (live && r < R) z[(int64_t)(rb + r) * ldz + c] = zr[q][k];
       }
     }
     if (bn) {
@@ -397,7 +403,7 @@ __global__ __launch_bounds__((GroupShape<G, SGP>::THREADS)) void bn_relu_fwd_gro
       rstd = 1.0f / sqrtf(var + eps);
       if (ty == 0) {
         stat[n][0][tx] = mean; stat[n][1][tx] = var;
-        if (live) { mean_out[(int64_t)n * C + c] = mean; rstd_out[(int64_t)n * C + c] = rstd; }
+        if (live && n < count) { mean_out[(int64_t)n * C + c] = mean; rstd_out[(int64_t)n * C + c] = rstd; }
       }
     } else if (q > 0 && aT) {
       __syncthreads();                            // the tile of the round before has been read
@@ -408,13 +414,13 @@ __global__ __launch_bounds__((GroupShape<G, SGP>::THREADS)) void bn_relu_fwd_gro
       float v = 0.f;
       if (live && r < R) {
         v = bn ? fmaxf(fmaf(g, (zr[q][k] - mean) * rstd, b), 0.f) : fmaxf(zr[q][k], 0.f);
-        a[(int64_t)(n * R + r) * lda + c] = f32_to_bf16(v);
+        a[(int64_t)(rb + r) * lda + c] = f32_to_bf16(v);
       }
       if (aT) tile[sub][tx][r] = f32_to_bf16(v);
     }
     if (aT) {
       __syncthreads();
-      store_transposed_sub(tile[sub], aT + n * R, ldt, c0, C, R, t);
+      store_transposed_sub(tile[sub], aT + rb, ldt, c0, C, R, t);
     }
   }
   // moving statistics of this device: one blend per pass, node after node (Section 4.1)
@@ -424,8 +430,10 @@ __global__ __launch_bounds__((GroupShape<G, SGP>::THREADS)) void bn_relu_fwd_gro
       float rm = run_mean[c], rv = run_var[c];
 #pragma unroll
       for (int n = 0; n < G; ++n) {
-        rm = fmaf(run_mix, stat[n][0][tx] - rm, rm);
-        rv = fmaf(run_mix, stat[n][1][tx] - rv, rv);
+        if (n < count) {
+          rm = fmaf(run_mix, stat[n][0][tx] - rm, rm);
+          rv = fmaf(run_mix, stat[n][1][tx] - rv, rv);
+        }
       }
       run_mean[c] = rm; run_var[c] = rv;
     }
@@ -434,7 +442,8 @@ __global__ __launch_bounds__((GroupShape<G, SGP>::THREADS)) void bn_relu_fwd_gro
 
 template <int NS, int G, int SGP>
 __global__ __launch_bounds__((GroupShape<G, SGP>::THREADS)) void bn_relu_bwd_group_kernel(
-    float* __restrict__ dap, int64_t slab, int64_t ldda, const float* __restrict__ z, int64_t ldz, int R, int C,
+    float* __restrict__ dap, int64_t slab, int64_t ldda, const float* __restrict__ z, int64_t ldz, GroupRows gr,
+    int count, int C,
     const float* __restrict__ gamma, const float* __restrict__ beta, int round_params,
     const float* __restrict__ mean_in, const float* __restrict__ rstd_in, bf16_t* __restrict__ dz, int64_t lddz,
     bf16_t* __restrict__ dzT, int64_t ldt, GradOut gout_g, GradOut gout_b, float tscale) {
@@ -465,14 +474,15 @@ __global__ __launch_bounds__((GroupShape<G, SGP>::THREADS)) void bn_relu_bwd_gro
   for (int q = 0; q < RND; ++q)
 #pragma unroll
     for (int k = 0; k < RPT; ++k) {
-      const int rc = (q * SG + sub) * R + min(ty + RL * k, R - 1);
+      const int rc = gr.base[q * SG + sub] + max(min(ty + RL * k, gr.rows[q * SG + sub] - 1), 0);
       xr[q][k] = z[(int64_t)rc * ldz + cc];
       dr[q][k] = sum_slabs<NS>(dap, slab, (int64_t)rc * ldda + cc);
     }
-  const float invR = 1.0f / (float)R;
 #pragma unroll
   for (int q = 0; q < RND; ++q) {
     const int n = q * SG + sub;
+    const int R = gr.rows[n], rb = gr.base[n];    // (R = 0 behind the unit's last node: nothing is stored)
+    const float invR = 1.0f / (float)R;
     float sg = 0.f, sb = 0.f;
 #pragma unroll
     for (int k = 0; k < RPT; ++k) {
@@ -496,13 +506,13 @@ __global__ __launch_bounds__((GroupShape<G, SGP>::THREADS)) void bn_relu_bwd_gro
       float v = 0.f;
       if (live && r < R) {
         v = bn ? kk * (dr[q][k] - sb * invR - xr[q][k] * sg * invR) : dr[q][k];
-        dz[(int64_t)(n * R + r) * lddz + c] = f32_to_bf16(v);
+        dz[(int64_t)(rb + r) * lddz + c] = f32_to_bf16(v);
       }
       if (dzT) tile[sub][tx][r] = f32_to_bf16(v * tscale);
     }
     if (dzT) {
       __syncthreads();                            // (the next round writes the tile behind its reductions' barriers)
-      store_transposed_sub(tile[sub], dzT + n * R, ldt, c0, C, R, t);
+      store_transposed_sub(tile[sub], dzT + rb, ldt, c0, C, R, t);
     }
   }
   // the nodes of a group have one weight: their small-vector gradients are added up in node order
@@ -512,8 +522,10 @@ __global__ __launch_bounds__((GroupShape<G, SGP>::THREADS)) void bn_relu_bwd_gro
     float tg = 0.f, tb = 0.f;
 #pragma unroll
     for (int n = 0; n < G; ++n) {
-      tg = n ? tg + sums[n][0][tx] : sums[n][0][tx];
-      tb = n ? tb + sums[n][1][tx] : sums[n][1][tx];
+      if (n < count) {
+        tg = n ? tg + sums[n][0][tx] : sums[n][0][tx];
+        tb = n ? tb + sums[n][1][tx] : sums[n][1][tx];
+      }
     }
     if (bn) grad_store(gout_g, c, tg);
     if (gout_b.dst) grad_store(gout_b, c, tb);
@@ -579,31 +591,51 @@ int group_subgroups(int grid) {
   return grid <= 256 ? 4 : 2;
 }
 
+// The row ranges of a unit's nodes for the group kernels: `group` nodes of R rows each, or of
+// node_rows[n] rows when given.  Every node at most 128 rows; ranges start on multiples of 8 when
+// transposed copies are written.
+int group_rows(int group, int R, const int* node_rows, bool transposed, GroupRows* gr) {
+  if (group < 2 || group > 8) return VF_EINVAL;
+  int at = 0;
+  for (int n = 0; n < 8; ++n) {
+    const int rows = n < group ? (node_rows ? node_rows[n] : R) : 0;
+    if (n < group && (rows < 1 || rows > RCH || (transposed && (rows & 7)))) return VF_EINVAL;
+    gr->base[n] = n < group ? at : 0;
+    gr->rows[n] = rows;
+    at += rows;
+  }
+  return VF_OK;
+}
+
 int launch_bn_relu_fwd(const float* zp, int nsplit, int64_t slab, int64_t ldzp, int R, int C,
                        const float* gamma, const float* beta, int round_params, float eps, float* z,
                        int64_t ldz, void* a, int64_t lda, int a_is_bf16, bf16_t* aT, int64_t ldt,
                        float* mean, float* rstd, float* run_mean, float* run_var, float run_mix,
-                       hipStream_t s, int group) {
+                       hipStream_t s, int group, const int* node_rows) {
   if (R <= 0 || C <= 0 || nsplit < 1) return VF_EINVAL;
   if ((run_mean == nullptr) != (run_var == nullptr)) return VF_EINVAL;
   if (aT && ((ldt & 7) || !a_is_bf16)) return VF_EINVAL;
   const int grid = (C + CB - 1) / CB;
   const int subgroups = group_subgroups(grid);
   const bool small = R <= RCH;
-  if (group != 1 && (!small || !a_is_bf16 || (group != 2 && group != 4 && group != 8) || (aT && (R & 7)))) return VF_EINVAL;
+  GroupRows gr{};
+  if (group != 1) {
+    if (!a_is_bf16) return VF_EINVAL;
+    VF_TRY(group_rows(group, R, node_rows, aT != nullptr, &gr));
+  }
 #define VF_FWD2(TT, NS, SM, GG)                                                                    \
   bn_relu_fwd_kernel<TT, NS, SM, GG><<<grid, 256, 0, s>>>(zp, slab, ldzp, R, C, gamma, beta, round_params, \
       eps, z, ldz, static_cast<TT*>(a), lda, aT, ldt, mean, rstd, run_mean, run_var, run_mix)
 #define VF_FWDG1(NS, GG, SS)                                                                        \
-  bn_relu_fwd_group_kernel<NS, GG, SS><<<grid, GroupShape<GG, SS>::THREADS, 0, s>>>(zp, slab, ldzp, R, C, gamma, beta, \
+  bn_relu_fwd_group_kernel<NS, GG, SS><<<grid, GroupShape<GG, SS>::THREADS, 0, s>>>(zp, slab, ldzp, gr, group, C, gamma, beta, \
       round_params, eps, z, ldz, static_cast<bf16_t*>(a), lda, aT, ldt, mean, rstd, run_mean, run_var, run_mix)
 #define VF_FWDG(NS, GG)                                                                            \
   do { if (subgroups == 4) VF_FWDG1(NS, GG, 4); else VF_FWDG1(NS, GG, 2); } while (0)
 #define VF_FWD(NS)                                                                                 \
   case NS:                                                                                         \
     if (group == 2) VF_FWDG(NS, 2);                                                                \
-    else if (group == 4) VF_FWDG(NS, 4);                                                           \
-    else if (group == 8) VF_FWDG(NS, 8);                                                           \
+    else if (group > 2 && group <= 4) VF_FWDG(NS, 4);                                              \
+    else if (group > 4) VF_FWDG(NS, 8);                                                            \
     else if (a_is_bf16) { if (small) VF_FWD2(bf16_t, NS, true, 1); else VF_FWD2(bf16_t, NS, false, 1); } \
     else           { if (small) VF_FWD2(float, NS, true, 1);  else VF_FWD2(float, NS, false, 1); } \
     break;
@@ -623,26 +655,30 @@ int launch_bn_relu_bwd(float* dap, int nsplit, int64_t slab, int64_t ldda, const
                        int64_t ldz, int R, int C, const float* gamma, const float* beta,
                        int round_params, const float* mean, const float* rstd, void* dz, int64_t lddz,
                        int dz_is_bf16, bf16_t* dzT, int64_t ldt, GradOut gout_g, GradOut gout_b,
-                       hipStream_t s, float tscale, int group) {
+                       hipStream_t s, float tscale, int group, const int* node_rows) {
   if (R <= 0 || C <= 0 || nsplit < 1) return VF_EINVAL;
   if (dzT && ((ldt & 7) || !dz_is_bf16)) return VF_EINVAL;
   const int grid = (C + CB - 1) / CB;
   const int subgroups = group_subgroups(grid);
   const bool small = R <= RCH;
-  if (group != 1 && (!small || !dz_is_bf16 || (group != 2 && group != 4 && group != 8) || (dzT && (R & 7)))) return VF_EINVAL;
+  GroupRows gr{};
+  if (group != 1) {
+    if (!dz_is_bf16) return VF_EINVAL;
+    VF_TRY(group_rows(group, R, node_rows, dzT != nullptr, &gr));
+  }
 #define VF_BWD2(TT, NS, SM, GG)                                                                    \
   bn_relu_bwd_kernel<TT, NS, SM, GG><<<grid, 256, 0, s>>>(dap, slab, ldda, z, ldz, R, C, gamma, beta,  \
       round_params, mean, rstd, static_cast<TT*>(dz), lddz, dzT, ldt, gout_g, gout_b, tscale)
 #define VF_BWDG1(NS, GG, SS)                                                                        \
-  bn_relu_bwd_group_kernel<NS, GG, SS><<<grid, GroupShape<GG, SS>::THREADS, 0, s>>>(dap, slab, ldda, z, ldz, R, C, gamma, \
+  bn_relu_bwd_group_kernel<NS, GG, SS><<<grid, GroupShape<GG, SS>::THREADS, 0, s>>>(dap, slab, ldda, z, ldz, gr, group, C, gamma, \
       beta, round_params, mean, rstd, static_cast<bf16_t*>(dz), lddz, dzT, ldt, gout_g, gout_b, tscale)
 #define VF_BWDG(NS, GG)                                                                            \
   do { if (subgroups == 4) VF_BWDG1(NS, GG, 4); else VF_BWDG1(NS, GG, 2); } while (0)
 #define VF_BWD(NS)                                                                                 \
   case NS:                                                                                         \
     if (group == 2) VF_BWDG(NS, 2);                                                                \
-    else if (group == 4) VF_BWDG(NS, 4);                                                           \
-    else if (group == 8) VF_BWDG(NS, 8);                                                           \
+    else if (group > 2 && group <= 4) VF_BWDG(NS, 4);                                              \
+    else if (group > 4) VF_BWDG(NS, 8);                                                            \
     else if (dz_is_bf16) { if (small) VF_BWD2(bf16_t, NS, true, 1); else VF_BWD2(bf16_t, NS, false, 1); } \
     else            { if (small) VF_BWD2(float, NS, true, 1);  else VF_BWD2(float, NS, false, 1); } \
     break;

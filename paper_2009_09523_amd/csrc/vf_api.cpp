@@ -71,7 +71,7 @@ int validate_config(const vf_config& c) {
 
 bool set_matches(const Ctx::GraphSet& g, const StepArgs& a) {
   return !g.graphs.empty() && g.params == a.params && g.x == a.x && g.y == a.y && g.sizes == a.sizes &&
-         g.seg == a.seg;
+         g.node_sizes == a.node_sizes;
 }
 
 // Selects the captured set that fits this call, if there is one.
@@ -205,7 +205,7 @@ int capture_whole_step(Ctx& c, const StepArgs& a) {
     c.gs().graphs.clear();
     return rc;
   }
-  c.gs().params = a.params; c.gs().x = a.x; c.gs().y = a.y; c.gs().sizes = a.sizes; c.gs().seg = a.seg;
+  c.gs().params = a.params; c.gs().x = a.x; c.gs().y = a.y; c.gs().sizes = a.sizes; c.gs().node_sizes = a.node_sizes;
   return VF_OK;
 }
 
@@ -224,7 +224,7 @@ int capture_graphs(Ctx& c, const StepArgs& a) {
     drop_graph(c);
     return rc;
   }
-  c.gs().params = a.params; c.gs().x = a.x; c.gs().y = a.y; c.gs().sizes = a.sizes; c.gs().seg = a.seg;
+  c.gs().params = a.params; c.gs().x = a.x; c.gs().y = a.y; c.gs().sizes = a.sizes; c.gs().node_sizes = a.node_sizes;
   return VF_OK;
 }
 
@@ -534,18 +534,27 @@ int vf_step(vf_ctx* h, void* params, const void* batch_x, const int32_t* batch_y
   a.node_off.resize(V + 1);
   a.node_w.resize(V);
   vf_partition(node_sizes, V, B, a.node_off.data(), a.node_w.data());
-  // the units of the passes: the nodes, or runs of up to `group` equal-sized nodes (2, 4 or 8 at a time)
+  // the units of the passes: the nodes, or runs of up to `group` consecutive nodes -- of any sizes the
+  // model takes together, or (models that want equal sizes) 2, 4 or 8 nodes of one size
   for (int32_t i = 0; i < V;) {
     int take = 1;
     const int most = std::min(c.group, c.model->max_group(node_sizes[i]));
     if (most > 1) {
       int run = 1;
-      while (i + run < V && run < most && node_sizes[i + run] == node_sizes[i]) ++run;
-      take = run >= 8 ? 8 : (run >= 4 ? 4 : (run >= 2 ? 2 : 1));
+      if (c.model->groups_unequal()) {
+        while (i + run < V && run < most && c.model->max_group(node_sizes[i + run]) > 1) ++run;
+        take = run;
+      } else {
+        while (i + run < V && run < most && node_sizes[i + run] == node_sizes[i]) ++run;
+        take = run >= 8 ? 8 : (run >= 4 ? 4 : (run >= 2 ? 2 : 1));
+      }
     }
-    a.sizes.push_back(take * node_sizes[i]);
+    int32_t rows = 0;
+    for (int j = 0; j < take; ++j) rows += node_sizes[i + j];
+    a.sizes.push_back(rows);
     a.seg.push_back(node_sizes[i]);
     a.first.push_back(i);
+    a.count.push_back(take);
     i += take;
   }
   a.V = (int32_t)a.sizes.size();

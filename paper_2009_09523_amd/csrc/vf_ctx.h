@@ -45,10 +45,10 @@ class Arena {
 
 // What the passes of a step iterate over.  V, sizes, off, w describe the UNITS that go through the
 // passes one after another: the virtual nodes themselves, or -- with node_group > 1 -- groups of
-// consecutive equal-sized nodes taken together (sizes[i] rows = seg[i] rows per node times the
-// nodes in the group; w[i] = sizes[i] / B, the sum of its nodes' weights, so a unit's loss is the
-// mean over all its rows).  What stays per node reads seg[i] (BatchNorm statistics) and the node
-// lists (losses).
+// consecutive nodes taken together (sizes[i] rows = the rows of its count[i] nodes; w[i] =
+// sizes[i] / B, the sum of its nodes' weights, so a unit's loss is the mean over all its rows).
+// What stays per node reads the node lists: first[i] is the unit's first node, its nodes are
+// node_sizes[first[i]] .. node_sizes[first[i] + count[i] - 1] (BatchNorm statistics, losses).
 struct StepArgs {
   float* params;
   const void* x;
@@ -56,12 +56,14 @@ struct StepArgs {
   int32_t B, V;
   std::vector<int32_t> sizes, off;
   std::vector<float> w;
-  std::vector<int32_t> seg;               // rows per node within unit i (== sizes[i] without groups)
+  std::vector<int32_t> seg;               // rows of unit i's first node (== sizes[i] without groups)
   std::vector<int32_t> first;             // index of unit i's first node
+  std::vector<int32_t> count;             // nodes in unit i
   int32_t nodes;                          // the virtual nodes of the step ...
   std::vector<int32_t> node_sizes, node_off;
   std::vector<float> node_w;              // ... with their offsets and weights b_i/B
-  int group(int i) const { return sizes[i] / seg[i]; }
+  int group(int i) const { return count[i]; }
+  const int32_t* rows_of(int i) const { return node_sizes.data() + first[i]; }
 };
 
 struct Ctx;
@@ -114,8 +116,10 @@ class Model {
   virtual void update_ranges(std::vector<UpdateRange>* out) const { out->clear(); }
   // Largest fold window the side part can take (it must keep that many nodes' operands).
   virtual int max_window() const { return 1; }
-  // How many equal-sized nodes of `rows` rows each the passes take as one unit at most (1: none).
+  // How many nodes of `rows` rows the passes take as one unit at most (1: none) ...
   virtual int max_group(int rows) const { (void)rows; return 1; }
+  // ... and whether the nodes of a unit may differ in size.
+  virtual bool groups_unequal() const { return false; }
   // State that the passes themselves carry from step to step on this device (BatchNorm moving
   // mean and variance, Section 4.1): `state_floats` fp32 values at `state_ptr`, laid out as all
   // layers' means then all layers' variances; init_state sets the starting values.
@@ -192,7 +196,7 @@ struct Ctx {
   // prefetching entry points do, replays instead of recapturing); `cur` is the one in use.
   struct GraphSet {
     std::vector<hipGraphExec_t> graphs;     // one graph, or [0] prepare, [1+2i] fwd(i), [2+2i] bwd(i), [1+2V+w] side(w)
-    std::vector<int32_t> sizes, seg;
+    std::vector<int32_t> sizes, node_sizes;
     const void* params = nullptr;
     const void* x = nullptr;
     const void* y = nullptr;

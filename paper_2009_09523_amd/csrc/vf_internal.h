@@ -165,15 +165,16 @@ int launch_cast_bf16(const float* in, int64_t ldi, bf16_t* out, int64_t ldo, int
 // transposed, [C, ldt].  Saves mean, rstd.  With gamma == nullptr: a = relu(z).
 // run_mean / run_var (both or neither): moving statistics, blended in place with the pass's
 // own: run += run_mix * (stat - run), biased variance.
-// group = 2, 4 or 8 (bf16, R <= 128, R a multiple of 8 when aT is given): the rows are `group` nodes
-// of R rows each, one after the other; statistics, the blend of the moving statistics and (in the
-// backward kernel) the small-vector gradients are taken per node in node order; mean and rstd
-// hold `group` vectors of C, the transposed copies node g's rows at columns g*R.
+// group = 2 .. 8 (bf16): the rows are `group` nodes one after the other, of R rows each or, with
+// node_rows (host array), of node_rows[n] rows (each at most 128, multiples of 8 when aT is
+// given); statistics, the blend of the moving statistics and (in the backward kernel) the
+// small-vector gradients are taken per node in node order; mean and rstd hold `group` vectors of
+// C, the transposed copies every node's rows at the columns of its rows.
 int launch_bn_relu_fwd(const float* zp, int nsplit, int64_t slab, int64_t ldzp, int R, int C,
                        const float* gamma, const float* beta, int round_params, float eps, float* z,
                        int64_t ldz, void* a, int64_t lda, int a_is_bf16, bf16_t* aT, int64_t ldt,
                        float* mean, float* rstd, float* run_mean, float* run_var, float run_mix,
-                       hipStream_t s, int group = 1);
+                       hipStream_t s, int group = 1, const int* node_rows = nullptr);
 // Backward of the above.  dap: nsplit partial slabs of the fp32 gradient w.r.t. a (slab 0 is
 // overwritten when nsplit > 1).  Writes dz (T), dzT (optional, bf16, [C, ldt]) and, with
 // BatchNorm, dgamma/dbeta through GradOut; without BatchNorm (gamma == nullptr) the bias
@@ -183,7 +184,7 @@ int launch_bn_relu_bwd(float* dap, int nsplit, int64_t slab, int64_t ldda, const
                        int64_t ldz, int R, int C, const float* gamma, const float* beta,
                        int round_params, const float* mean, const float* rstd, void* dz, int64_t lddz,
                        int dz_is_bf16, bf16_t* dzT, int64_t ldt, GradOut gout_g, GradOut gout_b,
-                       hipStream_t s, float tscale = 1.f, int group = 1);
+                       hipStream_t s, float tscale = 1.f, int group = 1, const int* node_rows = nullptr);
 // out[r] = sum_c x[r*ld + c] through GradOut (bias gradient from a transposed bf16 gradient)
 int launch_rowsum_bf16(const bf16_t* x, int64_t ld, int R, int C, GradOut out, hipStream_t s);
 // out[c] = sum_r x[r*ld + c] through GradOut (x is T)

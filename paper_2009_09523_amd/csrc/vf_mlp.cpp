@@ -103,6 +103,7 @@ class Mlp final : public Model {
   // groups of nodes: the BatchNorm kernels keep a node of up to 128 rows in registers, and the
   // transposed copies want node boundaries on 16-byte boundaries
   int max_group(int rows) const override { return (bf16_ && rows <= 128 && (rows & 7) == 0) ? 8 : 1; }
+  bool groups_unequal() const override { return true; }
   int max_window() const override { return bf16_ ? kFoldMax : 1; }
 
   // The side part finishes the layers from the last to the first; a layer's stretch of the
@@ -232,7 +233,7 @@ class Mlp final : public Model {
                                        bf16_, cfg_.bn_eps, L.z[q], L.ld, L.a[q], L.ld, bf16_, bf16_ ? L.aT + pc : nullptr, ldw_,
                                        L.mean[q], L.rstd[q], L.has_bn ? state_ + L.s_off : nullptr,
                                        L.has_bn ? state_ + bn_width_ + L.s_off : nullptr, cfg_.bn_momentum, st,
-                                       s.group(i)));
+                                       s.group(i), s.rows_of(i)));
       else
         VF_KS(c, st, "softmax_xent", launch_softmax_xent(slab_buf, split, slab, L.ld, L.z[q], L.ld, y, b, L.N,
                                                          c.rowloss + row0, L.dz[q], L.ld, bf16_, bf16_ ? L.dzT + pc : nullptr, ldw_, w, i,
@@ -284,7 +285,7 @@ class Mlp final : public Model {
       VF_KS(c, st, "bn_relu_bwd", launch_bn_relu_bwd(slab_buf, split, slab, Pv.ld, Pv.z[q], Pv.ld, s.seg[i], Pv.N,
                                      Pv.has_bn ? P + Pv.g_off : nullptr, Pv.has_bn ? P + Pv.be_off : nullptr,
                                      bf16_, Pv.mean[q], Pv.rstd[q], Pv.dz[0], Pv.ld, bf16_, bf16_ ? Pv.dzT + pc : nullptr, ldw_,
-                                     gg, gb, st, tscale(c, s, i), s.group(i)));
+                                     gg, gb, st, tscale(c, s, i), s.group(i), s.rows_of(i)));
     }
     return VF_OK;
   }

@@ -127,7 +127,7 @@ def test_rejected_step_leaves_state_untouched():
 BENCH = FUSED | NO_GRAPH | 4        # what bench.py times: fused fold, two streams, eager launches, window 8
 
 
-BENCH_GROUP = 8                     # ... and up to 8 equal-sized nodes through their passes together
+BENCH_GROUP = 8                     # ... and up to 8 nodes through their passes together
 
 
 @pytest.mark.parametrize("name,flags,window,group", [("C2", BENCH, 8, BENCH_GROUP), ("C3", BENCH, 8, BENCH_GROUP),
@@ -398,15 +398,15 @@ def test_changing_the_split_between_steps_replays_the_right_graph():
     assert run(FUSED).tobytes() == run(FUSED | NO_GRAPH).tobytes()
 
 
-# ---- node groups: consecutive equal-sized nodes through their passes together ---------------------
+# ---- node groups: consecutive nodes through their passes together ---------------------
 
 @pytest.mark.parametrize("group", [2, 4, 8])
 @pytest.mark.parametrize("name,sizes", [("mlp_mid_bn_bf16", [40] * 6), ("mlp_mid_bf16", [40] * 6),
                                         ("mlp_mid_bn_bf16", [40, 40, 40, 16, 16, 8, 8, 8, 8, 56]),
                                         ("mlp_mid_bn_bf16", [112, 112, 16]), ("mlp_mid_bn_bf16", [24] * 10)])
 def test_node_groups_match_the_oracle(name, sizes, group):
-    """Runs of equal-sized nodes taken 2, 4 or 8 at a time (a run of 3 goes as 2 + 1, one of 10 as 8 + 2; sizes that are
-    no multiple of 8 would go one by one), in every fold mode, on one and two streams, replayed and
+    """Up to 2, 4 or 8 consecutive nodes, of one size or of several, taken through their passes as one
+    unit (ten nodes go as 8 + 2; sizes that are no multiple of 8 would go alone), in every fold mode, on one and two streams, replayed and
     launched one by one: BatchNorm statistics, node losses and the weights b_i/B stay per node, so
     the oracle's node-by-node result must come out; the modes agree bitwise with one another."""
     wl, theta, x, y = _case(name)
