@@ -55,7 +55,7 @@ __device__ __forceinline__ u32x4 load_vec(const bf16_t* __restrict__ base, int64
 // A wavefront whose tiles lie wholly inside the matrix takes a path without per-element
 // branches, so that all its reads of R are in flight together (a weight gradient that adds
 // into the gradient buffer would otherwise pay one trip to memory per element).
-template <int TM, int TN>
+template <int TM, int TN, bool STREAM = false>
 __device__ __forceinline__ void store_tiles(const f32x16 (&acc)[TM][TN], const Epilogue& ep, char* cbase,
                                             bool first_slice, int mbase, int nbase, int M, int N, int lane) {
   const int rowoff = 4 * (lane >> 5);
@@ -93,6 +93,7 @@ __device__ __forceinline__ void store_tiles(const f32x16 (&acc)[TM][TN], const E
           const float addend = ep.R ? fmaf(ep.beta, add[i][j][r], bias[j]) : bias[j];
           const float v = fmaf(ep.alpha, acc[i][j][r], addend);
           if (ep.c_is_bf16) reinterpret_cast<bf16_t*>(cbase)[(int64_t)m * ep.ldc + n] = f32_to_bf16(v);
+          else if (STREAM) __builtin_nontemporal_store(v, &reinterpret_cast<float*>(cbase)[(int64_t)m * ep.ldc + n]);
           else              reinterpret_cast<float*>(cbase)[(int64_t)m * ep.ldc + n] = v;
         }
     return;
@@ -716,7 +717,209 @@ __global__ __launch_bounds__(512) void gemm_bf16_wide_kernel(const bf16_t* __res
     f32x16 row[1][TN];
 #pragma unroll
     for (int j = 0; j < TN; ++j) row[0][j] = acc[i][j];
-    store_tiles<1, TN>(row, ep, cbase, blockIdx.z == 0, m0 + wm * 64 + i * 32, n0 + wn * (BN / 2), M, N, lane);
+    if (ep.stream_c) store_tiles<1, TN, true>(row, ep, cbase, blockIdx.z == 0, m0 + wm * 64 + i * 32, n0 + wn * (BN / 2), M, N, lane);
+    else store_tiles<1, TN>(row, ep, cbase, blockIdx.z == 0, m0 + wm * 64 + i * 32, n0 + wn * (BN / 2), M, N, lane);
+  };
+  store_row(std::integral_constant<int, 0>{});
+  store_row(std::integral_constant<int, 1>{});
+}
+
+// ---- the same tile with whole lines in flight for longer ------------------------------------------
+// What the ring above cannot give a 256 x 256 tile is time: a load takes about 1.3 us from issue to
+// arrival here (the workgroups of an XCD walk along their shared operand panels in step, so almost
+// every load instruction holds a line that nobody has fetched yet and waits for HBM), and three
+// stages of 32 elements keep 64 KB in flight per compute unit -- 12.5 TB/s over the chip by
+// Little's law, which is what the loads of that kernel reach with everything else switched off;
+// deeper rings of half lines then meet the L2-to-L1 limit, because every 128-byte line crosses
+// twice.  Here a stage is 64 elements (whole lines), and LDS, all 160 KB of it, is cut so that
+// every load is issued one and a half to two stages before its first use:
+//   A: three slots of 256 rows (32 KB); stage s+2 is requested while stage s is consumed;
+//   B: a wavefront works through its four column tiles in two halves (tiles 0, 1 over all four
+//      steps of the stage, then tiles 2, 3, its A fragments staying in registers), so the rows of
+//      the first half (BF, 128 rows, 16 KB) are free in the middle of the stage and those of the
+//      second (BS) are not needed before: two slots each, BF of stage s+2 requested at the middle
+//      of stage s, BS of stage s+1 at its start.
+// Two barriers per stage (start: A and BF of the stage have landed, A and BS of the one before are
+// read; middle: BS has landed, BF is read), loads complete in order, and per wavefront four load
+// instructions follow each barrier (two at once, two a phase later), so the waits are fixed counts:
+// at most 8 outstanding at the start of a stage, at most 10 at its middle.
+__device__ __forceinline__ int line_swizzle(int r) { return (r & 7) ^ ((r >> 3) & 1); }
+
+__global__ __launch_bounds__(512) void gemm_bf16_wide_line_kernel(const bf16_t* __restrict__ A, int64_t lda,
+                                                                  const bf16_t* __restrict__ B, int64_t ldb,
+                                                                  int M, int N, int K, int kchunk,
+                                                                  int64_t slab_stride, Epilogue ep, int tiles_m,
+                                                                  int tiles_n) {
+  constexpr int BM = 256, BN = 256, KS = 64;
+  constexpr int AUNIT = BM * KS, BUNIT = (BN / 2) * KS;      // elements: 32 KB, 16 KB
+  constexpr int A0 = 0, BF0 = 3 * AUNIT, BS0 = BF0 + 2 * BUNIT;
+  static_assert((BS0 + 2 * BUNIT) * 2 == 160 * 1024, "LDS");
+  extern __shared__ __attribute__((aligned(1024))) bf16_t lds_wide[];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int ntile = tiles_m * tiles_n;
+  const int per = (ntile + 7) >> 3;
+  const int local = blockIdx.x >> 3;
+  if (local >= per) return;
+  const int t = (blockIdx.x & 7) * per + local;
+  if (t >= ntile) return;
+  const int panel = t / (8 * tiles_n);
+  const int in_panel = t - panel * 8 * tiles_n;
+  const int prow = min(8, tiles_m - panel * 8);
+  const int m0 = (panel * 8 + in_panel % prow) * BM, n0 = (in_panel / prow) * BN;
+  const int kbeg = blockIdx.z * kchunk;
+  const int kend = min(K, kbeg + kchunk);
+  const int nstage = kend > kbeg ? (kend - kbeg) / KS : 0;
+
+  // one load instruction of a wavefront: 8 rows of 128 bytes (lane / 8 the row, lane % 8 the chunk)
+  const bf16_t* ga[4];
+  const bf16_t* gbf[2];
+  const bf16_t* gbs[2];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int row = (wave + 8 * q) * 8 + (lane >> 3);
+    ga[q] = A + (int64_t)min(m0 + row, M - 1) * lda + kbeg + (((lane & 7) ^ line_swizzle(row)) * 8);
+  }
+#pragma unroll
+  for (int q = 0; q < 2; ++q) {
+    const int lr = (wave + 8 * q) * 8 + (lane >> 3);          // row within the half unit: 64 rows per column half
+    const int trow = (lr >> 6) * (BN / 2) + (lr & 63);
+    const int chunk = ((lane & 7) ^ line_swizzle(lr)) * 8;
+    gbf[q] = B + (int64_t)min(n0 + trow, N - 1) * ldb + kbeg + chunk;
+    gbs[q] = B + (int64_t)min(n0 + trow + 64, N - 1) * ldb + kbeg + chunk;
+  }
+  auto load16 = [&](const bf16_t* src, bf16_t* dst) {
+    __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)src,
+                                     (void __attribute__((address_space(3)))*)dst, 16, 0, 0);
+  };
+  // (a stage past the end repeats the last one: it lands in a free slot and is never read)
+  auto issue_a = [&](int q, int stage, int slot) {
+    load16(ga[q] + min(stage, nstage - 1) * KS, &lds_wide[A0 + slot * AUNIT + (wave + 8 * q) * 512]);
+  };
+  auto issue_bf = [&](int q, int stage, int slot) {
+    load16(gbf[q] + min(stage, nstage - 1) * KS, &lds_wide[BF0 + slot * BUNIT + (wave + 8 * q) * 512]);
+  };
+  auto issue_bs = [&](int q, int stage, int slot) {
+    load16(gbs[q] + min(stage, nstage - 1) * KS, &lds_wide[BS0 + slot * BUNIT + (wave + 8 * q) * 512]);
+  };
+
+  f32x16 acc[2][4];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  int arow[2], asw[2], brow[2], bsw[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) { arow[i] = wm * 64 + i * 32 + (lane & 31); asw[i] = line_swizzle(arow[i]); }
+#pragma unroll
+  for (int j = 0; j < 2; ++j) { brow[j] = wn * 64 + j * 32 + (lane & 31); bsw[j] = line_swizzle(brow[j]); }
+
+  if (nstage > 0) {
+    // prologue, in the order the steady state would have issued them
+#pragma unroll
+    for (int q = 0; q < 4; ++q) issue_a(q, 0, 0);
+#pragma unroll
+    for (int q = 0; q < 2; ++q) issue_bf(q, 0, 0);
+#pragma unroll
+    for (int q = 0; q < 2; ++q) issue_bs(q, 0, 0);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) issue_a(q, 1, 1);
+#pragma unroll
+    for (int q = 0; q < 2; ++q) issue_bf(q, 1, 1);
+
+    bf16x8 a[4][2], b[2][2];
+    auto read_a = [&](int slot, int kk) {
+      const bf16_t* as = &lds_wide[A0 + slot * AUNIT];
+      const int cidx = 2 * kk + (lane >> 5);
+#pragma unroll
+      for (int i = 0; i < 2; ++i) a[kk][i] = *reinterpret_cast<const bf16x8*>(&as[arow[i] * KS + ((cidx ^ asw[i]) * 8)]);
+    };
+    auto read_b = [&](const bf16_t* bs, int kk, int buf) {
+      const int cidx = 2 * kk + (lane >> 5);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) b[buf][j] = *reinterpret_cast<const bf16x8*>(&bs[brow[j] * KS + ((cidx ^ bsw[j]) * 8)]);
+    };
+    // names fragments as used: the compiler's wait for their LDS reads goes here (see gemm_bf16_wide_kernel)
+    auto arrived_b = [&](int buf) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j) asm volatile("" : "+v"(b[buf][j]));
+    };
+    auto arrived_a = [&](int kk) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i) asm volatile("" : "+v"(a[kk][i]));
+    };
+
+    wait_loads_but<8>();                   // A and BF of stage 0
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    read_a(0, 0);
+    read_b(&lds_wide[BF0], 0, 0);
+#pragma unroll
+    for (int q = 0; q < 2; ++q) issue_bs(q, 1, 1);
+
+    int sa = 0, sb = 0;                    // stage % 3, stage % 2
+    for (int s = 0; s < nstage; ++s) {
+      const int sa1 = sa == 2 ? 0 : sa + 1, sa2 = sa == 0 ? 2 : sa - 1;    // (s+1) % 3, (s+2) % 3
+      const bf16_t* bf = &lds_wide[BF0 + sb * BUNIT];
+      const bf16_t* bs = &lds_wide[BS0 + sb * BUNIT];
+#pragma unroll
+      for (int p = 0; p < 8; ++p) {
+        const int h = p >> 2, kk = p & 3;
+        if (h == 0) arrived_a(kk);
+        arrived_b(p & 1);
+        __builtin_amdgcn_sched_barrier(0);
+        if (p == 3) {
+          // middle of the stage: BS of this stage has landed, and behind the barrier BF is read by all
+          wait_loads_but<10>();
+          __builtin_amdgcn_s_barrier();
+          asm volatile("" ::: "memory");
+          read_b(bs, 0, 0);
+#pragma unroll
+          for (int q = 0; q < 2; ++q) issue_bf(q, s + 2, sb);
+        } else if (p == 7) {
+          if (s + 1 < nstage) {
+            // start of the next stage: its A and BF have landed; A and BS of this one are read by all
+            wait_loads_but<8>();
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            read_a(sa1, 0);
+            read_b(&lds_wide[BF0 + (sb ^ 1) * BUNIT], 0, 0);
+#pragma unroll
+            for (int q = 0; q < 2; ++q) issue_bs(q, s + 2, sb);
+          }
+        } else {
+          if (h == 0) read_a(sa, kk + 1);
+          read_b(h ? bs : bf, kk + 1, (p + 1) & 1);
+          if (p == 0) { issue_a(0, s + 2, sa2); issue_a(1, s + 2, sa2); }
+          if (p == 4) { issue_a(2, s + 2, sa2); issue_a(3, s + 2, sa2); }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+            acc[i][2 * h + j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk][i], b[p & 1][j], acc[i][2 * h + j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      sa = sa1;
+      sb ^= 1;
+    }
+    wait_loads_but<0>();
+  }
+
+  char* cbase = static_cast<char*>(ep.C) + (int64_t)blockIdx.z * slab_stride * (ep.c_is_bf16 ? 2 : 4);
+  auto store_row = [&](auto ic) {
+    constexpr int i = decltype(ic)::value;
+    f32x16 row[1][4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) row[0][j] = acc[i][j];
+    if (ep.stream_c) store_tiles<1, 4, true>(row, ep, cbase, blockIdx.z == 0, m0 + wm * 64 + i * 32, n0 + wn * (BN / 2), M, N, lane);
+    else store_tiles<1, 4>(row, ep, cbase, blockIdx.z == 0, m0 + wm * 64 + i * 32, n0 + wn * (BN / 2), M, N, lane);
   };
   store_row(std::integral_constant<int, 0>{});
   store_row(std::integral_constant<int, 1>{});
@@ -1172,6 +1375,7 @@ int pipe_depth() {
 int launch_wide(const Shape& g, const Epilogue& ep, hipStream_t s);
 
 }  // namespace
+static int launch_gemm_bf16_ep(const Shape& g, const Epilogue& ep, hipStream_t s);
 
 // Compute-bound shapes take the big tile; everything else (few rows, or a short contraction
 // whose cost is writing the output) does better with many small workgroups in flight.
@@ -1247,7 +1451,24 @@ int launch_wide_cfg(const Shape& g, const Epilogue& ep, hipStream_t s) {
   VF_LAUNCH_CHECK();
   return VF_OK;
 }
-int wide_variant() {   // tuning aid: VF_GEMM_WIDE_V=<n> picks another ring for the 256-wide tile
+int launch_wide_line(const Shape& g, const Epilogue& ep, hipStream_t s) {
+  constexpr int bytes = 160 * 1024;
+  static bool ready = false;
+  if (!ready) {
+    VF_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_wide_line_kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
+    ready = true;
+  }
+  const int kchunk = ((g.K + g.nsplit - 1) / g.nsplit + BK - 1) / BK * BK;
+  const int tiles_m = (g.M + 255) / 256, tiles_n = (g.N + 255) / 256;
+  const int ntile = tiles_m * tiles_n;
+  dim3 grid(((ntile + 7) / 8) * 8, 1, g.nsplit);
+  gemm_bf16_wide_line_kernel<<<grid, 512, bytes, s>>>(g.A, g.lda, g.B, g.ldb, g.M, g.N, g.K, kchunk, g.slab, ep, tiles_m,
+                                                      tiles_n);
+  VF_LAUNCH_CHECK();
+  return VF_OK;
+}
+int wide_variant() {   // tuning aid: VF_GEMM_WIDE_V=1 runs 256-wide tiles on the ring of three half-line stages
   static int cached = -1;
   if (cached < 0) {
     const char* e = std::getenv("VF_GEMM_WIDE_V");
@@ -1256,17 +1477,8 @@ int wide_variant() {   // tuning aid: VF_GEMM_WIDE_V=<n> picks another ring for 
   return cached;
 }
 int launch_wide(const Shape& g, const Epilogue& ep, hipStream_t s) {
-  if (wide_tile_n(g.M, g.N) == 256) {
-    switch (wide_variant()) {
-      case 1: return launch_wide_cfg<256, 64, 2>(g, ep, s);
-      case 2: return launch_wide_cfg<256, 32, 5>(g, ep, s);
-      case 3: return launch_wide_cfg<256, 32, 4>(g, ep, s);
-      default: return launch_wide_cfg<256, 32, 3>(g, ep, s);   // measured best on every shape tried (4 and 5 stages: 3 to 8 % slower)
-    }
-  }
-  if (wide_variant() == 4) return launch_wide_cfg<128, 32, 6>(g, ep, s);
-  if (wide_variant() == 5) return launch_wide_cfg<128, 64, 2>(g, ep, s);
-  if (wide_variant() == 6) return launch_wide_cfg<128, 32, 4>(g, ep, s);
+  if (wide_tile_n(g.M, g.N) == 256)
+    return wide_variant() == 1 ? launch_wide_cfg<256, 32, 3>(g, ep, s) : launch_wide_line(g, ep, s);
   return launch_wide_cfg<128, 64, 3>(g, ep, s);
 }
 }  // namespace
@@ -1279,6 +1491,25 @@ int launch_gemm_bf16(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb,
       (reinterpret_cast<uintptr_t>(B) & 15))
     return VF_EINVAL;
   Shape g{A, lda, B, ldb, M, N, K, nsplit, slab_stride};
+  // Epilogue::stream_c stores an fp32 result with the non-temporal hint.  Stored the ordinary way,
+  // the tiles that the workgroups of an XCD finish together (8 MB) pass through its 4 MB L2 and push
+  // out the operand panels the next tiles share: the operand traffic of an 8192^3 product alone
+  // takes 330 us, with the result stored the ordinary way 590 us, with the hint 370 us.  Inside the
+  // product that is worth 3 % on long contractions (8192^3: 939 -> 906 us) and costs on short ones
+  // (8192 x 8192 x 1024: 151 -> 166 us), and the kernel that reads the result next finds less of it
+  // in the caches (BatchNorm forward of a 2048-row unit: 48 -> 54 us), so no caller sets it;
+  // VF_GEMM_NT=1 sets it for every product (tuning aid).
+  static const int force_nt = std::getenv("VF_GEMM_NT") ? std::atoi(std::getenv("VF_GEMM_NT")) : 0;
+  Epilogue epx = ep;
+  if (force_nt && !ep.c_is_bf16) epx.stream_c = 1;
+  return launch_gemm_bf16_ep(g, epx, s);
+}
+
+static int launch_gemm_bf16_ep(const Shape& g, const Epilogue& ep, hipStream_t s) {
+  const bf16_t* A = g.A; const bf16_t* B = g.B;
+  const int64_t lda = g.lda, ldb = g.ldb;
+  const int M = g.M, N = g.N, K = g.K, nsplit = g.nsplit;
+  const int64_t slab_stride = g.slab;
   switch (forced_tile()) {
     case 1: return launch_cfg<128, 128, 2, 2>(g, ep, s);
     case 2: return launch_cfg<128, 64, 2, 2>(g, ep, s);

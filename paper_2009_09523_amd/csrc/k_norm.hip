@@ -12,6 +12,7 @@
 // lanes, so a 4096-wide layer gives 256 workgroups (one per compute unit).  For nodes of up
 // to RPT*16 = 128 rows every thread keeps its rows in registers and global memory is read
 // exactly once; larger nodes re-read the reduced values.
+#include <algorithm>
 #include <cstdlib>
 
 #include "vf_device.h"
@@ -324,6 +325,7 @@ __global__ __launch_bounds__(256) void bn_relu_bwd_kernel(float* __restrict__ da
 // the transposed copy node n's rows at columns n*R .. n*R + R-1.
 // Row ranges of the nodes of a unit: node n has rows[n] <= 128 rows starting at row base[n] of the
 // unit (a multiple of 8 when transposed copies are written); entries beyond the unit's nodes are 0.
+constexpr int kBnGroup = 8;   // nodes per launch of the group kernels
 struct GroupRows { int base[8]; int rows[8]; };
 
 template <int G, int SG_> struct GroupShape {
@@ -613,6 +615,23 @@ int launch_bn_relu_fwd(const float* zp, int nsplit, int64_t slab, int64_t ldzp, 
                        float* mean, float* rstd, float* run_mean, float* run_var, float run_mix,
                        hipStream_t s, int group, const int* node_rows) {
   if (R <= 0 || C <= 0 || nsplit < 1) return VF_EINVAL;
+  if (group > kBnGroup) {
+    // a unit of more than kBnGroup nodes: one launch per kBnGroup nodes, in node order (the moving
+    // statistics are blended node after node by launches that follow each other on the stream)
+    if (!a_is_bf16) return VF_EINVAL;
+    int64_t row = 0;
+    for (int n0 = 0; n0 < group; n0 += kBnGroup) {
+      const int cnt = std::min(kBnGroup, group - n0);
+      int64_t rows = 0;
+      for (int n = 0; n < cnt; ++n) rows += node_rows ? node_rows[n0 + n] : R;
+      VF_TRY(launch_bn_relu_fwd(zp + row * ldzp, nsplit, slab, ldzp, node_rows ? node_rows[n0] : R, C, gamma, beta,
+                                round_params, eps, z + row * ldz, ldz, static_cast<bf16_t*>(a) + row * lda, lda, 1,
+                                aT ? aT + row : nullptr, ldt, mean + (int64_t)n0 * C, rstd + (int64_t)n0 * C, run_mean,
+                                run_var, run_mix, s, cnt, node_rows ? node_rows + n0 : nullptr));
+      row += rows;
+    }
+    return VF_OK;
+  }
   if ((run_mean == nullptr) != (run_var == nullptr)) return VF_EINVAL;
   if (aT && ((ldt & 7) || !a_is_bf16)) return VF_EINVAL;
   const int grid = (C + CB - 1) / CB;
@@ -657,6 +676,25 @@ int launch_bn_relu_bwd(float* dap, int nsplit, int64_t slab, int64_t ldda, const
                        int dz_is_bf16, bf16_t* dzT, int64_t ldt, GradOut gout_g, GradOut gout_b,
                        hipStream_t s, float tscale, int group, const int* node_rows) {
   if (R <= 0 || C <= 0 || nsplit < 1) return VF_EINVAL;
+  if (group > kBnGroup) {
+    // a unit of more than kBnGroup nodes: one launch per kBnGroup nodes; the small-vector gradients
+    // of the later launches are added to what the first one left
+    if (!dz_is_bf16) return VF_EINVAL;
+    int64_t row = 0;
+    for (int n0 = 0; n0 < group; n0 += kBnGroup) {
+      const int cnt = std::min(kBnGroup, group - n0);
+      int64_t rows = 0;
+      for (int n = 0; n < cnt; ++n) rows += node_rows ? node_rows[n0 + n] : R;
+      GradOut gg = gout_g, gb = gout_b;
+      if (n0) { gg.accumulate = 1; gb.accumulate = 1; }
+      VF_TRY(launch_bn_relu_bwd(dap + row * ldda, nsplit, slab, ldda, z + row * ldz, ldz, node_rows ? node_rows[n0] : R, C,
+                                gamma, beta, round_params, mean + (int64_t)n0 * C, rstd + (int64_t)n0 * C,
+                                static_cast<bf16_t*>(dz) + row * lddz, lddz, 1, dzT ? dzT + row : nullptr, ldt, gg, gb, s,
+                                tscale, cnt, node_rows ? node_rows + n0 : nullptr));
+      row += rows;
+    }
+    return VF_OK;
+  }
   if (dzT && ((ldt & 7) || !dz_is_bf16)) return VF_EINVAL;
   const int grid = (C + CB - 1) / CB;
   const int subgroups = group_subgroups(grid);

@@ -39,7 +39,9 @@ int validate_config(const vf_config& c) {
   if (c.max_node_size > c.max_batch) return VF_EINVAL;
   if (!(c.bn_momentum >= 0.f && c.bn_momentum <= 1.f)) return VF_EINVAL;
   if (c.fold_window < 0 || c.fold_window > kFoldMax) return VF_EINVAL;
-  if (c.node_group != 0 && c.node_group != 1 && c.node_group != 2 && c.node_group != 4 && c.node_group != 8) return VF_EINVAL;
+  if (c.node_group != 0 && c.node_group != 1 && c.node_group != 2 && c.node_group != 4 && c.node_group != 8 &&
+      c.node_group != 16 && c.node_group != 32)
+    return VF_EINVAL;
   if (c.model_kind == VF_MLP) {
     if (c.n_dims < 2 || c.n_dims > VF_MAX_DIMS) return VF_EINVAL;
     for (int i = 0; i < c.n_dims; ++i)
@@ -387,6 +389,13 @@ int vf_init(const vf_config* cfg, vf_ctx** out) {
   if (!h) return VF_ENOMEM;
   Ctx& c = h->c;
   c.cfg = *cfg;
+  // Units of 16 or 32 nodes: a fold window never needs more units than a batch has (the window's
+  // transposed operand copies are sized by window x largest unit).
+  if (c.cfg.node_group >= 16 && c.cfg.fold_window > 1) {
+    const int64_t unit = (int64_t)c.cfg.max_node_size * c.cfg.node_group;
+    c.cfg.fold_window = (int32_t)std::max<int64_t>(1, std::min<int64_t>(c.cfg.fold_window, (c.cfg.max_batch + unit - 1) / unit));
+  }
+  cfg = &c.cfg;
   c.stream = static_cast<hipStream_t>(cfg->stream);
   if (!c.stream) c.cfg.flags |= VF_FLAG_NO_GRAPH;   // the default stream cannot be captured
   c.bf16 = cfg->dtype == VF_BF16;

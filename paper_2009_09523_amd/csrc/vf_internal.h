@@ -62,6 +62,7 @@ struct Epilogue {
   void* C = nullptr;
   int64_t ldc = 0;
   int c_is_bf16 = 0;             // store C as bf16 (RNE) instead of fp32
+  int stream_c = 0;              // store C with the non-temporal hint (it is not kept in the L2s)
 };
 
 // ---------------------------------------------------------------------------------------

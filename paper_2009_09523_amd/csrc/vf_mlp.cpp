@@ -102,7 +102,7 @@ class Mlp final : public Model {
   bool supports_overlap() const override { return bf16_; }
   // groups of nodes: the BatchNorm kernels keep a node of up to 128 rows in registers, and the
   // transposed copies want node boundaries on 16-byte boundaries
-  int max_group(int rows) const override { return (bf16_ && rows <= 128 && (rows & 7) == 0) ? 8 : 1; }
+  int max_group(int rows) const override { return (bf16_ && rows <= 128 && (rows & 7) == 0) ? 32 : 1; }
   bool groups_unequal() const override { return true; }
   int max_window() const override { return bf16_ ? kFoldMax : 1; }
 

@@ -67,7 +67,7 @@ def _cfg(**kw):
 
 @pytest.mark.parametrize("kw", [dict(dtype=7), dict(optimizer=3), dict(max_nodes=0), dict(max_node_size=0),
                                 dict(n_dims=1), dict(n_dims=17), dict(model_kind=5),
-                                dict(max_node_size=100, max_batch=64), dict(node_group=3), dict(node_group=16),
+                                dict(max_node_size=100, max_batch=64), dict(node_group=3), dict(node_group=64),
                                 dict(node_group=-1), dict(fold_window=9)])
 def test_init_rejects_bad_config_before_touching_the_device(kw):
     h = C.c_void_p(123)

@@ -83,8 +83,11 @@ def test_adam_kernel(n):
 GEMM_SHAPES = [(128, 4096 // 8, 1024 // 4), (48, 1000, 520), (16, 392, 1000), (8, 520, 256), (40, 264, 392),
                (300, 100, 392), (392, 1000, 128), (520, 392, 48), (256, 520, 16), (256, 520, 8), (1, 8, 8),
                (33, 65, 72), (129, 257, 264), (304, 1003, 128), (2048, 2304, 768),
-               # enough 256 x 256 tiles to fill the machine: the wide LDS-direct kernel, ragged on both sides
-               (4000, 3585, 192)]
+               # the 256-row LDS-direct kernel, ragged on both sides, 256 x 128 tiles ...
+               (4000, 3585, 192),
+               # ... and 256 x 256 tiles (exactly one round of 256 tiles: the whole-line kernel), with
+               # three, one and two stages of 64
+               (4000, 3900, 192), (3900, 4000, 64), (4000, 3900, 128)]
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
@@ -121,7 +124,9 @@ def test_gemm_against_float64_matmul(M, N, K, dtype):
                                          (128, 4096, 4096, 4), (100, 1000, 1024, 8), (70, 130, 192, 3),
                                          (65, 64, 64, 1), (48, 392, 64, 2), (128, 1000, 4096, 16),
                                          # 256 x 256 tiles, sliced contraction
-                                         (1100, 1030, 2048, 16)])
+                                         (1100, 1030, 2048, 16),
+                                         # the whole-line kernel (one round of 256 x 256 tiles), slices of 4 and 3 stages
+                                         (4000, 3900, 1024, 4), (4000, 3900, 384, 2)])
 def test_gemm_split_contraction_slabs_sum_to_product(M, N, K, nsplit):
     import torch
     import paper_2009_09523_amd as vf

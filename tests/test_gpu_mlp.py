@@ -127,7 +127,7 @@ def test_rejected_step_leaves_state_untouched():
 BENCH = FUSED | NO_GRAPH | 4        # what bench.py times: fused fold, two streams, eager launches, window 8
 
 
-BENCH_GROUP = 8                     # ... and up to 8 nodes through their passes together
+BENCH_GROUP = 16                    # ... and up to 16 nodes through their passes together
 
 
 @pytest.mark.parametrize("name,flags,window,group", [("C2", BENCH, 8, BENCH_GROUP), ("C3", BENCH, 8, BENCH_GROUP),
@@ -152,10 +152,11 @@ def test_full_size_configurations(name, flags, window, group):
 
 def test_c5_full_size_launch_configuration():
     """Large-batch emulation: MLP 2048-8192x6-1000 + BatchNorm, 64 nodes of 128 (B = 8192), in the
-    launch configuration bench.py times (fused fold, two streams, launches one by one, groups
-    of 8 nodes per pass, windows of 8 groups).  The oracle can afford single nodes of this model: it
-    evaluates the eight distinct nodes 0..7 (one whole unit of the device's passes), and the device
-    runs V = 64 nodes of which node i holds the rows of node i mod 8 -- the combined gradient is then
+    launch configuration bench.py times (fused fold, two streams, launches one by one, units
+    of 16 nodes per pass, one window over the four units).  The oracle can afford single nodes of this
+    model: it evaluates the eight distinct nodes 0..7, and the device runs V = 64 nodes of which node i
+    holds the rows of node i mod 8 (a unit of the device's passes is these eight nodes twice, its
+    BatchNorm launches take eight nodes each) -- the combined gradient is then
     (g_0 + .. + g_7)/8 (Section 5.2 with 64 weights of 1/64), every fold of step 3 and the update of
     step 5 run over all 64 nodes.
 
@@ -211,11 +212,12 @@ def test_c5_full_size_launch_configuration():
     check_update_from_own_gradient(wl, gpu, theta)
     G64 = gpu["G"].copy()
     del gpu, xa, ya
-    # the same eight nodes as ONE unit: eight such units in one window against that (fp32 rounding only;
+    # the same nodes as ONE unit: four such units in one window against that (fp32 rounding only;
     # a unit of another shape would not do: at this depth another shape of the products, which means
     # another order of fp32 sums, already moves the early layers by percents)
-    once = run_gpu(wl.with_nodes([128] * K), theta, x[:128 * K], y[:128 * K], flags=BENCH, fold_window=8,
-                   node_group=BENCH_GROUP)
+    U = BENCH_GROUP // K
+    once = run_gpu(wl.with_nodes([128] * BENCH_GROUP), theta, np.tile(x[:128 * K], (U, 1)), np.tile(y[:128 * K], U),
+                   flags=BENCH, fold_window=8, node_group=BENCH_GROUP)
     assert np.linalg.norm(G64 - once["G"]) <= 1e-6 * np.linalg.norm(once["G"])
     del once
     # the bound that does not depend on where operands are rounded (nodes 0 .. 7, weights only)
@@ -425,6 +427,37 @@ def test_node_groups_match_the_oracle(name, sizes, group):
         assert gpu["G"].tobytes() == base["G"].tobytes(), (flags, window)
         assert gpu["theta"].tobytes() == base["theta"].tobytes(), (flags, window)
     # a windowed product over groups against the oracle as well
+    gpu = run_gpu(wl, theta, x, y, node_sizes=sizes, flags=FUSED | NO_GRAPH | OVERLAP, fold_window=4, node_group=group)
+    check_against_oracle(wl, gpu, ref)
+    assert np.linalg.norm(gpu["G"] - plain["G"]) <= 2e-2 * np.linalg.norm(plain["G"])
+
+
+@pytest.mark.parametrize("group", [16, 32])
+@pytest.mark.parametrize("name,sizes", [("mlp_mid_bn_bf16", [8] * 30), ("mlp_mid_bf16", [8] * 30),
+                                        ("mlp_mid_bn_bf16", [16, 8, 8] * 7 + [16]), ("mlp_mid_bn_bf16", [24] * 9)])
+def test_units_of_more_than_eight_nodes_match_the_oracle(name, sizes, group):
+    """Units of up to 16 or 32 nodes (the BatchNorm kernels then take a unit in launches of eight nodes,
+    the last one ragged; 30 nodes go as 16 + 14 or as one unit, 9 nodes as 8 + 1): the oracle's
+    node-by-node result, the same bits in every launch mode, per-node losses unchanged."""
+    wl, theta, x, y = _case(name)
+    B = sum(sizes)
+    x, y = x[:B], y[:B]
+    ref = oracle_steps(wl, theta, x, y, node_sizes=sizes)
+    plain = run_gpu(wl, theta, x, y, node_sizes=sizes, flags=FUSED)
+    base = None
+    for flags, window in ((FUSED, 0), (FUSED | NO_GRAPH | OVERLAP, 0), (FUSED | OVERLAP, 0), (0, 0)):
+        gpu = run_gpu(wl, theta, x, y, node_sizes=sizes, flags=flags, fold_window=window, node_group=group)
+        check_against_oracle(wl, gpu, ref)
+        np.testing.assert_allclose(gpu["node_losses"], plain["node_losses"], rtol=1e-5)
+        if base is None:
+            base = gpu
+        if flags & FUSED:
+            assert gpu["G"].tobytes() == base["G"].tobytes(), (flags, window)
+            assert gpu["theta"].tobytes() == base["theta"].tobytes(), (flags, window)
+        else:
+            # staged fold: the BatchNorm scale / shift gradients of a unit's launches of eight nodes are
+            # added in the staging vector before the weight is applied, not weighted one by one
+            assert np.abs(gpu["G"] - base["G"]).max() <= 1e-6 * np.abs(base["G"]).max()
     gpu = run_gpu(wl, theta, x, y, node_sizes=sizes, flags=FUSED | NO_GRAPH | OVERLAP, fold_window=4, node_group=group)
     check_against_oracle(wl, gpu, ref)
     assert np.linalg.norm(gpu["G"] - plain["G"]) <= 2e-2 * np.linalg.norm(plain["G"])
