@@ -547,6 +547,15 @@ __global__ __launch_bounds__(NT) void gemm_bf16_dl_kernel(const bf16_t* __restri
 // XCD form an 8 x 4 block sharing 8 + 4 operand panels on that XCD's L2.
 // Requires whole stages in every contraction slice; operand rows are clamped into the matrix
 // (their products never stored).
+// One LDS-direct load of 16 bytes per lane: global address = scalar base + 32-bit lane offset, LDS
+// address (wavefront-uniform; lane l lands 16 l bytes behind it) through M0.  No destination
+// register: the data is in LDS when the wavefront's vmcnt says so.
+__device__ __forceinline__ void lds_load16(const char* base, uint32_t off, bf16_t* dst) {
+  const uint32_t l = (uint32_t)(uintptr_t)(void __attribute__((address_space(3)))*)dst;
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :: "s"(l), "v"(off), "s"(base) : "memory", "m0");
+}
+
 template <int KS>
 __device__ __forceinline__ int wide_swizzle(int r) {
   return KS == 64 ? ((r & 7) ^ ((r >> 3) & 1)) : ((r >> 2) & 3);
@@ -573,7 +582,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_wide_kernel(const bf16_t* __res
   extern __shared__ __attribute__((aligned(1024))) bf16_t lds_wide[];
 
   const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
+  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // (in a scalar register)
   const int wm = wave >> 1, wn = wave & 1;
   // this workgroup's tile
   const int ntile = tiles_m * tiles_n;
@@ -590,29 +599,28 @@ __global__ __launch_bounds__(512) void gemm_bf16_wide_kernel(const bf16_t* __res
   const int kend = min(K, kbeg + kchunk);
   const int nstage = kend > kbeg ? (kend - kbeg) / KS : 0;
 
-  const bf16_t* ga[AL];
-  const bf16_t* gb[BL];
+  // Addresses are a scalar base (matrix, contraction offset) plus a 32-bit byte offset per lane (row
+  // and chunk), and the LDS address of a load goes through M0 from scalar registers: the loop then
+  // has no vector arithmetic for its loads.  (The host checks that both operands span less than 2 GiB.)
+  uint32_t oa[AL], ob[BL];
 #pragma unroll
   for (int q = 0; q < AL; ++q) {
     const int row = (wave + 8 * q) * RPI + lane / CPR;
-    ga[q] = A + (int64_t)min(m0 + row, M - 1) * lda + kbeg + (((lane % CPR) ^ wide_swizzle<KS>(row)) * 8);
+    oa[q] = (uint32_t)(((int64_t)min(m0 + row, M - 1) * lda + (((lane % CPR) ^ wide_swizzle<KS>(row)) * 8)) * 2);
   }
 #pragma unroll
   for (int q = 0; q < BL; ++q) {
     const int row = (wave + 8 * q) * RPI + lane / CPR;
-    gb[q] = B + (int64_t)min(n0 + row, N - 1) * ldb + kbeg + (((lane % CPR) ^ wide_swizzle<KS>(row)) * 8);
+    ob[q] = (uint32_t)(((int64_t)min(n0 + row, N - 1) * ldb + (((lane % CPR) ^ wide_swizzle<KS>(row)) * 8)) * 2);
   }
+  const char* Ab = reinterpret_cast<const char*>(A + kbeg);
+  const char* Bb = reinterpret_cast<const char*>(B + kbeg);
   // load number j (0 .. LPS-1) of a stage: first the A rows, then the B rows
   auto issue_one = [&](int j, int stage, int slot) {
-    const int k = stage * KS;
+    const size_t k = (size_t)stage * (KS * 2);
     bf16_t* base = &lds_wide[slot * STAGE];
-    if (j < AL)
-      __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(ga[j] + k),
-                                       (void __attribute__((address_space(3)))*)(base + (wave + 8 * j) * 512), 16, 0, 0);
-    else
-      __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(gb[j - AL] + k),
-                                       (void __attribute__((address_space(3)))*)(base + ATILE + (wave + 8 * (j - AL)) * 512),
-                                       16, 0, 0);
+    if (j < AL) lds_load16(Ab + k, oa[j], base + (wave + 8 * j) * 512);
+    else lds_load16(Bb + k, ob[j - AL], base + ATILE + (wave + 8 * (j - AL)) * 512);
   };
 
   f32x16 acc[2][TN];
@@ -630,81 +638,77 @@ __global__ __launch_bounds__(512) void gemm_bf16_wide_kernel(const bf16_t* __res
   for (int j = 0; j < TN; ++j) { brow[j] = wn * (BN / 2) + j * 32 + (lane & 31); bsw[j] = wide_swizzle<KS>(brow[j]); }
 
   if (nstage > 0) {
-    // Schedule.  The fragments of a stage's first MFMA step are read one step EARLY, during the
-    // last step of the stage before: there the wavefront waits for the next stage's loads, meets
-    // the others at the barrier, issues those reads and only then starts the last step's MFMAs
-    // (whose operands are in registers already), so neither the barrier nor the LDS latency
-    // behind it leaves the matrix cores without queued work.  At that barrier every wavefront has
-    // read all of the current stage into registers, so its slot is free: the loads of the stage
-    // NS ahead go into it, half of them right there, half during the next step.
+    // Schedule.  A step's MFMAs are issued with the step's other instructions between them, one at a
+    // time: the two wavefronts of a SIMD run in step (every barrier puts them side by side again), so
+    // what a wavefront issues in a block of its own leaves the matrix core idle, while an instruction
+    // issued behind an MFMA runs in that MFMA's shadow.  Behind the first MFMAs of a step come the
+    // reads of the next step's fragments (in the order that step uses them); the loads of the stage
+    // NS-1 ahead follow, half of them in the stage's last step -- there the wavefront first waits
+    // for the next stage's loads and meets the others at the barrier, after which every wavefront has
+    // read all of the current stage, so that its slot is free -- and the rest over the steps before.
     constexpr int H0 = LPS / 2;                        // loads issued behind the barrier
+    constexpr int NM = 2 * TN;                         // MFMAs of a step
+    constexpr int NR = 2 + TN;                         // fragment reads of a step
+    static_assert(H0 <= NM && (LPS - H0 + STEPS - 2) / (STEPS - 1) <= NM, "a load behind every MFMA at most");
 #pragma unroll
     for (int s = 0; s < NS - 1; ++s)
 #pragma unroll
       for (int j = 0; j < LPS; ++j) issue_one(j, min(s, nstage - 1), s);
     bf16x8 a[2][2], b[2][TN];
-    auto read_frags = [&](int stage, int kk, int buf) {
+    // fragment number r of step kk of a stage, in the order a step uses them: A tile 0, the B tiles, A tile 1
+    auto read_one = [&](int stage, int kk, int buf, int r) {
       const bf16_t* as = &lds_wide[(stage % NS) * STAGE];
       const bf16_t* bs = as + ATILE;
       const int cidx = 2 * kk + (lane >> 5);
-#pragma unroll
-      for (int i = 0; i < 2; ++i) a[buf][i] = *reinterpret_cast<const bf16x8*>(&as[arow[i] * KS + ((cidx ^ asw[i]) * 8)]);
-#pragma unroll
-      for (int j = 0; j < TN; ++j) b[buf][j] = *reinterpret_cast<const bf16x8*>(&bs[brow[j] * KS + ((cidx ^ bsw[j]) * 8)]);
-    };
-    // Names a buffer's fragments as used.  The compiler puts its wait for their LDS reads in front
-    // of the first use, and with LDS-direct loads in flight that wait is always "all LDS reads"; so
-    // the first use is placed BEFORE the next fragments' reads are issued, which leaves those a whole
-    // MFMA step to arrive (placed behind them, every step would wait for the reads it just issued).
-    auto arrived = [&](int buf) {
-#pragma unroll
-      for (int i = 0; i < 2; ++i) asm volatile("" : "+v"(a[buf][i]));
-#pragma unroll
-      for (int j = 0; j < TN; ++j) asm volatile("" : "+v"(b[buf][j]));
-      __builtin_amdgcn_sched_barrier(0);
-    };
-    auto mfmas = [&](int buf) {
-      __builtin_amdgcn_sched_barrier(0);      // the reads and loads issued before stay ahead of the MFMAs
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[buf][i], b[buf][j], acc[i][j], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
+      if (r == 0 || r == NR - 1) {
+        const int i = r ? 1 : 0;
+        a[buf][i] = *reinterpret_cast<const bf16x8*>(&as[arow[i] * KS + ((cidx ^ asw[i]) * 8)]);
+      } else {
+        const int j = r - 1;
+        b[buf][j] = *reinterpret_cast<const bf16x8*>(&bs[brow[j] * KS + ((cidx ^ bsw[j]) * 8)]);
+      }
     };
     // stage 0 has landed when at most NS-2 stages are outstanding (loads complete in order)
     wait_loads_but<(NS - 2) * LPS>();
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    read_frags(0, 0, 0);
-    // the last ring slot is still empty: stage NS-1 goes there (first half now, second half in step 0)
+#pragma unroll
+    for (int r = 0; r < NR; ++r) read_one(0, 0, 0, r);
+    // the last ring slot is still empty: stage NS-1 goes there (first half now, second half in the first steps)
 #pragma unroll
     for (int j = 0; j < H0; ++j) issue_one(j, min(NS - 1, nstage - 1), NS - 1);
     for (int it = 0; it < nstage; ++it) {
       // the stage whose loads are being issued while stage `it` is consumed, and its slot
       const int cur_ld = min(it + NS - 1, nstage - 1), cur_slot = (it + NS - 1) % NS;
       const int nxt_ld = min(it + NS, nstage - 1), nxt_slot = it % NS;
+      const bool more = it + 1 < nstage;
 #pragma unroll
       for (int kk = 0; kk < STEPS; ++kk) {
-        arrived(kk & 1);
-        if (kk + 1 < STEPS) {
-          read_frags(it, kk + 1, (kk + 1) & 1);
-          // the second half of the loads of stage it+NS-1, spread over the steps before the last
-#pragma unroll
-          for (int j = H0 + kk * (LPS - H0) / (STEPS - 1); j < H0 + (kk + 1) * (LPS - H0) / (STEPS - 1); ++j)
-            issue_one(j, cur_ld, cur_slot);
-        } else if (it + 1 < nstage) {
-          // everything of stage it+1 must have landed: outstanding may be the stages it+2 .. it+NS-1
+        const int buf = kk & 1;
+        const bool last = kk + 1 == STEPS;
+        __builtin_amdgcn_sched_barrier(0);
+        if (last && more) {
+          // this wavefront's own reads of stage `it` have returned (the slot is overwritten behind the
+          // barrier), and everything of stage it+1 has landed: outstanding may be the stages it+2 .. it+NS-1
+          asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
           wait_loads_but<(NS - 2) * LPS>();
-          // (this wavefront's reads of stage `it` have all returned: its last fragments were named
-          // as used above, and LDS reads return in order)
           __builtin_amdgcn_s_barrier();
           asm volatile("" ::: "memory");
-          read_frags(it + 1, 0, 0);
-#pragma unroll
-          for (int j = 0; j < H0; ++j) issue_one(j, nxt_ld, nxt_slot);
         }
-        mfmas(kk & 1);
+        // the loads of this step: [lo, hi) of stage cur_ld, or (last step) the first H0 of stage nxt_ld
+        const int lo = last ? 0 : H0 + kk * (LPS - H0) / (STEPS - 1);
+        const int hi = last ? H0 : H0 + (kk + 1) * (LPS - H0) / (STEPS - 1);
+#pragma unroll
+        for (int m = 0; m < NM; ++m) {
+          const int i = m / TN, j = m % TN;
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[buf][i], b[buf][j], acc[i][j], 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
+          if (m < NR && (!last || more)) read_one(last ? it + 1 : it, last ? 0 : kk + 1, buf ^ 1, m);
+          // loads behind the last MFMAs of the step
+          const int l = lo + m - (NM - (hi - lo));
+          if (l >= lo && l < hi && (!last || more)) issue_one(l, last ? nxt_ld : cur_ld, last ? nxt_slot : cur_slot);
+          __builtin_amdgcn_sched_barrier(0);
+        }
       }
     }
     wait_loads_but<0>();
@@ -757,7 +761,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_wide_line_kernel(const bf16_t* 
   extern __shared__ __attribute__((aligned(1024))) bf16_t lds_wide[];
 
   const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
+  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // (in a scalar register)
   const int wm = wave >> 1, wn = wave & 1;
   const int ntile = tiles_m * tiles_n;
   const int per = (ntile + 7) >> 3;
@@ -773,36 +777,36 @@ __global__ __launch_bounds__(512) void gemm_bf16_wide_line_kernel(const bf16_t* 
   const int kend = min(K, kbeg + kchunk);
   const int nstage = kend > kbeg ? (kend - kbeg) / KS : 0;
 
-  // one load instruction of a wavefront: 8 rows of 128 bytes (lane / 8 the row, lane % 8 the chunk)
-  const bf16_t* ga[4];
-  const bf16_t* gbf[2];
-  const bf16_t* gbs[2];
+  // One load instruction of a wavefront: 8 rows of 128 bytes (lane / 8 the row, lane % 8 the chunk).
+  // Addresses are a scalar base (matrix, contraction offset) plus a 32-bit byte offset per lane (row
+  // and chunk): the stage to stage arithmetic is scalar, and a load reads one address register per
+  // lane.  (The host checks that both operands span less than 2 GiB.)
+  uint32_t oa[4], obf[2], obs[2];
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
     const int row = (wave + 8 * q) * 8 + (lane >> 3);
-    ga[q] = A + (int64_t)min(m0 + row, M - 1) * lda + kbeg + (((lane & 7) ^ line_swizzle(row)) * 8);
+    oa[q] = (uint32_t)(((int64_t)min(m0 + row, M - 1) * lda + (((lane & 7) ^ line_swizzle(row)) * 8)) * 2);
   }
 #pragma unroll
   for (int q = 0; q < 2; ++q) {
     const int lr = (wave + 8 * q) * 8 + (lane >> 3);          // row within the half unit: 64 rows per column half
     const int trow = (lr >> 6) * (BN / 2) + (lr & 63);
     const int chunk = ((lane & 7) ^ line_swizzle(lr)) * 8;
-    gbf[q] = B + (int64_t)min(n0 + trow, N - 1) * ldb + kbeg + chunk;
-    gbs[q] = B + (int64_t)min(n0 + trow + 64, N - 1) * ldb + kbeg + chunk;
+    obf[q] = (uint32_t)(((int64_t)min(n0 + trow, N - 1) * ldb + chunk) * 2);
+    obs[q] = (uint32_t)(((int64_t)min(n0 + trow + 64, N - 1) * ldb + chunk) * 2);
   }
-  auto load16 = [&](const bf16_t* src, bf16_t* dst) {
-    __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)src,
-                                     (void __attribute__((address_space(3)))*)dst, 16, 0, 0);
-  };
+  const char* Ab = reinterpret_cast<const char*>(A + kbeg);
+  const char* Bb = reinterpret_cast<const char*>(B + kbeg);
+  auto load16 = [&](const char* base, uint32_t off, bf16_t* dst) { lds_load16(base, off, dst); };
   // (a stage past the end repeats the last one: it lands in a free slot and is never read)
   auto issue_a = [&](int q, int stage, int slot) {
-    load16(ga[q] + min(stage, nstage - 1) * KS, &lds_wide[A0 + slot * AUNIT + (wave + 8 * q) * 512]);
+    load16(Ab + (size_t)min(stage, nstage - 1) * (KS * 2), oa[q], &lds_wide[A0 + slot * AUNIT + (wave + 8 * q) * 512]);
   };
   auto issue_bf = [&](int q, int stage, int slot) {
-    load16(gbf[q] + min(stage, nstage - 1) * KS, &lds_wide[BF0 + slot * BUNIT + (wave + 8 * q) * 512]);
+    load16(Bb + (size_t)min(stage, nstage - 1) * (KS * 2), obf[q], &lds_wide[BF0 + slot * BUNIT + (wave + 8 * q) * 512]);
   };
   auto issue_bs = [&](int q, int stage, int slot) {
-    load16(gbs[q] + min(stage, nstage - 1) * KS, &lds_wide[BS0 + slot * BUNIT + (wave + 8 * q) * 512]);
+    load16(Bb + (size_t)min(stage, nstage - 1) * (KS * 2), obs[q], &lds_wide[BS0 + slot * BUNIT + (wave + 8 * q) * 512]);
   };
 
   f32x16 acc[2][4];
@@ -844,16 +848,6 @@ __global__ __launch_bounds__(512) void gemm_bf16_wide_line_kernel(const bf16_t* 
 #pragma unroll
       for (int j = 0; j < 2; ++j) b[buf][j] = *reinterpret_cast<const bf16x8*>(&bs[brow[j] * KS + ((cidx ^ bsw[j]) * 8)]);
     };
-    // names fragments as used: the compiler's wait for their LDS reads goes here (see gemm_bf16_wide_kernel)
-    auto arrived_b = [&](int buf) {
-#pragma unroll
-      for (int j = 0; j < 2; ++j) asm volatile("" : "+v"(b[buf][j]));
-    };
-    auto arrived_a = [&](int kk) {
-#pragma unroll
-      for (int i = 0; i < 2; ++i) asm volatile("" : "+v"(a[kk][i]));
-    };
-
     wait_loads_but<8>();                   // A and BF of stage 0
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
@@ -862,49 +856,76 @@ __global__ __launch_bounds__(512) void gemm_bf16_wide_line_kernel(const bf16_t* 
 #pragma unroll
     for (int q = 0; q < 2; ++q) issue_bs(q, 1, 1);
 
+    // One fragment read: A row tile i or B column tile j of MFMA step kk.
+    auto rd_a = [&](int slot, int kk, int i) {
+      const bf16_t* as = &lds_wide[A0 + slot * AUNIT];
+      a[kk][i] = *reinterpret_cast<const bf16x8*>(&as[arow[i] * KS + (((2 * kk + (lane >> 5)) ^ asw[i]) * 8)]);
+    };
+    auto rd_b = [&](const bf16_t* bs, int kk, int buf, int j) {
+      b[buf][j] = *reinterpret_cast<const bf16x8*>(&bs[brow[j] * KS + (((2 * kk + (lane >> 5)) ^ bsw[j]) * 8)]);
+    };
+
     int sa = 0, sb = 0;                    // stage % 3, stage % 2
     for (int s = 0; s < nstage; ++s) {
       const int sa1 = sa == 2 ? 0 : sa + 1, sa2 = sa == 0 ? 2 : sa - 1;    // (s+1) % 3, (s+2) % 3
       const bf16_t* bf = &lds_wide[BF0 + sb * BUNIT];
       const bf16_t* bs = &lds_wide[BS0 + sb * BUNIT];
+      const bf16_t* bfn = &lds_wide[BF0 + (sb ^ 1) * BUNIT];
+      const bool more = s + 1 < nstage;
 #pragma unroll
       for (int p = 0; p < 8; ++p) {
         const int h = p >> 2, kk = p & 3;
-        if (h == 0) arrived_a(kk);
-        arrived_b(p & 1);
         __builtin_amdgcn_sched_barrier(0);
         if (p == 3) {
           // middle of the stage: BS of this stage has landed, and behind the barrier BF is read by all
+          // (this wavefront's own reads have returned)
+          asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
           wait_loads_but<10>();
           __builtin_amdgcn_s_barrier();
           asm volatile("" ::: "memory");
-          read_b(bs, 0, 0);
-#pragma unroll
-          for (int q = 0; q < 2; ++q) issue_bf(q, s + 2, sb);
-        } else if (p == 7) {
-          if (s + 1 < nstage) {
-            // start of the next stage: its A and BF have landed; A and BS of this one are read by all
-            wait_loads_but<8>();
-            __builtin_amdgcn_s_barrier();
-            asm volatile("" ::: "memory");
-            read_a(sa1, 0);
-            read_b(&lds_wide[BF0 + (sb ^ 1) * BUNIT], 0, 0);
-#pragma unroll
-            for (int q = 0; q < 2; ++q) issue_bs(q, s + 2, sb);
-          }
-        } else {
-          if (h == 0) read_a(sa, kk + 1);
-          read_b(h ? bs : bf, kk + 1, (p + 1) & 1);
-          if (p == 0) { issue_a(0, s + 2, sa2); issue_a(1, s + 2, sa2); }
-          if (p == 4) { issue_a(2, s + 2, sa2); issue_a(3, s + 2, sa2); }
+        } else if (p == 7 && more) {
+          // start of the next stage: its A and BF have landed; A and BS of this one are read by all
+          asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+          wait_loads_but<8>();
+          __builtin_amdgcn_s_barrier();
+          asm volatile("" ::: "memory");
         }
-        __builtin_amdgcn_sched_barrier(0);
+        // The phase's four MFMAs with its other instructions between them, one at a time: the two
+        // wavefronts of a SIMD run in step (every barrier puts them side by side again), so what a
+        // wavefront issues in a block of its own leaves the matrix core idle, while an instruction
+        // issued behind an MFMA runs in that MFMA's shadow.
+        //   slot 0, 1: fragments of the next phase (A of step kk+1 in the first half; at a barrier:
+        //              of the unit that has just landed);  slot 2, 3: its B fragments and the loads
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-          for (int j = 0; j < 2; ++j)
-            acc[i][2 * h + j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk][i], b[p & 1][j], acc[i][2 * h + j], 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
+        for (int m = 0; m < 4; ++m) {
+          const int i = m >> 1, j = m & 1;
+          acc[i][2 * h + j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk][i], b[p & 1][j], acc[i][2 * h + j], 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
+          // (fragments in the order the next phase uses them: A tile 0, B tile 0, B tile 1, A tile 1)
+          if (p == 3) {
+            if (m < 2) rd_b(bs, 0, 0, m);
+            else issue_bf(m - 2, s + 2, sb);
+          } else if (p == 7) {
+            if (more) {
+              if (m == 0) rd_a(sa1, 0, 0);
+              if (m == 1) rd_b(bfn, 0, 0, 0);
+              if (m == 2) { rd_b(bfn, 0, 0, 1); issue_bs(0, s + 2, sb); }
+              if (m == 3) { rd_a(sa1, 0, 1); issue_bs(1, s + 2, sb); }
+            }
+          } else {
+            if (h == 0) {
+              if (m == 0) rd_a(sa, kk + 1, 0);
+              if (m == 1) rd_b(bf, kk + 1, (p + 1) & 1, 0);
+              if (m == 2) rd_b(bf, kk + 1, (p + 1) & 1, 1);
+              if (m == 3) rd_a(sa, kk + 1, 1);
+            } else {
+              if (m < 2) rd_b(bs, kk + 1, (p + 1) & 1, m);
+            }
+            if (p == 0 && m >= 2) issue_a(m - 2, s + 2, sa2);
+            if (p == 4 && m >= 2) issue_a(m, s + 2, sa2);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
       }
       sa = sa1;
       sb ^= 1;
@@ -1406,6 +1427,7 @@ static int wide_tile_n(int M, int N) {
 }
 static bool wide_fits(int M, int N, int K, int nsplit) {
   if (!wide_mode() || M <= 128 || N < 128 || (K % BK)) return false;
+  // (the 256-row kernels address their operands with 32-bit byte offsets: launch_gemm_bf16 checks the spans)
   const int kchunk = ((K + nsplit - 1) / nsplit + BK - 1) / BK * BK;
   return (K % kchunk) == 0 || nsplit == 1;
 }
@@ -1463,7 +1485,11 @@ int launch_wide_line(const Shape& g, const Epilogue& ep, hipStream_t s) {
   const int tiles_m = (g.M + 255) / 256, tiles_n = (g.N + 255) / 256;
   const int ntile = tiles_m * tiles_n;
   dim3 grid(((ntile + 7) / 8) * 8, 1, g.nsplit);
-  gemm_bf16_wide_line_kernel<<<grid, 512, bytes, s>>>(g.A, g.lda, g.B, g.ldb, g.M, g.N, g.K, kchunk, g.slab, ep, tiles_m,
+  // Several rounds of tiles: an fp32 result is stored with the non-temporal hint (see launch_gemm_bf16),
+  // which is worth 9 % there (8192^3: 690 -> 630 us on operands of zeros); one round gains nothing.
+  Epilogue epx = ep;
+  if (ntile >= 512 && !ep.c_is_bf16 && !ep.R) epx.stream_c = 1;
+  gemm_bf16_wide_line_kernel<<<grid, 512, bytes, s>>>(g.A, g.lda, g.B, g.ldb, g.M, g.N, g.K, kchunk, g.slab, epx, tiles_m,
                                                       tiles_n);
   VF_LAUNCH_CHECK();
   return VF_OK;
@@ -1530,7 +1556,9 @@ static int launch_gemm_bf16_ep(const Shape& g, const Epilogue& ep, hipStream_t s
     VF_LAUNCH_CHECK();
     return VF_OK;
   }
-  if (wide_fits(M, N, K, nsplit)) return launch_wide(g, ep, s);
+  // (the 256-row kernels address their operands with 32-bit byte offsets)
+  const bool spans32 = (int64_t)M * lda * 2 < ((int64_t)1 << 31) && (int64_t)N * ldb * 2 < ((int64_t)1 << 31);
+  if (spans32 && wide_fits(M, N, K, nsplit)) return launch_wide(g, ep, s);
   if (use_big_tile(M, N, K)) return launch_cfg<128, 128, 2, 2>(g, ep, s);
   if (M <= 32) return launch_cfg<32, 128, 1, 4>(g, ep, s);
   if (N <= 32) return launch_cfg<128, 32, 4, 1>(g, ep, s);
