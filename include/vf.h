@@ -154,8 +154,8 @@ typedef struct vf_config {
                                     1/window of the buffer traffic; the transposed bf16 operands of
                                     the window's nodes are kept until then, so the workspace grows
                                     with the window (not with V). */
-  int32_t node_group;            /* MLP (bf16) and encoder: up to this many CONSECUTIVE nodes (1, 2, 4
-                                    or 8; 0 = 1) go through their passes together as one unit: their
+  int32_t node_group;            /* MLP (bf16) and encoder: up to this many CONSECUTIVE nodes (1, 2, 4,
+                                    8, 16 or 32; 0 = 1) go through their passes together as one unit: their
                                     rows form one operand of every product, so the weights are read
                                     once per unit instead of once per node.  Everything a node owns
                                     stays per node -- BatchNorm statistics and their moving averages
@@ -164,7 +164,10 @@ typedef struct vf_config {
                                     additions and (nodes of different sizes) one bf16 rounding of
                                     the output gradients, which carry 1/rows of the unit instead of
                                     1/b_i.  MLP: nodes of at most 128 rows, a multiple of 8, of any
-                                    mix of sizes; other nodes go alone.  Encoder: runs of 2 or 4
+                                    mix of sizes; other nodes go alone (units of 16 or 32 nodes: the
+                                    staged fold then differs from the fused one by fp32 rounding in the
+                                    BatchNorm scale / shift gradients, and a fold window holds at most
+                                    as many units as a batch has).  Encoder: runs of 2 or 4
                                     nodes of one size.  The per-node workspace grows by this factor
                                     (not with V). */
   uint32_t flags;                /* VF_FLAG_* */
