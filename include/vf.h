@@ -53,7 +53,8 @@
  *     VF_GEMM_PIPE=0..4    ring depth of the register-staged product kernel (default 3, 0 = off)
  *     VF_GEMM_SPLIT_TARGET=<n>   workgroups a small product is sliced up to (default 256)
  *     VF_GEMM_WIDE=0|1|128|256   256-row product kernel off / on (default) / with 128 or 256 columns
- *     VF_GEMM_WIDE_V=1     256 x 256 tiles on the ring of three 32-element stages instead of whole lines
+ *     VF_GEMM_WIDE_V=1|2   256 x 256 tiles on the ring of three 32-element stages (1) or on the whole-line kernel
+ *                          with the 32x32x16 instruction (2) instead of the whole-line kernel with 16x16x32
  *     VF_GEMM_NT=1         fp32 results of the bf16 products stored with the non-temporal hint
  *     VF_CONV_LDS=0        3x3 convolutions without the filters-resident-in-LDS kernel
  *     VF_CONV_EXPLICIT=1   convolutions always write the patch matrix and call the product kernel

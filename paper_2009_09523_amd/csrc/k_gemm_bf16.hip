@@ -946,6 +946,248 @@ __global__ __launch_bounds__(512) void gemm_bf16_wide_line_kernel(const bf16_t* 
   store_row(std::integral_constant<int, 1>{});
 }
 
+// ---- the whole-line kernel on the 16x16x32 instruction ------------------------------------------
+// Same tile, same LDS plan, same loads and waits as gemm_bf16_wide_line_kernel.  The chip lowers
+// its clock under these products, and per flop the 16x16x32 MFMA draws less than 32x32x16 (a
+// register-only loop on random operands: 2.0 against 1.7 PFLOP/s), so on normally distributed
+// operands this form is the faster one.  A wavefront's 64 x 128 tile is 4 x 8 tiles of 16 x 16;
+// a stage of 64 elements is two MFMA steps of 32; the halves of B are column tiles 0-3 and 4-7:
+// four phases (half, step) of 16 MFMAs per stage, the A fragments of both steps (8) staying in
+// registers for the second half.  A fragment of 16 rows x 32 elements is one 16-byte read per lane
+// (lane % 16 the row, lane / 16 the 16-byte chunk), and the products are taken as B-tile x A-tile,
+// so that a lane ends up with four CONSECUTIVE columns of one row of C (row lane % 16 of the tile,
+// columns 4 (lane / 16) ..): the epilogue stores 16 bytes per lane.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// Epilogue of one row of 16 x 16 tiles (tile row i of the wavefront: 16 rows, 8 x 16 columns).
+template <bool STREAM>
+__device__ __forceinline__ void store_tiles16_row(const f32x4 (&acc)[8], const Epilogue& ep, char* cbase, bool first_slice,
+                                                  int mbase, int nbase, int M, int N, int lane) {
+  const int m = mbase + (lane & 15);
+  const int nq = 4 * (lane >> 4);
+  float* C = reinterpret_cast<float*>(cbase);
+  const bool vec = !ep.c_is_bf16 && mbase + 16 <= M && nbase + 128 <= N && (ep.ldc & 3) == 0 &&
+                   (reinterpret_cast<uintptr_t>(cbase) & 15) == 0 &&
+                   (!ep.R || ((ep.ldr & 3) == 0 && (reinterpret_cast<uintptr_t>(ep.R) & 15) == 0)) &&
+                   (!ep.bias || (reinterpret_cast<uintptr_t>(ep.bias) & 15) == 0);
+  if (vec) {
+    f32x4 add[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      f32x4 bias = {0.f, 0.f, 0.f, 0.f};
+      if (ep.bias && first_slice) {
+        bias = *reinterpret_cast<const f32x4*>(&ep.bias[nbase + 16 * j + nq]);
+        if (ep.bias_round_bf16)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) bias[e] = round_bf16(bias[e]);
+      }
+      add[j] = bias;
+    }
+    if (ep.R) {
+      f32x4 r[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) r[j] = *reinterpret_cast<const f32x4*>(&ep.R[(int64_t)m * ep.ldr + nbase + 16 * j + nq]);
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) add[j][e] = fmaf(ep.beta, r[j][e], add[j][e]);
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      f32x4 v;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = fmaf(ep.alpha, acc[j][e], add[j][e]);
+      f32x4* dst = reinterpret_cast<f32x4*>(&C[(int64_t)m * ep.ldc + nbase + 16 * j + nq]);
+      if (STREAM) __builtin_nontemporal_store(v, dst);
+      else *dst = v;
+    }
+    return;
+  }
+  if (m >= M) return;
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int n = nbase + 16 * j + nq + e;
+      if (n >= N) continue;
+      float addend = 0.f;
+      if (ep.bias && first_slice) {
+        addend = ep.bias[n];
+        if (ep.bias_round_bf16) addend = round_bf16(addend);
+      }
+      if (ep.R) addend = fmaf(ep.beta, ep.R[(int64_t)m * ep.ldr + n], addend);
+      const float v = fmaf(ep.alpha, acc[j][e], addend);
+      if (ep.c_is_bf16) reinterpret_cast<bf16_t*>(cbase)[(int64_t)m * ep.ldc + n] = f32_to_bf16(v);
+      else C[(int64_t)m * ep.ldc + n] = v;
+    }
+}
+
+__global__ __launch_bounds__(512) void gemm_bf16_wide_line16_kernel(const bf16_t* __restrict__ A, int64_t lda,
+                                                                    const bf16_t* __restrict__ B, int64_t ldb,
+                                                                    int M, int N, int K, int kchunk,
+                                                                    int64_t slab_stride, Epilogue ep, int tiles_m,
+                                                                    int tiles_n) {
+  constexpr int BM = 256, BN = 256, KS = 64;
+  constexpr int AUNIT = BM * KS, BUNIT = (BN / 2) * KS;      // elements: 32 KB, 16 KB
+  constexpr int A0 = 0, BF0 = 3 * AUNIT, BS0 = BF0 + 2 * BUNIT;
+  static_assert((BS0 + 2 * BUNIT) * 2 == 160 * 1024, "LDS");
+  extern __shared__ __attribute__((aligned(1024))) bf16_t lds_wide[];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // (in a scalar register)
+  const int wm = wave >> 1, wn = wave & 1;
+  const int ntile = tiles_m * tiles_n;
+  const int per = (ntile + 7) >> 3;
+  const int local = blockIdx.x >> 3;
+  if (local >= per) return;
+  const int t = (blockIdx.x & 7) * per + local;
+  if (t >= ntile) return;
+  const int panel = t / (8 * tiles_n);
+  const int in_panel = t - panel * 8 * tiles_n;
+  const int prow = min(8, tiles_m - panel * 8);
+  const int m0 = (panel * 8 + in_panel % prow) * BM, n0 = (in_panel / prow) * BN;
+  const int kbeg = blockIdx.z * kchunk;
+  const int kend = min(K, kbeg + kchunk);
+  const int nstage = kend > kbeg ? (kend - kbeg) / KS : 0;
+
+  // loads: exactly those of gemm_bf16_wide_line_kernel
+  uint32_t oa[4], obf[2], obs[2];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int row = (wave + 8 * q) * 8 + (lane >> 3);
+    oa[q] = (uint32_t)(((int64_t)min(m0 + row, M - 1) * lda + (((lane & 7) ^ line_swizzle(row)) * 8)) * 2);
+  }
+#pragma unroll
+  for (int q = 0; q < 2; ++q) {
+    const int lr = (wave + 8 * q) * 8 + (lane >> 3);
+    const int trow = (lr >> 6) * (BN / 2) + (lr & 63);
+    const int chunk = ((lane & 7) ^ line_swizzle(lr)) * 8;
+    obf[q] = (uint32_t)(((int64_t)min(n0 + trow, N - 1) * ldb + chunk) * 2);
+    obs[q] = (uint32_t)(((int64_t)min(n0 + trow + 64, N - 1) * ldb + chunk) * 2);
+  }
+  const char* Ab = reinterpret_cast<const char*>(A + kbeg);
+  const char* Bb = reinterpret_cast<const char*>(B + kbeg);
+  auto issue_a = [&](int q, int stage, int slot) {
+    lds_load16(Ab + (size_t)min(stage, nstage - 1) * (KS * 2), oa[q], &lds_wide[A0 + slot * AUNIT + (wave + 8 * q) * 512]);
+  };
+  auto issue_bf = [&](int q, int stage, int slot) {
+    lds_load16(Bb + (size_t)min(stage, nstage - 1) * (KS * 2), obf[q], &lds_wide[BF0 + slot * BUNIT + (wave + 8 * q) * 512]);
+  };
+  auto issue_bs = [&](int q, int stage, int slot) {
+    lds_load16(Bb + (size_t)min(stage, nstage - 1) * (KS * 2), obs[q], &lds_wide[BS0 + slot * BUNIT + (wave + 8 * q) * 512]);
+  };
+
+  f32x4 acc[4][8];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  // fragment rows of tile 0 (tile i is 16 rows = 2 KB further: the chunk permutation repeats every 16 rows)
+  const int ar = wm * 64 + (lane & 15), br = wn * 64 + (lane & 15);
+  const int asw = line_swizzle(ar), bsw = line_swizzle(br);
+
+  if (nstage > 0) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) issue_a(q, 0, 0);
+#pragma unroll
+    for (int q = 0; q < 2; ++q) issue_bf(q, 0, 0);
+#pragma unroll
+    for (int q = 0; q < 2; ++q) issue_bs(q, 0, 0);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) issue_a(q, 1, 1);
+#pragma unroll
+    for (int q = 0; q < 2; ++q) issue_bf(q, 1, 1);
+
+    bf16x8 a[2][4], b[2][4];
+    auto rd_a = [&](int slot, int ks, int i) {
+      const bf16_t* as = &lds_wide[A0 + slot * AUNIT];
+      a[ks][i] = *reinterpret_cast<const bf16x8*>(&as[(ar + 16 * i) * KS + (((4 * ks + (lane >> 4)) ^ asw) * 8)]);
+    };
+    auto rd_b = [&](const bf16_t* bs, int ks, int buf, int j) {
+      b[buf][j] = *reinterpret_cast<const bf16x8*>(&bs[(br + 16 * j) * KS + (((4 * ks + (lane >> 4)) ^ bsw) * 8)]);
+    };
+
+    wait_loads_but<8>();                   // A and BF of stage 0
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int i = 0; i < 4; ++i) rd_a(0, 0, i);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) rd_b(&lds_wide[BF0], 0, 0, j);
+#pragma unroll
+    for (int q = 0; q < 2; ++q) issue_bs(q, 1, 1);
+
+    int sa = 0, sb = 0;                    // stage % 3, stage % 2
+    for (int s = 0; s < nstage; ++s) {
+      const int sa1 = sa == 2 ? 0 : sa + 1, sa2 = sa == 0 ? 2 : sa - 1;    // (s+1) % 3, (s+2) % 3
+      const bf16_t* bf = &lds_wide[BF0 + sb * BUNIT];
+      const bf16_t* bs = &lds_wide[BS0 + sb * BUNIT];
+      const bf16_t* bfn = &lds_wide[BF0 + (sb ^ 1) * BUNIT];
+      const bool more = s + 1 < nstage;
+#pragma unroll
+      for (int p = 0; p < 4; ++p) {
+        const int h = p >> 1, ks = p & 1;
+        __builtin_amdgcn_sched_barrier(0);
+        if (p == 1) {
+          // middle of the stage: BS of this stage has landed, and behind the barrier BF is read by all
+          asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+          wait_loads_but<10>();
+          __builtin_amdgcn_s_barrier();
+          asm volatile("" ::: "memory");
+        } else if (p == 3 && more) {
+          // start of the next stage: its A and BF have landed; A and BS of this one are read by all
+          asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+          wait_loads_but<8>();
+          __builtin_amdgcn_s_barrier();
+          asm volatile("" ::: "memory");
+        }
+        // 16 MFMAs, one other instruction behind each of the first ten at most (see
+        // gemm_bf16_wide_line_kernel): the next phase's fragments, then this phase's two loads
+#pragma unroll
+        for (int m = 0; m < 16; ++m) {
+          const int i = m >> 2, j = m & 3;
+          acc[i][4 * h + j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b[p & 1][j], a[ks][i], acc[i][4 * h + j], 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
+          if (p == 0) {          // next: (half 0, step 1): its A fragments, B from BF
+            if (m < 4) rd_a(sa, 1, m);
+            else if (m < 8) rd_b(bf, 1, 1, m - 4);
+            else if (m < 10) issue_a(m - 8, s + 2, sa2);
+          } else if (p == 1) {   // next: (half 1, step 0): B from BS (A of step 0 is in registers)
+            if (m < 4) rd_b(bs, 0, 0, m);
+            else if (m < 6) issue_bf(m - 4, s + 2, sb);
+          } else if (p == 2) {   // next: (half 1, step 1)
+            if (m < 4) rd_b(bs, 1, 1, m);
+            else if (m < 6) issue_a(m - 2, s + 2, sa2);
+          } else if (more) {     // next: (half 0, step 0) of stage s+1
+            if (m < 4) rd_a(sa1, 0, m);
+            else if (m < 8) rd_b(bfn, 0, 0, m - 4);
+            else if (m < 10) issue_bs(m - 8, s + 2, sb);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+      sa = sa1;
+      sb ^= 1;
+    }
+    wait_loads_but<0>();
+  }
+
+  char* cbase = static_cast<char*>(ep.C) + (int64_t)blockIdx.z * slab_stride * (ep.c_is_bf16 ? 2 : 4);
+  auto store_row = [&](auto ic) {
+    constexpr int i = decltype(ic)::value;
+    f32x4 row[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) row[j] = acc[i][j];
+    if (ep.stream_c) store_tiles16_row<true>(row, ep, cbase, blockIdx.z == 0, m0 + wm * 64 + 16 * i, n0 + wn * (BN / 2), M, N, lane);
+    else store_tiles16_row<false>(row, ep, cbase, blockIdx.z == 0, m0 + wm * 64 + 16 * i, n0 + wn * (BN / 2), M, N, lane);
+  };
+  store_row(std::integral_constant<int, 0>{});
+  store_row(std::integral_constant<int, 1>{});
+  store_row(std::integral_constant<int, 2>{});
+  store_row(std::integral_constant<int, 3>{});
+}
+
 // ---- 3x3 convolution with the filters resident in LDS -------------------------------------------
 // 64 input channels (one 128-byte row per position), 64 output channels per workgroup, image width
 // W a power of two from 8 to 64.  The workgroup keeps its 64 x 576 filters in LDS (nine 64 x 64 tiles,
@@ -1473,11 +1715,14 @@ int launch_wide_cfg(const Shape& g, const Epilogue& ep, hipStream_t s) {
   VF_LAUNCH_CHECK();
   return VF_OK;
 }
+int wide_variant();
 int launch_wide_line(const Shape& g, const Epilogue& ep, hipStream_t s) {
   constexpr int bytes = 160 * 1024;
   static bool ready = false;
   if (!ready) {
     VF_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_wide_line_kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
+    VF_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_wide_line16_kernel),
                                hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
     ready = true;
   }
@@ -1489,12 +1734,16 @@ int launch_wide_line(const Shape& g, const Epilogue& ep, hipStream_t s) {
   // which is worth 9 % there (8192^3: 690 -> 630 us on operands of zeros); one round gains nothing.
   Epilogue epx = ep;
   if (ntile >= 512 && !ep.c_is_bf16 && !ep.R) epx.stream_c = 1;
-  gemm_bf16_wide_line_kernel<<<grid, 512, bytes, s>>>(g.A, g.lda, g.B, g.ldb, g.M, g.N, g.K, kchunk, g.slab, epx, tiles_m,
-                                                      tiles_n);
+  if (wide_variant() == 2)
+    gemm_bf16_wide_line_kernel<<<grid, 512, bytes, s>>>(g.A, g.lda, g.B, g.ldb, g.M, g.N, g.K, kchunk, g.slab, epx, tiles_m,
+                                                        tiles_n);
+  else
+    gemm_bf16_wide_line16_kernel<<<grid, 512, bytes, s>>>(g.A, g.lda, g.B, g.ldb, g.M, g.N, g.K, kchunk, g.slab, epx,
+                                                          tiles_m, tiles_n);
   VF_LAUNCH_CHECK();
   return VF_OK;
 }
-int wide_variant() {   // tuning aid: VF_GEMM_WIDE_V=1 runs 256-wide tiles on the ring of three half-line stages
+int wide_variant() {   // tuning aid: VF_GEMM_WIDE_V=1 runs 256-wide tiles on the ring of three half-line stages, 2 on the whole-line kernel with 32x32x16 MFMAs
   static int cached = -1;
   if (cached < 0) {
     const char* e = std::getenv("VF_GEMM_WIDE_V");
