@@ -959,6 +959,14 @@ __global__ __launch_bounds__(512) void gemm_bf16_wide_line_kernel(const bf16_t* 
 // columns 4 (lane / 16) ..): the epilogue stores 16 bytes per lane.
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+// Chunk permutation of this kernel's LDS rows.  A 16-byte fragment read of 16 rows x 4 chunks (lane % 16
+// the row, lane / 16 the chunk) takes 4 cycles when no two of the 16 lanes served together meet on a
+// bank, and a probe that timed such reads under every linear map from the row's low four bits to the
+// chunk position measured: unpermuted 16 cycles, line_swizzle 8 (half of this kernel's LDS cycles were
+// bank conflicts by the counters), and 4 for the maps that send bits 0-2 or bits 1-3 of the row to the
+// three position bits one to one.  The first of those:
+__device__ __forceinline__ int line16_swizzle(int r) { return r & 7; }
+
 // Epilogue of one row of 16 x 16 tiles (tile row i of the wavefront: 16 rows, 8 x 16 columns).
 template <bool STREAM>
 __device__ __forceinline__ void store_tiles16_row(const f32x4 (&acc)[8], const Epilogue& ep, char* cbase, bool first_slice,
@@ -1055,13 +1063,13 @@ __global__ __launch_bounds__(512) void gemm_bf16_wide_line16_kernel(const bf16_t
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
     const int row = (wave + 8 * q) * 8 + (lane >> 3);
-    oa[q] = (uint32_t)(((int64_t)min(m0 + row, M - 1) * lda + (((lane & 7) ^ line_swizzle(row)) * 8)) * 2);
+    oa[q] = (uint32_t)(((int64_t)min(m0 + row, M - 1) * lda + (((lane & 7) ^ line16_swizzle(row)) * 8)) * 2);
   }
 #pragma unroll
   for (int q = 0; q < 2; ++q) {
     const int lr = (wave + 8 * q) * 8 + (lane >> 3);
     const int trow = (lr >> 6) * (BN / 2) + (lr & 63);
-    const int chunk = ((lane & 7) ^ line_swizzle(lr)) * 8;
+    const int chunk = ((lane & 7) ^ line16_swizzle(lr)) * 8;
     obf[q] = (uint32_t)(((int64_t)min(n0 + trow, N - 1) * ldb + chunk) * 2);
     obs[q] = (uint32_t)(((int64_t)min(n0 + trow + 64, N - 1) * ldb + chunk) * 2);
   }
@@ -1085,7 +1093,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_wide_line16_kernel(const bf16_t
 
   // fragment rows of tile 0 (tile i is 16 rows = 2 KB further: the chunk permutation repeats every 16 rows)
   const int ar = wm * 64 + (lane & 15), br = wn * 64 + (lane & 15);
-  const int asw = line_swizzle(ar), bsw = line_swizzle(br);
+  const int asw = line16_swizzle(ar), bsw = line16_swizzle(br);
 
   if (nstage > 0) {
 #pragma unroll
