@@ -326,7 +326,8 @@ __global__ __launch_bounds__(256) void bn_relu_bwd_kernel(float* __restrict__ da
 // Row ranges of the nodes of a unit: node n has rows[n] <= 128 rows starting at row base[n] of the
 // unit (a multiple of 8 when transposed copies are written); entries beyond the unit's nodes are 0.
 constexpr int kBnGroup = 8;   // nodes per launch of the group kernels
-struct GroupRows { int base[8]; int rows[8]; };
+constexpr int kBnGroupPair = 16;   // nodes per launch of the forward two-column kernel
+struct GroupRows { int base[16]; int rows[16]; };
 
 template <int G, int SG_> struct GroupShape {
   static constexpr int SG = SG_ < G ? SG_ : G;   // sub-groups side by side
@@ -534,6 +535,252 @@ __global__ __launch_bounds__((GroupShape<G, SGP>::THREADS)) void bn_relu_bwd_gro
   }
 }
 
+
+// ---- two columns per thread -----------------------------------------------------------------------
+// The group kernels above with a workgroup on 2 CB = 32 columns, every thread on two neighbouring
+// ones: a row of a workgroup's block is a whole 128-byte line of the fp32 tensors (8 bytes per lane)
+// and half a line of the bf16 ones, and the four workgroups that an XCD receives in a row cover 512
+// contiguous bytes of every row.  (A probe of the bare access pattern over 2048 x 8192: 16 columns
+// per workgroup 5.0 TB/s, 32 columns 6.1, and 7.0 with sixteen nodes per launch; 64 columns leave
+// too few workgroups.)  For wide layers whose input is unsliced and lies where it is kept.  Per
+// column the arithmetic is that of the kernels above, operation for operation.
+constexpr int CB2 = 2 * CB;
+
+__device__ __forceinline__ float2 col_reduce2(float2 v, float (*red)[RL][CB + 1], int tx, int ty) {
+  red[0][ty][tx] = v.x;
+  red[1][ty][tx] = v.y;
+  __syncthreads();
+  float2 s = {0.f, 0.f};
+#pragma unroll
+  for (int i = 0; i < RL; ++i) { s.x += red[0][i][tx]; s.y += red[1][i][tx]; }
+  __syncthreads();
+  return s;
+}
+
+__device__ __forceinline__ void store_transposed_pair(const bf16_t (*tile)[RCH + 8], bf16_t* __restrict__ outT,
+                                                      int64_t ldt, int c0, int C, int R, int t) {
+  const int seg = t & 15, rl = seg * 8;
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int col = (t >> 4) + 16 * h;          // 2 x 16 columns x 16 segments of 8 rows
+    const int c = c0 + col;
+    if (c < C && rl < R)
+      *reinterpret_cast<uint4*>(&outT[(int64_t)c * ldt + rl]) = *reinterpret_cast<const uint4*>(&tile[col][rl]);
+  }
+}
+
+template <int G, int SGP>
+__global__ __launch_bounds__((GroupShape<G, SGP>::THREADS)) void bn_relu_fwd_pair_kernel(
+    const float* __restrict__ z, int64_t ldz, GroupRows gr, int count, int C, const float* __restrict__ gamma,
+    const float* __restrict__ beta, int round_params, float eps, bf16_t* __restrict__ a, int64_t lda,
+    bf16_t* __restrict__ aT, int64_t ldt, float* __restrict__ mean_out, float* __restrict__ rstd_out,
+    float* __restrict__ run_mean, float* __restrict__ run_var, float run_mix) {
+  constexpr int SG = GroupShape<G, SGP>::SG, RND = GroupShape<G, SGP>::RND;
+  __shared__ float red[SG][2][RL][CB + 1];
+  __shared__ __attribute__((aligned(16))) bf16_t tile[SG][CB2][RCH + 8];
+  __shared__ float stat[G][2][CB2];
+  const int sub = threadIdx.x >> 8, t = threadIdx.x & 255;
+  const int tx = t % CB, ty = t / CB;
+  const int c0 = xcd_column_block(blockIdx.x, gridDim.x) * CB2;
+  const int c = c0 + 2 * tx;                      // C is even: c and c + 1 are live together
+  const bool live = c < C;
+  const bool bn = gamma != nullptr;
+  const int cc = min(c, C - 2);
+  float2 g = {1.f, 1.f}, b = {0.f, 0.f};
+  if (bn && live) { g = *reinterpret_cast<const float2*>(&gamma[c]); b = *reinterpret_cast<const float2*>(&beta[c]); }
+  float2 zr[RND][RPT];
+#pragma unroll
+  for (int q = 0; q < RND; ++q)
+#pragma unroll
+    for (int k = 0; k < RPT; ++k) {
+      const int r = ty + RL * k;
+      const int n = q * SG + sub;
+      zr[q][k] = *reinterpret_cast<const float2*>(&z[(int64_t)(gr.base[n] + max(min(r, gr.rows[n] - 1), 0)) * ldz + cc]);
+    }
+  if (bn && live && round_params) { g.x = round_bf16(g.x); g.y = round_bf16(g.y); b.x = round_bf16(b.x); b.y = round_bf16(b.y); }
+#pragma unroll
+  for (int q = 0; q < RND; ++q) {
+    const int n = q * SG + sub;
+    const int R = gr.rows[n], rb = gr.base[n];    // (R = 0 behind the unit's last node: nothing is stored)
+    float2 mean = {0.f, 0.f}, rstd = {1.f, 1.f};
+    float2 s = {0.f, 0.f};
+#pragma unroll
+    for (int k = 0; k < RPT; ++k) {
+      const int r = ty + RL * k;
+      if (!(live && r < R)) zr[q][k] = float2{0.f, 0.f};
+      s.x += zr[q][k].x; s.y += zr[q][k].y;
+    }
+    if (bn) {
+      const float2 sm = col_reduce2(s, red[sub], tx, ty);
+      mean.x = sm.x / (float)R; mean.y = sm.y / (float)R;
+      float2 qq = {0.f, 0.f};
+#pragma unroll
+      for (int k = 0; k < RPT; ++k) {
+        const int r = ty + RL * k;
+        const bool on = live && r < R;
+        const float dx = on ? zr[q][k].x - mean.x : 0.f, dy = on ? zr[q][k].y - mean.y : 0.f;
+        qq.x = fmaf(dx, dx, qq.x); qq.y = fmaf(dy, dy, qq.y);
+      }
+      const float2 sq = col_reduce2(qq, red[sub], tx, ty);
+      const float2 var = {sq.x / (float)R, sq.y / (float)R};
+      rstd.x = 1.0f / sqrtf(var.x + eps); rstd.y = 1.0f / sqrtf(var.y + eps);
+      if (ty == 0) {
+        stat[n][0][2 * tx] = mean.x; stat[n][0][2 * tx + 1] = mean.y;
+        stat[n][1][2 * tx] = var.x;  stat[n][1][2 * tx + 1] = var.y;
+        if (live && n < count) {
+          *reinterpret_cast<float2*>(&mean_out[(int64_t)n * C + c]) = mean;
+          *reinterpret_cast<float2*>(&rstd_out[(int64_t)n * C + c]) = rstd;
+        }
+      }
+    } else if (q > 0 && aT) {
+      __syncthreads();                            // the tile of the round before has been read
+    }
+#pragma unroll
+    for (int k = 0; k < RPT; ++k) {
+      const int r = ty + RL * k;
+      float vx = 0.f, vy = 0.f;
+      if (live && r < R) {
+        vx = bn ? fmaxf(fmaf(g.x, (zr[q][k].x - mean.x) * rstd.x, b.x), 0.f) : fmaxf(zr[q][k].x, 0.f);
+        vy = bn ? fmaxf(fmaf(g.y, (zr[q][k].y - mean.y) * rstd.y, b.y), 0.f) : fmaxf(zr[q][k].y, 0.f);
+        *reinterpret_cast<uint32_t*>(&a[(int64_t)(rb + r) * lda + c]) = (uint32_t)f32_to_bf16(vx) | ((uint32_t)f32_to_bf16(vy) << 16);
+      }
+      if (aT) { tile[sub][2 * tx][r] = f32_to_bf16(vx); tile[sub][2 * tx + 1][r] = f32_to_bf16(vy); }
+    }
+    if (aT) {
+      __syncthreads();
+      store_transposed_pair(tile[sub], aT + rb, ldt, c0, C, R, t);
+    }
+  }
+  // moving statistics of this device: one blend per pass, node after node (Section 4.1)
+  if (bn && run_mean) {
+    __syncthreads();
+    if (sub == 0 && ty == 0 && live) {
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        float rm = run_mean[c + e], rv = run_var[c + e];
+#pragma unroll
+        for (int n = 0; n < G; ++n) {
+          if (n < count) {
+            rm = fmaf(run_mix, stat[n][0][2 * tx + e] - rm, rm);
+            rv = fmaf(run_mix, stat[n][1][2 * tx + e] - rv, rv);
+          }
+        }
+        run_mean[c + e] = rm; run_var[c + e] = rv;
+      }
+    }
+  }
+}
+
+template <int G, int SGP>
+__global__ __launch_bounds__((GroupShape<G, SGP>::THREADS)) void bn_relu_bwd_pair_kernel(
+    const float* __restrict__ da, int64_t ldda, const float* __restrict__ z, int64_t ldz, GroupRows gr, int count, int C,
+    const float* __restrict__ gamma, const float* __restrict__ beta, int round_params,
+    const float* __restrict__ mean_in, const float* __restrict__ rstd_in, bf16_t* __restrict__ dz, int64_t lddz,
+    bf16_t* __restrict__ dzT, int64_t ldt, GradOut gout_g, GradOut gout_b, float tscale) {
+  constexpr int SG = GroupShape<G, SGP>::SG, RND = GroupShape<G, SGP>::RND;
+  __shared__ float red[SG][2][RL][CB + 1];
+  __shared__ __attribute__((aligned(16))) bf16_t tile[SG][CB2][RCH + 8];
+  __shared__ float sums[G][2][CB2];
+  const int sub = threadIdx.x >> 8, t = threadIdx.x & 255;
+  const int tx = t % CB, ty = t / CB;
+  const int c0 = xcd_column_block(blockIdx.x, gridDim.x) * CB2;
+  const int c = c0 + 2 * tx;
+  const bool live = c < C;
+  const bool bn = gamma != nullptr;
+  const int cc = min(c, C - 2);
+  float2 g = {1.f, 1.f}, b = {0.f, 0.f}, mean[RND], rstd[RND];
+#pragma unroll
+  for (int q = 0; q < RND; ++q) { mean[q] = float2{0.f, 0.f}; rstd[q] = float2{1.f, 1.f}; }
+  if (live && bn) {
+    g = *reinterpret_cast<const float2*>(&gamma[c]); b = *reinterpret_cast<const float2*>(&beta[c]);
+    if (round_params) { g.x = round_bf16(g.x); g.y = round_bf16(g.y); b.x = round_bf16(b.x); b.y = round_bf16(b.y); }
+#pragma unroll
+    for (int q = 0; q < RND; ++q) {
+      const int nn = min(q * SG + sub, count - 1);
+      mean[q] = *reinterpret_cast<const float2*>(&mean_in[(int64_t)nn * C + c]);
+      rstd[q] = *reinterpret_cast<const float2*>(&rstd_in[(int64_t)nn * C + c]);
+    }
+  }
+  float2 xr[RND][RPT], dr[RND][RPT];
+#pragma unroll
+  for (int q = 0; q < RND; ++q)
+#pragma unroll
+    for (int k = 0; k < RPT; ++k) {
+      const int rc = gr.base[q * SG + sub] + max(min(ty + RL * k, gr.rows[q * SG + sub] - 1), 0);
+      xr[q][k] = *reinterpret_cast<const float2*>(&z[(int64_t)rc * ldz + cc]);
+      dr[q][k] = *reinterpret_cast<const float2*>(&da[(int64_t)rc * ldda + cc]);
+    }
+#pragma unroll
+  for (int q = 0; q < RND; ++q) {
+    const int n = q * SG + sub;
+    const int R = gr.rows[n], rb = gr.base[n];    // (R = 0 behind the unit's last node: nothing is stored)
+    const float invR = 1.0f / (float)R;
+    float2 sg = {0.f, 0.f}, sb = {0.f, 0.f};
+#pragma unroll
+    for (int k = 0; k < RPT; ++k) {
+      const int r = ty + RL * k;
+      const bool on = live && r < R;
+      {
+        const float zz = xr[q][k].x;
+        const float xhat = (zz - mean[q].x) * rstd[q].x;
+        const float pre = bn ? fmaf(g.x, xhat, b.x) : zz;
+        xr[q][k].x = on ? xhat : 0.f;
+        dr[q][k].x = (on && pre > 0.f) ? dr[q][k].x : 0.f;
+        sg.x = fmaf(dr[q][k].x, xr[q][k].x, sg.x);
+        sb.x += dr[q][k].x;
+      }
+      {
+        const float zz = xr[q][k].y;
+        const float xhat = (zz - mean[q].y) * rstd[q].y;
+        const float pre = bn ? fmaf(g.y, xhat, b.y) : zz;
+        xr[q][k].y = on ? xhat : 0.f;
+        dr[q][k].y = (on && pre > 0.f) ? dr[q][k].y : 0.f;
+        sg.y = fmaf(dr[q][k].y, xr[q][k].y, sg.y);
+        sb.y += dr[q][k].y;
+      }
+    }
+    sg = col_reduce2(sg, red[sub], tx, ty);
+    sb = col_reduce2(sb, red[sub], tx, ty);
+    if (ty == 0) {
+      sums[n][0][2 * tx] = sg.x; sums[n][0][2 * tx + 1] = sg.y;
+      sums[n][1][2 * tx] = sb.x; sums[n][1][2 * tx + 1] = sb.y;
+    }
+    const float2 kk = {g.x * rstd[q].x, g.y * rstd[q].y};
+#pragma unroll
+    for (int k = 0; k < RPT; ++k) {
+      const int r = ty + RL * k;
+      float vx = 0.f, vy = 0.f;
+      if (live && r < R) {
+        vx = bn ? kk.x * (dr[q][k].x - sb.x * invR - xr[q][k].x * sg.x * invR) : dr[q][k].x;
+        vy = bn ? kk.y * (dr[q][k].y - sb.y * invR - xr[q][k].y * sg.y * invR) : dr[q][k].y;
+        *reinterpret_cast<uint32_t*>(&dz[(int64_t)(rb + r) * lddz + c]) = (uint32_t)f32_to_bf16(vx) | ((uint32_t)f32_to_bf16(vy) << 16);
+      }
+      if (dzT) { tile[sub][2 * tx][r] = f32_to_bf16(vx * tscale); tile[sub][2 * tx + 1][r] = f32_to_bf16(vy * tscale); }
+    }
+    if (dzT) {
+      __syncthreads();                            // (the next round writes the tile behind its reductions' barriers)
+      store_transposed_pair(tile[sub], dzT + rb, ldt, c0, C, R, t);
+    }
+  }
+  // small-vector gradients: added up in node order and folded in once, as in the kernels above
+  __syncthreads();
+  if (sub == 0 && ty == 0 && live) {
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+      float tg = 0.f, tb = 0.f;
+#pragma unroll
+      for (int n = 0; n < G; ++n) {
+        if (n < count) {
+          tg = n ? tg + sums[n][0][2 * tx + e] : sums[n][0][2 * tx + e];
+          tb = n ? tb + sums[n][1][2 * tx + e] : sums[n][1][2 * tx + e];
+        }
+      }
+      if (bn) grad_store(gout_g, c + e, tg);
+      if (gout_b.dst) grad_store(gout_b, c + e, tb);
+    }
+  }
+}
+
 constexpr int SCB = 32, SRL = 8;
 template <typename T>
 __global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ x, int64_t ld, int R, int C,
@@ -587,6 +834,16 @@ __global__ __launch_bounds__(256) void rowsum_nodes_kernel(NodeList nl, int64_t 
 // Sub-groups of 256 threads per workgroup of the group kernels: four while that is what it takes to
 // give every compute unit enough threads, two for wide layers (whose column blocks alone do).
 // VF_BN_SUBGROUPS = 2 | 4 overrides (tuning aid).
+// Whether the two-column kernels take a layer of C columns: even, and wide enough that blocks of 32
+// columns still give every compute unit a workgroup.  VF_BN_PAIR = 0 switches them off, 1 takes
+// them for every even width (tuning and testing aid).
+bool pair_width(int C) {
+  static const int mode = std::getenv("VF_BN_PAIR") ? std::atoi(std::getenv("VF_BN_PAIR")) : -1;
+  if (mode == 0 || (C & 1)) return false;
+  return mode == 1 || (C + CB2 - 1) / CB2 >= 192;
+}
+bool aligned_to(const void* p, uintptr_t n) { return (reinterpret_cast<uintptr_t>(p) & (n - 1)) == 0; }
+
 int group_subgroups(int grid) {
   static const int forced = std::getenv("VF_BN_SUBGROUPS") ? std::atoi(std::getenv("VF_BN_SUBGROUPS")) : 0;
   if (forced == 2 || forced == 4) return forced;
@@ -597,9 +854,9 @@ int group_subgroups(int grid) {
 // node_rows[n] rows when given.  Every node at most 128 rows; ranges start on multiples of 8 when
 // transposed copies are written.
 int group_rows(int group, int R, const int* node_rows, bool transposed, GroupRows* gr) {
-  if (group < 2 || group > 8) return VF_EINVAL;
+  if (group < 2 || group > kBnGroupPair) return VF_EINVAL;
   int at = 0;
-  for (int n = 0; n < 8; ++n) {
+  for (int n = 0; n < kBnGroupPair; ++n) {
     const int rows = n < group ? (node_rows ? node_rows[n] : R) : 0;
     if (n < group && (rows < 1 || rows > RCH || (transposed && (rows & 7)))) return VF_EINVAL;
     gr->base[n] = n < group ? at : 0;
@@ -615,13 +872,17 @@ int launch_bn_relu_fwd(const float* zp, int nsplit, int64_t slab, int64_t ldzp, 
                        float* mean, float* rstd, float* run_mean, float* run_var, float run_mix,
                        hipStream_t s, int group, const int* node_rows) {
   if (R <= 0 || C <= 0 || nsplit < 1) return VF_EINVAL;
-  if (group > kBnGroup) {
-    // a unit of more than kBnGroup nodes: one launch per kBnGroup nodes, in node order (the moving
+  const bool pair = group >= 2 && nsplit == 1 && zp == z && a_is_bf16 && pair_width(C) && !(ldz & 1) && !(lda & 1) &&
+                    aligned_to(z, 8) && aligned_to(a, 4) && aligned_to(gamma, 8) && aligned_to(beta, 8) &&
+                    aligned_to(mean, 8) && aligned_to(rstd, 8);
+  const int per = pair ? kBnGroupPair : kBnGroup;
+  if (group > per) {
+    // a unit of more nodes than a launch takes: one launch per `per` nodes, in node order (the moving
     // statistics are blended node after node by launches that follow each other on the stream)
     if (!a_is_bf16) return VF_EINVAL;
     int64_t row = 0;
-    for (int n0 = 0; n0 < group; n0 += kBnGroup) {
-      const int cnt = std::min(kBnGroup, group - n0);
+    for (int n0 = 0; n0 < group; n0 += per) {
+      const int cnt = std::min(per, group - n0);
       int64_t rows = 0;
       for (int n = 0; n < cnt; ++n) rows += node_rows ? node_rows[n0 + n] : R;
       VF_TRY(launch_bn_relu_fwd(zp + row * ldzp, nsplit, slab, ldzp, node_rows ? node_rows[n0] : R, C, gamma, beta,
@@ -641,6 +902,19 @@ int launch_bn_relu_fwd(const float* zp, int nsplit, int64_t slab, int64_t ldzp, 
   if (group != 1) {
     if (!a_is_bf16) return VF_EINVAL;
     VF_TRY(group_rows(group, R, node_rows, aT != nullptr, &gr));
+  }
+  if (pair) {
+    const int pgrid = (C + CB2 - 1) / CB2;
+#define VF_FWDP(GG, SS)                                                                              \
+  bn_relu_fwd_pair_kernel<GG, SS><<<pgrid, GroupShape<GG, SS>::THREADS, 0, s>>>(z, ldz, gr, group, C, gamma, beta, \
+      round_params, eps, static_cast<bf16_t*>(a), lda, aT, ldt, mean, rstd, run_mean, run_var, run_mix)
+    if (group > 8) VF_FWDP(16, 4);
+    else if (group > 4) VF_FWDP(8, 4);
+    else if (group > 2) VF_FWDP(4, 4);
+    else VF_FWDP(2, 2);
+#undef VF_FWDP
+    VF_LAUNCH_CHECK();
+    return VF_OK;
   }
 #define VF_FWD2(TT, NS, SM, GG)                                                                    \
   bn_relu_fwd_kernel<TT, NS, SM, GG><<<grid, 256, 0, s>>>(zp, slab, ldzp, R, C, gamma, beta, round_params, \
@@ -676,6 +950,9 @@ int launch_bn_relu_bwd(float* dap, int nsplit, int64_t slab, int64_t ldda, const
                        int dz_is_bf16, bf16_t* dzT, int64_t ldt, GradOut gout_g, GradOut gout_b,
                        hipStream_t s, float tscale, int group, const int* node_rows) {
   if (R <= 0 || C <= 0 || nsplit < 1) return VF_EINVAL;
+  const bool pair = group >= 2 && nsplit == 1 && dz_is_bf16 && pair_width(C) && !(ldz & 1) && !(ldda & 1) && !(lddz & 1) &&
+                    aligned_to(z, 8) && aligned_to(dap, 8) && aligned_to(dz, 4) && aligned_to(gamma, 8) &&
+                    aligned_to(beta, 8) && aligned_to(mean, 8) && aligned_to(rstd, 8);
   if (group > kBnGroup) {
     // a unit of more than kBnGroup nodes: one launch per kBnGroup nodes; the small-vector gradients
     // of the later launches are added to what the first one left
@@ -703,6 +980,18 @@ int launch_bn_relu_bwd(float* dap, int nsplit, int64_t slab, int64_t ldda, const
   if (group != 1) {
     if (!dz_is_bf16) return VF_EINVAL;
     VF_TRY(group_rows(group, R, node_rows, dzT != nullptr, &gr));
+  }
+  if (pair) {
+    const int pgrid = (C + CB2 - 1) / CB2;
+#define VF_BWDP(GG, SS)                                                                              \
+  bn_relu_bwd_pair_kernel<GG, SS><<<pgrid, GroupShape<GG, SS>::THREADS, 0, s>>>(dap, ldda, z, ldz, gr, group, C, gamma, \
+      beta, round_params, mean, rstd, static_cast<bf16_t*>(dz), lddz, dzT, ldt, gout_g, gout_b, tscale)
+    if (group > 4) VF_BWDP(8, 4);
+    else if (group > 2) VF_BWDP(4, 4);
+    else VF_BWDP(2, 2);
+#undef VF_BWDP
+    VF_LAUNCH_CHECK();
+    return VF_OK;
   }
 #define VF_BWD2(TT, NS, SM, GG)                                                                    \
   bn_relu_bwd_kernel<TT, NS, SM, GG><<<grid, 256, 0, s>>>(dap, slab, ldda, z, ldz, R, C, gamma, beta,  \
