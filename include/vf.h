@@ -60,6 +60,10 @@
  *     VF_CONV_EXPLICIT=1   convolutions always write the patch matrix and call the product kernel
  *     VF_LN_WGS=<n>        workgroups of the LayerNorm backward kernel (default 256)
  *     VF_BN_SUBGROUPS=2|4  sub-groups of 256 threads per workgroup of the grouped BatchNorm kernels
+ *     VF_BN_PAIR=0|1       grouped BatchNorm kernels with two columns per thread: never | for every even width
+ *                          (default: for layers of at least 6144 columns)
+ *     VF_FLAT_NT=0|1       accumulate and optimizer kernels with non-temporal accesses: never | always
+ *                          (default: for vectors of 64 MB and more)
  */
 #ifndef VF_H
 #define VF_H

@@ -80,6 +80,43 @@ def test_adam_kernel(n):
     np.testing.assert_allclose(ut.cpu().numpy(), u, rtol=5e-5, atol=1e-9)
 
 
+def test_flat_kernels_on_vectors_beyond_the_cache():
+    """Vectors of 64 MB and more take the kernels' non-temporal form (here 256 MB): accumulate (two nodes, bit for bit
+    against its fma chain), SGD-momentum and Adam (one step each against the oracle), ragged tail included."""
+    import torch
+    import paper_2009_09523_amd as vf
+    n = (64 << 20) + 5
+    print(f"flat kernels n={n}", flush=True)
+    rng = np.random.Generator(np.random.PCG64(77))
+    g0 = rng.standard_normal(n, dtype=np.float32)
+    g1 = rng.standard_normal(n, dtype=np.float32)
+    w = [np.float32(48) / np.float32(256), np.float32(208) / np.float32(256)]
+    buf = torch.full((n,), 7.0, device="cuda")
+    vf.vf_accumulate(buf, torch.from_numpy(g0).cuda(), float(w[0]), first=True)
+    vf.vf_accumulate(buf, torch.from_numpy(g1).cuda(), float(w[1]), first=False)
+    torch.cuda.synchronize()
+    acc = (np.float64(w[0]) * g0.astype(np.float64)).astype(np.float32).astype(np.float64)
+    acc = (np.float64(w[1]) * g1.astype(np.float64) + acc).astype(np.float32)
+    G = buf.cpu().numpy()
+    np.testing.assert_array_equal(G, acc)
+    del acc
+    th0 = rng.standard_normal(n, dtype=np.float32)
+    tht, vt = torch.from_numpy(th0).cuda(), torch.zeros(n, device="cuda")
+    vf.vf_sgdm_update(tht, vt, buf, 0.1, 0.9)
+    th, v = O.sgdm_update(th0.astype(np.float64), G, np.zeros(n), 0.1, 0.9)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(tht.cpu().numpy(), th, rtol=1e-5, atol=1e-6)
+    np.testing.assert_allclose(vt.cpu().numpy(), v, rtol=1e-5, atol=1e-6)
+    del th, v
+    tht, mt, ut = torch.from_numpy(th0).cuda(), torch.zeros(n, device="cuda"), torch.zeros(n, device="cuda")
+    vf.vf_adam_update(tht, mt, ut, buf, 1e-3, 0.9, 0.999, 1e-8, 1)
+    th, m, u = O.adam_update(th0.astype(np.float64), G, np.zeros(n), np.zeros(n), 1, 1e-3, 0.9, 0.999, 1e-8)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(tht.cpu().numpy(), th, rtol=1e-5, atol=1e-6)
+    np.testing.assert_allclose(mt.cpu().numpy(), m, rtol=1e-5, atol=1e-7)
+    np.testing.assert_allclose(ut.cpu().numpy(), u, rtol=5e-5, atol=1e-9)
+
+
 GEMM_SHAPES = [(128, 4096 // 8, 1024 // 4), (48, 1000, 520), (16, 392, 1000), (8, 520, 256), (40, 264, 392),
                (300, 100, 392), (392, 1000, 128), (520, 392, 48), (256, 520, 16), (256, 520, 8), (1, 8, 8),
                (33, 65, 72), (129, 257, 264), (304, 1003, 128), (2048, 2304, 768),
