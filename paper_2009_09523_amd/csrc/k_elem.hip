@@ -90,7 +90,7 @@ __global__ __launch_bounds__(256) void cast_weight_kernel(const float* __restric
   float4 vin[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
-    vin[i] = *reinterpret_cast<const float4*>(&in[(int64_t)min(r0 + g + 16 * i, R - 1) * ldi + min(c0 + 4 * q, C - 4)]);
+    vin[i] = load4_stream(&in[(int64_t)min(r0 + g + 16 * i, R - 1) * ldi + min(c0 + 4 * q, C - 4)]);
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int rl = g + 16 * i, r = r0 + rl, c = c0 + 4 * q;

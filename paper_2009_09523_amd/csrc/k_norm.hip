@@ -565,7 +565,7 @@ __device__ __forceinline__ void store_transposed_pair(const bf16_t (*tile)[RCH +
     const int col = (t >> 4) + 16 * h;          // 2 x 16 columns x 16 segments of 8 rows
     const int c = c0 + col;
     if (c < C && rl < R)
-      *reinterpret_cast<uint4*>(&outT[(int64_t)c * ldt + rl]) = *reinterpret_cast<const uint4*>(&tile[col][rl]);
+      store16_stream(&outT[(int64_t)c * ldt + rl], *reinterpret_cast<const uint4*>(&tile[col][rl]));
   }
 }
 
@@ -595,7 +595,7 @@ __global__ __launch_bounds__((GroupShape<G, SGP>::THREADS)) void bn_relu_fwd_pai
     for (int k = 0; k < RPT; ++k) {
       const int r = ty + RL * k;
       const int n = q * SG + sub;
-      zr[q][k] = *reinterpret_cast<const float2*>(&z[(int64_t)(gr.base[n] + max(min(r, gr.rows[n] - 1), 0)) * ldz + cc]);
+      zr[q][k] = load2_stream(&z[(int64_t)(gr.base[n] + max(min(r, gr.rows[n] - 1), 0)) * ldz + cc]);
     }
   if (bn && live && round_params) { g.x = round_bf16(g.x); g.y = round_bf16(g.y); b.x = round_bf16(b.x); b.y = round_bf16(b.y); }
 #pragma unroll
@@ -707,8 +707,8 @@ __global__ __launch_bounds__((GroupShape<G, SGP>::THREADS)) void bn_relu_bwd_pai
 #pragma unroll
     for (int k = 0; k < RPT; ++k) {
       const int rc = gr.base[q * SG + sub] + max(min(ty + RL * k, gr.rows[q * SG + sub] - 1), 0);
-      xr[q][k] = *reinterpret_cast<const float2*>(&z[(int64_t)rc * ldz + cc]);
-      dr[q][k] = *reinterpret_cast<const float2*>(&da[(int64_t)rc * ldda + cc]);
+      xr[q][k] = load2_stream(&z[(int64_t)rc * ldz + cc]);
+      dr[q][k] = load2_stream(&da[(int64_t)rc * ldda + cc]);
     }
 #pragma unroll
   for (int q = 0; q < RND; ++q) {

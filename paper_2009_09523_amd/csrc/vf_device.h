@@ -28,6 +28,23 @@ __device__ __forceinline__ void store_f2(bf16_t* p, float a, float b) {
   *reinterpret_cast<uint32_t*>(p) = (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
 }
 
+// Accesses with the non-temporal hint, for data that is read or written once and not used again soon.
+typedef float vf_f32x4 __attribute__((ext_vector_type(4)));
+typedef float vf_f32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t vf_u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 load4_stream(const float* p) {
+  const vf_f32x4 r = __builtin_nontemporal_load(reinterpret_cast<const vf_f32x4*>(p));
+  return float4{r[0], r[1], r[2], r[3]};
+}
+__device__ __forceinline__ float2 load2_stream(const float* p) {
+  const vf_f32x2 r = __builtin_nontemporal_load(reinterpret_cast<const vf_f32x2*>(p));
+  return float2{r[0], r[1]};
+}
+__device__ __forceinline__ void store16_stream(void* p, uint4 v) {
+  const vf_u32x4 r = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(r, reinterpret_cast<vf_u32x4*>(p));
+}
+
 __device__ __forceinline__ void grad_store(const GradOut& g, int64_t p, float v) {
   float old = g.accumulate ? g.dst[p] : 0.f;
   g.dst[p] = fmaf(g.alpha, v, old);
