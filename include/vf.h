@@ -62,6 +62,8 @@
  *     VF_BN_SUBGROUPS=2|4  sub-groups of 256 threads per workgroup of the grouped BatchNorm kernels
  *     VF_BN_PAIR=0|1       grouped BatchNorm kernels with two columns per thread: never | for every even width
  *                          (default: for layers of at least 6144 columns)
+ *     VF_BN_FUSE=0         the BatchNorm backward pass as a kernel of its own also where the input-gradient
+ *                          product's epilogue would take it (units of whole 128-row nodes on wide layers)
  *     VF_FLAT_NT=0|1       accumulate and optimizer kernels with non-temporal accesses: never | always
  *                          (default: for vectors of 64 MB and more)
  */

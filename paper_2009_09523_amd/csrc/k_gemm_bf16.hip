@@ -1030,11 +1030,151 @@ __device__ __forceinline__ void store_tiles16_row(const f32x4 (&acc)[8], const E
     }
 }
 
+// BatchNorm + ReLU backward of a finished 256 x 256 tile of the incoming gradient, in place of
+// storing it (Section 4.1: statistics per virtual node; here a tile's rows are two whole nodes of
+// 128, wavefronts wm = 0, 1 on the first and 2, 3 on the second).  With dr = the gradient where the
+// layer's output was positive, xhat = (z - mean) rstd:
+//   dz = gamma rstd (dr - sum(dr) / 128 - xhat sum(dr xhat) / 128)        (dz = dr without BatchNorm),
+// the sums over the node's rows: four rows per lane, 16 lanes by exchange, the node's two wavefronts
+// through LDS (the lower rows first), one group of 16 columns at a time.  A lane holds four consecutive columns of a row, so dz leaves in
+// 8-byte stores; the transposed copy goes through LDS (per wavefront 128 columns x 64 rows) and
+// leaves in 16-byte stores of eight rows.  LDS: the sums at 0 (8 KB), the transposed tiles behind.
+constexpr int kFuseTPitch = 72;   // bf16 elements per column of a wavefront's transposed tile (64 rows + 8)
+__device__ __forceinline__ void bn_bwd_tile(f32x4 (&acc)[4][8], const BnBwdArgs& fa, bf16_t* lds, int m0, int n0, int N,
+                                            int wave, int lane) {
+  const int wm = wave >> 1, wn = wave & 1;
+  const int lq = lane >> 4, lr = lane & 15;
+  const int node = (m0 + wm * 64) >> 7;
+  const int colw = n0 + wn * 128;                      // the wavefront's first column
+  const int row0 = m0 + wm * 64;                       // ... and first row
+  const bool bn = fa.gamma != nullptr;
+  const bool same = fa.tscale == 1.f;
+  const float invR = 1.0f / 128.0f;
+  float* part = reinterpret_cast<float*>(lds);         // [wave][2][128]
+  bf16_t* tT = lds + 4096 + wave * (128 * kFuseTPitch);
+
+  // every wavefront is done with the operand stages before the sums and tiles overwrite them
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+
+  auto params = [&](int c, f32x4& mean, f32x4& rstd, f32x4& g, f32x4& b) {
+    mean = f32x4{0.f, 0.f, 0.f, 0.f}; rstd = f32x4{1.f, 1.f, 1.f, 1.f};
+    g = f32x4{1.f, 1.f, 1.f, 1.f}; b = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (bn) {
+      mean = *reinterpret_cast<const f32x4*>(&fa.mean[(int64_t)node * N + c]);
+      rstd = *reinterpret_cast<const f32x4*>(&fa.rstd[(int64_t)node * N + c]);
+      g = *reinterpret_cast<const f32x4*>(&fa.gamma[c]);
+      b = *reinterpret_cast<const f32x4*>(&fa.beta[c]);
+      if (fa.round_params)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { g[e] = round_bf16(g[e]); b[e] = round_bf16(b[e]); }
+    }
+  };
+
+  // Column group j (16 columns; 4 per lane) at a time: the layer's pre-activations of group j + 1 are
+  // requested before group j is worked on, so that they are read once and a trip to memory is hidden
+  // behind the group before; mask by the layer's output, sums of this wavefront's 64 rows, exchange
+  // with the node's other wavefront (the lower rows first), dz and the transposed tile.
+  const int w0 = (wm & ~1) * 2 + wn, w1 = w0 + 2;
+  auto load_z = [&](int j, f32x4 (&zz)[4]) {
+    const int c = colw + 16 * j + 4 * lq;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      zz[i] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(&fa.z[(int64_t)(row0 + 16 * i + lr) * fa.ldz + c]));
+  };
+  f32x4 znext[4], mean_n, rstd_n, g_n, b_n;
+  load_z(0, znext);
+  params(colw + 4 * lq, mean_n, rstd_n, g_n, b_n);
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int c = colw + 16 * j + 4 * lq;
+    const int pc = 16 * j + 4 * lq;
+    f32x4 zz[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) zz[i] = znext[i];
+    const f32x4 mean = mean_n, rstd = rstd_n, g = g_n, b = b_n;
+    if (j + 1 < 8) {
+      load_z(j + 1, znext);
+      params(c + 16, mean_n, rstd_n, g_n, b_n);
+    }
+    f32x4 sg = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float xhat = (zz[i][e] - mean[e]) * rstd[e];
+        const float pre = bn ? fmaf(g[e], xhat, b[e]) : zz[i][e];
+        const float dr = pre > 0.f ? acc[i][j][e] : 0.f;
+        acc[i][j][e] = dr;
+        zz[i][e] = xhat;
+        sg[e] = fmaf(dr, xhat, sg[e]);
+        sb[e] += dr;
+      }
+#pragma unroll
+    for (int off = 1; off < 16; off <<= 1)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        sg[e] += __shfl_xor(sg[e], off);
+        sb[e] += __shfl_xor(sb[e], off);
+      }
+    if (lr == 0) {
+      *reinterpret_cast<f32x4*>(&part[(wave * 2 + 0) * 128 + pc]) = sg;
+      *reinterpret_cast<f32x4*>(&part[(wave * 2 + 1) * 128 + pc]) = sb;
+    }
+    __syncthreads();
+    const f32x4 sg0 = *reinterpret_cast<const f32x4*>(&part[(w0 * 2 + 0) * 128 + pc]);
+    const f32x4 sg1 = *reinterpret_cast<const f32x4*>(&part[(w1 * 2 + 0) * 128 + pc]);
+    const f32x4 sb0 = *reinterpret_cast<const f32x4*>(&part[(w0 * 2 + 1) * 128 + pc]);
+    const f32x4 sb1 = *reinterpret_cast<const f32x4*>(&part[(w1 * 2 + 1) * 128 + pc]);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { sg[e] = sg0[e] + sg1[e]; sb[e] = sb0[e] + sb1[e]; }
+    if (!(wm & 1) && lr == 0) {
+      *reinterpret_cast<f32x4*>(&fa.sums[((int64_t)node * 2 + 0) * N + c]) = sg;
+      *reinterpret_cast<f32x4*>(&fa.sums[((int64_t)node * 2 + 1) * N + c]) = sb;
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      float v[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float dr = acc[i][j][e];
+        if (bn) {
+          const float kk = g[e] * rstd[e];
+          v[e] = kk * (dr - sb[e] * invR - zz[i][e] * sg[e] * invR);
+        } else {
+          v[e] = dr;
+        }
+      }
+      uint2 pk;
+      pk.x = f32x2_to_bf16x2(v[0], v[1]);
+      pk.y = f32x2_to_bf16x2(v[2], v[3]);
+      *reinterpret_cast<uint2*>(&fa.dz[(int64_t)(row0 + 16 * i + lr) * fa.lddz + c]) = pk;
+      uint2 pt = pk;                      // the transposed copy's values: the same where the scale is 1
+      if (!same) { pt.x = f32x2_to_bf16x2(v[0] * fa.tscale, v[1] * fa.tscale); pt.y = f32x2_to_bf16x2(v[2] * fa.tscale, v[3] * fa.tscale); }
+      bf16_t* tp = &tT[pc * kFuseTPitch + 16 * i + lr];
+      tp[0] = (bf16_t)pt.x; tp[kFuseTPitch] = (bf16_t)(pt.x >> 16);
+      tp[2 * kFuseTPitch] = (bf16_t)pt.y; tp[3 * kFuseTPitch] = (bf16_t)(pt.y >> 16);
+    }
+  }
+  __syncthreads();
+  // the wavefront's transposed tile: 8 columns per instruction, 8 lanes x 8 rows each
+#pragma unroll
+  for (int it = 0; it < 16; ++it) {
+    const int col = it * 8 + (lane >> 3), seg = lane & 7;
+    const u32x4 v = *reinterpret_cast<const u32x4*>(&tT[col * kFuseTPitch + seg * 8]);
+    __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(&fa.dzT[(int64_t)(colw + col) * fa.ldt + row0 + seg * 8]));
+  }
+}
+
+// FUSE: the tile is finished by bn_bwd_tile instead of being stored (whole tiles only: M and N are
+// multiples of 256, one slice).
+template <bool FUSE>
 __global__ __launch_bounds__(512) void gemm_bf16_wide_line16_kernel(const bf16_t* __restrict__ A, int64_t lda,
                                                                     const bf16_t* __restrict__ B, int64_t ldb,
                                                                     int M, int N, int K, int kchunk,
                                                                     int64_t slab_stride, Epilogue ep, int tiles_m,
-                                                                    int tiles_n) {
+                                                                    int tiles_n, BnBwdArgs fa) {
   constexpr int BM = 256, BN = 256, KS = 64;
   constexpr int AUNIT = BM * KS, BUNIT = (BN / 2) * KS;      // elements: 32 KB, 16 KB
   constexpr int A0 = 0, BF0 = 3 * AUNIT, BS0 = BF0 + 2 * BUNIT;
@@ -1181,6 +1321,10 @@ __global__ __launch_bounds__(512) void gemm_bf16_wide_line16_kernel(const bf16_t
     wait_loads_but<0>();
   }
 
+  if constexpr (FUSE) {
+    bn_bwd_tile(acc, fa, lds_wide, m0, n0, N, wave, lane);
+    return;
+  }
   char* cbase = static_cast<char*>(ep.C) + (int64_t)blockIdx.z * slab_stride * (ep.c_is_bf16 ? 2 : 4);
   auto store_row = [&](auto ic) {
     constexpr int i = decltype(ic)::value;
@@ -1730,7 +1874,9 @@ int launch_wide_line(const Shape& g, const Epilogue& ep, hipStream_t s) {
   if (!ready) {
     VF_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_wide_line_kernel),
                                hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
-    VF_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_wide_line16_kernel),
+    VF_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_wide_line16_kernel<false>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
+    VF_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_wide_line16_kernel<true>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
     ready = true;
   }
@@ -1746,8 +1892,8 @@ int launch_wide_line(const Shape& g, const Epilogue& ep, hipStream_t s) {
     gemm_bf16_wide_line_kernel<<<grid, 512, bytes, s>>>(g.A, g.lda, g.B, g.ldb, g.M, g.N, g.K, kchunk, g.slab, epx, tiles_m,
                                                         tiles_n);
   else
-    gemm_bf16_wide_line16_kernel<<<grid, 512, bytes, s>>>(g.A, g.lda, g.B, g.ldb, g.M, g.N, g.K, kchunk, g.slab, epx,
-                                                          tiles_m, tiles_n);
+    gemm_bf16_wide_line16_kernel<false><<<grid, 512, bytes, s>>>(g.A, g.lda, g.B, g.ldb, g.M, g.N, g.K, kchunk, g.slab, epx,
+                                                                 tiles_m, tiles_n, BnBwdArgs{});
   VF_LAUNCH_CHECK();
   return VF_OK;
 }
@@ -1765,6 +1911,40 @@ int launch_wide(const Shape& g, const Epilogue& ep, hipStream_t s) {
   return launch_wide_cfg<128, 64, 3>(g, ep, s);
 }
 }  // namespace
+
+// The product with the BatchNorm backward pass in its epilogue (see bn_bwd_tile): shapes that the
+// 256 x 256 kernel on the 16x16x32 MFMA takes in whole tiles.  VF_BN_FUSE = 0 switches it off.
+bool gemm_bf16_bn_bwd_takes(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, int M, int N, int K,
+                            const BnBwdArgs& fa) {
+  static const bool enabled = !(std::getenv("VF_BN_FUSE") && std::atoi(std::getenv("VF_BN_FUSE")) == 0);
+  if (!enabled || M <= 0 || N <= 0 || K <= 0 || !A || !B || !fa.z || !fa.dz || !fa.dzT || !fa.sums) return false;
+  if ((fa.gamma == nullptr) != (fa.beta == nullptr) || (fa.gamma && (!fa.mean || !fa.rstd))) return false;
+  auto al = [](const void* p, uintptr_t n) { return (reinterpret_cast<uintptr_t>(p) & (n - 1)) == 0; };
+  const bool spans32 = (int64_t)M * lda * 2 < ((int64_t)1 << 31) && (int64_t)N * ldb * 2 < ((int64_t)1 << 31);
+  return (M % 256) == 0 && (N % 256) == 0 && (K % 64) == 0 && spans32 && wide_fits(M, N, K, 1) &&
+         wide_tile_n(M, N) == 256 && wide_variant() == 0 && !(lda & 7) && !(ldb & 7) && al(A, 16) && al(B, 16) &&
+         !(fa.ldz & 3) && !(fa.lddz & 3) && !(fa.ldt & 7) && al(fa.z, 16) && al(fa.dz, 8) && al(fa.dzT, 16) &&
+         al(fa.sums, 16) && al(fa.mean, 16) && al(fa.rstd, 16) && al(fa.gamma, 16) && al(fa.beta, 16);
+}
+
+int launch_gemm_bf16_bn_bwd(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, int M, int N, int K,
+                            const BnBwdArgs& fa, hipStream_t s) {
+  if (!gemm_bf16_bn_bwd_takes(A, lda, B, ldb, M, N, K, fa)) return VF_EINVAL;
+  constexpr int bytes = 160 * 1024;
+  static bool ready = false;
+  if (!ready) {
+    VF_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_wide_line16_kernel<true>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
+    ready = true;
+  }
+  const int tiles_m = M / 256, tiles_n = N / 256;
+  const int ntile = tiles_m * tiles_n;
+  dim3 grid(((ntile + 7) / 8) * 8, 1, 1);
+  gemm_bf16_wide_line16_kernel<true><<<grid, 512, bytes, s>>>(A, lda, B, ldb, M, N, K, K, 0, Epilogue{}, tiles_m, tiles_n, fa);
+  VF_LAUNCH_CHECK();
+  return VF_OK;
+}
+
 
 int launch_gemm_bf16(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, int M, int N,
                      int K, int nsplit, int64_t slab_stride, const Epilogue& ep, hipStream_t s) {

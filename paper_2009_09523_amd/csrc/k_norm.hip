@@ -781,6 +781,33 @@ __global__ __launch_bounds__((GroupShape<G, SGP>::THREADS)) void bn_relu_bwd_pai
   }
 }
 
+// Scale / shift (or bias) gradients from per-node column sums [nodes][2][C] (left by a product whose
+// epilogue took the BatchNorm backward pass): added up in node order and folded in once, as the
+// group kernels do.
+__global__ __launch_bounds__(256) void bn_sums_finish_kernel(const float* __restrict__ sums, int nodes, int C,
+                                                             GradOut gout_g, GradOut gout_b) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= C) return;
+  float tg = 0.f, tb = 0.f;
+  for (int n0 = 0; n0 < nodes; n0 += 16) {         // sixteen nodes' loads in flight together
+    float sg[16], sb[16];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+      const int n = min(n0 + k, nodes - 1);
+      sg[k] = sums[((int64_t)n * 2 + 0) * C + c];
+      sb[k] = sums[((int64_t)n * 2 + 1) * C + c];
+    }
+#pragma unroll
+    for (int k = 0; k < 16; ++k)
+      if (n0 + k < nodes) {
+        tg = (n0 + k) ? tg + sg[k] : sg[k];
+        tb = (n0 + k) ? tb + sb[k] : sb[k];
+      }
+  }
+  if (gout_g.dst) grad_store(gout_g, c, tg);
+  if (gout_b.dst) grad_store(gout_b, c, tb);
+}
+
 constexpr int SCB = 32, SRL = 8;
 template <typename T>
 __global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ x, int64_t ld, int R, int C,
@@ -1017,6 +1044,13 @@ int launch_bn_relu_bwd(float* dap, int nsplit, int64_t slab, int64_t ldda, const
 #undef VF_BWDG
 #undef VF_BWDG1
 #undef VF_BWD2
+  VF_LAUNCH_CHECK();
+  return VF_OK;
+}
+
+int launch_bn_sums_finish(const float* sums, int nodes, int C, GradOut gout_g, GradOut gout_b, hipStream_t s) {
+  if (!sums || nodes < 1 || C <= 0) return VF_EINVAL;
+  bn_sums_finish_kernel<<<(C + 255) / 256, 256, 0, s>>>(sums, nodes, C, gout_g, gout_b);
   VF_LAUNCH_CHECK();
   return VF_OK;
 }

@@ -65,6 +65,26 @@ struct Epilogue {
   int stream_c = 0;              // store C with the non-temporal hint (it is not kept in the L2s)
 };
 
+// BatchNorm + ReLU backward of whole nodes of 128 rows, taken inside the epilogue of the product that
+// computes the incoming gradient (launch_gemm_bf16_bn_bwd): the layer's stored pre-activations and
+// per-node statistics in, the bf16 gradient at the pre-activation and its transposed copy out, and
+// per node the two column sums that the scale / shift (or bias) gradients are made of.
+struct BnBwdArgs {
+  const float* z = nullptr;      // pre-activations [M, N], fp32
+  int64_t ldz = 0;
+  const float* mean = nullptr;   // [nodes, N] (unused without BatchNorm)
+  const float* rstd = nullptr;
+  const float* gamma = nullptr;  // [N], or null: ReLU only
+  const float* beta = nullptr;
+  int round_params = 0;          // gamma, beta rounded to bf16 first
+  bf16_t* dz = nullptr;          // [M, N]
+  int64_t lddz = 0;
+  bf16_t* dzT = nullptr;         // [N, ldt]: column = row of the unit, values times tscale
+  int64_t ldt = 0;
+  float tscale = 1.f;
+  float* sums = nullptr;         // [nodes][2][N]: sum over the node's rows of dr * xhat, and of dr
+};
+
 // ---------------------------------------------------------------------------------------
 // kernel launchers (each returns VF_OK or VF_EDEVICE/VF_EINVAL); all asynchronous
 // ---------------------------------------------------------------------------------------
@@ -90,6 +110,16 @@ int gemm_f32_pick_split(int M, int N, int K);
 // slabs in order).  With nsplit > 1 the epilogue may not add R; the bias goes to slab 0.
 int launch_gemm_bf16(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, int M, int N,
                      int K, int nsplit, int64_t slab_stride, const Epilogue& ep, hipStream_t s);
+// The product A B^T [M, N] (no bias, no addend, unsliced) followed, tile by tile inside the kernel, by
+// the BatchNorm + ReLU backward pass of the layer it arrives at; every node has 128 rows.
+// gemm_bf16_bn_bwd_takes: whether the fused kernel takes these operands (whole 256 x 256 tiles, enough
+// of them, alignments); the launch returns VF_EINVAL otherwise.
+bool gemm_bf16_bn_bwd_takes(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, int M, int N, int K,
+                            const BnBwdArgs& fa);
+int launch_gemm_bf16_bn_bwd(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, int M, int N, int K,
+                            const BnBwdArgs& fa, hipStream_t s);
+// Scale / shift (or bias) gradients from the per-node column sums, added up in node order.
+int launch_bn_sums_finish(const float* sums, int nodes, int C, GradOut gout_g, GradOut gout_b, hipStream_t s);
 // Number of slices that fills the chip for this shape (1 when the tile grid already does).
 int gemm_bf16_pick_split(int M, int N, int K);
 

@@ -283,13 +283,35 @@ class Mlp final : public Model {
       const int64_t slab = (int64_t)b * Pv.ld;
       Epilogue ed;
       ed.C = slab_buf; ed.ldc = Pv.ld;
+      GradOut gg = Pv.has_bn ? c.gout(Pv.g_off, w, i) : GradOut{nullptr, 0.f, 0};
+      GradOut gb = c.gout(Pv.has_bn ? Pv.be_off : Pv.b_off, w, i);
+      // A unit of whole nodes of 128 rows on a wide layer: the product's epilogue takes the BatchNorm /
+      // ReLU backward pass itself (the incoming gradient is never stored); the scratch holds the
+      // per-node column sums for the small launch that makes the scale / shift gradients of them.
+      bool whole = bf16_ && split == 1 && s.group(i) >= 2 && b == 128 * s.group(i);
+      for (int n = 0; n < s.group(i) && whole; ++n) whole = s.rows_of(i)[n] == 128;
+      if (whole) {
+        BnBwdArgs fa;
+        fa.z = Pv.z[q]; fa.ldz = Pv.ld;
+        fa.mean = Pv.mean[q]; fa.rstd = Pv.rstd[q];
+        fa.gamma = Pv.has_bn ? P + Pv.g_off : nullptr; fa.beta = Pv.has_bn ? P + Pv.be_off : nullptr;
+        fa.round_params = bf16_;
+        fa.dz = static_cast<bf16_t*>(Pv.dz[0]); fa.lddz = Pv.ld;
+        fa.dzT = Pv.dzT + pc; fa.ldt = ldw_;
+        fa.tscale = tscale(c, s, i);
+        fa.sums = slab_buf;
+        if (gemm_bf16_bn_bwd_takes(static_cast<const bf16_t*>(dz_in), L.ld, L.wnat, L.ldn, b, L.K, kdim(L), fa)) {
+          VF_KS(c, st, "gemm_dgrad", launch_gemm_bf16_bn_bwd(static_cast<const bf16_t*>(dz_in), L.ld, L.wnat, L.ldn, b, L.K,
+                                                             kdim(L), fa, st));
+          VF_KS(c, st, "bn_relu_bwd", launch_bn_sums_finish(slab_buf, s.group(i), Pv.N, gg, gb, st));
+          continue;
+        }
+      }
       if (bf16_)
         VF_KS(c, st, "gemm_dgrad", launch_gemm_bf16(static_cast<const bf16_t*>(dz_in), L.ld, L.wnat, L.ldn, b, L.K, kdim(L),
                                                     split, slab, ed, st));
       else
         VF_KS(c, st, "gemm_dgrad", launch_gemm_f32(static_cast<const float*>(dz_in), L.ld, 1, P + L.w_off, L.N, 1, b, L.K, L.N, split, slab, ed, st));
-      GradOut gg = Pv.has_bn ? c.gout(Pv.g_off, w, i) : GradOut{nullptr, 0.f, 0};
-      GradOut gb = c.gout(Pv.has_bn ? Pv.be_off : Pv.b_off, w, i);
       VF_KS(c, st, "bn_relu_bwd", launch_bn_relu_bwd(slab_buf, split, slab, Pv.ld, Pv.z[q], Pv.ld, s.seg[i], Pv.N,
                                      Pv.has_bn ? P + Pv.g_off : nullptr, Pv.has_bn ? P + Pv.be_off : nullptr,
                                      bf16_, Pv.mean[q], Pv.rstd[q], Pv.dz[0], Pv.ld, bf16_, bf16_ ? Pv.dzT + pc : nullptr, ldw_,
