@@ -1039,6 +1039,21 @@ __device__ __forceinline__ void store_tiles16_row(const f32x4 (&acc)[8], const E
 // through LDS (the lower rows first), one group of 16 columns at a time.  A lane holds four consecutive columns of a row, so dz leaves in
 // 8-byte stores; the transposed copy goes through LDS (per wavefront 128 columns x 64 rows) and
 // leaves in 16-byte stores of eight rows.  LDS: the sums at 0 (8 KB), the transposed tiles behind.
+// Sum over the 16 lanes of a row (lanes 16 k .. 16 k + 15), to all of them, by data-parallel-primitive
+// moves: neighbours, pairs, the quad's mirror image in its half row, the half row's in the row.  Both
+// partners of an exchange add the same two values, so every lane ends with the same bits.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float row16_sum(float v) {
+  v += dpp_move<0xB1>(v);    // quad_perm [1, 0, 3, 2]
+  v += dpp_move<0x4E>(v);    // quad_perm [2, 3, 0, 1]
+  v += dpp_move<0x141>(v);   // row_half_mirror
+  v += dpp_move<0x140>(v);   // row_mirror
+  return v;
+}
+
 constexpr int kFuseTPitch = 72;   // bf16 elements per column of a wavefront's transposed tile (64 rows + 8)
 __device__ __forceinline__ void bn_bwd_tile(f32x4 (&acc)[4][8], const BnBwdArgs& fa, bf16_t* lds, int m0, int n0, int N,
                                             int wave, int lane) {
@@ -1112,12 +1127,7 @@ __device__ __forceinline__ void bn_bwd_tile(f32x4 (&acc)[4][8], const BnBwdArgs&
         sb[e] += dr;
       }
 #pragma unroll
-    for (int off = 1; off < 16; off <<= 1)
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        sg[e] += __shfl_xor(sg[e], off);
-        sb[e] += __shfl_xor(sb[e], off);
-      }
+    for (int e = 0; e < 4; ++e) { sg[e] = row16_sum(sg[e]); sb[e] = row16_sum(sb[e]); }
     if (lr == 0) {
       *reinterpret_cast<f32x4*>(&part[(wave * 2 + 0) * 128 + pc]) = sg;
       *reinterpret_cast<f32x4*>(&part[(wave * 2 + 1) * 128 + pc]) = sb;

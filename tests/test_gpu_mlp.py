@@ -463,6 +463,33 @@ def test_units_of_more_than_eight_nodes_match_the_oracle(name, sizes, group):
     assert np.linalg.norm(gpu["G"] - plain["G"]) <= 2e-2 * np.linalg.norm(plain["G"])
 
 
+@pytest.mark.parametrize("name", ["mlp_wide_bn_bf16", "mlp_wide_bf16"])
+def test_wide_units_of_whole_nodes_match_the_oracle(name):
+    """Sixteen nodes of 128 rows on layers of 8192 columns, as one unit: the input-gradient products run
+    on the 256 x 256 tiles with the BatchNorm / ReLU backward pass in their epilogue (two whole nodes
+    per tile; with and without BatchNorm), the forward pass on the two-column BatchNorm kernel.  The
+    oracle's node-by-node result, per-node losses, and the same bits from every launch mode; with the
+    last node cut in two (units of unequal nodes: the separate backward kernel) the oracle again."""
+    wl = I.workload(name)
+    theta = I.make_params(wl, jitter=0.1)
+    x, y = I.make_batch(wl)
+    print(f"wide units {name}", flush=True)
+    ref = oracle_steps(wl, theta, x, y)
+    base = None
+    for flags in (FUSED | NO_GRAPH | OVERLAP, FUSED, 0):
+        gpu = run_gpu(wl, theta, x, y, flags=flags, node_group=16)
+        check_against_oracle(wl, gpu, ref)
+        np.testing.assert_allclose(gpu["node_losses"], ref["node_losses"], rtol=1e-3)
+        if base is None:
+            base = gpu
+        assert gpu["G"].tobytes() == base["G"].tobytes(), flags
+        assert gpu["theta"].tobytes() == base["theta"].tobytes(), flags
+    sizes = [128] * 15 + [64, 64]
+    ref = oracle_steps(wl, theta, x, y, node_sizes=sizes)
+    gpu = run_gpu(wl, theta, x, y, node_sizes=sizes, flags=FUSED | NO_GRAPH | OVERLAP, node_group=32)
+    check_against_oracle(wl, gpu, ref)
+
+
 def test_node_groups_keep_the_workspace_independent_of_the_node_count():
     wl, theta, x, y = _case("mlp_mid_bn_bf16")
     few = run_gpu(wl, theta, x[:80], y[:80], node_sizes=[40, 40], flags=FUSED, node_group=4, max_node_size=40,

@@ -120,6 +120,10 @@ WORKLOADS: Dict[str, Workload] = {
                             [48, 16, 128, 40, 8], "bf16"),
     "mlp_mid_bf16": _mlp("mlp_mid_bf16", [256, 520, 392, 1000], False,
                          [48, 16, 128, 40, 8], "bf16"),
+    # layers wide enough for the 256 x 256 product tiles in one round per unit of sixteen 128-row nodes
+    # (the input-gradient products whose epilogue takes the BatchNorm / ReLU backward pass)
+    "mlp_wide_bn_bf16": _mlp("mlp_wide_bn_bf16", [64, 8192, 8192, 16], True, [128] * 16, "bf16"),
+    "mlp_wide_bf16": _mlp("mlp_wide_bf16", [64, 8192, 8192, 16], False, [128] * 16, "bf16"),
     "mlp_big_node_bf16": _mlp("mlp_big_node_bf16", [256, 520, 392, 100], True,
                               [300, 212], "bf16"),
     "enc_tiny_f32": _enc("enc_tiny_f32", 2, 64, 2, 136, 16, 211, [3, 1, 2], "f32",
