@@ -490,14 +490,29 @@ def bench_workload(name, args, primary):
                        "ms_per_step": v["total_ms"] / steps,
                        "share": v["total_ms"] / tot} for k, v in prof.items()}
         out["kernels"] = kernels
+        units = pass_units(wl, args.node_group)
+        if wl.kind == "mlp" and "gemm_dgrad_bn" in kernels and "gemm_dgrad" not in kernels:
+            # every input-gradient product took the BatchNorm / ReLU backward pass in its epilogue: the
+            # product's flops; weights and incoming gradient in (bf16), the layer's pre-activations in
+            # (fp32), the gradient at the pre-activation and its transposed copy out (bf16)
+            esz = 2
+            mats = [(wl.dims[i], wl.dims[i + 1]) for i in range(len(wl.dims) - 1)]
+            fused_bytes = units * sum(k * n for k, n in mats[1:]) * esz + sum(
+                b * (n * esz + k * 4 + 2 * k * esz) for b in wl.node_sizes for k, n in mats[1:])
+            work["gemm_dgrad_bn"] = (fused_bytes, work["gemm_dgrad"][1], work["gemm_dgrad"][2])
         dom = max((k for k in kernels if k in work), key=lambda k: kernels[k]["ms_per_step"])
         out["roofline"] = roofline_for(dom, work, kernels[dom]["avg_launch_ms"])
         out["roofline"]["traffic"] = measured_traffic(wl.name, args.accumulate, dom)
-        units = pass_units(wl, args.node_group)
         if units != wl.n_nodes:
             out["roofline"]["note"] = (
                 f"a launch takes a unit of {wl.n_nodes // units} nodes and reads the weights once: bytes and flops "
                 "are those of the launch as made (node by node, the same weights would be streamed once per node)")
+        if dom == "gemm_dgrad_bn":
+            out["roofline"]["note"] = out["roofline"].get("note", "") + (
+                "; gemm_dgrad_bn is the input-gradient product WITH the BatchNorm / ReLU backward pass of the layer it "
+                "arrives at in its epilogue (the layer's fp32 pre-activations read, the bf16 gradient and its transposed "
+                "copy written; no kernel of its own for that pass): its duration holds both, its flops are the "
+                "product's alone.  The pure products are gemm_fwd and gemm_wgrad in roofline_all")
         out["roofline_all"] = {k: {kk: vv for kk, vv in roofline_for(k, work, kernels[k]["avg_launch_ms"]).items()
                                    if kk in ("bound", "achieved", "peak", "unit", "frac", "mfma_tflops", "mfma_frac")}
                                for k in kernels if k in work}

@@ -1096,8 +1096,9 @@ __device__ __forceinline__ void bn_bwd_tile(f32x4 (&acc)[4][8], const BnBwdArgs&
     const int c = colw + 16 * j + 4 * lq;
 #pragma unroll
     for (int i = 0; i < 4; ++i)
-      zz[i] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(&fa.z[(int64_t)(row0 + 16 * i + lr) * fa.ldz + c]));
-  };
+      zz[i] = *reinterpret_cast<const f32x4*>(&fa.z[(int64_t)(row0 + 16 * i + lr) * fa.ldz + c]);   // (half a line: the
+  };                                                     // next group asks for the other half, so no streaming hint)
+  uint2 held[4][4];
   f32x4 znext[4], mean_n, rstd_n, g_n, b_n;
   load_z(0, znext);
   params(colw + 4 * lq, mean_n, rstd_n, g_n, b_n);
@@ -1159,12 +1160,22 @@ __device__ __forceinline__ void bn_bwd_tile(f32x4 (&acc)[4][8], const BnBwdArgs&
       uint2 pk;
       pk.x = f32x2_to_bf16x2(v[0], v[1]);
       pk.y = f32x2_to_bf16x2(v[2], v[3]);
-      *reinterpret_cast<uint2*>(&fa.dz[(int64_t)(row0 + 16 * i + lr) * fa.lddz + c]) = pk;
+      held[j & 3][i] = pk;
       uint2 pt = pk;                      // the transposed copy's values: the same where the scale is 1
       if (!same) { pt.x = f32x2_to_bf16x2(v[0] * fa.tscale, v[1] * fa.tscale); pt.y = f32x2_to_bf16x2(v[2] * fa.tscale, v[3] * fa.tscale); }
       bf16_t* tp = &tT[pc * kFuseTPitch + 16 * i + lr];
       tp[0] = (bf16_t)pt.x; tp[kFuseTPitch] = (bf16_t)(pt.x >> 16);
       tp[2 * kFuseTPitch] = (bf16_t)pt.y; tp[3 * kFuseTPitch] = (bf16_t)(pt.y >> 16);
+    }
+    // dz leaves four groups at a time, the four 32-byte parts of a row's 128-byte line one behind the
+    // other (stored group by group as they are finished, a line's parts reached the memory apart:
+    // 1.3 times the bytes written by the counters)
+    if ((j & 3) == 3) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj)
+          *reinterpret_cast<uint2*>(&fa.dz[(int64_t)(row0 + 16 * i + lr) * fa.lddz + colw + 16 * (j - 3 + jj) + 4 * lq]) = held[jj][i];
     }
   }
   __syncthreads();

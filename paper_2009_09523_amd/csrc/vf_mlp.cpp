@@ -301,9 +301,9 @@ class Mlp final : public Model {
         fa.tscale = tscale(c, s, i);
         fa.sums = slab_buf;
         if (gemm_bf16_bn_bwd_takes(static_cast<const bf16_t*>(dz_in), L.ld, L.wnat, L.ldn, b, L.K, kdim(L), fa)) {
-          VF_KS(c, st, "gemm_dgrad", launch_gemm_bf16_bn_bwd(static_cast<const bf16_t*>(dz_in), L.ld, L.wnat, L.ldn, b, L.K,
+          VF_KS(c, st, "gemm_dgrad_bn", launch_gemm_bf16_bn_bwd(static_cast<const bf16_t*>(dz_in), L.ld, L.wnat, L.ldn, b, L.K,
                                                              kdim(L), fa, st));
-          VF_KS(c, st, "bn_relu_bwd", launch_bn_sums_finish(slab_buf, s.group(i), Pv.N, gg, gb, st));
+          VF_KS(c, st, "bn_sums_finish", launch_bn_sums_finish(slab_buf, s.group(i), Pv.N, gg, gb, st));
           continue;
         }
       }
