@@ -500,6 +500,18 @@ def bench_workload(name, args, primary):
             fused_bytes = units * sum(k * n for k, n in mats[1:]) * esz + sum(
                 b * (n * esz + k * 4 + 2 * k * esz) for b in wl.node_sizes for k, n in mats[1:])
             work["gemm_dgrad_bn"] = (fused_bytes, work["gemm_dgrad"][1], work["gemm_dgrad"][2])
+        if wl.kind == "mlp" and "gemm_fwd_bn" in kernels and kernels["gemm_fwd_bn"]["launches_per_step"] == units * (len(wl.dims) - 2):
+            # every hidden layer's forward product took BatchNorm + ReLU in its epilogue: weights and input in
+            # (bf16), pre-activations out (fp32), activation and its transposed copy out (bf16); gemm_fwd is
+            # then the last layer's product alone
+            esz = 2
+            mats = [(wl.dims[i], wl.dims[i + 1]) for i in range(len(wl.dims) - 1)]
+            hid, last = mats[:-1], mats[-1:]
+            hb = units * sum(k * n for k, n in hid) * esz + sum(
+                b * (k * esz + n * 4 + 2 * n * esz) for b in wl.node_sizes for k, n in hid)
+            work["gemm_fwd_bn"] = (hb, 2 * wl.batch * sum(k * n for k, n in hid), units * len(hid))
+            lb = units * sum(k * n for k, n in last) * esz + sum(b * (k * esz + n * 4) for b in wl.node_sizes for k, n in last)
+            work["gemm_fwd"] = (lb, 2 * wl.batch * sum(k * n for k, n in last), units)
         dom = max((k for k in kernels if k in work), key=lambda k: kernels[k]["ms_per_step"])
         out["roofline"] = roofline_for(dom, work, kernels[dom]["avg_launch_ms"])
         out["roofline"]["traffic"] = measured_traffic(wl.name, args.accumulate, dom)
@@ -507,12 +519,18 @@ def bench_workload(name, args, primary):
             out["roofline"]["note"] = (
                 f"a launch takes a unit of {wl.n_nodes // units} nodes and reads the weights once: bytes and flops "
                 "are those of the launch as made (node by node, the same weights would be streamed once per node)")
+        if dom == "gemm_fwd_bn":
+            out["roofline"]["note"] = out["roofline"].get("note", "") + (
+                "; gemm_fwd_bn is a hidden layer's forward product WITH BatchNorm + ReLU in its epilogue (pre-activations, "
+                "activation and its transposed copy written, statistics per node; no kernel of its own for that pass): its "
+                "duration holds both, its flops are the product's alone.  The pure products are gemm_wgrad (and the last "
+                "layer's gemm_fwd) in roofline_all")
         if dom == "gemm_dgrad_bn":
             out["roofline"]["note"] = out["roofline"].get("note", "") + (
                 "; gemm_dgrad_bn is the input-gradient product WITH the BatchNorm / ReLU backward pass of the layer it "
                 "arrives at in its epilogue (the layer's fp32 pre-activations read, the bf16 gradient and its transposed "
                 "copy written; no kernel of its own for that pass): its duration holds both, its flops are the "
-                "product's alone.  The pure products are gemm_fwd and gemm_wgrad in roofline_all")
+                "product's alone.  The pure products are gemm_wgrad (and gemm_fwd where present) in roofline_all")
         out["roofline_all"] = {k: {kk: vv for kk, vv in roofline_for(k, work, kernels[k]["avg_launch_ms"]).items()
                                    if kk in ("bound", "achieved", "peak", "unit", "frac", "mfma_tflops", "mfma_frac")}
                                for k in kernels if k in work}

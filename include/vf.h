@@ -64,6 +64,7 @@
  *                          (default: for layers of at least 6144 columns)
  *     VF_BN_FUSE=0         the BatchNorm backward pass as a kernel of its own also where the input-gradient
  *                          product's epilogue would take it (units of whole 128-row nodes on wide layers)
+ *     VF_BN_FUSE_FWD=0     the same for the forward pass
  *     VF_FLAT_NT=0|1       accumulate and optimizer kernels with non-temporal accesses: never | always
  *                          (default: for vectors of 64 MB and more)
  */

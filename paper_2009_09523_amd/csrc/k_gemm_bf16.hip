@@ -1188,14 +1188,140 @@ __device__ __forceinline__ void bn_bwd_tile(f32x4 (&acc)[4][8], const BnBwdArgs&
   }
 }
 
-// FUSE: the tile is finished by bn_bwd_tile instead of being stored (whole tiles only: M and N are
+// BatchNorm + ReLU forward of a finished 256 x 256 tile of pre-activations (two whole nodes of 128
+// rows, as in bn_bwd_tile): per group of 16 columns the node's mean (sum over its rows), then the
+// sum of squared deviations from it, each exchanged between the node's two wavefronts through LDS
+// (slots 0 and 1 of the sums), then a = max(gamma (z - mean) rstd + beta, 0) -- without BatchNorm
+// a = max(z, 0), z including the layer's bias.  z is stored two groups at a time (a row's 128-byte
+// line), a four groups at a time, the transposed copy through LDS.
+__device__ __forceinline__ void bn_fwd_tile(f32x4 (&acc)[4][8], const BnFwdArgs& fa, bf16_t* lds, int m0, int n0, int N,
+                                            int wave, int lane) {
+  const int wm = wave >> 1, wn = wave & 1;
+  const int lq = lane >> 4, lr = lane & 15;
+  const int node = (m0 + wm * 64) >> 7;
+  const int colw = n0 + wn * 128;
+  const int row0 = m0 + wm * 64;
+  const bool bn = fa.gamma != nullptr;
+  const float invR = 1.0f / 128.0f;
+  float* part = reinterpret_cast<float*>(lds);         // [wave][2][128]
+  bf16_t* tT = lds + 4096 + wave * (128 * kFuseTPitch);
+  const int w0 = (wm & ~1) * 2 + wn, w1 = w0 + 2;
+
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+
+  uint2 held[4][4];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int c = colw + 16 * j + 4 * lq;
+    const int pc = 16 * j + 4 * lq;
+    f32x4 g = {1.f, 1.f, 1.f, 1.f}, b = {0.f, 0.f, 0.f, 0.f};
+    if (bn) {
+      g = *reinterpret_cast<const f32x4*>(&fa.gamma[c]);
+      b = *reinterpret_cast<const f32x4*>(&fa.beta[c]);
+      if (fa.round_params)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { g[e] = round_bf16(g[e]); b[e] = round_bf16(b[e]); }
+    } else if (fa.bias) {
+      f32x4 bias = *reinterpret_cast<const f32x4*>(&fa.bias[c]);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float bb = fa.round_params ? round_bf16(bias[e]) : bias[e];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[i][j][e] = fmaf(1.f, acc[i][j][e], bb);   // (the product epilogue's own form)
+      }
+    }
+    f32x4 mean = {0.f, 0.f, 0.f, 0.f}, rstd = {1.f, 1.f, 1.f, 1.f};
+    if (bn) {
+      f32x4 s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) s[e] += acc[i][j][e];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) s[e] = row16_sum(s[e]);
+      if (lr == 0) *reinterpret_cast<f32x4*>(&part[(wave * 2 + 0) * 128 + pc]) = s;
+      __syncthreads();
+      {
+        const f32x4 s0 = *reinterpret_cast<const f32x4*>(&part[(w0 * 2 + 0) * 128 + pc]);
+        const f32x4 s1 = *reinterpret_cast<const f32x4*>(&part[(w1 * 2 + 0) * 128 + pc]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) mean[e] = (s0[e] + s1[e]) * invR;
+      }
+      f32x4 q = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float d = acc[i][j][e] - mean[e];
+          q[e] = fmaf(d, d, q[e]);
+        }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) q[e] = row16_sum(q[e]);
+      if (lr == 0) *reinterpret_cast<f32x4*>(&part[(wave * 2 + 1) * 128 + pc]) = q;
+      __syncthreads();
+      f32x4 var;
+      {
+        const f32x4 q0 = *reinterpret_cast<const f32x4*>(&part[(w0 * 2 + 1) * 128 + pc]);
+        const f32x4 q1 = *reinterpret_cast<const f32x4*>(&part[(w1 * 2 + 1) * 128 + pc]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { var[e] = (q0[e] + q1[e]) * invR; rstd[e] = 1.0f / sqrtf(var[e] + fa.eps); }
+      }
+      if (!(wm & 1) && lr == 0) {
+        *reinterpret_cast<f32x4*>(&fa.mean[(int64_t)node * N + c]) = mean;
+        *reinterpret_cast<f32x4*>(&fa.rstd[(int64_t)node * N + c]) = rstd;
+        *reinterpret_cast<f32x4*>(&fa.var[(int64_t)node * N + c]) = var;
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      float v[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float zz = acc[i][j][e];
+        v[e] = bn ? fmaxf(fmaf(g[e], (zz - mean[e]) * rstd[e], b[e]), 0.f) : fmaxf(zz, 0.f);
+      }
+      uint2 pk;
+      pk.x = f32x2_to_bf16x2(v[0], v[1]);
+      pk.y = f32x2_to_bf16x2(v[2], v[3]);
+      held[j & 3][i] = pk;
+      bf16_t* tp = &tT[pc * kFuseTPitch + 16 * i + lr];
+      tp[0] = (bf16_t)pk.x; tp[kFuseTPitch] = (bf16_t)(pk.x >> 16);
+      tp[2 * kFuseTPitch] = (bf16_t)pk.y; tp[3 * kFuseTPitch] = (bf16_t)(pk.y >> 16);
+    }
+    if (j & 1) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj)
+          *reinterpret_cast<f32x4*>(&fa.z[(int64_t)(row0 + 16 * i + lr) * fa.ldz + colw + 16 * (j - 1 + jj) + 4 * lq]) = acc[i][j - 1 + jj];
+    }
+    if ((j & 3) == 3) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj)
+          *reinterpret_cast<uint2*>(&fa.a[(int64_t)(row0 + 16 * i + lr) * fa.lda + colw + 16 * (j - 3 + jj) + 4 * lq]) = held[jj][i];
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int it = 0; it < 16; ++it) {
+    const int col = it * 8 + (lane >> 3), seg = lane & 7;
+    const u32x4 v = *reinterpret_cast<const u32x4*>(&tT[col * kFuseTPitch + seg * 8]);
+    __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(&fa.aT[(int64_t)(colw + col) * fa.ldt + row0 + seg * 8]));
+  }
+}
+
+// FUSE = 1: the tile is finished by bn_bwd_tile instead of being stored, FUSE = 2: by bn_fwd_tile (whole tiles only: M and N are
 // multiples of 256, one slice).
-template <bool FUSE>
+template <int FUSE>
 __global__ __launch_bounds__(512) void gemm_bf16_wide_line16_kernel(const bf16_t* __restrict__ A, int64_t lda,
                                                                     const bf16_t* __restrict__ B, int64_t ldb,
                                                                     int M, int N, int K, int kchunk,
                                                                     int64_t slab_stride, Epilogue ep, int tiles_m,
-                                                                    int tiles_n, BnBwdArgs fa) {
+                                                                    int tiles_n, BnBwdArgs fa, BnFwdArgs ff) {
   constexpr int BM = 256, BN = 256, KS = 64;
   constexpr int AUNIT = BM * KS, BUNIT = (BN / 2) * KS;      // elements: 32 KB, 16 KB
   constexpr int A0 = 0, BF0 = 3 * AUNIT, BS0 = BF0 + 2 * BUNIT;
@@ -1342,8 +1468,12 @@ __global__ __launch_bounds__(512) void gemm_bf16_wide_line16_kernel(const bf16_t
     wait_loads_but<0>();
   }
 
-  if constexpr (FUSE) {
+  if constexpr (FUSE == 1) {
     bn_bwd_tile(acc, fa, lds_wide, m0, n0, N, wave, lane);
+    return;
+  }
+  if constexpr (FUSE == 2) {
+    bn_fwd_tile(acc, ff, lds_wide, m0, n0, N, wave, lane);
     return;
   }
   char* cbase = static_cast<char*>(ep.C) + (int64_t)blockIdx.z * slab_stride * (ep.c_is_bf16 ? 2 : 4);
@@ -1895,9 +2025,9 @@ int launch_wide_line(const Shape& g, const Epilogue& ep, hipStream_t s) {
   if (!ready) {
     VF_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_wide_line_kernel),
                                hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
-    VF_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_wide_line16_kernel<false>),
+    VF_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_wide_line16_kernel<0>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
-    VF_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_wide_line16_kernel<true>),
+    VF_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_wide_line16_kernel<1>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
     ready = true;
   }
@@ -1913,8 +2043,8 @@ int launch_wide_line(const Shape& g, const Epilogue& ep, hipStream_t s) {
     gemm_bf16_wide_line_kernel<<<grid, 512, bytes, s>>>(g.A, g.lda, g.B, g.ldb, g.M, g.N, g.K, kchunk, g.slab, epx, tiles_m,
                                                         tiles_n);
   else
-    gemm_bf16_wide_line16_kernel<false><<<grid, 512, bytes, s>>>(g.A, g.lda, g.B, g.ldb, g.M, g.N, g.K, kchunk, g.slab, epx,
-                                                                 tiles_m, tiles_n, BnBwdArgs{});
+    gemm_bf16_wide_line16_kernel<0><<<grid, 512, bytes, s>>>(g.A, g.lda, g.B, g.ldb, g.M, g.N, g.K, kchunk, g.slab, epx,
+                                                                 tiles_m, tiles_n, BnBwdArgs{}, BnFwdArgs{});
   VF_LAUNCH_CHECK();
   return VF_OK;
 }
@@ -1935,6 +2065,38 @@ int launch_wide(const Shape& g, const Epilogue& ep, hipStream_t s) {
 
 // The product with the BatchNorm backward pass in its epilogue (see bn_bwd_tile): shapes that the
 // 256 x 256 kernel on the 16x16x32 MFMA takes in whole tiles.  VF_BN_FUSE = 0 switches it off.
+bool gemm_bf16_bn_fwd_takes(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, int M, int N, int K,
+                            const BnFwdArgs& fa) {
+  static const bool enabled = !(std::getenv("VF_BN_FUSE_FWD") && std::atoi(std::getenv("VF_BN_FUSE_FWD")) == 0);
+  if (!enabled || M <= 0 || N <= 0 || K <= 0 || !A || !B || !fa.z || !fa.a || !fa.aT) return false;
+  if ((fa.gamma == nullptr) != (fa.beta == nullptr) || (fa.gamma && (!fa.mean || !fa.rstd || !fa.var || fa.bias))) return false;
+  auto al = [](const void* p, uintptr_t n) { return (reinterpret_cast<uintptr_t>(p) & (n - 1)) == 0; };
+  const bool spans32 = (int64_t)M * lda * 2 < ((int64_t)1 << 31) && (int64_t)N * ldb * 2 < ((int64_t)1 << 31);
+  return (M % 256) == 0 && (N % 256) == 0 && (K % 64) == 0 && spans32 && wide_fits(M, N, K, 1) &&
+         wide_tile_n(M, N) == 256 && wide_variant() == 0 && !(lda & 7) && !(ldb & 7) && al(A, 16) && al(B, 16) &&
+         !(fa.ldz & 3) && !(fa.lda & 3) && !(fa.ldt & 7) && al(fa.z, 16) && al(fa.a, 8) && al(fa.aT, 16) &&
+         al(fa.mean, 16) && al(fa.rstd, 16) && al(fa.var, 16) && al(fa.gamma, 16) && al(fa.beta, 16) && al(fa.bias, 16);
+}
+
+int launch_gemm_bf16_bn_fwd(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, int M, int N, int K,
+                            const BnFwdArgs& fa, hipStream_t s) {
+  if (!gemm_bf16_bn_fwd_takes(A, lda, B, ldb, M, N, K, fa)) return VF_EINVAL;
+  constexpr int bytes = 160 * 1024;
+  static bool ready = false;
+  if (!ready) {
+    VF_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_wide_line16_kernel<2>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
+    ready = true;
+  }
+  const int tiles_m = M / 256, tiles_n = N / 256;
+  const int ntile = tiles_m * tiles_n;
+  dim3 grid(((ntile + 7) / 8) * 8, 1, 1);
+  gemm_bf16_wide_line16_kernel<2><<<grid, 512, bytes, s>>>(A, lda, B, ldb, M, N, K, K, 0, Epilogue{}, tiles_m, tiles_n,
+                                                           BnBwdArgs{}, fa);
+  VF_LAUNCH_CHECK();
+  return VF_OK;
+}
+
 bool gemm_bf16_bn_bwd_takes(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, int M, int N, int K,
                             const BnBwdArgs& fa) {
   static const bool enabled = !(std::getenv("VF_BN_FUSE") && std::atoi(std::getenv("VF_BN_FUSE")) == 0);
@@ -1954,14 +2116,14 @@ int launch_gemm_bf16_bn_bwd(const bf16_t* A, int64_t lda, const bf16_t* B, int64
   constexpr int bytes = 160 * 1024;
   static bool ready = false;
   if (!ready) {
-    VF_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_wide_line16_kernel<true>),
+    VF_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_wide_line16_kernel<1>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
     ready = true;
   }
   const int tiles_m = M / 256, tiles_n = N / 256;
   const int ntile = tiles_m * tiles_n;
   dim3 grid(((ntile + 7) / 8) * 8, 1, 1);
-  gemm_bf16_wide_line16_kernel<true><<<grid, 512, bytes, s>>>(A, lda, B, ldb, M, N, K, K, 0, Epilogue{}, tiles_m, tiles_n, fa);
+  gemm_bf16_wide_line16_kernel<1><<<grid, 512, bytes, s>>>(A, lda, B, ldb, M, N, K, K, 0, Epilogue{}, tiles_m, tiles_n, fa, BnFwdArgs{});
   VF_LAUNCH_CHECK();
   return VF_OK;
 }

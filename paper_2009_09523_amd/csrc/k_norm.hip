@@ -808,6 +808,32 @@ __global__ __launch_bounds__(256) void bn_sums_finish_kernel(const float* __rest
   if (gout_b.dst) grad_store(gout_b, c, tb);
 }
 
+// Moving statistics from per-node batch statistics [nodes][C] (left by a product whose epilogue took
+// the BatchNorm forward pass): one blend per node, node after node (Section 4.1), as the kernels above.
+__global__ __launch_bounds__(256) void bn_stats_finish_kernel(const float* __restrict__ mean, const float* __restrict__ var,
+                                                              int nodes, int C, float* __restrict__ run_mean,
+                                                              float* __restrict__ run_var, float run_mix) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= C) return;
+  float rm = run_mean[c], rv = run_var[c];
+  for (int n0 = 0; n0 < nodes; n0 += 16) {
+    float m[16], v[16];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+      const int n = min(n0 + k, nodes - 1);
+      m[k] = mean[(int64_t)n * C + c];
+      v[k] = var[(int64_t)n * C + c];
+    }
+#pragma unroll
+    for (int k = 0; k < 16; ++k)
+      if (n0 + k < nodes) {
+        rm = fmaf(run_mix, m[k] - rm, rm);
+        rv = fmaf(run_mix, v[k] - rv, rv);
+      }
+  }
+  run_mean[c] = rm; run_var[c] = rv;
+}
+
 constexpr int SCB = 32, SRL = 8;
 template <typename T>
 __global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ x, int64_t ld, int R, int C,
@@ -1044,6 +1070,14 @@ int launch_bn_relu_bwd(float* dap, int nsplit, int64_t slab, int64_t ldda, const
 #undef VF_BWDG
 #undef VF_BWDG1
 #undef VF_BWD2
+  VF_LAUNCH_CHECK();
+  return VF_OK;
+}
+
+int launch_bn_stats_finish(const float* mean, const float* var, int nodes, int C, float* run_mean, float* run_var,
+                           float run_mix, hipStream_t s) {
+  if (!mean || !var || !run_mean || !run_var || nodes < 1 || C <= 0) return VF_EINVAL;
+  bn_stats_finish_kernel<<<(C + 255) / 256, 256, 0, s>>>(mean, var, nodes, C, run_mean, run_var, run_mix);
   VF_LAUNCH_CHECK();
   return VF_OK;
 }

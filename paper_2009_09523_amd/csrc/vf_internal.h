@@ -85,6 +85,28 @@ struct BnBwdArgs {
   float* sums = nullptr;         // [nodes][2][N]: sum over the node's rows of dr * xhat, and of dr
 };
 
+// BatchNorm + ReLU forward of whole nodes of 128 rows inside the epilogue of the product that computes
+// the layer's pre-activations (launch_gemm_bf16_bn_fwd): the pre-activations are stored as usual (the
+// backward pass needs them), and with them the bf16 activation, its transposed copy and the per-node
+// statistics; `var` receives the per-node biased variances for the small launch that blends the
+// moving statistics in node order.
+struct BnFwdArgs {
+  float* z = nullptr;            // pre-activations [M, N], fp32 (written)
+  int64_t ldz = 0;
+  const float* gamma = nullptr;  // [N], or null: bias + ReLU only
+  const float* beta = nullptr;
+  const float* bias = nullptr;   // [N] or null (layers without BatchNorm)
+  int round_params = 0;          // gamma, beta, bias rounded to bf16 first
+  float eps = 0.f;
+  bf16_t* a = nullptr;           // activation [M, N]
+  int64_t lda = 0;
+  bf16_t* aT = nullptr;          // [N, ldt]: column = row of the unit
+  int64_t ldt = 0;
+  float* mean = nullptr;         // [nodes, N] (BatchNorm only)
+  float* rstd = nullptr;
+  float* var = nullptr;          // [nodes, N] scratch (BatchNorm only)
+};
+
 // ---------------------------------------------------------------------------------------
 // kernel launchers (each returns VF_OK or VF_EDEVICE/VF_EINVAL); all asynchronous
 // ---------------------------------------------------------------------------------------
@@ -118,6 +140,15 @@ bool gemm_bf16_bn_bwd_takes(const bf16_t* A, int64_t lda, const bf16_t* B, int64
                             const BnBwdArgs& fa);
 int launch_gemm_bf16_bn_bwd(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, int M, int N, int K,
                             const BnBwdArgs& fa, hipStream_t s);
+// The same for the forward pass: A B^T [M, N] stored as the pre-activations, and BatchNorm + ReLU of
+// whole nodes of 128 rows applied to it tile by tile inside the kernel.
+bool gemm_bf16_bn_fwd_takes(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, int M, int N, int K,
+                            const BnFwdArgs& fa);
+int launch_gemm_bf16_bn_fwd(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, int M, int N, int K,
+                            const BnFwdArgs& fa, hipStream_t s);
+// Moving statistics blended with the per-node batch statistics, node after node (Section 4.1).
+int launch_bn_stats_finish(const float* mean, const float* var, int nodes, int C, float* run_mean, float* run_var,
+                           float run_mix, hipStream_t s);
 // Scale / shift (or bias) gradients from the per-node column sums, added up in node order.
 int launch_bn_sums_finish(const float* sums, int nodes, int C, GradOut gout_g, GradOut gout_b, hipStream_t s);
 // Number of slices that fills the chip for this shape (1 when the tile grid already does).

@@ -227,6 +227,29 @@ class Mlp final : public Model {
       // an unsliced product of a hidden layer writes the pre-activation where it is kept: the
       // normalisation kernel then has nothing to copy
       float* zsrc = (split == 1 && L.hidden) ? L.z[q] : slab_buf;
+      // A unit of whole nodes of 128 rows on a wide layer: the product's epilogue takes BatchNorm and
+      // ReLU itself (the pre-activations are stored and not read again in this pass); the scratch
+      // holds the per-node variances for the small launch that blends the moving statistics.
+      bool whole = bf16_ && L.hidden && split == 1 && s.group(i) >= 2 && b == 128 * s.group(i);
+      for (int n = 0; n < s.group(i) && whole; ++n) whole = s.rows_of(i)[n] == 128;
+      if (whole) {
+        BnFwdArgs ff;
+        ff.z = L.z[q]; ff.ldz = L.ld;
+        if (L.has_bn) { ff.gamma = P + L.g_off; ff.beta = P + L.be_off; }
+        else if (L.has_bias) ff.bias = P + L.b_off;
+        ff.round_params = bf16_;
+        ff.eps = cfg_.bn_eps;
+        ff.a = static_cast<bf16_t*>(L.a[q]); ff.lda = L.ld;
+        ff.aT = L.aT + pc; ff.ldt = ldw_;
+        ff.mean = L.mean[q]; ff.rstd = L.rstd[q]; ff.var = slab_buf;
+        if (gemm_bf16_bn_fwd_takes(static_cast<const bf16_t*>(in), ldin, L.wtr, L.ldt, b, L.N, L.K, ff)) {
+          VF_KS(c, st, "gemm_fwd_bn", launch_gemm_bf16_bn_fwd(static_cast<const bf16_t*>(in), ldin, L.wtr, L.ldt, b, L.N, L.K, ff, st));
+          if (L.has_bn)
+            VF_KS(c, st, "bn_stats_finish", launch_bn_stats_finish(L.mean[q], slab_buf, s.group(i), L.N, state_ + L.s_off,
+                                                                   state_ + bn_width_ + L.s_off, cfg_.bn_momentum, st));
+          continue;
+        }
+      }
       Epilogue ep;
       ep.C = zsrc; ep.ldc = L.ld;
       if (L.has_bias) { ep.bias = P + L.b_off; ep.bias_round_bf16 = bf16_; }

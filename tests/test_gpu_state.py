@@ -69,6 +69,24 @@ def test_moving_statistics_of_grouped_nodes_are_blended_node_after_node(group, n
     assert np.max(np.abs(st["bn_var"] - want_var)) <= tol * np.max(np.abs(want_var))
 
 
+def test_moving_statistics_of_wide_units_are_blended_node_after_node():
+    """Sixteen whole nodes of 128 rows on 8192-wide layers, one unit: the forward products take BatchNorm in
+    their epilogue and leave per-node statistics, which a small launch blends into the moving ones in node
+    order -- the oracle's values after one step."""
+    import paper_2009_09523_amd as vf
+    wl = I.workload("mlp_wide_bn_bf16")
+    theta, x, y, params, xt, yt = _setup(wl)
+    eng, stream = _engine(wl, FUSED, node_group=16)
+    eng.step(params, xt, yt, list(wl.node_sizes))
+    st = vf.parse_state(eng.state_export(params))
+    eng.close()
+    ref = oracle_steps(wl, theta, x, y, steps=1)
+    want_mean, want_var = np.concatenate(ref["state"]["bn_mean"]), np.concatenate(ref["state"]["bn_var"])
+    tol = TOL[wl.dtype]
+    assert np.max(np.abs(st["bn_mean"] - want_mean)) <= tol * np.max(np.abs(want_mean))
+    assert np.max(np.abs(st["bn_var"] - want_var)) <= tol * np.max(np.abs(want_var))
+
+
 def test_zero_share_freezes_the_moving_statistics():
     import paper_2009_09523_amd as vf
     wl = replace(I.workload("mlp_small_bn_f32"), bn_momentum=0.0)
