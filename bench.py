@@ -331,7 +331,7 @@ def main():
                     help="fused fold: the weight gradients of this many consecutive nodes (1..8) are folded "
                          "into the gradient buffer in one pass (nodes of one size: one product over the "
                          "window's rows; the workspace keeps that many nodes' transposed bf16 operands)")
-    ap.add_argument("--node-group", type=int, choices=[1, 2, 4, 8, 16, 32], default=16,
+    ap.add_argument("--node-group", type=int, choices=[1, 2, 4, 8, 16, 32], default=32,
                     help="up to this many consecutive nodes go through their passes together "
                          "(one operand of every product, so the weights are read once per group; BatchNorm "
                          "statistics, node losses and weights stay per node); 1: node after node")

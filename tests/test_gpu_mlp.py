@@ -127,7 +127,7 @@ def test_rejected_step_leaves_state_untouched():
 BENCH = FUSED | NO_GRAPH | 4        # what bench.py times: fused fold, two streams, eager launches, window 8
 
 
-BENCH_GROUP = 16                    # ... and up to 16 nodes through their passes together
+BENCH_GROUP = 32                    # ... and up to 32 nodes through their passes together
 
 
 @pytest.mark.parametrize("name,flags,window,group", [("C2", BENCH, 8, BENCH_GROUP), ("C3", BENCH, 8, BENCH_GROUP),
@@ -153,7 +153,7 @@ def test_full_size_configurations(name, flags, window, group):
 def test_c5_full_size_launch_configuration():
     """Large-batch emulation: MLP 2048-8192x6-1000 + BatchNorm, 64 nodes of 128 (B = 8192), in the
     launch configuration bench.py times (fused fold, two streams, launches one by one, units
-    of 16 nodes per pass, one window over the four units).  The oracle can afford single nodes of this
+    of 32 nodes per pass, one window over the two units).  The oracle can afford single nodes of this
     model: it evaluates the eight distinct nodes 0..7, and the device runs V = 64 nodes of which node i
     holds the rows of node i mod 8 (a unit of the device's passes is these eight nodes twice, its
     BatchNorm launches take eight nodes each) -- the combined gradient is then
