@@ -488,6 +488,16 @@ def test_wide_units_of_whole_nodes_match_the_oracle(name):
     ref = oracle_steps(wl, theta, x, y, node_sizes=sizes)
     gpu = run_gpu(wl, theta, x, y, node_sizes=sizes, flags=FUSED | NO_GRAPH | OVERLAP, node_group=32)
     check_against_oracle(wl, gpu, ref)
+    if name == "mlp_wide_bn_bf16":
+        # a unit of sixteen whole nodes and a unit of sixteen nodes of 64 rows in one fold window: the
+        # window's joint weight-gradient product takes the nodes' weights b_i/B inside its operand, i.e.
+        # the fused epilogue writes its transposed copy scaled
+        sizes = [128] * 16 + [64] * 16
+        wl2 = wl.with_nodes(sizes)
+        x2, y2 = I.make_batch(wl2)
+        ref = oracle_steps(wl2, theta, x2, y2)
+        gpu = run_gpu(wl2, theta, x2, y2, flags=BENCH, fold_window=8, node_group=16)
+        check_against_oracle(wl2, gpu, ref)
 
 
 def test_node_groups_keep_the_workspace_independent_of_the_node_count():
