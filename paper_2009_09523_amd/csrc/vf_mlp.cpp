@@ -41,9 +41,12 @@ class Mlp final : public Model {
  public:
   explicit Mlp(const vf_config& cfg) : cfg_(cfg) {
     bf16_ = cfg.dtype == VF_BF16;
-    // a unit of the passes is up to node_group nodes: every per-unit buffer is sized for that many rows
+    // a unit of the passes is one node of any size, or up to node_group nodes of at most 128 rows each
+    // (max_group), and never has more rows than a batch: every per-unit buffer is sized for that
     group_ = bf16_ ? std::max(1, cfg.node_group) : 1;
-    max_rows_ = cfg.max_node_size * group_;
+    const int64_t grouped = std::min<int64_t>((int64_t)std::min(cfg.max_node_size, 128) * group_,
+                                              std::max(cfg.max_batch, cfg.max_node_size));
+    max_rows_ = (int)std::max<int64_t>(cfg.max_node_size, group_ > 1 ? grouped : 0);
     // as many copies of the weight-gradient operands as Ctx::copies() will ask for
     copies_ = std::max((cfg.flags & VF_FLAG_OVERLAP) ? 2 : 1, cfg.fold_window);
     const int nl = cfg.n_dims - 1;
